@@ -1,0 +1,455 @@
+/*
+ * fp64 CPU oracle for the GA3C hot path.  TEST INFRASTRUCTURE ONLY.
+ *
+ * This file is the slow, plain definition of what the GPU library computes:
+ * the batched policy/value CNN forward pass and one A3C update (n-step
+ * returns, advantage, policy + entropy + value loss, backward by the chain
+ * rule, global-norm clip, non-centred RMSProp).  It is used by the tests,
+ * the smoke check and the cpu_baseline leg of the benchmark, and by nothing
+ * on the product path.  It shares no code, header or table with the HIP
+ * library.
+ *
+ * Citations are to the paper (arXiv 1611.06256):
+ *   Sec. 3.2           network shape; rectifier after each hidden layer;
+ *                      softmax policy head and linear value head
+ *   Eq. 1              policy objective  log pi(a|s) (R - V) + beta H(pi)
+ *   text after Eq. 1   n-step return R_t = sum_i gamma^i r_{t+i} + gamma^k V
+ *   Eq. 2              value cost (R - V)^2
+ *   Eq. 3              RMSProp  g = a g + (1-a) d^2 ; th -= eta d / sqrt(g+eps)
+ *   Eq. 5              epsilon-stabilised log(pi+eps), H with log(pi+eps)
+ *   Sec. 5.3           gradients are SUMMED over the training batch
+ *
+ * Everything is double precision, NCHW, naive loops.  Convolutions are VALID
+ * cross-correlations.  OpenMP is used only as "parallel for" over frames or
+ * over output rows; no loop is blocked, fused or reordered.
+ *
+ * Flat parameter order (shared convention with any caller, stated here in
+ * full so this file stands alone): for each conv layer W[oc][ic][kh][kw] then
+ * b[oc]; fc W[out][in] with in = c*H*W + h*W + w, fc b[out]; policy W[A][F],
+ * policy b[A]; value W[F], value b.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORC_MAX_CONV 4
+
+typedef struct {
+    int in_c, in_h, in_w;
+    int n_conv;
+    int oc[ORC_MAX_CONV], k[ORC_MAX_CONV], stride[ORC_MAX_CONV];
+    int fc_units;
+    int n_actions;
+} orc_net;
+
+typedef struct {
+    double gamma, beta, value_coef, log_eps;
+    double lr, rms_decay, rms_eps, clip_norm;
+} orc_hparams;
+
+typedef struct {
+    double policy_loss, value_loss, entropy, grad_norm, clip_scale;
+} orc_stats;
+
+/* ---- shapes ------------------------------------------------------------ */
+
+/* channels / height / width of the input of conv layer l (l == n_conv gives
+ * the shape that is flattened into the fc layer). */
+static void layer_in_shape(const orc_net *net, int l, int *c, int *h, int *w) {
+    int cc = net->in_c, hh = net->in_h, ww = net->in_w;
+    for (int i = 0; i < l; ++i) {
+        hh = (hh - net->k[i]) / net->stride[i] + 1;
+        ww = (ww - net->k[i]) / net->stride[i] + 1;
+        cc = net->oc[i];
+    }
+    *c = cc; *h = hh; *w = ww;
+}
+
+/* Offsets of every tensor in the flat parameter vector.
+ * off[2l], off[2l+1] = conv l weight, bias; then fcW, fcb, polW, polb, valW,
+ * valb, and finally the total count.  Returns the number of entries. */
+int orc_offsets(const orc_net *net, int64_t *off) {
+    int64_t p = 0; int n = 0;
+    for (int l = 0; l < net->n_conv; ++l) {
+        int c, h, w; layer_in_shape(net, l, &c, &h, &w);
+        off[n++] = p; p += (int64_t)net->oc[l] * c * net->k[l] * net->k[l];
+        off[n++] = p; p += net->oc[l];
+    }
+    int c, h, w; layer_in_shape(net, net->n_conv, &c, &h, &w);
+    int64_t flat = (int64_t)c * h * w;
+    off[n++] = p; p += flat * net->fc_units;
+    off[n++] = p; p += net->fc_units;
+    off[n++] = p; p += (int64_t)net->n_actions * net->fc_units;
+    off[n++] = p; p += net->n_actions;
+    off[n++] = p; p += net->fc_units;
+    off[n++] = p; p += 1;
+    off[n++] = p;
+    return n;
+}
+
+int64_t orc_param_count(const orc_net *net) {
+    int64_t off[2 * ORC_MAX_CONV + 8];
+    int n = orc_offsets(net, off);
+    return off[n - 1];
+}
+
+/* Number of doubles of saved activations per frame: the scaled input, every
+ * conv output (post-ReLU) and the fc output (post-ReLU), in that order. */
+int64_t orc_acts_per_frame(const orc_net *net) {
+    int64_t s = (int64_t)net->in_c * net->in_h * net->in_w;
+    for (int l = 1; l <= net->n_conv; ++l) {
+        int c, h, w; layer_in_shape(net, l, &c, &h, &w);
+        s += (int64_t)c * h * w;
+    }
+    return s + net->fc_units;
+}
+
+/* ---- forward ----------------------------------------------------------- */
+
+/* VALID cross-correlation + bias + ReLU for one frame (Sec. 3.2). */
+static void conv_relu(const double *x, int C, int H, int W,
+                      const double *wt, const double *bias, int OC, int K, int S,
+                      double *y) {
+    int OH = (H - K) / S + 1, OW = (W - K) / S + 1;
+    for (int o = 0; o < OC; ++o)
+        for (int i = 0; i < OH; ++i)
+            for (int j = 0; j < OW; ++j) {
+                double acc = bias[o];
+                for (int c = 0; c < C; ++c)
+                    for (int u = 0; u < K; ++u)
+                        for (int v = 0; v < K; ++v)
+                            acc += wt[((o * C + c) * K + u) * K + v] *
+                                   x[(c * H + i * S + u) * W + j * S + v];
+                y[(o * OH + i) * OW + j] = acc > 0.0 ? acc : 0.0;
+            }
+}
+
+static void softmax(const double *z, int A, double *p) {
+    double m = z[0];
+    for (int j = 1; j < A; ++j) if (z[j] > m) m = z[j];
+    double s = 0.0;
+    for (int j = 0; j < A; ++j) { p[j] = exp(z[j] - m); s += p[j]; }
+    for (int j = 0; j < A; ++j) p[j] /= s;
+}
+
+/* Forward pass of one frame.  acts (may not be NULL) receives the saved
+ * activations in the order of orc_acts_per_frame. */
+static void forward_one(const orc_net *net, const double *theta, const int64_t *off,
+                        const uint8_t *frame, double *acts,
+                        double *logits, double *value, double *probs) {
+    int64_t in_sz = (int64_t)net->in_c * net->in_h * net->in_w;
+    double *x = acts;
+    for (int64_t i = 0; i < in_sz; ++i) x[i] = frame[i] / 255.0;
+    double *cur = x; int64_t cur_sz = in_sz;
+    for (int l = 0; l < net->n_conv; ++l) {
+        int c, h, w; layer_in_shape(net, l, &c, &h, &w);
+        double *y = cur + cur_sz;
+        conv_relu(cur, c, h, w, theta + off[2 * l], theta + off[2 * l + 1],
+                  net->oc[l], net->k[l], net->stride[l], y);
+        int c2, h2, w2; layer_in_shape(net, l + 1, &c2, &h2, &w2);
+        cur = y; cur_sz = (int64_t)c2 * h2 * w2;
+    }
+    int nb = 2 * net->n_conv;
+    const double *Wf = theta + off[nb], *bf = theta + off[nb + 1];
+    const double *Wp = theta + off[nb + 2], *bp = theta + off[nb + 3];
+    const double *Wv = theta + off[nb + 4], *bv = theta + off[nb + 5];
+    int F = net->fc_units, A = net->n_actions;
+    double *hfc = cur + cur_sz;
+    for (int o = 0; o < F; ++o) {
+        double acc = bf[o];
+        for (int64_t i = 0; i < cur_sz; ++i) acc += Wf[o * cur_sz + i] * cur[i];
+        hfc[o] = acc > 0.0 ? acc : 0.0;
+    }
+    for (int a = 0; a < A; ++a) {
+        double acc = bp[a];
+        for (int i = 0; i < F; ++i) acc += Wp[a * F + i] * hfc[i];
+        logits[a] = acc;
+    }
+    double v = bv[0];
+    for (int i = 0; i < F; ++i) v += Wv[i] * hfc[i];
+    *value = v;
+    if (probs) softmax(logits, A, probs);
+}
+
+/* Batched forward.  acts may be NULL (then a scratch frame buffer is used);
+ * probs may be NULL. */
+int orc_forward(const orc_net *net, const double *theta, const uint8_t *frames, int B,
+                double *acts, double *logits, double *values, double *probs) {
+    int64_t off[2 * ORC_MAX_CONV + 8]; orc_offsets(net, off);
+    int64_t apf = orc_acts_per_frame(net);
+    int64_t in_sz = (int64_t)net->in_c * net->in_h * net->in_w;
+    int A = net->n_actions;
+    int fail = 0;
+#pragma omp parallel for schedule(static)
+    for (int b = 0; b < B; ++b) {
+        double *a = acts ? acts + (int64_t)b * apf : (double *)malloc(sizeof(double) * apf);
+        if (!a) { fail = 1; continue; }
+        forward_one(net, theta, off, frames + (int64_t)b * in_sz, a,
+                    logits + (int64_t)b * A, values + b, probs ? probs + (int64_t)b * A : NULL);
+        if (!acts) free(a);
+    }
+    return fail ? -1 : 0;
+}
+
+/* Inverse-CDF sampling: the first action whose running sum of probabilities
+ * exceeds u; the last action if none does (Sec. 4.1: the agent chooses
+ * actions according to the policy). */
+int orc_sample(const double *p, int A, double u) {
+    double c = 0.0;
+    for (int j = 0; j < A; ++j) { c += p[j]; if (c > u) return j; }
+    return A - 1;
+}
+
+/* ---- returns (text after Eq. 1) ----------------------------------------- */
+
+/* R[n][T] = bootstrap[n];  R[n][t] = r[n][t] + gamma (1 - done[n][t]) R[n][t+1].
+ * A terminal at step t cuts the sum there, which is the k < t_max case. */
+void orc_returns(const double *rewards, const uint8_t *dones, const double *bootstrap,
+                 int N, int T, double gamma, double *R) {
+    for (int n = 0; n < N; ++n) {
+        double next = bootstrap ? bootstrap[n] : 0.0;
+        for (int t = T - 1; t >= 0; --t) {
+            double cont = dones[n * T + t] ? 0.0 : 1.0;
+            next = rewards[n * T + t] + gamma * cont * next;
+            R[n * T + t] = next;
+        }
+    }
+}
+
+/* ---- loss and its gradient w.r.t. the two heads (Eq. 1, 2, 5) ----------- */
+
+/* Minimised quantity per frame:
+ *   L = -log(p[a] + e) * adv - beta * H + cv * (R - V)^2,
+ *   H = -sum_j p_j log(p_j + e),  adv = R - V held constant in the first term.
+ * Outputs dz[A] = dL/dz, *dv = dL/dV and the three loss pieces. */
+static void loss_one(const double *z, double V, int a, double R, int A,
+                     double beta, double cv, double e,
+                     double *dz, double *dv, double *pl, double *vl, double *ent) {
+    double p[64];
+    softmax(z, A, p);
+    double adv = R - V;
+    double H = 0.0;
+    for (int j = 0; j < A; ++j) if (p[j] + e > 0.0) H -= p[j] * log(p[j] + e);
+    *pl = -log(p[a] + e) * adv;
+    *vl = (R - V) * (R - V);
+    *ent = H;
+    /* dL/dp_k, then through the softmax Jacobian dp_k/dz_j = p_k (1[k=j] - p_j). */
+    double dp[64], dot = 0.0;
+    for (int k = 0; k < A; ++k) {
+        double lg = (p[k] + e > 0.0) ? log(p[k] + e) : 0.0;
+        double r = (p[k] + e > 0.0) ? p[k] / (p[k] + e) : 0.0;
+        dp[k] = beta * (lg + r);
+        if (k == a) dp[k] -= adv / (p[k] + e);
+        dot += p[k] * dp[k];
+    }
+    for (int j = 0; j < A; ++j) dz[j] = p[j] * (dp[j] - dot);
+    *dv = -2.0 * cv * (R - V);
+}
+
+void orc_loss_grad(const double *logits, const double *values, const int32_t *actions,
+                   const double *R, int B, int A, double beta, double cv, double e,
+                   double *dZ, double *dV, double *sums /* policy, value, entropy */) {
+    sums[0] = sums[1] = sums[2] = 0.0;
+    for (int b = 0; b < B; ++b) {
+        double pl, vl, en;
+        loss_one(logits + (int64_t)b * A, values[b], actions[b], R[b], A, beta, cv, e,
+                 dZ + (int64_t)b * A, dV + b, &pl, &vl, &en);
+        sums[0] += pl; sums[1] += vl; sums[2] += en;
+    }
+}
+
+/* ---- backward ----------------------------------------------------------- */
+
+/* Gradient of one frame's loss w.r.t. all parameters, ADDED into grad.
+ * dz[A], dv are dL/dlogits and dL/dvalue for this frame. */
+static void backward_one(const orc_net *net, const double *theta, const int64_t *off,
+                         const double *acts, const double *dz, double dv, double *grad,
+                         double *scratch /* 2 * acts_per_frame doubles */) {
+    int nb = 2 * net->n_conv;
+    int F = net->fc_units, A = net->n_actions;
+    int c, h, w; layer_in_shape(net, net->n_conv, &c, &h, &w);
+    int64_t flat = (int64_t)c * h * w;
+    /* locate saved activations */
+    const double *layer_in[ORC_MAX_CONV + 1];
+    int64_t pos = 0;
+    for (int l = 0; l <= net->n_conv; ++l) {
+        int cc, hh, ww; layer_in_shape(net, l, &cc, &hh, &ww);
+        layer_in[l] = acts + pos; pos += (int64_t)cc * hh * ww;
+    }
+    const double *hfc = acts + pos;
+    const double *Wf = theta + off[nb];
+    const double *Wp = theta + off[nb + 2], *Wv = theta + off[nb + 4];
+    double *gWf = grad + off[nb], *gbf = grad + off[nb + 1];
+    double *gWp = grad + off[nb + 2], *gbp = grad + off[nb + 3];
+    double *gWv = grad + off[nb + 4], *gbv = grad + off[nb + 5];
+
+    /* heads */
+    double *dh = scratch;                    /* F */
+    for (int i = 0; i < F; ++i) dh[i] = 0.0;
+    for (int a = 0; a < A; ++a) {
+        gbp[a] += dz[a];
+        for (int i = 0; i < F; ++i) { gWp[a * F + i] += dz[a] * hfc[i]; dh[i] += dz[a] * Wp[a * F + i]; }
+    }
+    gbv[0] += dv;
+    for (int i = 0; i < F; ++i) { gWv[i] += dv * hfc[i]; dh[i] += dv * Wv[i]; }
+    for (int i = 0; i < F; ++i) if (!(hfc[i] > 0.0)) dh[i] = 0.0;   /* ReLU of fc */
+
+    /* fc */
+    const double *xin = layer_in[net->n_conv];
+    double *dcur = scratch + F;              /* gradient w.r.t. current layer input */
+    for (int64_t i = 0; i < flat; ++i) dcur[i] = 0.0;
+    for (int o = 0; o < F; ++o) {
+        gbf[o] += dh[o];
+        for (int64_t i = 0; i < flat; ++i) {
+            gWf[o * flat + i] += dh[o] * xin[i];
+            dcur[i] += dh[o] * Wf[o * flat + i];
+        }
+    }
+
+    /* conv layers, last to first.  dcur holds dL/d(output of conv l) before
+     * that layer's ReLU mask.  The two buffers swap roles per layer, so each
+     * is as large as the largest conv output (2*acts_per_frame covers it). */
+    int64_t maxsz = flat;
+    for (int l = 1; l <= net->n_conv; ++l) {
+        int cc, hh, ww; layer_in_shape(net, l, &cc, &hh, &ww);
+        if ((int64_t)cc * hh * ww > maxsz) maxsz = (int64_t)cc * hh * ww;
+    }
+    double *dprev = dcur + maxsz;
+    for (int l = net->n_conv - 1; l >= 0; --l) {
+        int C, H, W; layer_in_shape(net, l, &C, &H, &W);
+        int OC = net->oc[l], K = net->k[l], S = net->stride[l];
+        int OH = (H - K) / S + 1, OW = (W - K) / S + 1;
+        const double *y = layer_in[l + 1];
+        const double *x = layer_in[l];
+        const double *wt = theta + off[2 * l];
+        double *gw = grad + off[2 * l], *gb = grad + off[2 * l + 1];
+        int64_t in_sz = (int64_t)C * H * W;
+        if (l > 0) for (int64_t i = 0; i < in_sz; ++i) dprev[i] = 0.0;
+        for (int o = 0; o < OC; ++o)
+            for (int i = 0; i < OH; ++i)
+                for (int j = 0; j < OW; ++j) {
+                    int64_t yi = (o * OH + i) * OW + j;
+                    if (!(y[yi] > 0.0)) continue;          /* ReLU */
+                    double d = dcur[yi];
+                    gb[o] += d;
+                    for (int cc = 0; cc < C; ++cc)
+                        for (int u = 0; u < K; ++u)
+                            for (int v = 0; v < K; ++v) {
+                                int64_t wi = ((o * C + cc) * K + u) * K + v;
+                                int64_t xi = (cc * H + i * S + u) * W + j * S + v;
+                                gw[wi] += d * x[xi];
+                                if (l > 0) dprev[xi] += d * wt[wi];
+                            }
+                }
+        /* the input of layer 0 is data: no gradient needed */
+        double *t = dcur; dcur = dprev; dprev = t;
+    }
+}
+
+/* Sum over the batch (Sec. 5.3) of the per-frame parameter gradients.
+ * grad is overwritten.  Frames are processed in index order by each thread
+ * on a private accumulator; the accumulators are then added in thread order,
+ * so the result does not depend on scheduling. */
+int orc_backward(const orc_net *net, const double *theta, const double *acts, int B,
+                 const double *dZ, const double *dV, double *grad) {
+    int64_t off[2 * ORC_MAX_CONV + 8]; orc_offsets(net, off);
+    int64_t P = orc_param_count(net), apf = orc_acts_per_frame(net);
+    int A = net->n_actions;
+    int nthreads = 1;
+#ifdef _OPENMP
+    extern int omp_get_max_threads(void);
+    nthreads = omp_get_max_threads();
+#endif
+    if (nthreads > B) nthreads = B > 0 ? B : 1;
+    double *priv = (double *)calloc((size_t)nthreads * P, sizeof(double));
+    double *scr = (double *)malloc(sizeof(double) * (size_t)nthreads * 2 * apf);
+    if (!priv || !scr) { free(priv); free(scr); return -1; }
+#pragma omp parallel for schedule(static) num_threads(nthreads)
+    for (int t = 0; t < nthreads; ++t) {
+        int b0 = (int)((int64_t)B * t / nthreads), b1 = (int)((int64_t)B * (t + 1) / nthreads);
+        for (int b = b0; b < b1; ++b)
+            backward_one(net, theta, off, acts + (int64_t)b * apf, dZ + (int64_t)b * A, dV[b],
+                         priv + (int64_t)t * P, scr + (int64_t)t * 2 * apf);
+    }
+    for (int64_t i = 0; i < P; ++i) {
+        double s = 0.0;
+        for (int t = 0; t < nthreads; ++t) s += priv[(int64_t)t * P + i];
+        grad[i] = s;
+    }
+    free(priv); free(scr);
+    return 0;
+}
+
+/* ---- clip and RMSProp --------------------------------------------------- */
+
+double orc_grad_norm(const double *grad, int64_t P) {
+    double s = 0.0;
+    for (int64_t i = 0; i < P; ++i) s += grad[i] * grad[i];
+    return sqrt(s);
+}
+
+/* Global L2-norm rescale: s = min(1, c / ||grad||); c <= 0 disables. */
+double orc_clip_scale(double norm, double c) {
+    if (!(c > 0.0)) return 1.0;
+    return norm > c ? c / norm : 1.0;
+}
+
+/* Eq. 3 with d = scale * grad; eps inside the root. */
+void orc_rmsprop(double *theta, double *g, const double *grad, int64_t P,
+                 double scale, double lr, double alpha, double eps) {
+    for (int64_t i = 0; i < P; ++i) {
+        double d = scale * grad[i];
+        g[i] = alpha * g[i] + (1.0 - alpha) * d * d;
+        theta[i] -= lr * d / sqrt(g[i] + eps);
+    }
+}
+
+/* ---- one whole update --------------------------------------------------- */
+
+/* frames [N][T][C][H][W]; actions, rewards, dones [N][T]; bootstrap [N] or NULL.
+ * theta and g are updated in place; grad (P doubles) receives the unclipped
+ * summed gradient.  Optional outputs (may be NULL): R_out [N*T], dZ_out
+ * [N*T][A], dV_out [N*T], logits_out [N*T][A], values_out [N*T]. */
+int orc_train_step(const orc_net *net, double *theta, double *g, double *grad,
+                   const uint8_t *frames, const int32_t *actions, const double *rewards,
+                   const uint8_t *dones, const double *bootstrap, int N, int T,
+                   const orc_hparams *hp, orc_stats *stats,
+                   double *R_out, double *dZ_out, double *dV_out,
+                   double *logits_out, double *values_out) {
+    int B = N * T, A = net->n_actions;
+    int64_t P = orc_param_count(net), apf = orc_acts_per_frame(net);
+    double *acts = (double *)malloc(sizeof(double) * (size_t)B * apf);
+    double *logits = (double *)malloc(sizeof(double) * (size_t)B * A);
+    double *values = (double *)malloc(sizeof(double) * B);
+    double *R = (double *)malloc(sizeof(double) * B);
+    double *dZ = (double *)malloc(sizeof(double) * (size_t)B * A);
+    double *dV = (double *)malloc(sizeof(double) * B);
+    int rc = -1;
+    if (acts && logits && values && R && dZ && dV) {
+        double sums[3];
+        rc = orc_forward(net, theta, frames, B, acts, logits, values, NULL);
+        if (rc == 0) {
+            orc_returns(rewards, dones, bootstrap, N, T, hp->gamma, R);
+            orc_loss_grad(logits, values, actions, R, B, A, hp->beta, hp->value_coef, hp->log_eps,
+                          dZ, dV, sums);
+            rc = orc_backward(net, theta, acts, B, dZ, dV, grad);
+        }
+        if (rc == 0) {
+            double norm = orc_grad_norm(grad, P);
+            double s = orc_clip_scale(norm, hp->clip_norm);
+            orc_rmsprop(theta, g, grad, P, s, hp->lr, hp->rms_decay, hp->rms_eps);
+            if (stats) {
+                stats->policy_loss = sums[0]; stats->value_loss = sums[1]; stats->entropy = sums[2];
+                stats->grad_norm = norm; stats->clip_scale = s;
+            }
+            if (R_out) memcpy(R_out, R, sizeof(double) * B);
+            if (dZ_out) memcpy(dZ_out, dZ, sizeof(double) * (size_t)B * A);
+            if (dV_out) memcpy(dV_out, dV, sizeof(double) * B);
+            if (logits_out) memcpy(logits_out, logits, sizeof(double) * (size_t)B * A);
+            if (values_out) memcpy(values_out, values, sizeof(double) * B);
+        }
+    }
+    free(acts); free(logits); free(values); free(R); free(dZ); free(dV);
+    return rc;
+}

@@ -1,0 +1,421 @@
+"""Pins of the fp64 CPU oracle against things other than itself.
+
+The paper (arXiv 1611.06256) prints no worked numeric example for any of its
+equations, so nothing here is a paper-printed value; the pins are
+brute-force loops written independently in Python, library routines
+(torch fp64 conv2d / autograd, numpy matmul), central finite differences,
+closed forms and invariants.  Each test names the passage it checks.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import ga3c_synth as synth
+import oracle as orc
+
+TINY = orc.Net(in_c=2, in_h=12, in_w=12, conv=((3, 4, 2), (4, 2, 1)), fc_units=5, n_actions=3)
+TINY3 = orc.Net(in_c=1, in_h=15, in_w=13, conv=((2, 5, 2), (3, 3, 1), (2, 2, 1)), fc_units=4, n_actions=4)
+SMALL6 = orc.Net(n_actions=6)
+SMALL18 = orc.Net(n_actions=18)
+LARGE = orc.Net(conv=((32, 8, 4), (64, 4, 2), (64, 3, 1)), fc_units=512, n_actions=18)
+
+
+def theta_for(net, seed, scale_bias=0.05):
+    return synth.perturbed_theta(seed, orc.offsets(net), orc.param_count(net), scale_bias).astype(np.float64)
+
+
+# ---------------------------------------------------------------- shapes ----
+
+def test_param_counts_and_offsets():
+    # Sec. 3.2 network: 16@8x8 s4, 32@4x4 s2, fc 256 on 4x84x84 input.
+    assert orc.param_count(SMALL6) == 677943
+    assert orc.param_count(SMALL18) == 681027
+    assert orc.param_count(LARGE) == 1693875
+    o = orc.offsets(SMALL6)
+    got = [o[k][0] for k in ("conv1.W", "conv1.b", "conv2.W", "conv2.b", "fc.W", "fc.b",
+                             "policy.W", "policy.b", "value.W", "value.b")]
+    assert got == [0, 4096, 4112, 12304, 12336, 675888, 676144, 677680, 677686, 677942]
+    assert o["fc.W"][1] == (256, 2592)
+
+
+# ------------------------------------------------------------ convolution ----
+
+def brute_forward(net, th, frames):
+    """Independent pure-Python forward pass (Sec. 3.2), loops written out."""
+    v = orc.views(net, th)
+    B = frames.shape[0]
+    logits = np.zeros((B, net.n_actions)); values = np.zeros(B)
+    for b in range(B):
+        x = frames[b].astype(np.float64) / 255.0
+        for l, (oc, k, s) in enumerate(net.conv):
+            W = v[f"conv{l + 1}.W"]; bias = v[f"conv{l + 1}.b"]
+            C_, H, Wd = x.shape
+            OH, OW = (H - k) // s + 1, (Wd - k) // s + 1
+            y = np.zeros((oc, OH, OW))
+            for o in range(oc):
+                for i in range(OH):
+                    for j in range(OW):
+                        acc = bias[o]
+                        for c in range(C_):
+                            for u in range(k):
+                                for w_ in range(k):
+                                    acc += W[o, c, u, w_] * x[c, i * s + u, j * s + w_]
+                        y[o, i, j] = max(acc, 0.0)
+            x = y
+        flat = x.reshape(-1)
+        h = np.maximum(v["fc.W"] @ flat + v["fc.b"], 0.0)
+        logits[b] = v["policy.W"] @ h + v["policy.b"]
+        values[b] = (v["value.W"] @ h + v["value.b"])[0]
+    return logits, values
+
+
+@pytest.mark.parametrize("net", [TINY, TINY3])
+def test_forward_vs_bruteforce(net):
+    th = theta_for(net, 3)
+    frames = synth.uniform_frames(5, (3, net.in_c, net.in_h, net.in_w))
+    out = orc.forward(net, th, frames)
+    lg, vl = brute_forward(net, th, frames)
+    np.testing.assert_allclose(out["logits"], lg, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(out["values"], vl, rtol=1e-12, atol=1e-13)
+
+
+def torch_forward(net, th_t, frames_t):
+    """Library third opinion: torch fp64 conv2d / linear.  th_t is a flat tensor."""
+    x = frames_t.double() / 255.0
+    offs = orc.offsets(net)
+
+    def get(name):
+        o, shape = offs[name]
+        return th_t[o:o + int(np.prod(shape))].reshape(shape)
+
+    for l, (oc, k, s) in enumerate(net.conv):
+        x = torch.relu(torch.nn.functional.conv2d(x, get(f"conv{l + 1}.W"), get(f"conv{l + 1}.b"), stride=s))
+    h = torch.relu(x.reshape(x.shape[0], -1) @ get("fc.W").T + get("fc.b"))
+    logits = h @ get("policy.W").T + get("policy.b")
+    values = (h @ get("value.W").T + get("value.b"))[:, 0]
+    return logits, values
+
+
+@pytest.mark.parametrize("net", [SMALL6, LARGE])
+def test_forward_vs_torch_full_size(net):
+    th = theta_for(net, 11)
+    frames = synth.uniform_frames(12, (4, 4, 84, 84))
+    out = orc.forward(net, th, frames)
+    lg, vl = torch_forward(net, torch.from_numpy(th), torch.from_numpy(frames))
+    np.testing.assert_allclose(out["logits"], lg.numpy(), rtol=1e-10, atol=1e-11)
+    np.testing.assert_allclose(out["values"], vl.numpy(), rtol=1e-10, atol=1e-11)
+
+
+def test_conv_special_cases():
+    # (a) a kernel as large as its input is a fully connected layer;
+    # (b) a one-hot kernel sub-samples the input with the stride.
+    net = orc.Net(in_c=2, in_h=6, in_w=6, conv=((3, 6, 1),), fc_units=4, n_actions=2)
+    th = theta_for(net, 21)
+    frames = synth.uniform_frames(22, (2, 2, 6, 6))
+    acts = orc.forward(net, th, frames, want_acts=True)["acts"]
+    v = orc.views(net, th)
+    x = frames.reshape(2, -1) / 255.0
+    want = np.maximum(x @ v["conv1.W"].reshape(3, -1).T + v["conv1.b"], 0.0)
+    np.testing.assert_allclose(acts[:, 72:75], want, rtol=1e-13)
+
+    net = orc.Net(in_c=1, in_h=9, in_w=9, conv=((1, 3, 2),), fc_units=2, n_actions=2)
+    th = np.zeros(orc.param_count(net)); v = orc.views(net, th)
+    v["conv1.W"][0, 0, 1, 2] = 1.0
+    frames = synth.uniform_frames(23, (1, 1, 9, 9))
+    acts = orc.forward(net, th, frames, want_acts=True)["acts"]
+    got = acts[0, 81:81 + 16].reshape(4, 4)
+    np.testing.assert_allclose(got, frames[0, 0, 1:9:2, 2:9:2][:4, :4] / 255.0, rtol=1e-15)
+
+
+def test_forward_saved_activations_layout():
+    th = theta_for(TINY, 4)
+    frames = synth.uniform_frames(6, (2, 2, 12, 12))
+    acts = orc.forward(TINY, th, frames, want_acts=True)["acts"]
+    assert acts.shape[1] == 2 * 144 + 3 * 25 + 4 * 16 + 5
+    np.testing.assert_allclose(acts[:, :288], frames.reshape(2, -1) / 255.0)
+    assert (acts >= 0).all()
+
+
+# ------------------------------------------------- softmax / entropy / sampler
+
+def test_softmax_invariants():
+    th = theta_for(SMALL18, 31)
+    frames = synth.uniform_frames(32, (5, 4, 84, 84))
+    out = orc.forward(SMALL18, th, frames)
+    p = out["probs"]
+    np.testing.assert_allclose(p.sum(1), 1.0, atol=1e-15)
+    # shift invariance, through the loss routine's internal softmax
+    z = out["logits"]
+    a = np.zeros(5, np.int32); R = np.zeros(5)
+    d1, _, s1 = orc.loss_grad(z, out["values"], a, R, 0.01, 1.0, 0.0)
+    d2, _, s2 = orc.loss_grad(z + 37.5, out["values"], a, R, 0.01, 1.0, 0.0)
+    np.testing.assert_allclose(d1, d2, atol=1e-13)
+    assert 0.0 <= s1["entropy"] <= 5 * math.log(18) + 1e-12
+
+
+def test_entropy_max_at_uniform_policy():
+    # zero policy head -> p = 1/A, H = log A, and the entropy gradient vanishes
+    th = theta_for(SMALL6, 33); v = orc.views(SMALL6, th)
+    v["policy.W"][:] = 0; v["policy.b"][:] = 0
+    frames = synth.uniform_frames(34, (3, 4, 84, 84))
+    out = orc.forward(SMALL6, th, frames)
+    np.testing.assert_allclose(out["probs"], 1 / 6, rtol=1e-15)
+    vals = out["values"]
+    dZ, dV, s = orc.loss_grad(out["logits"], vals, np.zeros(3, np.int32), vals.copy(), 0.7, 1.0, 0.0)
+    assert abs(s["entropy"] - 3 * math.log(6)) < 1e-13
+    np.testing.assert_allclose(dZ, 0.0, atol=1e-15)       # adv = 0 and uniform p
+    np.testing.assert_allclose(dV, 0.0, atol=1e-15)
+
+
+def test_sampler_edges_and_frequencies():
+    p = np.array([[0.0, 0.2, 0.0, 0.5, 0.3, 0.0]])
+    assert orc.sample(p, np.array([0.0]))[0] == 1            # first action with p > 0
+    assert orc.sample(p, np.array([0.19999]))[0] == 1
+    assert orc.sample(p, np.array([0.2]))[0] == 3            # strict '>' at the edge
+    assert orc.sample(p, np.array([0.999999]))[0] == 4
+    assert orc.sample(p, np.array([1.0]))[0] == 5            # nothing exceeds u -> last
+    # frequencies follow p (chi-square, 5 dof, 99.9 % quantile 20.5)
+    q = np.array([0.05, 0.3, 0.1, 0.25, 0.2, 0.1])
+    n = 200000
+    u = synth.rng(77).random(n)
+    a = orc.sample(np.tile(q, (n, 1)), u)
+    cnt = np.bincount(a, minlength=6)
+    chi2 = ((cnt - n * q) ** 2 / (n * q)).sum()
+    assert chi2 < 20.5
+    # equals numpy's searchsorted on the fp64 cumulative sum
+    np.testing.assert_array_equal(a, np.minimum(np.searchsorted(np.cumsum(q), u, side="right"), 5))
+
+
+# ---------------------------------------------------------------- returns ----
+
+def test_returns_closed_forms():
+    N, T, gam = 4, 5, 0.9
+    r = np.full((N, T), 0.5); d = np.zeros((N, T), np.uint8); boot = np.array([0.0, 1.0, -2.0, 3.5])
+    R = orc.returns(r, d, boot, gam)
+    for t in range(T):
+        k = T - t
+        np.testing.assert_allclose(R[:, t], 0.5 * (1 - gam ** k) / (1 - gam) + gam ** k * boot, rtol=1e-14)
+    # gamma = 1: plain sums
+    R1 = orc.returns(r, d, boot, 1.0)
+    np.testing.assert_allclose(R1[:, 0], 2.5 + boot)
+    # every step terminal: R_t = r_t, bootstrap ignored
+    rr = synth.rng(1).standard_normal((N, T))
+    Rd = orc.returns(rr, np.ones((N, T), np.uint8), boot, gam)
+    np.testing.assert_allclose(Rd, rr)
+    # NULL bootstrap = 0
+    np.testing.assert_allclose(orc.returns(r, d, None, gam), orc.returns(r, d, np.zeros(N), gam))
+
+
+def test_returns_direct_sum_with_terminals():
+    # text after Eq. 1: R_t = sum_{i<k} gamma^i r_{t+i} + gamma^k V(s_{t+k}), where the
+    # segment ends at the first terminal at or after t (then no bootstrap term).
+    tr = synth.trajectories(41, 64, 5, 6)
+    r = tr["rewards"].astype(np.float64)
+    d = (synth.rng(42).random((64, 5)) < 0.25).astype(np.uint8)
+    boot = synth.rng(43).standard_normal(64)
+    gam = 0.99
+    R = orc.returns(r, d, boot, gam)
+    for n in range(64):
+        for t in range(5):
+            acc, disc, ended = 0.0, 1.0, False
+            for i in range(t, 5):
+                acc += disc * r[n, i]; disc *= gam
+                if d[n, i]:
+                    ended = True
+                    break
+            if not ended:
+                acc += disc * boot[n]
+            assert abs(R[n, t] - acc) < 1e-13
+
+
+# ------------------------------------------------------- loss, output grads --
+
+def loss_total_np(z, V, a, R, adv, beta, cv, e):
+    """Eq. 1 / 2 / 5 evaluated with log-sum-exp in numpy; adv is passed in frozen."""
+    zs = z - z.max(1, keepdims=True)
+    p = np.exp(zs) / np.exp(zs).sum(1, keepdims=True)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        lp = np.log(p + e)
+    H = -(p * lp).sum(1)
+    pa = p[np.arange(len(a)), a]
+    return (-(np.log(pa + e)) * adv - beta * H + cv * (R - V) ** 2).sum()
+
+
+@pytest.mark.parametrize("eps", [0.0, 1e-3])
+def test_output_gradients(eps):
+    g = synth.rng(51)
+    B, A = 7, 6
+    z = g.standard_normal((B, A)) * 2; V = g.standard_normal(B); R = g.standard_normal(B)
+    a = g.integers(0, A, B).astype(np.int32)
+    beta, cv = 0.3, 0.7
+    dZ, dV, s = orc.loss_grad(z, V, a, R, beta, cv, eps)
+    np.testing.assert_allclose(dV, -2 * cv * (R - V), rtol=1e-14)
+    if eps == 0.0:
+        np.testing.assert_allclose(dZ.sum(1), 0.0, atol=1e-14)   # softmax Jacobian kills constants
+    adv = R - V
+    h = 1e-6
+    for b in range(B):
+        for j in range(A):
+            zp = z.copy(); zm = z.copy(); zp[b, j] += h; zm[b, j] -= h
+            fd = (loss_total_np(zp, V, a, R, adv, beta, cv, eps) - loss_total_np(zm, V, a, R, adv, beta, cv, eps)) / (2 * h)
+            assert abs(fd - dZ[b, j]) < 1e-7 * max(1.0, abs(fd))
+    total = s["policy_loss"] - beta * s["entropy"] + cv * s["value_loss"]
+    assert abs(total - loss_total_np(z, V, a, R, adv, beta, cv, eps)) < 1e-12
+    # adv = 0 and beta = 0  =>  no policy gradient at all
+    dZ0, _, _ = orc.loss_grad(z, V, a, V.copy(), 0.0, cv, eps)
+    np.testing.assert_allclose(dZ0, 0.0, atol=1e-15)
+
+
+def test_eps_bounds_the_log_factor():
+    # Eq. 5 discussion: d log(pi+eps) = dpi / (pi+eps), so the factor is <= 1/eps.
+    z = np.array([[40.0, 0.0, -40.0]]); V = np.zeros(1); R = np.ones(1)
+    a = np.array([2], np.int32)
+    d_plain, _, _ = orc.loss_grad(z, V, a, R, 0.0, 1.0, 0.0)
+    d_eps, _, s = orc.loss_grad(z, V, a, R, 0.0, 1.0, 1e-2)
+    assert np.isfinite(s["policy_loss"])
+    assert abs(d_plain).max() > 0.99            # |p_j - 1| adv with p_a ~ 0
+    assert abs(d_eps).max() < 1e-30             # pi(a) ~ e^-80: gradient bounded by pi/eps
+
+
+# --------------------------------------------------------- whole backward ----
+
+def train_inputs(net, seed, N, T):
+    frames = synth.uniform_frames(seed, (N, T, net.in_c, net.in_h, net.in_w))
+    tr = synth.trajectories(seed + 1, N, T, net.n_actions)
+    boot = synth.rng(seed + 2).standard_normal(N)
+    return frames, tr, boot
+
+
+def torch_loss(net, th_t, frames, tr, R, adv, hp):
+    lg, vl = torch_forward(net, th_t, torch.from_numpy(frames.reshape((-1,) + frames.shape[2:])))
+    a = torch.from_numpy(tr["actions"].reshape(-1).astype(np.int64))
+    p = torch.softmax(lg, 1)
+    lp = torch.log(p + hp.log_eps)
+    H = -(p * lp).sum(1)
+    lpa = lp[torch.arange(len(a)), a]
+    Rt = torch.from_numpy(R.reshape(-1)); advt = torch.from_numpy(adv.reshape(-1))
+    return (-lpa * advt - hp.beta * H + hp.value_coef * (Rt - vl) ** 2).sum()
+
+
+@pytest.mark.parametrize("net,eps", [(TINY, 0.0), (TINY3, 0.0), (TINY, 1e-2)])
+def test_backward_vs_autograd_and_finite_differences(net, eps):
+    hp = orc.HParams(beta=0.2, value_coef=0.6, log_eps=eps, gamma=0.95)
+    th = theta_for(net, 61, scale_bias=0.3)
+    frames, tr, boot = train_inputs(net, 62, 3, 4)
+    res = orc.train_step(net, th, np.zeros_like(th), frames, tr["actions"], tr["rewards"], tr["dones"], boot, hp)
+    R = res["R"]; adv = R.reshape(-1) - res["values"]          # frozen at theta_0 (Eq. 1 uses theta_t)
+    # (1) torch autograd, fp64
+    th_t = torch.from_numpy(th.copy()).requires_grad_(True)
+    torch_loss(net, th_t, frames, tr, R, adv, hp).backward()
+    ga = th_t.grad.numpy()
+    np.testing.assert_allclose(res["grad"], ga, rtol=1e-9, atol=1e-11)
+    assert np.abs(ga).max() > 1e-3
+    # (2) central finite differences on every parameter
+    P = th.size
+    fd = np.zeros(P)
+    h = 1e-6
+    with torch.no_grad():
+        for i in range(P):
+            tp = th.copy(); tp[i] += h; tm = th.copy(); tm[i] -= h
+            fd[i] = (float(torch_loss(net, torch.from_numpy(tp), frames, tr, R, adv, hp)) -
+                     float(torch_loss(net, torch.from_numpy(tm), frames, tr, R, adv, hp))) / (2 * h)
+    err = np.abs(fd - res["grad"]).max() / np.abs(res["grad"]).max()
+    assert err < 1e-6, err
+
+
+def test_backward_vs_autograd_full_small_net():
+    net = SMALL6
+    hp = orc.HParams()
+    th = theta_for(net, 71)
+    frames, tr, boot = train_inputs(net, 72, 2, 5)
+    res = orc.train_step(net, th, np.zeros_like(th), frames, tr["actions"], tr["rewards"], tr["dones"], boot, hp)
+    R = res["R"]; adv = R.reshape(-1) - res["values"]
+    th_t = torch.from_numpy(th.copy()).requires_grad_(True)
+    torch_loss(net, th_t, frames, tr, R, adv, hp).backward()
+    ga = th_t.grad.numpy()
+    for name, (o, shape) in orc.offsets(net).items():
+        n = int(np.prod(shape))
+        a, b = res["grad"][o:o + n], ga[o:o + n]
+        assert np.abs(a - b).max() <= 1e-9 * max(np.abs(b).max(), 1e-12), name
+
+
+def test_gradient_is_additive_over_the_batch():
+    # Sec. 5.3: gradients are summed over the merged training batch.
+    net = TINY
+    hp = orc.HParams(lr=0.0)
+    th = theta_for(net, 81)
+    frames, tr, boot = train_inputs(net, 82, 4, 3)
+    full = orc.train_step(net, th, np.zeros_like(th), frames, tr["actions"], tr["rewards"], tr["dones"], boot, hp)
+    parts = []
+    for sl in (slice(0, 1), slice(1, 4)):
+        parts.append(orc.train_step(net, th, np.zeros_like(th), frames[sl], tr["actions"][sl], tr["rewards"][sl],
+                                    tr["dones"][sl], boot[sl], hp)["grad"])
+    np.testing.assert_allclose(full["grad"], parts[0] + parts[1], rtol=1e-11, atol=1e-13)
+    np.testing.assert_array_equal(full["theta"], th)          # lr = 0 leaves theta alone
+
+
+def test_backward_pieces_match_train_step():
+    net = TINY
+    hp = orc.HParams(beta=0.05)
+    th = theta_for(net, 91)
+    frames, tr, boot = train_inputs(net, 92, 2, 5)
+    res = orc.train_step(net, th, np.zeros_like(th), frames, tr["actions"], tr["rewards"], tr["dones"], boot, hp)
+    fw = orc.forward(net, th, frames.reshape((-1,) + frames.shape[2:]), want_acts=True)
+    R = orc.returns(tr["rewards"], tr["dones"], boot, hp.gamma)
+    dZ, dV, _ = orc.loss_grad(fw["logits"], fw["values"], tr["actions"], R, hp.beta, hp.value_coef, hp.log_eps)
+    grad = orc.backward(net, th, fw["acts"], dZ, dV)
+    np.testing.assert_allclose(grad, res["grad"], rtol=1e-13, atol=1e-15)
+    np.testing.assert_allclose(R, res["R"])
+
+
+# ------------------------------------------------------------ clip, RMSProp --
+
+def test_clip():
+    g = synth.rng(101).standard_normal(1000) * 3
+    n = orc.grad_norm(g)
+    assert abs(n - np.linalg.norm(g)) < 1e-12 * n
+    assert orc.clip_scale(n, 0.0) == 1.0 and orc.clip_scale(n, -1.0) == 1.0
+    assert orc.clip_scale(n, 2 * n) == 1.0
+    s = orc.clip_scale(n, 40.0)
+    assert abs(np.linalg.norm(s * g) - min(n, 40.0)) < 1e-12 * n
+
+
+def test_rmsprop_closed_forms():
+    # Eq. 3, eps inside the root.
+    g = synth.rng(111)
+    th = g.standard_normal(50); d = g.standard_normal(50); d[:5] = 0.0
+    lr, al, eps = 3e-4, 0.99, 0.1
+    t1, g1 = orc.rmsprop(th, np.zeros(50), d, 1.0, lr, al, eps)
+    np.testing.assert_allclose(t1 - th, -lr * d / np.sqrt((1 - al) * d * d + eps), rtol=1e-9, atol=1e-15)  # th - step cancels
+    np.testing.assert_array_equal(t1[:5], th[:5]); np.testing.assert_array_equal(g1[:5], 0.0)
+    # |step| <= lr / sqrt(1 - alpha) whatever the gradient, eps >= 0
+    big = g.standard_normal(50) * 1e6
+    t2, _ = orc.rmsprop(th, np.zeros(50), big, 1.0, lr, al, 0.0)
+    assert np.abs(t2 - th).max() <= lr / math.sqrt(1 - al) * (1 + 1e-12)
+    # k steps of a constant gradient: g_k = d^2 (1 - alpha^k)
+    tk, gk = th, np.zeros(50)
+    for _ in range(7):
+        tk, gk = orc.rmsprop(tk, gk, d, 1.0, lr, al, eps)
+    np.testing.assert_allclose(gk, d * d * (1 - al ** 7), rtol=1e-12)
+    # the clip scale multiplies the gradient before both uses
+    t3, g3 = orc.rmsprop(th, np.zeros(50), d, 0.25, lr, al, eps)
+    t4, g4 = orc.rmsprop(th, np.zeros(50), 0.25 * d, 1.0, lr, al, eps)
+    np.testing.assert_allclose(t3, t4, rtol=1e-15); np.testing.assert_allclose(g3, g4, rtol=1e-15)
+
+
+def test_train_step_composes_clip_and_rmsprop():
+    net = TINY
+    hp = orc.HParams(clip_norm=0.05, lr=1e-2)
+    th = theta_for(net, 121); g0 = np.abs(synth.rng(122).standard_normal(th.size)) * 0.01
+    frames, tr, boot = train_inputs(net, 123, 3, 5)
+    res = orc.train_step(net, th, g0, frames, tr["actions"], tr["rewards"], tr["dones"], boot, hp)
+    n = np.linalg.norm(res["grad"])
+    assert n > 0.05 and abs(res["stats"]["grad_norm"] - n) < 1e-12 * n
+    s = 0.05 / n
+    assert abs(res["stats"]["clip_scale"] - s) < 1e-15
+    d = s * res["grad"]
+    g1 = 0.99 * g0 + 0.01 * d * d
+    np.testing.assert_allclose(res["g"], g1, rtol=1e-13)
+    np.testing.assert_allclose(res["theta"], th - 1e-2 * d / np.sqrt(g1 + 0.1), rtol=1e-13, atol=1e-16)
