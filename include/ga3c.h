@@ -1,0 +1,175 @@
+/*
+ * ga3c.h -- C ABI of the MI355X (gfx950) library for the GPU side of hybrid
+ * CPU/GPU A3C (arXiv 1611.06256, "GA3C").
+ *
+ * The paper keeps ONE copy of the policy/value network on the GPU
+ * (Sec. 4.1).  Predictor threads send it batches of states and get back the
+ * policy and the value; trainer threads send it batches of experiences and
+ * the network is updated in place.  This library is that network: two calls
+ * that do all of their work in hand-written HIP kernels, plus parameter
+ * access.
+ *
+ * Conventions that hold for every entry point
+ *   - Pointers named *_dev are DEVICE memory owned by the caller; pointers
+ *     without the suffix are HOST memory.  The library never frees or keeps a
+ *     caller's pointer beyond the kernels it enqueues in that call.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *     Calls only enqueue work on it and never synchronise the host; outputs
+ *     are valid once the caller has synchronised the stream.  Calls on one
+ *     context must be stream-ordered with respect to each other (they share
+ *     the context's workspaces and parameters); ordering across two streams
+ *     is the caller's job (events).
+ *   - Return value: GA3C_OK or a negative GA3C_E* code.  Nothing is printed,
+ *     no C++ exception crosses the boundary.  ga3c_last_error() returns a
+ *     thread-local description of the last failure on the calling thread.
+ *   - Float tensors are IEEE fp32, row-major, the last index fastest.
+ *
+ * Flat parameter vector (what ga3c_params_get / _set speak), in this order:
+ *   for each conv layer l: W[oc][ic][kh][kw], b[oc];
+ *   fc W[fc_units][flat] with flat index = c*H*W + h*W + w of the last conv
+ *   output, fc b[fc_units]; policy W[n_actions][fc_units], policy b[n_actions];
+ *   value W[fc_units], value b[1].
+ */
+#ifndef GA3C_H
+#define GA3C_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define GA3C_OK        0
+#define GA3C_EINVAL   -1   /* null pointer, bad shape, batch above the capacity given at create */
+#define GA3C_ENOMEM   -2   /* device or host allocation failed */
+#define GA3C_EHIP     -3   /* a HIP runtime call failed; see ga3c_last_error() */
+
+#define GA3C_MAX_CONV  4
+#define GA3C_MAX_ACTIONS 63
+
+typedef struct ga3c_ctx ga3c_ctx;   /* opaque: parameters, RMSProp state, gradient, workspaces */
+
+/* Network shape.  Sec. 3.2 describes the small network: conv 16 filters 8x8
+ * stride 4, conv 32 filters 4x4 stride 2, fully connected 256, a rectifier
+ * after each hidden layer, a softmax policy output and a linear value
+ * output.  Convolutions are VALID cross-correlations.  Limits: n_conv in
+ * [1,4]; n_actions in [1,63]; every spatial size must stay >= 1. */
+typedef struct {
+    int in_c, in_h, in_w;                 /* input planes / height / width (4, 84, 84) */
+    int n_conv;
+    struct { int oc, k, stride; } conv[GA3C_MAX_CONV];
+    int fc_units;
+    int n_actions;
+    int math;                             /* 0 = fp32 MFMA (the only mode built so far) */
+} ga3c_net_desc;
+
+/* Hyper-parameters of one update, read on the host at call time.
+ *   gamma      discount of the n-step return (text after Eq. 1)
+ *   beta       weight of the entropy term (Eq. 1)
+ *   value_coef weight of the value cost (Eq. 2 has none: 1.0)
+ *   log_eps    epsilon added inside the logarithms (Eq. 5); 0 = plain Eq. 1
+ *   lr, rms_decay, rms_eps   eta, alpha, epsilon of RMSProp (Eq. 3; epsilon
+ *              is inside the square root)
+ *   clip_norm  threshold of the global L2-norm rescale of the summed
+ *              gradient; <= 0 disables it */
+typedef struct {
+    float gamma, beta, value_coef, log_eps;
+    float lr, rms_decay, rms_eps, clip_norm;
+} ga3c_hparams;
+
+/* Written by ga3c_train_step to device memory when asked for.  Losses are
+ * SUMS over the frames of the call (Sec. 5.3 sums gradients over the batch).
+ * nonfinite is 1 when the gradient norm is NaN or infinite. */
+typedef struct {
+    float policy_loss, value_loss, entropy, grad_norm, clip_scale;
+    int32_t nonfinite;
+} ga3c_train_stats;
+
+/* Create a context on the current HIP device.  Allocates (with hipMalloc)
+ * the parameters theta, the RMSProp accumulator g, the gradient and all
+ * workspaces for up to max_predict_batch frames per ga3c_predict and
+ * max_train_frames frames (= N*T) per ga3c_train_step.  theta and g start at
+ * zero.  On failure *out is NULL. */
+int ga3c_create(const ga3c_net_desc *desc, int max_predict_batch, int max_train_frames,
+                ga3c_ctx **out);
+
+/* Waits for the device, then frees everything the context owns. */
+int ga3c_destroy(ga3c_ctx *ctx);
+
+/* Number of floats in the flat parameter vector (0 for a NULL context). */
+size_t ga3c_params_count(const ga3c_ctx *ctx);
+
+/* Offsets of the tensors in the flat vector, in the order listed at the top,
+ * followed by the total: 2*n_conv + 7 entries.  `off` is host memory with
+ * room for `cap` entries; returns the number written or GA3C_EINVAL. */
+int ga3c_params_offsets(const ga3c_ctx *ctx, int64_t *off, int cap);
+
+/* theta: weights ~ N(0, 2/fan_in) ("He normal"), biases 0; g = 0.  The
+ * normal deviates come from a counter-based generator keyed by (seed, flat
+ * index), so the result depends on nothing else.  (The paper does not state
+ * its initialisation.) */
+int ga3c_params_init(ga3c_ctx *ctx, uint64_t seed, void *stream);
+
+/* Copy n = ga3c_params_count() floats out of / into the context.
+ * which: 0 = theta, 1 = RMSProp accumulator g, 2 = gradient of the last
+ * ga3c_train_step (unclipped sum over its frames; get only). */
+int ga3c_params_get(ga3c_ctx *ctx, int which, float *dst_dev, size_t n, void *stream);
+int ga3c_params_set(ga3c_ctx *ctx, int which, const float *src_dev, size_t n, void *stream);
+
+/* Prediction (Sec. 4.1, the predictor's inference query): states in, policy
+ * and value out.
+ *   frames_dev   u8 [B][in_c][in_h][in_w], raw pixels; scaled by 1/255 inside
+ *   uniforms_dev f32 [B] in [0,1), or NULL.  Needed iff actions_dev != NULL.
+ *   logits_dev   f32 [B][n_actions]  pre-softmax policy output (may be NULL)
+ *   values_dev   f32 [B]             V(s) (may be NULL)
+ *   probs_dev    f32 [B][n_actions]  softmax policy pi(.|s) (may be NULL)
+ *   actions_dev  i32 [B] (may be NULL): a = the first j whose running fp32 sum
+ *                p_0 + ... + p_j (added left to right) exceeds u, else
+ *                n_actions - 1.
+ * 0 <= B <= max_predict_batch; B = 0 is a no-op. */
+int ga3c_predict(ga3c_ctx *ctx, const uint8_t *frames_dev, int B,
+                 const float *uniforms_dev,
+                 float *logits_dev, float *values_dev, float *probs_dev, int32_t *actions_dev,
+                 void *stream);
+
+/* One A3C update on N agents x T steps (Sec. 3.2; Sec. 4.1, the trainer's
+ * model update; gradients summed over all N*T frames, Sec. 5.3):
+ *   R[n][T] = bootstrap[n]; R[n][t] = r[n][t] + gamma (1 - done[n][t]) R[n][t+1]
+ *   minimise  sum_i  -log(pi_i[a_i] + log_eps) (R_i - V_i)        (R_i - V_i constant here)
+ *                    - beta H(pi_i) + value_coef (R_i - V_i)^2    (Eq. 1, 2, 5)
+ *   d = min(1, clip_norm / ||grad||) * grad;  g = alpha g + (1 - alpha) d^2;
+ *   theta -= lr d / sqrt(g + rms_eps)                             (Eq. 3)
+ *   frames_dev    u8  [N][T][in_c][in_h][in_w]
+ *   actions_dev   i32 [N][T], each in [0, n_actions)
+ *   rewards_dev   f32 [N][T]
+ *   dones_dev     u8  [N][T], non-zero = the episode ended with this step
+ *   bootstrap_dev f32 [N] value of the state after the last step, or NULL = 0
+ *   hp            host pointer
+ *   stats_dev     device pointer or NULL
+ * N*T <= max_train_frames; N*T = 0 is a no-op. */
+int ga3c_train_step(ga3c_ctx *ctx, const uint8_t *frames_dev, const int32_t *actions_dev,
+                    const float *rewards_dev, const uint8_t *dones_dev,
+                    const float *bootstrap_dev, int N, int T,
+                    const ga3c_hparams *hp, ga3c_train_stats *stats_dev, void *stream);
+
+/* Intermediates of the last ga3c_train_step, for checking it step by step.
+ * which: 0 = returns R [N*T]; 1 = logits [N*T][A]; 2 = values [N*T];
+ * 3 = dL/d(logits, value) [N*T][A+1].  Copies n floats (n must not exceed the
+ * tensor's size for the last call's N*T). */
+int ga3c_train_debug_get(ga3c_ctx *ctx, int which, float *dst_dev, size_t n, void *stream);
+
+/* RMSProp alone (Eq. 3) on caller-owned flat buffers of any length, with the
+ * same kernel ga3c_train_step uses; scale multiplies the gradient first.
+ * Exists so that the kernel can be measured on a buffer far larger than the
+ * last-level cache. */
+int ga3c_rmsprop_flat(float *theta_dev, float *g_dev, const float *grad_dev, size_t n,
+                      float scale, float lr, float rms_decay, float rms_eps, void *stream);
+
+/* Thread-local text of the last error on this thread ("" if none). */
+const char *ga3c_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GA3C_H */

@@ -1,0 +1,258 @@
+"""ctypes binding of libga3c.so.  Argument marshalling only.
+
+torch is used for device memory and for the stream handle; tensors passed in
+must live on the GPU, be contiguous and have the dtype the C ABI names.
+There is no CPU fallback: without the compiled library, or without a GPU,
+the calls raise.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Dict, Optional, Sequence, Tuple
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+MAX_CONV = 4
+
+
+class Ga3cError(RuntimeError):
+    pass
+
+
+class _Conv(C.Structure):
+    _fields_ = [("oc", C.c_int), ("k", C.c_int), ("stride", C.c_int)]
+
+
+class _NetDesc(C.Structure):
+    _fields_ = [("in_c", C.c_int), ("in_h", C.c_int), ("in_w", C.c_int), ("n_conv", C.c_int),
+                ("conv", _Conv * MAX_CONV), ("fc_units", C.c_int), ("n_actions", C.c_int), ("math", C.c_int)]
+
+
+class _HParams(C.Structure):
+    _fields_ = [(n, C.c_float) for n in
+                ("gamma", "beta", "value_coef", "log_eps", "lr", "rms_decay", "rms_eps", "clip_norm")]
+
+
+class TrainStats(C.Structure):
+    _fields_ = [("policy_loss", C.c_float), ("value_loss", C.c_float), ("entropy", C.c_float),
+                ("grad_norm", C.c_float), ("clip_scale", C.c_float), ("nonfinite", C.c_int32)]
+
+
+@dataclass
+class NetDesc:
+    in_c: int = 4
+    in_h: int = 84
+    in_w: int = 84
+    conv: Sequence[Tuple[int, int, int]] = ((16, 8, 4), (32, 4, 2))
+    fc_units: int = 256
+    n_actions: int = 18
+    math: int = 0
+
+    def c(self) -> _NetDesc:
+        d = _NetDesc()
+        d.in_c, d.in_h, d.in_w, d.n_conv = self.in_c, self.in_h, self.in_w, len(self.conv)
+        for i, (oc, k, s) in enumerate(self.conv):
+            d.conv[i].oc, d.conv[i].k, d.conv[i].stride = oc, k, s
+        d.fc_units, d.n_actions, d.math = self.fc_units, self.n_actions, self.math
+        return d
+
+
+def SMALL_NET(n_actions: int = 18) -> NetDesc:
+    return NetDesc(n_actions=n_actions)
+
+
+def LARGE_NET(n_actions: int = 18) -> NetDesc:
+    return NetDesc(conv=((32, 8, 4), (64, 4, 2), (64, 3, 1)), fc_units=512, n_actions=n_actions)
+
+
+@dataclass
+class HParams:
+    gamma: float = 0.99
+    beta: float = 0.01
+    value_coef: float = 1.0
+    log_eps: float = 0.0
+    lr: float = 3e-4
+    rms_decay: float = 0.99
+    rms_eps: float = 0.1
+    clip_norm: float = 0.0
+
+    def c(self) -> _HParams:
+        return _HParams(self.gamma, self.beta, self.value_coef, self.log_eps,
+                        self.lr, self.rms_decay, self.rms_eps, self.clip_norm)
+
+
+def lib_path() -> str:
+    return os.path.join(HERE, "libga3c.so")
+
+
+_lib = None
+
+EXPORTS = ("ga3c_create", "ga3c_destroy", "ga3c_params_count", "ga3c_params_offsets", "ga3c_params_init",
+           "ga3c_params_get", "ga3c_params_set", "ga3c_predict", "ga3c_train_step", "ga3c_train_debug_get",
+           "ga3c_rmsprop_flat", "ga3c_last_error")
+
+
+def load_library() -> C.CDLL:
+    """Loads the built library; builds it first only if it is not there."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = lib_path()
+    if not os.path.exists(path):
+        from . import build as _build
+        _build.build(True)
+    lib = C.CDLL(path)
+    vp, i32, u64, sz, f32 = C.c_void_p, C.c_int, C.c_uint64, C.c_size_t, C.c_float
+    lib.ga3c_create.argtypes = [C.POINTER(_NetDesc), i32, i32, C.POINTER(vp)]
+    lib.ga3c_destroy.argtypes = [vp]
+    lib.ga3c_params_count.argtypes = [vp]
+    lib.ga3c_params_count.restype = sz
+    lib.ga3c_params_offsets.argtypes = [vp, C.POINTER(C.c_int64), i32]
+    lib.ga3c_params_init.argtypes = [vp, u64, vp]
+    lib.ga3c_params_get.argtypes = [vp, i32, vp, sz, vp]
+    lib.ga3c_params_set.argtypes = [vp, i32, vp, sz, vp]
+    lib.ga3c_predict.argtypes = [vp, vp, i32, vp, vp, vp, vp, vp, vp]
+    lib.ga3c_train_step.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, C.POINTER(_HParams), vp, vp]
+    lib.ga3c_train_debug_get.argtypes = [vp, i32, vp, sz, vp]
+    lib.ga3c_rmsprop_flat.argtypes = [vp, vp, vp, sz, f32, f32, f32, f32, vp]
+    lib.ga3c_last_error.restype = C.c_char_p
+    _lib = lib
+    return lib
+
+
+def _check(rc: int, what: str) -> None:
+    if rc < 0:
+        raise Ga3cError(f"{what} failed ({rc}): {load_library().ga3c_last_error().decode()}")
+
+
+def _ptr(t, dtype, what: str):
+    """Device pointer of a tensor after checking device, dtype and layout."""
+    import torch
+    if t is None:
+        return None
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise Ga3cError(f"{what}: expected a GPU tensor")
+    if t.dtype != dtype:
+        raise Ga3cError(f"{what}: expected dtype {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise Ga3cError(f"{what}: tensor must be contiguous")
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> C.c_void_p:
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return C.c_void_p(s.cuda_stream)
+
+
+class Ga3c:
+    """One network on the current GPU: ga3c_create .. ga3c_destroy."""
+
+    def __init__(self, desc: NetDesc, max_predict_batch: int, max_train_frames: int):
+        import torch
+        if not torch.cuda.is_available():
+            raise Ga3cError("no GPU visible: the HIP path has no CPU fallback")
+        self._lib = load_library()
+        self.desc = desc
+        self._ctx = C.c_void_p()
+        cd = desc.c()
+        _check(self._lib.ga3c_create(C.byref(cd), max_predict_batch, max_train_frames, C.byref(self._ctx)),
+               "ga3c_create")
+        self.n_params = int(self._lib.ga3c_params_count(self._ctx))
+        self.n_actions = desc.n_actions
+
+    def close(self) -> None:
+        if getattr(self, "_ctx", None) is not None and self._ctx.value:
+            self._lib.ga3c_destroy(self._ctx)
+            self._ctx = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def offsets(self) -> Dict[str, Tuple[int, Tuple[int, ...]]]:
+        """Name -> (offset, shape) of each tensor in the flat parameter vector."""
+        off = (C.c_int64 * (2 * MAX_CONV + 7))()
+        n = self._lib.ga3c_params_offsets(self._ctx, off, len(off))
+        _check(n, "ga3c_params_offsets")
+        o = [int(off[i]) for i in range(n)]
+        d = self.desc
+        out: Dict[str, Tuple[int, Tuple[int, ...]]] = {}
+        c, h, w = d.in_c, d.in_h, d.in_w
+        for l, (oc, k, s) in enumerate(d.conv):
+            out[f"conv{l + 1}.W"] = (o[2 * l], (oc, c, k, k))
+            out[f"conv{l + 1}.b"] = (o[2 * l + 1], (oc,))
+            c, h, w = oc, (h - k) // s + 1, (w - k) // s + 1
+        nb = 2 * len(d.conv)
+        out["fc.W"] = (o[nb], (d.fc_units, c * h * w))
+        out["fc.b"] = (o[nb + 1], (d.fc_units,))
+        out["policy.W"] = (o[nb + 2], (d.n_actions, d.fc_units))
+        out["policy.b"] = (o[nb + 3], (d.n_actions,))
+        out["value.W"] = (o[nb + 4], (1, d.fc_units))
+        out["value.b"] = (o[nb + 5], (1,))
+        return out
+
+    def params_init(self, seed: int, stream=None) -> None:
+        _check(self._lib.ga3c_params_init(self._ctx, seed, _stream(stream)), "ga3c_params_init")
+
+    def params_get(self, which: int = 0, out=None, stream=None):
+        import torch
+        if out is None:
+            out = torch.empty(self.n_params, dtype=torch.float32, device="cuda")
+        _check(self._lib.ga3c_params_get(self._ctx, which, _ptr(out, torch.float32, "out"), out.numel(),
+                                         _stream(stream)), "ga3c_params_get")
+        return out
+
+    def params_set(self, src, which: int = 0, stream=None) -> None:
+        import torch
+        _check(self._lib.ga3c_params_set(self._ctx, which, _ptr(src, torch.float32, "src"), src.numel(),
+                                         _stream(stream)), "ga3c_params_set")
+
+    def predict(self, frames, uniforms=None, logits=None, values=None, probs=None, actions=None, stream=None):
+        """frames u8 [B,C,H,W].  Output tensors that are passed in are filled."""
+        import torch
+        B = int(frames.shape[0])
+        _check(self._lib.ga3c_predict(self._ctx, _ptr(frames, torch.uint8, "frames"), B,
+                                      _ptr(uniforms, torch.float32, "uniforms"),
+                                      _ptr(logits, torch.float32, "logits"), _ptr(values, torch.float32, "values"),
+                                      _ptr(probs, torch.float32, "probs"), _ptr(actions, torch.int32, "actions"),
+                                      _stream(stream)), "ga3c_predict")
+
+    def train_step(self, frames, actions, rewards, dones, bootstrap, hp: HParams, stats=None, stream=None) -> None:
+        """frames u8 [N,T,C,H,W]; actions i32, rewards f32, dones u8 [N,T]; bootstrap f32 [N] or None;
+        stats: optional u8/any GPU tensor of at least 24 bytes that receives ga3c_train_stats."""
+        import torch
+        N, T = int(frames.shape[0]), int(frames.shape[1])
+        hpc = hp.c()
+        sp = None
+        if stats is not None:
+            if not stats.is_cuda or stats.numel() * stats.element_size() < C.sizeof(TrainStats):
+                raise Ga3cError("stats: need a GPU tensor of at least 24 bytes")
+            sp = C.c_void_p(stats.data_ptr())
+        _check(self._lib.ga3c_train_step(self._ctx, _ptr(frames, torch.uint8, "frames"),
+                                         _ptr(actions, torch.int32, "actions"), _ptr(rewards, torch.float32, "rewards"),
+                                         _ptr(dones, torch.uint8, "dones"), _ptr(bootstrap, torch.float32, "bootstrap"),
+                                         N, T, C.byref(hpc), sp, _stream(stream)), "ga3c_train_step")
+
+    def train_debug_get(self, which: int, out, stream=None):
+        import torch
+        _check(self._lib.ga3c_train_debug_get(self._ctx, which, _ptr(out, torch.float32, "out"), out.numel(),
+                                              _stream(stream)), "ga3c_train_debug_get")
+        return out
+
+
+def rmsprop_flat(theta, g, grad, scale: float, lr: float, rms_decay: float, rms_eps: float, stream=None) -> None:
+    import torch
+    _check(load_library().ga3c_rmsprop_flat(_ptr(theta, torch.float32, "theta"), _ptr(g, torch.float32, "g"),
+                                            _ptr(grad, torch.float32, "grad"), theta.numel(), scale, lr, rms_decay,
+                                            rms_eps, _stream(stream)), "ga3c_rmsprop_flat")
+
+
+def stats_from_tensor(t) -> Dict[str, float]:
+    """Decode a ga3c_train_stats struct held in a (synchronised) GPU tensor."""
+    raw = bytes(t.detach().cpu().numpy().tobytes()[:C.sizeof(TrainStats)])
+    st = TrainStats.from_buffer_copy(raw)
+    return {n: getattr(st, n) for n, _ in TrainStats._fields_}

@@ -1,0 +1,32 @@
+"""Compiles the HIP library for gfx950 with hipcc (in-tree, next to this file)."""
+from __future__ import annotations
+
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB = os.path.join(HERE, "libga3c.so")
+SOURCES = [os.path.join(HERE, "csrc", "ga3c.hip")]
+HEADERS = [os.path.join(HERE, "csrc", "gemm_mfma.hpp"), os.path.join(HERE, "csrc", "problems.hpp"),
+           os.path.join(os.path.dirname(HERE), "include", "ga3c.h")]
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
+         # packed fp32 instructions stay off: the compiler must not form them
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+
+
+def stale() -> bool:
+    if not os.path.exists(LIB):
+        return True
+    t = os.path.getmtime(LIB)
+    return any(os.path.getmtime(f) > t for f in SOURCES + HEADERS)
+
+
+def build(force: bool = True) -> str:
+    if force or stale():
+        hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+        subprocess.check_call([hipcc] + FLAGS + ["-o", LIB] + SOURCES)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(True))

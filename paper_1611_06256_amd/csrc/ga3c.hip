@@ -1,0 +1,801 @@
+// GA3C hot path on MI355X (gfx950): the C ABI declared in include/ga3c.h and
+// the kernels behind it that are not matrix products (heads + softmax +
+// sampling, returns + loss, reductions, RMSProp, parameter initialisation).
+// The matrix products are instances of gemm_mfma.hpp / problems.hpp.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/ga3c.h"
+#include "problems.hpp"
+
+using namespace ga3c;
+
+// ---------------------------------------------------------------- errors ----
+
+static thread_local char g_err[512] = "";
+
+static int fail(int code, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+#define HIP_TRY(expr)                                                                   \
+    do {                                                                                \
+        hipError_t e_ = (expr);                                                         \
+        if (e_ != hipSuccess)                                                           \
+            return fail(e_ == hipErrorOutOfMemory ? GA3C_ENOMEM : GA3C_EHIP, "%s: %s", \
+                        #expr, hipGetErrorString(e_));                                  \
+    } while (0)
+
+extern "C" const char *ga3c_last_error(void) { return g_err; }
+
+// ---------------------------------------------------------------- context ---
+
+namespace {
+
+constexpr int NORM_BLOCKS = 256;    // partial sums of the squared gradient norm
+constexpr int LOSS_THREADS = 128;   // agents per block in the returns/loss kernel
+
+struct Work {            // activations of one call; predict and train own one each
+    int cap = 0;         // frames
+    float *act[GA3C_MAX_CONV] = {nullptr, nullptr, nullptr, nullptr};   // conv outputs, NCHW, post-ReLU
+    float *h = nullptr;  // fc output [cap][F], post-ReLU
+    float *zv = nullptr; // logits and value [cap][A+1]
+    float *ws = nullptr; // split-k partial products of this call
+    size_t ws_floats = 0;
+};
+
+}  // namespace
+
+struct ga3c_ctx {
+    ga3c_net_desc desc;
+    int nconv, F, A, flat;
+    ConvGeom geom[GA3C_MAX_CONV];
+    int *koff[GA3C_MAX_CONV];
+    int64_t off[2 * GA3C_MAX_CONV + 7];
+    int noff;
+    size_t P;
+    int max_pred, max_train;
+    float *theta, *g, *grad;
+    Work pred, train;
+    // training only
+    float *dact[GA3C_MAX_CONV];   // dL/d(pre-activation) of each conv output
+    float *dh;                    // dL/d(pre-activation) of the fc output
+    float *dzv;                   // dL/d(logits, value) [cap][A+1]
+    float *R;                     // returns [cap]
+    float *partials;              // NORM_BLOCKS + 3 * loss blocks
+    float *scale;                 // clip scale of the last step (1 float)
+    ga3c_train_stats *stats;      // stats of the last step
+    int last_frames;
+};
+
+namespace {
+
+// ------------------------------------------------------------ small kernels -
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+// Policy and value heads (Sec. 3.2: softmax policy output, linear value
+// output) for one frame per wavefront, then softmax and inverse-CDF sampling.
+// h [B][F]; Wp [A][F], bp [A], Wv [F], bv [1].  zv [B][A+1] is written when
+// not null (training keeps it); logits / values / probs / actions are the
+// caller's optional outputs.
+__global__ __launch_bounds__(256) void heads_fwd_kernel(const float *__restrict__ h, int B, int F, int A,
+                                                        const float *__restrict__ Wp, const float *__restrict__ bp,
+                                                        const float *__restrict__ Wv, const float *__restrict__ bv,
+                                                        float *zv, float *logits, float *values, float *probs,
+                                                        const float *uniforms, int32_t *actions) {
+    const int lane = threadIdx.x & 63;
+    const int b = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (b >= B) return;
+    const float *hb = h + (size_t)b * F;
+    // lane j ends up with output j (j < A: logit j, j == A: value)
+    float mine = 0.f;
+    for (int a = 0; a <= A; ++a) {
+        const float *wr = a < A ? Wp + (size_t)a * F : Wv;
+        float s = 0.f;
+        for (int k = lane; k < F; k += 64) s += hb[k] * wr[k];
+        s = wave_sum(s);
+        if (lane == a) mine = s + (a < A ? bp[a] : bv[0]);
+    }
+    if (lane <= A && zv) zv[(size_t)b * (A + 1) + lane] = mine;
+    if (lane < A && logits) logits[(size_t)b * A + lane] = mine;
+    if (lane == A && values) values[b] = mine;
+    if (!probs && !actions) return;
+    const float zmax = wave_max(lane < A ? mine : -INFINITY);
+    const float e = lane < A ? expf(mine - zmax) : 0.f;
+    const float p = e / wave_sum(e);
+    if (lane < A && probs) probs[(size_t)b * A + lane] = p;
+    if (actions) {
+        const float u = uniforms[b];
+        float c = 0.f;
+        int act = A - 1;
+        for (int j = 0; j < A; ++j) {           // left-to-right fp32 running sum
+            c += __shfl(p, j, 64);
+            if (c > u) { act = j; break; }      // uniform across the wave: every lane sees the same c
+        }
+        if (lane == 0) actions[b] = act;
+    }
+}
+
+// n-step returns (text after Eq. 1) and the loss with its gradient w.r.t. the
+// head outputs (Eq. 1, 2, 5), one thread per agent walking its T steps
+// backwards.  Per-block sums of the three loss pieces go to part[3*block..].
+__global__ __launch_bounds__(LOSS_THREADS) void returns_loss_kernel(
+    const float *__restrict__ zv, const int32_t *__restrict__ actions, const float *__restrict__ rewards,
+    const uint8_t *__restrict__ dones, const float *__restrict__ bootstrap, int N, int T, int A, float gamma,
+    float beta, float cv, float eps, float *__restrict__ R, float *__restrict__ dzv, float *__restrict__ part) {
+    const int n = blockIdx.x * LOSS_THREADS + threadIdx.x;
+    float s_pl = 0.f, s_vl = 0.f, s_en = 0.f;
+    if (n < N) {
+        float next = bootstrap ? bootstrap[n] : 0.f;
+        for (int t = T - 1; t >= 0; --t) {
+            const size_t i = (size_t)n * T + t;
+            next = rewards[i] + gamma * (dones[i] ? 0.f : 1.f) * next;
+            R[i] = next;
+            const float *z = zv + i * (A + 1);
+            float *dz = dzv + i * (A + 1);
+            const float V = z[A];
+            const int a = actions[i];
+            const float adv = next - V;
+            float zmax = z[0];
+            for (int j = 1; j < A; ++j) zmax = fmaxf(zmax, z[j]);
+            float S = 0.f;
+            for (int j = 0; j < A; ++j) S += expf(z[j] - zmax);
+            const float logS = logf(S), invS = 1.f / S;
+            // dL/dp_k = beta (lg_k + r_k) - [k=a] adv/(p_a+eps);  lg = log(p+eps), r = p/(p+eps)
+            float H = 0.f, dot = 0.f, lga = 0.f, ra = 1.f;
+            for (int j = 0; j < A; ++j) {
+                const float p = expf(z[j] - zmax) * invS;
+                float lg, r;
+                if (eps == 0.f) { lg = z[j] - zmax - logS; r = 1.f; }
+                else { lg = logf(p + eps); r = p / (p + eps); }
+                H -= p * lg;
+                dot += p * beta * (lg + r);
+                if (j == a) { lga = lg; ra = r; }
+            }
+            dot -= adv * ra;
+            for (int j = 0; j < A; ++j) {
+                const float p = expf(z[j] - zmax) * invS;
+                float lg, r;
+                if (eps == 0.f) { lg = z[j] - zmax - logS; r = 1.f; }
+                else { lg = logf(p + eps); r = p / (p + eps); }
+                dz[j] = p * (beta * (lg + r) - dot) - (j == a ? adv * ra : 0.f);
+            }
+            dz[A] = -2.f * cv * adv;
+            s_pl += -lga * adv;
+            s_vl += adv * adv;
+            s_en += H;
+        }
+    }
+    __shared__ float sh[3][LOSS_THREADS / 64];
+    s_pl = wave_sum(s_pl); s_vl = wave_sum(s_vl); s_en = wave_sum(s_en);
+    if ((threadIdx.x & 63) == 0) {
+        sh[0][threadIdx.x >> 6] = s_pl; sh[1][threadIdx.x >> 6] = s_vl; sh[2][threadIdx.x >> 6] = s_en;
+    }
+    __syncthreads();
+    if (threadIdx.x < 3) {
+        float s = 0.f;
+        for (int w = 0; w < LOSS_THREADS / 64; ++w) s += sh[threadIdx.x][w];
+        part[3 * blockIdx.x + threadIdx.x] = s;
+    }
+}
+
+// dL/d(pre-activation of fc)[b][k] = [h > 0] * (sum_a dz[b][a] Wp[a][k] + dv[b] Wv[k]).
+__global__ __launch_bounds__(256) void heads_dgrad_kernel(const float *__restrict__ dzv, const float *__restrict__ h,
+                                                          const float *__restrict__ Wp, const float *__restrict__ Wv,
+                                                          int B, int F, int A, float *__restrict__ dh) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= (size_t)B * F) return;
+    const int b = (int)(i / F), k = (int)(i % F);
+    const float *dz = dzv + (size_t)b * (A + 1);
+    float s = dz[A] * Wv[k];
+    for (int a = 0; a < A; ++a) s += dz[a] * Wp[(size_t)a * F + k];
+    dh[i] = h[i] > 0.f ? s : 0.f;
+}
+
+// Adds the nz split-k partials ws[z][M][N] in order of z.
+// WGRAD: rows [r0, r1) go to gW[(m-r0)*(N-1) + n] for n < N-1 and gb[m-r0] for n = N-1.
+__global__ __launch_bounds__(256) void reduce_wgrad_kernel(const float *__restrict__ ws, int nz, int M, int N, int r0,
+                                                           int r1, float *__restrict__ gW, float *__restrict__ gb) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t cnt = (size_t)(r1 - r0) * N;
+    if (i >= cnt) return;
+    const int m = r0 + (int)(i / N), n = (int)(i % N);
+    float s = 0.f;
+    for (int z = 0; z < nz; ++z) s += ws[((size_t)z * M + m) * N + n];
+    if (n < N - 1) gW[(size_t)(m - r0) * (N - 1) + n] = s;
+    else gb[m - r0] = s;
+}
+
+// out[m][n] = max(0, sum_z ws[z][m][n] + bias[n]).
+__global__ __launch_bounds__(256) void reduce_bias_relu_kernel(const float *__restrict__ ws, int nz, int M, int N,
+                                                               const float *__restrict__ bias, float *__restrict__ out) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= (size_t)M * N) return;
+    float s = 0.f;
+    for (int z = 0; z < nz; ++z) s += ws[(size_t)z * M * N + i];
+    s += bias[i % N];
+    out[i] = s > 0.f ? s : 0.f;
+}
+
+// Block b sums the squares of its contiguous slice of grad.
+__global__ __launch_bounds__(256) void sqnorm_partial_kernel(const float *__restrict__ grad, size_t n,
+                                                             float *__restrict__ part) {
+    const size_t per = (n + gridDim.x - 1) / gridDim.x;
+    const size_t lo = per * blockIdx.x, hi = lo + per < n ? lo + per : n;
+    float s = 0.f;
+    for (size_t i = lo + threadIdx.x; i < hi; i += 256) s += grad[i] * grad[i];
+    __shared__ float sh[4];
+    s = wave_sum(s);
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) part[blockIdx.x] = sh[0] + sh[1] + sh[2] + sh[3];
+}
+
+// One wavefront: total norm, clip scale s = min(1, c/||grad||) (c <= 0: off),
+// and the loss sums.  Writes scale[0], *own and, if not null, *user.
+__global__ __launch_bounds__(64) void finalize_kernel(const float *__restrict__ normpart, int nnorm,
+                                                      const float *__restrict__ losspart, int nloss, float clip,
+                                                      float *__restrict__ scale, ga3c_train_stats *own,
+                                                      ga3c_train_stats *user) {
+    const int lane = threadIdx.x;
+    float s = 0.f;
+    for (int i = lane; i < nnorm; i += 64) s += normpart[i];
+    s = wave_sum(s);
+    float l[3] = {0.f, 0.f, 0.f};
+    for (int i = lane; i < nloss; i += 64)
+        for (int c = 0; c < 3; ++c) l[c] += losspart[3 * i + c];
+    for (int c = 0; c < 3; ++c) l[c] = wave_sum(l[c]);
+    if (lane == 0) {
+        const float norm = sqrtf(s);
+        float sc = 1.f;
+        if (clip > 0.f && norm > clip) sc = clip / norm;
+        const bool bad = !(norm <= 3.0e38f);
+        scale[0] = sc;
+        ga3c_train_stats st;
+        st.policy_loss = l[0]; st.value_loss = l[1]; st.entropy = l[2];
+        st.grad_norm = norm; st.clip_scale = sc; st.nonfinite = bad ? 1 : 0;
+        *own = st;
+        if (user) *user = st;
+    }
+}
+
+// Eq. 3 on a flat buffer: d = s*grad; g = alpha g + (1-alpha) d^2;
+// theta -= lr d / sqrt(g + eps).  20 bytes of traffic per parameter.
+// s = scale_dev[0] when scale_dev is not null, else scale_host.
+__global__ __launch_bounds__(256) void rmsprop_kernel(float *__restrict__ theta, float *__restrict__ g,
+                                                      const float *__restrict__ grad, size_t n,
+                                                      const float *__restrict__ scale_dev, float scale_host, float lr,
+                                                      float alpha, float eps) {
+    const float s = scale_dev ? scale_dev[0] : scale_host;
+    const float oma = 1.f - alpha;
+    const size_t n4 = n / 4;
+    const size_t stride = (size_t)gridDim.x * 256;
+    float4 *t4 = (float4 *)theta;
+    float4 *g4 = (float4 *)g;
+    const float4 *d4 = (const float4 *)grad;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride) {
+        float4 t = t4[i], gg = g4[i], d = d4[i];
+        d.x *= s; d.y *= s; d.z *= s; d.w *= s;
+        gg.x = alpha * gg.x + oma * d.x * d.x; gg.y = alpha * gg.y + oma * d.y * d.y;
+        gg.z = alpha * gg.z + oma * d.z * d.z; gg.w = alpha * gg.w + oma * d.w * d.w;
+        t.x -= lr * d.x / sqrtf(gg.x + eps); t.y -= lr * d.y / sqrtf(gg.y + eps);
+        t.z -= lr * d.z / sqrtf(gg.z + eps); t.w -= lr * d.w / sqrtf(gg.w + eps);
+        g4[i] = gg; t4[i] = t;
+    }
+    for (size_t i = n4 * 4 + (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
+        const float d = s * grad[i];
+        const float gg = alpha * g[i] + oma * d * d;
+        g[i] = gg;
+        theta[i] -= lr * d / sqrtf(gg + eps);
+    }
+}
+
+// Counter-based normal deviates: splitmix64 of (seed, index) gives two
+// 24-bit uniforms, Box-Muller turns them into one N(0,1) value.
+__device__ __forceinline__ uint64_t splitmix64(uint64_t x) {
+    x += 0x9E3779B97F4A7C15ull;
+    x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull;
+    x = (x ^ (x >> 27)) * 0x94D049BB133111EBull;
+    return x ^ (x >> 31);
+}
+__global__ __launch_bounds__(256) void init_normal_kernel(float *__restrict__ dst, size_t base, size_t n, float std,
+                                                          uint64_t seed) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const uint64_t r = splitmix64(seed * 0xD1342543DE82EF95ull + (base + i));
+    const float u1 = ((float)((r >> 40) & 0xFFFFFF) + 1.f) * (1.f / 16777216.f);   // (0, 1]
+    const float u2 = (float)((r >> 8) & 0xFFFFFF) * (1.f / 16777216.f);             // [0, 1)
+    dst[i] = std * sqrtf(-2.f * logf(u1)) * cosf(6.28318530717958647692f * u2);
+}
+__global__ __launch_bounds__(256) void fill_kernel(float *__restrict__ dst, size_t n, float v) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) dst[i] = v;
+}
+
+// ------------------------------------------------------------ host helpers --
+
+inline unsigned blocks_for(size_t n, int per = 256) { return (unsigned)((n + per - 1) / per); }
+
+// Number of k-chunks for a split-k product with `tiles` output tiles and a
+// reduction of length K: enough blocks to fill 256 compute units a few times
+// over, chunks a multiple of the k-tile and at least two k-tiles long.
+inline void pick_split(int tiles, int K, int &nz, int &kchunk) {
+    int want = (1024 + tiles - 1) / tiles;
+    int maxz = std::max(1, K / (2 * GEMM_BK));
+    want = std::max(1, std::min(want, maxz));
+    kchunk = (K + want - 1) / want;
+    kchunk = (kchunk + GEMM_BK - 1) / GEMM_BK * GEMM_BK;
+    nz = (K + kchunk - 1) / kchunk;
+}
+
+inline int cdiv(int a, int b) { return (a + b - 1) / b; }
+
+int alloc_work(Work &w, const ga3c_ctx *c, int cap) {
+    w.cap = cap;
+    if (cap <= 0) return GA3C_OK;
+    for (int l = 0; l < c->nconv; ++l)
+        HIP_TRY(hipMalloc(&w.act[l], sizeof(float) * (size_t)cap * c->geom[l].OC * c->geom[l].OHW));
+    HIP_TRY(hipMalloc(&w.h, sizeof(float) * (size_t)cap * c->F));
+    HIP_TRY(hipMalloc(&w.zv, sizeof(float) * (size_t)cap * (c->A + 1)));
+    return GA3C_OK;
+}
+
+void free_work(Work &w) {
+    (void)hipFree(w.ws);
+    for (int l = 0; l < GA3C_MAX_CONV; ++l) (void)hipFree(w.act[l]);
+    (void)hipFree(w.h);
+    (void)hipFree(w.zv);
+}
+
+// Tile shapes: output channels are few (16..64), pixels are many.
+template <class P>
+hipError_t launch_conv_like(const P &p, int nz, hipStream_t s, bool a_rows_unused = false) {
+    (void)a_rows_unused;
+    if (p.M <= 16) return launch_gemm<1, 4, 1, 4, false, true>(p, nz, s);   // 16 x 256
+    if (p.M <= 32) return launch_gemm<2, 2, 1, 4, false, true>(p, nz, s);   // 32 x 128
+    return launch_gemm<2, 2, 2, 2, false, true>(p, nz, s);                  // 64 x 64
+}
+inline int conv_like_tiles(int M, int N) {
+    if (M <= 16) return cdiv(N, 256);
+    if (M <= 32) return cdiv(N, 128);
+    return cdiv(M, 64) * cdiv(N, 64);
+}
+
+// Forward pass of `B` frames into `w`; heads outputs to the optional pointers.
+int forward(ga3c_ctx *c, Work &w, const uint8_t *frames, int B, bool keep_zv, float *logits, float *values,
+            float *probs, const float *uniforms, int32_t *actions, hipStream_t s) {
+    const int nb = 2 * c->nconv;
+    for (int l = 0; l < c->nconv; ++l) {
+        const ConvGeom &g = c->geom[l];
+        if (l == 0) {
+            ConvFwdP<uint8_t> p;
+            p.M = g.OC; p.N = B * g.OHW; p.K = g.K; p.g = g;
+            p.x = frames; p.w = c->theta + c->off[0]; p.bias = c->theta + c->off[1];
+            p.y = w.act[0]; p.scale = 1.f / 255.f;
+            HIP_TRY(launch_conv_like(p, 1, s));
+        } else {
+            ConvFwdP<float> p;
+            p.M = g.OC; p.N = B * g.OHW; p.K = g.K; p.g = g;
+            p.x = w.act[l - 1]; p.w = c->theta + c->off[2 * l]; p.bias = c->theta + c->off[2 * l + 1];
+            p.y = w.act[l]; p.scale = 1.f;
+            HIP_TRY(launch_conv_like(p, 1, s));
+        }
+    }
+    {   // fully connected + bias + ReLU: h[b][o] = sum_i x[b][i] Wfc[o][i]
+        const int tiles = cdiv(B, 64) * cdiv(c->F, 64);
+        int nz, kchunk;
+        pick_split(tiles, c->flat, nz, kchunk);
+        const float *x = w.act[c->nconv - 1];
+        if (nz == 1) {
+            GemmP<EPI_BIAS_RELU, false> p;
+            p.M = B; p.N = c->F; p.K = c->flat; p.kchunk = kchunk;
+            p.A = x; p.sAm = c->flat; p.sAk = 1;
+            p.B = c->theta + c->off[nb]; p.sBn = c->flat; p.sBk = 1;
+            p.C = w.h; p.ldc = c->F; p.aux = c->theta + c->off[nb + 1];
+            HIP_TRY((launch_gemm<2, 2, 2, 2, false, false>(p, 1, s)));
+        } else {
+            GemmP<EPI_PARTIAL, false> p;
+            p.M = B; p.N = c->F; p.K = c->flat; p.kchunk = kchunk;
+            p.A = x; p.sAm = c->flat; p.sAk = 1;
+            p.B = c->theta + c->off[nb]; p.sBn = c->flat; p.sBk = 1;
+            p.C = w.ws; p.ldc = c->F; p.aux = nullptr;
+            if ((size_t)nz * B * c->F > w.ws_floats) return fail(GA3C_EINVAL, "internal: split-k workspace too small (fc)");
+            HIP_TRY((launch_gemm<2, 2, 2, 2, false, false>(p, nz, s)));
+            hipLaunchKernelGGL(reduce_bias_relu_kernel, dim3(blocks_for((size_t)B * c->F)), dim3(256), 0, s, w.ws, nz,
+                               B, c->F, c->theta + c->off[nb + 1], w.h);
+            HIP_TRY(hipGetLastError());
+        }
+    }
+    hipLaunchKernelGGL(heads_fwd_kernel, dim3(cdiv(B, 4)), dim3(256), 0, s, w.h, B, c->F, c->A,
+                       c->theta + c->off[nb + 2], c->theta + c->off[nb + 3], c->theta + c->off[nb + 4],
+                       c->theta + c->off[nb + 5], keep_zv ? w.zv : nullptr, logits, values, probs, uniforms, actions);
+    HIP_TRY(hipGetLastError());
+    return GA3C_OK;
+}
+
+// Floats of split-k workspace a call on up to `cap` frames can need.
+size_t workspace_floats(const ga3c_ctx *c, int cap, bool training) {
+    size_t need = 0;
+    for (int B = 1; B <= cap; ++B) {        // fc forward: depends on the batch
+        int nz, kc;
+        pick_split(cdiv(B, 64) * cdiv(c->F, 64), c->flat, nz, kc);
+        if (nz > 1) need = std::max(need, (size_t)nz * B * c->F);
+    }
+    const int B = cap;
+    if (training && B > 0) {
+        int nz, kc;
+        for (int l = 0; l < c->nconv; ++l) {
+            const ConvGeom &g = c->geom[l];
+            pick_split(conv_like_tiles(g.OC, g.K + 1), B * g.OHW, nz, kc);
+            need = std::max(need, (size_t)nz * g.OC * (g.K + 1));
+        }
+        pick_split(cdiv(c->F, 64) * cdiv(c->flat + 1, 64), B, nz, kc);
+        need = std::max(need, (size_t)nz * c->F * (c->flat + 1));
+        pick_split(conv_like_tiles(c->A + 1, c->F + 1), B, nz, kc);
+        need = std::max(need, (size_t)nz * (c->A + 1) * (c->F + 1));
+    }
+    return need;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------ C ABI ---
+
+extern "C" int ga3c_create(const ga3c_net_desc *d, int max_predict_batch, int max_train_frames, ga3c_ctx **out) {
+    if (out) *out = nullptr;
+    if (!d || !out) return fail(GA3C_EINVAL, "ga3c_create: null argument");
+    if (d->n_conv < 1 || d->n_conv > GA3C_MAX_CONV) return fail(GA3C_EINVAL, "ga3c_create: n_conv must be 1..4");
+    if (d->n_actions < 1 || d->n_actions > GA3C_MAX_ACTIONS)
+        return fail(GA3C_EINVAL, "ga3c_create: n_actions must be 1..%d", GA3C_MAX_ACTIONS);
+    if (d->in_c < 1 || d->in_h < 1 || d->in_w < 1 || d->fc_units < 1) return fail(GA3C_EINVAL, "ga3c_create: bad sizes");
+    if (d->math != 0) return fail(GA3C_EINVAL, "ga3c_create: only math = 0 (fp32) is built");
+    if (max_predict_batch < 0 || max_train_frames < 0) return fail(GA3C_EINVAL, "ga3c_create: negative capacity");
+
+    ga3c_ctx *c = new (std::nothrow) ga3c_ctx();
+    if (!c) return fail(GA3C_ENOMEM, "ga3c_create: host allocation failed");
+    memset((void *)c, 0, sizeof(*c));
+    c->desc = *d;
+    c->nconv = d->n_conv; c->F = d->fc_units; c->A = d->n_actions;
+    c->max_pred = max_predict_batch; c->max_train = max_train_frames;
+
+    int C = d->in_c, H = d->in_h, W = d->in_w;
+    int64_t pos = 0; int no = 0;
+    for (int l = 0; l < c->nconv; ++l) {
+        const int oc = d->conv[l].oc, ks = d->conv[l].k, st = d->conv[l].stride;
+        if (oc < 1 || ks < 1 || st < 1 || ks > H || ks > W) {
+            delete c;
+            return fail(GA3C_EINVAL, "ga3c_create: conv layer %d does not fit its input", l);
+        }
+        ConvGeom &g = c->geom[l];
+        g.C = C; g.H = H; g.W = W; g.OC = oc; g.KS = ks; g.S = st;
+        g.OH = (H - ks) / st + 1; g.OW = (W - ks) / st + 1;
+        g.K = C * ks * ks; g.OHW = g.OH * g.OW; g.CHW = C * H * W;
+        g.dOHW = FastDiv(g.OHW); g.dOW = FastDiv(g.OW);
+        g.koff = nullptr;
+        c->off[no++] = pos; pos += (int64_t)oc * g.K;
+        c->off[no++] = pos; pos += oc;
+        C = oc; H = g.OH; W = g.OW;
+    }
+    c->flat = C * H * W;
+    c->off[no++] = pos; pos += (int64_t)c->flat * c->F;
+    c->off[no++] = pos; pos += c->F;
+    c->off[no++] = pos; pos += (int64_t)c->A * c->F;
+    c->off[no++] = pos; pos += c->A;
+    c->off[no++] = pos; pos += c->F;
+    c->off[no++] = pos; pos += 1;
+    c->off[no++] = pos;
+    c->noff = no; c->P = (size_t)pos;
+    // 32-bit index limits of the kernels
+    const int maxB = std::max(max_predict_batch, max_train_frames);
+    for (int l = 0; l < c->nconv; ++l)
+        if ((double)maxB * std::max(c->geom[l].OHW, c->geom[l].H * c->geom[l].W) >= 2.0e9) {
+            delete c;
+            return fail(GA3C_EINVAL, "ga3c_create: capacity too large for 32-bit pixel indices");
+        }
+
+    int rc = GA3C_OK;
+    auto guard = [&](int r) { if (r != GA3C_OK && rc == GA3C_OK) rc = r; return r == GA3C_OK; };
+    auto dmalloc = [&](void **p, size_t bytes) -> int {
+        HIP_TRY(hipMalloc(p, bytes ? bytes : 16));
+        return GA3C_OK;
+    };
+    // filter-tap offset tables
+    for (int l = 0; l < c->nconv && rc == GA3C_OK; ++l) {
+        ConvGeom &g = c->geom[l];
+        const int n = (g.K + 3) / 4 * 4;
+        std::vector<int> t(n, 0);
+        for (int cc = 0; cc < g.C; ++cc)
+            for (int u = 0; u < g.KS; ++u)
+                for (int v = 0; v < g.KS; ++v) t[(cc * g.KS + u) * g.KS + v] = cc * g.H * g.W + u * g.W + v;
+        if (!guard(dmalloc((void **)&c->koff[l], sizeof(int) * n))) break;
+        hipError_t e = hipMemcpy(c->koff[l], t.data(), sizeof(int) * n, hipMemcpyHostToDevice);
+        if (e != hipSuccess) { guard(fail(GA3C_EHIP, "hipMemcpy: %s", hipGetErrorString(e))); break; }
+        g.koff = c->koff[l];
+    }
+    if (rc == GA3C_OK) guard(dmalloc((void **)&c->theta, sizeof(float) * c->P));
+    if (rc == GA3C_OK) guard(dmalloc((void **)&c->g, sizeof(float) * c->P));
+    if (rc == GA3C_OK) guard(dmalloc((void **)&c->grad, sizeof(float) * c->P));
+    if (rc == GA3C_OK) {
+        hipError_t e = hipMemset(c->theta, 0, sizeof(float) * c->P);
+        if (e == hipSuccess) e = hipMemset(c->g, 0, sizeof(float) * c->P);
+        if (e == hipSuccess) e = hipMemset(c->grad, 0, sizeof(float) * c->P);
+        if (e != hipSuccess) guard(fail(GA3C_EHIP, "hipMemset: %s", hipGetErrorString(e)));
+    }
+    if (rc == GA3C_OK) guard(alloc_work(c->pred, c, max_predict_batch));
+    if (rc == GA3C_OK) guard(alloc_work(c->train, c, max_train_frames));
+    if (rc == GA3C_OK && max_train_frames > 0) {
+        const size_t B = (size_t)max_train_frames;
+        for (int l = 0; l < c->nconv && rc == GA3C_OK; ++l)
+            guard(dmalloc((void **)&c->dact[l], sizeof(float) * B * c->geom[l].OC * c->geom[l].OHW));
+        if (rc == GA3C_OK) guard(dmalloc((void **)&c->dh, sizeof(float) * B * c->F));
+        if (rc == GA3C_OK) guard(dmalloc((void **)&c->dzv, sizeof(float) * B * (c->A + 1)));
+        if (rc == GA3C_OK) guard(dmalloc((void **)&c->R, sizeof(float) * B));
+        if (rc == GA3C_OK) guard(dmalloc((void **)&c->partials, sizeof(float) * (NORM_BLOCKS + 3 * (B / LOSS_THREADS + 1))));
+        if (rc == GA3C_OK) guard(dmalloc((void **)&c->scale, sizeof(float)));
+        if (rc == GA3C_OK) guard(dmalloc((void **)&c->stats, sizeof(ga3c_train_stats)));
+        if (rc == GA3C_OK) {
+            hipError_t e = hipMemset(c->stats, 0, sizeof(ga3c_train_stats));
+            if (e != hipSuccess) guard(fail(GA3C_EHIP, "hipMemset: %s", hipGetErrorString(e)));
+        }
+    }
+    if (rc == GA3C_OK) {
+        c->pred.ws_floats = workspace_floats(c, max_predict_batch, false);
+        guard(dmalloc((void **)&c->pred.ws, sizeof(float) * c->pred.ws_floats));
+    }
+    if (rc == GA3C_OK) {
+        c->train.ws_floats = workspace_floats(c, max_train_frames, true);
+        guard(dmalloc((void **)&c->train.ws, sizeof(float) * c->train.ws_floats));
+    }
+    if (rc != GA3C_OK) {
+        char keep[sizeof(g_err)];
+        memcpy(keep, g_err, sizeof(keep));
+        ga3c_destroy(c);
+        memcpy(g_err, keep, sizeof(keep));
+        return rc;
+    }
+    *out = c;
+    return GA3C_OK;
+}
+
+extern "C" int ga3c_destroy(ga3c_ctx *c) {
+    if (!c) return GA3C_OK;
+    (void)hipDeviceSynchronize();
+    for (int l = 0; l < GA3C_MAX_CONV; ++l) { (void)hipFree(c->koff[l]); (void)hipFree(c->dact[l]); }
+    (void)hipFree(c->theta); (void)hipFree(c->g); (void)hipFree(c->grad);
+    free_work(c->pred); free_work(c->train);
+    (void)hipFree(c->dh); (void)hipFree(c->dzv); (void)hipFree(c->R);
+    (void)hipFree(c->partials); (void)hipFree(c->scale); (void)hipFree(c->stats);
+    delete c;
+    return GA3C_OK;
+}
+
+extern "C" size_t ga3c_params_count(const ga3c_ctx *c) { return c ? c->P : 0; }
+
+extern "C" int ga3c_params_offsets(const ga3c_ctx *c, int64_t *off, int cap) {
+    if (!c || !off || cap < c->noff) return fail(GA3C_EINVAL, "ga3c_params_offsets: null argument or cap too small");
+    for (int i = 0; i < c->noff; ++i) off[i] = c->off[i];
+    return c->noff;
+}
+
+extern "C" int ga3c_params_init(ga3c_ctx *c, uint64_t seed, void *stream) {
+    if (!c) return fail(GA3C_EINVAL, "ga3c_params_init: null context");
+    hipStream_t s = (hipStream_t)stream;
+    hipLaunchKernelGGL(fill_kernel, dim3(blocks_for(c->P)), dim3(256), 0, s, c->theta, c->P, 0.f);
+    hipLaunchKernelGGL(fill_kernel, dim3(blocks_for(c->P)), dim3(256), 0, s, c->g, c->P, 0.f);
+    HIP_TRY(hipGetLastError());
+    const int nb = 2 * c->nconv;
+    // weight tensors and their fan-in; biases stay zero
+    struct { int64_t off; size_t n; int fan_in; } t[GA3C_MAX_CONV + 3];
+    int nt = 0;
+    for (int l = 0; l < c->nconv; ++l) t[nt++] = {c->off[2 * l], (size_t)c->geom[l].OC * c->geom[l].K, c->geom[l].K};
+    t[nt++] = {c->off[nb], (size_t)c->flat * c->F, c->flat};
+    t[nt++] = {c->off[nb + 2], (size_t)c->A * c->F, c->F};
+    t[nt++] = {c->off[nb + 4], (size_t)c->F, c->F};
+    for (int i = 0; i < nt; ++i) {
+        hipLaunchKernelGGL(init_normal_kernel, dim3(blocks_for(t[i].n)), dim3(256), 0, s, c->theta + t[i].off,
+                           (size_t)t[i].off, t[i].n, sqrtf(2.f / (float)t[i].fan_in), seed);
+        HIP_TRY(hipGetLastError());
+    }
+    return GA3C_OK;
+}
+
+static float *select_buffer(ga3c_ctx *c, int which) {
+    return which == 0 ? c->theta : which == 1 ? c->g : which == 2 ? c->grad : nullptr;
+}
+
+extern "C" int ga3c_params_get(ga3c_ctx *c, int which, float *dst, size_t n, void *stream) {
+    if (!c || !dst) return fail(GA3C_EINVAL, "ga3c_params_get: null argument");
+    float *src = select_buffer(c, which);
+    if (!src || n != c->P) return fail(GA3C_EINVAL, "ga3c_params_get: which must be 0..2 and n the parameter count");
+    HIP_TRY(hipMemcpyAsync(dst, src, sizeof(float) * n, hipMemcpyDeviceToDevice, (hipStream_t)stream));
+    return GA3C_OK;
+}
+
+extern "C" int ga3c_params_set(ga3c_ctx *c, int which, const float *src, size_t n, void *stream) {
+    if (!c || !src) return fail(GA3C_EINVAL, "ga3c_params_set: null argument");
+    if ((which != 0 && which != 1) || n != c->P)
+        return fail(GA3C_EINVAL, "ga3c_params_set: which must be 0 or 1 and n the parameter count");
+    HIP_TRY(hipMemcpyAsync(select_buffer(c, which), src, sizeof(float) * n, hipMemcpyDeviceToDevice, (hipStream_t)stream));
+    return GA3C_OK;
+}
+
+extern "C" int ga3c_predict(ga3c_ctx *c, const uint8_t *frames, int B, const float *uniforms, float *logits,
+                            float *values, float *probs, int32_t *actions, void *stream) {
+    if (!c) return fail(GA3C_EINVAL, "ga3c_predict: null context");
+    if (B < 0 || B > c->max_pred) return fail(GA3C_EINVAL, "ga3c_predict: B = %d outside [0, %d]", B, c->max_pred);
+    if (B == 0) return GA3C_OK;
+    if (!frames) return fail(GA3C_EINVAL, "ga3c_predict: null frames");
+    if (actions && !uniforms) return fail(GA3C_EINVAL, "ga3c_predict: actions requested without uniforms");
+    return forward(c, c->pred, frames, B, false, logits, values, probs, uniforms, actions, (hipStream_t)stream);
+}
+
+extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t *actions, const float *rewards,
+                               const uint8_t *dones, const float *bootstrap, int N, int T, const ga3c_hparams *hp,
+                               ga3c_train_stats *stats, void *stream) {
+    if (!c) return fail(GA3C_EINVAL, "ga3c_train_step: null context");
+    if (N < 0 || T < 0) return fail(GA3C_EINVAL, "ga3c_train_step: negative N or T");
+    const long long BL = (long long)N * T;
+    if (BL > c->max_train) return fail(GA3C_EINVAL, "ga3c_train_step: N*T = %lld above capacity %d", BL, c->max_train);
+    if (BL == 0) return GA3C_OK;
+    if (!frames || !actions || !rewards || !dones || !hp) return fail(GA3C_EINVAL, "ga3c_train_step: null argument");
+    const int B = (int)BL;
+    hipStream_t s = (hipStream_t)stream;
+    Work &w = c->train;
+    const int nb = 2 * c->nconv, A = c->A, F = c->F;
+    c->last_frames = B;
+
+    int rc = forward(c, w, frames, B, true, nullptr, nullptr, nullptr, nullptr, nullptr, s);
+    if (rc != GA3C_OK) return rc;
+
+    const int nloss = cdiv(N, LOSS_THREADS);
+    float *losspart = c->partials + NORM_BLOCKS;
+    hipLaunchKernelGGL(returns_loss_kernel, dim3(nloss), dim3(LOSS_THREADS), 0, s, w.zv, actions, rewards, dones,
+                       bootstrap, N, T, A, hp->gamma, hp->beta, hp->value_coef, hp->log_eps, c->R, c->dzv, losspart);
+    HIP_TRY(hipGetLastError());
+
+    const float *Wp = c->theta + c->off[nb + 2], *Wv = c->theta + c->off[nb + 4];
+    int nz, kchunk;
+    {   // heads: weight and bias gradients, dgrad
+        GemmP<EPI_PARTIAL, true> p;
+        p.M = A + 1; p.N = F + 1; p.K = B;
+        pick_split(conv_like_tiles(p.M, p.N), B, nz, kchunk);
+        p.kchunk = kchunk;
+        p.A = c->dzv; p.sAm = 1; p.sAk = A + 1;
+        p.B = w.h; p.sBn = 1; p.sBk = F;
+        p.C = w.ws; p.ldc = 0; p.aux = nullptr;
+        if ((size_t)nz * p.M * p.N > w.ws_floats) return fail(GA3C_EINVAL, "internal: split-k workspace too small (heads)");
+        HIP_TRY(launch_conv_like(p, nz, s));
+        hipLaunchKernelGGL(reduce_wgrad_kernel, dim3(blocks_for((size_t)A * (F + 1))), dim3(256), 0, s, w.ws, nz,
+                           A + 1, F + 1, 0, A, c->grad + c->off[nb + 2], c->grad + c->off[nb + 3]);
+        hipLaunchKernelGGL(reduce_wgrad_kernel, dim3(blocks_for((size_t)(F + 1))), dim3(256), 0, s, w.ws, nz, A + 1,
+                           F + 1, A, A + 1, c->grad + c->off[nb + 4], c->grad + c->off[nb + 5]);
+        hipLaunchKernelGGL(heads_dgrad_kernel, dim3(blocks_for((size_t)B * F)), dim3(256), 0, s, c->dzv, w.h, Wp, Wv, B,
+                           F, A, c->dh);
+        HIP_TRY(hipGetLastError());
+    }
+    const float *xfc = w.act[c->nconv - 1];
+    {   // fc weight + bias gradient: D[o][i] = sum_b dh[b][o] x[b][i]
+        GemmP<EPI_PARTIAL, true> p;
+        p.M = F; p.N = c->flat + 1; p.K = B;
+        pick_split(cdiv(p.M, 64) * cdiv(p.N, 64), B, nz, kchunk);
+        p.kchunk = kchunk;
+        p.A = c->dh; p.sAm = 1; p.sAk = F;
+        p.B = xfc; p.sBn = 1; p.sBk = c->flat;
+        p.C = w.ws; p.ldc = 0; p.aux = nullptr;
+        if ((size_t)nz * p.M * p.N > w.ws_floats) return fail(GA3C_EINVAL, "internal: split-k workspace too small (fc wgrad)");
+        HIP_TRY((launch_gemm<2, 2, 2, 2, true, true>(p, nz, s)));
+        hipLaunchKernelGGL(reduce_wgrad_kernel, dim3(blocks_for((size_t)p.M * p.N)), dim3(256), 0, s, w.ws, nz, p.M,
+                           p.N, 0, p.M, c->grad + c->off[nb], c->grad + c->off[nb + 1]);
+        HIP_TRY(hipGetLastError());
+    }
+    {   // fc input gradient, masked by the ReLU of the last conv layer
+        GemmP<EPI_MASK, false> p;
+        p.M = B; p.N = c->flat; p.K = F; p.kchunk = (F + GEMM_BK - 1) / GEMM_BK * GEMM_BK;
+        p.A = c->dh; p.sAm = F; p.sAk = 1;
+        p.B = c->theta + c->off[nb]; p.sBn = 1; p.sBk = c->flat;
+        p.C = c->dact[c->nconv - 1]; p.ldc = c->flat; p.aux = xfc;
+        HIP_TRY((launch_gemm<2, 2, 2, 2, false, true>(p, 1, s)));
+    }
+    for (int l = c->nconv - 1; l >= 0; --l) {
+        const ConvGeom &g = c->geom[l];
+        // weight + bias gradient
+        pick_split(conv_like_tiles(g.OC, g.K + 1), B * g.OHW, nz, kchunk);
+        if ((size_t)nz * g.OC * (g.K + 1) > w.ws_floats) return fail(GA3C_EINVAL, "internal: split-k workspace too small (conv)");
+        if (l == 0) {
+            ConvWgradP<uint8_t> p;
+            p.M = g.OC; p.N = g.K + 1; p.K = B * g.OHW; p.kchunk = kchunk; p.g = g;
+            p.x = frames; p.dy = c->dact[0]; p.ws = w.ws; p.scale = 1.f / 255.f;
+            HIP_TRY(launch_conv_like(p, nz, s));
+        } else {
+            ConvWgradP<float> p;
+            p.M = g.OC; p.N = g.K + 1; p.K = B * g.OHW; p.kchunk = kchunk; p.g = g;
+            p.x = w.act[l - 1]; p.dy = c->dact[l]; p.ws = w.ws; p.scale = 1.f;
+            HIP_TRY(launch_conv_like(p, nz, s));
+        }
+        hipLaunchKernelGGL(reduce_wgrad_kernel, dim3(blocks_for((size_t)g.OC * (g.K + 1))), dim3(256), 0, s, w.ws, nz,
+                           g.OC, g.K + 1, 0, g.OC, c->grad + c->off[2 * l], c->grad + c->off[2 * l + 1]);
+        HIP_TRY(hipGetLastError());
+        if (l == 0) break;   // the input is data: no gradient needed
+        // input gradient, one launch per stride phase
+        for (int ry = 0; ry < g.S; ++ry)
+            for (int rx = 0; rx < g.S; ++rx) {
+                ConvDgradP p;
+                p.g = g; p.ry = ry; p.rx = rx;
+                p.nH = ry < g.H ? (g.H - ry + g.S - 1) / g.S : 0;
+                p.nW = rx < g.W ? (g.W - rx + g.S - 1) / g.S : 0;
+                if (p.nH == 0 || p.nW == 0) continue;
+                p.TA = (g.KS + g.S - 1) / g.S; p.TB = p.TA;
+                p.dNHW = FastDiv(p.nH * p.nW); p.dNW = FastDiv(p.nW);
+                p.dTAB = FastDiv(p.TA * p.TB); p.dTB = FastDiv(p.TB);
+                p.M = g.C; p.N = B * p.nH * p.nW; p.K = g.OC * p.TA * p.TB;
+                p.w = c->theta + c->off[2 * l]; p.dy = c->dact[l]; p.xmask = w.act[l - 1]; p.dx = c->dact[l - 1];
+                HIP_TRY(launch_conv_like(p, 1, s));
+            }
+    }
+    // global norm, clip scale, stats; then RMSProp
+    hipLaunchKernelGGL(sqnorm_partial_kernel, dim3(NORM_BLOCKS), dim3(256), 0, s, c->grad, c->P, c->partials);
+    hipLaunchKernelGGL(finalize_kernel, dim3(1), dim3(64), 0, s, c->partials, NORM_BLOCKS, losspart, nloss,
+                       hp->clip_norm, c->scale, c->stats, stats);
+    const unsigned rb = std::min<unsigned>(blocks_for(c->P / 4 + 1), 2048u);
+    hipLaunchKernelGGL(rmsprop_kernel, dim3(rb), dim3(256), 0, s, c->theta, c->g, c->grad, c->P, c->scale, 1.f, hp->lr,
+                       hp->rms_decay, hp->rms_eps);
+    HIP_TRY(hipGetLastError());
+    return GA3C_OK;
+}
+
+extern "C" int ga3c_train_debug_get(ga3c_ctx *c, int which, float *dst, size_t n, void *stream) {
+    if (!c || !dst) return fail(GA3C_EINVAL, "ga3c_train_debug_get: null argument");
+    const size_t B = (size_t)c->last_frames;
+    const float *src = nullptr;
+    size_t cap = 0;
+    if (which == 0) { src = c->R; cap = B; }
+    else if (which == 3) { src = c->dzv; cap = B * (c->A + 1); }
+    else if (which == 1 || which == 2) { src = c->train.zv; cap = B * (c->A + 1); }
+    if (!src || n > (which == 1 ? B * c->A : which == 2 ? B : cap))
+        return fail(GA3C_EINVAL, "ga3c_train_debug_get: bad selector or size");
+    hipStream_t s = (hipStream_t)stream;
+    if (which == 1 || which == 2) {
+        // strided copy out of the packed [B][A+1] buffer
+        const size_t rows = which == 1 ? n / c->A : n;
+        HIP_TRY(hipMemcpy2DAsync(dst, sizeof(float) * (which == 1 ? c->A : 1), src + (which == 2 ? c->A : 0),
+                                 sizeof(float) * (c->A + 1), sizeof(float) * (which == 1 ? c->A : 1), rows,
+                                 hipMemcpyDeviceToDevice, s));
+        return GA3C_OK;
+    }
+    HIP_TRY(hipMemcpyAsync(dst, src, sizeof(float) * n, hipMemcpyDeviceToDevice, s));
+    return GA3C_OK;
+}
+
+extern "C" int ga3c_rmsprop_flat(float *theta, float *g, const float *grad, size_t n, float scale, float lr,
+                                 float rms_decay, float rms_eps, void *stream) {
+    if (!theta || !g || !grad) return fail(GA3C_EINVAL, "ga3c_rmsprop_flat: null argument");
+    if (n == 0) return GA3C_OK;
+    if ((((uintptr_t)theta) | ((uintptr_t)g) | ((uintptr_t)grad)) & 15)
+        return fail(GA3C_EINVAL, "ga3c_rmsprop_flat: buffers must be 16-byte aligned");
+    const unsigned rb = std::min<unsigned>(blocks_for(n / 4 + 1), 8192u);
+    hipLaunchKernelGGL(rmsprop_kernel, dim3(rb), dim3(256), 0, (hipStream_t)stream, theta, g, grad, n,
+                       (const float *)nullptr, scale, lr, rms_decay, rms_eps);
+    HIP_TRY(hipGetLastError());
+    return GA3C_OK;
+}
