@@ -1,0 +1,191 @@
+#!/usr/bin/env python3
+"""Benchmark of the GA3C hot path on one MI355X.
+
+A step is one balanced pass of the whole path (Sec. 4.2 of the paper: in a
+balanced configuration PPS ~ TPS * t_max): t_max = 5 prediction calls of N
+frames each, one per action of every agent, followed by one training step on
+the N agents x 5 frames those actions produced.  N = 512 agents, the small
+network of Sec. 3.2 with 18 actions, synthetic game-like frames that are
+resident in HBM before the timed region starts.
+
+Prints ONE JSON line.  `value` = frames per second through predict AND
+train_step (each frame is predicted once and trained on once).  The line
+also carries predict-only and train-only rates, per-stage times measured with
+HIP events inside the library, the roofline of the dominant kernel and the
+fp64 CPU oracle timed on the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP32_MFMA = 157.3e12   # MI355X dense fp32 matrix, FLOP/s
+PEAK_HBM = 8.0e12           # B/s
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--agents", type=int, default=512)
+    ap.add_argument("--net", choices=("small", "large"), default="small")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--rmsprop-big", action="store_true", help="also time RMSProp on 2^28 parameters")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported "
+              "(no collectives or sharding are part of it)", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import ga3c_synth as synth
+    import paper_1611_06256_amd as g
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    N, T, A = args.agents, 5, 18
+    desc = g.SMALL_NET(A) if args.net == "small" else g.LARGE_NET(A)
+    net = g.Ga3c(desc, max(N, 1024), N * T)
+    net.params_init(synth.BASE_SEED)
+    hp = g.HParams(clip_norm=40.0)
+
+    seed = synth.BASE_SEED + 2
+    frames_np = synth.rectangle_frames_tiled(seed, N * T).reshape(N, T, 4, 84, 84)
+    tr = synth.trajectories(seed + 1, N, T, A)
+    frames = torch.from_numpy(frames_np).cuda()
+    # predict call t sees the frames of step t of every agent
+    pframes = [frames[:, t].contiguous() for t in range(T)]
+    boot_frames = torch.from_numpy(synth.rectangle_frames_tiled(seed + 2, N)).cuda()
+    actions = torch.from_numpy(tr["actions"]).cuda()
+    rewards = torch.from_numpy(tr["rewards"]).cuda()
+    dones = torch.from_numpy(tr["dones"]).cuda()
+    uniforms = torch.from_numpy(synth.uniforms(seed + 3, N)).cuda()
+    logits = torch.empty(N, A, device="cuda"); values = torch.empty(N, device="cuda")
+    probs = torch.empty(N, A, device="cuda"); sampled = torch.empty(N, dtype=torch.int32, device="cuda")
+    boot = torch.empty(N, device="cuda")
+    stats = torch.zeros(8, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def step():
+        for t in range(T):
+            net.predict(pframes[t], uniforms=uniforms, logits=logits, values=values, probs=probs, actions=sampled,
+                        stream=stream)
+        net.predict(boot_frames, values=boot, stream=stream)           # V(s_{t+k}) for the returns
+        net.train_step(frames, actions, rewards, dones, boot, hp, stats=stats, stream=stream)
+
+    def timed(fn, k):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(k):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / k
+
+    for _ in range(args.warmup):
+        step()
+    sec = timed(step, args.steps)
+    frames_per_step = N * T
+
+    # predict-only and train-only rates (same buffers)
+    big = torch.from_numpy(synth.rectangle_frames_tiled(seed + 4, 1024)).cuda()
+    bl = torch.empty(1024, A, device="cuda"); bv = torch.empty(1024, device="cuda")
+    pred_fn = lambda: net.predict(big, logits=bl, values=bv, stream=stream)
+    train_fn = lambda: net.train_step(frames, actions, rewards, dones, boot, hp, stats=stats, stream=stream)
+    for _ in range(3):
+        pred_fn(); train_fn()
+    pred_sec = timed(pred_fn, max(args.steps, 20))
+    train_sec = timed(train_fn, max(args.steps, 20))
+
+    # per-stage times with HIP events recorded by the library on the same stream
+    net.profile_enable(True)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    prof = net.profile_read()
+    net.profile_enable(False)
+    stages = []
+    for name, p in prof.items():
+        per_call_ms = p["ms"] / p["calls"]
+        e = {"stage": name, "calls_per_step": p["calls"] / args.steps, "ms_per_call": round(per_call_ms, 5),
+             "ms_per_step": round(p["ms"] / args.steps, 5)}
+        if p["flop"] > 0:
+            e["tflops"] = round(p["flop"] / (p["ms"] * 1e-3) / 1e12, 3)
+            e["frac_fp32_mfma_peak"] = round(p["flop"] / (p["ms"] * 1e-3) / PEAK_FP32_MFMA, 4)
+        elif p["bytes"] > 0:
+            e["gbps"] = round(p["bytes"] / (p["ms"] * 1e-3) / 1e9, 2)
+        stages.append(e)
+    stages.sort(key=lambda e: -e["ms_per_step"])
+    dom = stages[0]
+    dp = prof[dom["stage"]]
+    if dp["flop"] > 0:
+        ach = dp["flop"] / (dp["ms"] * 1e-3) / 1e12
+        roofline = {"kernel": dom["stage"], "bound": "mfma", "achieved": round(ach, 3), "peak": PEAK_FP32_MFMA / 1e12,
+                    "unit": "TFLOP/s", "frac": round(ach * 1e12 / PEAK_FP32_MFMA, 4), "traffic": None,
+                    "ms_per_launch": round(dp["ms"] / dp["calls"], 5)}
+    else:
+        ach = dp["bytes"] / (dp["ms"] * 1e-3) / 1e9
+        roofline = {"kernel": dom["stage"], "bound": "hbm", "achieved": round(ach, 2), "peak": PEAK_HBM / 1e9,
+                    "unit": "GB/s", "frac": round(ach * 1e9 / PEAK_HBM, 4), "traffic": None,
+                    "ms_per_launch": round(dp["ms"] / dp["calls"], 5)}
+    flop_step = sum(p["flop"] for p in prof.values()) / args.steps
+    whole = {"tflops": round(flop_step / sec / 1e12, 3), "frac_fp32_mfma_peak": round(flop_step / sec / PEAK_FP32_MFMA, 4)}
+
+    out = {
+        "metric": "frames/s through predict and train_step, balanced (PPS = TPS*t_max)",
+        "value": round(frames_per_step / sec, 1), "unit": "frames/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(sec * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"configs[1]+[2]: {args.net} net, 18 actions; per step {T}x predict B={N} "
+                               f"(+1 bootstrap predict B={N}) and 1 train_step {N} agents x t_max={T} = {N * T} frames, "
+                               "clip 40", "agents": N, "t_max": T, "seed": seed},
+        "pps_predict_only": {"value": round(1024 / pred_sec, 1), "batch": 1024, "ms_per_call": round(pred_sec * 1e3, 4)},
+        "tps_train_only": {"value": round(frames_per_step / train_sec, 1), "frames": frames_per_step,
+                           "ms_per_call": round(train_sec * 1e3, 4), "paper_tps_batches_of_5": round(N / train_sec, 1)},
+        "whole_step": whole,
+        "roofline": roofline,
+        "stages": stages,
+    }
+
+    if args.rmsprop_big:
+        n = 1 << 28
+        th = torch.zeros(n, device="cuda"); gg = torch.zeros(n, device="cuda"); dd = torch.ones(n, device="cuda")
+        f = lambda: g.rmsprop_flat(th, gg, dd, 1.0, 3e-4, 0.99, 0.1, stream=stream)
+        f(); f()
+        s = timed(f, 10)
+        out["rmsprop_2p28"] = {"gbps": round(20.0 * n / s / 1e9, 1), "frac_hbm_peak": round(20.0 * n / s / PEAK_HBM, 4),
+                               "ms": round(s * 1e3, 4)}
+        del th, gg, dd
+
+    if not args.no_cpu_baseline:
+        import oracle as orc
+        onet = orc.Net(conv=tuple(desc.conv), fc_units=desc.fc_units, n_actions=A)
+        theta = net.params_get(0).cpu().numpy().astype(np.float64)
+        cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        t0 = time.perf_counter()
+        for t in range(T):
+            orc.forward(onet, theta, frames_np[:, t])
+        bo = orc.forward(onet, theta, boot_frames.cpu().numpy())["values"]
+        orc.train_step(onet, theta, np.zeros_like(theta), frames_np, tr["actions"], tr["rewards"], tr["dones"], bo,
+                       orc.HParams(clip_norm=40.0))
+        cpu_sec = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(frames_per_step / cpu_sec, 1), "unit": "frames/s", "cores": cores,
+                               "kind": "oracle", "sample": f"1 whole step of the same workload ({cpu_sec:.1f} s, fp64, OpenMP over frames)"}
+    net.close()
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -166,6 +166,18 @@ int ga3c_train_debug_get(ga3c_ctx *ctx, int which, float *dst_dev, size_t n, voi
 int ga3c_rmsprop_flat(float *theta_dev, float *g_dev, const float *grad_dev, size_t n,
                       float scale, float lr, float rms_decay, float rms_eps, void *stream);
 
+/* Per-stage timing for measurement, off by default.  While it is on, every
+ * kernel launch (or group of launches that forms one stage) of ga3c_predict
+ * and ga3c_train_step is bracketed by two HIP events recorded on the call's
+ * stream.  ga3c_profile_read waits for the recorded events, adds up the
+ * elapsed times and writes one text line per stage into the HOST buffer buf:
+ *   "<stage> <calls> <total_ms> <algorithmic_flop> <algorithmic_bytes>\n"
+ * then forgets what it has reported.  Returns GA3C_EINVAL if cap is too small.
+ * The flop and byte figures are those of the method (2 per multiply-add of
+ * the layer's definition; 20 bytes per parameter for RMSProp), not counters. */
+int ga3c_profile_enable(ga3c_ctx *ctx, int on);
+int ga3c_profile_read(ga3c_ctx *ctx, char *buf, size_t cap);
+
 /* Thread-local text of the last error on this thread ("" if none). */
 const char *ga3c_last_error(void);
 

@@ -57,7 +57,20 @@ struct Work {            // activations of one call; predict and train own one e
 
 }  // namespace
 
+namespace {
+// Optional per-stage timing with HIP events on the stream of the call.
+struct ProfStage { const char *name; long calls; double ms, flop, bytes; };
+struct ProfRec { int stage; hipEvent_t a, b; };
+struct Profiler {
+    bool on = false;
+    std::vector<ProfStage> stages;
+    std::vector<ProfRec> recs;          // recorded, not yet read
+    std::vector<hipEvent_t> pool;       // idle events
+};
+}  // namespace
+
 struct ga3c_ctx {
+    Profiler *prof;
     ga3c_net_desc desc;
     int nconv, F, A, flat;
     ConvGeom geom[GA3C_MAX_CONV];
@@ -335,6 +348,34 @@ __global__ __launch_bounds__(256) void fill_kernel(float *__restrict__ dst, size
 
 // ------------------------------------------------------------ host helpers --
 
+// Brackets the kernels launched during its lifetime with two events when
+// profiling is on; costs one branch when it is off.
+struct ProfScope {
+    Profiler *p; hipStream_t s; int idx;
+    ProfScope(ga3c_ctx *c, hipStream_t st, const char *name, double flop, double bytes) : p(c->prof), s(st), idx(-1) {
+        if (!p || !p->on) { p = nullptr; return; }
+        int sid = -1;
+        for (size_t i = 0; i < p->stages.size(); ++i) if (!strcmp(p->stages[i].name, name)) { sid = (int)i; break; }
+        if (sid < 0) { p->stages.push_back({name, 0, 0.0, 0.0, 0.0}); sid = (int)p->stages.size() - 1; }
+        p->stages[sid].calls += 1; p->stages[sid].flop += flop; p->stages[sid].bytes += bytes;
+        ProfRec r; r.stage = sid; r.a = r.b = nullptr;
+        for (hipEvent_t *e : {&r.a, &r.b}) {
+            if (!p->pool.empty()) { *e = p->pool.back(); p->pool.pop_back(); }
+            else if (hipEventCreate(e) != hipSuccess) { *e = nullptr; }
+        }
+        if (!r.a || !r.b) { p = nullptr; return; }
+        (void)hipEventRecord(r.a, s);
+        p->recs.push_back(r); idx = (int)p->recs.size() - 1;
+    }
+    ~ProfScope() { if (p && idx >= 0) (void)hipEventRecord(p->recs[idx].b, s); }
+};
+#define STAGE(name, flop, bytes) ProfScope prof_scope_(c, s, name, (double)(flop), (double)(bytes))
+
+const char *const CONV_FWD[GA3C_MAX_CONV] = {"conv1_fwd", "conv2_fwd", "conv3_fwd", "conv4_fwd"};
+const char *const CONV_WGRAD[GA3C_MAX_CONV] = {"conv1_wgrad", "conv2_wgrad", "conv3_wgrad", "conv4_wgrad"};
+const char *const CONV_WRED[GA3C_MAX_CONV] = {"conv1_wgrad_reduce", "conv2_wgrad_reduce", "conv3_wgrad_reduce", "conv4_wgrad_reduce"};
+const char *const CONV_DGRAD[GA3C_MAX_CONV] = {"conv1_dgrad", "conv2_dgrad", "conv3_dgrad", "conv4_dgrad"};
+
 inline unsigned blocks_for(size_t n, int per = 256) { return (unsigned)((n + per - 1) / per); }
 
 // Number of k-chunks for a split-k product with `tiles` output tiles and a
@@ -388,6 +429,7 @@ int forward(ga3c_ctx *c, Work &w, const uint8_t *frames, int B, bool keep_zv, fl
     const int nb = 2 * c->nconv;
     for (int l = 0; l < c->nconv; ++l) {
         const ConvGeom &g = c->geom[l];
+        STAGE(CONV_FWD[l], 2.0 * B * g.OHW * g.OC * g.K, 0);
         if (l == 0) {
             ConvFwdP<uint8_t> p;
             p.M = g.OC; p.N = B * g.OHW; p.K = g.K; p.g = g;
@@ -413,6 +455,7 @@ int forward(ga3c_ctx *c, Work &w, const uint8_t *frames, int B, bool keep_zv, fl
             p.A = x; p.sAm = c->flat; p.sAk = 1;
             p.B = c->theta + c->off[nb]; p.sBn = c->flat; p.sBk = 1;
             p.C = w.h; p.ldc = c->F; p.aux = c->theta + c->off[nb + 1];
+            STAGE("fc_fwd", 2.0 * B * c->F * c->flat, 0);
             HIP_TRY((launch_gemm<2, 2, 2, 2, false, false>(p, 1, s)));
         } else {
             GemmP<EPI_PARTIAL, false> p;
@@ -421,12 +464,17 @@ int forward(ga3c_ctx *c, Work &w, const uint8_t *frames, int B, bool keep_zv, fl
             p.B = c->theta + c->off[nb]; p.sBn = c->flat; p.sBk = 1;
             p.C = w.ws; p.ldc = c->F; p.aux = nullptr;
             if ((size_t)nz * B * c->F > w.ws_floats) return fail(GA3C_EINVAL, "internal: split-k workspace too small (fc)");
-            HIP_TRY((launch_gemm<2, 2, 2, 2, false, false>(p, nz, s)));
+            {
+                STAGE("fc_fwd", 2.0 * B * c->F * c->flat, 0);
+                HIP_TRY((launch_gemm<2, 2, 2, 2, false, false>(p, nz, s)));
+            }
+            STAGE("fc_fwd_reduce", 0, 4.0 * (nz + 1) * B * c->F);
             hipLaunchKernelGGL(reduce_bias_relu_kernel, dim3(blocks_for((size_t)B * c->F)), dim3(256), 0, s, w.ws, nz,
                                B, c->F, c->theta + c->off[nb + 1], w.h);
             HIP_TRY(hipGetLastError());
         }
     }
+    STAGE("heads_fwd", 2.0 * B * c->F * (c->A + 1), 0);
     hipLaunchKernelGGL(heads_fwd_kernel, dim3(cdiv(B, 4)), dim3(256), 0, s, w.h, B, c->F, c->A,
                        c->theta + c->off[nb + 2], c->theta + c->off[nb + 3], c->theta + c->off[nb + 4],
                        c->theta + c->off[nb + 5], keep_zv ? w.zv : nullptr, logits, values, probs, uniforms, actions);
@@ -475,6 +523,7 @@ extern "C" int ga3c_create(const ga3c_net_desc *d, int max_predict_batch, int ma
     ga3c_ctx *c = new (std::nothrow) ga3c_ctx();
     if (!c) return fail(GA3C_ENOMEM, "ga3c_create: host allocation failed");
     memset((void *)c, 0, sizeof(*c));
+    c->prof = new (std::nothrow) Profiler();
     c->desc = *d;
     c->nconv = d->n_conv; c->F = d->fc_units; c->A = d->n_actions;
     c->max_pred = max_predict_batch; c->max_train = max_train_frames;
@@ -586,6 +635,11 @@ extern "C" int ga3c_destroy(ga3c_ctx *c) {
     free_work(c->pred); free_work(c->train);
     (void)hipFree(c->dh); (void)hipFree(c->dzv); (void)hipFree(c->R);
     (void)hipFree(c->partials); (void)hipFree(c->scale); (void)hipFree(c->stats);
+    if (c->prof) {
+        for (ProfRec &r : c->prof->recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+        for (hipEvent_t e : c->prof->pool) (void)hipEventDestroy(e);
+        delete c->prof;
+    }
     delete c;
     return GA3C_OK;
 }
@@ -670,9 +724,12 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
 
     const int nloss = cdiv(N, LOSS_THREADS);
     float *losspart = c->partials + NORM_BLOCKS;
-    hipLaunchKernelGGL(returns_loss_kernel, dim3(nloss), dim3(LOSS_THREADS), 0, s, w.zv, actions, rewards, dones,
-                       bootstrap, N, T, A, hp->gamma, hp->beta, hp->value_coef, hp->log_eps, c->R, c->dzv, losspart);
-    HIP_TRY(hipGetLastError());
+    {
+        STAGE("returns_loss", 0, 4.0 * B * (2 * (A + 1) + 4));
+        hipLaunchKernelGGL(returns_loss_kernel, dim3(nloss), dim3(LOSS_THREADS), 0, s, w.zv, actions, rewards, dones,
+                           bootstrap, N, T, A, hp->gamma, hp->beta, hp->value_coef, hp->log_eps, c->R, c->dzv, losspart);
+        HIP_TRY(hipGetLastError());
+    }
 
     const float *Wp = c->theta + c->off[nb + 2], *Wv = c->theta + c->off[nb + 4];
     int nz, kchunk;
@@ -685,11 +742,18 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
         p.B = w.h; p.sBn = 1; p.sBk = F;
         p.C = w.ws; p.ldc = 0; p.aux = nullptr;
         if ((size_t)nz * p.M * p.N > w.ws_floats) return fail(GA3C_EINVAL, "internal: split-k workspace too small (heads)");
-        HIP_TRY(launch_conv_like(p, nz, s));
-        hipLaunchKernelGGL(reduce_wgrad_kernel, dim3(blocks_for((size_t)A * (F + 1))), dim3(256), 0, s, w.ws, nz,
-                           A + 1, F + 1, 0, A, c->grad + c->off[nb + 2], c->grad + c->off[nb + 3]);
-        hipLaunchKernelGGL(reduce_wgrad_kernel, dim3(blocks_for((size_t)(F + 1))), dim3(256), 0, s, w.ws, nz, A + 1,
-                           F + 1, A, A + 1, c->grad + c->off[nb + 4], c->grad + c->off[nb + 5]);
+        {
+            STAGE("heads_wgrad", 2.0 * B * (A + 1) * F, 0);
+            HIP_TRY(launch_conv_like(p, nz, s));
+        }
+        {
+            STAGE("heads_wgrad_reduce", 0, 4.0 * (nz + 1) * (A + 1) * (F + 1));
+            hipLaunchKernelGGL(reduce_wgrad_kernel, dim3(blocks_for((size_t)A * (F + 1))), dim3(256), 0, s, w.ws, nz,
+                               A + 1, F + 1, 0, A, c->grad + c->off[nb + 2], c->grad + c->off[nb + 3]);
+            hipLaunchKernelGGL(reduce_wgrad_kernel, dim3(blocks_for((size_t)(F + 1))), dim3(256), 0, s, w.ws, nz, A + 1,
+                               F + 1, A, A + 1, c->grad + c->off[nb + 4], c->grad + c->off[nb + 5]);
+        }
+        STAGE("heads_dgrad", 2.0 * B * (A + 1) * F, 0);
         hipLaunchKernelGGL(heads_dgrad_kernel, dim3(blocks_for((size_t)B * F)), dim3(256), 0, s, c->dzv, w.h, Wp, Wv, B,
                            F, A, c->dh);
         HIP_TRY(hipGetLastError());
@@ -704,7 +768,11 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
         p.B = xfc; p.sBn = 1; p.sBk = c->flat;
         p.C = w.ws; p.ldc = 0; p.aux = nullptr;
         if ((size_t)nz * p.M * p.N > w.ws_floats) return fail(GA3C_EINVAL, "internal: split-k workspace too small (fc wgrad)");
-        HIP_TRY((launch_gemm<2, 2, 2, 2, true, true>(p, nz, s)));
+        {
+            STAGE("fc_wgrad", 2.0 * B * F * c->flat, 0);
+            HIP_TRY((launch_gemm<2, 2, 2, 2, true, true>(p, nz, s)));
+        }
+        STAGE("fc_wgrad_reduce", 0, 4.0 * (nz + 1) * p.M * p.N);
         hipLaunchKernelGGL(reduce_wgrad_kernel, dim3(blocks_for((size_t)p.M * p.N)), dim3(256), 0, s, w.ws, nz, p.M,
                            p.N, 0, p.M, c->grad + c->off[nb], c->grad + c->off[nb + 1]);
         HIP_TRY(hipGetLastError());
@@ -715,6 +783,7 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
         p.A = c->dh; p.sAm = F; p.sAk = 1;
         p.B = c->theta + c->off[nb]; p.sBn = 1; p.sBk = c->flat;
         p.C = c->dact[c->nconv - 1]; p.ldc = c->flat; p.aux = xfc;
+        STAGE("fc_dgrad", 2.0 * B * F * c->flat, 0);
         HIP_TRY((launch_gemm<2, 2, 2, 2, false, true>(p, 1, s)));
     }
     for (int l = c->nconv - 1; l >= 0; --l) {
@@ -722,6 +791,8 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
         // weight + bias gradient
         pick_split(conv_like_tiles(g.OC, g.K + 1), B * g.OHW, nz, kchunk);
         if ((size_t)nz * g.OC * (g.K + 1) > w.ws_floats) return fail(GA3C_EINVAL, "internal: split-k workspace too small (conv)");
+        {
+        STAGE(CONV_WGRAD[l], 2.0 * B * g.OHW * g.OC * g.K, 0);
         if (l == 0) {
             ConvWgradP<uint8_t> p;
             p.M = g.OC; p.N = g.K + 1; p.K = B * g.OHW; p.kchunk = kchunk; p.g = g;
@@ -733,11 +804,16 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
             p.x = w.act[l - 1]; p.dy = c->dact[l]; p.ws = w.ws; p.scale = 1.f;
             HIP_TRY(launch_conv_like(p, nz, s));
         }
-        hipLaunchKernelGGL(reduce_wgrad_kernel, dim3(blocks_for((size_t)g.OC * (g.K + 1))), dim3(256), 0, s, w.ws, nz,
-                           g.OC, g.K + 1, 0, g.OC, c->grad + c->off[2 * l], c->grad + c->off[2 * l + 1]);
-        HIP_TRY(hipGetLastError());
+        }
+        {
+            STAGE(CONV_WRED[l], 0, 4.0 * (nz + 1) * g.OC * (g.K + 1));
+            hipLaunchKernelGGL(reduce_wgrad_kernel, dim3(blocks_for((size_t)g.OC * (g.K + 1))), dim3(256), 0, s, w.ws, nz,
+                               g.OC, g.K + 1, 0, g.OC, c->grad + c->off[2 * l], c->grad + c->off[2 * l + 1]);
+            HIP_TRY(hipGetLastError());
+        }
         if (l == 0) break;   // the input is data: no gradient needed
         // input gradient, one launch per stride phase
+        STAGE(CONV_DGRAD[l], 2.0 * B * g.OHW * g.OC * g.K, 0);
         for (int ry = 0; ry < g.S; ++ry)
             for (int rx = 0; rx < g.S; ++rx) {
                 ConvDgradP p;
@@ -754,9 +830,16 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
             }
     }
     // global norm, clip scale, stats; then RMSProp
-    hipLaunchKernelGGL(sqnorm_partial_kernel, dim3(NORM_BLOCKS), dim3(256), 0, s, c->grad, c->P, c->partials);
+    {
+        STAGE("sqnorm", 2.0 * c->P, 4.0 * c->P);
+        hipLaunchKernelGGL(sqnorm_partial_kernel, dim3(NORM_BLOCKS), dim3(256), 0, s, c->grad, c->P, c->partials);
+    }
+    {
+    STAGE("finalize", 0, 0);
     hipLaunchKernelGGL(finalize_kernel, dim3(1), dim3(64), 0, s, c->partials, NORM_BLOCKS, losspart, nloss,
                        hp->clip_norm, c->scale, c->stats, stats);
+    }
+    STAGE("rmsprop", 8.0 * c->P, 20.0 * c->P);
     const unsigned rb = std::min<unsigned>(blocks_for(c->P / 4 + 1), 2048u);
     hipLaunchKernelGGL(rmsprop_kernel, dim3(rb), dim3(256), 0, s, c->theta, c->g, c->grad, c->P, c->scale, 1.f, hp->lr,
                        hp->rms_decay, hp->rms_eps);
@@ -797,5 +880,33 @@ extern "C" int ga3c_rmsprop_flat(float *theta, float *g, const float *grad, size
     hipLaunchKernelGGL(rmsprop_kernel, dim3(rb), dim3(256), 0, (hipStream_t)stream, theta, g, grad, n,
                        (const float *)nullptr, scale, lr, rms_decay, rms_eps);
     HIP_TRY(hipGetLastError());
+    return GA3C_OK;
+}
+
+extern "C" int ga3c_profile_enable(ga3c_ctx *c, int on) {
+    if (!c || !c->prof) return fail(GA3C_EINVAL, "ga3c_profile_enable: null context");
+    c->prof->on = on != 0;
+    return GA3C_OK;
+}
+
+extern "C" int ga3c_profile_read(ga3c_ctx *c, char *buf, size_t cap) {
+    if (!c || !c->prof || !buf || cap == 0) return fail(GA3C_EINVAL, "ga3c_profile_read: null argument");
+    Profiler *p = c->prof;
+    for (ProfRec &r : p->recs) {
+        HIP_TRY(hipEventSynchronize(r.b));
+        float ms = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ms, r.a, r.b));
+        p->stages[r.stage].ms += ms;
+        p->pool.push_back(r.a); p->pool.push_back(r.b);
+    }
+    p->recs.clear();
+    size_t pos = 0;
+    buf[0] = 0;
+    for (const ProfStage &st : p->stages) {
+        int n = snprintf(buf + pos, cap - pos, "%s %ld %.6f %.6e %.6e\n", st.name, st.calls, st.ms, st.flop, st.bytes);
+        if (n < 0 || (size_t)n >= cap - pos) return fail(GA3C_EINVAL, "ga3c_profile_read: buffer too small");
+        pos += (size_t)n;
+    }
+    p->stages.clear();
     return GA3C_OK;
 }
