@@ -166,6 +166,12 @@ int ga3c_train_debug_get(ga3c_ctx *ctx, int which, float *dst_dev, size_t n, voi
 int ga3c_rmsprop_flat(float *theta_dev, float *g_dev, const float *grad_dev, size_t n,
                       float scale, float lr, float rms_decay, float rms_eps, void *stream);
 
+/* Layers whose shape matches one of the paper's networks run on kernels
+ * compiled for that shape; every other shape runs on the general gather
+ * kernels.  on != 0 forces the general kernels for all layers (used to test
+ * them at the paper's shapes too); on == 0 restores the default. */
+int ga3c_use_generic_kernels(ga3c_ctx *ctx, int on);
+
 /* Per-stage timing for measurement, off by default.  While it is on, every
  * kernel launch (or group of launches that forms one stage) of ga3c_predict
  * and ga3c_train_step is bracketed by two HIP events recorded on the call's

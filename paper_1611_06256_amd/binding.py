@@ -90,7 +90,8 @@ _lib = None
 
 EXPORTS = ("ga3c_create", "ga3c_destroy", "ga3c_params_count", "ga3c_params_offsets", "ga3c_params_init",
            "ga3c_params_get", "ga3c_params_set", "ga3c_predict", "ga3c_train_step", "ga3c_train_debug_get",
-           "ga3c_rmsprop_flat", "ga3c_last_error", "ga3c_profile_enable", "ga3c_profile_read")
+           "ga3c_rmsprop_flat", "ga3c_last_error", "ga3c_profile_enable", "ga3c_profile_read",
+           "ga3c_use_generic_kernels")
 
 
 def load_library() -> C.CDLL:
@@ -118,6 +119,7 @@ def load_library() -> C.CDLL:
     lib.ga3c_rmsprop_flat.argtypes = [vp, vp, vp, sz, f32, f32, f32, f32, vp]
     lib.ga3c_last_error.restype = C.c_char_p
     lib.ga3c_profile_enable.argtypes = [vp, i32]
+    lib.ga3c_use_generic_kernels.argtypes = [vp, i32]
     lib.ga3c_profile_read.argtypes = [vp, C.c_char_p, sz]
     _lib = lib
     return lib
@@ -238,6 +240,9 @@ class Ga3c:
                                          _ptr(actions, torch.int32, "actions"), _ptr(rewards, torch.float32, "rewards"),
                                          _ptr(dones, torch.uint8, "dones"), _ptr(bootstrap, torch.float32, "bootstrap"),
                                          N, T, C.byref(hpc), sp, _stream(stream)), "ga3c_train_step")
+
+    def use_generic_kernels(self, on: bool) -> None:
+        _check(self._lib.ga3c_use_generic_kernels(self._ctx, 1 if on else 0), "ga3c_use_generic_kernels")
 
     def profile_enable(self, on: bool) -> None:
         _check(self._lib.ga3c_profile_enable(self._ctx, 1 if on else 0), "ga3c_profile_enable")

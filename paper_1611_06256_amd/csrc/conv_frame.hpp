@@ -1,0 +1,324 @@
+// Frame-resident convolution kernels for the shapes of the paper's small
+// network (Sec. 3.2: 16 filters 8x8 stride 4 on 4x84x84, then 32 filters 4x4
+// stride 2), compiled for a fixed geometry.
+//
+// One block keeps a whole input frame and the layer's filters in LDS and walks
+// over the frames assigned to it, so that every byte of the frame is fetched
+// from HBM once and the im2col gather happens between LDS and registers.  The
+// products run on v_mfma_f32_16x16x4_f32 with the filters as the row operand
+// and 16 output pixels as the column operand, so that a lane ends up with 4
+// output channels of one pixel and stores are contiguous along pixels (NCHW).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "gemm_mfma.hpp"
+
+namespace ga3c {
+
+template <class TIn_, int C_, int H_, int W_, int OC_, int KS_, int S_>
+struct ConvSpec {
+    typedef TIn_ TIn;
+    static constexpr int C = C_, H = H_, W = W_, OC = OC_, KS = KS_, S = S_;
+    static constexpr int OH = (H - KS) / S + 1, OW = (W - KS) / S + 1;
+    static constexpr int K = C * KS * KS, NPIX = OH * OW, CHW = C * H * W;
+    static constexpr int NT = (NPIX + 15) / 16;      // pixel tiles per frame
+    static constexpr int OT = OC / 16;               // filter tiles
+    static constexpr int WPITCH = K + 4;             // LDS row pitch of the filters (floats)
+    static_assert(OC % 16 == 0 && (OT == 1 || OT == 2 || OT == 4), "filter count must be 16, 32 or 64");
+    static_assert(KS == 4 || KS == 8, "kernel width must be 4 or 8 (4 taps of a row are fetched at once)");
+    static_assert(K % 16 == 0, "filter length must be a multiple of 16");
+    // element offset inside a frame of filter tap k = (c, u, v)
+    __host__ __device__ static constexpr int koff(int k) {
+        return (k / (KS * KS)) * H * W + ((k / KS) % KS) * W + (k % KS);
+    }
+};
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ floatx4 mfma4(float a, float b, floatx4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+
+// Four consecutive taps of one filter row, as floats.
+__device__ __forceinline__ float4 lds_taps(const uint8_t *xs, int off) {
+    const uint32_t v = *(const uint32_t *)(xs + off);      // off is a multiple of 4
+    return make_float4((float)(v & 0xff), (float)((v >> 8) & 0xff), (float)((v >> 16) & 0xff), (float)(v >> 24));
+}
+__device__ __forceinline__ float4 lds_taps(const float *xs, int off) {
+    const float2 a = *(const float2 *)(xs + off);          // off is even
+    const float2 b = *(const float2 *)(xs + off + 2);
+    return make_float4(a.x, a.y, b.x, b.y);
+}
+
+// y[b][oc][pix] = max(0, scale * sum_k W[oc][k] x[b][tap k at pix] + bias[oc]).
+// Block = 4 wavefronts; frames blockIdx.x, blockIdx.x + gridDim.x, ...
+template <class SP>
+__global__ __launch_bounds__(256, 2) void conv_fwd_frame_kernel(const typename SP::TIn *__restrict__ x,
+                                                                const float *__restrict__ w,
+                                                                const float *__restrict__ bias,
+                                                                float *__restrict__ y, int nframes, float scale) {
+    typedef typename SP::TIn TIn;
+    constexpr int FRAME_BYTES = SP::CHW * (int)sizeof(TIn);
+    static_assert(FRAME_BYTES % 16 == 0, "frame size must be a multiple of 16 bytes");
+    constexpr int NV = FRAME_BYTES / 16;                         // uint4 per frame
+    constexpr int VPT = (NV + 255) / 256;                        // uint4 per thread
+    constexpr int JOBS = SP::NT * SP::OT;                        // (pixel tile, filter tile) pairs per frame
+    constexpr int TPW = (JOBS + 3) / 4;                          // pairs per wave, the last one maybe absent
+    constexpr int FULL = JOBS % 4 == 0 ? TPW : TPW - 1;          // pairs every wave has
+    constexpr int NLAST = JOBS - 4 * FULL;                       // waves that have one more
+    // the frame, padded so that every thread can store all of its VPT vectors
+    __shared__ __attribute__((aligned(16))) unsigned char xs_raw[VPT * 256 * 16];
+    __shared__ __attribute__((aligned(16))) float ws[SP::OC * SP::WPITCH];
+    const TIn *xs = (const TIn *)xs_raw;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l16 = lane & 15, g = lane >> 4;
+    const int ot = wave % SP::OT;
+
+    // filters -> LDS, row pitch K+4 so that the 16 rows a wave reads hit different banks
+    for (int e = tid; e < SP::OC * SP::K / 4; e += 256) {
+        const int oc = e / (SP::K / 4), kq = e % (SP::K / 4);
+        const float4 v = *(const float4 *)(w + (size_t)oc * SP::K + 4 * kq);
+        *(float4 *)(ws + oc * SP::WPITCH + 4 * kq) = v;
+    }
+    float bv[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) bv[r] = bias[ot * 16 + 4 * g + r];
+
+    // per-lane constants: where each of my pixels starts in the frame, and the
+    // offset of my share (4g .. 4g+3) of every group of 16 taps
+    int pixbase[TPW], pixidx[TPW];
+#pragma unroll
+    for (int i = 0; i < TPW; ++i) {
+        const int job = wave + 4 * i;
+        const int pt = job / SP::OT;
+        int p = pt * 16 + l16;
+        pixidx[i] = (job < JOBS && p < SP::NPIX) ? p : -1;
+        if (p >= SP::NPIX) p = 0;
+        pixbase[i] = (p / SP::OW) * SP::S * SP::W + (p % SP::OW) * SP::S;
+    }
+    const int lane_koff = SP::koff(4 * g);
+    const float *wrow = ws + (ot * 16 + l16) * SP::WPITCH + 4 * g;
+
+    // a thread's vectors of the frame; indices past the end re-read the last one
+    int vidx[VPT];
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) vidx[i] = min(tid + 256 * i, NV - 1);
+
+    u32x4 pre[VPT];
+    int f = blockIdx.x;
+    {
+        const u32x4 *src = (const u32x4 *)(x + (size_t)min(f, nframes - 1) * SP::CHW);
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) pre[i] = src[vidx[i]];
+    }
+    for (; f < nframes; f += gridDim.x) {
+        __syncthreads();                       // everyone is done with the previous frame
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) ((u32x4 *)xs_raw)[tid + 256 * i] = pre[i];
+        __syncthreads();
+        {   // fetch the next frame while this one is computed
+            const u32x4 *src = (const u32x4 *)(x + (size_t)min(f + (int)gridDim.x, nframes - 1) * SP::CHW);
+#pragma unroll
+            for (int i = 0; i < VPT; ++i) pre[i] = src[vidx[i]];
+        }
+        floatx4 acc[TPW];
+#pragma unroll
+        for (int i = 0; i < TPW; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int q = 0; q < SP::K / 16; ++q) {
+            const float4 wv = *(const float4 *)(wrow + 16 * q);
+            const int ko = SP::koff(16 * q) + lane_koff;
+#pragma unroll
+            for (int i = 0; i < FULL; ++i) {
+                const float4 xv = lds_taps(xs, pixbase[i] + ko);
+                acc[i] = mfma4(wv.x, xv.x, acc[i]);
+                acc[i] = mfma4(wv.y, xv.y, acc[i]);
+                acc[i] = mfma4(wv.z, xv.z, acc[i]);
+                acc[i] = mfma4(wv.w, xv.w, acc[i]);
+            }
+        }
+        if (NLAST > 0 && wave < NLAST) {       // uniform per wave
+            constexpr int i = TPW - 1;
+#pragma unroll
+            for (int q = 0; q < SP::K / 16; ++q) {
+                const float4 wv = *(const float4 *)(wrow + 16 * q);
+                const float4 xv = lds_taps(xs, pixbase[i] + SP::koff(16 * q) + lane_koff);
+                acc[i] = mfma4(wv.x, xv.x, acc[i]);
+                acc[i] = mfma4(wv.y, xv.y, acc[i]);
+                acc[i] = mfma4(wv.z, xv.z, acc[i]);
+                acc[i] = mfma4(wv.w, xv.w, acc[i]);
+            }
+        }
+        float *yb = y + (size_t)f * SP::OC * SP::NPIX;
+#pragma unroll
+        for (int i = 0; i < TPW; ++i) {
+            if (pixidx[i] >= 0) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float v = acc[i][r] * scale + bv[r];
+                    yb[(ot * 16 + 4 * g + r) * SP::NPIX + pixidx[i]] = v > 0.f ? v : 0.f;
+                }
+            }
+        }
+    }
+}
+
+template <class SP>
+inline hipError_t launch_conv_fwd_frame(const typename SP::TIn *x, const float *w, const float *bias, float *y,
+                                        int nframes, float scale, hipStream_t s) {
+    if (nframes <= 0) return hipSuccess;
+    const int grid = nframes < 512 ? nframes : 512;
+    hipLaunchKernelGGL((conv_fwd_frame_kernel<SP>), dim3(grid), dim3(256), 0, s, x, w, bias, y, nframes, scale);
+    return hipGetLastError();
+}
+
+
+// Weight and bias gradient of the same layers.
+//   dW[oc][k] = sum over frames and output pixels of dY[oc][pix] * x[tap k at pix]
+//   db[oc]    = sum of dY[oc][pix]
+// The sum over pixels is the contraction index of the MFMA (4 pixels per
+// instruction, one per lane group), the filters are the rows and 16 filter
+// taps the columns of an output tile.  A wave owns K/64 tap tiles times all
+// filter tiles and keeps them in registers over all frames of its block; each
+// block then writes one partial dW, which a second kernel adds up in block
+// order (no atomics, so the result does not depend on timing).
+// part: [gridDim.x][OC][K+1], the last column is the bias gradient.
+template <class SP>
+__global__ __launch_bounds__(256, 2) void conv_wgrad_frame_kernel(const typename SP::TIn *__restrict__ x,
+                                                                  const float *__restrict__ dy,
+                                                                  float *__restrict__ part, int nframes, float scale) {
+    typedef typename SP::TIn TIn;
+    constexpr int FRAME_BYTES = SP::CHW * (int)sizeof(TIn);
+    constexpr int NV = FRAME_BYTES / 16, VPT = (NV + 255) / 256;
+    constexpr int NS = (SP::NPIX + 3) / 4;                       // contraction steps per frame
+    constexpr int DPITCH = ((4 * NS + 31) / 32) * 32 + 4;        // row pitch of dY in LDS: 4 mod 32 banks
+    constexpr int NDY = SP::OC * SP::NPIX, DPT = (NDY + 255) / 256;
+    constexpr int KT = SP::K / 16, KTW = KT / 4;                 // tap tiles in all / per wave
+    static_assert(KT % 4 == 0, "tap tiles must split evenly over 4 waves");
+    static_assert(256 % SP::OC == 0, "bias sums use 256/OC threads per filter");
+    constexpr int TPO = 256 / SP::OC;                            // threads per filter in the bias sum
+    __shared__ __attribute__((aligned(16))) unsigned char xs_raw[VPT * 256 * 16];
+    __shared__ __attribute__((aligned(16))) float ds[SP::OC * DPITCH];
+    const TIn *xs = (const TIn *)xs_raw;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l16 = lane & 15, g = lane >> 4;
+
+    for (int e = tid; e < SP::OC * DPITCH; e += 256) ds[e] = 0.f;   // the padding stays zero
+
+    int tapoff[KTW];                                             // my tap in each of my tiles
+#pragma unroll
+    for (int t = 0; t < KTW; ++t) tapoff[t] = SP::koff(16 * (wave * KTW + t) + l16);
+    // pixel 4s+g of a frame -> offset of its window
+    int pixoff[SP::OW % 4 == 0 ? 1 : NS];
+    if (SP::OW % 4 != 0) {
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            int p = 4 * s + g;
+            if (p >= SP::NPIX) p = 0;                             // dY is zero there
+            pixoff[SP::OW % 4 == 0 ? 0 : s] = (p / SP::OW) * SP::S * SP::W + (p % SP::OW) * SP::S;
+        }
+    }
+    int vidx[VPT];
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) vidx[i] = min(tid + 256 * i, NV - 1);
+    int didx[DPT], dlds[DPT];
+#pragma unroll
+    for (int i = 0; i < DPT; ++i) {
+        const int e = min(tid + 256 * i, NDY - 1);
+        didx[i] = e;
+        dlds[i] = (e / SP::NPIX) * DPITCH + e % SP::NPIX;
+    }
+
+    floatx4 acc[SP::OT][KTW];
+#pragma unroll
+    for (int o = 0; o < SP::OT; ++o)
+#pragma unroll
+        for (int t = 0; t < KTW; ++t) acc[o][t] = floatx4{0.f, 0.f, 0.f, 0.f};
+    float bsum = 0.f;
+
+    u32x4 pre[VPT];
+    float dpre[DPT];
+    int f = blockIdx.x;
+    {
+        const int ff = min(f, nframes - 1);
+        const u32x4 *src = (const u32x4 *)(x + (size_t)ff * SP::CHW);
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) pre[i] = src[vidx[i]];
+        const float *dsrc = dy + (size_t)ff * NDY;
+#pragma unroll
+        for (int i = 0; i < DPT; ++i) dpre[i] = dsrc[didx[i]];
+    }
+    for (; f < nframes; f += gridDim.x) {
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) ((u32x4 *)xs_raw)[tid + 256 * i] = pre[i];
+#pragma unroll
+        for (int i = 0; i < DPT; ++i) ds[dlds[i]] = dpre[i];
+        __syncthreads();
+        {
+            const int ff = min(f + (int)gridDim.x, nframes - 1);
+            const u32x4 *src = (const u32x4 *)(x + (size_t)ff * SP::CHW);
+#pragma unroll
+            for (int i = 0; i < VPT; ++i) pre[i] = src[vidx[i]];
+            const float *dsrc = dy + (size_t)ff * NDY;
+#pragma unroll
+            for (int i = 0; i < DPT; ++i) dpre[i] = dsrc[didx[i]];
+        }
+        {   // bias: TPO threads share a filter row, combined in lane order
+            const int oc = tid / TPO, part_id = tid % TPO;
+            float sum = 0.f;
+            for (int pp = part_id; pp < SP::NPIX; pp += TPO) sum += ds[oc * DPITCH + pp];
+#pragma unroll
+            for (int o = TPO / 2; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
+            bsum += sum;
+        }
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            int po;
+            if (SP::OW % 4 == 0) {
+                constexpr int dummy = 0; (void)dummy;
+                po = ((4 * s) / SP::OW) * SP::S * SP::W + ((4 * s) % SP::OW + g) * SP::S;
+            } else {
+                po = pixoff[SP::OW % 4 == 0 ? 0 : s];
+            }
+            float a[SP::OT];
+#pragma unroll
+            for (int o = 0; o < SP::OT; ++o) a[o] = ds[(o * 16 + l16) * DPITCH + 4 * s + g];
+#pragma unroll
+            for (int t = 0; t < KTW; ++t) {
+                const float b = (float)xs[po + tapoff[t]];
+#pragma unroll
+                for (int o = 0; o < SP::OT; ++o) acc[o][t] = mfma4(a[o], b, acc[o][t]);
+            }
+        }
+    }
+    // lane (l16, g) register r of tile (o, t): filter o*16 + 4g + r, tap 16*(wave*KTW+t) + l16
+    float *pb = part + (size_t)blockIdx.x * SP::OC * (SP::K + 1);
+#pragma unroll
+    for (int o = 0; o < SP::OT; ++o)
+#pragma unroll
+        for (int t = 0; t < KTW; ++t)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                pb[(o * 16 + 4 * g + r) * (SP::K + 1) + 16 * (wave * KTW + t) + l16] = acc[o][t][r] * scale;
+    if (tid % TPO == 0) pb[(tid / TPO) * (SP::K + 1) + SP::K] = bsum;
+}
+
+template <class SP>
+inline int conv_wgrad_frame_blocks(int nframes) { return nframes < 512 ? nframes : 512; }
+
+template <class SP>
+inline hipError_t launch_conv_wgrad_frame(const typename SP::TIn *x, const float *dy, float *part, int nframes,
+                                          float scale, hipStream_t s) {
+    if (nframes <= 0) return hipSuccess;
+    hipLaunchKernelGGL((conv_wgrad_frame_kernel<SP>), dim3(conv_wgrad_frame_blocks<SP>(nframes)), dim3(256), 0, s, x,
+                       dy, part, nframes, scale);
+    return hipGetLastError();
+}
+
+}  // namespace ga3c

@@ -14,6 +14,7 @@
 
 #include "../../include/ga3c.h"
 #include "problems.hpp"
+#include "conv_frame.hpp"
 
 using namespace ga3c;
 
@@ -71,6 +72,7 @@ struct Profiler {
 
 struct ga3c_ctx {
     Profiler *prof;
+    bool fast;                    // use the fixed-geometry kernels where they apply
     ga3c_net_desc desc;
     int nconv, F, A, flat;
     ConvGeom geom[GA3C_MAX_CONV];
@@ -226,18 +228,31 @@ __global__ __launch_bounds__(256) void heads_dgrad_kernel(const float *__restric
     dh[i] = h[i] > 0.f ? s : 0.f;
 }
 
-// Adds the nz split-k partials ws[z][M][N] in order of z.
-// WGRAD: rows [r0, r1) go to gW[(m-r0)*(N-1) + n] for n < N-1 and gb[m-r0] for n = N-1.
+// Adds the nz split-k partials ws[z][M][N].  Rows [r0, r1) go to
+// gW[(m-r0)*(N-1) + n] for n < N-1 and gb[m-r0] for n = N-1.  A block handles
+// 32 outputs with 8 threads each; thread j adds z = j, j+8, ... in that order
+// and the 8 sums are then added in order of j, so the result is reproducible.
 __global__ __launch_bounds__(256) void reduce_wgrad_kernel(const float *__restrict__ ws, int nz, int M, int N, int r0,
                                                            int r1, float *__restrict__ gW, float *__restrict__ gb) {
-    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    __shared__ float sh[8][33];
+    const int o = threadIdx.x & 31, zg = threadIdx.x >> 5;
     const size_t cnt = (size_t)(r1 - r0) * N;
-    if (i >= cnt) return;
-    const int m = r0 + (int)(i / N), n = (int)(i % N);
+    const size_t i = (size_t)blockIdx.x * 32 + o;
     float s = 0.f;
-    for (int z = 0; z < nz; ++z) s += ws[((size_t)z * M + m) * N + n];
-    if (n < N - 1) gW[(size_t)(m - r0) * (N - 1) + n] = s;
-    else gb[m - r0] = s;
+    if (i < cnt) {
+        const size_t src = (size_t)r0 * N + i, stride = (size_t)M * N;
+        for (int z = zg; z < nz; z += 8) s += ws[z * stride + src];
+    }
+    sh[zg][o] = s;
+    __syncthreads();
+    if (zg == 0 && i < cnt) {
+        float t = sh[0][o];
+#pragma unroll
+        for (int j = 1; j < 8; ++j) t += sh[j][o];
+        const int m = (int)(i / N), n = (int)(i % N);
+        if (n < N - 1) gW[(size_t)m * (N - 1) + n] = t;
+        else gb[m] = t;
+    }
 }
 
 // out[m][n] = max(0, sum_z ws[z][m][n] + bias[n]).
@@ -423,6 +438,18 @@ inline int conv_like_tiles(int M, int N) {
     return cdiv(M, 64) * cdiv(N, 64);
 }
 
+// Fixed-geometry kernels exist for the layers of the paper's networks.
+typedef ConvSpec<uint8_t, 4, 84, 84, 16, 8, 4> SpecS1;    // small net, conv1
+typedef ConvSpec<float, 16, 20, 20, 32, 4, 2> SpecS2;     // small net, conv2
+typedef ConvSpec<uint8_t, 4, 84, 84, 32, 8, 4> SpecL1;    // large net, conv1
+
+template <class SP>
+inline bool spec_matches(const ConvGeom &g, bool byte_input) {
+    return g.C == SP::C && g.H == SP::H && g.W == SP::W && g.OC == SP::OC && g.KS == SP::KS && g.S == SP::S &&
+           byte_input == (sizeof(typename SP::TIn) == 1);
+}
+inline bool is_aligned16(const void *p) { return (((uintptr_t)p) & 15) == 0; }
+
 // Forward pass of `B` frames into `w`; heads outputs to the optional pointers.
 int forward(ga3c_ctx *c, Work &w, const uint8_t *frames, int B, bool keep_zv, float *logits, float *values,
             float *probs, const float *uniforms, int32_t *actions, hipStream_t s) {
@@ -430,6 +457,22 @@ int forward(ga3c_ctx *c, Work &w, const uint8_t *frames, int B, bool keep_zv, fl
     for (int l = 0; l < c->nconv; ++l) {
         const ConvGeom &g = c->geom[l];
         STAGE(CONV_FWD[l], 2.0 * B * g.OHW * g.OC * g.K, 0);
+        const float *wl = c->theta + c->off[2 * l], *bl = c->theta + c->off[2 * l + 1];
+        const void *xin = l == 0 ? (const void *)frames : (const void *)w.act[l - 1];
+        if (c->fast && is_aligned16(wl) && is_aligned16(xin)) {
+            if (spec_matches<SpecS1>(g, l == 0)) {
+                HIP_TRY(launch_conv_fwd_frame<SpecS1>((const uint8_t *)xin, wl, bl, w.act[l], B, 1.f / 255.f, s));
+                continue;
+            }
+            if (spec_matches<SpecL1>(g, l == 0)) {
+                HIP_TRY(launch_conv_fwd_frame<SpecL1>((const uint8_t *)xin, wl, bl, w.act[l], B, 1.f / 255.f, s));
+                continue;
+            }
+            if (spec_matches<SpecS2>(g, l == 0)) {
+                HIP_TRY(launch_conv_fwd_frame<SpecS2>((const float *)xin, wl, bl, w.act[l], B, 1.f, s));
+                continue;
+            }
+        }
         if (l == 0) {
             ConvFwdP<uint8_t> p;
             p.M = g.OC; p.N = B * g.OHW; p.K = g.K; p.g = g;
@@ -497,6 +540,7 @@ size_t workspace_floats(const ga3c_ctx *c, int cap, bool training) {
             const ConvGeom &g = c->geom[l];
             pick_split(conv_like_tiles(g.OC, g.K + 1), B * g.OHW, nz, kc);
             need = std::max(need, (size_t)nz * g.OC * (g.K + 1));
+            need = std::max(need, (size_t)std::min(B, 512) * g.OC * (g.K + 1));   // frame-resident kernels
         }
         pick_split(cdiv(c->F, 64) * cdiv(c->flat + 1, 64), B, nz, kc);
         need = std::max(need, (size_t)nz * c->F * (c->flat + 1));
@@ -524,6 +568,7 @@ extern "C" int ga3c_create(const ga3c_net_desc *d, int max_predict_batch, int ma
     if (!c) return fail(GA3C_ENOMEM, "ga3c_create: host allocation failed");
     memset((void *)c, 0, sizeof(*c));
     c->prof = new (std::nothrow) Profiler();
+    c->fast = true;
     c->desc = *d;
     c->nconv = d->n_conv; c->F = d->fc_units; c->A = d->n_actions;
     c->max_pred = max_predict_batch; c->max_train = max_train_frames;
@@ -748,9 +793,9 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
         }
         {
             STAGE("heads_wgrad_reduce", 0, 4.0 * (nz + 1) * (A + 1) * (F + 1));
-            hipLaunchKernelGGL(reduce_wgrad_kernel, dim3(blocks_for((size_t)A * (F + 1))), dim3(256), 0, s, w.ws, nz,
+            hipLaunchKernelGGL(reduce_wgrad_kernel, dim3(blocks_for((size_t)A * (F + 1), 32)), dim3(256), 0, s, w.ws, nz,
                                A + 1, F + 1, 0, A, c->grad + c->off[nb + 2], c->grad + c->off[nb + 3]);
-            hipLaunchKernelGGL(reduce_wgrad_kernel, dim3(blocks_for((size_t)(F + 1))), dim3(256), 0, s, w.ws, nz, A + 1,
+            hipLaunchKernelGGL(reduce_wgrad_kernel, dim3(blocks_for((size_t)(F + 1), 32)), dim3(256), 0, s, w.ws, nz, A + 1,
                                F + 1, A, A + 1, c->grad + c->off[nb + 4], c->grad + c->off[nb + 5]);
         }
         STAGE("heads_dgrad", 2.0 * B * (A + 1) * F, 0);
@@ -773,7 +818,7 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
             HIP_TRY((launch_gemm<2, 2, 2, 2, true, true>(p, nz, s)));
         }
         STAGE("fc_wgrad_reduce", 0, 4.0 * (nz + 1) * p.M * p.N);
-        hipLaunchKernelGGL(reduce_wgrad_kernel, dim3(blocks_for((size_t)p.M * p.N)), dim3(256), 0, s, w.ws, nz, p.M,
+        hipLaunchKernelGGL(reduce_wgrad_kernel, dim3(blocks_for((size_t)p.M * p.N, 32)), dim3(256), 0, s, w.ws, nz, p.M,
                            p.N, 0, p.M, c->grad + c->off[nb], c->grad + c->off[nb + 1]);
         HIP_TRY(hipGetLastError());
     }
@@ -789,6 +834,27 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
     for (int l = c->nconv - 1; l >= 0; --l) {
         const ConvGeom &g = c->geom[l];
         // weight + bias gradient
+        {
+            const void *xin = l == 0 ? (const void *)frames : (const void *)w.act[l - 1];
+            bool done = false;
+            if (c->fast && is_aligned16(xin)) {
+                STAGE(CONV_WGRAD[l], 2.0 * B * g.OHW * g.OC * g.K, 0);
+                if (spec_matches<SpecS1>(g, l == 0)) {
+                    nz = conv_wgrad_frame_blocks<SpecS1>(B);
+                    HIP_TRY(launch_conv_wgrad_frame<SpecS1>((const uint8_t *)xin, c->dact[l], w.ws, B, 1.f / 255.f, s));
+                    done = true;
+                } else if (spec_matches<SpecL1>(g, l == 0)) {
+                    nz = conv_wgrad_frame_blocks<SpecL1>(B);
+                    HIP_TRY(launch_conv_wgrad_frame<SpecL1>((const uint8_t *)xin, c->dact[l], w.ws, B, 1.f / 255.f, s));
+                    done = true;
+                } else if (spec_matches<SpecS2>(g, l == 0)) {
+                    nz = conv_wgrad_frame_blocks<SpecS2>(B);
+                    HIP_TRY(launch_conv_wgrad_frame<SpecS2>((const float *)xin, c->dact[l], w.ws, B, 1.f, s));
+                    done = true;
+                }
+            }
+            if (done) goto wgrad_reduce;
+        }
         pick_split(conv_like_tiles(g.OC, g.K + 1), B * g.OHW, nz, kchunk);
         if ((size_t)nz * g.OC * (g.K + 1) > w.ws_floats) return fail(GA3C_EINVAL, "internal: split-k workspace too small (conv)");
         {
@@ -805,9 +871,10 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
             HIP_TRY(launch_conv_like(p, nz, s));
         }
         }
+    wgrad_reduce:
         {
             STAGE(CONV_WRED[l], 0, 4.0 * (nz + 1) * g.OC * (g.K + 1));
-            hipLaunchKernelGGL(reduce_wgrad_kernel, dim3(blocks_for((size_t)g.OC * (g.K + 1))), dim3(256), 0, s, w.ws, nz,
+            hipLaunchKernelGGL(reduce_wgrad_kernel, dim3(blocks_for((size_t)g.OC * (g.K + 1), 32)), dim3(256), 0, s, w.ws, nz,
                                g.OC, g.K + 1, 0, g.OC, c->grad + c->off[2 * l], c->grad + c->off[2 * l + 1]);
             HIP_TRY(hipGetLastError());
         }
@@ -908,5 +975,11 @@ extern "C" int ga3c_profile_read(ga3c_ctx *c, char *buf, size_t cap) {
         pos += (size_t)n;
     }
     p->stages.clear();
+    return GA3C_OK;
+}
+
+extern "C" int ga3c_use_generic_kernels(ga3c_ctx *c, int on) {
+    if (!c) return fail(GA3C_EINVAL, "ga3c_use_generic_kernels: null context");
+    c->fast = on == 0;
     return GA3C_OK;
 }

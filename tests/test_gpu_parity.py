@@ -35,9 +35,20 @@ def to_orc(desc):
                    fc_units=desc.fc_units, n_actions=desc.n_actions)
 
 
+GENERIC = False     # set by the fixture below: run every test on both kernel families
+
+
+@pytest.fixture(autouse=True, params=["shape-specific", "generic"])
+def kernel_family(request):
+    global GENERIC
+    GENERIC = request.param == "generic"
+    yield
+
+
 def make(G, desc, max_pred, max_train, seed):
     import torch
     net = G.Ga3c(desc, max_pred, max_train)
+    net.use_generic_kernels(GENERIC)
     onet = to_orc(desc)
     assert net.n_params == orc.param_count(onet)
     assert net.offsets() == orc.offsets(onet)
