@@ -45,7 +45,7 @@ extern "C" const char *ga3c_last_error(void) { return g_err; }
 namespace {
 
 constexpr int NORM_BLOCKS = 256;    // partial sums of the squared gradient norm
-constexpr int LOSS_THREADS = 128;   // agents per block in the returns/loss kernel
+constexpr int LOSS_THREADS = 64;    // frames per block in the returns/loss kernel
 
 struct Work {            // activations of one call; predict and train own one each
     int cap = 0;         // frames
@@ -110,27 +110,83 @@ __device__ __forceinline__ float wave_max(float v) {
 }
 
 // Policy and value heads (Sec. 3.2: softmax policy output, linear value
-// output) for one frame per wavefront, then softmax and inverse-CDF sampling.
-// h [B][F]; Wp [A][F], bp [A], Wv [F], bv [1].  zv [B][A+1] is written when
-// not null (training keeps it); logits / values / probs / actions are the
-// caller's optional outputs.
-__global__ __launch_bounds__(256) void heads_fwd_kernel(const float *__restrict__ h, int B, int F, int A,
-                                                        const float *__restrict__ Wp, const float *__restrict__ bp,
-                                                        const float *__restrict__ Wv, const float *__restrict__ bv,
-                                                        float *zv, float *logits, float *values, float *probs,
-                                                        const float *uniforms, int32_t *actions) {
-    const int lane = threadIdx.x & 63;
-    const int b = blockIdx.x * 4 + (threadIdx.x >> 6);
+// output), then softmax and inverse-CDF sampling; optionally preceded by the
+// last step of a split-k fully connected layer.  A block takes 4 frames, one
+// per wavefront.
+//   ws != null: h[b][o] = max(0, bias[o] + sum_z ws[z][b][o]) is formed first
+//               (and written to h); otherwise h is read.
+//   h [B][F]; Wp [A][F], bp [A], Wv [F], bv [1].  zv [B][A+1] is written when
+//   not null (training keeps it); logits / values / probs / actions are the
+//   caller's optional outputs.
+// Dynamic LDS: (4 + A + 1) * F floats: the 4 rows of h, then both weight
+// matrices.  Global memory answers in about a microsecond, so every load a
+// thread needs is issued before the first one is used: the head weights go to
+// LDS in one sweep and the partial sums are read 16 at a time.
+__global__ __launch_bounds__(256) void heads_fwd_kernel(const float *__restrict__ ws, int nz,
+                                                        const float *__restrict__ fcb, float *__restrict__ h, int B,
+                                                        int F, int A, const float *__restrict__ Wp,
+                                                        const float *__restrict__ bp, const float *__restrict__ Wv,
+                                                        const float *__restrict__ bv, float *zv, float *logits,
+                                                        float *values, float *probs, const float *uniforms,
+                                                        int32_t *actions) {
+    extern __shared__ float hs[];      // [4][F] then [A+1][F]
+    float *wsh = hs + 4 * F;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int b0 = blockIdx.x * 4;
+    const int nf = min(4, B - b0);
+    for (int e = tid; e < A * F; e += 256) wsh[e] = Wp[e];
+    for (int e = tid; e < F; e += 256) wsh[A * F + e] = Wv[e];
+    for (int o = tid; o < F; o += 256) {
+        if (ws) {
+            const float bias = fcb[o];
+            const size_t stride = (size_t)B * F;
+            float acc4[4] = {0.f, 0.f, 0.f, 0.f};
+            for (int z = 0; z < nz; z += 4) {
+                float v[4][4];
+#pragma unroll
+                for (int fb = 0; fb < 4; ++fb)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        v[fb][i] = (fb < nf && z + i < nz) ? ws[(z + i) * stride + (size_t)(b0 + fb) * F + o] : 0.f;
+#pragma unroll
+                for (int fb = 0; fb < 4; ++fb)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) acc4[fb] += v[fb][i];
+            }
+#pragma unroll
+            for (int fb = 0; fb < 4; ++fb)
+                if (fb < nf) {
+                    float v = acc4[fb] + bias;
+                    v = v > 0.f ? v : 0.f;
+                    h[(size_t)(b0 + fb) * F + o] = v;
+                    hs[fb * F + o] = v;
+                }
+        } else {
+#pragma unroll
+            for (int fb = 0; fb < 4; ++fb)
+                if (fb < nf) hs[fb * F + o] = h[(size_t)(b0 + fb) * F + o];
+        }
+    }
+    __syncthreads();
+    const int b = b0 + wave;
     if (b >= B) return;
-    const float *hb = h + (size_t)b * F;
+    const float *hb = hs + wave * F;
     // lane j ends up with output j (j < A: logit j, j == A: value)
     float mine = 0.f;
-    for (int a = 0; a <= A; ++a) {
-        const float *wr = a < A ? Wp + (size_t)a * F : Wv;
-        float s = 0.f;
-        for (int k = lane; k < F; k += 64) s += hb[k] * wr[k];
-        s = wave_sum(s);
-        if (lane == a) mine = s + (a < A ? bp[a] : bv[0]);
+    for (int a0 = 0; a0 <= A; a0 += 4) {
+        float s[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int k = lane; k < F; k += 64) {
+            const float x = hb[k];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (a0 + i <= A) s[i] += x * wsh[(a0 + i) * F + k];
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float t = wave_sum(s[i]);
+            const int a = a0 + i;
+            if (lane == a) mine = t + (a < A ? bp[a] : bv[0]);
+        }
     }
     if (lane <= A && zv) zv[(size_t)b * (A + 1) + lane] = mine;
     if (lane < A && logits) logits[(size_t)b * A + lane] = mine;
@@ -146,61 +202,63 @@ __global__ __launch_bounds__(256) void heads_fwd_kernel(const float *__restrict_
         int act = A - 1;
         for (int j = 0; j < A; ++j) {           // left-to-right fp32 running sum
             c += __shfl(p, j, 64);
-            if (c > u) { act = j; break; }      // uniform across the wave: every lane sees the same c
+            if (c > u) { act = j; break; }      // every lane sees the same c
         }
         if (lane == 0) actions[b] = act;
     }
 }
 
 // n-step returns (text after Eq. 1) and the loss with its gradient w.r.t. the
-// head outputs (Eq. 1, 2, 5), one thread per agent walking its T steps
-// backwards.  Per-block sums of the three loss pieces go to part[3*block..].
+// head outputs (Eq. 1, 2, 5), one thread per frame (n, t).  The thread walks
+// its agent's steps T-1 .. t to get R_t, in the order of the recursion.
+// Per-block sums of the three loss pieces go to part[3*block..].
 __global__ __launch_bounds__(LOSS_THREADS) void returns_loss_kernel(
     const float *__restrict__ zv, const int32_t *__restrict__ actions, const float *__restrict__ rewards,
     const uint8_t *__restrict__ dones, const float *__restrict__ bootstrap, int N, int T, int A, float gamma,
     float beta, float cv, float eps, float *__restrict__ R, float *__restrict__ dzv, float *__restrict__ part) {
-    const int n = blockIdx.x * LOSS_THREADS + threadIdx.x;
+    const int i = blockIdx.x * LOSS_THREADS + threadIdx.x;
     float s_pl = 0.f, s_vl = 0.f, s_en = 0.f;
-    if (n < N) {
+    if (i < N * T) {
+        const int n = i / T, t = i % T;
         float next = bootstrap ? bootstrap[n] : 0.f;
-        for (int t = T - 1; t >= 0; --t) {
-            const size_t i = (size_t)n * T + t;
-            next = rewards[i] + gamma * (dones[i] ? 0.f : 1.f) * next;
-            R[i] = next;
-            const float *z = zv + i * (A + 1);
-            float *dz = dzv + i * (A + 1);
-            const float V = z[A];
-            const int a = actions[i];
-            const float adv = next - V;
-            float zmax = z[0];
-            for (int j = 1; j < A; ++j) zmax = fmaxf(zmax, z[j]);
-            float S = 0.f;
-            for (int j = 0; j < A; ++j) S += expf(z[j] - zmax);
-            const float logS = logf(S), invS = 1.f / S;
-            // dL/dp_k = beta (lg_k + r_k) - [k=a] adv/(p_a+eps);  lg = log(p+eps), r = p/(p+eps)
-            float H = 0.f, dot = 0.f, lga = 0.f, ra = 1.f;
-            for (int j = 0; j < A; ++j) {
-                const float p = expf(z[j] - zmax) * invS;
-                float lg, r;
-                if (eps == 0.f) { lg = z[j] - zmax - logS; r = 1.f; }
-                else { lg = logf(p + eps); r = p / (p + eps); }
-                H -= p * lg;
-                dot += p * beta * (lg + r);
-                if (j == a) { lga = lg; ra = r; }
-            }
-            dot -= adv * ra;
-            for (int j = 0; j < A; ++j) {
-                const float p = expf(z[j] - zmax) * invS;
-                float lg, r;
-                if (eps == 0.f) { lg = z[j] - zmax - logS; r = 1.f; }
-                else { lg = logf(p + eps); r = p / (p + eps); }
-                dz[j] = p * (beta * (lg + r) - dot) - (j == a ? adv * ra : 0.f);
-            }
-            dz[A] = -2.f * cv * adv;
-            s_pl += -lga * adv;
-            s_vl += adv * adv;
-            s_en += H;
+        for (int tt = T - 1; tt >= t; --tt) {
+            const size_t j = (size_t)n * T + tt;
+            next = rewards[j] + gamma * (dones[j] ? 0.f : 1.f) * next;
         }
+        R[i] = next;
+        const float *z = zv + (size_t)i * (A + 1);
+        float *dz = dzv + (size_t)i * (A + 1);
+        const float V = z[A];
+        const int a = actions[i];
+        const float adv = next - V;
+        float zmax = z[0];
+        for (int j = 1; j < A; ++j) zmax = fmaxf(zmax, z[j]);
+        float S = 0.f;
+        for (int j = 0; j < A; ++j) S += expf(z[j] - zmax);
+        const float logS = logf(S), invS = 1.f / S;
+        // dL/dp_k = beta (lg_k + r_k) - [k=a] adv/(p_a+eps);  lg = log(p+eps), r = p/(p+eps)
+        float H = 0.f, dot = 0.f, lga = 0.f, ra = 1.f;
+        for (int j = 0; j < A; ++j) {
+            const float p = expf(z[j] - zmax) * invS;
+            float lg, r;
+            if (eps == 0.f) { lg = z[j] - zmax - logS; r = 1.f; }
+            else { lg = logf(p + eps); r = p / (p + eps); }
+            H -= p * lg;
+            dot += p * beta * (lg + r);
+            if (j == a) { lga = lg; ra = r; }
+        }
+        dot -= adv * ra;
+        for (int j = 0; j < A; ++j) {
+            const float p = expf(z[j] - zmax) * invS;
+            float lg, r;
+            if (eps == 0.f) { lg = z[j] - zmax - logS; r = 1.f; }
+            else { lg = logf(p + eps); r = p / (p + eps); }
+            dz[j] = p * (beta * (lg + r) - dot) - (j == a ? adv * ra : 0.f);
+        }
+        dz[A] = -2.f * cv * adv;
+        s_pl = -lga * adv;
+        s_vl = adv * adv;
+        s_en = H;
     }
     __shared__ float sh[3][LOSS_THREADS / 64];
     s_pl = wave_sum(s_pl); s_vl = wave_sum(s_vl); s_en = wave_sum(s_en);
@@ -253,17 +311,6 @@ __global__ __launch_bounds__(256) void reduce_wgrad_kernel(const float *__restri
         if (n < N - 1) gW[(size_t)m * (N - 1) + n] = t;
         else gb[m] = t;
     }
-}
-
-// out[m][n] = max(0, sum_z ws[z][m][n] + bias[n]).
-__global__ __launch_bounds__(256) void reduce_bias_relu_kernel(const float *__restrict__ ws, int nz, int M, int N,
-                                                               const float *__restrict__ bias, float *__restrict__ out) {
-    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= (size_t)M * N) return;
-    float s = 0.f;
-    for (int z = 0; z < nz; ++z) s += ws[(size_t)z * M * N + i];
-    s += bias[i % N];
-    out[i] = s > 0.f ? s : 0.f;
 }
 
 // Block b sums the squares of its contiguous slice of grad.
@@ -397,7 +444,7 @@ inline unsigned blocks_for(size_t n, int per = 256) { return (unsigned)((n + per
 // reduction of length K: enough blocks to fill 256 compute units a few times
 // over, chunks a multiple of the k-tile and at least two k-tiles long.
 inline void pick_split(int tiles, int K, int &nz, int &kchunk) {
-    int want = (1024 + tiles - 1) / tiles;
+    int want = (512 + tiles - 1) / tiles;
     int maxz = std::max(1, K / (2 * GEMM_BK));
     want = std::max(1, std::min(want, maxz));
     kchunk = (K + want - 1) / want;
@@ -487,40 +534,37 @@ int forward(ga3c_ctx *c, Work &w, const uint8_t *frames, int B, bool keep_zv, fl
             HIP_TRY(launch_conv_like(p, 1, s));
         }
     }
-    {   // fully connected + bias + ReLU: h[b][o] = sum_i x[b][i] Wfc[o][i]
+    const float *fc_ws = nullptr;
+    int fc_nz = 1;
+    {   // fully connected: h[b][o] = max(0, b[o] + sum_i x[b][i] Wfc[o][i])
         const int tiles = cdiv(B, 64) * cdiv(c->F, 64);
         int nz, kchunk;
         pick_split(tiles, c->flat, nz, kchunk);
         const float *x = w.act[c->nconv - 1];
+        STAGE("fc_fwd", 2.0 * B * c->F * c->flat, 0);
         if (nz == 1) {
             GemmP<EPI_BIAS_RELU, false> p;
             p.M = B; p.N = c->F; p.K = c->flat; p.kchunk = kchunk;
             p.A = x; p.sAm = c->flat; p.sAk = 1;
             p.B = c->theta + c->off[nb]; p.sBn = c->flat; p.sBk = 1;
             p.C = w.h; p.ldc = c->F; p.aux = c->theta + c->off[nb + 1];
-            STAGE("fc_fwd", 2.0 * B * c->F * c->flat, 0);
             HIP_TRY((launch_gemm<2, 2, 2, 2, false, false>(p, 1, s)));
-        } else {
+        } else {   // partial sums; the heads kernel adds them up
             GemmP<EPI_PARTIAL, false> p;
             p.M = B; p.N = c->F; p.K = c->flat; p.kchunk = kchunk;
             p.A = x; p.sAm = c->flat; p.sAk = 1;
             p.B = c->theta + c->off[nb]; p.sBn = c->flat; p.sBk = 1;
             p.C = w.ws; p.ldc = c->F; p.aux = nullptr;
             if ((size_t)nz * B * c->F > w.ws_floats) return fail(GA3C_EINVAL, "internal: split-k workspace too small (fc)");
-            {
-                STAGE("fc_fwd", 2.0 * B * c->F * c->flat, 0);
-                HIP_TRY((launch_gemm<2, 2, 2, 2, false, false>(p, nz, s)));
-            }
-            STAGE("fc_fwd_reduce", 0, 4.0 * (nz + 1) * B * c->F);
-            hipLaunchKernelGGL(reduce_bias_relu_kernel, dim3(blocks_for((size_t)B * c->F)), dim3(256), 0, s, w.ws, nz,
-                               B, c->F, c->theta + c->off[nb + 1], w.h);
-            HIP_TRY(hipGetLastError());
+            HIP_TRY((launch_gemm<2, 2, 2, 2, false, false>(p, nz, s)));
+            fc_ws = w.ws; fc_nz = nz;
         }
     }
-    STAGE("heads_fwd", 2.0 * B * c->F * (c->A + 1), 0);
-    hipLaunchKernelGGL(heads_fwd_kernel, dim3(cdiv(B, 4)), dim3(256), 0, s, w.h, B, c->F, c->A,
-                       c->theta + c->off[nb + 2], c->theta + c->off[nb + 3], c->theta + c->off[nb + 4],
-                       c->theta + c->off[nb + 5], keep_zv ? w.zv : nullptr, logits, values, probs, uniforms, actions);
+    STAGE("heads_fwd", 2.0 * B * c->F * (c->A + 1), 4.0 * (fc_nz + 1) * B * c->F);
+    hipLaunchKernelGGL(heads_fwd_kernel, dim3(cdiv(B, 4)), dim3(256), sizeof(float) * (4 + c->A + 1) * c->F, s, fc_ws, fc_nz,
+                       c->theta + c->off[nb + 1], w.h, B, c->F, c->A, c->theta + c->off[nb + 2],
+                       c->theta + c->off[nb + 3], c->theta + c->off[nb + 4], c->theta + c->off[nb + 5],
+                       keep_zv ? w.zv : nullptr, logits, values, probs, uniforms, actions);
     HIP_TRY(hipGetLastError());
     return GA3C_OK;
 }
@@ -563,6 +607,8 @@ extern "C" int ga3c_create(const ga3c_net_desc *d, int max_predict_batch, int ma
     if (d->in_c < 1 || d->in_h < 1 || d->in_w < 1 || d->fc_units < 1) return fail(GA3C_EINVAL, "ga3c_create: bad sizes");
     if (d->math != 0) return fail(GA3C_EINVAL, "ga3c_create: only math = 0 (fp32) is built");
     if (max_predict_batch < 0 || max_train_frames < 0) return fail(GA3C_EINVAL, "ga3c_create: negative capacity");
+    if ((size_t)(4 + d->n_actions + 1) * d->fc_units * sizeof(float) > 64 * 1024)
+        return fail(GA3C_EINVAL, "ga3c_create: (n_actions + 5) * fc_units must not exceed 16384");
 
     ga3c_ctx *c = new (std::nothrow) ga3c_ctx();
     if (!c) return fail(GA3C_ENOMEM, "ga3c_create: host allocation failed");
@@ -767,7 +813,7 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
     int rc = forward(c, w, frames, B, true, nullptr, nullptr, nullptr, nullptr, nullptr, s);
     if (rc != GA3C_OK) return rc;
 
-    const int nloss = cdiv(N, LOSS_THREADS);
+    const int nloss = cdiv(B, LOSS_THREADS);
     float *losspart = c->partials + NORM_BLOCKS;
     {
         STAGE("returns_loss", 0, 4.0 * B * (2 * (A + 1) + 4));
@@ -879,8 +925,13 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
             HIP_TRY(hipGetLastError());
         }
         if (l == 0) break;   // the input is data: no gradient needed
-        // input gradient, one launch per stride phase
+        // input gradient
         STAGE(CONV_DGRAD[l], 2.0 * B * g.OHW * g.OC * g.K, 0);
+        if (c->fast && spec_matches<SpecS2>(g, false) && is_aligned16(c->theta + c->off[2 * l])) {
+            HIP_TRY(launch_conv_dgrad_frame<SpecS2>(c->dact[l], c->theta + c->off[2 * l], w.act[l - 1], c->dact[l - 1], B, s));
+            continue;
+        }
+        // general shapes: one launch per stride phase
         for (int ry = 0; ry < g.S; ++ry)
             for (int rx = 0; rx < g.S; ++rx) {
                 ConvDgradP p;

@@ -69,20 +69,47 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_mfma_kernel(const P p) {
 #pragma unroll
         for (int j = 0; j < TN; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-    for (int k0 = kbeg; k0 < kend; k0 += BK) {
+    // The next k-tile is fetched into registers while the current one, already
+    // in LDS, is multiplied.
+    constexpr int AI = (BM * QK + NT - 1) / NT, BI = (BN * QK + NT - 1) / NT;
+    float4 ra[AI], rb[BI];
+    auto fetch = [&](int k0) {
 #pragma unroll
-        for (int e = tid; e < BM * QK; e += NT) {
+        for (int it = 0; it < AI; ++it) {
+            const int e = tid + it * NT;
             int row, q;
             if (A_ROWS) { row = e % BM; q = e / BM; } else { q = e % QK; row = e / QK; }
-            As[q][row] = p.loadA(m0 + row, k0 + 4 * q, kend, z);
+            ra[it] = (BM * QK % NT == 0 || e < BM * QK) ? p.loadA(m0 + row, k0 + 4 * q, kend, z)
+                                                        : make_float4(0.f, 0.f, 0.f, 0.f);
         }
 #pragma unroll
-        for (int e = tid; e < BN * QK; e += NT) {
+        for (int it = 0; it < BI; ++it) {
+            const int e = tid + it * NT;
             int row, q;
             if (B_ROWS) { row = e % BN; q = e / BN; } else { q = e % QK; row = e / QK; }
-            Bs[q][row] = p.loadB(n0 + row, k0 + 4 * q, kend, z);
+            rb[it] = (BN * QK % NT == 0 || e < BN * QK) ? p.loadB(n0 + row, k0 + 4 * q, kend, z)
+                                                        : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    };
+    if (kbeg < kend) fetch(kbeg);
+    for (int k0 = kbeg; k0 < kend; k0 += BK) {
+        __syncthreads();
+#pragma unroll
+        for (int it = 0; it < AI; ++it) {
+            const int e = tid + it * NT;
+            int row, q;
+            if (A_ROWS) { row = e % BM; q = e / BM; } else { q = e % QK; row = e / QK; }
+            if (BM * QK % NT == 0 || e < BM * QK) As[q][row] = ra[it];
+        }
+#pragma unroll
+        for (int it = 0; it < BI; ++it) {
+            const int e = tid + it * NT;
+            int row, q;
+            if (B_ROWS) { row = e % BN; q = e / BN; } else { q = e % QK; row = e / QK; }
+            if (BN * QK % NT == 0 || e < BN * QK) Bs[q][row] = rb[it];
         }
         __syncthreads();
+        if (k0 + BK < kend) fetch(k0 + BK);
 #pragma unroll
         for (int kb = 0; kb < QK / 4; ++kb) {
             float4 a[TM], b[TN];
@@ -100,7 +127,6 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_mfma_kernel(const P p) {
                     acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[i].w, b[j].w, acc[i][j], 0, 0, 0);
                 }
         }
-        __syncthreads();
     }
 
     // Accumulator register r of lane (l16, g) holds D[4*g + r][l16] of its tile.
