@@ -15,6 +15,7 @@
 #include "../../include/ga3c.h"
 #include "problems.hpp"
 #include "conv_frame.hpp"
+#include "dense_gemm.hpp"
 
 using namespace ga3c;
 
@@ -89,6 +90,7 @@ struct ga3c_ctx {
     float *dzv;                   // dL/d(logits, value) [cap][A+1]
     float *R;                     // returns [cap]
     float *partials;              // NORM_BLOCKS + 3 * loss blocks
+    float *colpart;               // per-block column sums of dh [cap/HD_FRAMES + 1][F]
     float *scale;                 // clip scale of the last step (1 float)
     ga3c_train_stats *stats;      // stats of the last step
     int last_frames;
@@ -107,6 +109,24 @@ __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
     return v;
+}
+
+// Global memory answers in roughly half a microsecond, so short kernels are
+// bound by the number of dependent load rounds, not by bytes.  These helpers
+// issue a batch of independent loads (indices past the end are clamped, the
+// values then ignored) before any of them is used.
+template <int BATCH>
+__device__ __forceinline__ void copy_to_lds(float *dst, const float *__restrict__ src, int n, int tid, int nthreads) {
+    for (int e0 = 0; e0 < n; e0 += BATCH * nthreads) {
+        float v[BATCH];
+#pragma unroll
+        for (int j = 0; j < BATCH; ++j) v[j] = src[min(e0 + j * nthreads + tid, n - 1)];
+#pragma unroll
+        for (int j = 0; j < BATCH; ++j) {
+            const int idx = e0 + j * nthreads + tid;
+            if (idx < n) dst[idx] = v[j];
+        }
+    }
 }
 
 // Policy and value heads (Sec. 3.2: softmax policy output, linear value
@@ -134,12 +154,13 @@ __global__ __launch_bounds__(256) void heads_fwd_kernel(const float *__restrict_
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int b0 = blockIdx.x * 4;
     const int nf = min(4, B - b0);
-    for (int e = tid; e < A * F; e += 256) wsh[e] = Wp[e];
-    for (int e = tid; e < F; e += 256) wsh[A * F + e] = Wv[e];
+    copy_to_lds<8>(wsh, Wp, A * F, tid, 256);
+    copy_to_lds<2>(wsh + A * F, Wv, F, tid, 256);
     for (int o = tid; o < F; o += 256) {
         if (ws) {
             const float bias = fcb[o];
             const size_t stride = (size_t)B * F;
+            const float *src = ws + (size_t)b0 * F + o;
             float acc4[4] = {0.f, 0.f, 0.f, 0.f};
             for (int z = 0; z < nz; z += 4) {
                 float v[4][4];
@@ -147,11 +168,11 @@ __global__ __launch_bounds__(256) void heads_fwd_kernel(const float *__restrict_
                 for (int fb = 0; fb < 4; ++fb)
 #pragma unroll
                     for (int i = 0; i < 4; ++i)
-                        v[fb][i] = (fb < nf && z + i < nz) ? ws[(z + i) * stride + (size_t)(b0 + fb) * F + o] : 0.f;
+                        v[fb][i] = src[min(z + i, nz - 1) * stride + (size_t)min(fb, nf - 1) * F];
 #pragma unroll
                 for (int fb = 0; fb < 4; ++fb)
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) acc4[fb] += v[fb][i];
+                    for (int i = 0; i < 4; ++i) acc4[fb] += (z + i < nz) ? v[fb][i] : 0.f;
             }
 #pragma unroll
             for (int fb = 0; fb < 4; ++fb)
@@ -162,9 +183,12 @@ __global__ __launch_bounds__(256) void heads_fwd_kernel(const float *__restrict_
                     hs[fb * F + o] = v;
                 }
         } else {
+            float v[4];
+#pragma unroll
+            for (int fb = 0; fb < 4; ++fb) v[fb] = h[(size_t)(b0 + min(fb, nf - 1)) * F + o];
 #pragma unroll
             for (int fb = 0; fb < 4; ++fb)
-                if (fb < nf) hs[fb * F + o] = h[(size_t)(b0 + fb) * F + o];
+                if (fb < nf) hs[fb * F + o] = v[fb];
         }
     }
     __syncthreads();
@@ -210,26 +234,38 @@ __global__ __launch_bounds__(256) void heads_fwd_kernel(const float *__restrict_
 
 // n-step returns (text after Eq. 1) and the loss with its gradient w.r.t. the
 // head outputs (Eq. 1, 2, 5), one thread per frame (n, t).  The thread walks
-// its agent's steps T-1 .. t to get R_t, in the order of the recursion.
+// its agent's steps T-1 .. t to get R_t, in the order of the recursion.  The
+// block first copies the head outputs of its frames to LDS in one sweep.
 // Per-block sums of the three loss pieces go to part[3*block..].
+// Dynamic LDS: LOSS_THREADS * (A + 1) floats.
 __global__ __launch_bounds__(LOSS_THREADS) void returns_loss_kernel(
     const float *__restrict__ zv, const int32_t *__restrict__ actions, const float *__restrict__ rewards,
     const uint8_t *__restrict__ dones, const float *__restrict__ bootstrap, int N, int T, int A, float gamma,
     float beta, float cv, float eps, float *__restrict__ R, float *__restrict__ dzv, float *__restrict__ part) {
-    const int i = blockIdx.x * LOSS_THREADS + threadIdx.x;
+    extern __shared__ float zsh[];     // [LOSS_THREADS][A+1]
+    const int i0 = blockIdx.x * LOSS_THREADS;
+    const int i = i0 + threadIdx.x;
+    const int B = N * T;
+    const int nrows = min(LOSS_THREADS, B - i0);
+    copy_to_lds<8>(zsh, zv + (size_t)i0 * (A + 1), nrows * (A + 1), threadIdx.x, LOSS_THREADS);
     float s_pl = 0.f, s_vl = 0.f, s_en = 0.f;
-    if (i < N * T) {
+    float next = 0.f;
+    int a = 0;
+    if (i < B) {
         const int n = i / T, t = i % T;
-        float next = bootstrap ? bootstrap[n] : 0.f;
+        next = bootstrap ? bootstrap[n] : 0.f;
+        a = actions[i];
         for (int tt = T - 1; tt >= t; --tt) {
             const size_t j = (size_t)n * T + tt;
             next = rewards[j] + gamma * (dones[j] ? 0.f : 1.f) * next;
         }
         R[i] = next;
-        const float *z = zv + (size_t)i * (A + 1);
+    }
+    __syncthreads();
+    if (i < B) {
+        const float *z = zsh + threadIdx.x * (A + 1);
         float *dz = dzv + (size_t)i * (A + 1);
         const float V = z[A];
-        const int a = actions[i];
         const float adv = next - V;
         float zmax = z[0];
         for (int j = 1; j < A; ++j) zmax = fmaxf(zmax, z[j]);
@@ -274,24 +310,56 @@ __global__ __launch_bounds__(LOSS_THREADS) void returns_loss_kernel(
 }
 
 // dL/d(pre-activation of fc)[b][k] = [h > 0] * (sum_a dz[b][a] Wp[a][k] + dv[b] Wv[k]).
+// A block takes HD_FRAMES frames; both weight matrices and the frames' dz rows
+// are first copied to LDS.  colpart[block][k] receives the block's sum over
+// its frames, which a reduction turns into the fc bias gradient.  Dynamic LDS: (A + 1) * (F + HD_FRAMES) floats.
+constexpr int HD_FRAMES = 8;
 __global__ __launch_bounds__(256) void heads_dgrad_kernel(const float *__restrict__ dzv, const float *__restrict__ h,
                                                           const float *__restrict__ Wp, const float *__restrict__ Wv,
-                                                          int B, int F, int A, float *__restrict__ dh) {
-    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= (size_t)B * F) return;
-    const int b = (int)(i / F), k = (int)(i % F);
-    const float *dz = dzv + (size_t)b * (A + 1);
-    float s = dz[A] * Wv[k];
-    for (int a = 0; a < A; ++a) s += dz[a] * Wp[(size_t)a * F + k];
-    dh[i] = h[i] > 0.f ? s : 0.f;
+                                                          int B, int F, int A, float *__restrict__ dh,
+                                                          float *__restrict__ colpart) {
+    extern __shared__ float sm[];
+    float *wsh = sm;                        // [A+1][F]
+    float *dzs = sm + (A + 1) * F;          // [HD_FRAMES][A+1]
+    const int tid = threadIdx.x;
+    const int b0 = blockIdx.x * HD_FRAMES;
+    const int nf = min(HD_FRAMES, B - b0);
+    copy_to_lds<8>(wsh, Wp, A * F, tid, 256);
+    copy_to_lds<2>(wsh + A * F, Wv, F, tid, 256);
+    copy_to_lds<1>(dzs, dzv + (size_t)b0 * (A + 1), nf * (A + 1), tid, 256);
+    __syncthreads();
+    for (int k = tid; k < F; k += 256) {
+        float hv[HD_FRAMES];
+#pragma unroll
+        for (int fb = 0; fb < HD_FRAMES; ++fb) hv[fb] = h[(size_t)(b0 + min(fb, nf - 1)) * F + k];
+        float s[HD_FRAMES];
+#pragma unroll
+        for (int fb = 0; fb < HD_FRAMES; ++fb) s[fb] = 0.f;
+        for (int a = 0; a <= A; ++a) {
+            const float wv = wsh[a * F + k];
+#pragma unroll
+            for (int fb = 0; fb < HD_FRAMES; ++fb) s[fb] += dzs[min(fb, nf - 1) * (A + 1) + a] * wv;
+        }
+        float col = 0.f;
+#pragma unroll
+        for (int fb = 0; fb < HD_FRAMES; ++fb)
+            if (fb < nf) {
+                const float v = hv[fb] > 0.f ? s[fb] : 0.f;
+                dh[(size_t)(b0 + fb) * F + k] = v;
+                col += v;
+            }
+        colpart[(size_t)blockIdx.x * F + k] = col;      // this block's share of the fc bias gradient
+    }
 }
 
 // Adds the nz split-k partials ws[z][M][N].  Rows [r0, r1) go to
-// gW[(m-r0)*(N-1) + n] for n < N-1 and gb[m-r0] for n = N-1.  A block handles
+// gW[(m-r0)*(N-1) + n] for n < N-1 and gb[m-r0] for n = N-1 (bias_col != 0),
+// or all N columns to gW[(m-r0)*N + n] (bias_col == 0).  A block handles
 // 32 outputs with 8 threads each; thread j adds z = j, j+8, ... in that order
 // and the 8 sums are then added in order of j, so the result is reproducible.
 __global__ __launch_bounds__(256) void reduce_wgrad_kernel(const float *__restrict__ ws, int nz, int M, int N, int r0,
-                                                           int r1, float *__restrict__ gW, float *__restrict__ gb) {
+                                                           int r1, float *__restrict__ gW, float *__restrict__ gb,
+                                                           int bias_col) {
     __shared__ float sh[8][33];
     const int o = threadIdx.x & 31, zg = threadIdx.x >> 5;
     const size_t cnt = (size_t)(r1 - r0) * N;
@@ -299,7 +367,13 @@ __global__ __launch_bounds__(256) void reduce_wgrad_kernel(const float *__restri
     float s = 0.f;
     if (i < cnt) {
         const size_t src = (size_t)r0 * N + i, stride = (size_t)M * N;
-        for (int z = zg; z < nz; z += 8) s += ws[z * stride + src];
+        for (int z = zg; z < nz; z += 64) {         // 8 independent loads per round
+            float v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = ws[(size_t)min(z + 8 * j, nz - 1) * stride + src];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) s += (z + 8 * j < nz) ? v[j] : 0.f;
+        }
     }
     sh[zg][o] = s;
     __syncthreads();
@@ -308,7 +382,8 @@ __global__ __launch_bounds__(256) void reduce_wgrad_kernel(const float *__restri
 #pragma unroll
         for (int j = 1; j < 8; ++j) t += sh[j][o];
         const int m = (int)(i / N), n = (int)(i % N);
-        if (n < N - 1) gW[(size_t)m * (N - 1) + n] = t;
+        if (!bias_col) gW[i] = t;                 // all N columns are weights
+        else if (n < N - 1) gW[(size_t)m * (N - 1) + n] = t;
         else gb[m] = t;
     }
 }
@@ -319,7 +394,13 @@ __global__ __launch_bounds__(256) void sqnorm_partial_kernel(const float *__rest
     const size_t per = (n + gridDim.x - 1) / gridDim.x;
     const size_t lo = per * blockIdx.x, hi = lo + per < n ? lo + per : n;
     float s = 0.f;
-    for (size_t i = lo + threadIdx.x; i < hi; i += 256) s += grad[i] * grad[i];
+    for (size_t i = lo + threadIdx.x; i < hi; i += 8 * 256) {       // 8 independent loads per round
+        float v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) { const size_t k = i + 256 * j; v[j] = grad[k < hi ? k : hi - 1]; }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) s += (i + 256 * j < hi) ? v[j] * v[j] : 0.f;
+    }
     __shared__ float sh[4];
     s = wave_sum(s);
     if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = s;
@@ -454,6 +535,17 @@ inline void pick_split(int tiles, int K, int &nz, int &kchunk) {
 
 inline int cdiv(int a, int b) { return (a + b - 1) / b; }
 
+// k-chunks for the XCD-partitioned dense product: a multiple of 8 chunks (one
+// or more per XCD) when the reduction is long enough, about 512 blocks in all.
+inline void pick_split_xcd(int tiles, int K, int &nz, int &kchunk) {
+    int want = 8 * std::max(1, (512 + 8 * tiles - 1) / (8 * tiles));
+    const int maxz = std::max(1, K / (2 * GEMM_BK));
+    if (want > maxz) want = maxz >= 8 ? maxz / 8 * 8 : maxz;
+    kchunk = (K + want - 1) / want;
+    kchunk = (kchunk + GEMM_BK - 1) / GEMM_BK * GEMM_BK;
+    nz = (K + kchunk - 1) / kchunk;
+}
+
 int alloc_work(Work &w, const ga3c_ctx *c, int cap) {
     w.cap = cap;
     if (cap <= 0) return GA3C_OK;
@@ -537,23 +629,25 @@ int forward(ga3c_ctx *c, Work &w, const uint8_t *frames, int B, bool keep_zv, fl
     const float *fc_ws = nullptr;
     int fc_nz = 1;
     {   // fully connected: h[b][o] = max(0, b[o] + sum_i x[b][i] Wfc[o][i])
-        const int tiles = cdiv(B, 64) * cdiv(c->F, 64);
-        int nz, kchunk;
-        pick_split(tiles, c->flat, nz, kchunk);
         const float *x = w.act[c->nconv - 1];
+        const float *wfc = c->theta + c->off[nb];
         STAGE("fc_fwd", 2.0 * B * c->F * c->flat, 0);
-        if (nz == 1) {
-            GemmP<EPI_BIAS_RELU, false> p;
-            p.M = B; p.N = c->F; p.K = c->flat; p.kchunk = kchunk;
-            p.A = x; p.sAm = c->flat; p.sAk = 1;
-            p.B = c->theta + c->off[nb]; p.sBn = c->flat; p.sBk = 1;
-            p.C = w.h; p.ldc = c->F; p.aux = c->theta + c->off[nb + 1];
-            HIP_TRY((launch_gemm<2, 2, 2, 2, false, false>(p, 1, s)));
-        } else {   // partial sums; the heads kernel adds them up
+        int nz, kchunk;
+        if (c->fast && dense_operand_ok(x, c->flat, c->flat) && dense_operand_ok(wfc, c->flat, c->flat)) {
+            pick_split_xcd(cdiv(B, 64) * cdiv(c->F, 64), c->flat, nz, kchunk);
+            DenseGemmArgs p{};
+            p.M = B; p.N = c->F; p.K = c->flat; p.kchunk = kchunk; p.nz = nz;
+            p.A = x; p.lda = c->flat; p.B = wfc; p.ldb = c->flat;
+            p.C = w.ws; p.ldc = c->F; p.aux = nullptr;
+            if ((size_t)nz * B * c->F > w.ws_floats) return fail(GA3C_EINVAL, "internal: split-k workspace too small (fc)");
+            HIP_TRY((launch_dense_gemm<2, 2, 2, 2, false, false, DG_PARTIAL>(p, DG_SPLIT_Z, s)));
+            fc_ws = w.ws; fc_nz = nz;
+        } else {
+            pick_split(cdiv(B, 64) * cdiv(c->F, 64), c->flat, nz, kchunk);
             GemmP<EPI_PARTIAL, false> p;
             p.M = B; p.N = c->F; p.K = c->flat; p.kchunk = kchunk;
             p.A = x; p.sAm = c->flat; p.sAk = 1;
-            p.B = c->theta + c->off[nb]; p.sBn = c->flat; p.sBk = 1;
+            p.B = wfc; p.sBn = c->flat; p.sBk = 1;
             p.C = w.ws; p.ldc = c->F; p.aux = nullptr;
             if ((size_t)nz * B * c->F > w.ws_floats) return fail(GA3C_EINVAL, "internal: split-k workspace too small (fc)");
             HIP_TRY((launch_gemm<2, 2, 2, 2, false, false>(p, nz, s)));
@@ -575,7 +669,9 @@ size_t workspace_floats(const ga3c_ctx *c, int cap, bool training) {
     for (int B = 1; B <= cap; ++B) {        // fc forward: depends on the batch
         int nz, kc;
         pick_split(cdiv(B, 64) * cdiv(c->F, 64), c->flat, nz, kc);
-        if (nz > 1) need = std::max(need, (size_t)nz * B * c->F);
+        need = std::max(need, (size_t)nz * B * c->F);
+        pick_split_xcd(cdiv(B, 64) * cdiv(c->F, 64), c->flat, nz, kc);
+        need = std::max(need, (size_t)nz * B * c->F);
     }
     const int B = cap;
     if (training && B > 0) {
@@ -588,6 +684,8 @@ size_t workspace_floats(const ga3c_ctx *c, int cap, bool training) {
         }
         pick_split(cdiv(c->F, 64) * cdiv(c->flat + 1, 64), B, nz, kc);
         need = std::max(need, (size_t)nz * c->F * (c->flat + 1));
+        pick_split_xcd(cdiv(c->F, 64) * cdiv(c->flat, 64), B, nz, kc);
+        need = std::max(need, (size_t)nz * c->F * c->flat);
         pick_split(conv_like_tiles(c->A + 1, c->F + 1), B, nz, kc);
         need = std::max(need, (size_t)nz * (c->A + 1) * (c->F + 1));
     }
@@ -692,6 +790,7 @@ extern "C" int ga3c_create(const ga3c_net_desc *d, int max_predict_batch, int ma
         if (rc == GA3C_OK) guard(dmalloc((void **)&c->dzv, sizeof(float) * B * (c->A + 1)));
         if (rc == GA3C_OK) guard(dmalloc((void **)&c->R, sizeof(float) * B));
         if (rc == GA3C_OK) guard(dmalloc((void **)&c->partials, sizeof(float) * (NORM_BLOCKS + 3 * (B / LOSS_THREADS + 1))));
+        if (rc == GA3C_OK) guard(dmalloc((void **)&c->colpart, sizeof(float) * (B / HD_FRAMES + 1) * c->F));
         if (rc == GA3C_OK) guard(dmalloc((void **)&c->scale, sizeof(float)));
         if (rc == GA3C_OK) guard(dmalloc((void **)&c->stats, sizeof(ga3c_train_stats)));
         if (rc == GA3C_OK) {
@@ -725,7 +824,7 @@ extern "C" int ga3c_destroy(ga3c_ctx *c) {
     (void)hipFree(c->theta); (void)hipFree(c->g); (void)hipFree(c->grad);
     free_work(c->pred); free_work(c->train);
     (void)hipFree(c->dh); (void)hipFree(c->dzv); (void)hipFree(c->R);
-    (void)hipFree(c->partials); (void)hipFree(c->scale); (void)hipFree(c->stats);
+    (void)hipFree(c->partials); (void)hipFree(c->colpart); (void)hipFree(c->scale); (void)hipFree(c->stats);
     if (c->prof) {
         for (ProfRec &r : c->prof->recs) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
         for (hipEvent_t e : c->prof->pool) (void)hipEventDestroy(e);
@@ -817,7 +916,7 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
     float *losspart = c->partials + NORM_BLOCKS;
     {
         STAGE("returns_loss", 0, 4.0 * B * (2 * (A + 1) + 4));
-        hipLaunchKernelGGL(returns_loss_kernel, dim3(nloss), dim3(LOSS_THREADS), 0, s, w.zv, actions, rewards, dones,
+        hipLaunchKernelGGL(returns_loss_kernel, dim3(nloss), dim3(LOSS_THREADS), sizeof(float) * LOSS_THREADS * (A + 1), s, w.zv, actions, rewards, dones,
                            bootstrap, N, T, A, hp->gamma, hp->beta, hp->value_coef, hp->log_eps, c->R, c->dzv, losspart);
         HIP_TRY(hipGetLastError());
     }
@@ -840,17 +939,38 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
         {
             STAGE("heads_wgrad_reduce", 0, 4.0 * (nz + 1) * (A + 1) * (F + 1));
             hipLaunchKernelGGL(reduce_wgrad_kernel, dim3(blocks_for((size_t)A * (F + 1), 32)), dim3(256), 0, s, w.ws, nz,
-                               A + 1, F + 1, 0, A, c->grad + c->off[nb + 2], c->grad + c->off[nb + 3]);
+                               A + 1, F + 1, 0, A, c->grad + c->off[nb + 2], c->grad + c->off[nb + 3], 1);
             hipLaunchKernelGGL(reduce_wgrad_kernel, dim3(blocks_for((size_t)(F + 1), 32)), dim3(256), 0, s, w.ws, nz, A + 1,
-                               F + 1, A, A + 1, c->grad + c->off[nb + 4], c->grad + c->off[nb + 5]);
+                               F + 1, A, A + 1, c->grad + c->off[nb + 4], c->grad + c->off[nb + 5], 1);
         }
         STAGE("heads_dgrad", 2.0 * B * (A + 1) * F, 0);
-        hipLaunchKernelGGL(heads_dgrad_kernel, dim3(blocks_for((size_t)B * F)), dim3(256), 0, s, c->dzv, w.h, Wp, Wv, B,
-                           F, A, c->dh);
+        hipLaunchKernelGGL(heads_dgrad_kernel, dim3(cdiv(B, HD_FRAMES)), dim3(256), sizeof(float) * (A + 1) * (F + HD_FRAMES), s, c->dzv, w.h, Wp, Wv, B,
+                           F, A, c->dh, c->colpart);
         HIP_TRY(hipGetLastError());
     }
     const float *xfc = w.act[c->nconv - 1];
-    {   // fc weight + bias gradient: D[o][i] = sum_b dh[b][o] x[b][i]
+    const float *wfc = c->theta + c->off[nb];
+    const bool fc_dense = c->fast && dense_operand_ok(c->dh, F, F) && dense_operand_ok(xfc, c->flat, c->flat) &&
+                          dense_operand_ok(wfc, c->flat, c->flat);
+    if (fc_dense) {   // fc weight gradient: D[o][i] = sum_b dh[b][o] x[b][i]; bias from the column sums of dh
+        pick_split_xcd(cdiv(F, 64) * cdiv(c->flat, 64), B, nz, kchunk);
+        DenseGemmArgs p{};
+        p.M = F; p.N = c->flat; p.K = B; p.kchunk = kchunk; p.nz = nz;
+        p.A = c->dh; p.lda = F; p.B = xfc; p.ldb = c->flat;
+        p.C = w.ws; p.ldc = 0; p.aux = nullptr;
+        if ((size_t)nz * p.M * p.N > w.ws_floats) return fail(GA3C_EINVAL, "internal: split-k workspace too small (fc wgrad)");
+        {
+            STAGE("fc_wgrad", 2.0 * B * F * c->flat, 0);
+            HIP_TRY((launch_dense_gemm<2, 2, 2, 2, true, true, DG_PARTIAL>(p, DG_SPLIT_Z, s)));
+        }
+        STAGE("fc_wgrad_reduce", 0, 4.0 * (nz + 1) * p.M * p.N);
+        hipLaunchKernelGGL(reduce_wgrad_kernel, dim3(blocks_for((size_t)p.M * p.N, 32)), dim3(256), 0, s, w.ws, nz, p.M,
+                           p.N, 0, p.M, c->grad + c->off[nb], (float *)nullptr, 0);
+        const int ncol = cdiv(B, HD_FRAMES);
+        hipLaunchKernelGGL(reduce_wgrad_kernel, dim3(blocks_for((size_t)F, 32)), dim3(256), 0, s, c->colpart, ncol, 1, F,
+                           0, 1, c->grad + c->off[nb + 1], (float *)nullptr, 0);
+        HIP_TRY(hipGetLastError());
+    } else {   // general shapes: one more column of ones yields the bias gradient
         GemmP<EPI_PARTIAL, true> p;
         p.M = F; p.N = c->flat + 1; p.K = B;
         pick_split(cdiv(p.M, 64) * cdiv(p.N, 64), B, nz, kchunk);
@@ -865,17 +985,25 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
         }
         STAGE("fc_wgrad_reduce", 0, 4.0 * (nz + 1) * p.M * p.N);
         hipLaunchKernelGGL(reduce_wgrad_kernel, dim3(blocks_for((size_t)p.M * p.N, 32)), dim3(256), 0, s, w.ws, nz, p.M,
-                           p.N, 0, p.M, c->grad + c->off[nb], c->grad + c->off[nb + 1]);
+                           p.N, 0, p.M, c->grad + c->off[nb], c->grad + c->off[nb + 1], 1);
         HIP_TRY(hipGetLastError());
     }
     {   // fc input gradient, masked by the ReLU of the last conv layer
-        GemmP<EPI_MASK, false> p;
-        p.M = B; p.N = c->flat; p.K = F; p.kchunk = (F + GEMM_BK - 1) / GEMM_BK * GEMM_BK;
-        p.A = c->dh; p.sAm = F; p.sAk = 1;
-        p.B = c->theta + c->off[nb]; p.sBn = 1; p.sBk = c->flat;
-        p.C = c->dact[c->nconv - 1]; p.ldc = c->flat; p.aux = xfc;
         STAGE("fc_dgrad", 2.0 * B * F * c->flat, 0);
-        HIP_TRY((launch_gemm<2, 2, 2, 2, false, true>(p, 1, s)));
+        if (fc_dense) {
+            DenseGemmArgs p{};
+            p.M = B; p.N = c->flat; p.K = F; p.kchunk = (F + GEMM_BK - 1) / GEMM_BK * GEMM_BK; p.nz = 1;
+            p.A = c->dh; p.lda = F; p.B = wfc; p.ldb = c->flat;
+            p.C = c->dact[c->nconv - 1]; p.ldc = c->flat; p.aux = xfc;
+            HIP_TRY((launch_dense_gemm<2, 2, 2, 2, false, true, DG_MASK>(p, DG_SPLIT_N, s)));
+        } else {
+            GemmP<EPI_MASK, false> p;
+            p.M = B; p.N = c->flat; p.K = F; p.kchunk = (F + GEMM_BK - 1) / GEMM_BK * GEMM_BK;
+            p.A = c->dh; p.sAm = F; p.sAk = 1;
+            p.B = wfc; p.sBn = 1; p.sBk = c->flat;
+            p.C = c->dact[c->nconv - 1]; p.ldc = c->flat; p.aux = xfc;
+            HIP_TRY((launch_gemm<2, 2, 2, 2, false, true>(p, 1, s)));
+        }
     }
     for (int l = c->nconv - 1; l >= 0; --l) {
         const ConvGeom &g = c->geom[l];
@@ -921,7 +1049,7 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
         {
             STAGE(CONV_WRED[l], 0, 4.0 * (nz + 1) * g.OC * (g.K + 1));
             hipLaunchKernelGGL(reduce_wgrad_kernel, dim3(blocks_for((size_t)g.OC * (g.K + 1), 32)), dim3(256), 0, s, w.ws, nz,
-                               g.OC, g.K + 1, 0, g.OC, c->grad + c->off[2 * l], c->grad + c->off[2 * l + 1]);
+                               g.OC, g.K + 1, 0, g.OC, c->grad + c->off[2 * l], c->grad + c->off[2 * l + 1], 1);
             HIP_TRY(hipGetLastError());
         }
         if (l == 0) break;   // the input is data: no gradient needed
