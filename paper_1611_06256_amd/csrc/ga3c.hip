@@ -100,15 +100,30 @@ namespace {
 
 // ------------------------------------------------------------ small kernels -
 
+// Wavefront-wide sum and max in registers: butterflies inside each row of 16
+// lanes with DPP (quad permutes, then the two mirror patterns), then the four
+// row results are combined through scalar registers.  Every lane gets the
+// result; no LDS traffic, unlike __shfl_xor.
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+__device__ __forceinline__ float lane_f32(float v, int lane) {
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
+}
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-    return v;
+    v += dpp_f32<0xB1>(v);      // quad_perm [1,0,3,2]
+    v += dpp_f32<0x4E>(v);      // quad_perm [2,3,0,1]
+    v += dpp_f32<0x141>(v);     // row_half_mirror
+    v += dpp_f32<0x140>(v);     // row_mirror
+    return (lane_f32(v, 0) + lane_f32(v, 16)) + (lane_f32(v, 32) + lane_f32(v, 48));
 }
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-    return v;
+    v = fmaxf(v, dpp_f32<0xB1>(v));
+    v = fmaxf(v, dpp_f32<0x4E>(v));
+    v = fmaxf(v, dpp_f32<0x141>(v));
+    v = fmaxf(v, dpp_f32<0x140>(v));
+    return fmaxf(fmaxf(lane_f32(v, 0), lane_f32(v, 16)), fmaxf(lane_f32(v, 32), lane_f32(v, 48)));
 }
 
 // Global memory answers in roughly half a microsecond, so short kernels are
@@ -138,8 +153,8 @@ __device__ __forceinline__ void copy_to_lds(float *dst, const float *__restrict_
 //   h [B][F]; Wp [A][F], bp [A], Wv [F], bv [1].  zv [B][A+1] is written when
 //   not null (training keeps it); logits / values / probs / actions are the
 //   caller's optional outputs.
-// Dynamic LDS: (4 + A + 1) * F floats: the 4 rows of h, then both weight
-// matrices.  Global memory answers in about a microsecond, so every load a
+// Dynamic LDS: 4*F + (A+1)*(F+1) + 12*(A+1) floats: the 4 rows of h, both
+// weight matrices, the partial dot products.  Global memory answers in about a microsecond, so every load a
 // thread needs is issued before the first one is used: the head weights go to
 // LDS in one sweep and the partial sums are read 16 at a time.
 __global__ __launch_bounds__(256) void heads_fwd_kernel(const float *__restrict__ ws, int nz,
@@ -149,86 +164,111 @@ __global__ __launch_bounds__(256) void heads_fwd_kernel(const float *__restrict_
                                                         const float *__restrict__ bv, float *zv, float *logits,
                                                         float *values, float *probs, const float *uniforms,
                                                         int32_t *actions) {
-    extern __shared__ float hs[];      // [4][F] then [A+1][F]
-    float *wsh = hs + 4 * F;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    extern __shared__ float hs[];      // [4][F], weights, partial dots
+    float *wsh = hs + 4 * F;           // [A+1][F+1]: odd pitch, so that rows fall into different banks
+    const int tid = threadIdx.x;
     const int b0 = blockIdx.x * 4;
     const int nf = min(4, B - b0);
-    copy_to_lds<8>(wsh, Wp, A * F, tid, 256);
-    copy_to_lds<2>(wsh + A * F, Wv, F, tid, 256);
-    for (int o = tid; o < F; o += 256) {
-        if (ws) {
-            const float bias = fcb[o];
-            const size_t stride = (size_t)B * F;
-            const float *src = ws + (size_t)b0 * F + o;
-            float acc4[4] = {0.f, 0.f, 0.f, 0.f};
-            for (int z = 0; z < nz; z += 4) {
-                float v[4][4];
+    // Everything this thread needs from global memory is requested before any
+    // of it is used: up to 24 head weights and 4 x 16 partial sums at a time.
+    const int nw = (A + 1) * F;                 // Wp [A][F] and Wv [F] are adjacent in LDS, not in global memory
+    for (int e0 = 0; e0 < nw || e0 == 0; e0 += 24 * 256) {
+        float wv[24];
 #pragma unroll
-                for (int fb = 0; fb < 4; ++fb)
+        for (int j = 0; j < 24; ++j) {
+            const int e = min(e0 + j * 256 + tid, nw - 1);
+            wv[j] = e < A * F ? Wp[e] : Wv[e - A * F];
+        }
+        if (e0 == 0) {
+            for (int o = tid; o < F; o += 256) {
+                if (ws) {
+                    const float bias = fcb[o];
+                    const size_t stride = (size_t)B * F;
+                    const float *src = ws + (size_t)b0 * F + o;
+                    float acc4[4] = {0.f, 0.f, 0.f, 0.f};
+                    for (int z = 0; z < nz; z += 16) {
+                        float v[4][16];
 #pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        v[fb][i] = src[min(z + i, nz - 1) * stride + (size_t)min(fb, nf - 1) * F];
+                        for (int fb = 0; fb < 4; ++fb)
 #pragma unroll
-                for (int fb = 0; fb < 4; ++fb)
+                            for (int i = 0; i < 16; ++i)
+                                v[fb][i] = src[min(z + i, nz - 1) * stride + (size_t)min(fb, nf - 1) * F];
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) acc4[fb] += (z + i < nz) ? v[fb][i] : 0.f;
-            }
+                        for (int fb = 0; fb < 4; ++fb)
 #pragma unroll
-            for (int fb = 0; fb < 4; ++fb)
-                if (fb < nf) {
-                    float v = acc4[fb] + bias;
-                    v = v > 0.f ? v : 0.f;
-                    h[(size_t)(b0 + fb) * F + o] = v;
-                    hs[fb * F + o] = v;
+                            for (int i = 0; i < 16; ++i) acc4[fb] += (z + i < nz) ? v[fb][i] : 0.f;
+                    }
+#pragma unroll
+                    for (int fb = 0; fb < 4; ++fb)
+                        if (fb < nf) {
+                            float v = acc4[fb] + bias;
+                            v = v > 0.f ? v : 0.f;
+                            h[(size_t)(b0 + fb) * F + o] = v;
+                            hs[fb * F + o] = v;
+                        }
+                } else {
+                    float v[4];
+#pragma unroll
+                    for (int fb = 0; fb < 4; ++fb) v[fb] = h[(size_t)(b0 + min(fb, nf - 1)) * F + o];
+#pragma unroll
+                    for (int fb = 0; fb < 4; ++fb)
+                        if (fb < nf) hs[fb * F + o] = v[fb];
                 }
-        } else {
-            float v[4];
+            }
+        }
 #pragma unroll
-            for (int fb = 0; fb < 4; ++fb) v[fb] = h[(size_t)(b0 + min(fb, nf - 1)) * F + o];
-#pragma unroll
-            for (int fb = 0; fb < 4; ++fb)
-                if (fb < nf) hs[fb * F + o] = v[fb];
+        for (int j = 0; j < 24; ++j) {
+            const int e = e0 + j * 256 + tid;
+            if (e < nw) wsh[e + e / F] = wv[j];
         }
     }
     __syncthreads();
-    const int b = b0 + wave;
-    if (b >= B) return;
-    const float *hb = hs + wave * F;
-    // lane j ends up with output j (j < A: logit j, j == A: value)
-    float mine = 0.f;
-    for (int a0 = 0; a0 <= A; a0 += 4) {
-        float s[4] = {0.f, 0.f, 0.f, 0.f};
-        for (int k = lane; k < F; k += 64) {
-            const float x = hb[k];
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                if (a0 + i <= A) s[i] += x * wsh[(a0 + i) * F + k];
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const float t = wave_sum(s[i]);
-            const int a = a0 + i;
-            if (lane == a) mine = t + (a < A ? bp[a] : bv[0]);
-        }
+    // Dot products from LDS without cross-lane traffic: thread (frame, output,
+    // third of k) adds its share, three shares make one output.
+    float *zs = wsh + (A + 1) * (F + 1);             // [4][A+1][3] partial dots, then [4][A+1] results
+    const int nout = nf * (A + 1);
+    if (tid < 3 * nout) {
+        const int kp = tid / nout, r = tid % nout;
+        const int fb = r / (A + 1), a = r % (A + 1);
+        const int klo = (F * kp) / 3, khi = (F * (kp + 1)) / 3;
+        const float *hb = hs + fb * F, *wr = wsh + a * (F + 1);
+        float s0 = 0.f, s1 = 0.f;
+        int k = klo;
+        for (; k + 1 < khi; k += 2) { s0 += hb[k] * wr[k]; s1 += hb[k + 1] * wr[k + 1]; }
+        if (k < khi) s0 += hb[k] * wr[k];
+        zs[(fb * (A + 1) + a) * 3 + kp] = s0 + s1;
     }
-    if (lane <= A && zv) zv[(size_t)b * (A + 1) + lane] = mine;
-    if (lane < A && logits) logits[(size_t)b * A + lane] = mine;
-    if (lane == A && values) values[b] = mine;
+    __syncthreads();
+    float z = 0.f;
+    if (tid < nout) {
+        const int fb = tid / (A + 1), a = tid % (A + 1);
+        z = (zs[tid * 3] + zs[tid * 3 + 1]) + zs[tid * 3 + 2] + (a < A ? bp[a] : bv[0]);
+        const int b = b0 + fb;
+        if (zv) zv[(size_t)b * (A + 1) + a] = z;
+        if (a < A && logits) logits[(size_t)b * A + a] = z;
+        if (a == A && values) values[b] = z;
+    }
     if (!probs && !actions) return;
-    const float zmax = wave_max(lane < A ? mine : -INFINITY);
-    const float e = lane < A ? expf(mine - zmax) : 0.f;
-    const float p = e / wave_sum(e);
-    if (lane < A && probs) probs[(size_t)b * A + lane] = p;
-    if (actions) {
-        const float u = uniforms[b];
+    __syncthreads();                                  // all partials are consumed
+    if (tid < nout) zs[tid] = z;
+    __syncthreads();
+    if (tid < nf) {                                   // one thread per frame: softmax and the draw
+        const int b = b0 + tid;
+        float *zr = zs + tid * (A + 1);
+        float zmax = zr[0];
+        for (int j = 1; j < A; ++j) zmax = fmaxf(zmax, zr[j]);
+        float S = 0.f;
+        for (int j = 0; j < A; ++j) { const float e = expf(zr[j] - zmax); zr[j] = e; S += e; }
+        const float u = actions ? uniforms[b] : 0.f;
         float c = 0.f;
-        int act = A - 1;
-        for (int j = 0; j < A; ++j) {           // left-to-right fp32 running sum
-            c += __shfl(p, j, 64);
-            if (c > u) { act = j; break; }      // every lane sees the same c
+        int act = -1;
+        for (int j = 0; j < A; ++j) {                 // left-to-right fp32 running sum
+            const float p = zr[j] / S;
+            if (probs) probs[(size_t)b * A + j] = p;
+            c += p;
+            if (act < 0 && c > u) act = j;
         }
-        if (lane == 0) actions[b] = act;
+        if (actions) actions[b] = act < 0 ? A - 1 : act;
     }
 }
 
@@ -655,7 +695,7 @@ int forward(ga3c_ctx *c, Work &w, const uint8_t *frames, int B, bool keep_zv, fl
         }
     }
     STAGE("heads_fwd", 2.0 * B * c->F * (c->A + 1), 4.0 * (fc_nz + 1) * B * c->F);
-    hipLaunchKernelGGL(heads_fwd_kernel, dim3(cdiv(B, 4)), dim3(256), sizeof(float) * (4 + c->A + 1) * c->F, s, fc_ws, fc_nz,
+    hipLaunchKernelGGL(heads_fwd_kernel, dim3(cdiv(B, 4)), dim3(256), sizeof(float) * (4 * c->F + (c->A + 1) * (c->F + 13)), s, fc_ws, fc_nz,
                        c->theta + c->off[nb + 1], w.h, B, c->F, c->A, c->theta + c->off[nb + 2],
                        c->theta + c->off[nb + 3], c->theta + c->off[nb + 4], c->theta + c->off[nb + 5],
                        keep_zv ? w.zv : nullptr, logits, values, probs, uniforms, actions);
