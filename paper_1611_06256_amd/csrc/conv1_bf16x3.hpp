@@ -1,0 +1,170 @@
+// First convolution layer (8x8 filters, stride 4, on 4x84x84 byte frames;
+// paper Sec. 3.2) on the bf16 matrix cores without losing fp32 accuracy.
+//
+// A byte 0..255 has at most 8 significant bits, which is exactly what a bf16
+// holds, so the frame converts to bf16 without rounding.  An fp32 number is the
+// exact sum of three bf16 numbers (hi + mid + lo, 8 bits each).  The product of
+// a byte and a bf16 term has 16 bits and is exact in the fp32 accumulator.  So
+//   sum_k W[k] x[k] = sum_k (hi[k] + mid[k] + lo[k]) x[k]
+// evaluated with three v_mfma_f32_16x16x32_bf16 per 32 taps rounds only where
+// the fp32 MFMA path rounds too (in the accumulation), at 5x its rate.  The
+// layer then runs at the speed of fetching frames and storing activations.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "conv_frame.hpp"
+
+namespace ga3c {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+union Bf16x8Bits {
+    bf16x8 v;
+    u32x4 u;
+};
+
+// hi/mid/lo with f == hi + mid + lo exactly (round-to-nearest-even casts).
+__device__ __forceinline__ void split3(float f, __bf16 &hi, __bf16 &mid, __bf16 &lo) {
+    hi = (__bf16)f;
+    const float r1 = f - (float)hi;
+    mid = (__bf16)r1;
+    lo = (__bf16)(r1 - (float)mid);
+}
+
+// 16 bytes -> 16 bf16 (two 16-byte vectors)
+__device__ __forceinline__ void bytes_to_bf16(const u32x4 b, u32x4 &lo8, u32x4 &hi8) {
+    Bf16x8Bits o[2];
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        const uint32_t v = b[d];
+        o[d / 2].v[(d % 2) * 4 + 0] = (__bf16)(float)(v & 0xff);
+        o[d / 2].v[(d % 2) * 4 + 1] = (__bf16)(float)((v >> 8) & 0xff);
+        o[d / 2].v[(d % 2) * 4 + 2] = (__bf16)(float)((v >> 16) & 0xff);
+        o[d / 2].v[(d % 2) * 4 + 3] = (__bf16)(float)(v >> 24);
+    }
+    lo8 = o[0].u;
+    hi8 = o[1].u;
+}
+
+// y[b][oc][pix] = max(0, scale * sum_k W[oc][k] x[b][tap k at pix] + bias[oc]),  OC = 16 or 32.
+// Block = 4 wavefronts, frames blockIdx.x, blockIdx.x + gridDim.x, ...  The
+// frame sits in LDS as bf16 [4][84][84]; a lane (pixel p, group g) reads the 8
+// taps of filter row u = 4*(kb%2) + g of channel kb/2 in one go, which is the
+// k = 8g..8g+7 share of a 16x16x32 MFMA.  The split filters stay in registers.
+template <int OC>
+__global__ __launch_bounds__(256, 2) void conv1_bf16x3_fwd_kernel(const uint8_t *__restrict__ x,
+                                                                  const float *__restrict__ w,
+                                                                  const float *__restrict__ bias, float *__restrict__ y,
+                                                                  int nframes, float scale) {
+    constexpr int C = 4, H = 84, W = 84, S = 4, OW = 20, NPIX = 400, K = 256, CHW = C * H * W;
+    constexpr int NV = CHW / 16, VPT = (NV + 255) / 256;           // 16-byte vectors of the byte frame
+    constexpr int OT = OC / 16, JOBS = 25 * OT, TPW = (JOBS + 3) / 4;
+    constexpr int FULL = JOBS % 4 == 0 ? TPW : TPW - 1, NLAST = JOBS - 4 * FULL;
+    static_assert(OC == 16 || OC == 32, "16 or 32 filters");
+    __shared__ __attribute__((aligned(16))) __bf16 xs[VPT * 256 * 16];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    // the wave that gets the odd tile rotates with the block, so that two
+    // blocks sharing a compute unit do not load the same SIMD
+    const int wave = __builtin_amdgcn_readfirstlane(((tid >> 6) + (OT == 1 ? blockIdx.x : 2 * (blockIdx.x & 1))) & 3);
+    const int l16 = lane & 15, g = lane >> 4;
+    const int ot = wave % OT;
+
+    // my filter (row l16 of tile ot), split into three bf16 terms, 8 taps per 32-tap block
+    bf16x8 wq[3][8];
+#pragma unroll
+    for (int kb = 0; kb < 8; ++kb) {
+        const float *src = w + (size_t)(ot * 16 + l16) * K + (kb / 2) * 64 + (4 * (kb % 2) + g) * 8;
+        const float4 a = *(const float4 *)src, b = *(const float4 *)(src + 4);
+        const float f[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            __bf16 h, m, l;
+            split3(f[e], h, m, l);
+            wq[0][kb][e] = h; wq[1][kb][e] = m; wq[2][kb][e] = l;
+        }
+    }
+    float bv[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) bv[r] = bias[ot * 16 + 4 * g + r];
+
+    int pixbase[TPW], pixidx[TPW];
+#pragma unroll
+    for (int i = 0; i < TPW; ++i) {
+        const int job = wave + 4 * i;
+        int p = (job / OT) * 16 + l16;
+        pixidx[i] = (job < JOBS && p < NPIX) ? p : -1;
+        if (p >= NPIX) p = 0;
+        pixbase[i] = (p / OW) * S * W + (p % OW) * S + g * W;     // + row g of the 4 rows of a tap block
+    }
+    int vidx[VPT];
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) vidx[i] = min(tid + 256 * i, NV - 1);
+
+    u32x4 pre[VPT];
+    int f = blockIdx.x;
+    {
+        const u32x4 *src = (const u32x4 *)(x + (size_t)min(f, nframes - 1) * CHW);
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) pre[i] = src[vidx[i]];
+    }
+    for (; f < nframes; f += gridDim.x) {
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) {
+            u32x4 a, b;
+            bytes_to_bf16(pre[i], a, b);
+            u32x4 *dst = (u32x4 *)(xs + (size_t)(tid + 256 * i) * 16);
+            dst[0] = a; dst[1] = b;
+        }
+        __syncthreads();
+        {
+            const u32x4 *src = (const u32x4 *)(x + (size_t)min(f + (int)gridDim.x, nframes - 1) * CHW);
+#pragma unroll
+            for (int i = 0; i < VPT; ++i) pre[i] = src[vidx[i]];
+        }
+        floatx4 acc[TPW];
+#pragma unroll
+        for (int i = 0; i < TPW; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+        auto tile_step = [&](int i, int kb) {
+            const __bf16 *src = xs + pixbase[i] + (kb / 2) * (H * W) + 4 * (kb % 2) * W;   // 8-byte aligned
+            const uint2 lo = *(const uint2 *)src, hi = *(const uint2 *)(src + 4);
+            Bf16x8Bits xv;
+            xv.u = u32x4{lo.x, lo.y, hi.x, hi.y};
+            acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wq[2][kb], xv.v, acc[i], 0, 0, 0);
+            acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wq[1][kb], xv.v, acc[i], 0, 0, 0);
+            acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wq[0][kb], xv.v, acc[i], 0, 0, 0);
+        };
+#pragma unroll
+        for (int kb = 0; kb < 8; ++kb)
+#pragma unroll
+            for (int i = 0; i < FULL; ++i) tile_step(i, kb);
+        if (NLAST > 0 && wave < NLAST) {
+#pragma unroll
+            for (int kb = 0; kb < 8; ++kb) tile_step(TPW - 1, kb);
+        }
+        float *yb = y + (size_t)f * OC * NPIX;
+#pragma unroll
+        for (int i = 0; i < TPW; ++i) {
+            if (pixidx[i] >= 0) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float v = acc[i][r] * scale + bv[r];
+                    yb[(ot * 16 + 4 * g + r) * NPIX + pixidx[i]] = v > 0.f ? v : 0.f;
+                }
+            }
+        }
+    }
+}
+
+template <int OC>
+inline hipError_t launch_conv1_bf16x3_fwd(const uint8_t *x, const float *w, const float *bias, float *y, int nframes,
+                                          float scale, hipStream_t s) {
+    if (nframes <= 0) return hipSuccess;
+    const int grid = nframes < 512 ? nframes : 512;
+    hipLaunchKernelGGL((conv1_bf16x3_fwd_kernel<OC>), dim3(grid), dim3(256), 0, s, x, w, bias, y, nframes, scale);
+    return hipGetLastError();
+}
+
+}  // namespace ga3c

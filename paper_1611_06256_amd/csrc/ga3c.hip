@@ -16,6 +16,7 @@
 #include "problems.hpp"
 #include "conv_frame.hpp"
 #include "dense_gemm.hpp"
+#include "conv1_bf16x3.hpp"
 
 using namespace ga3c;
 
@@ -640,11 +641,11 @@ int forward(ga3c_ctx *c, Work &w, const uint8_t *frames, int B, bool keep_zv, fl
         const void *xin = l == 0 ? (const void *)frames : (const void *)w.act[l - 1];
         if (c->fast && is_aligned16(wl) && is_aligned16(xin)) {
             if (spec_matches<SpecS1>(g, l == 0)) {
-                HIP_TRY(launch_conv_fwd_frame<SpecS1>((const uint8_t *)xin, wl, bl, w.act[l], B, 1.f / 255.f, s));
+                HIP_TRY(launch_conv1_bf16x3_fwd<16>((const uint8_t *)xin, wl, bl, w.act[l], B, 1.f / 255.f, s));
                 continue;
             }
             if (spec_matches<SpecL1>(g, l == 0)) {
-                HIP_TRY(launch_conv_fwd_frame<SpecL1>((const uint8_t *)xin, wl, bl, w.act[l], B, 1.f / 255.f, s));
+                HIP_TRY(launch_conv1_bf16x3_fwd<32>((const uint8_t *)xin, wl, bl, w.act[l], B, 1.f / 255.f, s));
                 continue;
             }
             if (spec_matches<SpecS2>(g, l == 0)) {
