@@ -24,6 +24,12 @@ union Bf16x8Bits {
     u32x4 u;
 };
 
+// Sum step inside a row of 16 lanes (DPP control CTRL).
+template <int CTRL>
+__device__ __forceinline__ float dpp_row_f32(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+
 // hi/mid/lo with f == hi + mid + lo exactly (round-to-nearest-even casts).
 __device__ __forceinline__ void split3(float f, __bf16 &hi, __bf16 &mid, __bf16 &lo) {
     hi = (__bf16)f;
@@ -164,6 +170,164 @@ inline hipError_t launch_conv1_bf16x3_fwd(const uint8_t *x, const float *w, cons
     if (nframes <= 0) return hipSuccess;
     const int grid = nframes < 512 ? nframes : 512;
     hipLaunchKernelGGL((conv1_bf16x3_fwd_kernel<OC>), dim3(grid), dim3(256), 0, s, x, w, bias, y, nframes, scale);
+    return hipGetLastError();
+}
+
+
+// Weight and bias gradient of the same layer, same arithmetic: the frame is
+// exact in bf16 and dY is split into three bf16 terms.
+//   dW[oc][c][u][v] = sum_{i,j} dY[oc][i][j] x[c][4i+u][4j+v],   db[oc] = sum dY[oc][i][j]
+// The contraction runs over output pixels, 8 consecutive pixels of a row per
+// lane, so the frame is re-laid in LDS "space to depth": with u = 4a + u',
+// v = 4b + v' the pixel x[c][4i+u][4j+v] is X[(c,u',v')][i+a][j+b], and 8
+// consecutive j are 8 consecutive elements of a row of plane (c,u',v').  Plane
+// index q = (c,u',v') is the column of the MFMA tile (wave w owns channel w and
+// its 16 planes), the filters are the rows, and the four (a,b) are four
+// accumulators.  Shift b = 1 is made from the b = 0 vector and one more dword.
+// Rows of 20 pixels are padded to 24 = 3 blocks of 8 with zero dY.
+// part: [gridDim.x][16][257]; the last column is the bias gradient.
+__global__ __launch_bounds__(256) void conv1_bf16x3_wgrad_kernel(const uint8_t *__restrict__ x,
+                                                                 const float *__restrict__ dy,
+                                                                 float *__restrict__ part, int nframes, float scale) {
+    constexpr int C = 4, H = 84, W = 84, OC = 16, OH = 20, NPIX = 400, K = 256, CHW = C * H * W;
+    constexpr int XROW = 32, XPLANE = 21 * XROW + 8;       // bf16 elements; plane pitch 20 mod 32 dwords
+    constexpr int DROW = 24, DOC = OH * DROW + 8;          // dY rows padded to 24, filter pitch 20 mod 32 dwords
+    constexpr int NITEM = 336 * 6, IPT = (NITEM + 255) / 256;    // (frame row, group of 4 dwords)
+    constexpr int NDV = OC * NPIX / 4, DPT = (NDV + 255) / 256;  // float4 of dY per frame
+    constexpr int NSTEP = OH * 3 / 4;                      // 60 blocks of 8 pixels, 4 per MFMA
+    __shared__ __attribute__((aligned(16))) __bf16 xp[64 * XPLANE];
+    __shared__ __attribute__((aligned(16))) __bf16 dp[3 * OC * DOC];
+    __shared__ float bsh[NDV];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l16 = lane & 15, g = lane >> 4;
+
+    for (int e = tid; e < 64 * XPLANE / 2; e += 256) ((uint32_t *)xp)[e] = 0u;     // padding stays zero
+    for (int e = tid; e < 3 * OC * DOC / 2; e += 256) ((uint32_t *)dp)[e] = 0u;
+
+    // staging descriptors: where my dwords come from and where they go
+    int xsrc[IPT], xdst[IPT], xcnt[IPT];
+#pragma unroll
+    for (int i = 0; i < IPT; ++i) {
+        const int it = min(tid + 256 * i, NITEM - 1);
+        const int row = it / 6, gq = it % 6;               // row = c*84 + r
+        const int c = row / H, r = row % H;
+        xsrc[i] = row * (W / 4) + 4 * gq;                  // dword index in the frame
+        xcnt[i] = (tid + 256 * i < NITEM) ? (gq == 5 ? 1 : 4) : 0;
+        xdst[i] = ((c * 4 + r % 4) * 4) * XPLANE + (r / 4) * XROW + 4 * gq;   // plane (c, u'=r%4, v'=0)
+    }
+    int dsrc[DPT], ddst[DPT];
+#pragma unroll
+    for (int i = 0; i < DPT; ++i) {
+        const int e = min(tid + 256 * i, NDV - 1);
+        dsrc[i] = e;
+        const int oc = e / (NPIX / 4), pq = e % (NPIX / 4);           // 5 float4 per row of 20
+        ddst[i] = oc * DOC + (pq / 5) * DROW + 4 * (pq % 5);
+    }
+
+    floatx4 acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) acc[a][b] = floatx4{0.f, 0.f, 0.f, 0.f};
+    float bsum = 0.f;
+
+    uint32_t xpre[IPT][4];
+    float4 dpre[DPT];
+    auto fetch = [&](int ff) {
+        const uint32_t *xs = (const uint32_t *)(x + (size_t)ff * CHW);
+#pragma unroll
+        for (int i = 0; i < IPT; ++i)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) xpre[i][t] = xs[min(xsrc[i] + t, CHW / 4 - 1)];
+        const float4 *ds = (const float4 *)(dy + (size_t)ff * OC * NPIX);
+#pragma unroll
+        for (int i = 0; i < DPT; ++i) dpre[i] = ds[dsrc[i]];
+    };
+    int f = blockIdx.x;
+    fetch(min(f, nframes - 1));
+    const __bf16 *xq = xp + (wave * 16 + l16) * XPLANE;              // my plane
+    for (; f < nframes; f += gridDim.x) {
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < IPT; ++i) {
+            if (xcnt[i] > 0) {
+#pragma unroll
+                for (int vq = 0; vq < 4; ++vq) {             // plane v' = vq gets byte vq of each dword
+                    union { __bf16 h[4]; uint2 u; } o;
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+                        o.h[t] = (__bf16)(float)((t < xcnt[i] ? xpre[i][t] >> (8 * vq) : 0u) & 0xff);
+                    *(uint2 *)(xp + xdst[i] + vq * XPLANE) = o.u;
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < DPT; ++i) {
+            if (tid + 256 * i < NDV) {
+                const float v[4] = {dpre[i].x, dpre[i].y, dpre[i].z, dpre[i].w};
+                union { __bf16 h[4]; uint2 u; } o[3];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) split3(v[t], o[0].h[t], o[1].h[t], o[2].h[t]);
+#pragma unroll
+                for (int term = 0; term < 3; ++term) *(uint2 *)(dp + term * OC * DOC + ddst[i]) = o[term].u;
+                bsh[tid + 256 * i] = (v[0] + v[1]) + (v[2] + v[3]);
+            }
+        }
+        __syncthreads();
+        fetch(min(f + (int)gridDim.x, nframes - 1));
+        {   // bias: 16 lanes share a filter, 100 partial sums each
+            const int oc = tid / 16, pt = tid % 16;
+            float sum = 0.f;
+            for (int m = pt; m < NPIX / 4; m += 16) sum += bsh[oc * (NPIX / 4) + m];
+            sum += dpp_row_f32<0xB1>(sum); sum += dpp_row_f32<0x4E>(sum);
+            sum += dpp_row_f32<0x141>(sum); sum += dpp_row_f32<0x140>(sum);
+            bsum += sum;
+        }
+#pragma unroll
+        for (int st = 0; st < NSTEP; ++st) {
+            const int blk = 4 * st + g, i = blk / 3, jb = blk % 3;
+            Bf16x8Bits d[3];
+#pragma unroll
+            for (int term = 0; term < 3; ++term)
+                d[term].u = *(const u32x4 *)(dp + term * OC * DOC + l16 * DOC + i * DROW + 8 * jb);
+#pragma unroll
+            for (int a = 0; a < 2; ++a) {
+                const __bf16 *src = xq + (i + a) * XROW + 8 * jb;
+                const u32x4 c0 = *(const u32x4 *)src;
+                const uint32_t c4 = *(const uint32_t *)(src + 8);
+                Bf16x8Bits x0, x1;
+                x0.u = c0;
+                x1.u = u32x4{__builtin_amdgcn_alignbit(c0[1], c0[0], 16), __builtin_amdgcn_alignbit(c0[2], c0[1], 16),
+                             __builtin_amdgcn_alignbit(c0[3], c0[2], 16), __builtin_amdgcn_alignbit(c4, c0[3], 16)};
+#pragma unroll
+                for (int term = 2; term >= 0; --term) {
+                    acc[a][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(d[term].v, x0.v, acc[a][0], 0, 0, 0);
+                    acc[a][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(d[term].v, x1.v, acc[a][1], 0, 0, 0);
+                }
+            }
+        }
+    }
+    // lane (l16, g), register r of acc[a][b]: filter 4g + r, tap (c = wave, u = 4a + l16/4, v = 4b + l16%4)
+    float *pb = part + (size_t)blockIdx.x * OC * (K + 1);
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                pb[(4 * g + r) * (K + 1) + wave * 64 + (4 * a + l16 / 4) * 8 + 4 * b + l16 % 4] = acc[a][b][r] * scale;
+    if (tid % 16 == 0) pb[(tid / 16) * (K + 1) + K] = bsum;
+}
+
+inline int conv1_bf16x3_wgrad_blocks(int nframes) { return nframes < 256 ? nframes : 256; }
+
+inline hipError_t launch_conv1_bf16x3_wgrad(const uint8_t *x, const float *dy, float *part, int nframes, float scale,
+                                            hipStream_t s) {
+    if (nframes <= 0) return hipSuccess;
+    hipLaunchKernelGGL(conv1_bf16x3_wgrad_kernel, dim3(conv1_bf16x3_wgrad_blocks(nframes)), dim3(256), 0, s, x, dy, part,
+                       nframes, scale);
     return hipGetLastError();
 }
 

@@ -1054,9 +1054,9 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
             bool done = false;
             if (c->fast && is_aligned16(xin)) {
                 STAGE(CONV_WGRAD[l], 2.0 * B * g.OHW * g.OC * g.K, 0);
-                if (spec_matches<SpecS1>(g, l == 0)) {
-                    nz = conv_wgrad_frame_blocks<SpecS1>(B);
-                    HIP_TRY(launch_conv_wgrad_frame<SpecS1>((const uint8_t *)xin, c->dact[l], w.ws, B, 1.f / 255.f, s));
+                if (spec_matches<SpecS1>(g, l == 0) && is_aligned16(c->dact[l])) {
+                    nz = conv1_bf16x3_wgrad_blocks(B);
+                    HIP_TRY(launch_conv1_bf16x3_wgrad((const uint8_t *)xin, c->dact[l], w.ws, B, 1.f / 255.f, s));
                     done = true;
                 } else if (spec_matches<SpecL1>(g, l == 0)) {
                     nz = conv_wgrad_frame_blocks<SpecL1>(B);
