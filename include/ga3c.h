@@ -15,10 +15,14 @@
  *     caller's pointer beyond the kernels it enqueues in that call.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
  *     Calls only enqueue work on it and never synchronise the host; outputs
- *     are valid once the caller has synchronised the stream.  Calls on one
- *     context must be stream-ordered with respect to each other (they share
- *     the context's workspaces and parameters); ordering across two streams
- *     is the caller's job (events).
+ *     are valid once the caller has synchronised the stream.  ga3c_predict
+ *     calls must be stream-ordered among themselves, and so must
+ *     ga3c_train_step calls (each kind owns one set of workspaces), but the
+ *     two kinds may run on two different streams: the context keeps two
+ *     copies of the parameters, an update writes the copy that is not being
+ *     read and publishes it, and HIP events order that against the
+ *     predictions (a prediction sees the parameters of the last update that
+ *     was ENQUEUED before it, never a half-written set).
  *   - Return value: GA3C_OK or a negative GA3C_E* code.  Nothing is printed,
  *     no C++ exception crosses the boundary.  ga3c_last_error() returns a
  *     thread-local description of the last failure on the calling thread.
@@ -184,6 +188,91 @@ int ga3c_use_generic_kernels(ga3c_ctx *ctx, int on);
  * the layer's definition; 20 bytes per parameter for RMSProp), not counters. */
 int ga3c_profile_enable(ga3c_ctx *ctx, int on);
 int ga3c_profile_read(ga3c_ctx *ctx, char *buf, size_t cap);
+
+/* ---- queue-driven batching on one GPU (Sec. 4.1 and 4.3) -------------------
+ *
+ * The paper's predictors drain "as many prediction requests as are
+ * immediately available" into one inference call, its trainers merge the
+ * agents' experience batches into one update (at least a minimum number of
+ * frames, Sec. 5.3), and every period one of the system's knobs is changed at
+ * random by one step and the change kept if trainings per second did not drop
+ * (Sec. 4.3).  Here the knobs are the two batch caps; the two kinds of call
+ * run on two HIP streams of default priority that the scheduler owns.
+ *
+ * One host thread drives a scheduler: submit, tick and poll are not
+ * thread-safe against each other.  Frames are DEVICE memory owned by the
+ * caller, 16-byte aligned, and must stay unchanged until the tick that
+ * consumed them has finished on the GPU (ga3c_sched_drain, or the
+ * prediction's result has been polled).  Trajectories have exactly t_max
+ * steps; actions / rewards / dones are HOST arrays of t_max entries that are
+ * copied at submit time. */
+typedef struct ga3c_sched ga3c_sched;
+typedef struct ga3c_tuner ga3c_tuner;
+
+typedef struct {
+    int t_max;                              /* steps per trajectory (the paper's t_max = 5) */
+    int predict_cap;                        /* frames per prediction batch, 1 .. max_predict_batch */
+    int train_min;                          /* an update waits until this many frames are queued */
+    int train_cap;                          /* frames per update, t_max .. max_train_frames */
+    int adjust_period;                      /* ticks per adjustment window; 0 = caps stay fixed */
+    int predict_cap_lo, predict_cap_hi;     /* bounds for the adjustment (cap moves by factors of 2) */
+    int train_cap_lo, train_cap_hi, train_cap_step;   /* bounds and step (frames) for the adjustment */
+    uint64_t seed;                          /* of the adjustment's random choices */
+    ga3c_hparams hp;                        /* used for every update */
+} ga3c_sched_config;
+
+typedef struct { int32_t agent; int32_t action; float value; } ga3c_prediction;
+
+typedef struct {
+    int64_t ticks, predictions, predict_batches, trained_frames, train_batches;
+    int64_t sum_predict_queue, sum_train_queue;   /* queue lengths (requests / trajectories) summed over ticks */
+    int64_t predict_queue, train_queue;           /* now */
+    int64_t trials_accepted, trials_rejected;
+    int32_t predict_cap, train_cap;               /* now */
+    double last_window_frames_per_s;
+} ga3c_sched_stats;
+
+int ga3c_sched_create(ga3c_ctx *ctx, const ga3c_sched_config *cfg, ga3c_sched **out);
+/* Waits for the scheduler's streams, frees its buffers; the context stays. */
+int ga3c_sched_destroy(ga3c_sched *s);
+/* Agent `agent` asks for an action for the state in frame_dev (u8 [C][H][W]);
+ * uniform in [0,1) drives the draw. */
+int ga3c_sched_submit_predict(ga3c_sched *s, int agent, const uint8_t *frame_dev, float uniform);
+/* Agent `agent` hands in t_max experiences: frames_dev u8 [t_max][C][H][W]
+ * (device), actions / rewards / dones (host), and the value of the state
+ * after the last step. */
+int ga3c_sched_submit_trajectory(ga3c_sched *s, int agent, const uint8_t *frames_dev, const int32_t *actions,
+                                 const float *rewards, const uint8_t *dones, float bootstrap);
+/* One pass of predictor and trainer: at most one prediction batch (all queued
+ * requests up to the cap) and at most one update (queued trajectories up to
+ * the cap, if at least train_min frames wait) are enqueued on the GPU.
+ * *predicted / *trained (may be NULL) receive the frames issued.  At the end of
+ * an adjustment window the call waits for the window's GPU work to read the
+ * clock. */
+int ga3c_sched_tick(ga3c_sched *s, int *predicted, int *trained);
+/* Copies up to cap finished predictions to out (host), oldest first; returns
+ * how many, or a negative error code.  Never blocks. */
+int ga3c_sched_poll(ga3c_sched *s, ga3c_prediction *out, int cap);
+/* Waits until everything issued so far has finished. */
+int ga3c_sched_drain(ga3c_sched *s);
+int ga3c_sched_get_stats(const ga3c_sched *s, ga3c_sched_stats *out);
+const char *ga3c_sched_last_error(void);
+
+/* The adjustment rule alone (host only, no GPU): caps within [lo, hi]; the
+ * prediction cap moves by a factor 2 per step, the training cap by t_step.
+ * ga3c_tuner_report closes a window that ran the current caps at the given
+ * throughput: a trial that lowered the throughput is undone, otherwise the
+ * caps are kept; then one knob is stepped in a random direction and the new
+ * caps are returned.  Deterministic for a given seed. */
+int ga3c_tuner_create(int p_lo, int p_hi, int p0, int t_lo, int t_hi, int t_step, int t0, uint64_t seed,
+                      ga3c_tuner **out);
+int ga3c_tuner_report(ga3c_tuner *t, double throughput, int *predict_cap, int *train_cap);
+int ga3c_tuner_state(const ga3c_tuner *t, int *kept_predict_cap, int *kept_train_cap, int64_t *accepted,
+                     int64_t *rejected);
+int ga3c_tuner_destroy(ga3c_tuner *t);
+
+/* Shape and capacities the context was created with (any pointer may be NULL). */
+int ga3c_get_desc(const ga3c_ctx *ctx, ga3c_net_desc *desc, int *max_predict_batch, int *max_train_frames);
 
 /* Thread-local text of the last error on this thread ("" if none). */
 const char *ga3c_last_error(void);

@@ -83,7 +83,16 @@ struct ga3c_ctx {
     int noff;
     size_t P;
     int max_pred, max_train;
-    float *theta, *g, *grad;
+    // Two copies of the parameters.  theta2[cur] is the published snapshot that
+    // predictions and the forward/backward of an update read; RMSProp writes the
+    // other copy and publishes it.  ev_ready[i]: copy i has been written;
+    // ev_readers[i]: the last prediction that read copy i has finished.
+    float *theta2[2];
+    int cur;
+    hipEvent_t ev_ready[2], ev_readers[2];
+    hipStream_t ready_stream[2], readers_stream[2];   // where each event was last recorded
+    bool ready_set[2], readers_set[2];
+    float *g, *grad;
     Work pred, train;
     // training only
     float *dact[GA3C_MAX_CONV];   // dL/d(pre-activation) of each conv output
@@ -478,9 +487,9 @@ __global__ __launch_bounds__(64) void finalize_kernel(const float *__restrict__ 
 }
 
 // Eq. 3 on a flat buffer: d = s*grad; g = alpha g + (1-alpha) d^2;
-// theta -= lr d / sqrt(g + eps).  20 bytes of traffic per parameter.
+// theta_out = theta_in - lr d / sqrt(g + eps) (the two may be the same buffer).  20 bytes of traffic per parameter.
 // s = scale_dev[0] when scale_dev is not null, else scale_host.
-__global__ __launch_bounds__(256) void rmsprop_kernel(float *__restrict__ theta, float *__restrict__ g,
+__global__ __launch_bounds__(256) void rmsprop_kernel(const float *theta_in, float *theta_out, float *__restrict__ g,
                                                       const float *__restrict__ grad, size_t n,
                                                       const float *__restrict__ scale_dev, float scale_host, float lr,
                                                       float alpha, float eps) {
@@ -488,7 +497,8 @@ __global__ __launch_bounds__(256) void rmsprop_kernel(float *__restrict__ theta,
     const float oma = 1.f - alpha;
     const size_t n4 = n / 4;
     const size_t stride = (size_t)gridDim.x * 256;
-    float4 *t4 = (float4 *)theta;
+    const float4 *t4 = (const float4 *)theta_in;
+    float4 *o4 = (float4 *)theta_out;
     float4 *g4 = (float4 *)g;
     const float4 *d4 = (const float4 *)grad;
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += stride) {
@@ -498,13 +508,13 @@ __global__ __launch_bounds__(256) void rmsprop_kernel(float *__restrict__ theta,
         gg.z = alpha * gg.z + oma * d.z * d.z; gg.w = alpha * gg.w + oma * d.w * d.w;
         t.x -= lr * d.x / sqrtf(gg.x + eps); t.y -= lr * d.y / sqrtf(gg.y + eps);
         t.z -= lr * d.z / sqrtf(gg.z + eps); t.w -= lr * d.w / sqrtf(gg.w + eps);
-        g4[i] = gg; t4[i] = t;
+        g4[i] = gg; o4[i] = t;
     }
     for (size_t i = n4 * 4 + (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
         const float d = s * grad[i];
         const float gg = alpha * g[i] + oma * d * d;
         g[i] = gg;
-        theta[i] -= lr * d / sqrtf(gg + eps);
+        theta_out[i] = theta_in[i] - lr * d / sqrtf(gg + eps);
     }
 }
 
@@ -531,6 +541,28 @@ __global__ __launch_bounds__(256) void fill_kernel(float *__restrict__ dst, size
 }
 
 // ------------------------------------------------------------ host helpers --
+
+// Event fences between the calls of a context.  A wait is skipped when the
+// event was last recorded on the same stream (stream order already holds) or
+// never recorded.
+int fence_wait(hipStream_t s, hipEvent_t ev, bool set, hipStream_t where) {
+    if (!set || where == s) return GA3C_OK;
+    HIP_TRY(hipStreamWaitEvent(s, ev, 0));
+    return GA3C_OK;
+}
+int wait_ready(ga3c_ctx *c, int i, hipStream_t s) { return fence_wait(s, c->ev_ready[i], c->ready_set[i], c->ready_stream[i]); }
+int wait_readers(ga3c_ctx *c, int i, hipStream_t s) { return fence_wait(s, c->ev_readers[i], c->readers_set[i], c->readers_stream[i]); }
+int mark_ready(ga3c_ctx *c, int i, hipStream_t s) {
+    HIP_TRY(hipEventRecord(c->ev_ready[i], s));
+    c->ready_set[i] = true; c->ready_stream[i] = s;
+    return GA3C_OK;
+}
+int mark_readers(ga3c_ctx *c, int i, hipStream_t s) {
+    HIP_TRY(hipEventRecord(c->ev_readers[i], s));
+    c->readers_set[i] = true; c->readers_stream[i] = s;
+    return GA3C_OK;
+}
+#define TRY(expr) do { int rc_ = (expr); if (rc_ != GA3C_OK) return rc_; } while (0)
 
 // Brackets the kernels launched during its lifetime with two events when
 // profiling is on; costs one branch when it is off.
@@ -631,13 +663,13 @@ inline bool spec_matches(const ConvGeom &g, bool byte_input) {
 inline bool is_aligned16(const void *p) { return (((uintptr_t)p) & 15) == 0; }
 
 // Forward pass of `B` frames into `w`; heads outputs to the optional pointers.
-int forward(ga3c_ctx *c, Work &w, const uint8_t *frames, int B, bool keep_zv, float *logits, float *values,
+int forward(ga3c_ctx *c, const float *th, Work &w, const uint8_t *frames, int B, bool keep_zv, float *logits, float *values,
             float *probs, const float *uniforms, int32_t *actions, hipStream_t s) {
     const int nb = 2 * c->nconv;
     for (int l = 0; l < c->nconv; ++l) {
         const ConvGeom &g = c->geom[l];
-        STAGE(CONV_FWD[l], 2.0 * B * g.OHW * g.OC * g.K, 0);
-        const float *wl = c->theta + c->off[2 * l], *bl = c->theta + c->off[2 * l + 1];
+        STAGE(CONV_FWD[l], 2.0 * B * g.OHW * g.OC * g.K, (double)B * ((l == 0 ? 1.0 : 4.0) * g.CHW + 4.0 * g.OC * g.OHW));
+        const float *wl = th + c->off[2 * l], *bl = th + c->off[2 * l + 1];
         const void *xin = l == 0 ? (const void *)frames : (const void *)w.act[l - 1];
         if (c->fast && is_aligned16(wl) && is_aligned16(xin)) {
             if (spec_matches<SpecS1>(g, l == 0)) {
@@ -656,13 +688,13 @@ int forward(ga3c_ctx *c, Work &w, const uint8_t *frames, int B, bool keep_zv, fl
         if (l == 0) {
             ConvFwdP<uint8_t> p;
             p.M = g.OC; p.N = B * g.OHW; p.K = g.K; p.g = g;
-            p.x = frames; p.w = c->theta + c->off[0]; p.bias = c->theta + c->off[1];
+            p.x = frames; p.w = th + c->off[0]; p.bias = th + c->off[1];
             p.y = w.act[0]; p.scale = 1.f / 255.f;
             HIP_TRY(launch_conv_like(p, 1, s));
         } else {
             ConvFwdP<float> p;
             p.M = g.OC; p.N = B * g.OHW; p.K = g.K; p.g = g;
-            p.x = w.act[l - 1]; p.w = c->theta + c->off[2 * l]; p.bias = c->theta + c->off[2 * l + 1];
+            p.x = w.act[l - 1]; p.w = th + c->off[2 * l]; p.bias = th + c->off[2 * l + 1];
             p.y = w.act[l]; p.scale = 1.f;
             HIP_TRY(launch_conv_like(p, 1, s));
         }
@@ -671,7 +703,7 @@ int forward(ga3c_ctx *c, Work &w, const uint8_t *frames, int B, bool keep_zv, fl
     int fc_nz = 1;
     {   // fully connected: h[b][o] = max(0, b[o] + sum_i x[b][i] Wfc[o][i])
         const float *x = w.act[c->nconv - 1];
-        const float *wfc = c->theta + c->off[nb];
+        const float *wfc = th + c->off[nb];
         STAGE("fc_fwd", 2.0 * B * c->F * c->flat, 0);
         int nz, kchunk;
         if (c->fast && dense_operand_ok(x, c->flat, c->flat) && dense_operand_ok(wfc, c->flat, c->flat)) {
@@ -697,8 +729,8 @@ int forward(ga3c_ctx *c, Work &w, const uint8_t *frames, int B, bool keep_zv, fl
     }
     STAGE("heads_fwd", 2.0 * B * c->F * (c->A + 1), 4.0 * (fc_nz + 1) * B * c->F);
     hipLaunchKernelGGL(heads_fwd_kernel, dim3(cdiv(B, 4)), dim3(256), sizeof(float) * (4 * c->F + (c->A + 1) * (c->F + 13)), s, fc_ws, fc_nz,
-                       c->theta + c->off[nb + 1], w.h, B, c->F, c->A, c->theta + c->off[nb + 2],
-                       c->theta + c->off[nb + 3], c->theta + c->off[nb + 4], c->theta + c->off[nb + 5],
+                       th + c->off[nb + 1], w.h, B, c->F, c->A, th + c->off[nb + 2],
+                       th + c->off[nb + 3], th + c->off[nb + 4], th + c->off[nb + 5],
                        keep_zv ? w.zv : nullptr, logits, values, probs, uniforms, actions);
     HIP_TRY(hipGetLastError());
     return GA3C_OK;
@@ -812,11 +844,18 @@ extern "C" int ga3c_create(const ga3c_net_desc *d, int max_predict_batch, int ma
         if (e != hipSuccess) { guard(fail(GA3C_EHIP, "hipMemcpy: %s", hipGetErrorString(e))); break; }
         g.koff = c->koff[l];
     }
-    if (rc == GA3C_OK) guard(dmalloc((void **)&c->theta, sizeof(float) * c->P));
+    for (int i = 0; i < 2 && rc == GA3C_OK; ++i) {
+        guard(dmalloc((void **)&c->theta2[i], sizeof(float) * c->P));
+        if (rc == GA3C_OK && hipEventCreateWithFlags(&c->ev_ready[i], hipEventDisableTiming) != hipSuccess)
+            guard(fail(GA3C_EHIP, "hipEventCreate failed"));
+        if (rc == GA3C_OK && hipEventCreateWithFlags(&c->ev_readers[i], hipEventDisableTiming) != hipSuccess)
+            guard(fail(GA3C_EHIP, "hipEventCreate failed"));
+    }
     if (rc == GA3C_OK) guard(dmalloc((void **)&c->g, sizeof(float) * c->P));
     if (rc == GA3C_OK) guard(dmalloc((void **)&c->grad, sizeof(float) * c->P));
     if (rc == GA3C_OK) {
-        hipError_t e = hipMemset(c->theta, 0, sizeof(float) * c->P);
+        hipError_t e = hipMemset(c->theta2[0], 0, sizeof(float) * c->P);
+        if (e == hipSuccess) e = hipMemset(c->theta2[1], 0, sizeof(float) * c->P);
         if (e == hipSuccess) e = hipMemset(c->g, 0, sizeof(float) * c->P);
         if (e == hipSuccess) e = hipMemset(c->grad, 0, sizeof(float) * c->P);
         if (e != hipSuccess) guard(fail(GA3C_EHIP, "hipMemset: %s", hipGetErrorString(e)));
@@ -862,7 +901,12 @@ extern "C" int ga3c_destroy(ga3c_ctx *c) {
     if (!c) return GA3C_OK;
     (void)hipDeviceSynchronize();
     for (int l = 0; l < GA3C_MAX_CONV; ++l) { (void)hipFree(c->koff[l]); (void)hipFree(c->dact[l]); }
-    (void)hipFree(c->theta); (void)hipFree(c->g); (void)hipFree(c->grad);
+    for (int i = 0; i < 2; ++i) {
+        (void)hipFree(c->theta2[i]);
+        if (c->ev_ready[i]) (void)hipEventDestroy(c->ev_ready[i]);
+        if (c->ev_readers[i]) (void)hipEventDestroy(c->ev_readers[i]);
+    }
+    (void)hipFree(c->g); (void)hipFree(c->grad);
     free_work(c->pred); free_work(c->train);
     (void)hipFree(c->dh); (void)hipFree(c->dzv); (void)hipFree(c->R);
     (void)hipFree(c->partials); (void)hipFree(c->colpart); (void)hipFree(c->scale); (void)hipFree(c->stats);
@@ -886,7 +930,11 @@ extern "C" int ga3c_params_offsets(const ga3c_ctx *c, int64_t *off, int cap) {
 extern "C" int ga3c_params_init(ga3c_ctx *c, uint64_t seed, void *stream) {
     if (!c) return fail(GA3C_EINVAL, "ga3c_params_init: null context");
     hipStream_t s = (hipStream_t)stream;
-    hipLaunchKernelGGL(fill_kernel, dim3(blocks_for(c->P)), dim3(256), 0, s, c->theta, c->P, 0.f);
+    float *theta = c->theta2[c->cur];
+    // wait for whoever wrote or still reads this copy
+    TRY(wait_ready(c, c->cur, s));
+    TRY(wait_readers(c, c->cur, s));
+    hipLaunchKernelGGL(fill_kernel, dim3(blocks_for(c->P)), dim3(256), 0, s, theta, c->P, 0.f);
     hipLaunchKernelGGL(fill_kernel, dim3(blocks_for(c->P)), dim3(256), 0, s, c->g, c->P, 0.f);
     HIP_TRY(hipGetLastError());
     const int nb = 2 * c->nconv;
@@ -898,21 +946,23 @@ extern "C" int ga3c_params_init(ga3c_ctx *c, uint64_t seed, void *stream) {
     t[nt++] = {c->off[nb + 2], (size_t)c->A * c->F, c->F};
     t[nt++] = {c->off[nb + 4], (size_t)c->F, c->F};
     for (int i = 0; i < nt; ++i) {
-        hipLaunchKernelGGL(init_normal_kernel, dim3(blocks_for(t[i].n)), dim3(256), 0, s, c->theta + t[i].off,
+        hipLaunchKernelGGL(init_normal_kernel, dim3(blocks_for(t[i].n)), dim3(256), 0, s, theta + t[i].off,
                            (size_t)t[i].off, t[i].n, sqrtf(2.f / (float)t[i].fan_in), seed);
         HIP_TRY(hipGetLastError());
     }
+    TRY(mark_ready(c, c->cur, s));
     return GA3C_OK;
 }
 
 static float *select_buffer(ga3c_ctx *c, int which) {
-    return which == 0 ? c->theta : which == 1 ? c->g : which == 2 ? c->grad : nullptr;
+    return which == 0 ? c->theta2[c->cur] : which == 1 ? c->g : which == 2 ? c->grad : nullptr;
 }
 
 extern "C" int ga3c_params_get(ga3c_ctx *c, int which, float *dst, size_t n, void *stream) {
     if (!c || !dst) return fail(GA3C_EINVAL, "ga3c_params_get: null argument");
     float *src = select_buffer(c, which);
     if (!src || n != c->P) return fail(GA3C_EINVAL, "ga3c_params_get: which must be 0..2 and n the parameter count");
+    TRY(wait_ready(c, c->cur, (hipStream_t)stream));
     HIP_TRY(hipMemcpyAsync(dst, src, sizeof(float) * n, hipMemcpyDeviceToDevice, (hipStream_t)stream));
     return GA3C_OK;
 }
@@ -921,7 +971,11 @@ extern "C" int ga3c_params_set(ga3c_ctx *c, int which, const float *src, size_t 
     if (!c || !src) return fail(GA3C_EINVAL, "ga3c_params_set: null argument");
     if ((which != 0 && which != 1) || n != c->P)
         return fail(GA3C_EINVAL, "ga3c_params_set: which must be 0 or 1 and n the parameter count");
-    HIP_TRY(hipMemcpyAsync(select_buffer(c, which), src, sizeof(float) * n, hipMemcpyDeviceToDevice, (hipStream_t)stream));
+    hipStream_t s = (hipStream_t)stream;
+    TRY(wait_ready(c, c->cur, s));
+    TRY(wait_readers(c, c->cur, s));
+    HIP_TRY(hipMemcpyAsync(select_buffer(c, which), src, sizeof(float) * n, hipMemcpyDeviceToDevice, s));
+    if (which == 0) TRY(mark_ready(c, c->cur, s));
     return GA3C_OK;
 }
 
@@ -932,7 +986,13 @@ extern "C" int ga3c_predict(ga3c_ctx *c, const uint8_t *frames, int B, const flo
     if (B == 0) return GA3C_OK;
     if (!frames) return fail(GA3C_EINVAL, "ga3c_predict: null frames");
     if (actions && !uniforms) return fail(GA3C_EINVAL, "ga3c_predict: actions requested without uniforms");
-    return forward(c, c->pred, frames, B, false, logits, values, probs, uniforms, actions, (hipStream_t)stream);
+    hipStream_t s = (hipStream_t)stream;
+    const int cur = c->cur;
+    TRY(wait_ready(c, cur, s));
+    const int rc = forward(c, c->theta2[cur], c->pred, frames, B, false, logits, values, probs, uniforms, actions, s);
+    if (rc != GA3C_OK) return rc;
+    TRY(mark_readers(c, cur, s));
+    return GA3C_OK;
 }
 
 extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t *actions, const float *rewards,
@@ -950,7 +1010,10 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
     const int nb = 2 * c->nconv, A = c->A, F = c->F;
     c->last_frames = B;
 
-    int rc = forward(c, w, frames, B, true, nullptr, nullptr, nullptr, nullptr, nullptr, s);
+    const int cur = c->cur;
+    const float *th = c->theta2[cur];
+    TRY(wait_ready(c, cur, s));
+    int rc = forward(c, th, w, frames, B, true, nullptr, nullptr, nullptr, nullptr, nullptr, s);
     if (rc != GA3C_OK) return rc;
 
     const int nloss = cdiv(B, LOSS_THREADS);
@@ -962,7 +1025,7 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
         HIP_TRY(hipGetLastError());
     }
 
-    const float *Wp = c->theta + c->off[nb + 2], *Wv = c->theta + c->off[nb + 4];
+    const float *Wp = th + c->off[nb + 2], *Wv = th + c->off[nb + 4];
     int nz, kchunk;
     {   // heads: weight and bias gradients, dgrad
         GemmP<EPI_PARTIAL, true> p;
@@ -990,7 +1053,7 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
         HIP_TRY(hipGetLastError());
     }
     const float *xfc = w.act[c->nconv - 1];
-    const float *wfc = c->theta + c->off[nb];
+    const float *wfc = th + c->off[nb];
     const bool fc_dense = c->fast && dense_operand_ok(c->dh, F, F) && dense_operand_ok(xfc, c->flat, c->flat) &&
                           dense_operand_ok(wfc, c->flat, c->flat);
     if (fc_dense) {   // fc weight gradient: D[o][i] = sum_b dh[b][o] x[b][i]; bias from the column sums of dh
@@ -1053,7 +1116,7 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
             const void *xin = l == 0 ? (const void *)frames : (const void *)w.act[l - 1];
             bool done = false;
             if (c->fast && is_aligned16(xin)) {
-                STAGE(CONV_WGRAD[l], 2.0 * B * g.OHW * g.OC * g.K, 0);
+                STAGE(CONV_WGRAD[l], 2.0 * B * g.OHW * g.OC * g.K, (double)B * ((l == 0 ? 1.0 : 4.0) * g.CHW + 4.0 * g.OC * g.OHW));
                 if (spec_matches<SpecS1>(g, l == 0) && is_aligned16(c->dact[l])) {
                     nz = conv1_bf16x3_wgrad_blocks(B);
                     HIP_TRY(launch_conv1_bf16x3_wgrad((const uint8_t *)xin, c->dact[l], w.ws, B, 1.f / 255.f, s));
@@ -1096,8 +1159,8 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
         if (l == 0) break;   // the input is data: no gradient needed
         // input gradient
         STAGE(CONV_DGRAD[l], 2.0 * B * g.OHW * g.OC * g.K, 0);
-        if (c->fast && spec_matches<SpecS2>(g, false) && is_aligned16(c->theta + c->off[2 * l])) {
-            HIP_TRY(launch_conv_dgrad_frame<SpecS2>(c->dact[l], c->theta + c->off[2 * l], w.act[l - 1], c->dact[l - 1], B, s));
+        if (c->fast && spec_matches<SpecS2>(g, false) && is_aligned16(th + c->off[2 * l])) {
+            HIP_TRY(launch_conv_dgrad_frame<SpecS2>(c->dact[l], th + c->off[2 * l], w.act[l - 1], c->dact[l - 1], B, s));
             continue;
         }
         // general shapes: one launch per stride phase
@@ -1112,7 +1175,7 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
                 p.dNHW = FastDiv(p.nH * p.nW); p.dNW = FastDiv(p.nW);
                 p.dTAB = FastDiv(p.TA * p.TB); p.dTB = FastDiv(p.TB);
                 p.M = g.C; p.N = B * p.nH * p.nW; p.K = g.OC * p.TA * p.TB;
-                p.w = c->theta + c->off[2 * l]; p.dy = c->dact[l]; p.xmask = w.act[l - 1]; p.dx = c->dact[l - 1];
+                p.w = th + c->off[2 * l]; p.dy = c->dact[l]; p.xmask = w.act[l - 1]; p.dx = c->dact[l - 1];
                 HIP_TRY(launch_conv_like(p, 1, s));
             }
     }
@@ -1128,9 +1191,13 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
     }
     STAGE("rmsprop", 8.0 * c->P, 20.0 * c->P);
     const unsigned rb = std::min<unsigned>(blocks_for(c->P / 4 + 1), 2048u);
-    hipLaunchKernelGGL(rmsprop_kernel, dim3(rb), dim3(256), 0, s, c->theta, c->g, c->grad, c->P, c->scale, 1.f, hp->lr,
-                       hp->rms_decay, hp->rms_eps);
+    // the copy about to be overwritten may still be read by predictions issued before the last update
+    TRY(wait_readers(c, cur ^ 1, s));
+    hipLaunchKernelGGL(rmsprop_kernel, dim3(rb), dim3(256), 0, s, th, c->theta2[cur ^ 1], c->g, c->grad, c->P, c->scale,
+                       1.f, hp->lr, hp->rms_decay, hp->rms_eps);
     HIP_TRY(hipGetLastError());
+    TRY(mark_ready(c, cur ^ 1, s));
+    c->cur = cur ^ 1;        // calls enqueued from now on see the new parameters
     return GA3C_OK;
 }
 
@@ -1164,7 +1231,7 @@ extern "C" int ga3c_rmsprop_flat(float *theta, float *g, const float *grad, size
     if ((((uintptr_t)theta) | ((uintptr_t)g) | ((uintptr_t)grad)) & 15)
         return fail(GA3C_EINVAL, "ga3c_rmsprop_flat: buffers must be 16-byte aligned");
     const unsigned rb = std::min<unsigned>(blocks_for(n / 4 + 1), 8192u);
-    hipLaunchKernelGGL(rmsprop_kernel, dim3(rb), dim3(256), 0, (hipStream_t)stream, theta, g, grad, n,
+    hipLaunchKernelGGL(rmsprop_kernel, dim3(rb), dim3(256), 0, (hipStream_t)stream, theta, theta, g, grad, n,
                        (const float *)nullptr, scale, lr, rms_decay, rms_eps);
     HIP_TRY(hipGetLastError());
     return GA3C_OK;
@@ -1201,5 +1268,13 @@ extern "C" int ga3c_profile_read(ga3c_ctx *c, char *buf, size_t cap) {
 extern "C" int ga3c_use_generic_kernels(ga3c_ctx *c, int on) {
     if (!c) return fail(GA3C_EINVAL, "ga3c_use_generic_kernels: null context");
     c->fast = on == 0;
+    return GA3C_OK;
+}
+
+extern "C" int ga3c_get_desc(const ga3c_ctx *c, ga3c_net_desc *desc, int *max_predict_batch, int *max_train_frames) {
+    if (!c) return fail(GA3C_EINVAL, "ga3c_get_desc: null context");
+    if (desc) *desc = c->desc;
+    if (max_predict_batch) *max_predict_batch = c->max_pred;
+    if (max_train_frames) *max_train_frames = c->max_train;
     return GA3C_OK;
 }

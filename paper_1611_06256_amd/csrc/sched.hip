@@ -1,0 +1,496 @@
+// Queue-driven batching on one GPU (paper Sec. 4.1: prediction queue +
+// predictors, training queue + trainers) and the dynamic adjustment of the
+// batching knobs (Sec. 4.3), on top of ga3c_predict / ga3c_train_step.
+//
+// The paper runs predictor and trainer THREADS because each GPU call blocks
+// its Python caller.  Here every GPU call only enqueues, so one host thread
+// (the caller of ga3c_sched_tick) drains both queues: prediction requests that
+// are "immediately available" (Sec. 4.1) go out as one batch on the predict
+// stream, trajectories are merged until a minimum batch is reached (Sec. 5.3)
+// and go out as one update on the train stream.  The two streams overlap on
+// the GPU; the context's parameter snapshots keep a prediction from reading
+// half-updated weights.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <chrono>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <deque>
+#include <new>
+#include <vector>
+
+#include "../../include/ga3c.h"
+
+namespace {
+
+thread_local char s_err[512] = "";
+
+int sfail(int code, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(s_err, sizeof(s_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+#define SHIP(expr)                                                                                   \
+    do {                                                                                             \
+        hipError_t e_ = (expr);                                                                      \
+        if (e_ != hipSuccess)                                                                        \
+            return sfail(e_ == hipErrorOutOfMemory ? GA3C_ENOMEM : GA3C_EHIP, "%s: %s", #expr,       \
+                         hipGetErrorString(e_));                                                     \
+    } while (0)
+
+uint64_t splitmix(uint64_t &x) {
+    x += 0x9E3779B97F4A7C15ull;
+    uint64_t z = x;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+// Copies whole frames by pointer: dst[i] = *src[i], frame_vecs 16-byte vectors each.
+__global__ __launch_bounds__(256) void gather_frames_kernel(const uint4 *const *__restrict__ src, uint4 *__restrict__ dst,
+                                                            int frame_vecs) {
+    const uint4 *s = src[blockIdx.y];
+    uint4 *d = dst + (size_t)blockIdx.y * frame_vecs;
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < frame_vecs; i += gridDim.x * 256) d[i] = s[i];
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------- tuner -----
+
+// Sec. 4.3: every period one knob is changed at random by one step; the change
+// is kept if the throughput did not drop, otherwise undone.  Knobs here are the
+// two batch caps: the prediction cap moves on the ladder lo, 2 lo, 4 lo, ...
+// (one step = a factor 2), the training cap in steps of t_step frames.
+struct ga3c_tuner {
+    int p_lo, p_hi, t_lo, t_hi, t_step;
+    int p, t;              // configuration now running
+    int kept_p, kept_t;    // last accepted configuration
+    double kept_thr;       // its throughput
+    bool have_ref, trial;
+    uint64_t rng;
+    int64_t accepted, rejected;
+};
+
+extern "C" int ga3c_tuner_create(int p_lo, int p_hi, int p0, int t_lo, int t_hi, int t_step, int t0, uint64_t seed,
+                                 ga3c_tuner **out) {
+    if (out) *out = nullptr;
+    if (!out || p_lo < 1 || p_hi < p_lo || p0 < p_lo || p0 > p_hi || t_lo < 1 || t_hi < t_lo || t0 < t_lo || t0 > t_hi ||
+        t_step < 1)
+        return sfail(GA3C_EINVAL, "ga3c_tuner_create: bad bounds");
+    ga3c_tuner *t = new (std::nothrow) ga3c_tuner();
+    if (!t) return sfail(GA3C_ENOMEM, "ga3c_tuner_create: out of memory");
+    t->p_lo = p_lo; t->p_hi = p_hi; t->t_lo = t_lo; t->t_hi = t_hi; t->t_step = t_step;
+    t->p = t->kept_p = p0; t->t = t->kept_t = t0;
+    t->kept_thr = 0.0; t->have_ref = false; t->trial = false;
+    t->rng = seed; t->accepted = t->rejected = 0;
+    *out = t;
+    return GA3C_OK;
+}
+
+extern "C" int ga3c_tuner_destroy(ga3c_tuner *t) {
+    delete t;
+    return GA3C_OK;
+}
+
+// End of a measurement window that ran the current configuration with the
+// given throughput.  Decides about the trial (if one was running), then
+// proposes the next configuration and returns it.
+extern "C" int ga3c_tuner_report(ga3c_tuner *t, double throughput, int *predict_cap, int *train_cap) {
+    if (!t) return sfail(GA3C_EINVAL, "ga3c_tuner_report: null tuner");
+    if (t->trial && t->have_ref && throughput < t->kept_thr) {
+        t->rejected += 1;                       // undo; the reference stays
+    } else {
+        if (t->trial) t->accepted += 1;
+        t->kept_p = t->p; t->kept_t = t->t;
+        t->kept_thr = throughput; t->have_ref = true;
+    }
+    // next trial: one knob, one step, random direction; a step that would leave
+    // the bounds goes the other way, a knob with a single value is skipped
+    int np = t->kept_p, nt = t->kept_t;
+    for (int tries = 0; tries < 8; ++tries) {
+        const uint64_t r = splitmix(t->rng);
+        const bool knob_p = (r & 1) == 0;
+        const bool up = (r & 2) != 0;
+        if (knob_p) {
+            int c = up ? t->kept_p * 2 : t->kept_p / 2;
+            if (c > t->p_hi || c < t->p_lo) c = up ? t->kept_p / 2 : t->kept_p * 2;
+            if (c >= t->p_lo && c <= t->p_hi && c != t->kept_p) { np = c; break; }
+        } else {
+            int c = up ? t->kept_t + t->t_step : t->kept_t - t->t_step;
+            if (c > t->t_hi || c < t->t_lo) c = up ? t->kept_t - t->t_step : t->kept_t + t->t_step;
+            if (c >= t->t_lo && c <= t->t_hi && c != t->kept_t) { nt = c; break; }
+        }
+    }
+    t->p = np; t->t = nt;
+    t->trial = (np != t->kept_p) || (nt != t->kept_t);
+    if (predict_cap) *predict_cap = t->p;
+    if (train_cap) *train_cap = t->t;
+    return GA3C_OK;
+}
+
+extern "C" int ga3c_tuner_state(const ga3c_tuner *t, int *kept_predict_cap, int *kept_train_cap, int64_t *accepted,
+                                int64_t *rejected) {
+    if (!t) return sfail(GA3C_EINVAL, "ga3c_tuner_state: null tuner");
+    if (kept_predict_cap) *kept_predict_cap = t->kept_p;
+    if (kept_train_cap) *kept_train_cap = t->kept_t;
+    if (accepted) *accepted = t->accepted;
+    if (rejected) *rejected = t->rejected;
+    return GA3C_OK;
+}
+
+// ------------------------------------------------------------- scheduler ----
+
+namespace {
+
+constexpr int RING = 4;    // batches in flight per stream
+
+struct PredReq { int agent; const uint8_t *frame; float uniform; };
+struct Traj {
+    int agent;
+    const uint8_t *frames;
+    std::vector<int32_t> actions;
+    std::vector<float> rewards;
+    std::vector<uint8_t> dones;
+    float bootstrap;
+};
+
+struct PredSlot {
+    hipEvent_t done = nullptr;
+    bool busy = false;
+    int n = 0;
+    const uint4 **ptrs_h = nullptr, **ptrs_d = nullptr;   // pinned host / device pointer lists
+    float *unif_h = nullptr, *unif_d = nullptr;
+    uint8_t *frames_d = nullptr;
+    int32_t *act_d = nullptr, *act_h = nullptr;
+    float *val_d = nullptr, *val_h = nullptr;
+    std::vector<int> agents;
+};
+
+struct TrainSlot {
+    hipEvent_t done = nullptr;
+    bool busy = false;
+    int n_agents = 0;
+    const uint4 **ptrs_h = nullptr, **ptrs_d = nullptr;
+    uint8_t *frames_d = nullptr;
+    int32_t *act_h = nullptr, *act_d = nullptr;
+    float *rew_h = nullptr, *rew_d = nullptr;
+    uint8_t *done_h = nullptr, *done_d = nullptr;
+    float *boot_h = nullptr, *boot_d = nullptr;
+};
+
+}  // namespace
+
+struct ga3c_sched {
+    ga3c_ctx *ctx;
+    ga3c_sched_config cfg;
+    ga3c_net_desc desc;
+    int max_pred, max_train;
+    size_t frame_bytes;
+    int predict_cap, train_cap;
+    hipStream_t sp, st;
+    std::deque<PredReq> pq;
+    std::deque<Traj> tq;
+    PredSlot ps[RING];
+    TrainSlot ts[RING];
+    int ps_next, ts_next;
+    std::deque<ga3c_prediction> ready;
+    ga3c_tuner *tuner;
+    ga3c_sched_stats stats;
+    int64_t window_ticks, window_frames;
+    std::chrono::steady_clock::time_point window_start;
+};
+
+namespace {
+
+template <class T>
+int pinned(T **p, size_t n) {
+    SHIP(hipHostMalloc((void **)p, sizeof(T) * std::max<size_t>(n, 1), hipHostMallocDefault));
+    return GA3C_OK;
+}
+template <class T>
+int device(T **p, size_t n) {
+    SHIP(hipMalloc((void **)p, sizeof(T) * std::max<size_t>(n, 1)));
+    return GA3C_OK;
+}
+#define STRY(expr) do { int rc_ = (expr); if (rc_ != GA3C_OK) return rc_; } while (0)
+
+int alloc_slots(ga3c_sched *s) {
+    const int T = s->cfg.t_max;
+    const int maxN = s->max_train / T;
+    for (int i = 0; i < RING; ++i) {
+        PredSlot &p = s->ps[i];
+        SHIP(hipEventCreateWithFlags(&p.done, hipEventDisableTiming));
+        STRY(pinned(&p.ptrs_h, s->max_pred)); STRY(device(&p.ptrs_d, s->max_pred));
+        STRY(pinned(&p.unif_h, s->max_pred)); STRY(device(&p.unif_d, s->max_pred));
+        STRY(device(&p.frames_d, (size_t)s->max_pred * s->frame_bytes));
+        STRY(device(&p.act_d, s->max_pred)); STRY(pinned(&p.act_h, s->max_pred));
+        STRY(device(&p.val_d, s->max_pred)); STRY(pinned(&p.val_h, s->max_pred));
+        TrainSlot &t = s->ts[i];
+        SHIP(hipEventCreateWithFlags(&t.done, hipEventDisableTiming));
+        STRY(pinned(&t.ptrs_h, maxN)); STRY(device(&t.ptrs_d, maxN));
+        STRY(device(&t.frames_d, (size_t)s->max_train * s->frame_bytes));
+        STRY(pinned(&t.act_h, s->max_train)); STRY(device(&t.act_d, s->max_train));
+        STRY(pinned(&t.rew_h, s->max_train)); STRY(device(&t.rew_d, s->max_train));
+        STRY(pinned(&t.done_h, s->max_train)); STRY(device(&t.done_d, s->max_train));
+        STRY(pinned(&t.boot_h, maxN)); STRY(device(&t.boot_d, maxN));
+    }
+    return GA3C_OK;
+}
+
+// Moves the results of finished prediction batches to the ready list.
+int harvest(ga3c_sched *s, bool wait) {
+    for (int k = 0; k < RING; ++k) {
+        PredSlot &p = s->ps[(s->ps_next + k) % RING];        // oldest first
+        if (!p.busy) continue;
+        if (wait) SHIP(hipEventSynchronize(p.done));
+        else {
+            const hipError_t q = hipEventQuery(p.done);
+            if (q == hipErrorNotReady) continue;
+            if (q != hipSuccess) return sfail(GA3C_EHIP, "hipEventQuery: %s", hipGetErrorString(q));
+        }
+        for (int i = 0; i < p.n; ++i) s->ready.push_back(ga3c_prediction{p.agents[i], p.act_h[i], p.val_h[i]});
+        p.busy = false;
+    }
+    for (int k = 0; k < RING; ++k) {
+        TrainSlot &t = s->ts[k];
+        if (!t.busy) continue;
+        if (wait) SHIP(hipEventSynchronize(t.done));
+        else if (hipEventQuery(t.done) != hipSuccess) continue;
+        t.busy = false;
+    }
+    return GA3C_OK;
+}
+
+int issue_predict(ga3c_sched *s, int *count) {
+    *count = 0;
+    if (s->pq.empty()) return GA3C_OK;
+    PredSlot &p = s->ps[s->ps_next];
+    if (p.busy) {                                   // ring full: wait for the oldest batch
+        SHIP(hipEventSynchronize(p.done));
+        STRY(harvest(s, false));
+    }
+    const int n = (int)std::min<size_t>(s->pq.size(), (size_t)s->predict_cap);
+    p.agents.resize(n);
+    for (int i = 0; i < n; ++i) {
+        const PredReq r = s->pq.front();
+        s->pq.pop_front();
+        p.agents[i] = r.agent; p.ptrs_h[i] = (const uint4 *)r.frame; p.unif_h[i] = r.uniform;
+    }
+    SHIP(hipMemcpyAsync(p.ptrs_d, p.ptrs_h, sizeof(void *) * n, hipMemcpyHostToDevice, s->sp));
+    SHIP(hipMemcpyAsync(p.unif_d, p.unif_h, sizeof(float) * n, hipMemcpyHostToDevice, s->sp));
+    const int vecs = (int)(s->frame_bytes / 16);
+    hipLaunchKernelGGL(gather_frames_kernel, dim3(std::min(8, (vecs + 255) / 256), n), dim3(256), 0, s->sp, p.ptrs_d,
+                       (uint4 *)p.frames_d, vecs);
+    SHIP(hipGetLastError());
+    if (ga3c_predict(s->ctx, p.frames_d, n, p.unif_d, nullptr, p.val_d, nullptr, p.act_d, s->sp) != GA3C_OK)
+        return sfail(GA3C_EHIP, "ga3c_predict: %s", ga3c_last_error());
+    SHIP(hipMemcpyAsync(p.act_h, p.act_d, sizeof(int32_t) * n, hipMemcpyDeviceToHost, s->sp));
+    SHIP(hipMemcpyAsync(p.val_h, p.val_d, sizeof(float) * n, hipMemcpyDeviceToHost, s->sp));
+    SHIP(hipEventRecord(p.done, s->sp));
+    p.busy = true; p.n = n;
+    s->ps_next = (s->ps_next + 1) % RING;
+    s->stats.predictions += n; s->stats.predict_batches += 1;
+    *count = n;
+    return GA3C_OK;
+}
+
+int issue_train(ga3c_sched *s, int *count) {
+    *count = 0;
+    const int T = s->cfg.t_max;
+    if ((int64_t)s->tq.size() * T < s->cfg.train_min) return GA3C_OK;      // merge until the minimum batch is there
+    TrainSlot &t = s->ts[s->ts_next];
+    if (t.busy) {
+        SHIP(hipEventSynchronize(t.done));
+        t.busy = false;
+    }
+    const int n = (int)std::min<size_t>(s->tq.size(), (size_t)std::max(1, s->train_cap / T));
+    for (int i = 0; i < n; ++i) {
+        Traj &tr = s->tq.front();
+        t.ptrs_h[i] = (const uint4 *)tr.frames;
+        memcpy(t.act_h + (size_t)i * T, tr.actions.data(), sizeof(int32_t) * T);
+        memcpy(t.rew_h + (size_t)i * T, tr.rewards.data(), sizeof(float) * T);
+        memcpy(t.done_h + (size_t)i * T, tr.dones.data(), T);
+        t.boot_h[i] = tr.bootstrap;
+        s->tq.pop_front();
+    }
+    const size_t B = (size_t)n * T;
+    SHIP(hipMemcpyAsync(t.ptrs_d, t.ptrs_h, sizeof(void *) * n, hipMemcpyHostToDevice, s->st));
+    SHIP(hipMemcpyAsync(t.act_d, t.act_h, sizeof(int32_t) * B, hipMemcpyHostToDevice, s->st));
+    SHIP(hipMemcpyAsync(t.rew_d, t.rew_h, sizeof(float) * B, hipMemcpyHostToDevice, s->st));
+    SHIP(hipMemcpyAsync(t.done_d, t.done_h, B, hipMemcpyHostToDevice, s->st));
+    SHIP(hipMemcpyAsync(t.boot_d, t.boot_h, sizeof(float) * n, hipMemcpyHostToDevice, s->st));
+    const int vecs = (int)(s->frame_bytes * T / 16);       // a trajectory's frames are contiguous
+    hipLaunchKernelGGL(gather_frames_kernel, dim3(std::min(16, (vecs + 255) / 256), n), dim3(256), 0, s->st, t.ptrs_d,
+                       (uint4 *)t.frames_d, vecs);
+    SHIP(hipGetLastError());
+    if (ga3c_train_step(s->ctx, t.frames_d, t.act_d, t.rew_d, t.done_d, t.boot_d, n, T, &s->cfg.hp, nullptr, s->st) !=
+        GA3C_OK)
+        return sfail(GA3C_EHIP, "ga3c_train_step: %s", ga3c_last_error());
+    SHIP(hipEventRecord(t.done, s->st));
+    t.busy = true; t.n_agents = n;
+    s->ts_next = (s->ts_next + 1) % RING;
+    s->stats.trained_frames += (int64_t)B; s->stats.train_batches += 1;
+    *count = (int)B;
+    return GA3C_OK;
+}
+
+}  // namespace
+
+extern "C" int ga3c_sched_create(ga3c_ctx *ctx, const ga3c_sched_config *cfg, ga3c_sched **out) {
+    if (out) *out = nullptr;
+    if (!ctx || !cfg || !out) return sfail(GA3C_EINVAL, "ga3c_sched_create: null argument");
+    ga3c_net_desc d;
+    int mp, mt;
+    if (ga3c_get_desc(ctx, &d, &mp, &mt) != GA3C_OK) return sfail(GA3C_EINVAL, "ga3c_sched_create: bad context");
+    const size_t fb = (size_t)d.in_c * d.in_h * d.in_w;
+    if (fb % 16 != 0) return sfail(GA3C_EINVAL, "ga3c_sched_create: frame size must be a multiple of 16 bytes");
+    if (cfg->t_max < 1 || cfg->predict_cap < 1 || cfg->predict_cap > mp || cfg->train_min < 1 ||
+        cfg->train_cap < cfg->t_max || cfg->train_cap > mt || cfg->train_min > cfg->train_cap)
+        return sfail(GA3C_EINVAL, "ga3c_sched_create: caps outside the context's capacity (predict %d, train %d)", mp, mt);
+    if (cfg->adjust_period > 0 &&
+        (cfg->predict_cap_lo < 1 || cfg->predict_cap_hi > mp || cfg->predict_cap_lo > cfg->predict_cap ||
+         cfg->predict_cap_hi < cfg->predict_cap || cfg->train_cap_lo < cfg->train_min || cfg->train_cap_hi > mt ||
+         cfg->train_cap_lo > cfg->train_cap || cfg->train_cap_hi < cfg->train_cap || cfg->train_cap_step < 1))
+        return sfail(GA3C_EINVAL, "ga3c_sched_create: adjustment bounds must contain the initial caps and fit the context");
+    ga3c_sched *s = new (std::nothrow) ga3c_sched();
+    if (!s) return sfail(GA3C_ENOMEM, "ga3c_sched_create: out of memory");
+    s->ctx = ctx; s->cfg = *cfg; s->desc = d; s->max_pred = mp; s->max_train = mt; s->frame_bytes = fb;
+    s->predict_cap = cfg->predict_cap; s->train_cap = cfg->train_cap;
+    s->sp = s->st = nullptr; s->ps_next = s->ts_next = 0; s->tuner = nullptr;
+    memset(&s->stats, 0, sizeof(s->stats));
+    s->stats.predict_cap = s->predict_cap; s->stats.train_cap = s->train_cap;
+    s->window_ticks = s->window_frames = 0;
+    int rc = GA3C_OK;
+    // default priority for both streams
+    if (hipStreamCreateWithFlags(&s->sp, hipStreamNonBlocking) != hipSuccess ||
+        hipStreamCreateWithFlags(&s->st, hipStreamNonBlocking) != hipSuccess)
+        rc = sfail(GA3C_EHIP, "ga3c_sched_create: hipStreamCreate failed");
+    if (rc == GA3C_OK) rc = alloc_slots(s);
+    if (rc == GA3C_OK && cfg->adjust_period > 0)
+        rc = ga3c_tuner_create(cfg->predict_cap_lo, cfg->predict_cap_hi, cfg->predict_cap, cfg->train_cap_lo,
+                               cfg->train_cap_hi, cfg->train_cap_step, cfg->train_cap, cfg->seed, &s->tuner);
+    if (rc != GA3C_OK) {
+        char keep[sizeof(s_err)];
+        memcpy(keep, s_err, sizeof(keep));
+        ga3c_sched_destroy(s);
+        memcpy(s_err, keep, sizeof(keep));
+        return rc;
+    }
+    s->window_start = std::chrono::steady_clock::now();
+    *out = s;
+    return GA3C_OK;
+}
+
+extern "C" int ga3c_sched_destroy(ga3c_sched *s) {
+    if (!s) return GA3C_OK;
+    if (s->sp) (void)hipStreamSynchronize(s->sp);
+    if (s->st) (void)hipStreamSynchronize(s->st);
+    for (int i = 0; i < RING; ++i) {
+        PredSlot &p = s->ps[i];
+        if (p.done) (void)hipEventDestroy(p.done);
+        (void)hipHostFree(p.ptrs_h); (void)hipFree(p.ptrs_d); (void)hipHostFree(p.unif_h); (void)hipFree(p.unif_d);
+        (void)hipFree(p.frames_d); (void)hipFree(p.act_d); (void)hipHostFree(p.act_h); (void)hipFree(p.val_d);
+        (void)hipHostFree(p.val_h);
+        TrainSlot &t = s->ts[i];
+        if (t.done) (void)hipEventDestroy(t.done);
+        (void)hipHostFree(t.ptrs_h); (void)hipFree(t.ptrs_d); (void)hipFree(t.frames_d);
+        (void)hipHostFree(t.act_h); (void)hipFree(t.act_d); (void)hipHostFree(t.rew_h); (void)hipFree(t.rew_d);
+        (void)hipHostFree(t.done_h); (void)hipFree(t.done_d); (void)hipHostFree(t.boot_h); (void)hipFree(t.boot_d);
+    }
+    if (s->sp) (void)hipStreamDestroy(s->sp);
+    if (s->st) (void)hipStreamDestroy(s->st);
+    ga3c_tuner_destroy(s->tuner);
+    delete s;
+    return GA3C_OK;
+}
+
+extern "C" int ga3c_sched_submit_predict(ga3c_sched *s, int agent, const uint8_t *frame_dev, float uniform) {
+    if (!s || !frame_dev) return sfail(GA3C_EINVAL, "ga3c_sched_submit_predict: null argument");
+    if (((uintptr_t)frame_dev) & 15) return sfail(GA3C_EINVAL, "ga3c_sched_submit_predict: frame must be 16-byte aligned");
+    s->pq.push_back(PredReq{agent, frame_dev, uniform});
+    return GA3C_OK;
+}
+
+extern "C" int ga3c_sched_submit_trajectory(ga3c_sched *s, int agent, const uint8_t *frames_dev, const int32_t *actions,
+                                            const float *rewards, const uint8_t *dones, float bootstrap) {
+    if (!s || !frames_dev || !actions || !rewards || !dones)
+        return sfail(GA3C_EINVAL, "ga3c_sched_submit_trajectory: null argument");
+    if (((uintptr_t)frames_dev) & 15)
+        return sfail(GA3C_EINVAL, "ga3c_sched_submit_trajectory: frames must be 16-byte aligned");
+    const int T = s->cfg.t_max;
+    for (int i = 0; i < T; ++i)
+        if (actions[i] < 0 || actions[i] >= s->desc.n_actions)
+            return sfail(GA3C_EINVAL, "ga3c_sched_submit_trajectory: action %d out of range", (int)actions[i]);
+    Traj tr;
+    tr.agent = agent; tr.frames = frames_dev; tr.bootstrap = bootstrap;
+    tr.actions.assign(actions, actions + T);
+    tr.rewards.assign(rewards, rewards + T);
+    tr.dones.assign(dones, dones + T);
+    s->tq.push_back(std::move(tr));
+    return GA3C_OK;
+}
+
+extern "C" int ga3c_sched_tick(ga3c_sched *s, int *predicted, int *trained) {
+    if (!s) return sfail(GA3C_EINVAL, "ga3c_sched_tick: null scheduler");
+    int np = 0, nt = 0;
+    s->stats.ticks += 1;
+    s->stats.sum_predict_queue += (int64_t)s->pq.size();
+    s->stats.sum_train_queue += (int64_t)s->tq.size();
+    STRY(issue_predict(s, &np));
+    STRY(issue_train(s, &nt));
+    STRY(harvest(s, false));
+    if (predicted) *predicted = np;
+    if (trained) *trained = nt;
+    if (s->tuner) {
+        s->window_ticks += 1; s->window_frames += nt;
+        if (s->window_ticks >= s->cfg.adjust_period) {
+            // throughput of the window that just ended: finish its GPU work, then read the clock
+            SHIP(hipStreamSynchronize(s->st));
+            SHIP(hipStreamSynchronize(s->sp));
+            const auto now = std::chrono::steady_clock::now();
+            const double sec = std::chrono::duration<double>(now - s->window_start).count();
+            const double thr = sec > 0 ? (double)s->window_frames / sec : 0.0;
+            ga3c_tuner_report(s->tuner, thr, &s->predict_cap, &s->train_cap);
+            s->stats.last_window_frames_per_s = thr;
+            s->stats.predict_cap = s->predict_cap; s->stats.train_cap = s->train_cap;
+            ga3c_tuner_state(s->tuner, nullptr, nullptr, &s->stats.trials_accepted, &s->stats.trials_rejected);
+            s->window_ticks = s->window_frames = 0;
+            s->window_start = std::chrono::steady_clock::now();
+        }
+    }
+    return GA3C_OK;
+}
+
+extern "C" int ga3c_sched_poll(ga3c_sched *s, ga3c_prediction *out, int cap) {
+    if (!s || (!out && cap > 0) || cap < 0) return sfail(GA3C_EINVAL, "ga3c_sched_poll: bad argument");
+    STRY(harvest(s, false));
+    int n = 0;
+    while (n < cap && !s->ready.empty()) {
+        out[n++] = s->ready.front();
+        s->ready.pop_front();
+    }
+    return n;
+}
+
+extern "C" int ga3c_sched_drain(ga3c_sched *s) {
+    if (!s) return sfail(GA3C_EINVAL, "ga3c_sched_drain: null scheduler");
+    SHIP(hipStreamSynchronize(s->sp));
+    SHIP(hipStreamSynchronize(s->st));
+    return harvest(s, true);
+}
+
+extern "C" int ga3c_sched_get_stats(const ga3c_sched *s, ga3c_sched_stats *out) {
+    if (!s || !out) return sfail(GA3C_EINVAL, "ga3c_sched_get_stats: null argument");
+    *out = s->stats;
+    out->predict_queue = (int64_t)s->pq.size();
+    out->train_queue = (int64_t)s->tq.size();
+    return GA3C_OK;
+}
+
+extern "C" const char *ga3c_sched_last_error(void) { return s_err; }
