@@ -4,5 +4,6 @@ Thin Python binding over the C ABI in ``include/ga3c.h``; every step of the
 path runs in the HIP library, this package only marshals arguments.
 """
 from .binding import (  # noqa: F401
-    Ga3c, Ga3cError, HParams, NetDesc, TrainStats, SMALL_NET, LARGE_NET, lib_path, load_library, rmsprop_flat,
+    Ga3c, Ga3cError, HParams, NetDesc, TrainStats, SMALL_NET, LARGE_NET, Scheduler, Tuner, lib_path, load_library,
+    rmsprop_flat,
 )

@@ -34,6 +34,24 @@ class _HParams(C.Structure):
                 ("gamma", "beta", "value_coef", "log_eps", "lr", "rms_decay", "rms_eps", "clip_norm")]
 
 
+class _SchedConfig(C.Structure):
+    _fields_ = [("t_max", C.c_int), ("predict_cap", C.c_int), ("train_min", C.c_int), ("train_cap", C.c_int),
+                ("adjust_period", C.c_int), ("predict_cap_lo", C.c_int), ("predict_cap_hi", C.c_int),
+                ("train_cap_lo", C.c_int), ("train_cap_hi", C.c_int), ("train_cap_step", C.c_int),
+                ("seed", C.c_uint64), ("hp", _HParams)]
+
+
+class Prediction(C.Structure):
+    _fields_ = [("agent", C.c_int32), ("action", C.c_int32), ("value", C.c_float)]
+
+
+class SchedStats(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in
+                ("ticks", "predictions", "predict_batches", "trained_frames", "train_batches", "sum_predict_queue",
+                 "sum_train_queue", "predict_queue", "train_queue", "trials_accepted", "trials_rejected")] + \
+               [("predict_cap", C.c_int32), ("train_cap", C.c_int32), ("last_window_frames_per_s", C.c_double)]
+
+
 class TrainStats(C.Structure):
     _fields_ = [("policy_loss", C.c_float), ("value_loss", C.c_float), ("entropy", C.c_float),
                 ("grad_norm", C.c_float), ("clip_scale", C.c_float), ("nonfinite", C.c_int32)]
@@ -91,7 +109,10 @@ _lib = None
 EXPORTS = ("ga3c_create", "ga3c_destroy", "ga3c_params_count", "ga3c_params_offsets", "ga3c_params_init",
            "ga3c_params_get", "ga3c_params_set", "ga3c_predict", "ga3c_train_step", "ga3c_train_debug_get",
            "ga3c_rmsprop_flat", "ga3c_last_error", "ga3c_profile_enable", "ga3c_profile_read",
-           "ga3c_use_generic_kernels")
+           "ga3c_use_generic_kernels", "ga3c_get_desc",
+           "ga3c_sched_create", "ga3c_sched_destroy", "ga3c_sched_submit_predict", "ga3c_sched_submit_trajectory",
+           "ga3c_sched_tick", "ga3c_sched_poll", "ga3c_sched_drain", "ga3c_sched_get_stats", "ga3c_sched_last_error",
+           "ga3c_tuner_create", "ga3c_tuner_report", "ga3c_tuner_state", "ga3c_tuner_destroy")
 
 
 def load_library() -> C.CDLL:
@@ -119,6 +140,20 @@ def load_library() -> C.CDLL:
     lib.ga3c_rmsprop_flat.argtypes = [vp, vp, vp, sz, f32, f32, f32, f32, vp]
     lib.ga3c_last_error.restype = C.c_char_p
     lib.ga3c_profile_enable.argtypes = [vp, i32]
+    lib.ga3c_get_desc.argtypes = [vp, C.POINTER(_NetDesc), C.POINTER(i32), C.POINTER(i32)]
+    lib.ga3c_sched_create.argtypes = [vp, C.POINTER(_SchedConfig), C.POINTER(vp)]
+    lib.ga3c_sched_destroy.argtypes = [vp]
+    lib.ga3c_sched_submit_predict.argtypes = [vp, i32, vp, f32]
+    lib.ga3c_sched_submit_trajectory.argtypes = [vp, i32, vp, vp, vp, vp, f32]
+    lib.ga3c_sched_tick.argtypes = [vp, C.POINTER(i32), C.POINTER(i32)]
+    lib.ga3c_sched_poll.argtypes = [vp, C.POINTER(Prediction), i32]
+    lib.ga3c_sched_drain.argtypes = [vp]
+    lib.ga3c_sched_get_stats.argtypes = [vp, C.POINTER(SchedStats)]
+    lib.ga3c_sched_last_error.restype = C.c_char_p
+    lib.ga3c_tuner_create.argtypes = [i32, i32, i32, i32, i32, i32, i32, u64, C.POINTER(vp)]
+    lib.ga3c_tuner_report.argtypes = [vp, C.c_double, C.POINTER(i32), C.POINTER(i32)]
+    lib.ga3c_tuner_state.argtypes = [vp, C.POINTER(i32), C.POINTER(i32), C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
+    lib.ga3c_tuner_destroy.argtypes = [vp]
     lib.ga3c_use_generic_kernels.argtypes = [vp, i32]
     lib.ga3c_profile_read.argtypes = [vp, C.c_char_p, sz]
     _lib = lib
@@ -262,6 +297,100 @@ class Ga3c:
         _check(self._lib.ga3c_train_debug_get(self._ctx, which, _ptr(out, torch.float32, "out"), out.numel(),
                                               _stream(stream)), "ga3c_train_debug_get")
         return out
+
+
+def _scheck(rc: int, what: str) -> int:
+    if rc < 0:
+        raise Ga3cError(f"{what} failed ({rc}): {load_library().ga3c_sched_last_error().decode()}")
+    return rc
+
+
+class Tuner:
+    """The adjustment rule of the scheduler on its own (host only)."""
+
+    def __init__(self, p_lo, p_hi, p0, t_lo, t_hi, t_step, t0, seed):
+        self._lib = load_library()
+        self._t = C.c_void_p()
+        _scheck(self._lib.ga3c_tuner_create(p_lo, p_hi, p0, t_lo, t_hi, t_step, t0, seed, C.byref(self._t)),
+                "ga3c_tuner_create")
+
+    def report(self, throughput: float) -> Tuple[int, int]:
+        p, t = C.c_int(), C.c_int()
+        _scheck(self._lib.ga3c_tuner_report(self._t, throughput, C.byref(p), C.byref(t)), "ga3c_tuner_report")
+        return p.value, t.value
+
+    def state(self):
+        p, t, a, r = C.c_int(), C.c_int(), C.c_int64(), C.c_int64()
+        _scheck(self._lib.ga3c_tuner_state(self._t, C.byref(p), C.byref(t), C.byref(a), C.byref(r)), "ga3c_tuner_state")
+        return {"predict_cap": p.value, "train_cap": t.value, "accepted": a.value, "rejected": r.value}
+
+    def __del__(self):
+        try:
+            self._lib.ga3c_tuner_destroy(self._t)
+        except Exception:
+            pass
+
+
+class Scheduler:
+    """ga3c_sched_*: queues, two streams, batch caps and their adjustment."""
+
+    def __init__(self, net: Ga3c, hp: HParams, t_max=5, predict_cap=256, train_min=40, train_cap=1280,
+                 adjust_period=0, predict_cap_lo=1, predict_cap_hi=256, train_cap_lo=40, train_cap_hi=1280,
+                 train_cap_step=40, seed=0):
+        self._lib = load_library()
+        self._net = net
+        cfg = _SchedConfig(t_max, predict_cap, train_min, train_cap, adjust_period, predict_cap_lo, predict_cap_hi,
+                           train_cap_lo, train_cap_hi, train_cap_step, seed, hp.c())
+        self._s = C.c_void_p()
+        self.t_max = t_max
+        _scheck(self._lib.ga3c_sched_create(net._ctx, C.byref(cfg), C.byref(self._s)), "ga3c_sched_create")
+
+    def close(self):
+        if self._s.value:
+            self._lib.ga3c_sched_destroy(self._s)
+            self._s = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def submit_predict(self, agent: int, frame, uniform: float) -> None:
+        import torch
+        _scheck(self._lib.ga3c_sched_submit_predict(self._s, agent, _ptr(frame, torch.uint8, "frame"), uniform),
+                "ga3c_sched_submit_predict")
+
+    def submit_trajectory(self, agent: int, frames, actions, rewards, dones, bootstrap: float) -> None:
+        """frames: GPU u8 [t_max,C,H,W]; actions i32 / rewards f32 / dones u8: numpy arrays of t_max entries."""
+        import numpy as np
+        import torch
+        a = np.ascontiguousarray(actions, dtype=np.int32); r = np.ascontiguousarray(rewards, dtype=np.float32)
+        d = np.ascontiguousarray(dones, dtype=np.uint8)
+        if a.size != self.t_max or r.size != self.t_max or d.size != self.t_max:
+            raise Ga3cError("trajectory arrays must have t_max entries")
+        _scheck(self._lib.ga3c_sched_submit_trajectory(self._s, agent, _ptr(frames, torch.uint8, "frames"),
+                                                       a.ctypes.data_as(C.c_void_p), r.ctypes.data_as(C.c_void_p),
+                                                       d.ctypes.data_as(C.c_void_p), bootstrap),
+                "ga3c_sched_submit_trajectory")
+
+    def tick(self) -> Tuple[int, int]:
+        p, t = C.c_int(), C.c_int()
+        _scheck(self._lib.ga3c_sched_tick(self._s, C.byref(p), C.byref(t)), "ga3c_sched_tick")
+        return p.value, t.value
+
+    def poll(self, cap: int = 4096):
+        buf = (Prediction * cap)()
+        n = _scheck(self._lib.ga3c_sched_poll(self._s, buf, cap), "ga3c_sched_poll")
+        return [(buf[i].agent, buf[i].action, buf[i].value) for i in range(n)]
+
+    def drain(self) -> None:
+        _scheck(self._lib.ga3c_sched_drain(self._s), "ga3c_sched_drain")
+
+    def stats(self) -> Dict[str, float]:
+        st = SchedStats()
+        _scheck(self._lib.ga3c_sched_get_stats(self._s, C.byref(st)), "ga3c_sched_get_stats")
+        return {n: getattr(st, n) for n, _ in SchedStats._fields_}
 
 
 def rmsprop_flat(theta, g, grad, scale: float, lr: float, rms_decay: float, rms_eps: float, stream=None) -> None:
