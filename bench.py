@@ -39,6 +39,8 @@ def main() -> int:
     ap.add_argument("--net", choices=("small", "large"), default="small")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rmsprop-big", action="store_true", help="also time RMSProp on 2^28 parameters")
+    ap.add_argument("--mixed-seconds", type=float, default=1.0,
+                    help="length of each mixed-load run through the scheduler (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported "
@@ -147,6 +149,7 @@ def main() -> int:
     flop_step = sum(p["flop"] for p in prof.values()) / args.steps
     whole = {"tflops": round(flop_step / sec / 1e12, 3), "frac_fp32_mfma_peak": round(flop_step / sec / PEAK_FP32_MFMA, 4)}
 
+    theta_np = net.params_get(0).cpu().numpy()
     out = {
         "metric": "frames/s through predict and train_step, balanced (PPS = TPS*t_max)",
         "value": round(frames_per_step / sec, 1), "unit": "frames/s",
@@ -174,10 +177,18 @@ def main() -> int:
                                "ms": round(s * 1e3, 4)}
         del th, gg, dd
 
+    net.close()
+    net = None
+    if args.mixed_seconds > 0:
+        # 256 synthetic agents through the two-stream scheduler (bench_mixed.py): fixed caps, then adaptive caps
+        from bench_mixed import run_mixed
+        out["mixed_load"] = [run_mixed(args.net, think_us=0.0, seconds=args.mixed_seconds, dynamic=False),
+                             run_mixed(args.net, think_us=0.0, seconds=2 * args.mixed_seconds, dynamic=True)]
+
     if not args.no_cpu_baseline:
         import oracle as orc
         onet = orc.Net(conv=tuple(desc.conv), fc_units=desc.fc_units, n_actions=A)
-        theta = net.params_get(0).cpu().numpy().astype(np.float64)
+        theta = theta_np.astype(np.float64)
         cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
         t0 = time.perf_counter()
         for t in range(T):
@@ -188,7 +199,6 @@ def main() -> int:
         cpu_sec = time.perf_counter() - t0
         out["cpu_baseline"] = {"value": round(frames_per_step / cpu_sec, 1), "unit": "frames/s", "cores": cores,
                                "kind": "oracle", "sample": f"1 whole step of the same workload ({cpu_sec:.1f} s, fp64, OpenMP over frames)"}
-    net.close()
     print(json.dumps(out))
     return 0
 

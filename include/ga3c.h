@@ -243,6 +243,15 @@ int ga3c_sched_submit_predict(ga3c_sched *s, int agent, const uint8_t *frame_dev
  * after the last step. */
 int ga3c_sched_submit_trajectory(ga3c_sched *s, int agent, const uint8_t *frames_dev, const int32_t *actions,
                                  const float *rewards, const uint8_t *dones, float bootstrap);
+/* The same for n agents at once (host arrays of n entries; actions, rewards
+ * and dones are [n][t_max]).  Entries are queued in index order; on an error
+ * the entries before the offending one stay queued (trajectories) or nothing
+ * is queued (predictions). */
+int ga3c_sched_submit_predict_many(ga3c_sched *s, int n, const int32_t *agents, const uint8_t *const *frames_dev,
+                                   const float *uniforms);
+int ga3c_sched_submit_trajectory_many(ga3c_sched *s, int n, const int32_t *agents, const uint8_t *const *frames_dev,
+                                      const int32_t *actions, const float *rewards, const uint8_t *dones,
+                                      const float *bootstrap);
 /* One pass of predictor and trainer: at most one prediction batch (all queued
  * requests up to the cap) and at most one update (queued trajectories up to
  * the cap, if at least train_min frames wait) are enqueued on the GPU.

@@ -111,6 +111,7 @@ EXPORTS = ("ga3c_create", "ga3c_destroy", "ga3c_params_count", "ga3c_params_offs
            "ga3c_rmsprop_flat", "ga3c_last_error", "ga3c_profile_enable", "ga3c_profile_read",
            "ga3c_use_generic_kernels", "ga3c_get_desc",
            "ga3c_sched_create", "ga3c_sched_destroy", "ga3c_sched_submit_predict", "ga3c_sched_submit_trajectory",
+           "ga3c_sched_submit_predict_many", "ga3c_sched_submit_trajectory_many",
            "ga3c_sched_tick", "ga3c_sched_poll", "ga3c_sched_drain", "ga3c_sched_get_stats", "ga3c_sched_last_error",
            "ga3c_tuner_create", "ga3c_tuner_report", "ga3c_tuner_state", "ga3c_tuner_destroy")
 
@@ -145,6 +146,8 @@ def load_library() -> C.CDLL:
     lib.ga3c_sched_destroy.argtypes = [vp]
     lib.ga3c_sched_submit_predict.argtypes = [vp, i32, vp, f32]
     lib.ga3c_sched_submit_trajectory.argtypes = [vp, i32, vp, vp, vp, vp, f32]
+    lib.ga3c_sched_submit_predict_many.argtypes = [vp, i32, vp, vp, vp]
+    lib.ga3c_sched_submit_trajectory_many.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp]
     lib.ga3c_sched_tick.argtypes = [vp, C.POINTER(i32), C.POINTER(i32)]
     lib.ga3c_sched_poll.argtypes = [vp, C.POINTER(Prediction), i32]
     lib.ga3c_sched_drain.argtypes = [vp]
@@ -373,6 +376,35 @@ class Scheduler:
                                                        a.ctypes.data_as(C.c_void_p), r.ctypes.data_as(C.c_void_p),
                                                        d.ctypes.data_as(C.c_void_p), bootstrap),
                 "ga3c_sched_submit_trajectory")
+
+    def submit_predict_many(self, agents, frame_ptrs, uniforms) -> None:
+        """agents i32 [n], frame_ptrs u64 [n] (device addresses), uniforms f32 [n]: numpy arrays."""
+        import numpy as np
+        a = np.ascontiguousarray(agents, dtype=np.int32); p = np.ascontiguousarray(frame_ptrs, dtype=np.uint64)
+        u = np.ascontiguousarray(uniforms, dtype=np.float32)
+        _scheck(self._lib.ga3c_sched_submit_predict_many(self._s, a.size, a.ctypes.data_as(C.c_void_p),
+                                                         p.ctypes.data_as(C.c_void_p), u.ctypes.data_as(C.c_void_p)),
+                "ga3c_sched_submit_predict_many")
+
+    def submit_trajectory_many(self, agents, frame_ptrs, actions, rewards, dones, bootstrap) -> None:
+        import numpy as np
+        a = np.ascontiguousarray(agents, dtype=np.int32); p = np.ascontiguousarray(frame_ptrs, dtype=np.uint64)
+        ac = np.ascontiguousarray(actions, dtype=np.int32); r = np.ascontiguousarray(rewards, dtype=np.float32)
+        d = np.ascontiguousarray(dones, dtype=np.uint8); bo = np.ascontiguousarray(bootstrap, dtype=np.float32)
+        if ac.size != a.size * self.t_max or r.size != ac.size or d.size != ac.size or bo.size != a.size:
+            raise Ga3cError("trajectory arrays must be [n, t_max] and [n]")
+        _scheck(self._lib.ga3c_sched_submit_trajectory_many(
+            self._s, a.size, a.ctypes.data_as(C.c_void_p), p.ctypes.data_as(C.c_void_p),
+            ac.ctypes.data_as(C.c_void_p), r.ctypes.data_as(C.c_void_p), d.ctypes.data_as(C.c_void_p),
+            bo.ctypes.data_as(C.c_void_p)), "ga3c_sched_submit_trajectory_many")
+
+    def poll_arrays(self, cap: int = 4096):
+        """Finished predictions as numpy arrays (agents, actions, values)."""
+        import numpy as np
+        buf = (Prediction * cap)()
+        n = _scheck(self._lib.ga3c_sched_poll(self._s, buf, cap), "ga3c_sched_poll")
+        rec = np.frombuffer(buf, dtype=np.dtype([("agent", "<i4"), ("action", "<i4"), ("value", "<f4")]), count=n)
+        return rec["agent"].copy(), rec["action"].copy(), rec["value"].copy()
 
     def tick(self) -> Tuple[int, int]:
         p, t = C.c_int(), C.c_int()

@@ -436,6 +436,31 @@ extern "C" int ga3c_sched_submit_trajectory(ga3c_sched *s, int agent, const uint
     return GA3C_OK;
 }
 
+extern "C" int ga3c_sched_submit_predict_many(ga3c_sched *s, int n, const int32_t *agents,
+                                              const uint8_t *const *frames_dev, const float *uniforms) {
+    if (!s || n < 0 || (n > 0 && (!agents || !frames_dev || !uniforms)))
+        return sfail(GA3C_EINVAL, "ga3c_sched_submit_predict_many: bad argument");
+    for (int i = 0; i < n; ++i)
+        if (!frames_dev[i] || (((uintptr_t)frames_dev[i]) & 15))
+            return sfail(GA3C_EINVAL, "ga3c_sched_submit_predict_many: frame %d is null or not 16-byte aligned", i);
+    for (int i = 0; i < n; ++i) s->pq.push_back(PredReq{agents[i], frames_dev[i], uniforms[i]});
+    return GA3C_OK;
+}
+
+extern "C" int ga3c_sched_submit_trajectory_many(ga3c_sched *s, int n, const int32_t *agents,
+                                                 const uint8_t *const *frames_dev, const int32_t *actions,
+                                                 const float *rewards, const uint8_t *dones, const float *bootstrap) {
+    if (!s || n < 0 || (n > 0 && (!agents || !frames_dev || !actions || !rewards || !dones || !bootstrap)))
+        return sfail(GA3C_EINVAL, "ga3c_sched_submit_trajectory_many: bad argument");
+    const int T = s->cfg.t_max;
+    for (int i = 0; i < n; ++i) {
+        const int rc = ga3c_sched_submit_trajectory(s, agents[i], frames_dev[i], actions + (size_t)i * T,
+                                                    rewards + (size_t)i * T, dones + (size_t)i * T, bootstrap[i]);
+        if (rc != GA3C_OK) return rc;
+    }
+    return GA3C_OK;
+}
+
 extern "C" int ga3c_sched_tick(ga3c_sched *s, int *predicted, int *trained) {
     if (!s) return sfail(GA3C_EINVAL, "ga3c_sched_tick: null scheduler");
     int np = 0, nt = 0;
