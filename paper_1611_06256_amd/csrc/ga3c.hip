@@ -17,6 +17,7 @@
 #include "conv_frame.hpp"
 #include "dense_gemm.hpp"
 #include "conv1_bf16x3.hpp"
+#include "dense_gemm_bf16x6.hpp"
 
 using namespace ga3c;
 
@@ -713,7 +714,7 @@ int forward(ga3c_ctx *c, const float *th, Work &w, const uint8_t *frames, int B,
             p.A = x; p.lda = c->flat; p.B = wfc; p.ldb = c->flat;
             p.C = w.ws; p.ldc = c->F; p.aux = nullptr;
             if ((size_t)nz * B * c->F > w.ws_floats) return fail(GA3C_EINVAL, "internal: split-k workspace too small (fc)");
-            HIP_TRY((launch_dense_gemm<2, 2, 2, 2, false, false, DG_PARTIAL>(p, DG_SPLIT_Z, s)));
+            HIP_TRY((launch_dense_gemm_bf16x6<2, 2, 2, 2, false, false, DG_PARTIAL>(p, DG_SPLIT_Z, s)));
             fc_ws = w.ws; fc_nz = nz;
         } else {
             pick_split(cdiv(B, 64) * cdiv(c->F, 64), c->flat, nz, kchunk);
@@ -1099,7 +1100,7 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
             p.M = B; p.N = c->flat; p.K = F; p.kchunk = (F + GEMM_BK - 1) / GEMM_BK * GEMM_BK; p.nz = 1;
             p.A = c->dh; p.lda = F; p.B = wfc; p.ldb = c->flat;
             p.C = c->dact[c->nconv - 1]; p.ldc = c->flat; p.aux = xfc;
-            HIP_TRY((launch_dense_gemm<2, 2, 2, 2, false, true, DG_MASK>(p, DG_SPLIT_N, s)));
+            HIP_TRY((launch_dense_gemm_bf16x6<4, 2, 2, 2, false, true, DG_MASK>(p, DG_SPLIT_N, s)));
         } else {
             GemmP<EPI_MASK, false> p;
             p.M = B; p.N = c->flat; p.K = F; p.kchunk = (F + GEMM_BK - 1) / GEMM_BK * GEMM_BK;
