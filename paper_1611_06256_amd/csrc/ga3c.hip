@@ -47,7 +47,6 @@ extern "C" const char *ga3c_last_error(void) { return g_err; }
 
 namespace {
 
-constexpr int NORM_BLOCKS = 256;    // partial sums of the squared gradient norm
 constexpr int LOSS_THREADS = 64;    // frames per block in the returns/loss kernel
 
 struct Work {            // activations of one call; predict and train own one each
@@ -100,7 +99,8 @@ struct ga3c_ctx {
     float *dh;                    // dL/d(pre-activation) of the fc output
     float *dzv;                   // dL/d(logits, value) [cap][A+1]
     float *R;                     // returns [cap]
-    float *partials;              // NORM_BLOCKS + 3 * loss blocks
+    float *partials;              // one squared-norm partial per reduce block, then 3 per loss block
+    int max_norm_parts;
     float *colpart;               // per-block column sums of dh [cap/HD_FRAMES + 1][F]
     float *scale;                 // clip scale of the last step (1 float)
     ga3c_train_stats *stats;      // stats of the last step
@@ -403,84 +403,99 @@ __global__ __launch_bounds__(256) void heads_dgrad_kernel(const float *__restric
     }
 }
 
-// Adds the nz split-k partials ws[z][M][N].  Rows [r0, r1) go to
-// gW[(m-r0)*(N-1) + n] for n < N-1 and gb[m-r0] for n = N-1 (bias_col != 0),
-// or all N columns to gW[(m-r0)*N + n] (bias_col == 0).  A block handles
-// 32 outputs with 8 threads each; thread j adds z = j, j+8, ... in that order
-// and the 8 sums are then added in order of j, so the result is reproducible.
-__global__ __launch_bounds__(256) void reduce_wgrad_kernel(const float *__restrict__ ws, int nz, int M, int N, int r0,
-                                                           int r1, float *__restrict__ gW, float *__restrict__ gb,
-                                                           int bias_col) {
-    __shared__ float sh[8][33];
-    const int o = threadIdx.x & 31, zg = threadIdx.x >> 5;
-    const size_t cnt = (size_t)(r1 - r0) * N;
-    const size_t i = (size_t)blockIdx.x * 32 + o;
+// One launch adds up the partial weight gradients of every layer and, on the
+// way, the squares of the results (for the global norm).
+// A segment is a stack of nz partial matrices ws[z][M][N].  Rows [r0, r0+rows)
+// go to gW[(m-r0)*(N-1) + n] for n < N-1 and gb[m-r0] for n = N-1 (bias_col),
+// or all N columns to gW[(m-r0)*N + n] (no bias_col).  A block handles 256/zg
+// outputs with zg threads each: thread j adds z = j, j+zg, ... (eight loads in
+// flight at a time), then the zg sums are added in order of j.  Nothing depends
+// on timing, so the gradient is reproducible bit for bit.
+struct ReduceSeg {
+    const float *ws;
+    float *gW, *gb;
+    int nz, M, N, r0, rows, bias_col, zg, first_block;
+};
+constexpr int MAX_REDUCE_SEGS = 8;
+struct ReduceArgs {
+    ReduceSeg seg[MAX_REDUCE_SEGS];
+    int nseg;
+    float *normpart;     // one partial sum of squares per block
+};
+
+__global__ __launch_bounds__(256) void reduce_all_kernel(const ReduceArgs a) {
+    __shared__ float sh[256];
+    __shared__ float wsum[4];
+    int si = 0;
+    while (si + 1 < a.nseg && (int)blockIdx.x >= a.seg[si + 1].first_block) ++si;
+    const ReduceSeg &g = a.seg[si];
+    const int opb = 256 / g.zg;
+    const int o = threadIdx.x % opb, zi = threadIdx.x / opb;
+    const size_t cnt = (size_t)g.rows * g.N;
+    const size_t i = (size_t)(blockIdx.x - g.first_block) * opb + o;
     float s = 0.f;
     if (i < cnt) {
-        const size_t src = (size_t)r0 * N + i, stride = (size_t)M * N;
-        for (int z = zg; z < nz; z += 64) {         // 8 independent loads per round
+        const size_t src = (size_t)g.r0 * g.N + i, stride = (size_t)g.M * g.N;
+        for (int z = zi; z < g.nz; z += 8 * g.zg) {
             float v[8];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) v[j] = ws[(size_t)min(z + 8 * j, nz - 1) * stride + src];
+            for (int j = 0; j < 8; ++j) v[j] = g.ws[(size_t)min(z + j * g.zg, g.nz - 1) * stride + src];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) s += (z + 8 * j < nz) ? v[j] : 0.f;
+            for (int j = 0; j < 8; ++j) s += (z + j * g.zg < g.nz) ? v[j] : 0.f;
         }
     }
-    sh[zg][o] = s;
+    sh[threadIdx.x] = s;
     __syncthreads();
-    if (zg == 0 && i < cnt) {
-        float t = sh[0][o];
-#pragma unroll
-        for (int j = 1; j < 8; ++j) t += sh[j][o];
-        const int m = (int)(i / N), n = (int)(i % N);
-        if (!bias_col) gW[i] = t;                 // all N columns are weights
-        else if (n < N - 1) gW[(size_t)m * (N - 1) + n] = t;
-        else gb[m] = t;
+    float sq = 0.f;
+    if (zi == 0 && i < cnt) {
+        float t = sh[o];
+        for (int j = 1; j < g.zg; ++j) t += sh[j * opb + o];
+        const int m = (int)(i / g.N), n = (int)(i % g.N);
+        if (!g.bias_col) g.gW[i] = t;
+        else if (n < g.N - 1) g.gW[(size_t)m * (g.N - 1) + n] = t;
+        else g.gb[m] = t;
+        sq = t * t;
     }
+    sq = wave_sum(sq);
+    if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = sq;
+    __syncthreads();
+    if (threadIdx.x == 0) a.normpart[blockIdx.x] = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
 }
 
-// Block b sums the squares of its contiguous slice of grad.
-__global__ __launch_bounds__(256) void sqnorm_partial_kernel(const float *__restrict__ grad, size_t n,
-                                                             float *__restrict__ part) {
-    const size_t per = (n + gridDim.x - 1) / gridDim.x;
-    const size_t lo = per * blockIdx.x, hi = lo + per < n ? lo + per : n;
-    float s = 0.f;
-    for (size_t i = lo + threadIdx.x; i < hi; i += 8 * 256) {       // 8 independent loads per round
+// One block: total norm, clip scale s = min(1, c/||grad||) (c <= 0: off), and
+// the loss sums.  Writes scale[0], *own and, if not null, *user.
+__global__ __launch_bounds__(256) void finalize_kernel(const float *__restrict__ normpart, int nnorm,
+                                                       const float *__restrict__ losspart, int nloss, float clip,
+                                                       float *__restrict__ scale, ga3c_train_stats *own,
+                                                       ga3c_train_stats *user) {
+    __shared__ float sh[4][4];
+    const int tid = threadIdx.x;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};     // norm^2, policy loss, value loss, entropy
+    for (int i = tid; i < nnorm; i += 8 * 256) {
         float v[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) { const size_t k = i + 256 * j; v[j] = grad[k < hi ? k : hi - 1]; }
+        for (int j = 0; j < 8; ++j) v[j] = normpart[min(i + 256 * j, nnorm - 1)];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) s += (i + 256 * j < hi) ? v[j] * v[j] : 0.f;
+        for (int j = 0; j < 8; ++j) acc[0] += (i + 256 * j < nnorm) ? v[j] : 0.f;
     }
-    __shared__ float sh[4];
-    s = wave_sum(s);
-    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = s;
+    for (int i = tid; i < nloss; i += 256)
+        for (int c = 0; c < 3; ++c) acc[1 + c] += losspart[3 * i + c];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        acc[c] = wave_sum(acc[c]);
+        if ((tid & 63) == 0) sh[c][tid >> 6] = acc[c];
+    }
     __syncthreads();
-    if (threadIdx.x == 0) part[blockIdx.x] = sh[0] + sh[1] + sh[2] + sh[3];
-}
-
-// One wavefront: total norm, clip scale s = min(1, c/||grad||) (c <= 0: off),
-// and the loss sums.  Writes scale[0], *own and, if not null, *user.
-__global__ __launch_bounds__(64) void finalize_kernel(const float *__restrict__ normpart, int nnorm,
-                                                      const float *__restrict__ losspart, int nloss, float clip,
-                                                      float *__restrict__ scale, ga3c_train_stats *own,
-                                                      ga3c_train_stats *user) {
-    const int lane = threadIdx.x;
-    float s = 0.f;
-    for (int i = lane; i < nnorm; i += 64) s += normpart[i];
-    s = wave_sum(s);
-    float l[3] = {0.f, 0.f, 0.f};
-    for (int i = lane; i < nloss; i += 64)
-        for (int c = 0; c < 3; ++c) l[c] += losspart[3 * i + c];
-    for (int c = 0; c < 3; ++c) l[c] = wave_sum(l[c]);
-    if (lane == 0) {
-        const float norm = sqrtf(s);
+    if (tid == 0) {
+        float t[4];
+        for (int c = 0; c < 4; ++c) t[c] = (sh[c][0] + sh[c][1]) + (sh[c][2] + sh[c][3]);
+        const float norm = sqrtf(t[0]);
         float sc = 1.f;
         if (clip > 0.f && norm > clip) sc = clip / norm;
         const bool bad = !(norm <= 3.0e38f);
         scale[0] = sc;
         ga3c_train_stats st;
-        st.policy_loss = l[0]; st.value_loss = l[1]; st.entropy = l[2];
+        st.policy_loss = t[1]; st.value_loss = t[2]; st.entropy = t[3];
         st.grad_norm = norm; st.clip_scale = sc; st.nonfinite = bad ? 1 : 0;
         *own = st;
         if (user) *user = st;
@@ -590,7 +605,6 @@ struct ProfScope {
 
 const char *const CONV_FWD[GA3C_MAX_CONV] = {"conv1_fwd", "conv2_fwd", "conv3_fwd", "conv4_fwd"};
 const char *const CONV_WGRAD[GA3C_MAX_CONV] = {"conv1_wgrad", "conv2_wgrad", "conv3_wgrad", "conv4_wgrad"};
-const char *const CONV_WRED[GA3C_MAX_CONV] = {"conv1_wgrad_reduce", "conv2_wgrad_reduce", "conv3_wgrad_reduce", "conv4_wgrad_reduce"};
 const char *const CONV_DGRAD[GA3C_MAX_CONV] = {"conv1_dgrad", "conv2_dgrad", "conv3_dgrad", "conv4_dgrad"};
 
 inline unsigned blocks_for(size_t n, int per = 256) { return (unsigned)((n + per - 1) / per); }
@@ -610,9 +624,10 @@ inline void pick_split(int tiles, int K, int &nz, int &kchunk) {
 inline int cdiv(int a, int b) { return (a + b - 1) / b; }
 
 // k-chunks for the XCD-partitioned dense product: a multiple of 8 chunks (one
-// or more per XCD) when the reduction is long enough, about 512 blocks in all.
-inline void pick_split_xcd(int tiles, int K, int &nz, int &kchunk) {
-    int want = 8 * std::max(1, (512 + 8 * tiles - 1) / (8 * tiles));
+// or more per XCD) when the reduction is long enough, about `target` blocks in
+// all (fewer chunks mean fewer partial sums to write and add up again).
+inline void pick_split_xcd(int tiles, int K, int &nz, int &kchunk, int target = 512) {
+    int want = 8 * std::max(1, (target + 8 * tiles - 1) / (8 * tiles));
     const int maxz = std::max(1, K / (2 * GEMM_BK));
     if (want > maxz) want = maxz >= 8 ? maxz / 8 * 8 : maxz;
     kchunk = (K + want - 1) / want;
@@ -748,20 +763,22 @@ size_t workspace_floats(const ga3c_ctx *c, int cap, bool training) {
         need = std::max(need, (size_t)nz * B * c->F);
     }
     const int B = cap;
-    if (training && B > 0) {
+    if (training && B > 0) {       // every weight gradient has a region of its own (rounded up to 64 floats)
+        size_t sum = 0;
+        auto add = [&](size_t floats) { sum += (floats + 63) / 64 * 64; };
         int nz, kc;
         for (int l = 0; l < c->nconv; ++l) {
             const ConvGeom &g = c->geom[l];
             pick_split(conv_like_tiles(g.OC, g.K + 1), B * g.OHW, nz, kc);
-            need = std::max(need, (size_t)nz * g.OC * (g.K + 1));
-            need = std::max(need, (size_t)std::min(B, 512) * g.OC * (g.K + 1));   // frame-resident kernels
+            add((size_t)std::max(nz, std::min(B, 512)) * g.OC * (g.K + 1));      // generic or frame-resident kernel
         }
+        int nz2;
         pick_split(cdiv(c->F, 64) * cdiv(c->flat + 1, 64), B, nz, kc);
-        need = std::max(need, (size_t)nz * c->F * (c->flat + 1));
-        pick_split_xcd(cdiv(c->F, 64) * cdiv(c->flat, 64), B, nz, kc);
-        need = std::max(need, (size_t)nz * c->F * c->flat);
+        pick_split_xcd(cdiv(c->F, 64) * cdiv(c->flat, 64), B, nz2, kc, 256);
+        add((size_t)std::max(nz, nz2) * c->F * (c->flat + 1));
         pick_split(conv_like_tiles(c->A + 1, c->F + 1), B, nz, kc);
-        need = std::max(need, (size_t)nz * (c->A + 1) * (c->F + 1));
+        add((size_t)nz * (c->A + 1) * (c->F + 1));
+        need = std::max(need, sum);
     }
     return need;
 }
@@ -870,7 +887,8 @@ extern "C" int ga3c_create(const ga3c_net_desc *d, int max_predict_batch, int ma
         if (rc == GA3C_OK) guard(dmalloc((void **)&c->dh, sizeof(float) * B * c->F));
         if (rc == GA3C_OK) guard(dmalloc((void **)&c->dzv, sizeof(float) * B * (c->A + 1)));
         if (rc == GA3C_OK) guard(dmalloc((void **)&c->R, sizeof(float) * B));
-        if (rc == GA3C_OK) guard(dmalloc((void **)&c->partials, sizeof(float) * (NORM_BLOCKS + 3 * (B / LOSS_THREADS + 1))));
+        c->max_norm_parts = (int)(c->P / 4 + 16 * MAX_REDUCE_SEGS);   // a reduce block covers at least 4 outputs
+        if (rc == GA3C_OK) guard(dmalloc((void **)&c->partials, sizeof(float) * (c->max_norm_parts + 3 * (B / LOSS_THREADS + 1))));
         if (rc == GA3C_OK) guard(dmalloc((void **)&c->colpart, sizeof(float) * (B / HD_FRAMES + 1) * c->F));
         if (rc == GA3C_OK) guard(dmalloc((void **)&c->scale, sizeof(float)));
         if (rc == GA3C_OK) guard(dmalloc((void **)&c->stats, sizeof(ga3c_train_stats)));
@@ -1018,7 +1036,7 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
     if (rc != GA3C_OK) return rc;
 
     const int nloss = cdiv(B, LOSS_THREADS);
-    float *losspart = c->partials + NORM_BLOCKS;
+    float *losspart = c->partials + c->max_norm_parts;
     {
         STAGE("returns_loss", 0, 4.0 * B * (2 * (A + 1) + 4));
         hipLaunchKernelGGL(returns_loss_kernel, dim3(nloss), dim3(LOSS_THREADS), sizeof(float) * LOSS_THREADS * (A + 1), s, w.zv, actions, rewards, dones,
@@ -1028,6 +1046,26 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
 
     const float *Wp = th + c->off[nb + 2], *Wv = th + c->off[nb + 4];
     int nz, kchunk;
+    // Every weight gradient leaves its partial sums in a region of its own; one kernel adds them all up at the end.
+    ReduceArgs red;
+    red.nseg = 0; red.normpart = c->partials;
+    size_t ws_used = 0;
+    int red_blocks = 0;
+    double red_bytes = 0;
+    auto region = [&](size_t floats) -> float * {
+        float *r = ws_used + floats <= w.ws_floats ? w.ws + ws_used : nullptr;
+        ws_used += (floats + 63) / 64 * 64;
+        return r;
+    };
+    auto add_seg = [&](const float *ws, int nz_, int M, int Ncols, int r0, int rows, float *gW, float *gb, int bias_col) {
+        ReduceSeg &g = red.seg[red.nseg++];
+        g.ws = ws; g.nz = nz_; g.M = M; g.N = Ncols; g.r0 = r0; g.rows = rows; g.gW = gW; g.gb = gb; g.bias_col = bias_col;
+        int zg = 1;
+        while (zg < 64 && zg * 16 < nz_) zg *= 2;      // at most two rounds of eight loads per thread
+        g.zg = zg; g.first_block = red_blocks;
+        red_blocks += (int)(((size_t)rows * Ncols + 256 / zg - 1) / (256 / zg));
+        red_bytes += 4.0 * (nz_ + 1) * rows * Ncols;
+    };
     {   // heads: weight and bias gradients, dgrad
         GemmP<EPI_PARTIAL, true> p;
         p.M = A + 1; p.N = F + 1; p.K = B;
@@ -1035,19 +1073,14 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
         p.kchunk = kchunk;
         p.A = c->dzv; p.sAm = 1; p.sAk = A + 1;
         p.B = w.h; p.sBn = 1; p.sBk = F;
-        p.C = w.ws; p.ldc = 0; p.aux = nullptr;
-        if ((size_t)nz * p.M * p.N > w.ws_floats) return fail(GA3C_EINVAL, "internal: split-k workspace too small (heads)");
+        p.C = region((size_t)nz * p.M * p.N); p.ldc = 0; p.aux = nullptr;
+        if (!p.C) return fail(GA3C_EINVAL, "internal: split-k workspace too small (heads)");
         {
             STAGE("heads_wgrad", 2.0 * B * (A + 1) * F, 0);
             HIP_TRY(launch_conv_like(p, nz, s));
         }
-        {
-            STAGE("heads_wgrad_reduce", 0, 4.0 * (nz + 1) * (A + 1) * (F + 1));
-            hipLaunchKernelGGL(reduce_wgrad_kernel, dim3(blocks_for((size_t)A * (F + 1), 32)), dim3(256), 0, s, w.ws, nz,
-                               A + 1, F + 1, 0, A, c->grad + c->off[nb + 2], c->grad + c->off[nb + 3], 1);
-            hipLaunchKernelGGL(reduce_wgrad_kernel, dim3(blocks_for((size_t)(F + 1), 32)), dim3(256), 0, s, w.ws, nz, A + 1,
-                               F + 1, A, A + 1, c->grad + c->off[nb + 4], c->grad + c->off[nb + 5], 1);
-        }
+        add_seg(p.C, nz, A + 1, F + 1, 0, A, c->grad + c->off[nb + 2], c->grad + c->off[nb + 3], 1);
+        add_seg(p.C, nz, A + 1, F + 1, A, 1, c->grad + c->off[nb + 4], c->grad + c->off[nb + 5], 1);
         STAGE("heads_dgrad", 2.0 * B * (A + 1) * F, 0);
         hipLaunchKernelGGL(heads_dgrad_kernel, dim3(cdiv(B, HD_FRAMES)), dim3(256), sizeof(float) * (A + 1) * (F + HD_FRAMES), s, c->dzv, w.h, Wp, Wv, B,
                            F, A, c->dh, c->colpart);
@@ -1058,23 +1091,18 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
     const bool fc_dense = c->fast && dense_operand_ok(c->dh, F, F) && dense_operand_ok(xfc, c->flat, c->flat) &&
                           dense_operand_ok(wfc, c->flat, c->flat);
     if (fc_dense) {   // fc weight gradient: D[o][i] = sum_b dh[b][o] x[b][i]; bias from the column sums of dh
-        pick_split_xcd(cdiv(F, 64) * cdiv(c->flat, 64), B, nz, kchunk);
+        pick_split_xcd(cdiv(F, 64) * cdiv(c->flat, 64), B, nz, kchunk, 256);
         DenseGemmArgs p{};
         p.M = F; p.N = c->flat; p.K = B; p.kchunk = kchunk; p.nz = nz;
         p.A = c->dh; p.lda = F; p.B = xfc; p.ldb = c->flat;
-        p.C = w.ws; p.ldc = 0; p.aux = nullptr;
-        if ((size_t)nz * p.M * p.N > w.ws_floats) return fail(GA3C_EINVAL, "internal: split-k workspace too small (fc wgrad)");
+        p.C = region((size_t)nz * p.M * p.N); p.ldc = 0; p.aux = nullptr;
+        if (!p.C) return fail(GA3C_EINVAL, "internal: split-k workspace too small (fc wgrad)");
         {
             STAGE("fc_wgrad", 2.0 * B * F * c->flat, 0);
             HIP_TRY((launch_dense_gemm<2, 2, 2, 2, true, true, DG_PARTIAL>(p, DG_SPLIT_Z, s)));
         }
-        STAGE("fc_wgrad_reduce", 0, 4.0 * (nz + 1) * p.M * p.N);
-        hipLaunchKernelGGL(reduce_wgrad_kernel, dim3(blocks_for((size_t)p.M * p.N, 32)), dim3(256), 0, s, w.ws, nz, p.M,
-                           p.N, 0, p.M, c->grad + c->off[nb], (float *)nullptr, 0);
-        const int ncol = cdiv(B, HD_FRAMES);
-        hipLaunchKernelGGL(reduce_wgrad_kernel, dim3(blocks_for((size_t)F, 32)), dim3(256), 0, s, c->colpart, ncol, 1, F,
-                           0, 1, c->grad + c->off[nb + 1], (float *)nullptr, 0);
-        HIP_TRY(hipGetLastError());
+        add_seg(p.C, nz, p.M, p.N, 0, p.M, c->grad + c->off[nb], nullptr, 0);
+        add_seg(c->colpart, cdiv(B, HD_FRAMES), 1, F, 0, 1, c->grad + c->off[nb + 1], nullptr, 0);
     } else {   // general shapes: one more column of ones yields the bias gradient
         GemmP<EPI_PARTIAL, true> p;
         p.M = F; p.N = c->flat + 1; p.K = B;
@@ -1082,16 +1110,13 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
         p.kchunk = kchunk;
         p.A = c->dh; p.sAm = 1; p.sAk = F;
         p.B = xfc; p.sBn = 1; p.sBk = c->flat;
-        p.C = w.ws; p.ldc = 0; p.aux = nullptr;
-        if ((size_t)nz * p.M * p.N > w.ws_floats) return fail(GA3C_EINVAL, "internal: split-k workspace too small (fc wgrad)");
+        p.C = region((size_t)nz * p.M * p.N); p.ldc = 0; p.aux = nullptr;
+        if (!p.C) return fail(GA3C_EINVAL, "internal: split-k workspace too small (fc wgrad)");
         {
             STAGE("fc_wgrad", 2.0 * B * F * c->flat, 0);
             HIP_TRY((launch_gemm<2, 2, 2, 2, true, true>(p, nz, s)));
         }
-        STAGE("fc_wgrad_reduce", 0, 4.0 * (nz + 1) * p.M * p.N);
-        hipLaunchKernelGGL(reduce_wgrad_kernel, dim3(blocks_for((size_t)p.M * p.N, 32)), dim3(256), 0, s, w.ws, nz, p.M,
-                           p.N, 0, p.M, c->grad + c->off[nb], c->grad + c->off[nb + 1], 1);
-        HIP_TRY(hipGetLastError());
+        add_seg(p.C, nz, p.M, p.N, 0, p.M, c->grad + c->off[nb], c->grad + c->off[nb + 1], 1);
     }
     {   // fc input gradient, masked by the ReLU of the last conv layer
         STAGE("fc_dgrad", 2.0 * B * F * c->flat, 0);
@@ -1115,47 +1140,34 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
         // weight + bias gradient
         {
             const void *xin = l == 0 ? (const void *)frames : (const void *)w.act[l - 1];
-            bool done = false;
-            if (c->fast && is_aligned16(xin)) {
-                STAGE(CONV_WGRAD[l], 2.0 * B * g.OHW * g.OC * g.K, (double)B * ((l == 0 ? 1.0 : 4.0) * g.CHW + 4.0 * g.OC * g.OHW));
-                if (spec_matches<SpecS1>(g, l == 0) && is_aligned16(c->dact[l])) {
-                    nz = conv1_bf16x3_wgrad_blocks(B);
-                    HIP_TRY(launch_conv1_bf16x3_wgrad((const uint8_t *)xin, c->dact[l], w.ws, B, 1.f / 255.f, s));
-                    done = true;
-                } else if (spec_matches<SpecL1>(g, l == 0)) {
-                    nz = conv_wgrad_frame_blocks<SpecL1>(B);
-                    HIP_TRY(launch_conv_wgrad_frame<SpecL1>((const uint8_t *)xin, c->dact[l], w.ws, B, 1.f / 255.f, s));
-                    done = true;
-                } else if (spec_matches<SpecS2>(g, l == 0)) {
-                    nz = conv_wgrad_frame_blocks<SpecS2>(B);
-                    HIP_TRY(launch_conv_wgrad_frame<SpecS2>((const float *)xin, c->dact[l], w.ws, B, 1.f, s));
-                    done = true;
-                }
+            const bool ok = c->fast && is_aligned16(xin);
+            const int kind = !ok ? 0 : (spec_matches<SpecS1>(g, l == 0) && is_aligned16(c->dact[l])) ? 1
+                                     : spec_matches<SpecL1>(g, l == 0) ? 2 : spec_matches<SpecS2>(g, l == 0) ? 3 : 0;
+            if (kind == 1) nz = conv1_bf16x3_wgrad_blocks(B);
+            else if (kind == 2) nz = conv_wgrad_frame_blocks<SpecL1>(B);
+            else if (kind == 3) nz = conv_wgrad_frame_blocks<SpecS2>(B);
+            else pick_split(conv_like_tiles(g.OC, g.K + 1), B * g.OHW, nz, kchunk);
+            float *part = region((size_t)nz * g.OC * (g.K + 1));
+            if (!part) return fail(GA3C_EINVAL, "internal: split-k workspace too small (conv)");
+            STAGE(CONV_WGRAD[l], 2.0 * B * g.OHW * g.OC * g.K, (double)B * ((l == 0 ? 1.0 : 4.0) * g.CHW + 4.0 * g.OC * g.OHW));
+            if (kind == 1) {
+                HIP_TRY(launch_conv1_bf16x3_wgrad((const uint8_t *)xin, c->dact[l], part, B, 1.f / 255.f, s));
+            } else if (kind == 2) {
+                HIP_TRY(launch_conv_wgrad_frame<SpecL1>((const uint8_t *)xin, c->dact[l], part, B, 1.f / 255.f, s));
+            } else if (kind == 3) {
+                HIP_TRY(launch_conv_wgrad_frame<SpecS2>((const float *)xin, c->dact[l], part, B, 1.f, s));
+            } else if (l == 0) {
+                ConvWgradP<uint8_t> p;
+                p.M = g.OC; p.N = g.K + 1; p.K = B * g.OHW; p.kchunk = kchunk; p.g = g;
+                p.x = frames; p.dy = c->dact[0]; p.ws = part; p.scale = 1.f / 255.f;
+                HIP_TRY(launch_conv_like(p, nz, s));
+            } else {
+                ConvWgradP<float> p;
+                p.M = g.OC; p.N = g.K + 1; p.K = B * g.OHW; p.kchunk = kchunk; p.g = g;
+                p.x = w.act[l - 1]; p.dy = c->dact[l]; p.ws = part; p.scale = 1.f;
+                HIP_TRY(launch_conv_like(p, nz, s));
             }
-            if (done) goto wgrad_reduce;
-        }
-        pick_split(conv_like_tiles(g.OC, g.K + 1), B * g.OHW, nz, kchunk);
-        if ((size_t)nz * g.OC * (g.K + 1) > w.ws_floats) return fail(GA3C_EINVAL, "internal: split-k workspace too small (conv)");
-        {
-        STAGE(CONV_WGRAD[l], 2.0 * B * g.OHW * g.OC * g.K, 0);
-        if (l == 0) {
-            ConvWgradP<uint8_t> p;
-            p.M = g.OC; p.N = g.K + 1; p.K = B * g.OHW; p.kchunk = kchunk; p.g = g;
-            p.x = frames; p.dy = c->dact[0]; p.ws = w.ws; p.scale = 1.f / 255.f;
-            HIP_TRY(launch_conv_like(p, nz, s));
-        } else {
-            ConvWgradP<float> p;
-            p.M = g.OC; p.N = g.K + 1; p.K = B * g.OHW; p.kchunk = kchunk; p.g = g;
-            p.x = w.act[l - 1]; p.dy = c->dact[l]; p.ws = w.ws; p.scale = 1.f;
-            HIP_TRY(launch_conv_like(p, nz, s));
-        }
-        }
-    wgrad_reduce:
-        {
-            STAGE(CONV_WRED[l], 0, 4.0 * (nz + 1) * g.OC * (g.K + 1));
-            hipLaunchKernelGGL(reduce_wgrad_kernel, dim3(blocks_for((size_t)g.OC * (g.K + 1), 32)), dim3(256), 0, s, w.ws, nz,
-                               g.OC, g.K + 1, 0, g.OC, c->grad + c->off[2 * l], c->grad + c->off[2 * l + 1], 1);
-            HIP_TRY(hipGetLastError());
+            add_seg(part, nz, g.OC, g.K + 1, 0, g.OC, c->grad + c->off[2 * l], c->grad + c->off[2 * l + 1], 1);
         }
         if (l == 0) break;   // the input is data: no gradient needed
         // input gradient
@@ -1180,14 +1192,16 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
                 HIP_TRY(launch_conv_like(p, 1, s));
             }
     }
-    // global norm, clip scale, stats; then RMSProp
+    // all partial gradients -> gradient and its squared norm; then clip scale and stats; then RMSProp
+    if (red_blocks > c->max_norm_parts) return fail(GA3C_EINVAL, "internal: too many reduce blocks");
     {
-        STAGE("sqnorm", 2.0 * c->P, 4.0 * c->P);
-        hipLaunchKernelGGL(sqnorm_partial_kernel, dim3(NORM_BLOCKS), dim3(256), 0, s, c->grad, c->P, c->partials);
+        STAGE("wgrad_reduce", 0, red_bytes);
+        hipLaunchKernelGGL(reduce_all_kernel, dim3(red_blocks), dim3(256), 0, s, red);
+        HIP_TRY(hipGetLastError());
     }
     {
     STAGE("finalize", 0, 0);
-    hipLaunchKernelGGL(finalize_kernel, dim3(1), dim3(64), 0, s, c->partials, NORM_BLOCKS, losspart, nloss,
+    hipLaunchKernelGGL(finalize_kernel, dim3(1), dim3(256), 0, s, c->partials, red_blocks, losspart, nloss,
                        hp->clip_norm, c->scale, c->stats, stats);
     }
     STAGE("rmsprop", 8.0 * c->P, 20.0 * c->P);
