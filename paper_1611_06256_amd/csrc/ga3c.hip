@@ -18,6 +18,7 @@
 #include "dense_gemm.hpp"
 #include "conv1_bf16x3.hpp"
 #include "dense_gemm_bf16x6.hpp"
+#include "conv2_bf16x6.hpp"
 
 using namespace ga3c;
 
@@ -697,7 +698,7 @@ int forward(ga3c_ctx *c, const float *th, Work &w, const uint8_t *frames, int B,
                 continue;
             }
             if (spec_matches<SpecS2>(g, l == 0)) {
-                HIP_TRY(launch_conv_fwd_frame<SpecS2>((const float *)xin, wl, bl, w.act[l], B, 1.f, s));
+                HIP_TRY(launch_conv2_bf16x6_fwd((const float *)xin, wl, bl, w.act[l], B, s));
                 continue;
             }
         }
