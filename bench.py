@@ -29,6 +29,35 @@ if ROOT not in sys.path:
 PEAK_FP32_MFMA = 157.3e12   # MI355X dense fp32 matrix, FLOP/s
 PEAK_HBM = 8.0e12           # B/s
 
+# HBM traffic per launch from hardware counters: rocprofv3 --pmc FETCH_SIZE and --pmc WRITE_SIZE (two runs of
+# `python3 bench.py --steps 3 --warmup 1 --no-cpu-baseline --mixed-seconds 0 --rmsprop-big`), KiB per dispatch,
+# small net, by frames in the launch.  Every read request on this chip is a 128-byte line while FETCH_SIZE prices
+# it at 64 bytes: on the streaming RMSProp kernel over 2^28 parameters (12 B read, 8 B written per parameter) the
+# counters read 0.5000 and 1.0000 of the known bytes, hence the scale factors.  The summary is kept under profiles/.
+FETCH_SCALE, WRITE_SCALE = 2.0, 1.0
+COUNTER_KIB = {   # stage: {frames per launch: (FETCH_SIZE, WRITE_SIZE)}
+    "conv1_fwd": {512: (7305.2, 12806.4), 1024: (14377.3, 25630.1), 2560: (35593.2, 64110.6)},
+    "conv2_fwd": {512: (6698.0, 5184.0), 1024: (13098.0, 10368.7), 2560: (32298.0, 25922.8)},
+    "fc_fwd": {512: (4153.0, 7168.0), 1024: (6649.0, 8192.0), 2560: (14425.0, 20480.0)},
+    "heads_fwd": {512: (3778.3, 592.0), 1024: (4274.0, 1104.0), 2560: (10418.0, 2760.0)},
+    "conv1_wgrad": {2560: (67646.6, 4112.0)},
+    "conv2_wgrad": {2560: (45142.0, 16501.0)},
+    "conv2_dgrad": {2560: (45192.1, 64000.0)},
+    "fc_wgrad": {2560: (14305.3, 20736.4)},
+    "fc_dgrad": {2560: (25475.5, 28117.3)},
+    "wgrad_reduce": {2560: (48604.1, 2825.0)},
+    "rmsprop": {2560: (4010.1, 5320.6)},
+}
+
+
+def counter_traffic(stage, launches):
+    """Mean HBM bytes per launch of a stage over `launches` = [(frames, count), ...]; None where not measured."""
+    tab = COUNTER_KIB.get(stage)
+    if not tab or any(b not in tab for b, _ in launches):
+        return None
+    tot = sum(n * (FETCH_SCALE * tab[b][0] + WRITE_SCALE * tab[b][1]) * 1024.0 for b, n in launches)
+    return round(tot / sum(n for _, n in launches))
+
 
 def main() -> int:
     ap = argparse.ArgumentParser()
@@ -146,6 +175,10 @@ def main() -> int:
         roofline = {"kernel": dom["stage"], "bound": "hbm", "achieved": round(ach, 2), "peak": PEAK_HBM / 1e9,
                     "unit": "GB/s", "frac": round(ach * 1e9 / PEAK_HBM, 4), "traffic": None,
                     "ms_per_launch": round(dp["ms"] / dp["calls"], 5)}
+    if args.net == "small" and N == 512:
+        fwd = {"conv1_fwd", "conv2_fwd", "fc_fwd", "heads_fwd"}
+        roofline["traffic"] = counter_traffic(dom["stage"], [(N, T + 1), (N * T, 1)] if dom["stage"] in fwd else [(N * T, 1)])
+        roofline["algorithmic_bytes_per_launch"] = round(dp["bytes"] / dp["calls"]) if dp["bytes"] > 0 else None
     flop_step = sum(p["flop"] for p in prof.values()) / args.steps
     whole = {"tflops": round(flop_step / sec / 1e12, 3), "frac_fp32_mfma_peak": round(flop_step / sec / PEAK_FP32_MFMA, 4)}
 

@@ -260,6 +260,27 @@ def test_train_degenerate_inputs(G):
     net.close()
 
 
+def test_predict_full_size_sweep_end(G):
+    # largest batch of the prediction sweep (1024 frames, 18 actions, game-like frames), every frame checked
+    frames = synth.rectangle_frames_tiled(synth.BASE_SEED + 1, 1024)
+    check_predict(G, G.SMALL_NET(18), 1024, synth.BASE_SEED + 1, frames=frames)
+
+
+def test_train_full_size_512_agents(G):
+    # largest training step of the sweep, in the configuration the benchmark times: 512 agents x 5, clip 40
+    N, T = 512, 5
+    frames = synth.rectangle_frames_tiled(synth.BASE_SEED + 2, N * T).reshape(N, T, 4, 84, 84)
+    run_train(G, G.SMALL_NET(18), N, T, synth.BASE_SEED + 2, dict(clip_norm=40.0), frames=frames, g0_scale=1e-3)
+
+
+def test_large_net_full_size(G):
+    # larger CNN: predict 256, train 256 agents x 5
+    frames = synth.rectangle_frames_tiled(synth.BASE_SEED + 3, 256)
+    check_predict(G, G.LARGE_NET(18), 256, synth.BASE_SEED + 3, frames=frames)
+    tf = synth.rectangle_frames_tiled(synth.BASE_SEED + 4, 1280).reshape(256, 5, 4, 84, 84)
+    run_train(G, G.LARGE_NET(18), 256, 5, synth.BASE_SEED + 4, dict(clip_norm=40.0), frames=tf)
+
+
 def test_params_init_statistics_and_determinism(G):
     import torch
     net = G.Ga3c(G.SMALL_NET(18), 1, 0)
