@@ -1,0 +1,270 @@
+// First two convolution layers of the small network (paper Sec. 3.2) in one
+// kernel: 16 filters 8x8 stride 4 on the 4x84x84 byte frame, ReLU, 32 filters
+// 4x4 stride 2, ReLU.  The 16x20x20 activations between the two layers never
+// leave the compute unit unless the caller wants them (training keeps them for
+// the backward pass).
+//
+// Arithmetic as in conv1_bf16x3.hpp and conv2_bf16x6.hpp: bytes are exact in
+// bf16, fp32 numbers are split into three bf16 terms, products accumulate in
+// fp32 on v_mfma_f32_16x16x32_bf16.
+//
+// One block of 8 wavefronts per compute unit works as a two-stage pipeline:
+// wavefronts 0..3 run layer 1 of frame i (and split its output into three bf16
+// planes in LDS) while wavefronts 4..7 run layer 2 of frame i - 1 from the planes
+// written one iteration earlier.  The two groups hold only their own filters in
+// registers and share the matrix cores of each SIMD.
+//
+// LDS reads, not the matrix cores, bound this kernel, so the layout serves them:
+//  * the planes hold each channel as 2x2 pixel blocks, [row pair][column pair]
+//    [2][2]: the 2 rows x 4 columns a lane feeds to one MFMA are 16 contiguous
+//    bytes (the filter taps are permuted to that order when they are loaded);
+//  * a layer-2 wavefront computes both filter tiles from one fetch of the
+//    activations and takes half of the 256 taps instead; the two wavefronts of
+//    a pair swap half of their partial sums through LDS and finish one filter
+//    tile each, one iteration later, so that no extra barrier is needed.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "conv1_bf16x3.hpp"
+
+namespace ga3c {
+
+constexpr int C12_XS = 7 * 256 * 16;                 // bf16 elements of the staged frame (28 224 used)
+constexpr int C12_Y1 = 16 * 400;                     // elements of one plane of the layer-1 output
+constexpr int C12_EX = 4 * 3 * 4 * 64;               // floats one exchange buffer holds: [wavefront][tile][r][lane]
+constexpr size_t C12_LDS_BYTES = sizeof(__bf16) * (C12_XS + 2 * 3 * C12_Y1) + sizeof(float) * 2 * C12_EX;
+
+// x: [n][4][84][84] bytes; w1 [16][256], b1 [16]; w2 [32][256], b2 [32];
+// y1: [n][16][400] or nullptr; y2: [n][32][81].  Frames blockIdx.x, + gridDim.x, ...
+__global__ __launch_bounds__(512, 1) void conv12_fused_fwd_kernel(const uint8_t *__restrict__ x,
+                                                                  const float *__restrict__ w1,
+                                                                  const float *__restrict__ b1,
+                                                                  const float *__restrict__ w2,
+                                                                  const float *__restrict__ b2, float *__restrict__ y1,
+                                                                  float *__restrict__ y2, int nframes, float scale) {
+    constexpr int K = 256;
+    constexpr int CHW1 = 4 * 84 * 84, W1 = 84, NPIX1 = 400, OW1 = 20;
+    constexpr int NV = CHW1 / 16, VPT = 7;                         // 16-byte vectors of a frame, per layer-1 thread
+    constexpr int HW2 = 400, NPIX2 = 81, OW2 = 9, OC2 = 32;
+    extern __shared__ __attribute__((aligned(16))) unsigned char c12_smem[];
+    __bf16 *xs = (__bf16 *)c12_smem;
+    __bf16 *ys = xs + C12_XS;                                      // [2][3][C12_Y1]
+    float *exb = (float *)(ys + 2 * 3 * C12_Y1);                   // [2][C12_EX]
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool layer1 = wave < 4;
+    const int rw = wave & 3;                                       // wavefront within its group
+    const int rt = tid & 255;                                      // thread within its group
+    const int l16 = lane & 15, g = lane >> 4;
+    const int pg = rw >> 1, kh = rw & 1;                           // layer 2: pixel tiles pg, pg+2, pg+4; taps 128 kh ..
+
+    // Filter rows split into three bf16 terms, 8 taps per lane and slot.
+    // Layer 1: slot j = tap block j of filter l16 (taps 32 j + 8 g ..).
+    // Layer 2: slot j = tap block 4 kh + j/2 of filter 16 (j%2) + l16, taps in the
+    // order of a 2x2-block pair: (r0c0 r0c1 r1c0 r1c1 r0c2 r0c3 r1c2 r1c3).
+    bf16x8 wq[3][8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const float *src = layer1 ? w1 + (size_t)l16 * K + 32 * j + 8 * g
+                                  : w2 + (size_t)((j & 1) * 16 + l16) * K + 32 * (4 * kh + (j >> 1)) + 8 * g;
+        const float4 a = *(const float4 *)src, b = *(const float4 *)(src + 4);
+        const float f[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+        constexpr int PERM[8] = {0, 1, 4, 5, 2, 3, 6, 7};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            __bf16 h, m, l;
+            split3(layer1 ? f[e] : f[PERM[e]], h, m, l);
+            wq[0][j][e] = h; wq[1][j][e] = m; wq[2][j][e] = l;
+        }
+    }
+    float bv[4];                                                   // layer 2 finishes filter tile kh
+#pragma unroll
+    for (int r = 0; r < 4; ++r) bv[r] = layer1 ? b1[4 * g + r] : b2[kh * 16 + 4 * g + r];
+
+    const int grid = gridDim.x;
+    const int n = (nframes - (int)blockIdx.x + grid - 1) / grid;  // frames of this block (>= 1)
+
+    u32x4 pre[VPT];
+    int vidx[VPT];
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) vidx[i] = min(rt + 256 * i, NV - 1);
+    if (layer1) {
+        const u32x4 *src = (const u32x4 *)(x + (size_t)blockIdx.x * CHW1);
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) pre[i] = src[vidx[i]];
+    }
+    floatx4 keep[3];                                               // layer 2: my filter tile's sums of the previous frame
+#pragma unroll
+    for (int i = 0; i < 3; ++i) keep[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    // iteration it: layer 1 of frame it, layer 2 of frame it - 1, last step of layer 2 of frame it - 2
+    for (int it = 0; it <= n + 1; ++it) {
+        __syncthreads();          // layer 1 of the previous frame has read xs; layer 2 has read its planes
+        if (layer1 && it < n) {
+#pragma unroll
+            for (int i = 0; i < VPT; ++i) {
+                u32x4 a, b;
+                bytes_to_bf16(pre[i], a, b);
+                u32x4 *dst = (u32x4 *)(xs + (size_t)(rt + 256 * i) * 16);
+                dst[0] = a; dst[1] = b;
+            }
+        }
+        __syncthreads();
+        if (layer1) {
+            if (it < n) {
+                const int f = blockIdx.x + it * grid;
+                {
+                    const u32x4 *src = (const u32x4 *)(x + (size_t)min(f + grid, nframes - 1) * CHW1);
+#pragma unroll
+                    for (int i = 0; i < VPT; ++i) pre[i] = src[vidx[i]];
+                }
+                __bf16 *yp = ys + (it & 1) * 3 * C12_Y1;
+                float *yb = y1 ? y1 + (size_t)f * 16 * NPIX1 : nullptr;
+                // pixel tiles rw, rw + 4, ...: 25 tiles, wavefront 0 takes seven, the others six.
+                // Six independent accumulators: consecutive MFMAs never depend on each other.
+                auto tile_base = [&](int t) {
+                    const int p = t * 16 + l16;
+                    return (p / OW1) * 4 * W1 + (p % OW1) * 4 + g * W1;
+                };
+                auto operand = [&](int base, int kb) {
+                    const __bf16 *src = xs + base + (kb / 2) * (84 * 84) + 4 * (kb % 2) * W1;   // 8-byte aligned
+                    const uint2 lo = *(const uint2 *)src, hi = *(const uint2 *)(src + 4);
+                    Bf16x8Bits xv;
+                    xv.u = u32x4{lo.x, lo.y, hi.x, hi.y};
+                    return xv.v;
+                };
+                auto finish = [&](int t, const floatx4 acc) {
+                    const int p = t * 16 + l16;
+                    const int row = p / OW1, col = p % OW1;
+                    const int blk = (row >> 1) * 40 + (col >> 1) * 4 + (row & 1) * 2 + (col & 1);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        float v = acc[r] * scale + bv[r];
+                        v = v > 0.f ? v : 0.f;
+                        if (yb) yb[(4 * g + r) * NPIX1 + p] = v;
+                        __bf16 h, m, l;
+                        split3(v, h, m, l);
+                        const int e = (4 * g + r) * HW2 + blk;
+                        yp[e] = h; yp[C12_Y1 + e] = m; yp[2 * C12_Y1 + e] = l;
+                    }
+                };
+                {
+                    int base[6];
+                    floatx4 acc[6];
+#pragma unroll
+                    for (int j = 0; j < 6; ++j) {
+                        base[j] = tile_base(rw + 4 * j);
+                        acc[j] = floatx4{0.f, 0.f, 0.f, 0.f};
+                    }
+#pragma unroll
+                    for (int kb = 0; kb < 8; ++kb) {
+                        bf16x8 xv[6];
+#pragma unroll
+                        for (int j = 0; j < 6; ++j) xv[j] = operand(base[j], kb);
+#pragma unroll
+                        for (int term = 2; term >= 0; --term)
+#pragma unroll
+                            for (int j = 0; j < 6; ++j)
+                                acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wq[term][kb], xv[j], acc[j], 0, 0, 0);
+                    }
+#pragma unroll
+                    for (int j = 0; j < 6; ++j) finish(rw + 4 * j, acc[j]);
+                }
+                if (rw == 0) {
+                    const int base = tile_base(24);
+                    floatx4 acc = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int kb = 0; kb < 8; ++kb) {
+                        const bf16x8 xv = operand(base, kb);
+#pragma unroll
+                        for (int term = 2; term >= 0; --term)
+                            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wq[term][kb], xv, acc, 0, 0, 0);
+                    }
+                    finish(24, acc);
+                }
+            }
+        } else {
+            if (it >= 2) {       // frame it - 2: add what my partner summed over its taps, bias, ReLU, store
+                const float *ex = exb + ((it - 1) & 1) * C12_EX + (rw ^ 1) * (3 * 4 * 64);
+                float *yb = y2 + (size_t)(blockIdx.x + (it - 2) * grid) * OC2 * NPIX2;
+#pragma unroll
+                for (int i = 0; i < 3; ++i) {
+                    const int p = (pg + 2 * i) * 16 + l16;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const float v = keep[i][r] + ex[(i * 4 + r) * 64 + lane] + bv[r];
+                        if (p < NPIX2) yb[(kh * 16 + 4 * g + r) * NPIX2 + p] = v > 0.f ? v : 0.f;
+                    }
+                }
+            }
+            if (it >= 1 && it <= n) {
+                const __bf16 *yp = ys + ((it - 1) & 1) * 3 * C12_Y1;
+                // a lane's taps of block kb: channel 2 kb + g/2, window rows 2 (g%2) and 2 (g%2) + 1, 4 columns,
+                // = column pairs ox and ox + 1 of row pair oy + g%2
+                floatx4 acc[3][2];
+                int off[3];
+#pragma unroll
+                for (int i = 0; i < 3; ++i) {
+                    int p = (pg + 2 * i) * 16 + l16;
+                    if (p >= NPIX2) p = 0;
+                    off[i] = (g / 2) * HW2 + ((p / OW2) + (g % 2)) * 40 + (p % OW2) * 4 + 2 * (4 * kh) * HW2;
+                    acc[i][0] = floatx4{0.f, 0.f, 0.f, 0.f};
+                    acc[i][1] = floatx4{0.f, 0.f, 0.f, 0.f};
+                }
+#pragma unroll
+                for (int kbl = 0; kbl < 4; ++kbl) {
+                    Bf16x8Bits xv[3][3];                             // [tile][term]
+#pragma unroll
+                    for (int i = 0; i < 3; ++i) {
+#pragma unroll
+                        for (int term = 0; term < 3; ++term) {
+                            const uint2 *q = (const uint2 *)(yp + term * C12_Y1 + off[i] + 2 * kbl * HW2);   // 8-byte aligned
+                            const uint2 lo = q[0], hi = q[1];
+                            xv[i][term].u = u32x4{lo.x, lo.y, hi.x, hi.y};
+                        }
+                    }
+                    // the six largest term products, smallest first; six accumulators alternate
+                    constexpr int WT[6] = {2, 1, 0, 1, 0, 0}, XT[6] = {0, 1, 2, 0, 1, 0};
+#pragma unroll
+                    for (int q = 0; q < 6; ++q)
+#pragma unroll
+                        for (int i = 0; i < 3; ++i)
+#pragma unroll
+                            for (int o = 0; o < 2; ++o)
+                                acc[i][o] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wq[WT[q]][2 * kbl + o], xv[i][XT[q]].v,
+                                                                                    acc[i][o], 0, 0, 0);
+                }
+                // my partner finishes the other filter tile
+                float *ex = exb + (it & 1) * C12_EX + rw * (3 * 4 * 64);
+#pragma unroll
+                for (int i = 0; i < 3; ++i) {
+                    const floatx4 mine = kh ? acc[i][1] : acc[i][0], other = kh ? acc[i][0] : acc[i][1];
+                    keep[i] = mine;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) ex[(i * 4 + r) * 64 + lane] = other[r];
+                }
+            }
+        }
+    }
+}
+
+inline int conv12_fused_blocks(int nframes) { return nframes < 256 ? nframes : 256; }
+
+inline hipError_t launch_conv12_fused_fwd(const uint8_t *x, const float *w1, const float *b1, const float *w2,
+                                          const float *b2, float *y1, float *y2, int nframes, float scale, hipStream_t s) {
+    if (nframes <= 0) return hipSuccess;
+    static bool attr_set = false;     // the kernel needs more LDS than the default limit
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)conv12_fused_fwd_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)C12_LDS_BYTES);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(conv12_fused_fwd_kernel, dim3(conv12_fused_blocks(nframes)), dim3(512), C12_LDS_BYTES, s, x, w1, b1,
+                       w2, b2, y1, y2, nframes, scale);
+    return hipGetLastError();
+}
+
+}  // namespace ga3c

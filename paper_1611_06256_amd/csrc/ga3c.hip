@@ -19,6 +19,7 @@
 #include "conv1_bf16x3.hpp"
 #include "dense_gemm_bf16x6.hpp"
 #include "conv2_bf16x6.hpp"
+#include "conv12_fused.hpp"
 
 using namespace ga3c;
 
@@ -683,7 +684,18 @@ inline bool is_aligned16(const void *p) { return (((uintptr_t)p) & 15) == 0; }
 int forward(ga3c_ctx *c, const float *th, Work &w, const uint8_t *frames, int B, bool keep_zv, float *logits, float *values,
             float *probs, const float *uniforms, int32_t *actions, hipStream_t s) {
     const int nb = 2 * c->nconv;
-    for (int l = 0; l < c->nconv; ++l) {
+    int first = 0;
+    if (c->fast && c->nconv >= 2 && spec_matches<SpecS1>(c->geom[0], true) && spec_matches<SpecS2>(c->geom[1], false) &&
+        is_aligned16(frames) && is_aligned16(th + c->off[0]) && is_aligned16(th + c->off[2])) {
+        // small net: both convolution layers in one kernel; layer-1 activations go to HBM only when training
+        const ConvGeom &g0 = c->geom[0], &g1 = c->geom[1];
+        STAGE("conv12_fwd", 2.0 * B * (g0.OHW * g0.OC * g0.K + g1.OHW * g1.OC * g1.K),
+              (double)B * (g0.CHW + (keep_zv ? 4.0 * g0.OC * g0.OHW : 0.0) + 4.0 * g1.OC * g1.OHW));
+        HIP_TRY(launch_conv12_fused_fwd(frames, th + c->off[0], th + c->off[1], th + c->off[2], th + c->off[3],
+                                        keep_zv ? w.act[0] : nullptr, w.act[1], B, 1.f / 255.f, s));
+        first = 2;
+    }
+    for (int l = first; l < c->nconv; ++l) {
         const ConvGeom &g = c->geom[l];
         STAGE(CONV_FWD[l], 2.0 * B * g.OHW * g.OC * g.K, (double)B * ((l == 0 ? 1.0 : 4.0) * g.CHW + 4.0 * g.OC * g.OHW));
         const float *wl = th + c->off[2 * l], *bl = th + c->off[2 * l + 1];
