@@ -35,15 +35,53 @@ constexpr int C12_Y1 = 16 * 400;                     // elements of one plane of
 constexpr int C12_EX = 4 * 3 * 4 * 64;               // floats one exchange buffer holds: [wavefront][tile][r][lane]
 constexpr size_t C12_LDS_BYTES = sizeof(__bf16) * (C12_XS + 2 * 3 * C12_Y1) + sizeof(float) * 2 * C12_EX;
 
-// x: [n][4][84][84] bytes; w1 [16][256], b1 [16]; w2 [32][256], b2 [32];
+constexpr int C12_FRAG_SET = 3 * 8 * 64;             // 16-byte vectors of one fragment set: [term][slot][lane]
+
+// Filters of both layers as MFMA operand fragments, split into three bf16 terms
+// (w = hi + mid + lo exactly), in the order the forward kernel's lanes hold them.
+// Set 0: layer 1, slot j = tap block j of filter l16 (taps 32 j + 8 g ..).
+// Sets 1 + kh: layer 2, slot j = tap block 4 kh + j/2 of filter 16 (j%2) + l16, taps in the
+// order of a 2x2-block pair: (r0c0 r0c1 r1c0 r1c1 r0c2 r0c3 r1c2 r1c3).
+// One block of 192 threads; runs whenever the parameters change.
+__global__ __launch_bounds__(192) void conv12_filter_fragments_kernel(const float *__restrict__ w1,
+                                                                      const float *__restrict__ w2,
+                                                                      u32x4 *__restrict__ frag) {
+    constexpr int K = 256;
+    const int lane = threadIdx.x & 63, set = threadIdx.x >> 6;
+    const int l16 = lane & 15, g = lane >> 4, kh = set - 1;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const float *src = set == 0 ? w1 + (size_t)l16 * K + 32 * j + 8 * g
+                                    : w2 + (size_t)((j & 1) * 16 + l16) * K + 32 * (4 * kh + (j >> 1)) + 8 * g;
+        const float4 a = *(const float4 *)src, b = *(const float4 *)(src + 4);
+        const float f[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+        constexpr int PERM[8] = {0, 1, 4, 5, 2, 3, 6, 7};
+        Bf16x8Bits h, m, l;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            __bf16 th, tm, tl;
+            split3(set == 0 ? f[e] : f[PERM[e]], th, tm, tl);
+            h.v[e] = th; m.v[e] = tm; l.v[e] = tl;
+        }
+        u32x4 *dst = frag + (size_t)set * C12_FRAG_SET + lane;
+        dst[(0 * 8 + j) * 64] = h.u;
+        dst[(1 * 8 + j) * 64] = m.u;
+        dst[(2 * 8 + j) * 64] = l.u;
+    }
+}
+
+inline hipError_t launch_conv12_filter_fragments(const float *w1, const float *w2, u32x4 *frag, hipStream_t s) {
+    hipLaunchKernelGGL(conv12_filter_fragments_kernel, dim3(1), dim3(192), 0, s, w1, w2, frag);
+    return hipGetLastError();
+}
+
+// x: [n][4][84][84] bytes; frag: the three fragment sets; b1 [16], b2 [32];
 // y1: [n][16][400] or nullptr; y2: [n][32][81].  Frames blockIdx.x, + gridDim.x, ...
 __global__ __launch_bounds__(512, 1) void conv12_fused_fwd_kernel(const uint8_t *__restrict__ x,
-                                                                  const float *__restrict__ w1,
+                                                                  const u32x4 *__restrict__ frag,
                                                                   const float *__restrict__ b1,
-                                                                  const float *__restrict__ w2,
                                                                   const float *__restrict__ b2, float *__restrict__ y1,
                                                                   float *__restrict__ y2, int nframes, float scale) {
-    constexpr int K = 256;
     constexpr int CHW1 = 4 * 84 * 84, W1 = 84, NPIX1 = 400, OW1 = 20;
     constexpr int NV = CHW1 / 16, VPT = 7;                         // 16-byte vectors of a frame, per layer-1 thread
     constexpr int HW2 = 400, NPIX2 = 81, OW2 = 9, OC2 = 32;
@@ -60,32 +98,7 @@ __global__ __launch_bounds__(512, 1) void conv12_fused_fwd_kernel(const uint8_t 
     const int l16 = lane & 15, g = lane >> 4;
     const int pg = rw >> 1, kh = rw & 1;                           // layer 2: pixel tiles pg, pg+2, pg+4; taps 128 kh ..
 
-    // Filter rows split into three bf16 terms, 8 taps per lane and slot.
-    // Layer 1: slot j = tap block j of filter l16 (taps 32 j + 8 g ..).
-    // Layer 2: slot j = tap block 4 kh + j/2 of filter 16 (j%2) + l16, taps in the
-    // order of a 2x2-block pair: (r0c0 r0c1 r1c0 r1c1 r0c2 r0c3 r1c2 r1c3).
-    bf16x8 wq[3][8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const float *src = layer1 ? w1 + (size_t)l16 * K + 32 * j + 8 * g
-                                  : w2 + (size_t)((j & 1) * 16 + l16) * K + 32 * (4 * kh + (j >> 1)) + 8 * g;
-        const float4 a = *(const float4 *)src, b = *(const float4 *)(src + 4);
-        const float f[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-        constexpr int PERM[8] = {0, 1, 4, 5, 2, 3, 6, 7};
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            __bf16 h, m, l;
-            split3(layer1 ? f[e] : f[PERM[e]], h, m, l);
-            wq[0][j][e] = h; wq[1][j][e] = m; wq[2][j][e] = l;
-        }
-    }
-    float bv[4];                                                   // layer 2 finishes filter tile kh
-#pragma unroll
-    for (int r = 0; r < 4; ++r) bv[r] = layer1 ? b1[4 * g + r] : b2[kh * 16 + 4 * g + r];
-
-    const int grid = gridDim.x;
-    const int n = (nframes - (int)blockIdx.x + grid - 1) / grid;  // frames of this block (>= 1)
-
+    // the first frame is requested before anything else, so that it travels while the filters are prepared
     u32x4 pre[VPT];
     int vidx[VPT];
 #pragma unroll
@@ -95,6 +108,27 @@ __global__ __launch_bounds__(512, 1) void conv12_fused_fwd_kernel(const uint8_t 
 #pragma unroll
         for (int i = 0; i < VPT; ++i) pre[i] = src[vidx[i]];
     }
+
+    // my filter fragments, split into three bf16 terms ahead of time (conv12_filter_fragments_kernel)
+    bf16x8 wq[3][8];
+    {
+        const u32x4 *src = frag + (size_t)(layer1 ? 0 : 1 + kh) * C12_FRAG_SET + lane;
+#pragma unroll
+        for (int t = 0; t < 3; ++t)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                Bf16x8Bits v;
+                v.u = src[(t * 8 + j) * 64];
+                wq[t][j] = v.v;
+            }
+    }
+    float bv[4];                                                   // layer 2 finishes filter tile kh
+#pragma unroll
+    for (int r = 0; r < 4; ++r) bv[r] = layer1 ? b1[4 * g + r] : b2[kh * 16 + 4 * g + r];
+
+    const int grid = gridDim.x;
+    const int n = (nframes - (int)blockIdx.x + grid - 1) / grid;  // frames of this block (>= 1)
+
     floatx4 keep[3];                                               // layer 2: my filter tile's sums of the previous frame
 #pragma unroll
     for (int i = 0; i < 3; ++i) keep[i] = floatx4{0.f, 0.f, 0.f, 0.f};
@@ -252,8 +286,8 @@ __global__ __launch_bounds__(512, 1) void conv12_fused_fwd_kernel(const uint8_t 
 
 inline int conv12_fused_blocks(int nframes) { return nframes < 256 ? nframes : 256; }
 
-inline hipError_t launch_conv12_fused_fwd(const uint8_t *x, const float *w1, const float *b1, const float *w2,
-                                          const float *b2, float *y1, float *y2, int nframes, float scale, hipStream_t s) {
+inline hipError_t launch_conv12_fused_fwd(const uint8_t *x, const u32x4 *frag, const float *b1, const float *b2, float *y1,
+                                          float *y2, int nframes, float scale, hipStream_t s) {
     if (nframes <= 0) return hipSuccess;
     static bool attr_set = false;     // the kernel needs more LDS than the default limit
     if (!attr_set) {
@@ -262,8 +296,8 @@ inline hipError_t launch_conv12_fused_fwd(const uint8_t *x, const float *w1, con
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(conv12_fused_fwd_kernel, dim3(conv12_fused_blocks(nframes)), dim3(512), C12_LDS_BYTES, s, x, w1, b1,
-                       w2, b2, y1, y2, nframes, scale);
+    hipLaunchKernelGGL(conv12_fused_fwd_kernel, dim3(conv12_fused_blocks(nframes)), dim3(512), C12_LDS_BYTES, s, x, frag, b1,
+                       b2, y1, y2, nframes, scale);
     return hipGetLastError();
 }
 

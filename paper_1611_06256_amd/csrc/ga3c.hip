@@ -95,6 +95,9 @@ struct ga3c_ctx {
     hipStream_t ready_stream[2], readers_stream[2];   // where each event was last recorded
     bool ready_set[2], readers_set[2];
     float *g, *grad;
+    // small net: conv1/conv2 filters of each parameter copy as split MFMA fragments (nullptr for other nets);
+    // refreshed by whoever writes the copy
+    u32x4 *cfrag[2];
     Work pred, train;
     // training only
     float *dact[GA3C_MAX_CONV];   // dL/d(pre-activation) of each conv output
@@ -680,18 +683,25 @@ inline bool spec_matches(const ConvGeom &g, bool byte_input) {
 }
 inline bool is_aligned16(const void *p) { return (((uintptr_t)p) & 15) == 0; }
 
+// Things derived from parameter copy i, rebuilt on s after that copy was written there.
+int refresh_derived(ga3c_ctx *c, int i, hipStream_t s) {
+    if (c->cfrag[i])
+        HIP_TRY(launch_conv12_filter_fragments(c->theta2[i] + c->off[0], c->theta2[i] + c->off[2], c->cfrag[i], s));
+    return GA3C_OK;
+}
+
 // Forward pass of `B` frames into `w`; heads outputs to the optional pointers.
-int forward(ga3c_ctx *c, const float *th, Work &w, const uint8_t *frames, int B, bool keep_zv, float *logits, float *values,
+int forward(ga3c_ctx *c, int which, Work &w, const uint8_t *frames, int B, bool keep_zv, float *logits, float *values,
             float *probs, const float *uniforms, int32_t *actions, hipStream_t s) {
+    const float *th = c->theta2[which];
     const int nb = 2 * c->nconv;
     int first = 0;
-    if (c->fast && c->nconv >= 2 && spec_matches<SpecS1>(c->geom[0], true) && spec_matches<SpecS2>(c->geom[1], false) &&
-        is_aligned16(frames) && is_aligned16(th + c->off[0]) && is_aligned16(th + c->off[2])) {
+    if (c->fast && c->cfrag[which] && is_aligned16(frames)) {
         // small net: both convolution layers in one kernel; layer-1 activations go to HBM only when training
         const ConvGeom &g0 = c->geom[0], &g1 = c->geom[1];
         STAGE("conv12_fwd", 2.0 * B * (g0.OHW * g0.OC * g0.K + g1.OHW * g1.OC * g1.K),
               (double)B * (g0.CHW + (keep_zv ? 4.0 * g0.OC * g0.OHW : 0.0) + 4.0 * g1.OC * g1.OHW));
-        HIP_TRY(launch_conv12_fused_fwd(frames, th + c->off[0], th + c->off[1], th + c->off[2], th + c->off[3],
+        HIP_TRY(launch_conv12_fused_fwd(frames, c->cfrag[which], th + c->off[1], th + c->off[3],
                                         keep_zv ? w.act[0] : nullptr, w.act[1], B, 1.f / 255.f, s));
         first = 2;
     }
@@ -891,6 +901,13 @@ extern "C" int ga3c_create(const ga3c_net_desc *d, int max_predict_batch, int ma
         if (e == hipSuccess) e = hipMemset(c->grad, 0, sizeof(float) * c->P);
         if (e != hipSuccess) guard(fail(GA3C_EHIP, "hipMemset: %s", hipGetErrorString(e)));
     }
+    if (rc == GA3C_OK && c->nconv >= 2 && spec_matches<SpecS1>(c->geom[0], true) && spec_matches<SpecS2>(c->geom[1], false) &&
+        c->off[0] % 4 == 0 && c->off[2] % 4 == 0) {
+        for (int i = 0; i < 2 && rc == GA3C_OK; ++i) {
+            guard(dmalloc((void **)&c->cfrag[i], sizeof(u32x4) * 3 * C12_FRAG_SET));
+            if (rc == GA3C_OK) guard(refresh_derived(c, i, nullptr));
+        }
+    }
     if (rc == GA3C_OK) guard(alloc_work(c->pred, c, max_predict_batch));
     if (rc == GA3C_OK) guard(alloc_work(c->train, c, max_train_frames));
     if (rc == GA3C_OK && max_train_frames > 0) {
@@ -939,6 +956,7 @@ extern "C" int ga3c_destroy(ga3c_ctx *c) {
         if (c->ev_readers[i]) (void)hipEventDestroy(c->ev_readers[i]);
     }
     (void)hipFree(c->g); (void)hipFree(c->grad);
+    (void)hipFree(c->cfrag[0]); (void)hipFree(c->cfrag[1]);
     free_work(c->pred); free_work(c->train);
     (void)hipFree(c->dh); (void)hipFree(c->dzv); (void)hipFree(c->R);
     (void)hipFree(c->partials); (void)hipFree(c->colpart); (void)hipFree(c->scale); (void)hipFree(c->stats);
@@ -982,6 +1000,7 @@ extern "C" int ga3c_params_init(ga3c_ctx *c, uint64_t seed, void *stream) {
                            (size_t)t[i].off, t[i].n, sqrtf(2.f / (float)t[i].fan_in), seed);
         HIP_TRY(hipGetLastError());
     }
+    TRY(refresh_derived(c, c->cur, s));
     TRY(mark_ready(c, c->cur, s));
     return GA3C_OK;
 }
@@ -1007,7 +1026,10 @@ extern "C" int ga3c_params_set(ga3c_ctx *c, int which, const float *src, size_t 
     TRY(wait_ready(c, c->cur, s));
     TRY(wait_readers(c, c->cur, s));
     HIP_TRY(hipMemcpyAsync(select_buffer(c, which), src, sizeof(float) * n, hipMemcpyDeviceToDevice, s));
-    if (which == 0) TRY(mark_ready(c, c->cur, s));
+    if (which == 0) {
+        TRY(refresh_derived(c, c->cur, s));
+        TRY(mark_ready(c, c->cur, s));
+    }
     return GA3C_OK;
 }
 
@@ -1021,7 +1043,7 @@ extern "C" int ga3c_predict(ga3c_ctx *c, const uint8_t *frames, int B, const flo
     hipStream_t s = (hipStream_t)stream;
     const int cur = c->cur;
     TRY(wait_ready(c, cur, s));
-    const int rc = forward(c, c->theta2[cur], c->pred, frames, B, false, logits, values, probs, uniforms, actions, s);
+    const int rc = forward(c, cur, c->pred, frames, B, false, logits, values, probs, uniforms, actions, s);
     if (rc != GA3C_OK) return rc;
     TRY(mark_readers(c, cur, s));
     return GA3C_OK;
@@ -1045,7 +1067,7 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
     const int cur = c->cur;
     const float *th = c->theta2[cur];
     TRY(wait_ready(c, cur, s));
-    int rc = forward(c, th, w, frames, B, true, nullptr, nullptr, nullptr, nullptr, nullptr, s);
+    int rc = forward(c, cur, w, frames, B, true, nullptr, nullptr, nullptr, nullptr, nullptr, s);
     if (rc != GA3C_OK) return rc;
 
     const int nloss = cdiv(B, LOSS_THREADS);
@@ -1224,6 +1246,7 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
     hipLaunchKernelGGL(rmsprop_kernel, dim3(rb), dim3(256), 0, s, th, c->theta2[cur ^ 1], c->g, c->grad, c->P, c->scale,
                        1.f, hp->lr, hp->rms_decay, hp->rms_eps);
     HIP_TRY(hipGetLastError());
+    TRY(refresh_derived(c, cur ^ 1, s));
     TRY(mark_ready(c, cur ^ 1, s));
     c->cur = cur ^ 1;        // calls enqueued from now on see the new parameters
     return GA3C_OK;
