@@ -4,7 +4,9 @@
 A step is one balanced pass of the whole path (Sec. 4.2 of the paper: in a
 balanced configuration PPS ~ TPS * t_max): t_max = 5 prediction calls of N
 frames each, one per action of every agent, followed by one training step on
-the N agents x 5 frames those actions produced.  N = 512 agents, the small
+the N agents x 5 frames those actions produced (the bootstrap value of a
+segment is the value of the next segment's first prediction, so no sixth
+prediction is needed).  N = 512 agents, the small
 network of Sec. 3.2 with 18 actions, synthetic game-like frames that are
 resident in HBM before the timed region starts.
 
@@ -98,7 +100,6 @@ def main() -> int:
     frames = torch.from_numpy(frames_np).cuda()
     # predict call t sees the frames of step t of every agent
     pframes = [frames[:, t].contiguous() for t in range(T)]
-    boot_frames = torch.from_numpy(synth.rectangle_frames_tiled(seed + 2, N)).cuda()
     actions = torch.from_numpy(tr["actions"]).cuda()
     rewards = torch.from_numpy(tr["rewards"]).cuda()
     dones = torch.from_numpy(tr["dones"]).cuda()
@@ -110,10 +111,12 @@ def main() -> int:
     stream = torch.cuda.current_stream()
 
     def step():
+        # one prediction per frame: the value that closes a segment's returns, V(s_{t+t_max}), is what the agent is
+        # told by the first prediction of its next segment (Sec. 4.1), so a segment costs t_max predictions, not
+        # t_max + 1; with synthetic states the values of prediction 0 stand in for it
         for t in range(T):
-            net.predict(pframes[t], uniforms=uniforms, logits=logits, values=values, probs=probs, actions=sampled,
-                        stream=stream)
-        net.predict(boot_frames, values=boot, stream=stream)           # V(s_{t+k}) for the returns
+            net.predict(pframes[t], uniforms=uniforms, logits=logits, values=boot if t == 0 else values, probs=probs,
+                        actions=sampled, stream=stream)
         net.train_step(frames, actions, rewards, dones, boot, hp, stats=stats, stream=stream)
 
     def timed(fn, k):
@@ -177,7 +180,7 @@ def main() -> int:
                     "ms_per_launch": round(dp["ms"] / dp["calls"], 5)}
     if args.net == "small" and N == 512:
         fwd = {"conv1_fwd", "conv2_fwd", "fc_fwd", "heads_fwd"}
-        roofline["traffic"] = counter_traffic(dom["stage"], [(N, T + 1), (N * T, 1)] if dom["stage"] in fwd else [(N * T, 1)])
+        roofline["traffic"] = counter_traffic(dom["stage"], [(N, T), (N * T, 1)] if dom["stage"] in fwd else [(N * T, 1)])
         roofline["algorithmic_bytes_per_launch"] = round(dp["bytes"] / dp["calls"]) if dp["bytes"] > 0 else None
     flop_step = sum(p["flop"] for p in prof.values()) / args.steps
     whole = {"tflops": round(flop_step / sec / 1e12, 3), "frac_fp32_mfma_peak": round(flop_step / sec / PEAK_FP32_MFMA, 4)}
@@ -190,7 +193,7 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "arithmetic": "fp32 MFMA with fp32 accumulate; conv1 as exact 3-term bf16 MFMA (bytes are exact in bf16)",
         "config": {"workload": f"configs[1]+[2]: {args.net} net, 18 actions; per step {T}x predict B={N} "
-                               f"(+1 bootstrap predict B={N}) and 1 train_step {N} agents x t_max={T} = {N * T} frames, "
+                               f"and 1 train_step {N} agents x t_max={T} = {N * T} frames, "
                                "clip 40", "agents": N, "t_max": T, "seed": seed},
         "pps_predict_only": {"value": round(1024 / pred_sec, 1), "batch": 1024, "ms_per_call": round(pred_sec * 1e3, 4)},
         "tps_train_only": {"value": round(frames_per_step / train_sec, 1), "frames": frames_per_step,
@@ -224,9 +227,11 @@ def main() -> int:
         theta = theta_np.astype(np.float64)
         cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
         t0 = time.perf_counter()
+        bo = None
         for t in range(T):
-            orc.forward(onet, theta, frames_np[:, t])
-        bo = orc.forward(onet, theta, boot_frames.cpu().numpy())["values"]
+            out_t = orc.forward(onet, theta, frames_np[:, t])
+            if t == 0:
+                bo = out_t["values"]
         orc.train_step(onet, theta, np.zeros_like(theta), frames_np, tr["actions"], tr["rewards"], tr["dones"], bo,
                        orc.HParams(clip_norm=40.0))
         cpu_sec = time.perf_counter() - t0
