@@ -70,6 +70,34 @@ __global__ __launch_bounds__(192) void conv12_filter_fragments_kernel(const floa
     }
 }
 
+// The same fragments, four filter taps at a time: `rel` (a multiple of 4) is the index of v.x in the layer's
+// filter tensor [oc][256].  Lets the kernel that updates the parameters keep the fragments current.
+__device__ __forceinline__ void conv12_store_fragment4(u32x4 *__restrict__ frag, int layer2, int rel, const float4 v) {
+    const int oc = rel >> 8, k = rel & 255;
+    const int kb = k >> 5, g = (k >> 3) & 3, e0 = k & 7;               // e0 = 0 or 4
+    const float f[4] = {v.x, v.y, v.z, v.w};
+    union { __bf16 h[4]; uint32_t u[2]; } o[3];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) split3(f[e], o[0].h[e], o[1].h[e], o[2].h[e]);
+    if (!layer2) {
+        uint32_t *dst = (uint32_t *)(frag + (size_t)kb * 64 + g * 16 + oc) + e0 / 2;
+#pragma unroll
+        for (int t = 0; t < 3; ++t) {
+            dst[(size_t)t * 8 * 64 * 4] = o[t].u[0];
+            dst[(size_t)t * 8 * 64 * 4 + 1] = o[t].u[1];
+        }
+    } else {
+        const int kh = kb >> 2, j = 2 * (kb & 3) + (oc >> 4);
+        // taps e0, e0+1 go to positions e0/2, e0/2+1 of the vector; taps e0+2, e0+3 to positions 4 + e0/2, ..
+        uint32_t *dst = (uint32_t *)(frag + (size_t)(1 + kh) * C12_FRAG_SET + (size_t)j * 64 + g * 16 + (oc & 15)) + e0 / 4;
+#pragma unroll
+        for (int t = 0; t < 3; ++t) {
+            dst[(size_t)t * 8 * 64 * 4] = o[t].u[0];
+            dst[(size_t)t * 8 * 64 * 4 + 2] = o[t].u[1];
+        }
+    }
+}
+
 inline hipError_t launch_conv12_filter_fragments(const float *w1, const float *w2, u32x4 *frag, hipStream_t s) {
     hipLaunchKernelGGL(conv12_filter_fragments_kernel, dim3(1), dim3(192), 0, s, w1, w2, frag);
     return hipGetLastError();

@@ -373,7 +373,7 @@ constexpr int HD_FRAMES = 8;
 __global__ __launch_bounds__(256) void heads_dgrad_kernel(const float *__restrict__ dzv, const float *__restrict__ h,
                                                           const float *__restrict__ Wp, const float *__restrict__ Wv,
                                                           int B, int F, int A, float *__restrict__ dh,
-                                                          float *__restrict__ colpart) {
+                                                          float *__restrict__ colpart, float *__restrict__ wpart) {
     extern __shared__ float sm[];
     float *wsh = sm;                        // [A+1][F]
     float *dzs = sm + (A + 1) * F;          // [HD_FRAMES][A+1]
@@ -391,10 +391,19 @@ __global__ __launch_bounds__(256) void heads_dgrad_kernel(const float *__restric
         float s[HD_FRAMES];
 #pragma unroll
         for (int fb = 0; fb < HD_FRAMES; ++fb) s[fb] = 0.f;
+        // wpart (optional): this block's share of the heads' weight gradient,
+        // [block][A+1][F+1] with the bias gradient in the last column
+        float *wp = wpart ? wpart + (size_t)blockIdx.x * (A + 1) * (F + 1) + k : nullptr;
         for (int a = 0; a <= A; ++a) {
             const float wv = wsh[a * F + k];
+            float gw = 0.f;
 #pragma unroll
-            for (int fb = 0; fb < HD_FRAMES; ++fb) s[fb] += dzs[min(fb, nf - 1) * (A + 1) + a] * wv;
+            for (int fb = 0; fb < HD_FRAMES; ++fb) {
+                const float d = dzs[min(fb, nf - 1) * (A + 1) + a];
+                s[fb] += d * wv;
+                gw += fb < nf ? d * hv[fb] : 0.f;
+            }
+            if (wp) wp[(size_t)a * (F + 1)] = gw;
         }
         float col = 0.f;
 #pragma unroll
@@ -406,6 +415,11 @@ __global__ __launch_bounds__(256) void heads_dgrad_kernel(const float *__restric
             }
         colpart[(size_t)blockIdx.x * F + k] = col;      // this block's share of the fc bias gradient
     }
+    if (wpart && tid <= A) {
+        float gb = 0.f;
+        for (int fb = 0; fb < nf; ++fb) gb += dzs[fb * (A + 1) + tid];
+        wpart[((size_t)blockIdx.x * (A + 1) + tid) * (F + 1) + F] = gb;
+    }
 }
 
 // One launch adds up the partial weight gradients of every layer and, on the
@@ -416,10 +430,14 @@ __global__ __launch_bounds__(256) void heads_dgrad_kernel(const float *__restric
 // outputs with zg threads each: thread j adds z = j, j+zg, ... (eight loads in
 // flight at a time), then the zg sums are added in order of j.  Nothing depends
 // on timing, so the gradient is reproducible bit for bit.
+// Block ids go round-robin over the 8 XCDs; the ids of one XCD take consecutive
+// groups of outputs, so that blocks which share 128-byte lines of the partial
+// sums also share an L2.
 struct ReduceSeg {
     const float *ws;
     float *gW, *gb;
     int nz, M, N, r0, rows, bias_col, zg, first_block;
+    int per_xcd;         // the segment owns 8 * per_xcd block ids, first_block is a multiple of 8
 };
 constexpr int MAX_REDUCE_SEGS = 8;
 struct ReduceArgs {
@@ -437,7 +455,8 @@ __global__ __launch_bounds__(256) void reduce_all_kernel(const ReduceArgs a) {
     const int opb = 256 / g.zg;
     const int o = threadIdx.x % opb, zi = threadIdx.x / opb;
     const size_t cnt = (size_t)g.rows * g.N;
-    const size_t i = (size_t)(blockIdx.x - g.first_block) * opb + o;
+    const int lb = blockIdx.x - g.first_block;
+    const size_t i = ((size_t)(lb % 8) * g.per_xcd + lb / 8) * opb + o;
     float s = 0.f;
     if (i < cnt) {
         const size_t src = (size_t)g.r0 * g.N + i, stride = (size_t)g.M * g.N;
@@ -513,7 +532,10 @@ __global__ __launch_bounds__(256) void finalize_kernel(const float *__restrict__
 __global__ __launch_bounds__(256) void rmsprop_kernel(const float *theta_in, float *theta_out, float *__restrict__ g,
                                                       const float *__restrict__ grad, size_t n,
                                                       const float *__restrict__ scale_dev, float scale_host, float lr,
-                                                      float alpha, float eps) {
+                                                      float alpha, float eps, u32x4 *__restrict__ frag, unsigned w1_off,
+                                                      unsigned w2_off) {
+    // frag (optional): split MFMA fragments of the small net's conv filters, kept current with theta_out;
+    // w1_off / w2_off: where the two filter tensors start in the flat buffer (multiples of 4)
     const float s = scale_dev ? scale_dev[0] : scale_host;
     const float oma = 1.f - alpha;
     const size_t n4 = n / 4;
@@ -530,6 +552,11 @@ __global__ __launch_bounds__(256) void rmsprop_kernel(const float *theta_in, flo
         t.x -= lr * d.x / sqrtf(gg.x + eps); t.y -= lr * d.y / sqrtf(gg.y + eps);
         t.z -= lr * d.z / sqrtf(gg.z + eps); t.w -= lr * d.w / sqrtf(gg.w + eps);
         g4[i] = gg; o4[i] = t;
+        if (frag) {
+            const unsigned r1 = (unsigned)(4 * i) - w1_off, r2 = (unsigned)(4 * i) - w2_off;
+            if (r1 < 16u * 256u) conv12_store_fragment4(frag, 0, (int)r1, t);
+            else if (r2 < 32u * 256u) conv12_store_fragment4(frag, 1, (int)r2, t);
+        }
     }
     for (size_t i = n4 * 4 + (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
         const float d = s * grad[i];
@@ -800,7 +827,7 @@ size_t workspace_floats(const ga3c_ctx *c, int cap, bool training) {
         pick_split_xcd(cdiv(c->F, 64) * cdiv(c->flat, 64), B, nz2, kc, 256);
         add((size_t)std::max(nz, nz2) * c->F * (c->flat + 1));
         pick_split(conv_like_tiles(c->A + 1, c->F + 1), B, nz, kc);
-        add((size_t)nz * (c->A + 1) * (c->F + 1));
+        add((size_t)std::max(nz, cdiv(B, HD_FRAMES)) * (c->A + 1) * (c->F + 1));
         need = std::max(need, sum);
     }
     return need;
@@ -917,7 +944,7 @@ extern "C" int ga3c_create(const ga3c_net_desc *d, int max_predict_batch, int ma
         if (rc == GA3C_OK) guard(dmalloc((void **)&c->dh, sizeof(float) * B * c->F));
         if (rc == GA3C_OK) guard(dmalloc((void **)&c->dzv, sizeof(float) * B * (c->A + 1)));
         if (rc == GA3C_OK) guard(dmalloc((void **)&c->R, sizeof(float) * B));
-        c->max_norm_parts = (int)(c->P / 4 + 16 * MAX_REDUCE_SEGS);   // a reduce block covers at least 4 outputs
+        c->max_norm_parts = (int)(c->P / 4 + 24 * MAX_REDUCE_SEGS);   // a reduce block covers at least 4 outputs
         if (rc == GA3C_OK) guard(dmalloc((void **)&c->partials, sizeof(float) * (c->max_norm_parts + 3 * (B / LOSS_THREADS + 1))));
         if (rc == GA3C_OK) guard(dmalloc((void **)&c->colpart, sizeof(float) * (B / HD_FRAMES + 1) * c->F));
         if (rc == GA3C_OK) guard(dmalloc((void **)&c->scale, sizeof(float)));
@@ -1098,10 +1125,22 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
         int zg = 1;
         while (zg < 64 && zg * 16 < nz_) zg *= 2;      // at most two rounds of eight loads per thread
         g.zg = zg; g.first_block = red_blocks;
-        red_blocks += (int)(((size_t)rows * Ncols + 256 / zg - 1) / (256 / zg));
+        const int nblk = (int)(((size_t)rows * Ncols + 256 / zg - 1) / (256 / zg));
+        g.per_xcd = (nblk + 7) / 8;
+        red_blocks += 8 * g.per_xcd;
         red_bytes += 4.0 * (nz_ + 1) * rows * Ncols;
     };
-    {   // heads: weight and bias gradients, dgrad
+    if (c->fast) {   // heads: input gradient and, per block of frames, the block's share of the weight and bias gradients
+        const int nblk = cdiv(B, HD_FRAMES);
+        float *part = region((size_t)nblk * (A + 1) * (F + 1));
+        if (!part) return fail(GA3C_EINVAL, "internal: split-k workspace too small (heads)");
+        STAGE("heads_bwd", 4.0 * B * (A + 1) * F, 0);
+        hipLaunchKernelGGL(heads_dgrad_kernel, dim3(nblk), dim3(256), sizeof(float) * (A + 1) * (F + HD_FRAMES), s, c->dzv, w.h, Wp, Wv, B,
+                           F, A, c->dh, c->colpart, part);
+        HIP_TRY(hipGetLastError());
+        add_seg(part, nblk, A + 1, F + 1, 0, A, c->grad + c->off[nb + 2], c->grad + c->off[nb + 3], 1);
+        add_seg(part, nblk, A + 1, F + 1, A, 1, c->grad + c->off[nb + 4], c->grad + c->off[nb + 5], 1);
+    } else {   // heads: weight and bias gradients as a product, then the input gradient
         GemmP<EPI_PARTIAL, true> p;
         p.M = A + 1; p.N = F + 1; p.K = B;
         pick_split(conv_like_tiles(p.M, p.N), B, nz, kchunk);
@@ -1118,7 +1157,7 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
         add_seg(p.C, nz, A + 1, F + 1, A, 1, c->grad + c->off[nb + 4], c->grad + c->off[nb + 5], 1);
         STAGE("heads_dgrad", 2.0 * B * (A + 1) * F, 0);
         hipLaunchKernelGGL(heads_dgrad_kernel, dim3(cdiv(B, HD_FRAMES)), dim3(256), sizeof(float) * (A + 1) * (F + HD_FRAMES), s, c->dzv, w.h, Wp, Wv, B,
-                           F, A, c->dh, c->colpart);
+                           F, A, c->dh, c->colpart, (float *)nullptr);
         HIP_TRY(hipGetLastError());
     }
     const float *xfc = w.act[c->nconv - 1];
@@ -1244,9 +1283,8 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
     // the copy about to be overwritten may still be read by predictions issued before the last update
     TRY(wait_readers(c, cur ^ 1, s));
     hipLaunchKernelGGL(rmsprop_kernel, dim3(rb), dim3(256), 0, s, th, c->theta2[cur ^ 1], c->g, c->grad, c->P, c->scale,
-                       1.f, hp->lr, hp->rms_decay, hp->rms_eps);
+                       1.f, hp->lr, hp->rms_decay, hp->rms_eps, c->cfrag[cur ^ 1], (unsigned)c->off[0], (unsigned)c->off[2]);
     HIP_TRY(hipGetLastError());
-    TRY(refresh_derived(c, cur ^ 1, s));
     TRY(mark_ready(c, cur ^ 1, s));
     c->cur = cur ^ 1;        // calls enqueued from now on see the new parameters
     return GA3C_OK;
@@ -1283,7 +1321,7 @@ extern "C" int ga3c_rmsprop_flat(float *theta, float *g, const float *grad, size
         return fail(GA3C_EINVAL, "ga3c_rmsprop_flat: buffers must be 16-byte aligned");
     const unsigned rb = std::min<unsigned>(blocks_for(n / 4 + 1), 8192u);
     hipLaunchKernelGGL(rmsprop_kernel, dim3(rb), dim3(256), 0, (hipStream_t)stream, theta, theta, g, grad, n,
-                       (const float *)nullptr, scale, lr, rms_decay, rms_eps);
+                       (const float *)nullptr, scale, lr, rms_decay, rms_eps, (u32x4 *)nullptr, 0u, 0u);
     HIP_TRY(hipGetLastError());
     return GA3C_OK;
 }

@@ -222,6 +222,39 @@ def test_train_clip_active(G):
     assert ref["stats"]["clip_scale"] < 1.0
 
 
+def test_predict_follows_a_large_update(G):
+    # whatever the library derives from the parameters (split filter fragments) must follow an update, an explicit
+    # params_set and a re-initialisation: a large learning rate makes a stale copy show
+    import torch
+    N, T, A = 16, 5, 6
+    desc = G.SMALL_NET(A)
+    net, onet, theta = make(G, desc, N * T, N * T, 4242)
+    frames = synth.rectangle_frames(4243, N * T).reshape(N, T, 4, 84, 84)
+    tr = synth.trajectories(4244, N, T, A)
+    boot = torch.zeros(N, device="cuda")
+    flat = frames.reshape(N * T, 4, 84, 84)
+
+    def check(th):
+        lg, vl, pr, _ = run_predict(G, net, flat)
+        ref = orc.forward(onet, th.astype(np.float64), flat)
+        assert rel_err(lg, ref["logits"]) <= TOL_FWD
+        assert rel_err(vl, ref["values"]) <= TOL_FWD
+
+    for step in range(2):
+        net.train_step(torch.from_numpy(frames).cuda(), torch.from_numpy(tr["actions"]).cuda(),
+                       torch.from_numpy(tr["rewards"]).cuda(), torch.from_numpy(tr["dones"]).cuda(), boot,
+                       G.HParams(lr=0.02))
+        th1 = net.params_get(0).cpu().numpy()
+        assert rel_err(th1, theta) > 1e-2          # the update moved the parameters visibly
+        check(th1)
+    th2 = synth.perturbed_theta(4245, net.offsets(), net.n_params)
+    net.params_set(torch.from_numpy(th2).cuda(), 0)
+    check(th2)
+    net.params_init(77)
+    check(net.params_get(0).cpu().numpy())
+    net.close()
+
+
 @pytest.mark.parametrize("shape,N,T", [(TINY, 13, 5), (TINY3, 9, 3), (ODD, 11, 4)])
 def test_train_odd_shapes(G, shape, N, T):
     run_train(G, G.NetDesc(**shape), N, T, 600, dict(beta=0.05, value_coef=0.5, gamma=0.9), g0_scale=1e-2)
