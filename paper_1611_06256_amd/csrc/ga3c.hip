@@ -162,17 +162,20 @@ __device__ __forceinline__ void copy_to_lds(float *dst, const float *__restrict_
 
 // Policy and value heads (Sec. 3.2: softmax policy output, linear value
 // output), then softmax and inverse-CDF sampling; optionally preceded by the
-// last step of a split-k fully connected layer.  A block takes 4 frames, one
-// per wavefront.
+// last step of a split-k fully connected layer.  A block takes 4 frames.
 //   ws != null: h[b][o] = max(0, bias[o] + sum_z ws[z][b][o]) is formed first
 //               (and written to h); otherwise h is read.
 //   h [B][F]; Wp [A][F], bp [A], Wv [F], bv [1].  zv [B][A+1] is written when
 //   not null (training keeps it); logits / values / probs / actions are the
 //   caller's optional outputs.
-// Dynamic LDS: 4*F + (A+1)*(F+1) + 12*(A+1) floats: the 4 rows of h, both
-// weight matrices, the partial dot products.  Global memory answers in about a microsecond, so every load a
-// thread needs is issued before the first one is used: the head weights go to
-// LDS in one sweep and the partial sums are read 16 at a time.
+// Dynamic LDS: heads_lds_floats(F, A) floats: the 4 rows of h, both weight
+// matrices (rows padded to a multiple of 4 plus 4, so that rows start 16-byte
+// aligned in different banks), the partial dot products.  Global memory answers
+// in about a microsecond, so every load a thread needs (weights, partial sums,
+// biases, its uniform number) is issued before the first one is used.
+__host__ __device__ inline int heads_f4(int F) { return (F + 3) / 4 * 4; }
+__host__ __device__ inline int heads_lds_floats(int F, int A) { return 4 * heads_f4(F) + (A + 1) * (heads_f4(F) + 4 + 12); }
+
 __global__ __launch_bounds__(256) void heads_fwd_kernel(const float *__restrict__ ws, int nz,
                                                         const float *__restrict__ fcb, float *__restrict__ h, int B,
                                                         int F, int A, const float *__restrict__ Wp,
@@ -180,13 +183,20 @@ __global__ __launch_bounds__(256) void heads_fwd_kernel(const float *__restrict_
                                                         const float *__restrict__ bv, float *zv, float *logits,
                                                         float *values, float *probs, const float *uniforms,
                                                         int32_t *actions) {
-    extern __shared__ float hs[];      // [4][F], weights, partial dots
-    float *wsh = hs + 4 * F;           // [A+1][F+1]: odd pitch, so that rows fall into different banks
+    extern __shared__ __attribute__((aligned(16))) float hs[];      // [4][F4], weights [A+1][F4+4], partial dots
+    const int F4 = heads_f4(F), WP = F4 + 4;
+    float *wsh = hs + 4 * F4;
     const int tid = threadIdx.x;
     const int b0 = blockIdx.x * 4;
     const int nf = min(4, B - b0);
-    // Everything this thread needs from global memory is requested before any
-    // of it is used: up to 24 head weights and 4 x 16 partial sums at a time.
+    const int nout = nf * (A + 1);
+    // thread tid < nout finishes output a of frame fb
+    const int ofb = min(tid / (A + 1), nf - 1), oa = tid % (A + 1);
+    const float obias = oa < A ? bp[oa] : bv[0];
+    const float ou = (actions && tid < nout) ? uniforms[b0 + ofb] : 0.f;
+    // padding columns of the LDS rows stay zero
+    for (int e = tid; e < 4 * (F4 - F); e += 256) hs[(e / (F4 - F)) * F4 + F + e % (F4 - F)] = 0.f;
+    for (int e = tid; e < (A + 1) * (WP - F); e += 256) wsh[(e / (WP - F)) * WP + F + e % (WP - F)] = 0.f;
     const int nw = (A + 1) * F;                 // Wp [A][F] and Wv [F] are adjacent in LDS, not in global memory
     for (int e0 = 0; e0 < nw || e0 == 0; e0 += 24 * 256) {
         float wv[24];
@@ -215,76 +225,90 @@ __global__ __launch_bounds__(256) void heads_fwd_kernel(const float *__restrict_
                             for (int i = 0; i < 16; ++i) acc4[fb] += (z + i < nz) ? v[fb][i] : 0.f;
                     }
 #pragma unroll
-                    for (int fb = 0; fb < 4; ++fb)
-                        if (fb < nf) {
-                            float v = acc4[fb] + bias;
-                            v = v > 0.f ? v : 0.f;
-                            h[(size_t)(b0 + fb) * F + o] = v;
-                            hs[fb * F + o] = v;
-                        }
+                    for (int fb = 0; fb < 4; ++fb) {
+                        float v = acc4[fb] + bias;
+                        v = v > 0.f ? v : 0.f;
+                        if (fb < nf) h[(size_t)(b0 + fb) * F + o] = v;
+                        hs[fb * F4 + o] = v;
+                    }
                 } else {
                     float v[4];
 #pragma unroll
                     for (int fb = 0; fb < 4; ++fb) v[fb] = h[(size_t)(b0 + min(fb, nf - 1)) * F + o];
 #pragma unroll
-                    for (int fb = 0; fb < 4; ++fb)
-                        if (fb < nf) hs[fb * F + o] = v[fb];
+                    for (int fb = 0; fb < 4; ++fb) hs[fb * F4 + o] = v[fb];
                 }
             }
         }
 #pragma unroll
         for (int j = 0; j < 24; ++j) {
             const int e = e0 + j * 256 + tid;
-            if (e < nw) wsh[e + e / F] = wv[j];
+            if (e < nw) wsh[(e / F) * WP + e % F] = wv[j];
         }
     }
     __syncthreads();
-    // Dot products from LDS without cross-lane traffic: thread (frame, output,
-    // third of k) adds its share, three shares make one output.
-    float *zs = wsh + (A + 1) * (F + 1);             // [4][A+1][3] partial dots, then [4][A+1] results
-    const int nout = nf * (A + 1);
+    // Dot products from LDS, 16 bytes per read, without cross-lane traffic:
+    // thread (frame, output, third of k) adds its share, three shares make one output.
+    float *zs = wsh + (A + 1) * WP;                  // [4][A+1][3] partial dots, then [4][A+1] values
     if (tid < 3 * nout) {
         const int kp = tid / nout, r = tid % nout;
         const int fb = r / (A + 1), a = r % (A + 1);
-        const int klo = (F * kp) / 3, khi = (F * (kp + 1)) / 3;
-        const float *hb = hs + fb * F, *wr = wsh + a * (F + 1);
-        float s0 = 0.f, s1 = 0.f;
-        int k = klo;
-        for (; k + 1 < khi; k += 2) { s0 += hb[k] * wr[k]; s1 += hb[k + 1] * wr[k + 1]; }
-        if (k < khi) s0 += hb[k] * wr[k];
-        zs[(fb * (A + 1) + a) * 3 + kp] = s0 + s1;
+        const int nk = F4 / 4;
+        const int klo = (nk * kp) / 3, khi = (nk * (kp + 1)) / 3;
+        const float4 *hb = (const float4 *)(hs + fb * F4), *wr = (const float4 *)(wsh + a * WP);
+        float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+#pragma unroll 4
+        for (int k = klo; k < khi; ++k) {
+            const float4 x = hb[k], w = wr[k];
+            s0 += x.x * w.x; s1 += x.y * w.y; s2 += x.z * w.z; s3 += x.w * w.w;
+        }
+        zs[(fb * (A + 1) + a) * 3 + kp] = (s0 + s1) + (s2 + s3);
     }
     __syncthreads();
     float z = 0.f;
-    if (tid < nout) {
-        const int fb = tid / (A + 1), a = tid % (A + 1);
-        z = (zs[tid * 3] + zs[tid * 3 + 1]) + zs[tid * 3 + 2] + (a < A ? bp[a] : bv[0]);
-        const int b = b0 + fb;
-        if (zv) zv[(size_t)b * (A + 1) + a] = z;
-        if (a < A && logits) logits[(size_t)b * A + a] = z;
-        if (a == A && values) values[b] = z;
+    const bool mine = tid < nout;
+    const int b = b0 + ofb;
+    if (mine) {
+        z = (zs[tid * 3] + zs[tid * 3 + 1]) + zs[tid * 3 + 2] + obias;
+        if (zv) zv[(size_t)b * (A + 1) + oa] = z;
+        if (oa < A && logits) logits[(size_t)b * A + oa] = z;
+        if (oa == A && values) values[b] = z;
     }
     if (!probs && !actions) return;
+    // Softmax and the draw, one thread per (frame, action).  The sums run left to
+    // right in fp32 exactly as a single thread would form them, so the sampled
+    // action is a pure function of the probabilities written out.
+    const bool pol = mine && oa < A;
+    float *zr = zs + ofb * (A + 1);
     __syncthreads();                                  // all partials are consumed
-    if (tid < nout) zs[tid] = z;
+    if (mine) zs[tid] = z;
     __syncthreads();
-    if (tid < nf) {                                   // one thread per frame: softmax and the draw
-        const int b = b0 + tid;
-        float *zr = zs + tid * (A + 1);
+    float e = 0.f;
+    if (pol) {
         float zmax = zr[0];
         for (int j = 1; j < A; ++j) zmax = fmaxf(zmax, zr[j]);
+        e = expf(z - zmax);
+    }
+    __syncthreads();
+    if (pol) zr[oa] = e;
+    __syncthreads();
+    float pr = 0.f;
+    if (pol) {
         float S = 0.f;
-        for (int j = 0; j < A; ++j) { const float e = expf(zr[j] - zmax); zr[j] = e; S += e; }
-        const float u = actions ? uniforms[b] : 0.f;
-        float c = 0.f;
-        int act = -1;
-        for (int j = 0; j < A; ++j) {                 // left-to-right fp32 running sum
-            const float p = zr[j] / S;
-            if (probs) probs[(size_t)b * A + j] = p;
-            c += p;
-            if (act < 0 && c > u) act = j;
-        }
-        if (actions) actions[b] = act < 0 ? A - 1 : act;
+        for (int j = 0; j < A; ++j) S += zr[j];
+        pr = e / S;
+        if (probs) probs[(size_t)b * A + oa] = pr;
+    }
+    if (!actions) return;
+    __syncthreads();
+    if (pol) zr[oa] = pr;
+    __syncthreads();
+    if (pol) {
+        float c = 0.f, cprev = 0.f;
+        for (int j = 0; j <= oa; ++j) { cprev = c; c += zr[j]; }
+        // the first action whose running sum exceeds u; the last one if none does
+        if (c > ou && !(oa > 0 && cprev > ou)) actions[b] = oa;
+        else if (oa == A - 1 && !(c > ou)) actions[b] = A - 1;
     }
 }
 
@@ -794,7 +818,7 @@ int forward(ga3c_ctx *c, int which, Work &w, const uint8_t *frames, int B, bool 
         }
     }
     STAGE("heads_fwd", 2.0 * B * c->F * (c->A + 1), 4.0 * (fc_nz + 1) * B * c->F);
-    hipLaunchKernelGGL(heads_fwd_kernel, dim3(cdiv(B, 4)), dim3(256), sizeof(float) * (4 * c->F + (c->A + 1) * (c->F + 13)), s, fc_ws, fc_nz,
+    hipLaunchKernelGGL(heads_fwd_kernel, dim3(cdiv(B, 4)), dim3(256), sizeof(float) * heads_lds_floats(c->F, c->A), s, fc_ws, fc_nz,
                        th + c->off[nb + 1], w.h, B, c->F, c->A, th + c->off[nb + 2],
                        th + c->off[nb + 3], th + c->off[nb + 4], th + c->off[nb + 5],
                        keep_zv ? w.zv : nullptr, logits, values, probs, uniforms, actions);
@@ -846,8 +870,8 @@ extern "C" int ga3c_create(const ga3c_net_desc *d, int max_predict_batch, int ma
     if (d->in_c < 1 || d->in_h < 1 || d->in_w < 1 || d->fc_units < 1) return fail(GA3C_EINVAL, "ga3c_create: bad sizes");
     if (d->math != 0) return fail(GA3C_EINVAL, "ga3c_create: only math = 0 (fp32) is built");
     if (max_predict_batch < 0 || max_train_frames < 0) return fail(GA3C_EINVAL, "ga3c_create: negative capacity");
-    if ((size_t)(4 + d->n_actions + 1) * d->fc_units * sizeof(float) > 64 * 1024)
-        return fail(GA3C_EINVAL, "ga3c_create: (n_actions + 5) * fc_units must not exceed 16384");
+    if ((size_t)heads_lds_floats(d->fc_units, d->n_actions) * sizeof(float) > 64 * 1024)
+        return fail(GA3C_EINVAL, "ga3c_create: (n_actions + 5) * (fc_units + 16) must not exceed 16384");
 
     ga3c_ctx *c = new (std::nothrow) ga3c_ctx();
     if (!c) return fail(GA3C_ENOMEM, "ga3c_create: host allocation failed");
