@@ -38,17 +38,17 @@ PEAK_HBM = 8.0e12           # B/s
 # counters read 0.5000 and 1.0000 of the known bytes, hence the scale factors.  The summary is kept under profiles/.
 FETCH_SCALE, WRITE_SCALE = 2.0, 1.0
 COUNTER_KIB = {   # stage: {frames per launch: (FETCH_SIZE, WRITE_SIZE)}
-    "conv1_fwd": {512: (7305.2, 12806.4), 1024: (14377.3, 25630.1), 2560: (35593.2, 64110.6)},
-    "conv2_fwd": {512: (6698.0, 5184.0), 1024: (13098.0, 10368.7), 2560: (32298.0, 25922.8)},
+    "conv12_fwd": {512: (7554.7, 5184.0), 1024: (14626.7, 10368.0), 2560: (35842.8, 89931.1)},   # 2560: training, keeps y1
     "fc_fwd": {512: (4153.0, 7168.0), 1024: (6649.0, 8192.0), 2560: (14425.0, 20480.0)},
-    "heads_fwd": {512: (3778.3, 592.0), 1024: (4274.0, 1104.0), 2560: (10418.0, 2760.0)},
-    "conv1_wgrad": {2560: (67646.6, 4112.0)},
-    "conv2_wgrad": {2560: (45142.0, 16501.0)},
-    "conv2_dgrad": {2560: (45192.1, 64000.0)},
-    "fc_wgrad": {2560: (14305.3, 20736.4)},
-    "fc_dgrad": {2560: (25475.5, 28117.3)},
-    "wgrad_reduce": {2560: (48604.1, 2825.0)},
-    "rmsprop": {2560: (4010.1, 5320.6)},
+    "heads_fwd": {512: (3776.0, 592.0), 1024: (4268.5, 1104.0), 2560: (10412.5, 2760.0)},
+    "conv1_wgrad": {2560: (67652.6, 4112.0)},
+    "conv2_wgrad": {2560: (45142.0, 16513.0)},
+    "conv2_dgrad": {2560: (45191.8, 64000.0)},
+    "fc_wgrad": {2560: (14299.0, 20736.3)},
+    "fc_dgrad": {2560: (25421.0, 28214.6)},
+    "heads_bwd": {2560: (1511.5, 8994.4)},
+    "wgrad_reduce": {2560: (24733.3, 2807.6)},
+    "rmsprop": {2560: (4019.6, 5394.1)},
 }
 
 
@@ -179,7 +179,7 @@ def main() -> int:
                     "unit": "GB/s", "frac": round(ach * 1e9 / PEAK_HBM, 4), "traffic": None,
                     "ms_per_launch": round(dp["ms"] / dp["calls"], 5)}
     if args.net == "small" and N == 512:
-        fwd = {"conv1_fwd", "conv2_fwd", "fc_fwd", "heads_fwd"}
+        fwd = {"conv12_fwd", "fc_fwd", "heads_fwd"}
         roofline["traffic"] = counter_traffic(dom["stage"], [(N, T), (N * T, 1)] if dom["stage"] in fwd else [(N * T, 1)])
         roofline["algorithmic_bytes_per_launch"] = round(dp["bytes"] / dp["calls"]) if dp["bytes"] > 0 else None
     flop_step = sum(p["flop"] for p in prof.values()) / args.steps
