@@ -26,8 +26,12 @@ struct ConvSpec {
     static constexpr int OT = OC / 16;               // filter tiles
     static constexpr int WPITCH = K + 4;             // LDS row pitch of the filters (floats)
     static_assert(OC % 16 == 0 && (OT == 1 || OT == 2 || OT == 4), "filter count must be 16, 32 or 64");
-    static_assert(KS == 4 || KS == 8, "kernel width must be 4 or 8 (4 taps of a row are fetched at once)");
     static_assert(K % 16 == 0, "filter length must be a multiple of 16");
+    // Order of the contraction index in the forward kernel.  Kernel widths 4 and 8: (c, u, v) as in memory,
+    // four consecutive taps of a filter row are fetched at once.  Other widths: (u, v, c), so that four
+    // consecutive indices are four channels of one tap; needs C to be a multiple of 16.
+    static constexpr bool TAPMAJOR = !(KS == 4 || KS == 8);
+    static_assert(!TAPMAJOR || C % 16 == 0, "tap-major order needs a multiple of 16 input channels");
     // element offset inside a frame of filter tap k = (c, u, v)
     __host__ __device__ static constexpr int koff(int k) {
         return (k / (KS * KS)) * H * W + ((k / KS) % KS) * W + (k % KS);
@@ -52,8 +56,10 @@ __device__ __forceinline__ float4 lds_taps(const float *xs, int off) {
 }
 
 // y[b][oc][pix] = max(0, scale * sum_k W[oc][k] x[b][tap k at pix] + bias[oc]).
-// Block = 4 wavefronts; frames blockIdx.x, blockIdx.x + gridDim.x, ...
-template <class SP>
+// Block = 4 wavefronts; frames blockIdx.x, blockIdx.x + gridDim.x, ...; filters
+// OCS * blockIdx.y .. + OCS - 1 (a layer whose filters do not fit LDS next to the
+// frame is cut into slices of OCS filters, gridDim.y = OC / OCS).
+template <class SP, int OCS = SP::OC>
 __global__ __launch_bounds__(256, 2) void conv_fwd_frame_kernel(const typename SP::TIn *__restrict__ x,
                                                                 const float *__restrict__ w,
                                                                 const float *__restrict__ bias,
@@ -63,29 +69,41 @@ __global__ __launch_bounds__(256, 2) void conv_fwd_frame_kernel(const typename S
     static_assert(FRAME_BYTES % 16 == 0, "frame size must be a multiple of 16 bytes");
     constexpr int NV = FRAME_BYTES / 16;                         // uint4 per frame
     constexpr int VPT = (NV + 255) / 256;                        // uint4 per thread
-    constexpr int JOBS = SP::NT * SP::OT;                        // (pixel tile, filter tile) pairs per frame
+    constexpr int OT = OCS / 16;                                 // filter tiles of a slice
+    static_assert(OCS % 16 == 0 && SP::OC % OCS == 0, "a slice is a whole number of filter tiles");
+    constexpr int JOBS = SP::NT * OT;                            // (pixel tile, filter tile) pairs per frame
     constexpr int TPW = (JOBS + 3) / 4;                          // pairs per wave, the last one maybe absent
     constexpr int FULL = JOBS % 4 == 0 ? TPW : TPW - 1;          // pairs every wave has
     constexpr int NLAST = JOBS - 4 * FULL;                       // waves that have one more
     // the frame, padded so that every thread can store all of its VPT vectors
     __shared__ __attribute__((aligned(16))) unsigned char xs_raw[VPT * 256 * 16];
-    __shared__ __attribute__((aligned(16))) float ws[SP::OC * SP::WPITCH];
+    __shared__ __attribute__((aligned(16))) float ws[OCS * SP::WPITCH];
     const TIn *xs = (const TIn *)xs_raw;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l16 = lane & 15, g = lane >> 4;
-    const int ot = wave % SP::OT;
+    const int ot = wave % OT;
+    const int oc0 = blockIdx.y * OCS;
+    w += (size_t)oc0 * SP::K;
 
     // filters -> LDS, row pitch K+4 so that the 16 rows a wave reads hit different banks
-    for (int e = tid; e < SP::OC * SP::K / 4; e += 256) {
-        const int oc = e / (SP::K / 4), kq = e % (SP::K / 4);
-        const float4 v = *(const float4 *)(w + (size_t)oc * SP::K + 4 * kq);
-        *(float4 *)(ws + oc * SP::WPITCH + 4 * kq) = v;
+    if (!SP::TAPMAJOR) {
+        for (int e = tid; e < OCS * SP::K / 4; e += 256) {
+            const int oc = e / (SP::K / 4), kq = e % (SP::K / 4);
+            const float4 v = *(const float4 *)(w + (size_t)oc * SP::K + 4 * kq);
+            *(float4 *)(ws + oc * SP::WPITCH + 4 * kq) = v;
+        }
+    } else {   // position tap * C + c holds W[oc][c][tap]
+        for (int e = tid; e < OCS * SP::K; e += 256) {
+            const int oc = e / SP::K, kk = e % SP::K;
+            const int tap = kk / SP::C, c = kk % SP::C;
+            ws[oc * SP::WPITCH + kk] = w[(size_t)oc * SP::K + c * (SP::KS * SP::KS) + tap];
+        }
     }
     float bv[4];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) bv[r] = bias[ot * 16 + 4 * g + r];
+    for (int r = 0; r < 4; ++r) bv[r] = bias[oc0 + ot * 16 + 4 * g + r];
 
     // per-lane constants: where each of my pixels starts in the frame, and the
     // offset of my share (4g .. 4g+3) of every group of 16 taps
@@ -93,13 +111,24 @@ __global__ __launch_bounds__(256, 2) void conv_fwd_frame_kernel(const typename S
 #pragma unroll
     for (int i = 0; i < TPW; ++i) {
         const int job = wave + 4 * i;
-        const int pt = job / SP::OT;
+        const int pt = job / OT;
         int p = pt * 16 + l16;
         pixidx[i] = (job < JOBS && p < SP::NPIX) ? p : -1;
         if (p >= SP::NPIX) p = 0;
         pixbase[i] = (p / SP::OW) * SP::S * SP::W + (p % SP::OW) * SP::S;
     }
-    const int lane_koff = SP::koff(4 * g);
+    // offset of my share (4g .. 4g+3) of a group of 16 contraction indices, and of group q
+    const int lane_koff = SP::TAPMAJOR ? 4 * g * (SP::H * SP::W) : SP::koff(4 * g);
+    auto group_koff = [](int q) {
+        if (!SP::TAPMAJOR) return SP::koff(16 * q);
+        const int tap = (16 * q) / SP::C, c = (16 * q) % SP::C;
+        return c * (SP::H * SP::W) + (tap / SP::KS) * SP::W + tap % SP::KS;
+    };
+    auto taps = [&](int off) {
+        if (!SP::TAPMAJOR) return lds_taps(xs, off);
+        return make_float4((float)xs[off], (float)xs[off + SP::H * SP::W], (float)xs[off + 2 * SP::H * SP::W],
+                           (float)xs[off + 3 * SP::H * SP::W]);
+    };
     const float *wrow = ws + (ot * 16 + l16) * SP::WPITCH + 4 * g;
 
     // a thread's vectors of the frame; indices past the end re-read the last one
@@ -130,10 +159,10 @@ __global__ __launch_bounds__(256, 2) void conv_fwd_frame_kernel(const typename S
 #pragma unroll
         for (int q = 0; q < SP::K / 16; ++q) {
             const float4 wv = *(const float4 *)(wrow + 16 * q);
-            const int ko = SP::koff(16 * q) + lane_koff;
+            const int ko = group_koff(q) + lane_koff;
 #pragma unroll
             for (int i = 0; i < FULL; ++i) {
-                const float4 xv = lds_taps(xs, pixbase[i] + ko);
+                const float4 xv = taps(pixbase[i] + ko);
                 acc[i] = mfma4(wv.x, xv.x, acc[i]);
                 acc[i] = mfma4(wv.y, xv.y, acc[i]);
                 acc[i] = mfma4(wv.z, xv.z, acc[i]);
@@ -145,7 +174,7 @@ __global__ __launch_bounds__(256, 2) void conv_fwd_frame_kernel(const typename S
 #pragma unroll
             for (int q = 0; q < SP::K / 16; ++q) {
                 const float4 wv = *(const float4 *)(wrow + 16 * q);
-                const float4 xv = lds_taps(xs, pixbase[i] + SP::koff(16 * q) + lane_koff);
+                const float4 xv = taps(pixbase[i] + group_koff(q) + lane_koff);
                 acc[i] = mfma4(wv.x, xv.x, acc[i]);
                 acc[i] = mfma4(wv.y, xv.y, acc[i]);
                 acc[i] = mfma4(wv.z, xv.z, acc[i]);
@@ -159,19 +188,22 @@ __global__ __launch_bounds__(256, 2) void conv_fwd_frame_kernel(const typename S
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const float v = acc[i][r] * scale + bv[r];
-                    yb[(ot * 16 + 4 * g + r) * SP::NPIX + pixidx[i]] = v > 0.f ? v : 0.f;
+                    yb[(oc0 + ot * 16 + 4 * g + r) * SP::NPIX + pixidx[i]] = v > 0.f ? v : 0.f;
                 }
             }
         }
     }
 }
 
-template <class SP>
+// `blocks`: how many blocks the chip holds at once (LDS decides), shared out over the slices.
+template <class SP, int OCS = SP::OC>
 inline hipError_t launch_conv_fwd_frame(const typename SP::TIn *x, const float *w, const float *bias, float *y,
-                                        int nframes, float scale, hipStream_t s) {
+                                        int nframes, float scale, hipStream_t s, int blocks = 512) {
     if (nframes <= 0) return hipSuccess;
-    const int grid = nframes < 512 ? nframes : 512;
-    hipLaunchKernelGGL((conv_fwd_frame_kernel<SP>), dim3(grid), dim3(256), 0, s, x, w, bias, y, nframes, scale);
+    constexpr int SLICES = SP::OC / OCS;
+    const int per = blocks / SLICES;
+    const int grid = nframes < per ? nframes : per;
+    hipLaunchKernelGGL((conv_fwd_frame_kernel<SP, OCS>), dim3(grid, SLICES), dim3(256), 0, s, x, w, bias, y, nframes, scale);
     return hipGetLastError();
 }
 
@@ -186,7 +218,9 @@ inline hipError_t launch_conv_fwd_frame(const typename SP::TIn *x, const float *
 // block then writes one partial dW, which a second kernel adds up in block
 // order (no atomics, so the result does not depend on timing).
 // part: [gridDim.x][OC][K+1], the last column is the bias gradient.
-template <class SP>
+// KSL > 1 cuts the filter taps into KSL slices (blockIdx.y) where one block's
+// accumulators for all of them would not fit the register file.
+template <class SP, int KSL = 1>
 __global__ __launch_bounds__(256, 2) void conv_wgrad_frame_kernel(const typename SP::TIn *__restrict__ x,
                                                                   const float *__restrict__ dy,
                                                                   float *__restrict__ part, int nframes, float scale) {
@@ -196,8 +230,8 @@ __global__ __launch_bounds__(256, 2) void conv_wgrad_frame_kernel(const typename
     constexpr int NS = (SP::NPIX + 3) / 4;                       // contraction steps per frame
     constexpr int DPITCH = ((4 * NS + 31) / 32) * 32 + 4;        // row pitch of dY in LDS: 4 mod 32 banks
     constexpr int NDY = SP::OC * SP::NPIX, DPT = (NDY + 255) / 256;
-    constexpr int KT = SP::K / 16, KTW = KT / 4;                 // tap tiles in all / per wave
-    static_assert(KT % 4 == 0, "tap tiles must split evenly over 4 waves");
+    constexpr int KT = SP::K / 16, KTW = KT / (4 * KSL);         // tap tiles in all / per wave
+    static_assert(KT % (4 * KSL) == 0, "tap tiles must split evenly over the slices and 4 waves");
     static_assert(256 % SP::OC == 0, "bias sums use 256/OC threads per filter");
     constexpr int TPO = 256 / SP::OC;                            // threads per filter in the bias sum
     __shared__ __attribute__((aligned(16))) unsigned char xs_raw[VPT * 256 * 16];
@@ -212,7 +246,7 @@ __global__ __launch_bounds__(256, 2) void conv_wgrad_frame_kernel(const typename
 
     int tapoff[KTW];                                             // my tap in each of my tiles
 #pragma unroll
-    for (int t = 0; t < KTW; ++t) tapoff[t] = SP::koff(16 * (wave * KTW + t) + l16);
+    for (int t = 0; t < KTW; ++t) tapoff[t] = SP::koff(16 * ((blockIdx.y * 4 + wave) * KTW + t) + l16);
     // pixel 4s+g of a frame -> offset of its window
     int pixoff[SP::OW % 4 == 0 ? 1 : NS];
     if (SP::OW % 4 != 0) {
@@ -297,7 +331,7 @@ __global__ __launch_bounds__(256, 2) void conv_wgrad_frame_kernel(const typename
             }
         }
     }
-    // lane (l16, g) register r of tile (o, t): filter o*16 + 4g + r, tap 16*(wave*KTW+t) + l16
+    // lane (l16, g) register r of tile (o, t): filter o*16 + 4g + r, tap 16*((slice*4+wave)*KTW+t) + l16
     float *pb = part + (size_t)blockIdx.x * SP::OC * (SP::K + 1);
 #pragma unroll
     for (int o = 0; o < SP::OT; ++o)
@@ -305,18 +339,22 @@ __global__ __launch_bounds__(256, 2) void conv_wgrad_frame_kernel(const typename
         for (int t = 0; t < KTW; ++t)
 #pragma unroll
             for (int r = 0; r < 4; ++r)
-                pb[(o * 16 + 4 * g + r) * (SP::K + 1) + 16 * (wave * KTW + t) + l16] = acc[o][t][r] * scale;
-    if (tid % TPO == 0) pb[(tid / TPO) * (SP::K + 1) + SP::K] = bsum;
+                pb[(o * 16 + 4 * g + r) * (SP::K + 1) + 16 * ((blockIdx.y * 4 + wave) * KTW + t) + l16] = acc[o][t][r] * scale;
+    if (blockIdx.y == 0 && tid % TPO == 0) pb[(tid / TPO) * (SP::K + 1) + SP::K] = bsum;
 }
 
+// One partial dW per block: fewer blocks where a partial is large.
 template <class SP>
-inline int conv_wgrad_frame_blocks(int nframes) { return nframes < 512 ? nframes : 512; }
+inline int conv_wgrad_frame_blocks(int nframes) {
+    constexpr int LIMIT = SP::OC * (SP::K + 1) > 16384 ? 256 : 512;
+    return nframes < LIMIT ? nframes : LIMIT;
+}
 
-template <class SP>
+template <class SP, int KSL = 1>
 inline hipError_t launch_conv_wgrad_frame(const typename SP::TIn *x, const float *dy, float *part, int nframes,
                                           float scale, hipStream_t s) {
     if (nframes <= 0) return hipSuccess;
-    hipLaunchKernelGGL((conv_wgrad_frame_kernel<SP>), dim3(conv_wgrad_frame_blocks<SP>(nframes)), dim3(256), 0, s, x,
+    hipLaunchKernelGGL((conv_wgrad_frame_kernel<SP, KSL>), dim3(conv_wgrad_frame_blocks<SP>(nframes), KSL), dim3(256), 0, s, x,
                        dy, part, nframes, scale);
     return hipGetLastError();
 }

@@ -726,6 +726,8 @@ inline int conv_like_tiles(int M, int N) {
 typedef ConvSpec<uint8_t, 4, 84, 84, 16, 8, 4> SpecS1;    // small net, conv1
 typedef ConvSpec<float, 16, 20, 20, 32, 4, 2> SpecS2;     // small net, conv2
 typedef ConvSpec<uint8_t, 4, 84, 84, 32, 8, 4> SpecL1;    // large net, conv1
+typedef ConvSpec<float, 32, 20, 20, 64, 4, 2> SpecL2;     // large net, conv2
+typedef ConvSpec<float, 64, 9, 9, 64, 3, 1> SpecL3;       // large net, conv3
 
 template <class SP>
 inline bool spec_matches(const ConvGeom &g, bool byte_input) {
@@ -772,6 +774,14 @@ int forward(ga3c_ctx *c, int which, Work &w, const uint8_t *frames, int B, bool 
             }
             if (spec_matches<SpecS2>(g, l == 0)) {
                 HIP_TRY(launch_conv2_bf16x6_fwd((const float *)xin, wl, bl, w.act[l], B, s));
+                continue;
+            }
+            if (spec_matches<SpecL2>(g, l == 0)) {      // frame and 32 of the 64 filters in LDS: one block per CU
+                HIP_TRY((launch_conv_fwd_frame<SpecL2, 32>((const float *)xin, wl, bl, w.act[l], B, 1.f, s, 256)));
+                continue;
+            }
+            if (spec_matches<SpecL3>(g, l == 0)) {      // 16 filters per block, two blocks per CU
+                HIP_TRY((launch_conv_fwd_frame<SpecL3, 16>((const float *)xin, wl, bl, w.act[l], B, 1.f, s, 512)));
                 continue;
             }
         }
@@ -1240,10 +1250,13 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
             const void *xin = l == 0 ? (const void *)frames : (const void *)w.act[l - 1];
             const bool ok = c->fast && is_aligned16(xin);
             const int kind = !ok ? 0 : (spec_matches<SpecS1>(g, l == 0) && is_aligned16(c->dact[l])) ? 1
-                                     : spec_matches<SpecL1>(g, l == 0) ? 2 : spec_matches<SpecS2>(g, l == 0) ? 3 : 0;
+                                     : spec_matches<SpecL1>(g, l == 0) ? 2 : spec_matches<SpecS2>(g, l == 0) ? 3
+                                     : spec_matches<SpecL2>(g, l == 0) ? 4 : spec_matches<SpecL3>(g, l == 0) ? 5 : 0;
             if (kind == 1) nz = conv1_bf16x3_wgrad_blocks(B);
             else if (kind == 2) nz = conv_wgrad_frame_blocks<SpecL1>(B);
             else if (kind == 3) nz = conv_wgrad_frame_blocks<SpecS2>(B);
+            else if (kind == 4) nz = conv_wgrad_frame_blocks<SpecL2>(B);
+            else if (kind == 5) nz = conv_wgrad_frame_blocks<SpecL3>(B);
             else pick_split(conv_like_tiles(g.OC, g.K + 1), B * g.OHW, nz, kchunk);
             float *part = region((size_t)nz * g.OC * (g.K + 1));
             if (!part) return fail(GA3C_EINVAL, "internal: split-k workspace too small (conv)");
@@ -1254,6 +1267,10 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
                 HIP_TRY(launch_conv_wgrad_frame<SpecL1>((const uint8_t *)xin, c->dact[l], part, B, 1.f / 255.f, s));
             } else if (kind == 3) {
                 HIP_TRY(launch_conv_wgrad_frame<SpecS2>((const float *)xin, c->dact[l], part, B, 1.f, s));
+            } else if (kind == 4) {
+                HIP_TRY((launch_conv_wgrad_frame<SpecL2, 4>)((const float *)xin, c->dact[l], part, B, 1.f, s));
+            } else if (kind == 5) {
+                HIP_TRY((launch_conv_wgrad_frame<SpecL3, 3>)((const float *)xin, c->dact[l], part, B, 1.f, s));
             } else if (l == 0) {
                 ConvWgradP<uint8_t> p;
                 p.M = g.OC; p.N = g.K + 1; p.K = B * g.OHW; p.kchunk = kchunk; p.g = g;
