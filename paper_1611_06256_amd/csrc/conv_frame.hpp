@@ -369,14 +369,15 @@ inline hipError_t launch_conv_wgrad_frame(const typename SP::TIn *x, const float
 // row operand (C rows), 16 pixels of the phase grid the column operand, and
 // k = (oc, a, e) the contraction.  The four phases are interleaved in an LDS
 // copy of the output frame, which is then masked and stored with full-width
-// writes.
+// writes.  A block computes 16 input channels, 16 * blockIdx.y .. (gridDim.y = C / 16).
 template <class SP>
 __global__ __launch_bounds__(256, 2) void conv_dgrad_frame_kernel(const float *__restrict__ dy,
                                                                   const float *__restrict__ w,
                                                                   const float *__restrict__ xin,
                                                                   float *__restrict__ dx, int nframes) {
     static_assert(SP::KS == 2 * SP::S && SP::S == 2, "kernel must be 4x4 with stride 2");
-    static_assert(SP::C == 16, "one row tile of input channels");
+    static_assert(SP::C % 16 == 0, "whole row tiles of input channels");
+    constexpr int CS = 16;                                         // input channels of a block
     static_assert(SP::H % SP::S == 0 && SP::W % SP::S == 0, "phases must tile the input");
     constexpr int S = SP::S;
     constexpr int GH = SP::H / S, GW = SP::W / S, GP = GH * GW;   // phase grid
@@ -386,9 +387,9 @@ __global__ __launch_bounds__(256, 2) void conv_dgrad_frame_kernel(const float *_
     constexpr int KP = SP::OC * 4;                                // contraction length
     constexpr int WP = KP + 4;                                    // pitch of a sub-filter row
     constexpr int NDY = SP::OC * SP::NPIX, DPT = (NDY + 255) / 256;
-    constexpr int NX = SP::CHW, XV = NX / 4, XPT = (XV + 255) / 256;
+    constexpr int NX = CS * SP::H * SP::W, XV = NX / 4, XPT = (XV + 255) / 256;
     static_assert(GH <= SP::OH + 1 && GW <= SP::OW + 1, "phase grid must fit the padded dY");
-    __shared__ __attribute__((aligned(16))) float wp[4 * SP::C * WP];      // [phase][c][(oc,a,e)]
+    __shared__ __attribute__((aligned(16))) float wp[4 * CS * WP];         // [phase][c][(oc,a,e)]
     __shared__ __attribute__((aligned(16))) float dp[SP::OC * OCP];        // [oc][PH][PW]
     __shared__ __attribute__((aligned(16))) float outs[NX];                // [c][H][W]
 
@@ -397,11 +398,12 @@ __global__ __launch_bounds__(256, 2) void conv_dgrad_frame_kernel(const float *_
     const int l16 = lane & 15, g = lane >> 4;
     const int ry = wave / S, rx = wave % S;
 
-    for (int e = tid; e < 4 * SP::C * KP; e += 256) {
-        const int ph = e / (SP::C * KP), c = (e / KP) % SP::C, k = e % KP;
+    const int c0 = blockIdx.y * CS;
+    for (int e = tid; e < 4 * CS * KP; e += 256) {
+        const int ph = e / (CS * KP), c = (e / KP) % CS, k = e % KP;
         const int oc = k / 4, a = (k / 2) % 2, ee = k % 2;
         const int u = ph / S + S * a, v = ph % S + S * ee;
-        wp[(ph * SP::C + c) * WP + k] = w[((size_t)(oc * SP::C + c) * SP::KS + u) * SP::KS + v];
+        wp[(ph * CS + c) * WP + k] = w[((size_t)(oc * SP::C + c0 + c) * SP::KS + u) * SP::KS + v];
     }
     for (int e = tid; e < SP::OC * OCP; e += 256) dp[e] = 0.f;
 
@@ -428,7 +430,7 @@ __global__ __launch_bounds__(256, 2) void conv_dgrad_frame_kernel(const float *_
 #pragma unroll
     for (int i = 0; i < XPT; ++i) xidx[i] = min(tid + 256 * i, XV - 1);
 
-    const float *wrow = wp + ((ry * S + rx) * SP::C + l16) * WP + 4 * g;
+    const float *wrow = wp + ((ry * S + rx) * CS + l16) * WP + 4 * g;
     float dpre[DPT];
     int f = blockIdx.x;
     {
@@ -448,7 +450,7 @@ __global__ __launch_bounds__(256, 2) void conv_dgrad_frame_kernel(const float *_
         }
         float4 mask[XPT];
         {
-            const float4 *msrc = (const float4 *)(xin + (size_t)f * NX);
+            const float4 *msrc = (const float4 *)(xin + (size_t)f * SP::CHW + (size_t)c0 * (SP::H * SP::W));
 #pragma unroll
             for (int i = 0; i < XPT; ++i) mask[i] = msrc[xidx[i]];
         }
@@ -475,7 +477,7 @@ __global__ __launch_bounds__(256, 2) void conv_dgrad_frame_kernel(const float *_
                 for (int r = 0; r < 4; ++r) outs[(4 * g + r) * (SP::H * SP::W) + obase[i]] = acc[i][r];
             }
         __syncthreads();
-        float4 *dst = (float4 *)(dx + (size_t)f * NX);
+        float4 *dst = (float4 *)(dx + (size_t)f * SP::CHW + (size_t)c0 * (SP::H * SP::W));
 #pragma unroll
         for (int i = 0; i < XPT; ++i) {
             const int e = tid + 256 * i;
@@ -489,12 +491,141 @@ __global__ __launch_bounds__(256, 2) void conv_dgrad_frame_kernel(const float *_
     }
 }
 
+// `blocks`: how many blocks the chip holds at once (LDS decides), shared out over the channel slices.
 template <class SP>
 inline hipError_t launch_conv_dgrad_frame(const float *dy, const float *w, const float *xin, float *dx, int nframes,
-                                          hipStream_t s) {
+                                          hipStream_t s, int blocks = 512) {
     if (nframes <= 0) return hipSuccess;
-    const int grid = nframes < 512 ? nframes : 512;
-    hipLaunchKernelGGL((conv_dgrad_frame_kernel<SP>), dim3(grid), dim3(256), 0, s, dy, w, xin, dx, nframes);
+    constexpr int SLICES = SP::C / 16;
+    const int per = blocks / SLICES;
+    const int grid = nframes < per ? nframes : per;
+    hipLaunchKernelGGL((conv_dgrad_frame_kernel<SP>), dim3(grid, SLICES), dim3(256), 0, s, dy, w, xin, dx, nframes);
+    return hipGetLastError();
+}
+
+
+// Input gradient of a stride-1 layer:
+//   dX[c][y][x] = [xin[c][y][x] > 0] * sum_{oc,u,v} dY[oc][y-u][x-v] W[oc][c][u][v].
+// With dY padded by KS-1 zeros on every side this is a forward convolution of
+// the padded dY (OC planes) with the flipped, transposed filters
+// W'[c][oc][u'][v'] = W[oc][c][KS-1-u'][KS-1-v'], one output per input pixel.
+// The filters of CS input channels are the row operand, 16 pixels the column
+// operand, the contraction runs over (u', v', oc) with oc fastest, so that the
+// four values a lane feeds to four MFMAs are four planes at one offset.
+// Block = 4 wavefronts, (pixel tile, channel tile) pairs dealt round-robin;
+// input channels CS * blockIdx.y ..; frames blockIdx.x, + gridDim.x, ...
+template <class SP, int CS>
+__global__ __launch_bounds__(256) void conv_dgrad_s1_frame_kernel(const float *__restrict__ dy, const float *__restrict__ w,
+                                                                  const float *__restrict__ xin, float *__restrict__ dx,
+                                                                  int nframes) {
+    static_assert(SP::S == 1, "stride 1");
+    static_assert(SP::OC % 16 == 0 && CS % 16 == 0 && SP::C % CS == 0, "whole MFMA tiles");
+    constexpr int P = SP::KS - 1, PH = SP::OH + 2 * P, PW = SP::OW + 2 * P;
+    static_assert(PH == SP::H + P && PW == SP::W + P, "padded dY covers every window");
+    constexpr int OCP = ((PH * PW + 15) / 16) * 16 + 4;            // pitch per plane: a lane group's 4 planes are 16 banks on
+    constexpr int KP = SP::KS * SP::KS * SP::OC, WP = KP + 4;
+    constexpr int NPX = SP::H * SP::W, NT = (NPX + 15) / 16, CT = CS / 16;
+    constexpr int JOBS = NT * CT, TPW = (JOBS + 3) / 4;
+    constexpr int FULL = JOBS % 4 == 0 ? TPW : TPW - 1, NLAST = JOBS - 4 * FULL;
+    constexpr int NDY = SP::OC * SP::NPIX, DPT = (NDY + 255) / 256;
+    __shared__ __attribute__((aligned(16))) float wp[CS * WP];     // [c][(u', v', oc)]
+    __shared__ __attribute__((aligned(16))) float dp[SP::OC * OCP];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l16 = lane & 15, g = lane >> 4;
+    const int c0 = blockIdx.y * CS;
+
+    for (int e = tid; e < CS * KP; e += 256) {
+        const int c = e / KP, k = e % KP;
+        const int tap = k / SP::OC, oc = k % SP::OC;
+        const int u = P - tap / SP::KS, v = P - tap % SP::KS;
+        wp[c * WP + k] = w[((size_t)(oc * SP::C + c0 + c) * SP::KS + u) * SP::KS + v];
+    }
+    for (int e = tid; e < SP::OC * OCP; e += 256) dp[e] = 0.f;      // the border stays zero
+
+    int pbase[TPW], oidx[TPW], ct[TPW];
+#pragma unroll
+    for (int i = 0; i < TPW; ++i) {
+        const int job = wave + 4 * i;
+        ct[i] = job % CT;
+        int p = (job / CT) * 16 + l16;
+        const bool ok = job < JOBS && p < NPX;
+        if (p >= NPX) p = 0;
+        pbase[i] = (p / SP::W) * PW + p % SP::W + 4 * g * OCP;      // + my four planes of every group of 16
+        oidx[i] = ok ? p : -1;
+    }
+    int didx[DPT], dlds[DPT];
+#pragma unroll
+    for (int i = 0; i < DPT; ++i) {
+        const int e = min(tid + 256 * i, NDY - 1);
+        didx[i] = e;
+        const int oc = e / SP::NPIX, pix = e % SP::NPIX;
+        dlds[i] = oc * OCP + (pix / SP::OW + P) * PW + pix % SP::OW + P;
+    }
+    float dpre[DPT];
+    int f = blockIdx.x;
+    {
+        const float *dsrc = dy + (size_t)min(f, nframes - 1) * NDY;
+#pragma unroll
+        for (int i = 0; i < DPT; ++i) dpre[i] = dsrc[didx[i]];
+    }
+    for (; f < nframes; f += gridDim.x) {
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < DPT; ++i) dp[dlds[i]] = dpre[i];
+        __syncthreads();
+        {
+            const float *dsrc = dy + (size_t)min(f + (int)gridDim.x, nframes - 1) * NDY;
+#pragma unroll
+            for (int i = 0; i < DPT; ++i) dpre[i] = dsrc[didx[i]];
+        }
+        const size_t fbase = (size_t)f * SP::CHW + (size_t)c0 * NPX;
+        float mask[TPW][4];                                         // requested now, needed after the products
+#pragma unroll
+        for (int i = 0; i < TPW; ++i)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) mask[i][r] = xin[fbase + (size_t)(ct[i] * 16 + 4 * g + r) * NPX + max(oidx[i], 0)];
+        floatx4 acc[TPW];
+#pragma unroll
+        for (int i = 0; i < TPW; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+        auto step = [&](int i, int q) {
+            const int tap = (16 * q) / SP::OC, ocb = (16 * q) % SP::OC;
+            const int qoff = ocb * OCP + (tap / SP::KS) * PW + tap % SP::KS;
+            const float4 wv = *(const float4 *)(wp + (ct[i] * 16 + l16) * WP + 16 * q + 4 * g);
+            const float *b = dp + pbase[i] + qoff;
+            acc[i] = mfma4(wv.x, b[0], acc[i]);
+            acc[i] = mfma4(wv.y, b[OCP], acc[i]);
+            acc[i] = mfma4(wv.z, b[2 * OCP], acc[i]);
+            acc[i] = mfma4(wv.w, b[3 * OCP], acc[i]);
+        };
+        // the pairs every wavefront has run in one branch-free sweep; the odd ones after it
+#pragma unroll
+        for (int q = 0; q < KP / 16; ++q)
+#pragma unroll
+            for (int i = 0; i < FULL; ++i) step(i, q);
+        if (NLAST > 0 && wave < NLAST) {                            // uniform per wave
+#pragma unroll
+            for (int q = 0; q < KP / 16; ++q) step(TPW - 1, q);
+        }
+#pragma unroll
+        for (int i = 0; i < TPW; ++i)
+            if (oidx[i] >= 0) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    dx[fbase + (size_t)(ct[i] * 16 + 4 * g + r) * NPX + oidx[i]] = mask[i][r] > 0.f ? acc[i][r] : 0.f;
+            }
+    }
+}
+
+template <class SP, int CS>
+inline hipError_t launch_conv_dgrad_s1_frame(const float *dy, const float *w, const float *xin, float *dx, int nframes,
+                                             hipStream_t s, int blocks) {
+    if (nframes <= 0) return hipSuccess;
+    constexpr int SLICES = SP::C / CS;
+    const int per = blocks / SLICES;
+    const int grid = nframes < per ? nframes : per;
+    hipLaunchKernelGGL((conv_dgrad_s1_frame_kernel<SP, CS>), dim3(grid, SLICES), dim3(256), 0, s, dy, w, xin, dx, nframes);
     return hipGetLastError();
 }
 

@@ -1291,6 +1291,14 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
             HIP_TRY(launch_conv_dgrad_frame<SpecS2>(c->dact[l], th + c->off[2 * l], w.act[l - 1], c->dact[l - 1], B, s));
             continue;
         }
+        if (c->fast && spec_matches<SpecL2>(g, false) && is_aligned16(th + c->off[2 * l])) {   // one block per CU
+            HIP_TRY(launch_conv_dgrad_frame<SpecL2>(c->dact[l], th + c->off[2 * l], w.act[l - 1], c->dact[l - 1], B, s, 256));
+            continue;
+        }
+        if (c->fast && spec_matches<SpecL3>(g, false)) {
+            HIP_TRY((launch_conv_dgrad_s1_frame<SpecL3, 32>(c->dact[l], th + c->off[2 * l], w.act[l - 1], c->dact[l - 1], B, s, 256)));
+            continue;
+        }
         // general shapes: one launch per stride phase
         for (int ry = 0; ry < g.S; ++ry)
             for (int rx = 0; rx < g.S; ++rx) {
