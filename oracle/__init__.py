@@ -38,7 +38,7 @@ class _Net(C.Structure):
         ("in_c", C.c_int), ("in_h", C.c_int), ("in_w", C.c_int),
         ("n_conv", C.c_int),
         ("oc", C.c_int * MAX_CONV), ("k", C.c_int * MAX_CONV), ("stride", C.c_int * MAX_CONV),
-        ("fc_units", C.c_int), ("n_actions", C.c_int),
+        ("fc_units", C.c_int), ("n_actions", C.c_int), ("math", C.c_int),
     ]
 
 
@@ -61,6 +61,7 @@ class Net:
     conv: Sequence[Tuple[int, int, int]] = ((16, 8, 4), (32, 4, 2))
     fc_units: int = 256
     n_actions: int = 6
+    math: int = 0        # 1: operands of every contraction rounded to bfloat16
 
     def c(self) -> _Net:
         n = _Net()
@@ -69,6 +70,7 @@ class Net:
         for i, (oc, k, s) in enumerate(self.conv):
             n.oc[i], n.k[i], n.stride[i] = oc, k, s
         n.fc_units, n.n_actions = self.fc_units, self.n_actions
+        n.math = self.math
         return n
 
 
@@ -100,6 +102,8 @@ def lib() -> C.CDLL:
         _lib.orc_grad_norm.restype = C.c_double
         _lib.orc_clip_scale.restype = C.c_double
         _lib.orc_clip_scale.argtypes = [C.c_double, C.c_double]
+        _lib.orc_bf16_round.restype = C.c_double
+        _lib.orc_bf16_round.argtypes = [C.c_double]
         _lib.orc_sample.argtypes = [C.c_void_p, C.c_int, C.c_double]
     return _lib
 
@@ -201,6 +205,13 @@ def backward(net: Net, theta, acts, dZ, dV) -> np.ndarray:
     if rc != 0:
         raise MemoryError("orc_backward")
     return grad
+
+
+def bf16_round(values) -> np.ndarray:
+    """Nearest bfloat16, ties to even, of every element (the rounding math = 1 applies to operands)."""
+    L = lib()
+    v = np.asarray(values, dtype=np.float64)
+    return np.array([L.orc_bf16_round(float(x)) for x in v.reshape(-1)], dtype=np.float64).reshape(v.shape)
 
 
 def grad_norm(grad) -> float:

@@ -27,6 +27,17 @@
  * full so this file stands alone): for each conv layer W[oc][ic][kh][kw] then
  * b[oc]; fc W[out][in] with in = c*H*W + h*W + w, fc b[out]; policy W[A][F],
  * policy b[A]; value W[F], value b.
+ *
+ * math = 1 is the reduced-precision variant of the same network: every
+ * contraction (convolution, fully connected layer, heads, and each of their
+ * weight, bias and input gradients) takes both of its operands rounded to
+ * bfloat16 (8 significant bits, round to nearest even), multiplies them exactly
+ * and accumulates without further rounding; everything else (biases, ReLU,
+ * softmax, loss, clip, RMSProp, the stored parameters) is as for math = 0.  The
+ * input bytes are exact in bfloat16, so layer 1 multiplies the raw bytes and
+ * applies the 1/255 afterwards.  A bias gradient is the contraction of the
+ * output gradient with a vector of ones, so its terms are rounded too.
+ * The code for math = 0 is untouched by this: every use is behind `if (bf)`.
  */
 #include <math.h>
 #include <stdint.h>
@@ -41,6 +52,7 @@ typedef struct {
     int oc[ORC_MAX_CONV], k[ORC_MAX_CONV], stride[ORC_MAX_CONV];
     int fc_units;
     int n_actions;
+    int math;           /* 0: plain fp64; 1: operands of every contraction rounded to bfloat16 */
 } orc_net;
 
 typedef struct {
@@ -105,22 +117,49 @@ int64_t orc_acts_per_frame(const orc_net *net) {
     return s + net->fc_units;
 }
 
+/* ---- bfloat16 rounding (math = 1) --------------------------------------- */
+
+/* Nearest bfloat16 (1 sign, 8 exponent, 7 fraction bits), ties to even. */
+double orc_bf16_round(double v) {
+    float f = (float)v;
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    if ((u & 0x7f800000u) == 0x7f800000u) return (double)f;      /* inf, nan */
+    u += 0x7fffu + ((u >> 16) & 1u);
+    u &= 0xffff0000u;
+    memcpy(&f, &u, 4);
+    return (double)f;
+}
+#define Q(v) orc_bf16_round(v)
+
 /* ---- forward ----------------------------------------------------------- */
 
 /* VALID cross-correlation + bias + ReLU for one frame (Sec. 3.2). */
+/* bf != 0: operands rounded to bfloat16; xs = 255 for the first layer, whose
+ * stored input x = byte / 255 enters the products as the byte itself. */
 static void conv_relu(const double *x, int C, int H, int W,
                       const double *wt, const double *bias, int OC, int K, int S,
-                      double *y) {
+                      double *y, int bf, double xs) {
     int OH = (H - K) / S + 1, OW = (W - K) / S + 1;
     for (int o = 0; o < OC; ++o)
         for (int i = 0; i < OH; ++i)
             for (int j = 0; j < OW; ++j) {
                 double acc = bias[o];
-                for (int c = 0; c < C; ++c)
-                    for (int u = 0; u < K; ++u)
-                        for (int v = 0; v < K; ++v)
-                            acc += wt[((o * C + c) * K + u) * K + v] *
-                                   x[(c * H + i * S + u) * W + j * S + v];
+                if (!bf) {
+                    for (int c = 0; c < C; ++c)
+                        for (int u = 0; u < K; ++u)
+                            for (int v = 0; v < K; ++v)
+                                acc += wt[((o * C + c) * K + u) * K + v] *
+                                       x[(c * H + i * S + u) * W + j * S + v];
+                } else {
+                    double dot = 0.0;
+                    for (int c = 0; c < C; ++c)
+                        for (int u = 0; u < K; ++u)
+                            for (int v = 0; v < K; ++v)
+                                dot += Q(wt[((o * C + c) * K + u) * K + v]) *
+                                       Q(xs * x[(c * H + i * S + u) * W + j * S + v]);
+                    acc += dot / xs;
+                }
                 y[(o * OH + i) * OW + j] = acc > 0.0 ? acc : 0.0;
             }
 }
@@ -146,7 +185,7 @@ static void forward_one(const orc_net *net, const double *theta, const int64_t *
         int c, h, w; layer_in_shape(net, l, &c, &h, &w);
         double *y = cur + cur_sz;
         conv_relu(cur, c, h, w, theta + off[2 * l], theta + off[2 * l + 1],
-                  net->oc[l], net->k[l], net->stride[l], y);
+                  net->oc[l], net->k[l], net->stride[l], y, net->math, l == 0 ? 255.0 : 1.0);
         int c2, h2, w2; layer_in_shape(net, l + 1, &c2, &h2, &w2);
         cur = y; cur_sz = (int64_t)c2 * h2 * w2;
     }
@@ -156,18 +195,22 @@ static void forward_one(const orc_net *net, const double *theta, const int64_t *
     const double *Wv = theta + off[nb + 4], *bv = theta + off[nb + 5];
     int F = net->fc_units, A = net->n_actions;
     double *hfc = cur + cur_sz;
+    const int q = net->math;
     for (int o = 0; o < F; ++o) {
         double acc = bf[o];
-        for (int64_t i = 0; i < cur_sz; ++i) acc += Wf[o * cur_sz + i] * cur[i];
+        if (!q) for (int64_t i = 0; i < cur_sz; ++i) acc += Wf[o * cur_sz + i] * cur[i];
+        else for (int64_t i = 0; i < cur_sz; ++i) acc += Q(Wf[o * cur_sz + i]) * Q(cur[i]);
         hfc[o] = acc > 0.0 ? acc : 0.0;
     }
     for (int a = 0; a < A; ++a) {
         double acc = bp[a];
-        for (int i = 0; i < F; ++i) acc += Wp[a * F + i] * hfc[i];
+        if (!q) for (int i = 0; i < F; ++i) acc += Wp[a * F + i] * hfc[i];
+        else for (int i = 0; i < F; ++i) acc += Q(Wp[a * F + i]) * Q(hfc[i]);
         logits[a] = acc;
     }
     double v = bv[0];
-    for (int i = 0; i < F; ++i) v += Wv[i] * hfc[i];
+    if (!q) for (int i = 0; i < F; ++i) v += Wv[i] * hfc[i];
+    else for (int i = 0; i < F; ++i) v += Q(Wv[i]) * Q(hfc[i]);
     *value = v;
     if (probs) softmax(logits, A, probs);
 }
@@ -284,15 +327,27 @@ static void backward_one(const orc_net *net, const double *theta, const int64_t 
     double *gWp = grad + off[nb + 2], *gbp = grad + off[nb + 3];
     double *gWv = grad + off[nb + 4], *gbv = grad + off[nb + 5];
 
+    const int q = net->math;
     /* heads */
     double *dh = scratch;                    /* F */
     for (int i = 0; i < F; ++i) dh[i] = 0.0;
-    for (int a = 0; a < A; ++a) {
-        gbp[a] += dz[a];
-        for (int i = 0; i < F; ++i) { gWp[a * F + i] += dz[a] * hfc[i]; dh[i] += dz[a] * Wp[a * F + i]; }
+    if (!q) {
+        for (int a = 0; a < A; ++a) {
+            gbp[a] += dz[a];
+            for (int i = 0; i < F; ++i) { gWp[a * F + i] += dz[a] * hfc[i]; dh[i] += dz[a] * Wp[a * F + i]; }
+        }
+        gbv[0] += dv;
+        for (int i = 0; i < F; ++i) { gWv[i] += dv * hfc[i]; dh[i] += dv * Wv[i]; }
+    } else {
+        for (int a = 0; a < A; ++a) {
+            const double da = Q(dz[a]);
+            gbp[a] += da;
+            for (int i = 0; i < F; ++i) { gWp[a * F + i] += da * Q(hfc[i]); dh[i] += da * Q(Wp[a * F + i]); }
+        }
+        const double dq = Q(dv);
+        gbv[0] += dq;
+        for (int i = 0; i < F; ++i) { gWv[i] += dq * Q(hfc[i]); dh[i] += dq * Q(Wv[i]); }
     }
-    gbv[0] += dv;
-    for (int i = 0; i < F; ++i) { gWv[i] += dv * hfc[i]; dh[i] += dv * Wv[i]; }
     for (int i = 0; i < F; ++i) if (!(hfc[i] > 0.0)) dh[i] = 0.0;   /* ReLU of fc */
 
     /* fc */
@@ -300,10 +355,19 @@ static void backward_one(const orc_net *net, const double *theta, const int64_t 
     double *dcur = scratch + F;              /* gradient w.r.t. current layer input */
     for (int64_t i = 0; i < flat; ++i) dcur[i] = 0.0;
     for (int o = 0; o < F; ++o) {
-        gbf[o] += dh[o];
-        for (int64_t i = 0; i < flat; ++i) {
-            gWf[o * flat + i] += dh[o] * xin[i];
-            dcur[i] += dh[o] * Wf[o * flat + i];
+        if (!q) {
+            gbf[o] += dh[o];
+            for (int64_t i = 0; i < flat; ++i) {
+                gWf[o * flat + i] += dh[o] * xin[i];
+                dcur[i] += dh[o] * Wf[o * flat + i];
+            }
+        } else {
+            const double d = Q(dh[o]);
+            gbf[o] += d;
+            for (int64_t i = 0; i < flat; ++i) {
+                gWf[o * flat + i] += d * Q(xin[i]);
+                dcur[i] += d * Q(Wf[o * flat + i]);
+            }
         }
     }
 
@@ -332,6 +396,20 @@ static void backward_one(const orc_net *net, const double *theta, const int64_t 
                     int64_t yi = (o * OH + i) * OW + j;
                     if (!(y[yi] > 0.0)) continue;          /* ReLU */
                     double d = dcur[yi];
+                    if (q) {        /* operands rounded; the first layer multiplies the raw bytes */
+                        const double xs = l == 0 ? 255.0 : 1.0;
+                        d = Q(d);
+                        gb[o] += d;
+                        for (int cc = 0; cc < C; ++cc)
+                            for (int u = 0; u < K; ++u)
+                                for (int v = 0; v < K; ++v) {
+                                    int64_t wi = ((o * C + cc) * K + u) * K + v;
+                                    int64_t xi = (cc * H + i * S + u) * W + j * S + v;
+                                    gw[wi] += d * Q(xs * x[xi]) / xs;
+                                    if (l > 0) dprev[xi] += d * Q(wt[wi]);
+                                }
+                        continue;
+                    }
                     gb[o] += d;
                     for (int cc = 0; cc < C; ++cc)
                         for (int u = 0; u < K; ++u)

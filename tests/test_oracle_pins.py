@@ -419,3 +419,91 @@ def test_train_step_composes_clip_and_rmsprop():
     g1 = 0.99 * g0 + 0.01 * d * d
     np.testing.assert_allclose(res["g"], g1, rtol=1e-13)
     np.testing.assert_allclose(res["theta"], th - 1e-2 * d / np.sqrt(g1 + 0.1), rtol=1e-13, atol=1e-16)
+
+
+# -------------------------------------------------- bfloat16-operand variant --
+
+def test_bf16_round_matches_torch_and_closed_forms():
+    # the rounding that math = 1 applies, against an independent implementation and by hand
+    x = np.concatenate([synth.rng(131).standard_normal(4000) * np.exp(synth.rng(132).standard_normal(4000) * 4),
+                        np.arange(0, 256, dtype=np.float64), [0.0, -0.0, 1.0, -1.0, 2.0 ** -20, 3.0e38]])
+    want = torch.from_numpy(x.astype(np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+    np.testing.assert_array_equal(orc.bf16_round(x), want)
+    # 8 significant bits: bytes are exact; 257 = 1.00000001b * 2^8 is a tie and goes to the even neighbour 256
+    np.testing.assert_array_equal(orc.bf16_round(np.arange(256.0)), np.arange(256.0))
+    assert orc.bf16_round([257.0])[0] == 256.0 and orc.bf16_round([259.0])[0] == 260.0
+    assert orc.bf16_round([1.0 + 2.0 ** -8])[0] == 1.0 and orc.bf16_round([1.0 + 3 * 2.0 ** -8])[0] == 1.0 + 2.0 ** -6
+
+
+def _bf16_net(net):
+    return orc.Net(in_c=net.in_c, in_h=net.in_h, in_w=net.in_w, conv=net.conv, fc_units=net.fc_units,
+                   n_actions=net.n_actions, math=1)
+
+
+def test_bf16_variant_equals_fp64_on_representable_operands():
+    # if every operand of every contraction is already a bfloat16 number, rounding changes nothing: parameters on
+    # a coarse dyadic grid, a one-layer network (so no computed activation is an operand besides the bytes) and
+    # head gradients that are powers of two
+    net = orc.Net(in_c=2, in_h=9, in_w=9, conv=((3, 3, 2),), fc_units=4, n_actions=3)
+    th = np.round(theta_for(net, 141) * 64) / 64          # multiples of 1/64 below 2: at most 7 significant bits
+    assert np.array_equal(orc.bf16_round(th), th)
+    frames = synth.uniform_frames(142, (5, 2, 9, 9))
+    a = orc.forward(net, th, frames, want_acts=True)
+    b = orc.forward(_bf16_net(net), th, frames, want_acts=True)
+    # conv output is exact in both; the fc layer then sees activations that are not bfloat16 numbers, so compare it
+    off = orc.offsets(net)
+    n_in = 2 * 9 * 9
+    n_c1 = 3 * 4 * 4
+    np.testing.assert_allclose(b["acts"][:, n_in:n_in + n_c1], a["acts"][:, n_in:n_in + n_c1], rtol=1e-14, atol=1e-14)
+
+
+def test_bf16_variant_is_the_fp64_network_of_rounded_operands():
+    # forward: rounding parameters and every layer input by hand and running math = 0 layer by layer must give
+    # what math = 1 gives in one go (checked on the logits through a hand-rolled numpy forward)
+    net = TINY
+    th = theta_for(net, 151)
+    frames = synth.uniform_frames(152, (4, net.in_c, net.in_h, net.in_w))
+    got = orc.forward(_bf16_net(net), th, frames)
+    v = orc.views(net, th)
+    q = orc.bf16_round
+    x = frames.astype(np.float64)                            # raw bytes: exact operands
+    scale = 1.0 / 255.0
+    for l, (oc, k, s) in enumerate(net.conv):
+        W = q(v[f"conv{l + 1}.W"]); bvec = v[f"conv{l + 1}.b"]
+        y = torch.nn.functional.conv2d(torch.from_numpy(q(x)), torch.from_numpy(W), None, stride=s).numpy()
+        x = np.maximum(y * scale + bvec[None, :, None, None], 0.0)
+        scale = 1.0
+    flat = x.reshape(x.shape[0], -1)
+    h = np.maximum(q(flat) @ q(v["fc.W"]).T + v["fc.b"], 0.0)
+    logits = q(h) @ q(v["policy.W"]).T + v["policy.b"]
+    values = q(h) @ q(v["value.W"]).reshape(-1) + v["value.b"][0]
+    np.testing.assert_allclose(got["logits"], logits, rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(got["values"], values, rtol=1e-11, atol=1e-12)
+    # and it is close to, but not the same as, the exact network
+    exact = orc.forward(net, th, frames)
+    err = np.abs(got["logits"] - exact["logits"]).max() / np.abs(exact["logits"]).max()
+    assert 1e-5 < err < 3e-2
+
+
+def test_bf16_variant_backward_is_linear_in_rounded_operands():
+    # gradients: with one frame the weight gradient of the heads is the outer product of the rounded head
+    # gradient and the rounded fc output, the bias gradient the rounded head gradient itself
+    net = TINY
+    th = theta_for(net, 161)
+    frames = synth.uniform_frames(162, (1, net.in_c, net.in_h, net.in_w))
+    bn = _bf16_net(net)
+    fw = orc.forward(bn, th, frames, want_acts=True)
+    A, F = net.n_actions, net.fc_units
+    dZ = synth.rng(163).standard_normal((1, A)); dV = synth.rng(164).standard_normal(1)
+    g = orc.views(net, orc.backward(bn, th, fw["acts"], dZ, dV))
+    q = orc.bf16_round
+    h = fw["acts"][0, -F:]
+    np.testing.assert_allclose(g["policy.W"], np.outer(q(dZ[0]), q(h)), rtol=1e-13, atol=1e-15)
+    np.testing.assert_allclose(g["policy.b"], q(dZ[0]), rtol=0, atol=0)
+    np.testing.assert_allclose(g["value.W"].reshape(-1), q(dV)[0] * q(h), rtol=1e-13, atol=1e-15)
+    # fc weight gradient = outer(q(dh), q(flat)), dh = mask * (q(dZ) q(Wp) + q(dV) q(Wv))
+    v = orc.views(net, th)
+    dh = (q(dZ[0]) @ q(v["policy.W"]) + q(dV)[0] * q(v["value.W"]).reshape(-1)) * (h > 0)
+    flat = fw["acts"][0, -F - g["fc.W"].shape[1]:-F]
+    np.testing.assert_allclose(g["fc.W"], np.outer(q(dh), q(flat)), rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(g["fc.b"], q(dh), rtol=0, atol=0)
