@@ -68,6 +68,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--agents", type=int, default=512)
     ap.add_argument("--net", choices=("small", "large"), default="small")
+    ap.add_argument("--math", type=int, choices=(0, 1), default=0,
+                    help="0: fp32 accuracy (default); 1: operands of every contraction rounded to bfloat16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rmsprop-big", action="store_true", help="also time RMSProp on 2^28 parameters")
     ap.add_argument("--mixed-seconds", type=float, default=1.0,
@@ -89,7 +91,8 @@ def main() -> int:
         return 2
     torch.cuda.set_device(0)
     N, T, A = args.agents, 5, 18
-    desc = g.SMALL_NET(A) if args.net == "small" else g.LARGE_NET(A)
+    import dataclasses
+    desc = dataclasses.replace(g.SMALL_NET(A) if args.net == "small" else g.LARGE_NET(A), math=args.math)
     net = g.Ga3c(desc, max(N, 1024), N * T)
     net.params_init(synth.BASE_SEED)
     hp = g.HParams(clip_norm=40.0)
@@ -190,8 +193,10 @@ def main() -> int:
         "metric": "frames/s through predict and train_step, balanced (PPS = TPS*t_max)",
         "value": round(frames_per_step / sec, 1), "unit": "frames/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(sec * 1e3, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "arithmetic": "fp32 MFMA with fp32 accumulate; conv1 as exact 3-term bf16 MFMA (bytes are exact in bf16)",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32" if args.math == 0 else "bf16", "data": "synthetic",
+        "arithmetic": ("fp32 accuracy with fp32 accumulation: fp32 MFMA, or fp32 operands split exactly into three bf16 "
+                       "terms on the bf16 MFMA (bytes are exact in bf16)") if args.math == 0 else
+                      "operands of every contraction rounded to bfloat16, exact products, fp32 accumulation, fp32 parameters",
         "config": {"workload": f"configs[1]+[2]: {args.net} net, 18 actions; per step {T}x predict B={N} "
                                f"and 1 train_step {N} agents x t_max={T} = {N * T} frames, "
                                "clip 40", "agents": N, "t_max": T, "seed": seed},
@@ -223,7 +228,7 @@ def main() -> int:
 
     if not args.no_cpu_baseline:
         import oracle as orc
-        onet = orc.Net(conv=tuple(desc.conv), fc_units=desc.fc_units, n_actions=A)
+        onet = orc.Net(conv=tuple(desc.conv), fc_units=desc.fc_units, n_actions=A, math=args.math)
         theta = theta_np.astype(np.float64)
         cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
         t0 = time.perf_counter()

@@ -66,7 +66,7 @@ typedef struct {
     struct { int oc, k, stride; } conv[GA3C_MAX_CONV];
     int fc_units;
     int n_actions;
-    int math;                             /* 0 = fp32 MFMA (the only mode built so far) */
+    int math;                             /* 0 = fp32 accuracy; 1 = both operands of every contraction rounded to bfloat16 */
 } ga3c_net_desc;
 
 /* Hyper-parameters of one update, read on the host at call time.

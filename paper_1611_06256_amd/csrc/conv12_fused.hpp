@@ -45,7 +45,7 @@ constexpr int C12_FRAG_SET = 3 * 8 * 64;             // 16-byte vectors of one f
 // One block of 192 threads; runs whenever the parameters change.
 __global__ __launch_bounds__(192) void conv12_filter_fragments_kernel(const float *__restrict__ w1,
                                                                       const float *__restrict__ w2,
-                                                                      u32x4 *__restrict__ frag) {
+                                                                      u32x4 *__restrict__ frag, int rb) {
     constexpr int K = 256;
     const int lane = threadIdx.x & 63, set = threadIdx.x >> 6;
     const int l16 = lane & 15, g = lane >> 4, kh = set - 1;
@@ -60,7 +60,7 @@ __global__ __launch_bounds__(192) void conv12_filter_fragments_kernel(const floa
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             __bf16 th, tm, tl;
-            split3(set == 0 ? f[e] : f[PERM[e]], th, tm, tl);
+            split3(set == 0 ? f[e] : f[PERM[e]], th, tm, tl, rb);
             h.v[e] = th; m.v[e] = tm; l.v[e] = tl;
         }
         u32x4 *dst = frag + (size_t)set * C12_FRAG_SET + lane;
@@ -72,13 +72,14 @@ __global__ __launch_bounds__(192) void conv12_filter_fragments_kernel(const floa
 
 // The same fragments, four filter taps at a time: `rel` (a multiple of 4) is the index of v.x in the layer's
 // filter tensor [oc][256].  Lets the kernel that updates the parameters keep the fragments current.
-__device__ __forceinline__ void conv12_store_fragment4(u32x4 *__restrict__ frag, int layer2, int rel, const float4 v) {
+__device__ __forceinline__ void conv12_store_fragment4(u32x4 *__restrict__ frag, int layer2, int rel, const float4 v,
+                                                       int rb) {
     const int oc = rel >> 8, k = rel & 255;
     const int kb = k >> 5, g = (k >> 3) & 3, e0 = k & 7;               // e0 = 0 or 4
     const float f[4] = {v.x, v.y, v.z, v.w};
     union { __bf16 h[4]; uint32_t u[2]; } o[3];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) split3(f[e], o[0].h[e], o[1].h[e], o[2].h[e]);
+    for (int e = 0; e < 4; ++e) split3(f[e], o[0].h[e], o[1].h[e], o[2].h[e], rb);
     if (!layer2) {
         uint32_t *dst = (uint32_t *)(frag + (size_t)kb * 64 + g * 16 + oc) + e0 / 2;
 #pragma unroll
@@ -98,8 +99,8 @@ __device__ __forceinline__ void conv12_store_fragment4(u32x4 *__restrict__ frag,
     }
 }
 
-inline hipError_t launch_conv12_filter_fragments(const float *w1, const float *w2, u32x4 *frag, hipStream_t s) {
-    hipLaunchKernelGGL(conv12_filter_fragments_kernel, dim3(1), dim3(192), 0, s, w1, w2, frag);
+inline hipError_t launch_conv12_filter_fragments(const float *w1, const float *w2, u32x4 *frag, hipStream_t s, int rb) {
+    hipLaunchKernelGGL(conv12_filter_fragments_kernel, dim3(1), dim3(192), 0, s, w1, w2, frag, rb);
     return hipGetLastError();
 }
 
@@ -109,7 +110,8 @@ __global__ __launch_bounds__(512, 1) void conv12_fused_fwd_kernel(const uint8_t 
                                                                   const u32x4 *__restrict__ frag,
                                                                   const float *__restrict__ b1,
                                                                   const float *__restrict__ b2, float *__restrict__ y1,
-                                                                  float *__restrict__ y2, int nframes, float scale) {
+                                                                  float *__restrict__ y2, int nframes, float scale,
+                                                                  int rb) {
     constexpr int CHW1 = 4 * 84 * 84, W1 = 84, NPIX1 = 400, OW1 = 20;
     constexpr int NV = CHW1 / 16, VPT = 7;                         // 16-byte vectors of a frame, per layer-1 thread
     constexpr int HW2 = 400, NPIX2 = 81, OW2 = 9, OC2 = 32;
@@ -207,7 +209,7 @@ __global__ __launch_bounds__(512, 1) void conv12_fused_fwd_kernel(const uint8_t 
                         v = v > 0.f ? v : 0.f;
                         if (yb) yb[(4 * g + r) * NPIX1 + p] = v;
                         __bf16 h, m, l;
-                        split3(v, h, m, l);
+                        split3(v, h, m, l, rb);
                         const int e = (4 * g + r) * HW2 + blk;
                         yp[e] = h; yp[C12_Y1 + e] = m; yp[2 * C12_Y1 + e] = l;
                     }
@@ -315,7 +317,7 @@ __global__ __launch_bounds__(512, 1) void conv12_fused_fwd_kernel(const uint8_t 
 inline int conv12_fused_blocks(int nframes) { return nframes < 256 ? nframes : 256; }
 
 inline hipError_t launch_conv12_fused_fwd(const uint8_t *x, const u32x4 *frag, const float *b1, const float *b2, float *y1,
-                                          float *y2, int nframes, float scale, hipStream_t s) {
+                                          float *y2, int nframes, float scale, hipStream_t s, int rb) {
     if (nframes <= 0) return hipSuccess;
     static bool attr_set = false;     // the kernel needs more LDS than the default limit
     if (!attr_set) {
@@ -325,7 +327,7 @@ inline hipError_t launch_conv12_fused_fwd(const uint8_t *x, const u32x4 *frag, c
         attr_set = true;
     }
     hipLaunchKernelGGL(conv12_fused_fwd_kernel, dim3(conv12_fused_blocks(nframes)), dim3(512), C12_LDS_BYTES, s, x, frag, b1,
-                       b2, y1, y2, nframes, scale);
+                       b2, y1, y2, nframes, scale, rb);
     return hipGetLastError();
 }
 

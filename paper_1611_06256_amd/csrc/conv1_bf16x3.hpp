@@ -37,6 +37,13 @@ __device__ __forceinline__ void split3(float f, __bf16 &hi, __bf16 &mid, __bf16 
     mid = (__bf16)r1;
     lo = (__bf16)(r1 - (float)mid);
 }
+// The same with a switch: rb != 0 keeps only hi, i.e. the operand rounded to
+// bfloat16 (the reduced-precision variant of the network); the kernels then
+// multiply zeros in the other two terms.
+__device__ __forceinline__ void split3(float f, __bf16 &hi, __bf16 &mid, __bf16 &lo, int rb) {
+    split3(f, hi, mid, lo);
+    if (rb) { mid = (__bf16)0.f; lo = (__bf16)0.f; }
+}
 
 // 16 bytes -> 16 bf16 (two 16-byte vectors)
 __device__ __forceinline__ void bytes_to_bf16(const u32x4 b, u32x4 &lo8, u32x4 &hi8) {
@@ -62,7 +69,7 @@ template <int OC>
 __global__ __launch_bounds__(256, 2) void conv1_bf16x3_fwd_kernel(const uint8_t *__restrict__ x,
                                                                   const float *__restrict__ w,
                                                                   const float *__restrict__ bias, float *__restrict__ y,
-                                                                  int nframes, float scale) {
+                                                                  int nframes, float scale, int rb) {
     constexpr int C = 4, H = 84, W = 84, S = 4, OW = 20, NPIX = 400, K = 256, CHW = C * H * W;
     constexpr int NV = CHW / 16, VPT = (NV + 255) / 256;           // 16-byte vectors of the byte frame
     constexpr int OT = OC / 16, JOBS = 25 * OT, TPW = (JOBS + 3) / 4;
@@ -87,7 +94,7 @@ __global__ __launch_bounds__(256, 2) void conv1_bf16x3_fwd_kernel(const uint8_t 
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             __bf16 h, m, l;
-            split3(f[e], h, m, l);
+            split3(f[e], h, m, l, rb);
             wq[0][kb][e] = h; wq[1][kb][e] = m; wq[2][kb][e] = l;
         }
     }
@@ -166,10 +173,10 @@ __global__ __launch_bounds__(256, 2) void conv1_bf16x3_fwd_kernel(const uint8_t 
 
 template <int OC>
 inline hipError_t launch_conv1_bf16x3_fwd(const uint8_t *x, const float *w, const float *bias, float *y, int nframes,
-                                          float scale, hipStream_t s) {
+                                          float scale, hipStream_t s, int rb = 0) {
     if (nframes <= 0) return hipSuccess;
     const int grid = nframes < 512 ? nframes : 512;
-    hipLaunchKernelGGL((conv1_bf16x3_fwd_kernel<OC>), dim3(grid), dim3(256), 0, s, x, w, bias, y, nframes, scale);
+    hipLaunchKernelGGL((conv1_bf16x3_fwd_kernel<OC>), dim3(grid), dim3(256), 0, s, x, w, bias, y, nframes, scale, rb);
     return hipGetLastError();
 }
 
@@ -188,7 +195,9 @@ inline hipError_t launch_conv1_bf16x3_fwd(const uint8_t *x, const float *w, cons
 // part: [gridDim.x][16][257]; the last column is the bias gradient.
 __global__ __launch_bounds__(256) void conv1_bf16x3_wgrad_kernel(const uint8_t *__restrict__ x,
                                                                  const float *__restrict__ dy,
-                                                                 float *__restrict__ part, int nframes, float scale) {
+                                                                 float *__restrict__ part, int nframes, float scale,
+                                                                 int rb) {
+    // rb: dY enters the products (and the bias sums) rounded to bfloat16
     constexpr int C = 4, H = 84, W = 84, OC = 16, OH = 20, NPIX = 400, K = 256, CHW = C * H * W;
     constexpr int XROW = 32, XPLANE = 21 * XROW + 8;       // bf16 elements; plane pitch 20 mod 32 dwords
     constexpr int DROW = 24, DOC = OH * DROW + 8;          // dY rows padded to 24, filter pitch 20 mod 32 dwords
@@ -269,10 +278,11 @@ __global__ __launch_bounds__(256) void conv1_bf16x3_wgrad_kernel(const uint8_t *
                 const float v[4] = {dpre[i].x, dpre[i].y, dpre[i].z, dpre[i].w};
                 union { __bf16 h[4]; uint2 u; } o[3];
 #pragma unroll
-                for (int t = 0; t < 4; ++t) split3(v[t], o[0].h[t], o[1].h[t], o[2].h[t]);
+                for (int t = 0; t < 4; ++t) split3(v[t], o[0].h[t], o[1].h[t], o[2].h[t], rb);
 #pragma unroll
                 for (int term = 0; term < 3; ++term) *(uint2 *)(dp + term * OC * DOC + ddst[i]) = o[term].u;
-                bsh[tid + 256 * i] = (v[0] + v[1]) + (v[2] + v[3]);
+                bsh[tid + 256 * i] = rb ? ((float)o[0].h[0] + (float)o[0].h[1]) + ((float)o[0].h[2] + (float)o[0].h[3])
+                                        : (v[0] + v[1]) + (v[2] + v[3]);
             }
         }
         __syncthreads();
@@ -324,10 +334,10 @@ __global__ __launch_bounds__(256) void conv1_bf16x3_wgrad_kernel(const uint8_t *
 inline int conv1_bf16x3_wgrad_blocks(int nframes) { return nframes < 256 ? nframes : 256; }
 
 inline hipError_t launch_conv1_bf16x3_wgrad(const uint8_t *x, const float *dy, float *part, int nframes, float scale,
-                                            hipStream_t s) {
+                                            hipStream_t s, int rb = 0) {
     if (nframes <= 0) return hipSuccess;
     hipLaunchKernelGGL(conv1_bf16x3_wgrad_kernel, dim3(conv1_bf16x3_wgrad_blocks(nframes)), dim3(256), 0, s, x, dy, part,
-                       nframes, scale);
+                       nframes, scale, rb);
     return hipGetLastError();
 }
 

@@ -19,7 +19,7 @@ namespace ga3c {
 __global__ __launch_bounds__(256, 2) void conv2_bf16x6_fwd_kernel(const float *__restrict__ x,
                                                                   const float *__restrict__ w,
                                                                   const float *__restrict__ bias, float *__restrict__ y,
-                                                                  int nframes) {
+                                                                  int nframes, int rb) {
     constexpr int C = 16, H = 20, W = 20, OC = 32, S = 2, OW = 9, NPIX = 81, K = 256, CHW = C * H * W;
     constexpr int NV = CHW / 4, VPT = (NV + 255) / 256;      // float4 per frame / per thread
     constexpr int TPW = 3;
@@ -39,7 +39,7 @@ __global__ __launch_bounds__(256, 2) void conv2_bf16x6_fwd_kernel(const float *_
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             __bf16 h, m, l;
-            split3(f[e], h, m, l);
+            split3(f[e], h, m, l, rb);
             wq[0][kb][e] = h; wq[1][kb][e] = m; wq[2][kb][e] = l;
         }
     }
@@ -74,7 +74,7 @@ __global__ __launch_bounds__(256, 2) void conv2_bf16x6_fwd_kernel(const float *_
             const float v[4] = {pre[i].x, pre[i].y, pre[i].z, pre[i].w};
             union { __bf16 h[4]; uint2 u; } o[3];
 #pragma unroll
-            for (int t = 0; t < 4; ++t) split3(v[t], o[0].h[t], o[1].h[t], o[2].h[t]);
+            for (int t = 0; t < 4; ++t) split3(v[t], o[0].h[t], o[1].h[t], o[2].h[t], rb);
 #pragma unroll
             for (int term = 0; term < 3; ++term) *(uint2 *)(&xs[term][(tid + 256 * i) * 4]) = o[term].u;
         }
@@ -122,10 +122,10 @@ __global__ __launch_bounds__(256, 2) void conv2_bf16x6_fwd_kernel(const float *_
 }
 
 inline hipError_t launch_conv2_bf16x6_fwd(const float *x, const float *w, const float *bias, float *y, int nframes,
-                                          hipStream_t s) {
+                                          hipStream_t s, int rb = 0) {
     if (nframes <= 0) return hipSuccess;
     const int grid = nframes < 512 ? nframes : 512;
-    hipLaunchKernelGGL(conv2_bf16x6_fwd_kernel, dim3(grid), dim3(256), 0, s, x, w, bias, y, nframes);
+    hipLaunchKernelGGL(conv2_bf16x6_fwd_kernel, dim3(grid), dim3(256), 0, s, x, w, bias, y, nframes, rb);
     return hipGetLastError();
 }
 

@@ -40,6 +40,18 @@ struct ConvSpec {
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
+// Four floats held as raw bits, each rounded to bfloat16 and back (the
+// reduced-precision variant rounds float operands while they are staged; bytes
+// are exact and pass unchanged).
+template <class TIn>
+__device__ __forceinline__ u32x4 stage_round(u32x4 v, int rb) {
+    if (sizeof(TIn) == 4 && rb) {
+#pragma unroll
+        for (int d = 0; d < 4; ++d) v[d] = __float_as_uint(bf16_rne(__uint_as_float(v[d])));
+    }
+    return v;
+}
+
 __device__ __forceinline__ floatx4 mfma4(float a, float b, floatx4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
 }
@@ -63,7 +75,9 @@ template <class SP, int OCS = SP::OC>
 __global__ __launch_bounds__(256, 2) void conv_fwd_frame_kernel(const typename SP::TIn *__restrict__ x,
                                                                 const float *__restrict__ w,
                                                                 const float *__restrict__ bias,
-                                                                float *__restrict__ y, int nframes, float scale) {
+                                                                float *__restrict__ y, int nframes, float scale,
+                                                                int rb) {
+    // rb: filters and (float) frames are rounded to bfloat16 on their way to LDS
     typedef typename SP::TIn TIn;
     constexpr int FRAME_BYTES = SP::CHW * (int)sizeof(TIn);
     static_assert(FRAME_BYTES % 16 == 0, "frame size must be a multiple of 16 bytes");
@@ -92,13 +106,14 @@ __global__ __launch_bounds__(256, 2) void conv_fwd_frame_kernel(const typename S
         for (int e = tid; e < OCS * SP::K / 4; e += 256) {
             const int oc = e / (SP::K / 4), kq = e % (SP::K / 4);
             const float4 v = *(const float4 *)(w + (size_t)oc * SP::K + 4 * kq);
-            *(float4 *)(ws + oc * SP::WPITCH + 4 * kq) = v;
+            *(float4 *)(ws + oc * SP::WPITCH + 4 * kq) = rb ? bf16_rne(v) : v;
         }
     } else {   // position tap * C + c holds W[oc][c][tap]
         for (int e = tid; e < OCS * SP::K; e += 256) {
             const int oc = e / SP::K, kk = e % SP::K;
             const int tap = kk / SP::C, c = kk % SP::C;
-            ws[oc * SP::WPITCH + kk] = w[(size_t)oc * SP::K + c * (SP::KS * SP::KS) + tap];
+            const float v = w[(size_t)oc * SP::K + c * (SP::KS * SP::KS) + tap];
+            ws[oc * SP::WPITCH + kk] = rb ? bf16_rne(v) : v;
         }
     }
     float bv[4];
@@ -146,7 +161,7 @@ __global__ __launch_bounds__(256, 2) void conv_fwd_frame_kernel(const typename S
     for (; f < nframes; f += gridDim.x) {
         __syncthreads();                       // everyone is done with the previous frame
 #pragma unroll
-        for (int i = 0; i < VPT; ++i) ((u32x4 *)xs_raw)[tid + 256 * i] = pre[i];
+        for (int i = 0; i < VPT; ++i) ((u32x4 *)xs_raw)[tid + 256 * i] = stage_round<TIn>(pre[i], rb);
         __syncthreads();
         {   // fetch the next frame while this one is computed
             const u32x4 *src = (const u32x4 *)(x + (size_t)min(f + (int)gridDim.x, nframes - 1) * SP::CHW);
@@ -198,12 +213,13 @@ __global__ __launch_bounds__(256, 2) void conv_fwd_frame_kernel(const typename S
 // `blocks`: how many blocks the chip holds at once (LDS decides), shared out over the slices.
 template <class SP, int OCS = SP::OC>
 inline hipError_t launch_conv_fwd_frame(const typename SP::TIn *x, const float *w, const float *bias, float *y,
-                                        int nframes, float scale, hipStream_t s, int blocks = 512) {
+                                        int nframes, float scale, hipStream_t s, int blocks = 512, int rb = 0) {
     if (nframes <= 0) return hipSuccess;
     constexpr int SLICES = SP::OC / OCS;
     const int per = blocks / SLICES;
     const int grid = nframes < per ? nframes : per;
-    hipLaunchKernelGGL((conv_fwd_frame_kernel<SP, OCS>), dim3(grid, SLICES), dim3(256), 0, s, x, w, bias, y, nframes, scale);
+    hipLaunchKernelGGL((conv_fwd_frame_kernel<SP, OCS>), dim3(grid, SLICES), dim3(256), 0, s, x, w, bias, y, nframes, scale,
+                       rb);
     return hipGetLastError();
 }
 
@@ -223,7 +239,9 @@ inline hipError_t launch_conv_fwd_frame(const typename SP::TIn *x, const float *
 template <class SP, int KSL = 1>
 __global__ __launch_bounds__(256, 2) void conv_wgrad_frame_kernel(const typename SP::TIn *__restrict__ x,
                                                                   const float *__restrict__ dy,
-                                                                  float *__restrict__ part, int nframes, float scale) {
+                                                                  float *__restrict__ part, int nframes, float scale,
+                                                                  int rb) {
+    // rb: dY and (float) frames are rounded to bfloat16 on their way to LDS; the bias sums take the rounded dY
     typedef typename SP::TIn TIn;
     constexpr int FRAME_BYTES = SP::CHW * (int)sizeof(TIn);
     constexpr int NV = FRAME_BYTES / 16, VPT = (NV + 255) / 256;
@@ -290,9 +308,9 @@ __global__ __launch_bounds__(256, 2) void conv_wgrad_frame_kernel(const typename
     for (; f < nframes; f += gridDim.x) {
         __syncthreads();
 #pragma unroll
-        for (int i = 0; i < VPT; ++i) ((u32x4 *)xs_raw)[tid + 256 * i] = pre[i];
+        for (int i = 0; i < VPT; ++i) ((u32x4 *)xs_raw)[tid + 256 * i] = stage_round<TIn>(pre[i], rb);
 #pragma unroll
-        for (int i = 0; i < DPT; ++i) ds[dlds[i]] = dpre[i];
+        for (int i = 0; i < DPT; ++i) ds[dlds[i]] = rb ? bf16_rne(dpre[i]) : dpre[i];
         __syncthreads();
         {
             const int ff = min(f + (int)gridDim.x, nframes - 1);
@@ -352,10 +370,10 @@ inline int conv_wgrad_frame_blocks(int nframes) {
 
 template <class SP, int KSL = 1>
 inline hipError_t launch_conv_wgrad_frame(const typename SP::TIn *x, const float *dy, float *part, int nframes,
-                                          float scale, hipStream_t s) {
+                                          float scale, hipStream_t s, int rb = 0) {
     if (nframes <= 0) return hipSuccess;
     hipLaunchKernelGGL((conv_wgrad_frame_kernel<SP, KSL>), dim3(conv_wgrad_frame_blocks<SP>(nframes), KSL), dim3(256), 0, s, x,
-                       dy, part, nframes, scale);
+                       dy, part, nframes, scale, rb);
     return hipGetLastError();
 }
 
@@ -374,7 +392,8 @@ template <class SP>
 __global__ __launch_bounds__(256, 2) void conv_dgrad_frame_kernel(const float *__restrict__ dy,
                                                                   const float *__restrict__ w,
                                                                   const float *__restrict__ xin,
-                                                                  float *__restrict__ dx, int nframes) {
+                                                                  float *__restrict__ dx, int nframes, int rb) {
+    // rb: filters and dY are rounded to bfloat16 on their way to LDS
     static_assert(SP::KS == 2 * SP::S && SP::S == 2, "kernel must be 4x4 with stride 2");
     static_assert(SP::C % 16 == 0, "whole row tiles of input channels");
     constexpr int CS = 16;                                         // input channels of a block
@@ -403,7 +422,8 @@ __global__ __launch_bounds__(256, 2) void conv_dgrad_frame_kernel(const float *_
         const int ph = e / (CS * KP), c = (e / KP) % CS, k = e % KP;
         const int oc = k / 4, a = (k / 2) % 2, ee = k % 2;
         const int u = ph / S + S * a, v = ph % S + S * ee;
-        wp[(ph * CS + c) * WP + k] = w[((size_t)(oc * SP::C + c0 + c) * SP::KS + u) * SP::KS + v];
+        const float wv = w[((size_t)(oc * SP::C + c0 + c) * SP::KS + u) * SP::KS + v];
+        wp[(ph * CS + c) * WP + k] = rb ? bf16_rne(wv) : wv;
     }
     for (int e = tid; e < SP::OC * OCP; e += 256) dp[e] = 0.f;
 
@@ -441,7 +461,7 @@ __global__ __launch_bounds__(256, 2) void conv_dgrad_frame_kernel(const float *_
     for (; f < nframes; f += gridDim.x) {
         __syncthreads();
 #pragma unroll
-        for (int i = 0; i < DPT; ++i) dp[dlds[i]] = dpre[i];
+        for (int i = 0; i < DPT; ++i) dp[dlds[i]] = rb ? bf16_rne(dpre[i]) : dpre[i];
         __syncthreads();
         {
             const float *dsrc = dy + (size_t)min(f + (int)gridDim.x, nframes - 1) * NDY;
@@ -494,12 +514,12 @@ __global__ __launch_bounds__(256, 2) void conv_dgrad_frame_kernel(const float *_
 // `blocks`: how many blocks the chip holds at once (LDS decides), shared out over the channel slices.
 template <class SP>
 inline hipError_t launch_conv_dgrad_frame(const float *dy, const float *w, const float *xin, float *dx, int nframes,
-                                          hipStream_t s, int blocks = 512) {
+                                          hipStream_t s, int blocks = 512, int rb = 0) {
     if (nframes <= 0) return hipSuccess;
     constexpr int SLICES = SP::C / 16;
     const int per = blocks / SLICES;
     const int grid = nframes < per ? nframes : per;
-    hipLaunchKernelGGL((conv_dgrad_frame_kernel<SP>), dim3(grid, SLICES), dim3(256), 0, s, dy, w, xin, dx, nframes);
+    hipLaunchKernelGGL((conv_dgrad_frame_kernel<SP>), dim3(grid, SLICES), dim3(256), 0, s, dy, w, xin, dx, nframes, rb);
     return hipGetLastError();
 }
 
@@ -517,7 +537,8 @@ inline hipError_t launch_conv_dgrad_frame(const float *dy, const float *w, const
 template <class SP, int CS>
 __global__ __launch_bounds__(256) void conv_dgrad_s1_frame_kernel(const float *__restrict__ dy, const float *__restrict__ w,
                                                                   const float *__restrict__ xin, float *__restrict__ dx,
-                                                                  int nframes) {
+                                                                  int nframes, int rb) {
+    // rb: filters and dY are rounded to bfloat16 on their way to LDS
     static_assert(SP::S == 1, "stride 1");
     static_assert(SP::OC % 16 == 0 && CS % 16 == 0 && SP::C % CS == 0, "whole MFMA tiles");
     constexpr int P = SP::KS - 1, PH = SP::OH + 2 * P, PW = SP::OW + 2 * P;
@@ -540,7 +561,8 @@ __global__ __launch_bounds__(256) void conv_dgrad_s1_frame_kernel(const float *_
         const int c = e / KP, k = e % KP;
         const int tap = k / SP::OC, oc = k % SP::OC;
         const int u = P - tap / SP::KS, v = P - tap % SP::KS;
-        wp[c * WP + k] = w[((size_t)(oc * SP::C + c0 + c) * SP::KS + u) * SP::KS + v];
+        const float wv = w[((size_t)(oc * SP::C + c0 + c) * SP::KS + u) * SP::KS + v];
+        wp[c * WP + k] = rb ? bf16_rne(wv) : wv;
     }
     for (int e = tid; e < SP::OC * OCP; e += 256) dp[e] = 0.f;      // the border stays zero
 
@@ -573,7 +595,7 @@ __global__ __launch_bounds__(256) void conv_dgrad_s1_frame_kernel(const float *_
     for (; f < nframes; f += gridDim.x) {
         __syncthreads();
 #pragma unroll
-        for (int i = 0; i < DPT; ++i) dp[dlds[i]] = dpre[i];
+        for (int i = 0; i < DPT; ++i) dp[dlds[i]] = rb ? bf16_rne(dpre[i]) : dpre[i];
         __syncthreads();
         {
             const float *dsrc = dy + (size_t)min(f + (int)gridDim.x, nframes - 1) * NDY;
@@ -620,12 +642,12 @@ __global__ __launch_bounds__(256) void conv_dgrad_s1_frame_kernel(const float *_
 
 template <class SP, int CS>
 inline hipError_t launch_conv_dgrad_s1_frame(const float *dy, const float *w, const float *xin, float *dx, int nframes,
-                                             hipStream_t s, int blocks) {
+                                             hipStream_t s, int blocks, int rb) {
     if (nframes <= 0) return hipSuccess;
     constexpr int SLICES = SP::C / CS;
     const int per = blocks / SLICES;
     const int grid = nframes < per ? nframes : per;
-    hipLaunchKernelGGL((conv_dgrad_s1_frame_kernel<SP, CS>), dim3(grid, SLICES), dim3(256), 0, s, dy, w, xin, dx, nframes);
+    hipLaunchKernelGGL((conv_dgrad_s1_frame_kernel<SP, CS>), dim3(grid, SLICES), dim3(256), 0, s, dy, w, xin, dx, nframes, rb);
     return hipGetLastError();
 }
 

@@ -37,6 +37,7 @@ struct DenseGemmArgs {
     float *C;                // DG_PARTIAL: [nz][M][N]; otherwise [M][ldc]
     long ldc;
     const float *aux;        // bias[n] or mask[m*ldc + n]
+    int rb;                  // round both operands to bfloat16 on the way to LDS
 };
 
 constexpr int DG_XCDS = 8;
@@ -123,16 +124,18 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void dense_gemm_kernel(const DenseG
 #pragma unroll
         for (int it = 0; it < AI; ++it) {
             const int e = tid + it * NT;
-            if (!A_ROWMAJOR) *(float4 *)(As + ((e % QK) * (BM + 1) + e / QK) * 4) = r[it];
-            else *(float4 *)(As + (e / (BM / 4)) * (BM + 4) + 4 * (e % (BM / 4))) = r[it];
+            const float4 v = p.rb ? bf16_rne(r[it]) : r[it];
+            if (!A_ROWMAJOR) *(float4 *)(As + ((e % QK) * (BM + 1) + e / QK) * 4) = v;
+            else *(float4 *)(As + (e / (BM / 4)) * (BM + 4) + 4 * (e % (BM / 4))) = v;
         }
     };
     auto stashB = [&](const float4 (&r)[BI]) {
 #pragma unroll
         for (int it = 0; it < BI; ++it) {
             const int e = tid + it * NT;
-            if (!B_ROWMAJOR) *(float4 *)(Bs + ((e % QK) * (BN + 1) + e / QK) * 4) = r[it];
-            else *(float4 *)(Bs + (e / (BN / 4)) * (BN + 4) + 4 * (e % (BN / 4))) = r[it];
+            const float4 v = p.rb ? bf16_rne(r[it]) : r[it];
+            if (!B_ROWMAJOR) *(float4 *)(Bs + ((e % QK) * (BN + 1) + e / QK) * 4) = v;
+            else *(float4 *)(Bs + (e / (BN / 4)) * (BN + 4) + 4 * (e % (BN / 4))) = v;
         }
     };
 

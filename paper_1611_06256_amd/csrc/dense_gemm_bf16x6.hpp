@@ -20,12 +20,12 @@
 namespace ga3c {
 
 // 8 floats -> three bf16x8 vectors (hi, mid, lo)
-__device__ __forceinline__ void split3x8(const float (&f)[8], u32x4 &hi, u32x4 &mid, u32x4 &lo) {
+__device__ __forceinline__ void split3x8(const float (&f)[8], u32x4 &hi, u32x4 &mid, u32x4 &lo, int rb = 0) {
     Bf16x8Bits h, m, l;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         __bf16 a, b, c;
-        split3(f[e], a, b, c);
+        split3(f[e], a, b, c, rb);
         h.v[e] = a; m.v[e] = b; l.v[e] = c;
     }
     hi = h.u; mid = m.u; lo = l.u;
@@ -70,12 +70,12 @@ __device__ __forceinline__ void fetch_tile(const float *__restrict__ X, long ld,
 
 // Split what fetch_tile brought and store it as S[term][k-group][row].
 template <bool ROWMAJOR, int ROWS, int ITEMS, int NT>
-__device__ __forceinline__ void stash_tile(u32x4 (&S)[3][4][ROWS + 1], int tid, const float (&r)[ITEMS][8]) {
+__device__ __forceinline__ void stash_tile(u32x4 (&S)[3][4][ROWS + 1], int tid, const float (&r)[ITEMS][8], int rb) {
 #pragma unroll
     for (int it = 0; it < ITEMS; ++it) {
         const int e = tid + it * NT;
         const int row = ROWMAJOR ? e % ROWS : e / 4, kg = ROWMAJOR ? e / ROWS : e % 4;
-        split3x8(r[it], S[0][kg][row], S[1][kg][row], S[2][kg][row]);
+        split3x8(r[it], S[0][kg][row], S[1][kg][row], S[2][kg][row], rb);
     }
 }
 
@@ -124,8 +124,8 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void dense_gemm_bf16x6_kernel(const
     }
     for (int k0 = kbeg; k0 < kend; k0 += BK) {
         __syncthreads();
-        stash_tile<A_ROWMAJOR, BM, A_ITEMS, NT>(As, tid, ra);
-        stash_tile<B_ROWMAJOR, BN, B_ITEMS, NT>(Bs, tid, rb);
+        stash_tile<A_ROWMAJOR, BM, A_ITEMS, NT>(As, tid, ra, p.rb);
+        stash_tile<B_ROWMAJOR, BN, B_ITEMS, NT>(Bs, tid, rb, p.rb);
         __syncthreads();
         if (k0 + BK < kend) {
             fetch_tile<A_ROWMAJOR, BM, A_ITEMS, NT>(p.A, p.lda, m0, p.M, p.K, k0 + BK, kend, tid, ra);

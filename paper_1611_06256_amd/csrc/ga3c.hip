@@ -77,6 +77,7 @@ struct Profiler {
 struct ga3c_ctx {
     Profiler *prof;
     bool fast;                    // use the fixed-geometry kernels where they apply
+    int rb;                       // desc.math == 1: operands of every contraction are rounded to bfloat16
     ga3c_net_desc desc;
     int nconv, F, A, flat;
     ConvGeom geom[GA3C_MAX_CONV];
@@ -182,7 +183,8 @@ __global__ __launch_bounds__(256) void heads_fwd_kernel(const float *__restrict_
                                                         const float *__restrict__ bp, const float *__restrict__ Wv,
                                                         const float *__restrict__ bv, float *zv, float *logits,
                                                         float *values, float *probs, const float *uniforms,
-                                                        int32_t *actions) {
+                                                        int32_t *actions, int rb) {
+    // rb: the products of the heads take h and the weights rounded to bfloat16 (h itself is stored as computed)
     extern __shared__ __attribute__((aligned(16))) float hs[];      // [4][F4], weights [A+1][F4+4], partial dots
     const int F4 = heads_f4(F), WP = F4 + 4;
     float *wsh = hs + 4 * F4;
@@ -229,21 +231,21 @@ __global__ __launch_bounds__(256) void heads_fwd_kernel(const float *__restrict_
                         float v = acc4[fb] + bias;
                         v = v > 0.f ? v : 0.f;
                         if (fb < nf) h[(size_t)(b0 + fb) * F + o] = v;
-                        hs[fb * F4 + o] = v;
+                        hs[fb * F4 + o] = rb ? bf16_rne(v) : v;
                     }
                 } else {
                     float v[4];
 #pragma unroll
                     for (int fb = 0; fb < 4; ++fb) v[fb] = h[(size_t)(b0 + min(fb, nf - 1)) * F + o];
 #pragma unroll
-                    for (int fb = 0; fb < 4; ++fb) hs[fb * F4 + o] = v[fb];
+                    for (int fb = 0; fb < 4; ++fb) hs[fb * F4 + o] = rb ? bf16_rne(v[fb]) : v[fb];
                 }
             }
         }
 #pragma unroll
         for (int j = 0; j < 24; ++j) {
             const int e = e0 + j * 256 + tid;
-            if (e < nw) wsh[(e / F) * WP + e % F] = wv[j];
+            if (e < nw) wsh[(e / F) * WP + e % F] = rb ? bf16_rne(wv[j]) : wv[j];
         }
     }
     __syncthreads();
@@ -397,7 +399,9 @@ constexpr int HD_FRAMES = 8;
 __global__ __launch_bounds__(256) void heads_dgrad_kernel(const float *__restrict__ dzv, const float *__restrict__ h,
                                                           const float *__restrict__ Wp, const float *__restrict__ Wv,
                                                           int B, int F, int A, float *__restrict__ dh,
-                                                          float *__restrict__ colpart, float *__restrict__ wpart) {
+                                                          float *__restrict__ colpart, float *__restrict__ wpart, int rb) {
+    // rb: every product takes its operands rounded to bfloat16, and the sums that are products with ones
+    // (the bias gradients) take rounded terms; dh is stored as computed
     extern __shared__ float sm[];
     float *wsh = sm;                        // [A+1][F]
     float *dzs = sm + (A + 1) * F;          // [HD_FRAMES][A+1]
@@ -408,6 +412,11 @@ __global__ __launch_bounds__(256) void heads_dgrad_kernel(const float *__restric
     copy_to_lds<2>(wsh + A * F, Wv, F, tid, 256);
     copy_to_lds<1>(dzs, dzv + (size_t)b0 * (A + 1), nf * (A + 1), tid, 256);
     __syncthreads();
+    if (rb) {
+        for (int e = tid; e < (A + 1) * F; e += 256) wsh[e] = bf16_rne(wsh[e]);
+        for (int e = tid; e < nf * (A + 1); e += 256) dzs[e] = bf16_rne(dzs[e]);
+        __syncthreads();
+    }
     for (int k = tid; k < F; k += 256) {
         float hv[HD_FRAMES];
 #pragma unroll
@@ -425,7 +434,7 @@ __global__ __launch_bounds__(256) void heads_dgrad_kernel(const float *__restric
             for (int fb = 0; fb < HD_FRAMES; ++fb) {
                 const float d = dzs[min(fb, nf - 1) * (A + 1) + a];
                 s[fb] += d * wv;
-                gw += fb < nf ? d * hv[fb] : 0.f;
+                gw += fb < nf ? d * (rb ? bf16_rne(hv[fb]) : hv[fb]) : 0.f;
             }
             if (wp) wp[(size_t)a * (F + 1)] = gw;
         }
@@ -435,7 +444,7 @@ __global__ __launch_bounds__(256) void heads_dgrad_kernel(const float *__restric
             if (fb < nf) {
                 const float v = hv[fb] > 0.f ? s[fb] : 0.f;
                 dh[(size_t)(b0 + fb) * F + k] = v;
-                col += v;
+                col += rb ? bf16_rne(v) : v;
             }
         colpart[(size_t)blockIdx.x * F + k] = col;      // this block's share of the fc bias gradient
     }
@@ -557,7 +566,7 @@ __global__ __launch_bounds__(256) void rmsprop_kernel(const float *theta_in, flo
                                                       const float *__restrict__ grad, size_t n,
                                                       const float *__restrict__ scale_dev, float scale_host, float lr,
                                                       float alpha, float eps, u32x4 *__restrict__ frag, unsigned w1_off,
-                                                      unsigned w2_off) {
+                                                      unsigned w2_off, int frag_rb) {
     // frag (optional): split MFMA fragments of the small net's conv filters, kept current with theta_out;
     // w1_off / w2_off: where the two filter tensors start in the flat buffer (multiples of 4)
     const float s = scale_dev ? scale_dev[0] : scale_host;
@@ -578,8 +587,8 @@ __global__ __launch_bounds__(256) void rmsprop_kernel(const float *theta_in, flo
         g4[i] = gg; o4[i] = t;
         if (frag) {
             const unsigned r1 = (unsigned)(4 * i) - w1_off, r2 = (unsigned)(4 * i) - w2_off;
-            if (r1 < 16u * 256u) conv12_store_fragment4(frag, 0, (int)r1, t);
-            else if (r2 < 32u * 256u) conv12_store_fragment4(frag, 1, (int)r2, t);
+            if (r1 < 16u * 256u) conv12_store_fragment4(frag, 0, (int)r1, t, frag_rb);
+            else if (r2 < 32u * 256u) conv12_store_fragment4(frag, 1, (int)r2, t, frag_rb);
         }
     }
     for (size_t i = n4 * 4 + (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
@@ -739,7 +748,7 @@ inline bool is_aligned16(const void *p) { return (((uintptr_t)p) & 15) == 0; }
 // Things derived from parameter copy i, rebuilt on s after that copy was written there.
 int refresh_derived(ga3c_ctx *c, int i, hipStream_t s) {
     if (c->cfrag[i])
-        HIP_TRY(launch_conv12_filter_fragments(c->theta2[i] + c->off[0], c->theta2[i] + c->off[2], c->cfrag[i], s));
+        HIP_TRY(launch_conv12_filter_fragments(c->theta2[i] + c->off[0], c->theta2[i] + c->off[2], c->cfrag[i], s, c->rb));
     return GA3C_OK;
 }
 
@@ -755,7 +764,7 @@ int forward(ga3c_ctx *c, int which, Work &w, const uint8_t *frames, int B, bool 
         STAGE("conv12_fwd", 2.0 * B * (g0.OHW * g0.OC * g0.K + g1.OHW * g1.OC * g1.K),
               (double)B * (g0.CHW + (keep_zv ? 4.0 * g0.OC * g0.OHW : 0.0) + 4.0 * g1.OC * g1.OHW));
         HIP_TRY(launch_conv12_fused_fwd(frames, c->cfrag[which], th + c->off[1], th + c->off[3],
-                                        keep_zv ? w.act[0] : nullptr, w.act[1], B, 1.f / 255.f, s));
+                                        keep_zv ? w.act[0] : nullptr, w.act[1], B, 1.f / 255.f, s, c->rb));
         first = 2;
     }
     for (int l = first; l < c->nconv; ++l) {
@@ -765,34 +774,34 @@ int forward(ga3c_ctx *c, int which, Work &w, const uint8_t *frames, int B, bool 
         const void *xin = l == 0 ? (const void *)frames : (const void *)w.act[l - 1];
         if (c->fast && is_aligned16(wl) && is_aligned16(xin)) {
             if (spec_matches<SpecS1>(g, l == 0)) {
-                HIP_TRY(launch_conv1_bf16x3_fwd<16>((const uint8_t *)xin, wl, bl, w.act[l], B, 1.f / 255.f, s));
+                HIP_TRY(launch_conv1_bf16x3_fwd<16>((const uint8_t *)xin, wl, bl, w.act[l], B, 1.f / 255.f, s, c->rb));
                 continue;
             }
             if (spec_matches<SpecL1>(g, l == 0)) {
-                HIP_TRY(launch_conv1_bf16x3_fwd<32>((const uint8_t *)xin, wl, bl, w.act[l], B, 1.f / 255.f, s));
+                HIP_TRY(launch_conv1_bf16x3_fwd<32>((const uint8_t *)xin, wl, bl, w.act[l], B, 1.f / 255.f, s, c->rb));
                 continue;
             }
             if (spec_matches<SpecS2>(g, l == 0)) {
-                HIP_TRY(launch_conv2_bf16x6_fwd((const float *)xin, wl, bl, w.act[l], B, s));
+                HIP_TRY(launch_conv2_bf16x6_fwd((const float *)xin, wl, bl, w.act[l], B, s, c->rb));
                 continue;
             }
             if (spec_matches<SpecL2>(g, l == 0)) {      // frame and 32 of the 64 filters in LDS: one block per CU
-                HIP_TRY((launch_conv_fwd_frame<SpecL2, 32>((const float *)xin, wl, bl, w.act[l], B, 1.f, s, 256)));
+                HIP_TRY((launch_conv_fwd_frame<SpecL2, 32>((const float *)xin, wl, bl, w.act[l], B, 1.f, s, 256, c->rb)));
                 continue;
             }
             if (spec_matches<SpecL3>(g, l == 0)) {      // 16 filters per block, two blocks per CU
-                HIP_TRY((launch_conv_fwd_frame<SpecL3, 16>((const float *)xin, wl, bl, w.act[l], B, 1.f, s, 512)));
+                HIP_TRY((launch_conv_fwd_frame<SpecL3, 16>((const float *)xin, wl, bl, w.act[l], B, 1.f, s, 512, c->rb)));
                 continue;
             }
         }
         if (l == 0) {
-            ConvFwdP<uint8_t> p;
+            ConvFwdP<uint8_t> p; p.rb = c->rb;
             p.M = g.OC; p.N = B * g.OHW; p.K = g.K; p.g = g;
             p.x = frames; p.w = th + c->off[0]; p.bias = th + c->off[1];
             p.y = w.act[0]; p.scale = 1.f / 255.f;
             HIP_TRY(launch_conv_like(p, 1, s));
         } else {
-            ConvFwdP<float> p;
+            ConvFwdP<float> p; p.rb = c->rb;
             p.M = g.OC; p.N = B * g.OHW; p.K = g.K; p.g = g;
             p.x = w.act[l - 1]; p.w = th + c->off[2 * l]; p.bias = th + c->off[2 * l + 1];
             p.y = w.act[l]; p.scale = 1.f;
@@ -808,7 +817,7 @@ int forward(ga3c_ctx *c, int which, Work &w, const uint8_t *frames, int B, bool 
         int nz, kchunk;
         if (c->fast && dense_operand_ok(x, c->flat, c->flat) && dense_operand_ok(wfc, c->flat, c->flat)) {
             pick_split_xcd(cdiv(B, 64) * cdiv(c->F, 64), c->flat, nz, kchunk);
-            DenseGemmArgs p{};
+            DenseGemmArgs p{}; p.rb = c->rb;
             p.M = B; p.N = c->F; p.K = c->flat; p.kchunk = kchunk; p.nz = nz;
             p.A = x; p.lda = c->flat; p.B = wfc; p.ldb = c->flat;
             p.C = w.ws; p.ldc = c->F; p.aux = nullptr;
@@ -817,7 +826,7 @@ int forward(ga3c_ctx *c, int which, Work &w, const uint8_t *frames, int B, bool 
             fc_ws = w.ws; fc_nz = nz;
         } else {
             pick_split(cdiv(B, 64) * cdiv(c->F, 64), c->flat, nz, kchunk);
-            GemmP<EPI_PARTIAL, false> p;
+            GemmP<EPI_PARTIAL, false> p; p.rb = c->rb;
             p.M = B; p.N = c->F; p.K = c->flat; p.kchunk = kchunk;
             p.A = x; p.sAm = c->flat; p.sAk = 1;
             p.B = wfc; p.sBn = c->flat; p.sBk = 1;
@@ -831,7 +840,7 @@ int forward(ga3c_ctx *c, int which, Work &w, const uint8_t *frames, int B, bool 
     hipLaunchKernelGGL(heads_fwd_kernel, dim3(cdiv(B, 4)), dim3(256), sizeof(float) * heads_lds_floats(c->F, c->A), s, fc_ws, fc_nz,
                        th + c->off[nb + 1], w.h, B, c->F, c->A, th + c->off[nb + 2],
                        th + c->off[nb + 3], th + c->off[nb + 4], th + c->off[nb + 5],
-                       keep_zv ? w.zv : nullptr, logits, values, probs, uniforms, actions);
+                       keep_zv ? w.zv : nullptr, logits, values, probs, uniforms, actions, c->rb);
     HIP_TRY(hipGetLastError());
     return GA3C_OK;
 }
@@ -878,7 +887,7 @@ extern "C" int ga3c_create(const ga3c_net_desc *d, int max_predict_batch, int ma
     if (d->n_actions < 1 || d->n_actions > GA3C_MAX_ACTIONS)
         return fail(GA3C_EINVAL, "ga3c_create: n_actions must be 1..%d", GA3C_MAX_ACTIONS);
     if (d->in_c < 1 || d->in_h < 1 || d->in_w < 1 || d->fc_units < 1) return fail(GA3C_EINVAL, "ga3c_create: bad sizes");
-    if (d->math != 0) return fail(GA3C_EINVAL, "ga3c_create: only math = 0 (fp32) is built");
+    if (d->math != 0 && d->math != 1) return fail(GA3C_EINVAL, "ga3c_create: math must be 0 (fp32) or 1 (bfloat16 operands)");
     if (max_predict_batch < 0 || max_train_frames < 0) return fail(GA3C_EINVAL, "ga3c_create: negative capacity");
     if ((size_t)heads_lds_floats(d->fc_units, d->n_actions) * sizeof(float) > 64 * 1024)
         return fail(GA3C_EINVAL, "ga3c_create: (n_actions + 5) * (fc_units + 16) must not exceed 16384");
@@ -888,6 +897,7 @@ extern "C" int ga3c_create(const ga3c_net_desc *d, int max_predict_batch, int ma
     memset((void *)c, 0, sizeof(*c));
     c->prof = new (std::nothrow) Profiler();
     c->fast = true;
+    c->rb = d->math;
     c->desc = *d;
     c->nconv = d->n_conv; c->F = d->fc_units; c->A = d->n_actions;
     c->max_pred = max_predict_batch; c->max_train = max_train_frames;
@@ -1170,12 +1180,12 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
         if (!part) return fail(GA3C_EINVAL, "internal: split-k workspace too small (heads)");
         STAGE("heads_bwd", 4.0 * B * (A + 1) * F, 0);
         hipLaunchKernelGGL(heads_dgrad_kernel, dim3(nblk), dim3(256), sizeof(float) * (A + 1) * (F + HD_FRAMES), s, c->dzv, w.h, Wp, Wv, B,
-                           F, A, c->dh, c->colpart, part);
+                           F, A, c->dh, c->colpart, part, c->rb);
         HIP_TRY(hipGetLastError());
         add_seg(part, nblk, A + 1, F + 1, 0, A, c->grad + c->off[nb + 2], c->grad + c->off[nb + 3], 1);
         add_seg(part, nblk, A + 1, F + 1, A, 1, c->grad + c->off[nb + 4], c->grad + c->off[nb + 5], 1);
     } else {   // heads: weight and bias gradients as a product, then the input gradient
-        GemmP<EPI_PARTIAL, true> p;
+        GemmP<EPI_PARTIAL, true> p; p.rb = c->rb;
         p.M = A + 1; p.N = F + 1; p.K = B;
         pick_split(conv_like_tiles(p.M, p.N), B, nz, kchunk);
         p.kchunk = kchunk;
@@ -1191,7 +1201,7 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
         add_seg(p.C, nz, A + 1, F + 1, A, 1, c->grad + c->off[nb + 4], c->grad + c->off[nb + 5], 1);
         STAGE("heads_dgrad", 2.0 * B * (A + 1) * F, 0);
         hipLaunchKernelGGL(heads_dgrad_kernel, dim3(cdiv(B, HD_FRAMES)), dim3(256), sizeof(float) * (A + 1) * (F + HD_FRAMES), s, c->dzv, w.h, Wp, Wv, B,
-                           F, A, c->dh, c->colpart, (float *)nullptr);
+                           F, A, c->dh, c->colpart, (float *)nullptr, c->rb);
         HIP_TRY(hipGetLastError());
     }
     const float *xfc = w.act[c->nconv - 1];
@@ -1200,7 +1210,7 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
                           dense_operand_ok(wfc, c->flat, c->flat);
     if (fc_dense) {   // fc weight gradient: D[o][i] = sum_b dh[b][o] x[b][i]; bias from the column sums of dh
         pick_split_xcd(cdiv(F, 64) * cdiv(c->flat, 64), B, nz, kchunk, 256);
-        DenseGemmArgs p{};
+        DenseGemmArgs p{}; p.rb = c->rb;
         p.M = F; p.N = c->flat; p.K = B; p.kchunk = kchunk; p.nz = nz;
         p.A = c->dh; p.lda = F; p.B = xfc; p.ldb = c->flat;
         p.C = region((size_t)nz * p.M * p.N); p.ldc = 0; p.aux = nullptr;
@@ -1212,7 +1222,7 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
         add_seg(p.C, nz, p.M, p.N, 0, p.M, c->grad + c->off[nb], nullptr, 0);
         add_seg(c->colpart, cdiv(B, HD_FRAMES), 1, F, 0, 1, c->grad + c->off[nb + 1], nullptr, 0);
     } else {   // general shapes: one more column of ones yields the bias gradient
-        GemmP<EPI_PARTIAL, true> p;
+        GemmP<EPI_PARTIAL, true> p; p.rb = c->rb;
         p.M = F; p.N = c->flat + 1; p.K = B;
         pick_split(cdiv(p.M, 64) * cdiv(p.N, 64), B, nz, kchunk);
         p.kchunk = kchunk;
@@ -1229,13 +1239,13 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
     {   // fc input gradient, masked by the ReLU of the last conv layer
         STAGE("fc_dgrad", 2.0 * B * F * c->flat, 0);
         if (fc_dense) {
-            DenseGemmArgs p{};
+            DenseGemmArgs p{}; p.rb = c->rb;
             p.M = B; p.N = c->flat; p.K = F; p.kchunk = (F + GEMM_BK - 1) / GEMM_BK * GEMM_BK; p.nz = 1;
             p.A = c->dh; p.lda = F; p.B = wfc; p.ldb = c->flat;
             p.C = c->dact[c->nconv - 1]; p.ldc = c->flat; p.aux = xfc;
             HIP_TRY((launch_dense_gemm_bf16x6<4, 2, 2, 2, false, true, DG_MASK>(p, DG_SPLIT_N, s)));
         } else {
-            GemmP<EPI_MASK, false> p;
+            GemmP<EPI_MASK, false> p; p.rb = c->rb;
             p.M = B; p.N = c->flat; p.K = F; p.kchunk = (F + GEMM_BK - 1) / GEMM_BK * GEMM_BK;
             p.A = c->dh; p.sAm = F; p.sAk = 1;
             p.B = wfc; p.sBn = 1; p.sBk = c->flat;
@@ -1262,22 +1272,22 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
             if (!part) return fail(GA3C_EINVAL, "internal: split-k workspace too small (conv)");
             STAGE(CONV_WGRAD[l], 2.0 * B * g.OHW * g.OC * g.K, (double)B * ((l == 0 ? 1.0 : 4.0) * g.CHW + 4.0 * g.OC * g.OHW));
             if (kind == 1) {
-                HIP_TRY(launch_conv1_bf16x3_wgrad((const uint8_t *)xin, c->dact[l], part, B, 1.f / 255.f, s));
+                HIP_TRY(launch_conv1_bf16x3_wgrad((const uint8_t *)xin, c->dact[l], part, B, 1.f / 255.f, s, c->rb));
             } else if (kind == 2) {
-                HIP_TRY(launch_conv_wgrad_frame<SpecL1>((const uint8_t *)xin, c->dact[l], part, B, 1.f / 255.f, s));
+                HIP_TRY(launch_conv_wgrad_frame<SpecL1>((const uint8_t *)xin, c->dact[l], part, B, 1.f / 255.f, s, c->rb));
             } else if (kind == 3) {
-                HIP_TRY(launch_conv_wgrad_frame<SpecS2>((const float *)xin, c->dact[l], part, B, 1.f, s));
+                HIP_TRY(launch_conv_wgrad_frame<SpecS2>((const float *)xin, c->dact[l], part, B, 1.f, s, c->rb));
             } else if (kind == 4) {
-                HIP_TRY((launch_conv_wgrad_frame<SpecL2, 4>)((const float *)xin, c->dact[l], part, B, 1.f, s));
+                HIP_TRY((launch_conv_wgrad_frame<SpecL2, 4>)((const float *)xin, c->dact[l], part, B, 1.f, s, c->rb));
             } else if (kind == 5) {
-                HIP_TRY((launch_conv_wgrad_frame<SpecL3, 3>)((const float *)xin, c->dact[l], part, B, 1.f, s));
+                HIP_TRY((launch_conv_wgrad_frame<SpecL3, 3>)((const float *)xin, c->dact[l], part, B, 1.f, s, c->rb));
             } else if (l == 0) {
-                ConvWgradP<uint8_t> p;
+                ConvWgradP<uint8_t> p; p.rb = c->rb;
                 p.M = g.OC; p.N = g.K + 1; p.K = B * g.OHW; p.kchunk = kchunk; p.g = g;
                 p.x = frames; p.dy = c->dact[0]; p.ws = part; p.scale = 1.f / 255.f;
                 HIP_TRY(launch_conv_like(p, nz, s));
             } else {
-                ConvWgradP<float> p;
+                ConvWgradP<float> p; p.rb = c->rb;
                 p.M = g.OC; p.N = g.K + 1; p.K = B * g.OHW; p.kchunk = kchunk; p.g = g;
                 p.x = w.act[l - 1]; p.dy = c->dact[l]; p.ws = part; p.scale = 1.f;
                 HIP_TRY(launch_conv_like(p, nz, s));
@@ -1288,21 +1298,21 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
         // input gradient
         STAGE(CONV_DGRAD[l], 2.0 * B * g.OHW * g.OC * g.K, 0);
         if (c->fast && spec_matches<SpecS2>(g, false) && is_aligned16(th + c->off[2 * l])) {
-            HIP_TRY(launch_conv_dgrad_frame<SpecS2>(c->dact[l], th + c->off[2 * l], w.act[l - 1], c->dact[l - 1], B, s));
+            HIP_TRY(launch_conv_dgrad_frame<SpecS2>(c->dact[l], th + c->off[2 * l], w.act[l - 1], c->dact[l - 1], B, s, 512, c->rb));
             continue;
         }
         if (c->fast && spec_matches<SpecL2>(g, false) && is_aligned16(th + c->off[2 * l])) {   // one block per CU
-            HIP_TRY(launch_conv_dgrad_frame<SpecL2>(c->dact[l], th + c->off[2 * l], w.act[l - 1], c->dact[l - 1], B, s, 256));
+            HIP_TRY(launch_conv_dgrad_frame<SpecL2>(c->dact[l], th + c->off[2 * l], w.act[l - 1], c->dact[l - 1], B, s, 256, c->rb));
             continue;
         }
         if (c->fast && spec_matches<SpecL3>(g, false)) {
-            HIP_TRY((launch_conv_dgrad_s1_frame<SpecL3, 32>(c->dact[l], th + c->off[2 * l], w.act[l - 1], c->dact[l - 1], B, s, 256)));
+            HIP_TRY((launch_conv_dgrad_s1_frame<SpecL3, 32>(c->dact[l], th + c->off[2 * l], w.act[l - 1], c->dact[l - 1], B, s, 256, c->rb)));
             continue;
         }
         // general shapes: one launch per stride phase
         for (int ry = 0; ry < g.S; ++ry)
             for (int rx = 0; rx < g.S; ++rx) {
-                ConvDgradP p;
+                ConvDgradP p; p.rb = c->rb;
                 p.g = g; p.ry = ry; p.rx = rx;
                 p.nH = ry < g.H ? (g.H - ry + g.S - 1) / g.S : 0;
                 p.nW = rx < g.W ? (g.W - rx + g.S - 1) / g.S : 0;
@@ -1332,7 +1342,7 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
     // the copy about to be overwritten may still be read by predictions issued before the last update
     TRY(wait_readers(c, cur ^ 1, s));
     hipLaunchKernelGGL(rmsprop_kernel, dim3(rb), dim3(256), 0, s, th, c->theta2[cur ^ 1], c->g, c->grad, c->P, c->scale,
-                       1.f, hp->lr, hp->rms_decay, hp->rms_eps, c->cfrag[cur ^ 1], (unsigned)c->off[0], (unsigned)c->off[2]);
+                       1.f, hp->lr, hp->rms_decay, hp->rms_eps, c->cfrag[cur ^ 1], (unsigned)c->off[0], (unsigned)c->off[2], c->rb);
     HIP_TRY(hipGetLastError());
     TRY(mark_ready(c, cur ^ 1, s));
     c->cur = cur ^ 1;        // calls enqueued from now on see the new parameters
@@ -1370,7 +1380,7 @@ extern "C" int ga3c_rmsprop_flat(float *theta, float *g, const float *grad, size
         return fail(GA3C_EINVAL, "ga3c_rmsprop_flat: buffers must be 16-byte aligned");
     const unsigned rb = std::min<unsigned>(blocks_for(n / 4 + 1), 8192u);
     hipLaunchKernelGGL(rmsprop_kernel, dim3(rb), dim3(256), 0, (hipStream_t)stream, theta, theta, g, grad, n,
-                       (const float *)nullptr, scale, lr, rms_decay, rms_eps, (u32x4 *)nullptr, 0u, 0u);
+                       (const float *)nullptr, scale, lr, rms_decay, rms_eps, (u32x4 *)nullptr, 0u, 0u, 0);
     HIP_TRY(hipGetLastError());
     return GA3C_OK;
 }

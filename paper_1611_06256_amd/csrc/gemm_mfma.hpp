@@ -3,6 +3,10 @@
 //
 //   D[m][n] = sum_k A(m,k) * B(n,k)            m < M, n < N, k in [kbeg, kend)
 //
+// With P::rb set, both operands are rounded to bfloat16 as they are fetched
+// (products of two bfloat16 numbers are exact in fp32, so this is what a bf16
+// MFMA with fp32 accumulation computes).
+//
 // A problem type P supplies the two gathers and the store, so that the same
 // kernel serves convolution forward (B = implicit im2col), weight gradients
 // (reduction over pixels, split over blockIdx.z), the stride-phase form of the
@@ -41,6 +45,13 @@ struct FastDiv {
         r = n - q * d;
     }
 };
+
+// Round to bfloat16 (nearest even) and back: the reduced-precision variant of
+// the network feeds every contraction operands that have gone through this.
+__device__ __forceinline__ float bf16_rne(float f) { return (float)(__bf16)f; }
+__device__ __forceinline__ float4 bf16_rne(float4 v) {
+    return make_float4(bf16_rne(v.x), bf16_rne(v.y), bf16_rne(v.z), bf16_rne(v.w));
+}
 
 constexpr int GEMM_BK = 32;
 
@@ -81,6 +92,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_mfma_kernel(const P p) {
             if (A_ROWS) { row = e % BM; q = e / BM; } else { q = e % QK; row = e / QK; }
             ra[it] = (BM * QK % NT == 0 || e < BM * QK) ? p.loadA(m0 + row, k0 + 4 * q, kend, z)
                                                         : make_float4(0.f, 0.f, 0.f, 0.f);
+            if (p.rb) ra[it] = bf16_rne(ra[it]);
         }
 #pragma unroll
         for (int it = 0; it < BI; ++it) {
@@ -89,6 +101,7 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_mfma_kernel(const P p) {
             if (B_ROWS) { row = e % BN; q = e / BN; } else { q = e % QK; row = e / QK; }
             rb[it] = (BN * QK % NT == 0 || e < BN * QK) ? p.loadB(n0 + row, k0 + 4 * q, kend, z)
                                                         : make_float4(0.f, 0.f, 0.f, 0.f);
+            if (p.rb) rb[it] = bf16_rne(rb[it]);
         }
     };
     if (kbeg < kend) fetch(kbeg);

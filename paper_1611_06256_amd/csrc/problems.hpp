@@ -34,6 +34,7 @@ struct ConvFwdP {
     const float *w, *bias;
     float *y;
     float scale;
+    int rb = 0;          // round operands to bfloat16
 
     __device__ __forceinline__ void krange(int, int &kbeg, int &kend) const { kbeg = 0; kend = K; }
 
@@ -74,7 +75,8 @@ struct ConvFwdP {
 // D[oc][kk] = sum_P dY[P][oc] * x[frame(P)][tap kk at pixel(P)], with one more
 // column kk = K whose operand is 1, which yields the bias gradient.  The sum
 // over P is cut into chunks (blockIdx.z); each chunk writes its own partial
-// D, and a second kernel adds the partials in a fixed order.
+// D, and a second kernel adds the partials in a fixed order.  The input scale
+// (1/255 for bytes) multiplies the finished sums, not the operands.
 template <class TIn>
 struct ConvWgradP {
     int M, N, K;        // M = OC, N = g.K + 1, K = frames*OHW
@@ -84,6 +86,7 @@ struct ConvWgradP {
     const float *dy;
     float *ws;
     float scale;
+    int rb = 0;          // round operands to bfloat16
 
     __device__ __forceinline__ void krange(int z, int &kbeg, int &kend) const {
         kbeg = z * kchunk;
@@ -117,13 +120,13 @@ struct ConvWgradP {
         g.dOW.divmod(pix, i, j);
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            if (k + t < kend) r[t] = scale * to_f32(x[(size_t)b * g.CHW + (i * g.S) * g.W + j * g.S + ko]);
+            if (k + t < kend) r[t] = to_f32(x[(size_t)b * g.CHW + (i * g.S) * g.W + j * g.S + ko]);
             if (++j == (uint32_t)g.OW) { j = 0; if (++i == (uint32_t)g.OH) { i = 0; ++b; } }
         }
         return make_float4(r[0], r[1], r[2], r[3]);
     }
     __device__ __forceinline__ void store(int m, int n, float v, int z) const {
-        ws[((size_t)z * M + m) * N + n] = v;
+        ws[((size_t)z * M + m) * N + n] = n == g.K ? v : v * scale;
     }
 };
 
@@ -140,6 +143,7 @@ struct ConvDgradP {
     FastDiv dNHW, dNW, dTAB, dTB;
     const float *w, *dy, *xmask;
     float *dx;
+    int rb = 0;          // round operands to bfloat16
 
     __device__ __forceinline__ void krange(int, int &kbeg, int &kend) const { kbeg = 0; kend = K; }
 
@@ -201,6 +205,7 @@ struct GemmP {
     float *C;            // EPI_PARTIAL: workspace [z][M][N]; otherwise output with row pitch ldc
     long ldc;
     const float *aux;    // bias[n] or mask[m*ldc + n]
+    int rb = 0;          // round operands to bfloat16
 
     __device__ __forceinline__ void krange(int z, int &kbeg, int &kend) const {
         kbeg = z * kchunk;

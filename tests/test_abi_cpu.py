@@ -47,7 +47,7 @@ def test_bad_arguments_are_refused_without_a_device():
     assert b"conv layer 0" in lib.ga3c_last_error()
     d = g.SMALL_NET(6).c()
     assert lib.ga3c_create(C.byref(d), -1, 1, C.byref(ctx)) == -1
-    d.math = 1
+    d.math = 2                                  # 0 = fp32, 1 = bfloat16 operands; nothing else
     assert lib.ga3c_create(C.byref(d), 1, 1, C.byref(ctx)) == -1
     assert lib.ga3c_params_count(None) == 0
     assert lib.ga3c_destroy(None) == 0
