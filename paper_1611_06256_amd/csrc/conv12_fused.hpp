@@ -106,6 +106,10 @@ inline hipError_t launch_conv12_filter_fragments(const float *w1, const float *w
 
 // x: [n][4][84][84] bytes; frag: the three fragment sets; b1 [16], b2 [32];
 // y1: [n][16][400] or nullptr; y2: [n][32][81].  Frames blockIdx.x, + gridDim.x, ...
+// ONE: the reduced-precision variant (operands rounded to bfloat16): only the first
+// term of every operand exists, so one MFMA per tap block replaces three / six and
+// only the first plane of the layer-1 output is written and read.
+template <bool ONE>
 __global__ __launch_bounds__(512, 1) void conv12_fused_fwd_kernel(const uint8_t *__restrict__ x,
                                                                   const u32x4 *__restrict__ frag,
                                                                   const float *__restrict__ b1,
@@ -144,7 +148,7 @@ __global__ __launch_bounds__(512, 1) void conv12_fused_fwd_kernel(const uint8_t 
     {
         const u32x4 *src = frag + (size_t)(layer1 ? 0 : 1 + kh) * C12_FRAG_SET + lane;
 #pragma unroll
-        for (int t = 0; t < 3; ++t)
+        for (int t = 0; t < (ONE ? 1 : 3); ++t)
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 Bf16x8Bits v;
@@ -211,7 +215,8 @@ __global__ __launch_bounds__(512, 1) void conv12_fused_fwd_kernel(const uint8_t 
                         __bf16 h, m, l;
                         split3(v, h, m, l, rb);
                         const int e = (4 * g + r) * HW2 + blk;
-                        yp[e] = h; yp[C12_Y1 + e] = m; yp[2 * C12_Y1 + e] = l;
+                        yp[e] = h;
+                        if (!ONE) { yp[C12_Y1 + e] = m; yp[2 * C12_Y1 + e] = l; }
                     }
                 };
                 {
@@ -228,7 +233,7 @@ __global__ __launch_bounds__(512, 1) void conv12_fused_fwd_kernel(const uint8_t 
 #pragma unroll
                         for (int j = 0; j < 6; ++j) xv[j] = operand(base[j], kb);
 #pragma unroll
-                        for (int term = 2; term >= 0; --term)
+                        for (int term = ONE ? 0 : 2; term >= 0; --term)
 #pragma unroll
                             for (int j = 0; j < 6; ++j)
                                 acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wq[term][kb], xv[j], acc[j], 0, 0, 0);
@@ -243,7 +248,7 @@ __global__ __launch_bounds__(512, 1) void conv12_fused_fwd_kernel(const uint8_t 
                     for (int kb = 0; kb < 8; ++kb) {
                         const bf16x8 xv = operand(base, kb);
 #pragma unroll
-                        for (int term = 2; term >= 0; --term)
+                        for (int term = ONE ? 0 : 2; term >= 0; --term)
                             acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wq[term][kb], xv, acc, 0, 0, 0);
                     }
                     finish(24, acc);
@@ -283,7 +288,7 @@ __global__ __launch_bounds__(512, 1) void conv12_fused_fwd_kernel(const uint8_t 
 #pragma unroll
                     for (int i = 0; i < 3; ++i) {
 #pragma unroll
-                        for (int term = 0; term < 3; ++term) {
+                        for (int term = 0; term < (ONE ? 1 : 3); ++term) {
                             const uint2 *q = (const uint2 *)(yp + term * C12_Y1 + off[i] + 2 * kbl * HW2);   // 8-byte aligned
                             const uint2 lo = q[0], hi = q[1];
                             xv[i][term].u = u32x4{lo.x, lo.y, hi.x, hi.y};
@@ -292,7 +297,7 @@ __global__ __launch_bounds__(512, 1) void conv12_fused_fwd_kernel(const uint8_t 
                     // the six largest term products, smallest first; six accumulators alternate
                     constexpr int WT[6] = {2, 1, 0, 1, 0, 0}, XT[6] = {0, 1, 2, 0, 1, 0};
 #pragma unroll
-                    for (int q = 0; q < 6; ++q)
+                    for (int q = ONE ? 5 : 0; q < 6; ++q)          // q = 5 is the product of the two first terms
 #pragma unroll
                         for (int i = 0; i < 3; ++i)
 #pragma unroll
@@ -319,15 +324,19 @@ inline int conv12_fused_blocks(int nframes) { return nframes < 256 ? nframes : 2
 inline hipError_t launch_conv12_fused_fwd(const uint8_t *x, const u32x4 *frag, const float *b1, const float *b2, float *y1,
                                           float *y2, int nframes, float scale, hipStream_t s, int rb) {
     if (nframes <= 0) return hipSuccess;
-    static bool attr_set = false;     // the kernel needs more LDS than the default limit
+    static bool attr_set = false;     // the kernels need more LDS than the default limit
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)conv12_fused_fwd_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           (int)C12_LDS_BYTES);
+        hipError_t e = hipFuncSetAttribute((const void *)conv12_fused_fwd_kernel<false>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)C12_LDS_BYTES);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute((const void *)conv12_fused_fwd_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)C12_LDS_BYTES);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL(conv12_fused_fwd_kernel, dim3(conv12_fused_blocks(nframes)), dim3(512), C12_LDS_BYTES, s, x, frag, b1,
-                       b2, y1, y2, nframes, scale, rb);
+    const dim3 grid(conv12_fused_blocks(nframes)), block(512);
+    if (rb) hipLaunchKernelGGL(conv12_fused_fwd_kernel<true>, grid, block, C12_LDS_BYTES, s, x, frag, b1, b2, y1, y2, nframes, scale, rb);
+    else hipLaunchKernelGGL(conv12_fused_fwd_kernel<false>, grid, block, C12_LDS_BYTES, s, x, frag, b1, b2, y1, y2, nframes, scale, rb);
     return hipGetLastError();
 }
 

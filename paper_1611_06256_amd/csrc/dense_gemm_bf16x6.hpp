@@ -69,17 +69,24 @@ __device__ __forceinline__ void fetch_tile(const float *__restrict__ X, long ld,
 }
 
 // Split what fetch_tile brought and store it as S[term][k-group][row].
-template <bool ROWMAJOR, int ROWS, int ITEMS, int NT>
+template <bool ROWMAJOR, int ROWS, int ITEMS, int NT, bool ONE = false>
 __device__ __forceinline__ void stash_tile(u32x4 (&S)[3][4][ROWS + 1], int tid, const float (&r)[ITEMS][8], int rb) {
 #pragma unroll
     for (int it = 0; it < ITEMS; ++it) {
         const int e = tid + it * NT;
         const int row = ROWMAJOR ? e % ROWS : e / 4, kg = ROWMAJOR ? e / ROWS : e % 4;
-        split3x8(r[it], S[0][kg][row], S[1][kg][row], S[2][kg][row], rb);
+        if (ONE) {       // only the first term exists
+            u32x4 hi, mid, lo;
+            split3x8(r[it], hi, mid, lo, 1);
+            S[0][kg][row] = hi;
+        } else {
+            split3x8(r[it], S[0][kg][row], S[1][kg][row], S[2][kg][row], rb);
+        }
     }
 }
 
-template <int TM, int TN, int WM, int WN, bool A_ROWMAJOR, bool B_ROWMAJOR, int EPI>
+// ONE: the reduced-precision variant (operands rounded to bfloat16): one term per operand, one MFMA per tile pair.
+template <int TM, int TN, int WM, int WN, bool A_ROWMAJOR, bool B_ROWMAJOR, int EPI, bool ONE>
 __global__ __launch_bounds__(WM *WN * 64, 2) void dense_gemm_bf16x6_kernel(const DenseGemmArgs p) {
     constexpr int BM = 16 * TM * WM, BN = 16 * TN * WN, BK = 32, NT = WM * WN * 64;
     // LDS: [term][k-group of 8][row] in 16-byte units, one spare unit per line
@@ -124,8 +131,8 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void dense_gemm_bf16x6_kernel(const
     }
     for (int k0 = kbeg; k0 < kend; k0 += BK) {
         __syncthreads();
-        stash_tile<A_ROWMAJOR, BM, A_ITEMS, NT>(As, tid, ra, p.rb);
-        stash_tile<B_ROWMAJOR, BN, B_ITEMS, NT>(Bs, tid, rb, p.rb);
+        stash_tile<A_ROWMAJOR, BM, A_ITEMS, NT, ONE>(As, tid, ra, p.rb);
+        stash_tile<B_ROWMAJOR, BN, B_ITEMS, NT, ONE>(Bs, tid, rb, p.rb);
         __syncthreads();
         if (k0 + BK < kend) {
             fetch_tile<A_ROWMAJOR, BM, A_ITEMS, NT>(p.A, p.lda, m0, p.M, p.K, k0 + BK, kend, tid, ra);
@@ -135,21 +142,23 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void dense_gemm_bf16x6_kernel(const
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int t = 0; t < 3; ++t) a[i][t].u = As[t][g][(wm * TM + i) * 16 + l16];
+            for (int t = 0; t < (ONE ? 1 : 3); ++t) a[i][t].u = As[t][g][(wm * TM + i) * 16 + l16];
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int t = 0; t < 3; ++t) b[j][t].u = Bs[t][g][(wn * TN + j) * 16 + l16];
+            for (int t = 0; t < (ONE ? 1 : 3); ++t) b[j][t].u = Bs[t][g][(wn * TN + j) * 16 + l16];
         // smallest products first
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
-                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][2].v, b[j][0].v, acc[i][j], 0, 0, 0);
-                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][1].v, b[j][1].v, acc[i][j], 0, 0, 0);
-                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][0].v, b[j][2].v, acc[i][j], 0, 0, 0);
-                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][1].v, b[j][0].v, acc[i][j], 0, 0, 0);
-                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][0].v, b[j][1].v, acc[i][j], 0, 0, 0);
+                if (!ONE) {
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][2].v, b[j][0].v, acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][1].v, b[j][1].v, acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][0].v, b[j][2].v, acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][1].v, b[j][0].v, acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][0].v, b[j][1].v, acc[i][j], 0, 0, 0);
+                }
                 acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][0].v, b[j][0].v, acc[i][j], 0, 0, 0);
             }
     }
@@ -186,8 +195,12 @@ inline hipError_t launch_dense_gemm_bf16x6(DenseGemmArgs p, int split, hipStream
     p.split = split;
     if (split == DG_SPLIT_Z) p.per_xcd = ((p.nz + DG_XCDS - 1) / DG_XCDS) * p.ntm * p.ntn;
     else p.per_xcd = ((p.ntn + DG_XCDS - 1) / DG_XCDS) * p.ntm * p.nz;
-    hipLaunchKernelGGL((dense_gemm_bf16x6_kernel<TM, TN, WM, WN, A_ROWMAJOR, B_ROWMAJOR, EPI>),
-                       dim3(DG_XCDS * p.per_xcd), dim3(WM * WN * 64), 0, s, p);
+    if (p.rb)
+        hipLaunchKernelGGL((dense_gemm_bf16x6_kernel<TM, TN, WM, WN, A_ROWMAJOR, B_ROWMAJOR, EPI, true>),
+                           dim3(DG_XCDS * p.per_xcd), dim3(WM * WN * 64), 0, s, p);
+    else
+        hipLaunchKernelGGL((dense_gemm_bf16x6_kernel<TM, TN, WM, WN, A_ROWMAJOR, B_ROWMAJOR, EPI, false>),
+                           dim3(DG_XCDS * p.per_xcd), dim3(WM * WN * 64), 0, s, p);
     return hipGetLastError();
 }
 
