@@ -192,7 +192,9 @@ inline hipError_t launch_conv1_bf16x3_fwd(const uint8_t *x, const float *w, cons
 // its 16 planes), the filters are the rows, and the four (a,b) are four
 // accumulators.  Shift b = 1 is made from the b = 0 vector and one more dword.
 // Rows of 20 pixels are padded to 24 = 3 blocks of 8 with zero dY.
-// part: [gridDim.x][16][257]; the last column is the bias gradient.
+// part: [gridDim.x][OCT][257]; the last column is the bias gradient.  A layer
+// with OCT = 32 filters is done in two slices of 16 (blockIdx.y).
+template <int OCT>
 __global__ __launch_bounds__(256) void conv1_bf16x3_wgrad_kernel(const uint8_t *__restrict__ x,
                                                                  const float *__restrict__ dy,
                                                                  float *__restrict__ part, int nframes, float scale,
@@ -211,6 +213,8 @@ __global__ __launch_bounds__(256) void conv1_bf16x3_wgrad_kernel(const uint8_t *
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l16 = lane & 15, g = lane >> 4;
+    const int oc0 = blockIdx.y * OC;                       // my slice of the filters
+    static_assert(OCT % OC == 0, "whole slices of 16 filters");
 
     for (int e = tid; e < 64 * XPLANE / 2; e += 256) ((uint32_t *)xp)[e] = 0u;     // padding stays zero
     for (int e = tid; e < 3 * OC * DOC / 2; e += 256) ((uint32_t *)dp)[e] = 0u;
@@ -250,7 +254,7 @@ __global__ __launch_bounds__(256) void conv1_bf16x3_wgrad_kernel(const uint8_t *
         for (int i = 0; i < IPT; ++i)
 #pragma unroll
             for (int t = 0; t < 4; ++t) xpre[i][t] = xs[min(xsrc[i] + t, CHW / 4 - 1)];
-        const float4 *ds = (const float4 *)(dy + (size_t)ff * OC * NPIX);
+        const float4 *ds = (const float4 *)(dy + ((size_t)ff * OCT + oc0) * NPIX);
 #pragma unroll
         for (int i = 0; i < DPT; ++i) dpre[i] = ds[dsrc[i]];
     };
@@ -320,7 +324,7 @@ __global__ __launch_bounds__(256) void conv1_bf16x3_wgrad_kernel(const uint8_t *
         }
     }
     // lane (l16, g), register r of acc[a][b]: filter 4g + r, tap (c = wave, u = 4a + l16/4, v = 4b + l16%4)
-    float *pb = part + (size_t)blockIdx.x * OC * (K + 1);
+    float *pb = part + ((size_t)blockIdx.x * OCT + oc0) * (K + 1);
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
@@ -333,11 +337,12 @@ __global__ __launch_bounds__(256) void conv1_bf16x3_wgrad_kernel(const uint8_t *
 
 inline int conv1_bf16x3_wgrad_blocks(int nframes) { return nframes < 256 ? nframes : 256; }
 
+template <int OCT = 16>
 inline hipError_t launch_conv1_bf16x3_wgrad(const uint8_t *x, const float *dy, float *part, int nframes, float scale,
                                             hipStream_t s, int rb = 0) {
     if (nframes <= 0) return hipSuccess;
-    hipLaunchKernelGGL(conv1_bf16x3_wgrad_kernel, dim3(conv1_bf16x3_wgrad_blocks(nframes)), dim3(256), 0, s, x, dy, part,
-                       nframes, scale, rb);
+    hipLaunchKernelGGL(conv1_bf16x3_wgrad_kernel<OCT>, dim3(conv1_bf16x3_wgrad_blocks(nframes), OCT / 16), dim3(256), 0, s, x,
+                       dy, part, nframes, scale, rb);
     return hipGetLastError();
 }
 

@@ -1261,10 +1261,10 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
             const void *xin = l == 0 ? (const void *)frames : (const void *)w.act[l - 1];
             const bool ok = c->fast && is_aligned16(xin);
             const int kind = !ok ? 0 : (spec_matches<SpecS1>(g, l == 0) && is_aligned16(c->dact[l])) ? 1
-                                     : spec_matches<SpecL1>(g, l == 0) ? 2 : spec_matches<SpecS2>(g, l == 0) ? 3
+                                     : (spec_matches<SpecL1>(g, l == 0) && is_aligned16(c->dact[l])) ? 2 : spec_matches<SpecS2>(g, l == 0) ? 3
                                      : spec_matches<SpecL2>(g, l == 0) ? 4 : spec_matches<SpecL3>(g, l == 0) ? 5 : 0;
             if (kind == 1) nz = conv1_bf16x3_wgrad_blocks(B);
-            else if (kind == 2) nz = conv_wgrad_frame_blocks<SpecL1>(B);
+            else if (kind == 2) nz = conv1_bf16x3_wgrad_blocks(B);
             else if (kind == 3) nz = conv_wgrad_frame_blocks<SpecS2>(B);
             else if (kind == 4) nz = conv_wgrad_frame_blocks<SpecL2>(B);
             else if (kind == 5) nz = conv_wgrad_frame_blocks<SpecL3>(B);
@@ -1275,7 +1275,7 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
             if (kind == 1) {
                 HIP_TRY(launch_conv1_bf16x3_wgrad((const uint8_t *)xin, c->dact[l], part, B, 1.f / 255.f, s, c->rb));
             } else if (kind == 2) {
-                HIP_TRY(launch_conv_wgrad_frame<SpecL1>((const uint8_t *)xin, c->dact[l], part, B, 1.f / 255.f, s, c->rb));
+                HIP_TRY(launch_conv1_bf16x3_wgrad<32>((const uint8_t *)xin, c->dact[l], part, B, 1.f / 255.f, s, c->rb));
             } else if (kind == 3) {
                 HIP_TRY(launch_conv_wgrad_frame<SpecS2>((const float *)xin, c->dact[l], part, B, 1.f, s, c->rb));
             } else if (kind == 4) {
