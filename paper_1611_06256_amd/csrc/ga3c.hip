@@ -58,6 +58,8 @@ struct Work {            // activations of one call; predict and train own one e
     float *zv = nullptr; // logits and value [cap][A+1]
     float *ws = nullptr; // split-k partial products of this call
     size_t ws_floats = 0;
+    const float *fc_ws = nullptr;   // where the last forward left the fc partial sums, and how many
+    int fc_nz = 1;
 };
 
 }  // namespace
@@ -455,6 +457,247 @@ __global__ __launch_bounds__(256) void heads_dgrad_kernel(const float *__restric
     }
 }
 
+// Training only: everything between the fc products and the fc backward in one
+// kernel, for HD_FRAMES frames per block.  (1) last step of the split-k fc layer:
+// h = max(0, bias + sum_z ws[z]); (2) heads: z = W h + b; (3) n-step returns
+// (text after Eq. 1), loss and its gradient w.r.t. the head outputs (Eq. 1, 2,
+// 5), one thread per (frame, action), sums taken in action order so that they
+// do not depend on the thread layout; (4) heads backward: dh = [h > 0] dz W,
+// and the block's shares of the heads' weight and bias gradients (wpart
+// [block][A+1][F+1]) and of the fc bias gradient (colpart [block][F]).
+// Writes zv, R, dzv (kept for inspection), dh, colpart, wpart and three loss
+// sums per block.  rb: operands of every product rounded to bfloat16.
+// Dynamic LDS: heads_train_lds_floats(F, A) floats.
+__host__ __device__ inline int heads_train_kparts(int F, int A) {
+    const int kp = 256 / (A + 1), nk = heads_f4(F) / 4;
+    return kp < nk ? kp : nk;
+}
+__host__ __device__ inline int heads_train_lds_floats(int F, int A) {
+    return HD_FRAMES * heads_f4(F) + (A + 1) * (heads_f4(F) + 4) + HD_FRAMES * (A + 1) * (heads_train_kparts(F, A) + 4) + 512;
+}
+
+__global__ __launch_bounds__(256) void heads_train_kernel(
+    const float *__restrict__ ws, int nz, const float *__restrict__ fcb, int B, int F, int A,
+    const float *__restrict__ Wp, const float *__restrict__ bp, const float *__restrict__ Wv, const float *__restrict__ bv,
+    const int32_t *__restrict__ actions, const float *__restrict__ rewards, const uint8_t *__restrict__ dones,
+    const float *__restrict__ bootstrap, int T, float gamma, float beta, float cv, float eps,
+    float *__restrict__ zv, float *__restrict__ R, float *__restrict__ dzv, float *__restrict__ dh,
+    float *__restrict__ colpart, float *__restrict__ wpart, float *__restrict__ losspart, int rb) {
+    extern __shared__ __attribute__((aligned(16))) float sm[];
+    constexpr int NF = HD_FRAMES;
+    const int F4 = heads_f4(F), WP = F4 + 4, A1 = A + 1, KP = heads_train_kparts(F, A);
+    float *hs = sm;                          // [NF][F4]   fc output of my frames (rounded if rb)
+    float *wsh = hs + NF * F4;               // [A1][WP]   head weights (rounded if rb)
+    float *zp = wsh + A1 * WP;               // [NF][A1][KP] partial dots, later scratch of the loss
+    float *zs = zp + NF * A1 * KP;           // [NF][A1]   head outputs, later their gradients
+    float *ex = zs + NF * A1;                // [NF][A1]   exp / per-action terms
+    float *tm = ex + NF * A1;                // [NF][A1]   per-action terms
+    float *rw = tm + NF * A1;                // [256]      rewards of the agents my frames belong to
+    float *dn = rw + 256;                    // [256]      1 - done
+    const int tid = threadIdx.x;
+    const int b0 = blockIdx.x * NF;
+    const int nf = min(NF, B - b0);
+
+    // ---- everything from global memory is requested first
+    const int n0 = b0 / T, n1 = (b0 + nf - 1) / T;          // agents of my frames
+    const int nrw = (n1 - n0 + 1) * T;
+    const bool rw_lds = nrw <= 256;
+    float my_rw = 0.f, my_dn = 0.f;
+    if (rw_lds && tid < nrw) { my_rw = rewards[(size_t)n0 * T + tid]; my_dn = dones[(size_t)n0 * T + tid] ? 0.f : 1.f; }
+    const int ofb = min(tid / A1, nf - 1), oa = tid % A1;   // thread tid < nf*A1 owns output oa of frame ofb
+    const bool mine = tid < nf * A1;
+    const int ob = b0 + ofb;
+    const float obias = oa < A ? bp[oa] : bv[0];
+    const int oact = actions[ob];
+    const float oboot = bootstrap ? bootstrap[ob / T] : 0.f;
+    for (int e = tid; e < NF * (F4 - F); e += 256) hs[(e / (F4 - F)) * F4 + F + e % (F4 - F)] = 0.f;
+    for (int e = tid; e < A1 * (WP - F); e += 256) wsh[(e / (WP - F)) * WP + F + e % (WP - F)] = 0.f;
+    const int nw = A1 * F;
+    for (int e0 = 0; e0 < nw || e0 == 0; e0 += 24 * 256) {
+        float wv[24];
+#pragma unroll
+        for (int j = 0; j < 24; ++j) {
+            const int e = min(e0 + j * 256 + tid, nw - 1);
+            wv[j] = e < A * F ? Wp[e] : Wv[e - A * F];
+        }
+        if (e0 == 0) {
+            for (int o = tid; o < F; o += 256) {
+                const float bias = fcb[o];
+                const size_t stride = (size_t)B * F;
+                const float *src = ws + (size_t)b0 * F + o;
+                float acc[NF];
+#pragma unroll
+                for (int fb = 0; fb < NF; ++fb) acc[fb] = 0.f;
+                for (int z = 0; z < nz; z += 8) {
+                    float v[NF][8];
+#pragma unroll
+                    for (int fb = 0; fb < NF; ++fb)
+#pragma unroll
+                        for (int i = 0; i < 8; ++i)
+                            v[fb][i] = src[min(z + i, nz - 1) * stride + (size_t)min(fb, nf - 1) * F];
+#pragma unroll
+                    for (int fb = 0; fb < NF; ++fb)
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) acc[fb] += (z + i < nz) ? v[fb][i] : 0.f;
+                }
+#pragma unroll
+                for (int fb = 0; fb < NF; ++fb) {
+                    float v = acc[fb] + bias;
+                    v = v > 0.f ? v : 0.f;
+                    hs[fb * F4 + o] = rb ? bf16_rne(v) : v;
+                }
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 24; ++j) {
+            const int e = e0 + j * 256 + tid;
+            if (e < nw) wsh[(e / F) * WP + e % F] = rb ? bf16_rne(wv[j]) : wv[j];
+        }
+    }
+    if (rw_lds && tid < nrw) { rw[tid] = my_rw; dn[tid] = my_dn; }
+    __syncthreads();
+
+    // ---- heads: thread (action a, part kp of k) for all frames, then the parts are added in order
+    {
+        const int a = tid % A1, kp = tid / A1;
+        if (kp < KP) {
+            const int nk = F4 / 4;
+            const int klo = (nk * kp) / KP, khi = (nk * (kp + 1)) / KP;
+            const float4 *wr = (const float4 *)(wsh + a * WP);
+            float s[NF];
+#pragma unroll
+            for (int fb = 0; fb < NF; ++fb) s[fb] = 0.f;
+            for (int k = klo; k < khi; ++k) {
+                const float4 w = wr[k];
+#pragma unroll
+                for (int fb = 0; fb < NF; ++fb) {
+                    const float4 x = ((const float4 *)(hs + fb * F4))[k];
+                    s[fb] += (x.x * w.x + x.y * w.y) + (x.z * w.z + x.w * w.w);
+                }
+            }
+#pragma unroll
+            for (int fb = 0; fb < NF; ++fb) zp[(fb * A1 + a) * KP + kp] = s[fb];
+        }
+    }
+    __syncthreads();
+    float z = 0.f;
+    if (mine) {
+        const float *q = zp + (ofb * A1 + oa) * KP;
+        for (int kp = 0; kp < KP; ++kp) z += q[kp];
+        z += obias;
+        zv[(size_t)ob * A1 + oa] = z;
+        zs[ofb * A1 + oa] = z;
+    }
+    // ---- n-step return of my frame (threads with oa == A: one per frame)
+    float Rt = 0.f;
+    if (mine && oa == A) {
+        const int n = ob / T, t = ob % T;
+        float next = oboot;
+        if (rw_lds) {
+            for (int tt = T - 1; tt >= t; --tt) { const int j = (n - n0) * T + tt; next = rw[j] + gamma * dn[j] * next; }
+        } else {
+            for (int tt = T - 1; tt >= t; --tt) {
+                const size_t j = (size_t)n * T + tt;
+                next = rewards[j] + gamma * (dones[j] ? 0.f : 1.f) * next;
+            }
+        }
+        Rt = next;
+        R[ob] = next;
+        tm[ofb * A1 + A] = next;             // the policy threads of the frame read it from here
+    }
+    __syncthreads();
+    // ---- loss and dL/dz, thread (frame, action); sums over the actions run in index order
+    const bool pol = mine && oa < A;
+    const float *zr = zs + ofb * A1;
+    float zmax = 0.f, e = 0.f;
+    if (pol) {
+        zmax = zr[0];
+        for (int j = 1; j < A; ++j) zmax = fmaxf(zmax, zr[j]);
+        e = expf(z - zmax);
+        ex[ofb * A1 + oa] = e;
+    }
+    __syncthreads();
+    float p = 0.f, lg = 0.f, r = 1.f, adv = 0.f;
+    if (mine) {
+        const float V = zr[A];
+        adv = tm[ofb * A1 + A] - V;
+    }
+    if (pol) {
+        float S = 0.f;
+        for (int j = 0; j < A; ++j) S += ex[ofb * A1 + j];
+        const float logS = logf(S), invS = 1.f / S;
+        p = e * invS;
+        if (eps == 0.f) { lg = z - zmax - logS; r = 1.f; }
+        else { lg = logf(p + eps); r = p / (p + eps); }
+    }
+    __syncthreads();                                  // every exp has been read
+    if (pol) {
+        ex[ofb * A1 + oa] = p * lg;                   // -H terms
+        tm[ofb * A1 + oa] = p * beta * (lg + r);      // dot terms
+    }
+    __syncthreads();
+    float dzo = 0.f, s_pl = 0.f, s_vl = 0.f, s_en = 0.f;
+    // the thread of the action taken publishes its lg and r
+    if (pol && oa == oact) { dn[ofb * 2] = lg; dn[ofb * 2 + 1] = r; }      // (rw, dn are free again by now)
+    __syncthreads();
+    if (mine) {
+        float H = 0.f, dot = 0.f;
+        for (int j = 0; j < A; ++j) { H -= ex[ofb * A1 + j]; dot += tm[ofb * A1 + j]; }
+        const bool known = (unsigned)oact < (unsigned)A;
+        const float lga = known ? dn[ofb * 2] : 0.f, ra = known ? dn[ofb * 2 + 1] : 1.f;
+        dot -= adv * ra;
+        if (oa < A) dzo = p * (beta * (lg + r) - dot) - (oa == oact ? adv * ra : 0.f);
+        else {
+            dzo = -2.f * cv * adv;
+            s_pl = -lga * adv; s_vl = adv * adv; s_en = H;
+        }
+        dzv[(size_t)ob * A1 + oa] = dzo;
+    }
+    __syncthreads();                                  // zs (the head outputs) has been read by everyone
+    if (mine) zs[ofb * A1 + oa] = rb ? bf16_rne(dzo) : dzo;
+    // loss sums of the block, frames in order (threads oa == A hold them)
+    if (mine && oa == A) { rw[ofb] = s_pl; rw[NF + ofb] = s_vl; rw[2 * NF + ofb] = s_en; }
+    __syncthreads();
+    if (tid < 3) {
+        const float *src = rw + tid * NF;
+        float sum = 0.f;
+        for (int fb = 0; fb < nf; ++fb) sum += src[fb];
+        losspart[3 * blockIdx.x + tid] = sum;
+    }
+    // ---- heads backward (zs now holds dz of my frames)
+    for (int k = tid; k < F; k += 256) {
+        float hv[NF], sdh[NF];
+#pragma unroll
+        for (int fb = 0; fb < NF; ++fb) { hv[fb] = hs[fb * F4 + k]; sdh[fb] = 0.f; }
+        float *wp = wpart + (size_t)blockIdx.x * A1 * (F + 1) + k;
+        for (int a = 0; a <= A; ++a) {
+            const float wv = wsh[a * WP + k];
+            float gw = 0.f;
+#pragma unroll
+            for (int fb = 0; fb < NF; ++fb) {
+                const float d = fb < nf ? zs[fb * A1 + a] : 0.f;
+                sdh[fb] += d * wv;
+                gw += d * hv[fb];
+            }
+            wp[(size_t)a * (F + 1)] = gw;
+        }
+        float col = 0.f;
+#pragma unroll
+        for (int fb = 0; fb < NF; ++fb)
+            if (fb < nf) {
+                const float v = hv[fb] > 0.f ? sdh[fb] : 0.f;
+                dh[(size_t)(b0 + fb) * F + k] = v;
+                col += rb ? bf16_rne(v) : v;
+            }
+        colpart[(size_t)blockIdx.x * F + k] = col;
+    }
+    if (tid <= A) {
+        float gb = 0.f;
+        for (int fb = 0; fb < nf; ++fb) gb += zs[fb * A1 + tid];
+        wpart[((size_t)blockIdx.x * A1 + tid) * (F + 1) + F] = gb;
+    }
+}
+
 // One launch adds up the partial weight gradients of every layer and, on the
 // way, the squares of the results (for the global norm).
 // A segment is a stack of nz partial matrices ws[z][M][N].  Rows [r0, r0+rows)
@@ -731,6 +974,9 @@ inline int conv_like_tiles(int M, int N) {
     return cdiv(M, 64) * cdiv(N, 64);
 }
 
+// LDS the fused training heads kernel may ask for; larger heads fall back to the separate kernels.
+constexpr size_t HEADS_TRAIN_MAX_LDS = 96 * 1024;
+
 // Fixed-geometry kernels exist for the layers of the paper's networks.
 typedef ConvSpec<uint8_t, 4, 84, 84, 16, 8, 4> SpecS1;    // small net, conv1
 typedef ConvSpec<float, 16, 20, 20, 32, 4, 2> SpecS2;     // small net, conv2
@@ -754,7 +1000,7 @@ int refresh_derived(ga3c_ctx *c, int i, hipStream_t s) {
 
 // Forward pass of `B` frames into `w`; heads outputs to the optional pointers.
 int forward(ga3c_ctx *c, int which, Work &w, const uint8_t *frames, int B, bool keep_zv, float *logits, float *values,
-            float *probs, const float *uniforms, int32_t *actions, hipStream_t s) {
+            float *probs, const float *uniforms, int32_t *actions, hipStream_t s, bool with_heads = true) {
     const float *th = c->theta2[which];
     const int nb = 2 * c->nconv;
     int first = 0;
@@ -836,6 +1082,8 @@ int forward(ga3c_ctx *c, int which, Work &w, const uint8_t *frames, int B, bool 
             fc_ws = w.ws; fc_nz = nz;
         }
     }
+    w.fc_ws = fc_ws; w.fc_nz = fc_nz;
+    if (!with_heads) return GA3C_OK;          // the caller finishes the fc layer and the heads itself
     STAGE("heads_fwd", 2.0 * B * c->F * (c->A + 1), 4.0 * (fc_nz + 1) * B * c->F);
     hipLaunchKernelGGL(heads_fwd_kernel, dim3(cdiv(B, 4)), dim3(256), sizeof(float) * heads_lds_floats(c->F, c->A), s, fc_ws, fc_nz,
                        th + c->off[nb + 1], w.h, B, c->F, c->A, th + c->off[nb + 2],
@@ -871,7 +1119,7 @@ size_t workspace_floats(const ga3c_ctx *c, int cap, bool training) {
         add((size_t)std::max(nz, nz2) * c->F * (c->flat + 1));
         pick_split(conv_like_tiles(c->A + 1, c->F + 1), B, nz, kc);
         add((size_t)std::max(nz, cdiv(B, HD_FRAMES)) * (c->A + 1) * (c->F + 1));
-        need = std::max(need, sum);
+        need = (need + 63) / 64 * 64 + sum;      // the regions follow the fc partial sums
     }
     return need;
 }
@@ -989,7 +1237,7 @@ extern "C" int ga3c_create(const ga3c_net_desc *d, int max_predict_batch, int ma
         if (rc == GA3C_OK) guard(dmalloc((void **)&c->dzv, sizeof(float) * B * (c->A + 1)));
         if (rc == GA3C_OK) guard(dmalloc((void **)&c->R, sizeof(float) * B));
         c->max_norm_parts = (int)(c->P / 4 + 24 * MAX_REDUCE_SEGS);   // a reduce block covers at least 4 outputs
-        if (rc == GA3C_OK) guard(dmalloc((void **)&c->partials, sizeof(float) * (c->max_norm_parts + 3 * (B / LOSS_THREADS + 1))));
+        if (rc == GA3C_OK) guard(dmalloc((void **)&c->partials, sizeof(float) * (c->max_norm_parts + 3 * (B / HD_FRAMES + 1))));
         if (rc == GA3C_OK) guard(dmalloc((void **)&c->colpart, sizeof(float) * (B / HD_FRAMES + 1) * c->F));
         if (rc == GA3C_OK) guard(dmalloc((void **)&c->scale, sizeof(float)));
         if (rc == GA3C_OK) guard(dmalloc((void **)&c->stats, sizeof(ga3c_train_stats)));
@@ -1138,12 +1386,15 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
     const int cur = c->cur;
     const float *th = c->theta2[cur];
     TRY(wait_ready(c, cur, s));
-    int rc = forward(c, cur, w, frames, B, true, nullptr, nullptr, nullptr, nullptr, nullptr, s);
+    // One kernel finishes the fc layer, runs the heads, the loss and the heads' backward pass, if its LDS fits.
+    const size_t ht_lds = sizeof(float) * (size_t)heads_train_lds_floats(F, A);
+    const bool fused_heads = c->fast && ht_lds <= HEADS_TRAIN_MAX_LDS && HD_FRAMES * (A + 1) <= 256;      // a thread per (frame, output)
+    int rc = forward(c, cur, w, frames, B, true, nullptr, nullptr, nullptr, nullptr, nullptr, s, !fused_heads);
     if (rc != GA3C_OK) return rc;
 
-    const int nloss = cdiv(B, LOSS_THREADS);
+    const int nloss = fused_heads ? cdiv(B, HD_FRAMES) : cdiv(B, LOSS_THREADS);
     float *losspart = c->partials + c->max_norm_parts;
-    {
+    if (!fused_heads) {
         STAGE("returns_loss", 0, 4.0 * B * (2 * (A + 1) + 4));
         hipLaunchKernelGGL(returns_loss_kernel, dim3(nloss), dim3(LOSS_THREADS), sizeof(float) * LOSS_THREADS * (A + 1), s, w.zv, actions, rewards, dones,
                            bootstrap, N, T, A, hp->gamma, hp->beta, hp->value_coef, hp->log_eps, c->R, c->dzv, losspart);
@@ -1155,7 +1406,8 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
     // Every weight gradient leaves its partial sums in a region of its own; one kernel adds them all up at the end.
     ReduceArgs red;
     red.nseg = 0; red.normpart = c->partials;
-    size_t ws_used = 0;
+    // the fused heads kernel still reads the fc partial sums, which sit at the start of the workspace
+    size_t ws_used = fused_heads ? ((size_t)w.fc_nz * B * F + 63) / 64 * 64 : 0;
     int red_blocks = 0;
     double red_bytes = 0;
     auto region = [&](size_t floats) -> float * {
@@ -1174,7 +1426,23 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
         red_blocks += 8 * g.per_xcd;
         red_bytes += 4.0 * (nz_ + 1) * rows * Ncols;
     };
-    if (c->fast) {   // heads: input gradient and, per block of frames, the block's share of the weight and bias gradients
+    if (fused_heads) {
+        const int nblk = cdiv(B, HD_FRAMES);
+        float *part = region((size_t)nblk * (A + 1) * (F + 1));
+        if (!part) return fail(GA3C_EINVAL, "internal: split-k workspace too small (heads)");
+        static size_t lds_set = 0;      // raise the kernel's LDS limit once per size
+        if (ht_lds > 64 * 1024 && ht_lds > lds_set) {
+            HIP_TRY(hipFuncSetAttribute((const void *)heads_train_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)ht_lds));
+            lds_set = ht_lds;
+        }
+        STAGE("heads_train", 6.0 * B * (A + 1) * F, 4.0 * (w.fc_nz + 1) * B * F);
+        hipLaunchKernelGGL(heads_train_kernel, dim3(nblk), dim3(256), ht_lds, s, w.fc_ws, w.fc_nz, th + c->off[nb + 1], B, F, A, Wp,
+                           th + c->off[nb + 3], Wv, th + c->off[nb + 5], actions, rewards, dones, bootstrap, T, hp->gamma, hp->beta,
+                           hp->value_coef, hp->log_eps, w.zv, c->R, c->dzv, c->dh, c->colpart, part, losspart, c->rb);
+        HIP_TRY(hipGetLastError());
+        add_seg(part, nblk, A + 1, F + 1, 0, A, c->grad + c->off[nb + 2], c->grad + c->off[nb + 3], 1);
+        add_seg(part, nblk, A + 1, F + 1, A, 1, c->grad + c->off[nb + 4], c->grad + c->off[nb + 5], 1);
+    } else if (c->fast) {   // heads: input gradient and, per block of frames, the block's share of the weight and bias gradients
         const int nblk = cdiv(B, HD_FRAMES);
         float *part = region((size_t)nblk * (A + 1) * (F + 1));
         if (!part) return fail(GA3C_EINVAL, "internal: split-k workspace too small (heads)");
