@@ -8,7 +8,12 @@ the N agents x 5 frames those actions produced (the bootstrap value of a
 segment is the value of the next segment's first prediction, so no sixth
 prediction is needed).  N = 512 agents, the small
 network of Sec. 3.2 with 18 actions, synthetic game-like frames that are
-resident in HBM before the timed region starts.
+resident in HBM before the timed region starts.  By default the step is
+submitted the way the paper's predictor and trainer threads do it (Sec. 4.1):
+the five predictions on one stream, the training step (on the segment the
+previous step predicted) on another, so that the two calls share the GPU;
+`--streams 1` issues the six calls one after another, and both rates are
+always in the output.
 
 Prints ONE JSON line.  `value` = frames per second through predict AND
 train_step (each frame is predicted once and trained on once).  The line
@@ -70,6 +75,9 @@ def main() -> int:
     ap.add_argument("--net", choices=("small", "large"), default="small")
     ap.add_argument("--math", type=int, choices=(0, 1), default=0,
                     help="0: fp32 accuracy (default); 1: operands of every contraction rounded to bfloat16")
+    ap.add_argument("--streams", type=int, choices=(1, 2), default=2,
+                    help="2: predictions on one stream, training on another (predictor and trainer threads of "
+                         "Sec. 4.1 share the GPU); 1: the six calls of a step one after another")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rmsprop-big", action="store_true", help="also time RMSProp on 2^28 parameters")
     ap.add_argument("--mixed-seconds", type=float, default=1.0,
@@ -130,9 +138,33 @@ def main() -> int:
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / k
 
+    # The same work on two streams, as the predictor and trainer threads of Sec. 4.1 submit it: the predictions
+    # of segment i run while the training step works on segment i - 1.  Three sets of bootstrap values, so the
+    # predictions may run one segment ahead of training; events order writer and reader of each set.
+    s_pred, s_train = torch.cuda.Stream(), torch.cuda.Stream()
+    boots = [torch.zeros(N, device="cuda") for _ in range(3)]
+    ev_pred = [torch.cuda.Event() for _ in range(3)]
+    ev_train = [torch.cuda.Event() for _ in range(3)]
+    for e in ev_pred + ev_train:
+        e.record(stream)
+    seg = [0]
+
+    def step_two_streams():
+        i = seg[0]; seg[0] += 1
+        s_pred.wait_event(ev_train[i % 3])               # the training step that last read this set is done
+        for t in range(T):
+            net.predict(pframes[t], uniforms=uniforms, logits=logits, values=boots[i % 3] if t == 0 else values,
+                        probs=probs, actions=sampled, stream=s_pred)
+        ev_pred[i % 3].record(s_pred)
+        s_train.wait_event(ev_pred[(i - 1) % 3])         # values written by the predictions of segment i - 1
+        net.train_step(frames, actions, rewards, dones, boots[(i - 1) % 3], hp, stats=stats, stream=s_train)
+        ev_train[(i - 1) % 3].record(s_train)
+
     for _ in range(args.warmup):
-        step()
-    sec = timed(step, args.steps)
+        step(); step_two_streams()
+    sec_one = timed(step, args.steps)
+    sec_two = timed(step_two_streams, args.steps)
+    sec = sec_two if args.streams == 2 else sec_one
     frames_per_step = N * T
 
     # predict-only and train-only rates (same buffers)
@@ -187,6 +219,7 @@ def main() -> int:
         roofline["algorithmic_bytes_per_launch"] = round(dp["bytes"] / dp["calls"]) if dp["bytes"] > 0 else None
     flop_step = sum(p["flop"] for p in prof.values()) / args.steps
     whole = {"tflops": round(flop_step / sec / 1e12, 3), "frac_fp32_mfma_peak": round(flop_step / sec / PEAK_FP32_MFMA, 4)}
+    torch.cuda.synchronize()
 
     theta_np = net.params_get(0).cpu().numpy()
     out = {
@@ -199,7 +232,10 @@ def main() -> int:
                       "operands of every contraction rounded to bfloat16, exact products, fp32 accumulation, fp32 parameters",
         "config": {"workload": f"configs[1]+[2]: {args.net} net, 18 actions; per step {T}x predict B={N} "
                                f"and 1 train_step {N} agents x t_max={T} = {N * T} frames, "
-                               "clip 40", "agents": N, "t_max": T, "seed": seed},
+                               "clip 40; " + ("predictions and training on two streams" if args.streams == 2 else
+                                              "one stream"), "agents": N, "t_max": T, "seed": seed, "streams": args.streams},
+        "one_stream": {"value": round(frames_per_step / sec_one, 1), "ms_per_step": round(sec_one * 1e3, 4)},
+        "two_streams": {"value": round(frames_per_step / sec_two, 1), "ms_per_step": round(sec_two * 1e3, 4)},
         "pps_predict_only": {"value": round(1024 / pred_sec, 1), "batch": 1024, "ms_per_call": round(pred_sec * 1e3, 4)},
         "tps_train_only": {"value": round(frames_per_step / train_sec, 1), "frames": frames_per_step,
                            "ms_per_call": round(train_sec * 1e3, 4), "paper_tps_batches_of_5": round(N / train_sec, 1)},
@@ -232,16 +268,20 @@ def main() -> int:
         theta = theta_np.astype(np.float64)
         cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
         t0 = time.perf_counter()
-        bo = None
-        for t in range(T):
-            out_t = orc.forward(onet, theta, frames_np[:, t])
-            if t == 0:
-                bo = out_t["values"]
-        orc.train_step(onet, theta, np.zeros_like(theta), frames_np, tr["actions"], tr["rewards"], tr["dones"], bo,
-                       orc.HParams(clip_norm=40.0))
-        cpu_sec = time.perf_counter() - t0
+        cpu_steps = 0
+        while cpu_steps < 1 or (time.perf_counter() - t0 < 10.0 and cpu_steps < 64):     # about 10 s of CPU work
+            bo = None
+            for t in range(T):
+                out_t = orc.forward(onet, theta, frames_np[:, t])
+                if t == 0:
+                    bo = out_t["values"]
+            orc.train_step(onet, theta, np.zeros_like(theta), frames_np, tr["actions"], tr["rewards"], tr["dones"], bo,
+                           orc.HParams(clip_norm=40.0))
+            cpu_steps += 1
+        cpu_sec = (time.perf_counter() - t0) / cpu_steps
         out["cpu_baseline"] = {"value": round(frames_per_step / cpu_sec, 1), "unit": "frames/s", "cores": cores,
-                               "kind": "oracle", "sample": f"1 whole step of the same workload ({cpu_sec:.1f} s, fp64, OpenMP over frames)"}
+                               "kind": "oracle",
+                               "sample": f"{cpu_steps} whole steps of the same workload ({cpu_sec:.2f} s each, fp64, OpenMP over frames)"}
     print(json.dumps(out))
     return 0
 
