@@ -12,8 +12,8 @@ resident in HBM before the timed region starts.  By default the step is
 submitted the way the paper's predictor and trainer threads do it (Sec. 4.1):
 the five predictions on one stream, the training step (on the segment the
 previous step predicted) on another, so that the two calls share the GPU;
-`--streams 1` issues the six calls one after another, and both rates are
-always in the output.
+`--streams 1` issues the six calls one after another (the default run
+measures that too and reports both rates).
 
 Prints ONE JSON line.  `value` = frames per second through predict AND
 train_step (each frame is predicted once and trained on once).  The line
@@ -37,7 +37,7 @@ PEAK_FP32_MFMA = 157.3e12   # MI355X dense fp32 matrix, FLOP/s
 PEAK_HBM = 8.0e12           # B/s
 
 # HBM traffic per launch from hardware counters: rocprofv3 --pmc FETCH_SIZE and --pmc WRITE_SIZE (two runs of
-# `python3 bench.py --steps 3 --warmup 1 --no-cpu-baseline --mixed-seconds 0 --rmsprop-big`), KiB per dispatch,
+# `python3 bench.py --steps 3 --warmup 1 --streams 1 --no-cpu-baseline --mixed-seconds 0 --rmsprop-big`), KiB per dispatch,
 # small net, by frames in the launch.  Every read request on this chip is a 128-byte line while FETCH_SIZE prices
 # it at 64 bytes: on the streaming RMSProp kernel over 2^28 parameters (12 B read, 8 B written per parameter) the
 # counters read 0.5000 and 1.0000 of the known bytes, hence the scale factors.  The summary is kept under profiles/.
@@ -45,14 +45,14 @@ FETCH_SCALE, WRITE_SCALE = 2.0, 1.0
 COUNTER_KIB = {   # stage: {frames per launch: (FETCH_SIZE, WRITE_SIZE)}
     "conv12_fwd": {512: (7554.7, 5184.0), 1024: (14626.7, 10368.0), 2560: (35842.8, 89931.1)},   # 2560: training, keeps y1
     "fc_fwd": {512: (4153.0, 7168.0), 1024: (6649.0, 8192.0), 2560: (14425.0, 20480.0)},
-    "heads_fwd": {512: (3776.0, 592.0), 1024: (4268.5, 1104.0), 2560: (10412.5, 2760.0)},
+    "heads_fwd": {512: (3789.0, 592.0), 1024: (4282.0, 1104.0)},
+    "heads_train": {2560: (10524.6, 9396.2)},
     "conv1_wgrad": {2560: (67652.6, 4112.0)},
-    "conv2_wgrad": {2560: (45142.0, 16513.0)},
+    "conv2_wgrad": {2560: (45139.5, 16461.9)},
     "conv2_dgrad": {2560: (45191.8, 64000.0)},
     "fc_wgrad": {2560: (14299.0, 20736.3)},
-    "fc_dgrad": {2560: (25421.0, 28214.6)},
-    "heads_bwd": {2560: (1511.5, 8994.4)},
-    "wgrad_reduce": {2560: (24733.3, 2807.6)},
+    "fc_dgrad": {2560: (25714.2, 27410.9)},
+    "wgrad_reduce": {2560: (24878.8, 2809.9)},
     "rmsprop": {2560: (4019.6, 5394.1)},
 }
 
@@ -161,9 +161,13 @@ def main() -> int:
         ev_train[(i - 1) % 3].record(s_train)
 
     for _ in range(args.warmup):
-        step(); step_two_streams()
+        step()
     sec_one = timed(step, args.steps)
-    sec_two = timed(step_two_streams, args.steps)
+    sec_two = None
+    if args.streams == 2:
+        for _ in range(args.warmup):
+            step_two_streams()
+        sec_two = timed(step_two_streams, args.steps)
     sec = sec_two if args.streams == 2 else sec_one
     frames_per_step = N * T
 
@@ -214,8 +218,8 @@ def main() -> int:
                     "unit": "GB/s", "frac": round(ach * 1e9 / PEAK_HBM, 4), "traffic": None,
                     "ms_per_launch": round(dp["ms"] / dp["calls"], 5)}
     if args.net == "small" and N == 512:
-        fwd = {"conv12_fwd", "fc_fwd", "heads_fwd"}
-        roofline["traffic"] = counter_traffic(dom["stage"], [(N, T), (N * T, 1)] if dom["stage"] in fwd else [(N * T, 1)])
+        launches = {"conv12_fwd": [(N, T), (N * T, 1)], "fc_fwd": [(N, T), (N * T, 1)], "heads_fwd": [(N, T)]}
+        roofline["traffic"] = counter_traffic(dom["stage"], launches.get(dom["stage"], [(N * T, 1)]))
         roofline["algorithmic_bytes_per_launch"] = round(dp["bytes"] / dp["calls"]) if dp["bytes"] > 0 else None
     flop_step = sum(p["flop"] for p in prof.values()) / args.steps
     whole = {"tflops": round(flop_step / sec / 1e12, 3), "frac_fp32_mfma_peak": round(flop_step / sec / PEAK_FP32_MFMA, 4)}
@@ -235,7 +239,7 @@ def main() -> int:
                                "clip 40; " + ("predictions and training on two streams" if args.streams == 2 else
                                               "one stream"), "agents": N, "t_max": T, "seed": seed, "streams": args.streams},
         "one_stream": {"value": round(frames_per_step / sec_one, 1), "ms_per_step": round(sec_one * 1e3, 4)},
-        "two_streams": {"value": round(frames_per_step / sec_two, 1), "ms_per_step": round(sec_two * 1e3, 4)},
+        "two_streams": {"value": round(frames_per_step / sec_two, 1), "ms_per_step": round(sec_two * 1e3, 4)} if sec_two else None,
         "pps_predict_only": {"value": round(1024 / pred_sec, 1), "batch": 1024, "ms_per_call": round(pred_sec * 1e3, 4)},
         "tps_train_only": {"value": round(frames_per_step / train_sec, 1), "frames": frames_per_step,
                            "ms_per_call": round(train_sec * 1e3, 4), "paper_tps_batches_of_5": round(N / train_sec, 1)},
