@@ -289,6 +289,53 @@ def test_predict_follows_a_large_update(G):
     net.close()
 
 
+def test_predictions_on_one_stream_while_training_on_another(G):
+    # the way the benchmark and the scheduler submit work (Sec. 4.1: predictors and trainers share the GPU): every
+    # prediction must see one whole parameter set, the one before or the one after the update, never a mixture,
+    # and the update itself must not be disturbed by the predictions reading next to it
+    import torch
+    N, T, A = 64, 5, 18
+    desc = G.SMALL_NET(A)
+    net, onet, theta = make(G, desc, N, N * T, 5150)
+    frames = synth.rectangle_frames(5151, N * T).reshape(N, T, 4, 84, 84)
+    tr = synth.trajectories(5152, N, T, A)
+    boot = synth.rng(5153).standard_normal(N).astype(np.float32)
+    hp_kw = dict(lr=0.02)               # large, so that the two parameter sets give visibly different outputs
+    ref = orc.train_step(onet, theta.astype(np.float64), np.zeros(net.n_params), frames, tr["actions"], tr["rewards"],
+                         tr["dones"], boot.astype(np.float64), orc.HParams(**hp_kw))
+    pf = [frames[:, t] for t in range(T)]
+    want = [(orc.forward(onet, theta.astype(np.float64), f)["logits"], orc.forward(onet, ref["theta"], f)["logits"])
+            for f in pf]
+    assert all(rel_err(a, b) > 1e-2 for a, b in want)
+    d = dict(frames=torch.from_numpy(frames).cuda(), actions=torch.from_numpy(tr["actions"]).cuda(),
+             rewards=torch.from_numpy(tr["rewards"]).cuda(), dones=torch.from_numpy(tr["dones"]).cuda())
+    boot_t = torch.from_numpy(boot).cuda()
+    pft = [torch.from_numpy(np.ascontiguousarray(f)).cuda() for f in pf]
+    outs = [torch.full((N, A), float("nan"), device="cuda") for _ in range(3 * T)]
+    sp, st = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    print("predictions and a training step on two streams", flush=True)
+    for k in range(T):
+        net.predict(pft[k], logits=outs[k], stream=sp)
+    net.train_step(d["frames"], d["actions"], d["rewards"], d["dones"], boot_t, G.HParams(**hp_kw), stream=st)
+    for k in range(T, 3 * T):
+        net.predict(pft[k % T], logits=outs[k], stream=sp)
+    torch.cuda.synchronize()
+    th1 = net.params_get(0).cpu().numpy()
+    assert rel_err(th1, ref["theta"]) <= TOL_BWD
+    assert rel_err(th1.astype(np.float64) - theta, ref["theta"] - theta) <= 2 * TOL_BWD
+    seen_new = False
+    for k in range(3 * T):
+        lg = outs[k].cpu().numpy()
+        e_old, e_new = rel_err(lg, want[k % T][0]), rel_err(lg, want[k % T][1])
+        assert min(e_old, e_new) <= TOL_FWD, (k, e_old, e_new)
+        assert not (seen_new and e_new > TOL_FWD), f"prediction {k} went back to the old parameters"
+        seen_new = seen_new or e_new <= TOL_FWD
+    lg, _, _, _ = run_predict(G, net, pf[0])       # after everything has finished: the new parameters
+    assert rel_err(lg, want[0][1]) <= TOL_FWD
+    net.close()
+
+
 @pytest.mark.parametrize("shape,N,T", [(TINY, 13, 5), (TINY3, 9, 3), (ODD, 11, 4)])
 def test_train_odd_shapes(G, shape, N, T):
     run_train(G, G.NetDesc(**shape), N, T, 600, dict(beta=0.05, value_coef=0.5, gamma=0.9), g0_scale=1e-2)
