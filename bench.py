@@ -189,7 +189,7 @@ def main() -> int:
     prof = net.profile_read()
     net.profile_enable(False)
     # conv1 runs as exact bf16x3 MFMA and is bound by fetching frames and storing activations
-    hbm_stages = {"conv12_fwd", "conv1_fwd", "conv1_wgrad", "rmsprop", "sqnorm"}
+    hbm_stages = {"conv12_fwd", "conv1_fwd", "conv1_wgrad", "conv2_dgrad", "rmsprop", "sqnorm"}
     stages = []
     for name, p in prof.items():
         per_call_ms = p["ms"] / p["calls"]

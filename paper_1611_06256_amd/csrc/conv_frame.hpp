@@ -378,152 +378,6 @@ inline hipError_t launch_conv_wgrad_frame(const typename SP::TIn *x, const float
 }
 
 
-// Input gradient of a layer whose kernel is twice its stride (4x4 stride 2):
-//   dX[c][y][x] = [xin[c][y][x] > 0] * sum_{oc,u,v} dY[oc][i][j] W[oc][c][u][v],  y = S i + u, x = S j + v.
-// Input pixels fall into S*S phases (y mod S, x mod S); within a phase the sum
-// is a stride-1 correlation of dY with a 2x2 sub-filter, so every pixel has
-// the same 4*OC terms if dY is padded with a border of zeros.  Wave w of a
-// block computes phase w for all pixels of a frame: the sub-filters are the
-// row operand (C rows), 16 pixels of the phase grid the column operand, and
-// k = (oc, a, e) the contraction.  The four phases are interleaved in an LDS
-// copy of the output frame, which is then masked and stored with full-width
-// writes.  A block computes 16 input channels, 16 * blockIdx.y .. (gridDim.y = C / 16).
-template <class SP>
-__global__ __launch_bounds__(256, 2) void conv_dgrad_frame_kernel(const float *__restrict__ dy,
-                                                                  const float *__restrict__ w,
-                                                                  const float *__restrict__ xin,
-                                                                  float *__restrict__ dx, int nframes, int rb) {
-    // rb: filters and dY are rounded to bfloat16 on their way to LDS
-    static_assert(SP::KS == 2 * SP::S && SP::S == 2, "kernel must be 4x4 with stride 2");
-    static_assert(SP::C % 16 == 0, "whole row tiles of input channels");
-    constexpr int CS = 16;                                         // input channels of a block
-    static_assert(SP::H % SP::S == 0 && SP::W % SP::S == 0, "phases must tile the input");
-    constexpr int S = SP::S;
-    constexpr int GH = SP::H / S, GW = SP::W / S, GP = GH * GW;   // phase grid
-    constexpr int NT = (GP + 15) / 16;                            // pixel tiles per phase
-    constexpr int PH = SP::OH + 2, PW = SP::OW + 2;               // dY with a zero border
-    constexpr int OCP = ((PH * PW + 31) / 32) * 32 + 16;          // pitch per filter: 16 mod 32 banks
-    constexpr int KP = SP::OC * 4;                                // contraction length
-    constexpr int WP = KP + 4;                                    // pitch of a sub-filter row
-    constexpr int NDY = SP::OC * SP::NPIX, DPT = (NDY + 255) / 256;
-    constexpr int NX = CS * SP::H * SP::W, XV = NX / 4, XPT = (XV + 255) / 256;
-    static_assert(GH <= SP::OH + 1 && GW <= SP::OW + 1, "phase grid must fit the padded dY");
-    __shared__ __attribute__((aligned(16))) float wp[4 * CS * WP];         // [phase][c][(oc,a,e)]
-    __shared__ __attribute__((aligned(16))) float dp[SP::OC * OCP];        // [oc][PH][PW]
-    __shared__ __attribute__((aligned(16))) float outs[NX];                // [c][H][W]
-
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int l16 = lane & 15, g = lane >> 4;
-    const int ry = wave / S, rx = wave % S;
-
-    const int c0 = blockIdx.y * CS;
-    for (int e = tid; e < 4 * CS * KP; e += 256) {
-        const int ph = e / (CS * KP), c = (e / KP) % CS, k = e % KP;
-        const int oc = k / 4, a = (k / 2) % 2, ee = k % 2;
-        const int u = ph / S + S * a, v = ph % S + S * ee;
-        const float wv = w[((size_t)(oc * SP::C + c0 + c) * SP::KS + u) * SP::KS + v];
-        wp[(ph * CS + c) * WP + k] = rb ? bf16_rne(wv) : wv;
-    }
-    for (int e = tid; e < SP::OC * OCP; e += 256) dp[e] = 0.f;
-
-    int pbase[NT], obase[NT];
-#pragma unroll
-    for (int i = 0; i < NT; ++i) {
-        int p = 16 * i + l16;
-        const bool ok = p < GP;
-        if (!ok) p = 0;
-        const int iy = p / GW, ix = p % GW;
-        // element (iy - a + 1, ix - e + 1) of the padded plane = pbase + (1 - a) * PW + (1 - e)
-        pbase[i] = iy * PW + ix;
-        obase[i] = ok ? (S * iy + ry) * SP::W + S * ix + rx : -1;
-    }
-    int didx[DPT], dlds[DPT];
-#pragma unroll
-    for (int i = 0; i < DPT; ++i) {
-        const int e = min(tid + 256 * i, NDY - 1);
-        didx[i] = e;
-        const int oc = e / SP::NPIX, pix = e % SP::NPIX;
-        dlds[i] = oc * OCP + (pix / SP::OW + 1) * PW + pix % SP::OW + 1;
-    }
-    int xidx[XPT];
-#pragma unroll
-    for (int i = 0; i < XPT; ++i) xidx[i] = min(tid + 256 * i, XV - 1);
-
-    const float *wrow = wp + ((ry * S + rx) * CS + l16) * WP + 4 * g;
-    float dpre[DPT];
-    int f = blockIdx.x;
-    {
-        const float *dsrc = dy + (size_t)min(f, nframes - 1) * NDY;
-#pragma unroll
-        for (int i = 0; i < DPT; ++i) dpre[i] = dsrc[didx[i]];
-    }
-    for (; f < nframes; f += gridDim.x) {
-        __syncthreads();
-#pragma unroll
-        for (int i = 0; i < DPT; ++i) dp[dlds[i]] = rb ? bf16_rne(dpre[i]) : dpre[i];
-        __syncthreads();
-        {
-            const float *dsrc = dy + (size_t)min(f + (int)gridDim.x, nframes - 1) * NDY;
-#pragma unroll
-            for (int i = 0; i < DPT; ++i) dpre[i] = dsrc[didx[i]];
-        }
-        float4 mask[XPT];
-        {
-            const float4 *msrc = (const float4 *)(xin + (size_t)f * SP::CHW + (size_t)c0 * (SP::H * SP::W));
-#pragma unroll
-            for (int i = 0; i < XPT; ++i) mask[i] = msrc[xidx[i]];
-        }
-        floatx4 acc[NT];
-#pragma unroll
-        for (int i = 0; i < NT; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int q = 0; q < KP / 16; ++q) {
-            const float4 wv = *(const float4 *)(wrow + 16 * q);     // taps (a,e) = (0,0) (0,1) (1,0) (1,1) of filter 4q+g
-            const float *plane = dp + (4 * q + g) * OCP;
-#pragma unroll
-            for (int i = 0; i < NT; ++i) {
-                const float *b = plane + pbase[i];
-                acc[i] = mfma4(wv.x, b[PW + 1], acc[i]);
-                acc[i] = mfma4(wv.y, b[PW], acc[i]);
-                acc[i] = mfma4(wv.z, b[1], acc[i]);
-                acc[i] = mfma4(wv.w, b[0], acc[i]);
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < NT; ++i)
-            if (obase[i] >= 0) {
-#pragma unroll
-                for (int r = 0; r < 4; ++r) outs[(4 * g + r) * (SP::H * SP::W) + obase[i]] = acc[i][r];
-            }
-        __syncthreads();
-        float4 *dst = (float4 *)(dx + (size_t)f * SP::CHW + (size_t)c0 * (SP::H * SP::W));
-#pragma unroll
-        for (int i = 0; i < XPT; ++i) {
-            const int e = tid + 256 * i;
-            if (e < XV) {
-                float4 v = ((const float4 *)outs)[e];
-                v.x = mask[i].x > 0.f ? v.x : 0.f; v.y = mask[i].y > 0.f ? v.y : 0.f;
-                v.z = mask[i].z > 0.f ? v.z : 0.f; v.w = mask[i].w > 0.f ? v.w : 0.f;
-                dst[e] = v;
-            }
-        }
-    }
-}
-
-// `blocks`: how many blocks the chip holds at once (LDS decides), shared out over the channel slices.
-template <class SP>
-inline hipError_t launch_conv_dgrad_frame(const float *dy, const float *w, const float *xin, float *dx, int nframes,
-                                          hipStream_t s, int blocks = 512, int rb = 0) {
-    if (nframes <= 0) return hipSuccess;
-    constexpr int SLICES = SP::C / 16;
-    const int per = blocks / SLICES;
-    const int grid = nframes < per ? nframes : per;
-    hipLaunchKernelGGL((conv_dgrad_frame_kernel<SP>), dim3(grid, SLICES), dim3(256), 0, s, dy, w, xin, dx, nframes, rb);
-    return hipGetLastError();
-}
-
-
 // Input gradient of a stride-1 layer:
 //   dX[c][y][x] = [xin[c][y][x] > 0] * sum_{oc,u,v} dY[oc][y-u][x-v] W[oc][c][u][v].
 // With dY padded by KS-1 zeros on every side this is a forward convolution of

@@ -20,6 +20,7 @@
 #include "dense_gemm_bf16x6.hpp"
 #include "conv2_bf16x6.hpp"
 #include "conv12_fused.hpp"
+#include "conv_dgrad_bf16x6.hpp"
 
 using namespace ga3c;
 
@@ -1565,13 +1566,14 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
         }
         if (l == 0) break;   // the input is data: no gradient needed
         // input gradient
-        STAGE(CONV_DGRAD[l], 2.0 * B * g.OHW * g.OC * g.K, 0);
+        // bytes: dY in, the layer's input (for the ReLU mask) in, dX out
+        STAGE(CONV_DGRAD[l], 2.0 * B * g.OHW * g.OC * g.K, 4.0 * B * (g.OC * g.OHW + 2.0 * g.C * g.H * g.W));
         if (c->fast && spec_matches<SpecS2>(g, false) && is_aligned16(th + c->off[2 * l])) {
-            HIP_TRY(launch_conv_dgrad_frame<SpecS2>(c->dact[l], th + c->off[2 * l], w.act[l - 1], c->dact[l - 1], B, s, 512, c->rb));
+            HIP_TRY(launch_conv_dgrad_bf16x6<SpecS2>(c->dact[l], th + c->off[2 * l], w.act[l - 1], c->dact[l - 1], B, s, 512, c->rb));
             continue;
         }
-        if (c->fast && spec_matches<SpecL2>(g, false) && is_aligned16(th + c->off[2 * l])) {   // one block per CU
-            HIP_TRY(launch_conv_dgrad_frame<SpecL2>(c->dact[l], th + c->off[2 * l], w.act[l - 1], c->dact[l - 1], B, s, 256, c->rb));
+        if (c->fast && spec_matches<SpecL2>(g, false) && is_aligned16(th + c->off[2 * l])) {
+            HIP_TRY(launch_conv_dgrad_bf16x6<SpecL2>(c->dact[l], th + c->off[2 * l], w.act[l - 1], c->dact[l - 1], B, s, 512, c->rb));
             continue;
         }
         if (c->fast && spec_matches<SpecL3>(g, false)) {
