@@ -13,6 +13,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "conv_frame.hpp"
 
 namespace ga3c {
@@ -195,7 +197,7 @@ inline hipError_t launch_conv1_bf16x3_fwd(const uint8_t *x, const float *w, cons
 // part: [gridDim.x][OCT][257]; the last column is the bias gradient.  A layer
 // with OCT = 32 filters is done in two slices of 16 (blockIdx.y).
 template <int OCT>
-__global__ __launch_bounds__(256) void conv1_bf16x3_wgrad_kernel(const uint8_t *__restrict__ x,
+__global__ __launch_bounds__(512) void conv1_bf16x3_wgrad_kernel(const uint8_t *__restrict__ x,
                                                                  const float *__restrict__ dy,
                                                                  float *__restrict__ part, int nframes, float scale,
                                                                  int rb) {
@@ -203,8 +205,10 @@ __global__ __launch_bounds__(256) void conv1_bf16x3_wgrad_kernel(const uint8_t *
     constexpr int C = 4, H = 84, W = 84, OC = 16, OH = 20, NPIX = 400, K = 256, CHW = C * H * W;
     constexpr int XROW = 32, XPLANE = 21 * XROW + 8;       // bf16 elements; plane pitch 20 mod 32 dwords
     constexpr int DROW = 24, DOC = OH * DROW + 8;          // dY rows padded to 24, filter pitch 20 mod 32 dwords
-    constexpr int NITEM = 336 * 6, IPT = (NITEM + 255) / 256;    // (frame row, group of 4 dwords)
-    constexpr int NDV = OC * NPIX / 4, DPT = (NDV + 255) / 256;  // float4 of dY per frame
+    constexpr int NTHR = 512;                              // 8 wavefronts: two per SIMD, so that one's LDS and
+                                                           // conversion work fills the other's MFMA waits
+    constexpr int NITEM = 336 * 6, IPT = (NITEM + NTHR - 1) / NTHR;    // (frame row, group of 4 dwords)
+    constexpr int NDV = OC * NPIX / 4, DPT = (NDV + NTHR - 1) / NTHR;  // float4 of dY per frame
     constexpr int NSTEP = OH * 3 / 4;                      // 60 blocks of 8 pixels, 4 per MFMA
     __shared__ __attribute__((aligned(16))) __bf16 xp[64 * XPLANE];
     __shared__ __attribute__((aligned(16))) __bf16 dp[3 * OC * DOC];
@@ -216,24 +220,24 @@ __global__ __launch_bounds__(256) void conv1_bf16x3_wgrad_kernel(const uint8_t *
     const int oc0 = blockIdx.y * OC;                       // my slice of the filters
     static_assert(OCT % OC == 0, "whole slices of 16 filters");
 
-    for (int e = tid; e < 64 * XPLANE / 2; e += 256) ((uint32_t *)xp)[e] = 0u;     // padding stays zero
-    for (int e = tid; e < 3 * OC * DOC / 2; e += 256) ((uint32_t *)dp)[e] = 0u;
+    for (int e = tid; e < 64 * XPLANE / 2; e += NTHR) ((uint32_t *)xp)[e] = 0u;     // padding stays zero
+    for (int e = tid; e < 3 * OC * DOC / 2; e += NTHR) ((uint32_t *)dp)[e] = 0u;
 
     // staging descriptors: where my dwords come from and where they go
     int xsrc[IPT], xdst[IPT], xcnt[IPT];
 #pragma unroll
     for (int i = 0; i < IPT; ++i) {
-        const int it = min(tid + 256 * i, NITEM - 1);
+        const int it = min(tid + NTHR * i, NITEM - 1);
         const int row = it / 6, gq = it % 6;               // row = c*84 + r
         const int c = row / H, r = row % H;
         xsrc[i] = row * (W / 4) + 4 * gq;                  // dword index in the frame
-        xcnt[i] = (tid + 256 * i < NITEM) ? (gq == 5 ? 1 : 4) : 0;
+        xcnt[i] = (tid + NTHR * i < NITEM) ? (gq == 5 ? 1 : 4) : 0;
         xdst[i] = ((c * 4 + r % 4) * 4) * XPLANE + (r / 4) * XROW + 4 * gq;   // plane (c, u'=r%4, v'=0)
     }
     int dsrc[DPT], ddst[DPT];
 #pragma unroll
     for (int i = 0; i < DPT; ++i) {
-        const int e = min(tid + 256 * i, NDV - 1);
+        const int e = min(tid + NTHR * i, NDV - 1);
         dsrc[i] = e;
         const int oc = e / (NPIX / 4), pq = e % (NPIX / 4);           // 5 float4 per row of 20
         ddst[i] = oc * DOC + (pq / 5) * DROW + 4 * (pq % 5);
@@ -260,7 +264,8 @@ __global__ __launch_bounds__(256) void conv1_bf16x3_wgrad_kernel(const uint8_t *
     };
     int f = blockIdx.x;
     fetch(min(f, nframes - 1));
-    const __bf16 *xq = xp + (wave * 16 + l16) * XPLANE;              // my plane
+    const int ch = wave & 3, half = wave >> 2;       // wavefronts w and w + 4 share channel w and halve the pixel blocks
+    const __bf16 *xq = xp + (ch * 16 + l16) * XPLANE;                // my plane
     for (; f < nframes; f += gridDim.x) {
         __syncthreads();
 #pragma unroll
@@ -278,20 +283,20 @@ __global__ __launch_bounds__(256) void conv1_bf16x3_wgrad_kernel(const uint8_t *
         }
 #pragma unroll
         for (int i = 0; i < DPT; ++i) {
-            if (tid + 256 * i < NDV) {
+            if (tid + NTHR * i < NDV) {
                 const float v[4] = {dpre[i].x, dpre[i].y, dpre[i].z, dpre[i].w};
                 union { __bf16 h[4]; uint2 u; } o[3];
 #pragma unroll
                 for (int t = 0; t < 4; ++t) split3(v[t], o[0].h[t], o[1].h[t], o[2].h[t], rb);
 #pragma unroll
                 for (int term = 0; term < 3; ++term) *(uint2 *)(dp + term * OC * DOC + ddst[i]) = o[term].u;
-                bsh[tid + 256 * i] = rb ? ((float)o[0].h[0] + (float)o[0].h[1]) + ((float)o[0].h[2] + (float)o[0].h[3])
+                bsh[tid + NTHR * i] = rb ? ((float)o[0].h[0] + (float)o[0].h[1]) + ((float)o[0].h[2] + (float)o[0].h[3])
                                         : (v[0] + v[1]) + (v[2] + v[3]);
             }
         }
         __syncthreads();
         fetch(min(f + (int)gridDim.x, nframes - 1));
-        {   // bias: 16 lanes share a filter, 100 partial sums each
+        if (tid < 256) {   // bias: 16 lanes share a filter, 100 partial sums each
             const int oc = tid / 16, pt = tid % 16;
             float sum = 0.f;
             for (int m = pt; m < NPIX / 4; m += 16) sum += bsh[oc * (NPIX / 4) + m];
@@ -299,30 +304,54 @@ __global__ __launch_bounds__(256) void conv1_bf16x3_wgrad_kernel(const uint8_t *
             sum += dpp_row_f32<0x141>(sum); sum += dpp_row_f32<0x140>(sum);
             bsum += sum;
         }
+        auto steps = [&](auto first, auto last) {
 #pragma unroll
-        for (int st = 0; st < NSTEP; ++st) {
-            const int blk = 4 * st + g, i = blk / 3, jb = blk % 3;
-            Bf16x8Bits d[3];
+            for (int st = decltype(first)::value; st < decltype(last)::value; ++st) {
+                const int blk = 4 * st + g, i = blk / 3, jb = blk % 3;
+                Bf16x8Bits d[3];
 #pragma unroll
-            for (int term = 0; term < 3; ++term)
-                d[term].u = *(const u32x4 *)(dp + term * OC * DOC + l16 * DOC + i * DROW + 8 * jb);
+                for (int term = 0; term < 3; ++term)
+                    d[term].u = *(const u32x4 *)(dp + term * OC * DOC + l16 * DOC + i * DROW + 8 * jb);
 #pragma unroll
-            for (int a = 0; a < 2; ++a) {
-                const __bf16 *src = xq + (i + a) * XROW + 8 * jb;
-                const u32x4 c0 = *(const u32x4 *)src;
-                const uint32_t c4 = *(const uint32_t *)(src + 8);
-                Bf16x8Bits x0, x1;
-                x0.u = c0;
-                x1.u = u32x4{__builtin_amdgcn_alignbit(c0[1], c0[0], 16), __builtin_amdgcn_alignbit(c0[2], c0[1], 16),
-                             __builtin_amdgcn_alignbit(c0[3], c0[2], 16), __builtin_amdgcn_alignbit(c4, c0[3], 16)};
+                for (int a = 0; a < 2; ++a) {
+                    const __bf16 *src = xq + (i + a) * XROW + 8 * jb;
+                    const u32x4 c0 = *(const u32x4 *)src;
+                    const uint32_t c4 = *(const uint32_t *)(src + 8);
+                    Bf16x8Bits x0, x1;
+                    x0.u = c0;
+                    x1.u = u32x4{__builtin_amdgcn_alignbit(c0[1], c0[0], 16), __builtin_amdgcn_alignbit(c0[2], c0[1], 16),
+                                 __builtin_amdgcn_alignbit(c0[3], c0[2], 16), __builtin_amdgcn_alignbit(c4, c0[3], 16)};
 #pragma unroll
-                for (int term = 2; term >= 0; --term) {
-                    acc[a][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(d[term].v, x0.v, acc[a][0], 0, 0, 0);
-                    acc[a][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(d[term].v, x1.v, acc[a][1], 0, 0, 0);
+                    for (int term = 2; term >= 0; --term) {
+                        acc[a][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(d[term].v, x0.v, acc[a][0], 0, 0, 0);
+                        acc[a][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(d[term].v, x1.v, acc[a][1], 0, 0, 0);
+                    }
                 }
             }
-        }
+        };
+        constexpr int MID = (NSTEP + 1) / 2;
+        if (half == 0) steps(std::integral_constant<int, 0>{}, std::integral_constant<int, MID>{});
+        else steps(std::integral_constant<int, MID>{}, std::integral_constant<int, NSTEP>{});
     }
+    // the two halves of a channel's pixel blocks are added through LDS (dY planes are no longer needed)
+    __syncthreads();
+    float *xch = (float *)dp;
+    if (half == 1) {
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) xch[((ch * 16 + (a * 2 + b) * 4 + r) * 64) + lane] = acc[a][b][r];
+    }
+    __syncthreads();
+    if (half == 1) return;
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[a][b][r] += xch[((ch * 16 + (a * 2 + b) * 4 + r) * 64) + lane];
     // lane (l16, g), register r of acc[a][b]: filter 4g + r, tap (c = wave, u = 4a + l16/4, v = 4b + l16%4)
     float *pb = part + ((size_t)blockIdx.x * OCT + oc0) * (K + 1);
 #pragma unroll
@@ -331,8 +360,8 @@ __global__ __launch_bounds__(256) void conv1_bf16x3_wgrad_kernel(const uint8_t *
         for (int b = 0; b < 2; ++b)
 #pragma unroll
             for (int r = 0; r < 4; ++r)
-                pb[(4 * g + r) * (K + 1) + wave * 64 + (4 * a + l16 / 4) * 8 + 4 * b + l16 % 4] = acc[a][b][r] * scale;
-    if (tid % 16 == 0) pb[(tid / 16) * (K + 1) + K] = bsum;
+                pb[(4 * g + r) * (K + 1) + ch * 64 + (4 * a + l16 / 4) * 8 + 4 * b + l16 % 4] = acc[a][b][r] * scale;
+    if (tid % 16 == 0) pb[(tid / 16) * (K + 1) + K] = bsum;      // tid < 256 here
 }
 
 inline int conv1_bf16x3_wgrad_blocks(int nframes) { return nframes < 256 ? nframes : 256; }
@@ -341,7 +370,7 @@ template <int OCT = 16>
 inline hipError_t launch_conv1_bf16x3_wgrad(const uint8_t *x, const float *dy, float *part, int nframes, float scale,
                                             hipStream_t s, int rb = 0) {
     if (nframes <= 0) return hipSuccess;
-    hipLaunchKernelGGL(conv1_bf16x3_wgrad_kernel<OCT>, dim3(conv1_bf16x3_wgrad_blocks(nframes), OCT / 16), dim3(256), 0, s, x,
+    hipLaunchKernelGGL(conv1_bf16x3_wgrad_kernel<OCT>, dim3(conv1_bf16x3_wgrad_blocks(nframes), OCT / 16), dim3(512), 0, s, x,
                        dy, part, nframes, scale, rb);
     return hipGetLastError();
 }
