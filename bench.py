@@ -47,9 +47,9 @@ COUNTER_KIB = {   # stage: {frames per launch: (FETCH_SIZE, WRITE_SIZE)}
     "fc_fwd": {512: (4153.0, 7168.0), 1024: (6649.0, 8192.0), 2560: (14425.0, 20480.0)},
     "heads_fwd": {512: (3789.0, 592.0), 1024: (4282.0, 1104.0)},
     "heads_train": {2560: (10524.6, 9396.2)},
-    "conv1_wgrad": {2560: (67652.6, 4112.0)},
+    "conv1_wgrad": {2560: (67628.6, 4112.0)},
     "conv2_wgrad": {2560: (45139.5, 16461.9)},
-    "conv2_dgrad": {2560: (45191.8, 64000.0)},
+    "conv2_dgrad": {2560: (45193.5, 64000.0)},
     "fc_wgrad": {2560: (14299.0, 20736.3)},
     "fc_dgrad": {2560: (25714.2, 27410.9)},
     "wgrad_reduce": {2560: (24878.8, 2809.9)},
