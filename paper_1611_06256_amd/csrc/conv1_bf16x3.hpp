@@ -196,8 +196,8 @@ inline hipError_t launch_conv1_bf16x3_fwd(const uint8_t *x, const float *w, cons
 // Rows of 20 pixels are padded to 24 = 3 blocks of 8 with zero dY.
 // part: [gridDim.x][OCT][257]; the last column is the bias gradient.  A layer
 // with OCT = 32 filters is done in two slices of 16 (blockIdx.y).
-template <int OCT>
-__global__ __launch_bounds__(512) void conv1_bf16x3_wgrad_kernel(const uint8_t *__restrict__ x,
+template <int OCT, int NPART>
+__global__ __launch_bounds__(256 * NPART) void conv1_bf16x3_wgrad_kernel(const uint8_t *__restrict__ x,
                                                                  const float *__restrict__ dy,
                                                                  float *__restrict__ part, int nframes, float scale,
                                                                  int rb) {
@@ -205,8 +205,8 @@ __global__ __launch_bounds__(512) void conv1_bf16x3_wgrad_kernel(const uint8_t *
     constexpr int C = 4, H = 84, W = 84, OC = 16, OH = 20, NPIX = 400, K = 256, CHW = C * H * W;
     constexpr int XROW = 32, XPLANE = 21 * XROW + 8;       // bf16 elements; plane pitch 20 mod 32 dwords
     constexpr int DROW = 24, DOC = OH * DROW + 8;          // dY rows padded to 24, filter pitch 20 mod 32 dwords
-    constexpr int NTHR = 512;                              // 8 wavefronts: two per SIMD, so that one's LDS and
-                                                           // conversion work fills the other's MFMA waits
+    constexpr int NTHR = 256 * NPART;                      // NPART wavefronts per SIMD, so that one's LDS and
+                                                           // conversion work fills another's MFMA waits
     constexpr int NITEM = 336 * 6, IPT = (NITEM + NTHR - 1) / NTHR;    // (frame row, group of 4 dwords)
     constexpr int NDV = OC * NPIX / 4, DPT = (NDV + NTHR - 1) / NTHR;  // float4 of dY per frame
     constexpr int NSTEP = OH * 3 / 4;                      // 60 blocks of 8 pixels, 4 per MFMA
@@ -264,7 +264,7 @@ __global__ __launch_bounds__(512) void conv1_bf16x3_wgrad_kernel(const uint8_t *
     };
     int f = blockIdx.x;
     fetch(min(f, nframes - 1));
-    const int ch = wave & 3, half = wave >> 2;       // wavefronts w and w + 4 share channel w and halve the pixel blocks
+    const int ch = wave & 3, prt = wave >> 2;        // wavefronts w, w + 4, ... share channel w and divide the pixel blocks
     const __bf16 *xq = xp + (ch * 16 + l16) * XPLANE;                // my plane
     for (; f < nframes; f += gridDim.x) {
         __syncthreads();
@@ -329,29 +329,44 @@ __global__ __launch_bounds__(512) void conv1_bf16x3_wgrad_kernel(const uint8_t *
                 }
             }
         };
-        constexpr int MID = (NSTEP + 1) / 2;
-        if (half == 0) steps(std::integral_constant<int, 0>{}, std::integral_constant<int, MID>{});
-        else steps(std::integral_constant<int, MID>{}, std::integral_constant<int, NSTEP>{});
+        static_assert(NPART == 1 || NPART == 2 || NPART == 4, "one, two or four wavefronts per SIMD");
+        constexpr int Q1 = NSTEP / NPART, Q2 = 2 * NSTEP / NPART, Q3 = 3 * NSTEP / NPART;
+        typedef std::integral_constant<int, 0> I0;
+        typedef std::integral_constant<int, NSTEP> IN;
+        if (NPART == 1) steps(I0{}, IN{});
+        else if (NPART == 2) {
+            if (prt == 0) steps(I0{}, std::integral_constant<int, Q1>{});
+            else steps(std::integral_constant<int, Q1>{}, IN{});
+        } else {
+            if (prt == 0) steps(I0{}, std::integral_constant<int, Q1>{});
+            else if (prt == 1) steps(std::integral_constant<int, Q1>{}, std::integral_constant<int, Q2>{});
+            else if (prt == 2) steps(std::integral_constant<int, Q2>{}, std::integral_constant<int, Q3>{});
+            else steps(std::integral_constant<int, Q3>{}, IN{});
+        }
     }
-    // the two halves of a channel's pixel blocks are added through LDS (dY planes are no longer needed)
-    __syncthreads();
-    float *xch = (float *)dp;
-    if (half == 1) {
+    if (NPART > 1) {   // the parts of a channel's pixel blocks are added through LDS (the frame planes are no longer needed)
+        __syncthreads();
+        float *xch = (float *)xp;
+        if (prt > 0) {
 #pragma unroll
-        for (int a = 0; a < 2; ++a)
+            for (int a = 0; a < 2; ++a)
 #pragma unroll
-            for (int b = 0; b < 2; ++b)
+                for (int b = 0; b < 2; ++b)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) xch[((ch * 16 + (a * 2 + b) * 4 + r) * 64) + lane] = acc[a][b][r];
+                    for (int r = 0; r < 4; ++r)
+                        xch[(((prt - 1) * 4 + ch) * 16 + (a * 2 + b) * 4 + r) * 64 + lane] = acc[a][b][r];
+        }
+        __syncthreads();
+        if (prt > 0) return;
+#pragma unroll
+        for (int q = 0; q < NPART - 1; ++q)
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int b = 0; b < 2; ++b)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) acc[a][b][r] += xch[((q * 4 + ch) * 16 + (a * 2 + b) * 4 + r) * 64 + lane];
     }
-    __syncthreads();
-    if (half == 1) return;
-#pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) acc[a][b][r] += xch[((ch * 16 + (a * 2 + b) * 4 + r) * 64) + lane];
     // lane (l16, g), register r of acc[a][b]: filter 4g + r, tap (c = wave, u = 4a + l16/4, v = 4b + l16%4)
     float *pb = part + ((size_t)blockIdx.x * OCT + oc0) * (K + 1);
 #pragma unroll
@@ -366,12 +381,12 @@ __global__ __launch_bounds__(512) void conv1_bf16x3_wgrad_kernel(const uint8_t *
 
 inline int conv1_bf16x3_wgrad_blocks(int nframes) { return nframes < 256 ? nframes : 256; }
 
-template <int OCT = 16>
+template <int OCT = 16, int NPART = 4>
 inline hipError_t launch_conv1_bf16x3_wgrad(const uint8_t *x, const float *dy, float *part, int nframes, float scale,
                                             hipStream_t s, int rb = 0) {
     if (nframes <= 0) return hipSuccess;
-    hipLaunchKernelGGL(conv1_bf16x3_wgrad_kernel<OCT>, dim3(conv1_bf16x3_wgrad_blocks(nframes), OCT / 16), dim3(512), 0, s, x,
-                       dy, part, nframes, scale, rb);
+    hipLaunchKernelGGL((conv1_bf16x3_wgrad_kernel<OCT, NPART>), dim3(conv1_bf16x3_wgrad_blocks(nframes), OCT / 16),
+                       dim3(256 * NPART), 0, s, x, dy, part, nframes, scale, rb);
     return hipGetLastError();
 }
 
