@@ -236,23 +236,24 @@ inline hipError_t launch_conv_fwd_frame(const typename SP::TIn *x, const float *
 // part: [gridDim.x][OC][K+1], the last column is the bias gradient.
 // KSL > 1 cuts the filter taps into KSL slices (blockIdx.y) where one block's
 // accumulators for all of them would not fit the register file.
-template <class SP, int KSL = 1>
-__global__ __launch_bounds__(256, 2) void conv_wgrad_frame_kernel(const typename SP::TIn *__restrict__ x,
+template <class SP, int KSL = 1, int NW = 4>
+__global__ __launch_bounds__(64 * NW, 2) void conv_wgrad_frame_kernel(const typename SP::TIn *__restrict__ x,
                                                                   const float *__restrict__ dy,
                                                                   float *__restrict__ part, int nframes, float scale,
                                                                   int rb) {
     // rb: dY and (float) frames are rounded to bfloat16 on their way to LDS; the bias sums take the rounded dY
     typedef typename SP::TIn TIn;
     constexpr int FRAME_BYTES = SP::CHW * (int)sizeof(TIn);
-    constexpr int NV = FRAME_BYTES / 16, VPT = (NV + 255) / 256;
+    constexpr int NTHR = 64 * NW;                                // NW wavefronts share the tap tiles
+    constexpr int NV = FRAME_BYTES / 16, VPT = (NV + NTHR - 1) / NTHR;
     constexpr int NS = (SP::NPIX + 3) / 4;                       // contraction steps per frame
     constexpr int DPITCH = ((4 * NS + 31) / 32) * 32 + 4;        // row pitch of dY in LDS: 4 mod 32 banks
-    constexpr int NDY = SP::OC * SP::NPIX, DPT = (NDY + 255) / 256;
-    constexpr int KT = SP::K / 16, KTW = KT / (4 * KSL);         // tap tiles in all / per wave
-    static_assert(KT % (4 * KSL) == 0, "tap tiles must split evenly over the slices and 4 waves");
+    constexpr int NDY = SP::OC * SP::NPIX, DPT = (NDY + NTHR - 1) / NTHR;
+    constexpr int KT = SP::K / 16, KTW = KT / (NW * KSL);        // tap tiles in all / per wave
+    static_assert(KT % (NW * KSL) == 0, "tap tiles must split evenly over the slices and waves");
     static_assert(256 % SP::OC == 0, "bias sums use 256/OC threads per filter");
     constexpr int TPO = 256 / SP::OC;                            // threads per filter in the bias sum
-    __shared__ __attribute__((aligned(16))) unsigned char xs_raw[VPT * 256 * 16];
+    __shared__ __attribute__((aligned(16))) unsigned char xs_raw[VPT * NTHR * 16];
     __shared__ __attribute__((aligned(16))) float ds[SP::OC * DPITCH];
     const TIn *xs = (const TIn *)xs_raw;
 
@@ -260,11 +261,11 @@ __global__ __launch_bounds__(256, 2) void conv_wgrad_frame_kernel(const typename
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l16 = lane & 15, g = lane >> 4;
 
-    for (int e = tid; e < SP::OC * DPITCH; e += 256) ds[e] = 0.f;   // the padding stays zero
+    for (int e = tid; e < SP::OC * DPITCH; e += NTHR) ds[e] = 0.f;   // the padding stays zero
 
     int tapoff[KTW];                                             // my tap in each of my tiles
 #pragma unroll
-    for (int t = 0; t < KTW; ++t) tapoff[t] = SP::koff(16 * ((blockIdx.y * 4 + wave) * KTW + t) + l16);
+    for (int t = 0; t < KTW; ++t) tapoff[t] = SP::koff(16 * ((blockIdx.y * NW + wave) * KTW + t) + l16);
     // pixel 4s+g of a frame -> offset of its window
     int pixoff[SP::OW % 4 == 0 ? 1 : NS];
     if (SP::OW % 4 != 0) {
@@ -277,11 +278,11 @@ __global__ __launch_bounds__(256, 2) void conv_wgrad_frame_kernel(const typename
     }
     int vidx[VPT];
 #pragma unroll
-    for (int i = 0; i < VPT; ++i) vidx[i] = min(tid + 256 * i, NV - 1);
+    for (int i = 0; i < VPT; ++i) vidx[i] = min(tid + NTHR * i, NV - 1);
     int didx[DPT], dlds[DPT];
 #pragma unroll
     for (int i = 0; i < DPT; ++i) {
-        const int e = min(tid + 256 * i, NDY - 1);
+        const int e = min(tid + NTHR * i, NDY - 1);
         didx[i] = e;
         dlds[i] = (e / SP::NPIX) * DPITCH + e % SP::NPIX;
     }
@@ -308,7 +309,7 @@ __global__ __launch_bounds__(256, 2) void conv_wgrad_frame_kernel(const typename
     for (; f < nframes; f += gridDim.x) {
         __syncthreads();
 #pragma unroll
-        for (int i = 0; i < VPT; ++i) ((u32x4 *)xs_raw)[tid + 256 * i] = stage_round<TIn>(pre[i], rb);
+        for (int i = 0; i < VPT; ++i) ((u32x4 *)xs_raw)[tid + NTHR * i] = stage_round<TIn>(pre[i], rb);
 #pragma unroll
         for (int i = 0; i < DPT; ++i) ds[dlds[i]] = rb ? bf16_rne(dpre[i]) : dpre[i];
         __syncthreads();
@@ -321,7 +322,7 @@ __global__ __launch_bounds__(256, 2) void conv_wgrad_frame_kernel(const typename
 #pragma unroll
             for (int i = 0; i < DPT; ++i) dpre[i] = dsrc[didx[i]];
         }
-        {   // bias: TPO threads share a filter row, combined in lane order
+        if (tid < 256) {   // bias: TPO threads share a filter row, combined in lane order
             const int oc = tid / TPO, part_id = tid % TPO;
             float sum = 0.f;
             for (int pp = part_id; pp < SP::NPIX; pp += TPO) sum += ds[oc * DPITCH + pp];
@@ -349,7 +350,7 @@ __global__ __launch_bounds__(256, 2) void conv_wgrad_frame_kernel(const typename
             }
         }
     }
-    // lane (l16, g) register r of tile (o, t): filter o*16 + 4g + r, tap 16*((slice*4+wave)*KTW+t) + l16
+    // lane (l16, g) register r of tile (o, t): filter o*16 + 4g + r, tap 16*((slice*NW+wave)*KTW+t) + l16
     float *pb = part + (size_t)blockIdx.x * SP::OC * (SP::K + 1);
 #pragma unroll
     for (int o = 0; o < SP::OT; ++o)
@@ -357,8 +358,8 @@ __global__ __launch_bounds__(256, 2) void conv_wgrad_frame_kernel(const typename
         for (int t = 0; t < KTW; ++t)
 #pragma unroll
             for (int r = 0; r < 4; ++r)
-                pb[(o * 16 + 4 * g + r) * (SP::K + 1) + 16 * ((blockIdx.y * 4 + wave) * KTW + t) + l16] = acc[o][t][r] * scale;
-    if (blockIdx.y == 0 && tid % TPO == 0) pb[(tid / TPO) * (SP::K + 1) + SP::K] = bsum;
+                pb[(o * 16 + 4 * g + r) * (SP::K + 1) + 16 * ((blockIdx.y * NW + wave) * KTW + t) + l16] = acc[o][t][r] * scale;
+    if (blockIdx.y == 0 && tid < 256 && tid % TPO == 0) pb[(tid / TPO) * (SP::K + 1) + SP::K] = bsum;
 }
 
 // One partial dW per block: fewer blocks where a partial is large.
@@ -368,12 +369,12 @@ inline int conv_wgrad_frame_blocks(int nframes) {
     return nframes < LIMIT ? nframes : LIMIT;
 }
 
-template <class SP, int KSL = 1>
+template <class SP, int KSL = 1, int NW = 4>
 inline hipError_t launch_conv_wgrad_frame(const typename SP::TIn *x, const float *dy, float *part, int nframes,
                                           float scale, hipStream_t s, int rb = 0) {
     if (nframes <= 0) return hipSuccess;
-    hipLaunchKernelGGL((conv_wgrad_frame_kernel<SP, KSL>), dim3(conv_wgrad_frame_blocks<SP>(nframes), KSL), dim3(256), 0, s, x,
-                       dy, part, nframes, scale, rb);
+    hipLaunchKernelGGL((conv_wgrad_frame_kernel<SP, KSL, NW>), dim3(conv_wgrad_frame_blocks<SP>(nframes), KSL), dim3(64 * NW), 0,
+                       s, x, dy, part, nframes, scale, rb);
     return hipGetLastError();
 }
 

@@ -1546,9 +1546,9 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
             } else if (kind == 2) {
                 HIP_TRY(launch_conv1_bf16x3_wgrad<32>((const uint8_t *)xin, c->dact[l], part, B, 1.f / 255.f, s, c->rb));
             } else if (kind == 3) {
-                HIP_TRY(launch_conv_wgrad_frame<SpecS2>((const float *)xin, c->dact[l], part, B, 1.f, s, c->rb));
+                HIP_TRY((launch_conv_wgrad_frame<SpecS2, 1, 8>)((const float *)xin, c->dact[l], part, B, 1.f, s, c->rb));
             } else if (kind == 4) {
-                HIP_TRY((launch_conv_wgrad_frame<SpecL2, 4>)((const float *)xin, c->dact[l], part, B, 1.f, s, c->rb));
+                HIP_TRY((launch_conv_wgrad_frame<SpecL2, 4, 8>)((const float *)xin, c->dact[l], part, B, 1.f, s, c->rb));
             } else if (kind == 5) {
                 HIP_TRY((launch_conv_wgrad_frame<SpecL3, 3>)((const float *)xin, c->dact[l], part, B, 1.f, s, c->rb));
             } else if (l == 0) {
