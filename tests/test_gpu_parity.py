@@ -347,6 +347,54 @@ def test_train_eps_variant(G):
     run_train(G, G.SMALL_NET(6), 4, 5, 701, dict(log_eps=1e-6))
 
 
+def test_eps_variant_silences_a_near_zero_probability_sample(G):
+    # Eq. 5 discussion: with pi(a) ~ 0 the factor d log(pi + eps) / d pi = 1 / (pi + eps) is bounded, and the
+    # policy-gradient term of such a sample, (pi / (pi + eps)) * advantage, vanishes; with eps = 0 it is a full
+    # -advantage on the logit of the action taken.  Policy bias of action 0 pushed to -60, every sample took action 0.
+    import torch
+    from paper_1611_06256_amd.binding import stats_from_tensor
+    N, T, A = 6, 5, 6
+    desc = G.SMALL_NET(A)
+    norms = {}
+    for eps in (0.0, 1e-2):
+        net, onet, theta = make(G, desc, N * T, N * T, 7300)
+        ob, _ = net.offsets()["policy.b"]
+        theta = theta.copy(); theta[ob] = -60.0
+        net.params_set(torch.from_numpy(theta).cuda(), 0)
+        frames = synth.rectangle_frames(7301, N * T).reshape(N, T, 4, 84, 84)
+        tr = synth.trajectories(7302, N, T, A)
+        acts = np.zeros_like(tr["actions"])
+        boot = np.zeros(N, np.float32)
+        kw = dict(beta=0.0, value_coef=0.0, log_eps=eps)
+        stats_t = torch.zeros(8, device="cuda")
+        print(f"train eps={eps} with pi(a) ~ e^-60", flush=True)
+        net.train_step(torch.from_numpy(frames).cuda(), torch.from_numpy(acts).cuda(), torch.from_numpy(tr["rewards"]).cuda(),
+                       torch.from_numpy(tr["dones"]).cuda(), torch.from_numpy(boot).cuda(), G.HParams(**kw), stats=stats_t)
+        torch.cuda.synchronize()
+        ref = orc.train_step(onet, theta.astype(np.float64), np.zeros(net.n_params), frames, acts, tr["rewards"], tr["dones"],
+                             boot.astype(np.float64), orc.HParams(**kw))
+        grad = net.params_get(2).cpu().numpy()
+        st = stats_from_tensor(stats_t)
+        assert st["nonfinite"] == 0 and np.isfinite(st["policy_loss"])
+        scale = max(np.abs(ref["grad"]).max(), 1e-30)
+        if eps == 0.0:
+            assert np.abs(grad - ref["grad"]).max() <= TOL_BWD * scale
+        else:
+            assert np.abs(grad).max() < 1e-20 and np.abs(ref["grad"]).max() < 1e-20
+        norms[eps] = float(np.linalg.norm(grad))
+        net.close()
+    assert norms[0.0] > 1e-2 and norms[1e-2] < 1e-20 * norms[0.0] + 1e-20
+
+
+def test_predict_and_train_paper_family_net_stride3(G):
+    # one member of the paper's larger-network family (Sec. 5, footnote on network sizes): 32 filters of 8x8 in the
+    # first layer with stride 3, a third convolution of 64 filters of 4x4 with stride 2; VALID arithmetic gives
+    # 84 -> 26 -> 12 -> 5.  No shape-specific kernel exists for it: it runs on the any-shape kernels.
+    desc = G.NetDesc(in_c=4, in_h=84, in_w=84, conv=((32, 8, 3), (32, 4, 2), (64, 4, 2)), fc_units=256, n_actions=6)
+    check_predict(G, desc, 5, 7400, frames=synth.rectangle_frames(7401, 5))
+    run_train(G, desc, 2, 3, 7410, dict(clip_norm=40.0), frames=synth.rectangle_frames(7411, 6).reshape(2, 3, 4, 84, 84))
+
+
 def test_train_large_net(G):
     run_train(G, G.LARGE_NET(18), 5, 5, synth.BASE_SEED + 3, dict(clip_norm=40.0))
 
