@@ -27,6 +27,7 @@
 #include <stdint.h>
 
 #include "conv1_bf16x3.hpp"
+#include "dense_gemm_bf16x6.hpp"
 
 namespace ga3c {
 
@@ -109,7 +110,9 @@ inline hipError_t launch_conv12_filter_fragments(const float *w1, const float *w
 // ONE: the reduced-precision variant (operands rounded to bfloat16): only the first
 // term of every operand exists, so one MFMA per tap block replaces three / six and
 // only the first plane of the layer-1 output is written and read.
-template <bool ONE>
+// KEEP: the layer-1 output is also written to y1 (a template parameter rather than a test of the pointer, so that
+// the stores do not cut the epilogue into a basic block each).
+template <bool ONE, bool KEEP>
 __global__ __launch_bounds__(512, 1) void conv12_fused_fwd_kernel(const uint8_t *__restrict__ x,
                                                                   const u32x4 *__restrict__ frag,
                                                                   const float *__restrict__ b1,
@@ -189,7 +192,7 @@ __global__ __launch_bounds__(512, 1) void conv12_fused_fwd_kernel(const uint8_t 
                     for (int i = 0; i < VPT; ++i) pre[i] = src[vidx[i]];
                 }
                 __bf16 *yp = ys + (it & 1) * 3 * C12_Y1;
-                float *yb = y1 ? y1 + (size_t)f * 16 * NPIX1 : nullptr;
+                float *yb = KEEP ? y1 + (size_t)f * 16 * NPIX1 : nullptr;
                 // pixel tiles rw, rw + 4, ...: 25 tiles, wavefront 0 takes seven, the others six.
                 // Six independent accumulators: consecutive MFMAs never depend on each other.
                 auto tile_base = [&](int t) {
@@ -207,16 +210,28 @@ __global__ __launch_bounds__(512, 1) void conv12_fused_fwd_kernel(const uint8_t 
                     const int p = t * 16 + l16;
                     const int row = p / OW1, col = p % OW1;
                     const int blk = (row >> 1) * 40 + (col >> 1) * 4 + (row & 1) * 2 + (col & 1);
+                    float v[4];
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
-                        float v = acc[r] * scale + bv[r];
-                        v = v > 0.f ? v : 0.f;
-                        if (yb) yb[(4 * g + r) * NPIX1 + p] = v;
-                        __bf16 h, m, l;
-                        split3(v, h, m, l, rb);
-                        const int e = (4 * g + r) * HW2 + blk;
-                        yp[e] = h;
-                        if (!ONE) { yp[C12_Y1 + e] = m; yp[2 * C12_Y1 + e] = l; }
+                        v[r] = acc[r] * scale + bv[r];
+                        v[r] = v[r] > 0.f ? v[r] : 0.f;
+                        if (KEEP) yb[(4 * g + r) * NPIX1 + p] = v[r];
+                    }
+                    // split two values per conversion instruction (v = hi + mid + lo exactly; ONE: v rounded)
+#pragma unroll
+                    for (int q = 0; q < 2; ++q) {
+                        const float a = v[2 * q], b = v[2 * q + 1];
+                        union { uint32_t u; __bf16 h[2]; } hi, mid, lo;
+                        hi.u = pack_bf16_rne(a, b);
+                        const int e0 = (4 * g + 2 * q) * HW2 + blk, e1 = e0 + HW2;
+                        yp[e0] = hi.h[0]; yp[e1] = hi.h[1];
+                        if (!ONE) {
+                            const float ra = a - __uint_as_float(hi.u << 16), rb2 = b - __uint_as_float(hi.u & 0xffff0000u);
+                            mid.u = pack_bf16_rne(ra, rb2);
+                            lo.u = pack_bf16_rne(ra - __uint_as_float(mid.u << 16), rb2 - __uint_as_float(mid.u & 0xffff0000u));
+                            yp[C12_Y1 + e0] = mid.h[0]; yp[C12_Y1 + e1] = mid.h[1];
+                            yp[2 * C12_Y1 + e0] = lo.h[0]; yp[2 * C12_Y1 + e1] = lo.h[1];
+                        }
                     }
                 };
                 {
@@ -326,17 +341,21 @@ inline hipError_t launch_conv12_fused_fwd(const uint8_t *x, const u32x4 *frag, c
     if (nframes <= 0) return hipSuccess;
     static bool attr_set = false;     // the kernels need more LDS than the default limit
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)conv12_fused_fwd_kernel<false>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)C12_LDS_BYTES);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute((const void *)conv12_fused_fwd_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    (int)C12_LDS_BYTES);
-        if (e != hipSuccess) return e;
+        const void *ks[4] = {(const void *)conv12_fused_fwd_kernel<false, false>, (const void *)conv12_fused_fwd_kernel<false, true>,
+                             (const void *)conv12_fused_fwd_kernel<true, false>, (const void *)conv12_fused_fwd_kernel<true, true>};
+        for (const void *k : ks) {
+            const hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C12_LDS_BYTES);
+            if (e != hipSuccess) return e;
+        }
         attr_set = true;
     }
     const dim3 grid(conv12_fused_blocks(nframes)), block(512);
-    if (rb) hipLaunchKernelGGL(conv12_fused_fwd_kernel<true>, grid, block, C12_LDS_BYTES, s, x, frag, b1, b2, y1, y2, nframes, scale, rb);
-    else hipLaunchKernelGGL(conv12_fused_fwd_kernel<false>, grid, block, C12_LDS_BYTES, s, x, frag, b1, b2, y1, y2, nframes, scale, rb);
+#define GA3C_C12_LAUNCH(ONE_, KEEP_)                                                                                          \
+    hipLaunchKernelGGL((conv12_fused_fwd_kernel<ONE_, KEEP_>), grid, block, C12_LDS_BYTES, s, x, frag, b1, b2, y1, y2, nframes, \
+                       scale, rb)
+    if (rb) { if (y1) GA3C_C12_LAUNCH(true, true); else GA3C_C12_LAUNCH(true, false); }
+    else { if (y1) GA3C_C12_LAUNCH(false, true); else GA3C_C12_LAUNCH(false, false); }
+#undef GA3C_C12_LAUNCH
     return hipGetLastError();
 }
 

@@ -1486,8 +1486,7 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
         if (!p.C) return fail(GA3C_EINVAL, "internal: split-k workspace too small (fc wgrad)");
         {
             STAGE("fc_wgrad", 2.0 * B * F * c->flat, 0);
-            if (c->rb) HIP_TRY((launch_dense_gemm_bf16x6<2, 2, 2, 2, true, true, DG_PARTIAL>(p, DG_SPLIT_Z, s)));
-            else HIP_TRY((launch_dense_gemm<2, 2, 2, 2, true, true, DG_PARTIAL>(p, DG_SPLIT_Z, s)));
+            HIP_TRY((launch_dense_gemm_bf16x6<2, 2, 2, 2, true, true, DG_PARTIAL>(p, DG_SPLIT_Z, s)));
         }
         add_seg(p.C, nz, p.M, p.N, 0, p.M, c->grad + c->off[nb], nullptr, 0);
         add_seg(c->colpart, cdiv(B, HD_FRAMES), 1, F, 0, 1, c->grad + c->off[nb + 1], nullptr, 0);
