@@ -47,6 +47,25 @@ __device__ __forceinline__ void split3(float f, __bf16 &hi, __bf16 &mid, __bf16 
     if (rb) { mid = (__bf16)0.f; lo = (__bf16)0.f; }
 }
 
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+
+// two floats -> two bfloat16 (round to nearest even) in one register, x in the low half
+__device__ __forceinline__ uint32_t pack_bf16_rne(float x, float y) {
+    union { bf16x2_t v; uint32_t u; } c;
+    c.v = __builtin_convertvector(f32x2_t{x, y}, bf16x2_t);
+    return c.u;
+}
+
+// split3 for two values at a time (the same roundings, one conversion instruction per pair and term):
+// x in the low halves of hi, mid, lo and y in the high halves
+__device__ __forceinline__ void split3_pair(float x, float y, uint32_t &hi, uint32_t &mid, uint32_t &lo) {
+    hi = pack_bf16_rne(x, y);
+    const float rx = x - __uint_as_float(hi << 16), ry = y - __uint_as_float(hi & 0xffff0000u);
+    mid = pack_bf16_rne(rx, ry);
+    lo = pack_bf16_rne(rx - __uint_as_float(mid << 16), ry - __uint_as_float(mid & 0xffff0000u));
+}
+
 // 16 bytes -> 16 bf16 (two 16-byte vectors)
 __device__ __forceinline__ void bytes_to_bf16(const u32x4 b, u32x4 &lo8, u32x4 &hi8) {
     Bf16x8Bits o[2];
@@ -286,8 +305,9 @@ __global__ __launch_bounds__(256 * NPART) void conv1_bf16x3_wgrad_kernel(const u
             if (tid + NTHR * i < NDV) {
                 const float v[4] = {dpre[i].x, dpre[i].y, dpre[i].z, dpre[i].w};
                 union { __bf16 h[4]; uint2 u; } o[3];
-#pragma unroll
-                for (int t = 0; t < 4; ++t) split3(v[t], o[0].h[t], o[1].h[t], o[2].h[t], rb);
+                split3_pair(v[0], v[1], o[0].u.x, o[1].u.x, o[2].u.x);
+                split3_pair(v[2], v[3], o[0].u.y, o[1].u.y, o[2].u.y);
+                if (rb) { o[1].u = uint2{0u, 0u}; o[2].u = uint2{0u, 0u}; }
 #pragma unroll
                 for (int term = 0; term < 3; ++term) *(uint2 *)(dp + term * OC * DOC + ddst[i]) = o[term].u;
                 bsh[tid + NTHR * i] = rb ? ((float)o[0].h[0] + (float)o[0].h[1]) + ((float)o[0].h[2] + (float)o[0].h[3])

@@ -127,11 +127,11 @@ __global__ __launch_bounds__(256, 2) void conv_dgrad_bf16x6_kernel(const float *
 #pragma unroll
         for (int i = 0; i < DPT; ++i)
             if (tid + 256 * i < NITEM) {
-                union { __bf16 h[4]; uint2 u; } o[3];
+                uint2 o3[3];
+                split3_pair(dpre[i][0], dpre[i][1], o3[0].x, o3[1].x, o3[2].x);
+                split3_pair(dpre[i][2], dpre[i][3], o3[0].y, o3[1].y, o3[2].y);
 #pragma unroll
-                for (int j = 0; j < 4; ++j) split3(dpre[i][j], o[0].h[j], o[1].h[j], o[2].h[j]);
-#pragma unroll
-                for (int x = 0; x < NTERM; ++x) *(uint2 *)(dp + x * PLANE + dlds[i]) = o[x].u;
+                for (int x = 0; x < NTERM; ++x) *(uint2 *)(dp + x * PLANE + dlds[i]) = o3[x];
             }
         __syncthreads();
         fetch_dy(min(f + (int)gridDim.x, nframes - 1));

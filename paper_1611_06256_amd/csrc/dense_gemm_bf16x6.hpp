@@ -19,26 +19,13 @@
 
 namespace ga3c {
 
-typedef float f32x2_t __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-
-// two floats -> two bfloat16 (round to nearest even) in one register, x in the low half
-__device__ __forceinline__ uint32_t pack_bf16_rne(float x, float y) {
-    union { bf16x2_t v; uint32_t u; } c;
-    c.v = __builtin_convertvector(f32x2_t{x, y}, bf16x2_t);
-    return c.u;
-}
-
 // 8 floats -> three bf16x8 vectors (hi, mid, lo) with f = hi + mid + lo exactly, two values per conversion
 // instruction (the same roundings as split3, 5.5 instead of 7.5 vector instructions per value)
 __device__ __forceinline__ void split3x8(const float (&f)[8], u32x4 &hi, u32x4 &mid, u32x4 &lo, int rb = 0) {
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-        const float x = f[2 * e], y = f[2 * e + 1];
-        const uint32_t h = pack_bf16_rne(x, y);
-        const float rx = x - __uint_as_float(h << 16), ry = y - __uint_as_float(h & 0xffff0000u);
-        const uint32_t m = pack_bf16_rne(rx, ry);
-        const uint32_t l = pack_bf16_rne(rx - __uint_as_float(m << 16), ry - __uint_as_float(m & 0xffff0000u));
+        uint32_t h, m, l;
+        split3_pair(f[2 * e], f[2 * e + 1], h, m, l);
         hi[e] = h; mid[e] = rb ? 0u : m; lo[e] = rb ? 0u : l;
     }
 }
