@@ -43,15 +43,15 @@ PEAK_HBM = 8.0e12           # B/s
 # counters read 0.5000 and 1.0000 of the known bytes, hence the scale factors.  The summary is kept under profiles/.
 FETCH_SCALE, WRITE_SCALE = 2.0, 1.0
 COUNTER_KIB = {   # stage: {frames per launch: (FETCH_SIZE, WRITE_SIZE)}
-    "conv12_fwd": {512: (7554.7, 5184.0), 1024: (14626.7, 10368.0), 2560: (35842.8, 89931.1)},   # 2560: training, keeps y1
+    "conv12_fwd": {512: (7554.7, 5184.0), 1024: (14626.7, 10368.0), 2560: (36536.2, 94053.3)},   # 2560: training, keeps y1
     "fc_fwd": {512: (4153.0, 7168.0), 1024: (6649.0, 8192.0), 2560: (14425.0, 20480.0)},
     "heads_fwd": {512: (3789.0, 592.0), 1024: (4282.0, 1104.0)},
     "heads_train": {2560: (10524.6, 9396.2)},
-    "conv1_wgrad": {2560: (67628.6, 4112.0)},
-    "conv2_wgrad": {2560: (45139.5, 16461.9)},
+    "conv1_wgrad": {2560: (67617.1, 4112.0)},
+    "conv2_wgrad": {2560: (45123.3, 16558.4)},
     "conv2_dgrad": {2560: (45193.5, 64000.0)},
-    "fc_wgrad": {2560: (14299.0, 20736.3)},
-    "fc_dgrad": {2560: (25714.2, 27410.9)},
+    "fc_wgrad": {2560: (15324.3, 20736.0)},
+    "fc_dgrad": {2560: (25372.6, 27011.7)},
     "wgrad_reduce": {2560: (24878.8, 2809.9)},
     "rmsprop": {2560: (4019.6, 5394.1)},
 }
