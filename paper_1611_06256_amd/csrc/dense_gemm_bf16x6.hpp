@@ -38,7 +38,7 @@ __device__ __forceinline__ void split3x8(const float (&f)[8], u32x4 &hi, u32x4 &
 // matrix.  ZERO_TAIL: values at k >= kend are replaced by zeros (needed only
 // in a chunk's last, partial group of 32).  Rows beyond the matrix repeat its
 // last row: they only feed outputs that are never stored.
-template <bool ROWMAJOR, int ROWS, int ITEMS, int NT, bool ZERO_TAIL = true>
+template <bool ROWMAJOR, int ROWS, int ITEMS, int NT, bool ZERO_TAIL = true, bool PTR_STEPS = false>
 __device__ __forceinline__ void fetch_tile(const float *__restrict__ X, long ld, int R0, int R, int K, int k0, int kend,
                                            int tid, float (&r)[ITEMS][8]) {
 #pragma unroll
@@ -58,11 +58,18 @@ __device__ __forceinline__ void fetch_tile(const float *__restrict__ X, long ld,
         } else {
             const int kg = e / ROWS, row = e % ROWS;
             const int m = min(R0 + row, R - 1);
+            if (!ZERO_TAIL && PTR_STEPS) {      // every k is inside the matrix: plain pointer steps, no 64-bit products per
+                                                // load (pays when both operands are read this way, measured)
+                const float *src = X + ((long)(8 * kg) * ld + m) + (long)k0 * ld;
 #pragma unroll
-            for (int h = 0; h < 8; ++h) {
-                const int kk = k0 + 8 * kg + h;
-                const float v = X[(long)min(kk, K - 1) * ld + m];
-                r[it][h] = (!ZERO_TAIL || kk < kend) ? v : 0.f;
+                for (int h = 0; h < 8; ++h) r[it][h] = src[(long)h * ld];
+            } else {
+#pragma unroll
+                for (int h = 0; h < 8; ++h) {
+                    const int kk = k0 + 8 * kg + h;
+                    const float v = X[(long)min(kk, K - 1) * ld + m];
+                    r[it][h] = (!ZERO_TAIL || kk < kend) ? v : 0.f;
+                }
             }
         }
     }
@@ -135,8 +142,9 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void dense_gemm_bf16x6_kernel(const
         stash_tile<B_ROWMAJOR, BN, B_ITEMS, NT, ONE>(Bs, tid, rb, p.rb);
         __syncthreads();
         if (k0 + 2 * BK <= kend) {          // a whole group of 32 comes next: nothing to zero
-            fetch_tile<A_ROWMAJOR, BM, A_ITEMS, NT, false>(p.A, p.lda, m0, p.M, p.K, k0 + BK, kend, tid, ra);
-            fetch_tile<B_ROWMAJOR, BN, B_ITEMS, NT, false>(p.B, p.ldb, n0, p.N, p.K, k0 + BK, kend, tid, rb);
+            constexpr bool PS = A_ROWMAJOR && B_ROWMAJOR;
+            fetch_tile<A_ROWMAJOR, BM, A_ITEMS, NT, false, PS>(p.A, p.lda, m0, p.M, p.K, k0 + BK, kend, tid, ra);
+            fetch_tile<B_ROWMAJOR, BN, B_ITEMS, NT, false, PS>(p.B, p.ldb, n0, p.N, p.K, k0 + BK, kend, tid, rb);
         } else if (k0 + BK < kend) {
             fetch_tile<A_ROWMAJOR, BM, A_ITEMS, NT>(p.A, p.lda, m0, p.M, p.K, k0 + BK, kend, tid, ra);
             fetch_tile<B_ROWMAJOR, BN, B_ITEMS, NT>(p.B, p.ldb, n0, p.N, p.K, k0 + BK, kend, tid, rb);
