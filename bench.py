@@ -50,7 +50,7 @@ COUNTER_KIB = {   # stage: {frames per launch: (FETCH_SIZE, WRITE_SIZE)}
     "conv1_wgrad": {2560: (67617.1, 4112.0)},
     "conv2_wgrad": {2560: (45123.3, 16558.4)},
     "conv2_dgrad": {2560: (45193.5, 64000.0)},
-    "fc_wgrad": {2560: (15324.3, 20736.0)},
+    "fc_wgrad": {2560: (19955.3, 20736.0)},
     "fc_dgrad": {2560: (25372.6, 27011.7)},
     "wgrad_reduce": {2560: (24878.8, 2809.9)},
     "rmsprop": {2560: (4019.6, 5394.1)},
