@@ -253,13 +253,15 @@ __global__ __launch_bounds__(256) void heads_fwd_kernel(const float *__restrict_
     }
     __syncthreads();
     // Dot products from LDS, 16 bytes per read, without cross-lane traffic:
-    // thread (frame, output, third of k) adds its share, three shares make one output.
+    // thread (frame, output, part of k) adds its share; KP shares make one output (three where the block has
+    // threads for them, fewer when there are many actions).
     float *zs = wsh + (A + 1) * WP;                  // [4][A+1][3] partial dots, then [4][A+1] values
-    if (tid < 3 * nout) {
+    const int KP = max(1, min(3, 256 / (4 * (A + 1))));
+    if (tid < KP * nout) {
         const int kp = tid / nout, r = tid % nout;
         const int fb = r / (A + 1), a = r % (A + 1);
         const int nk = F4 / 4;
-        const int klo = (nk * kp) / 3, khi = (nk * (kp + 1)) / 3;
+        const int klo = (nk * kp) / KP, khi = (nk * (kp + 1)) / KP;
         const float4 *hb = (const float4 *)(hs + fb * F4), *wr = (const float4 *)(wsh + a * WP);
         float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
 #pragma unroll 4
@@ -274,7 +276,9 @@ __global__ __launch_bounds__(256) void heads_fwd_kernel(const float *__restrict_
     const bool mine = tid < nout;
     const int b = b0 + ofb;
     if (mine) {
-        z = (zs[tid * 3] + zs[tid * 3 + 1]) + zs[tid * 3 + 2] + obias;
+        z = zs[tid * 3];
+        for (int kp = 1; kp < KP; ++kp) z += zs[tid * 3 + kp];
+        z += obias;
         if (zv) zv[(size_t)b * (A + 1) + oa] = z;
         if (oa < A && logits) logits[(size_t)b * A + oa] = z;
         if (oa == A && values) values[b] = z;

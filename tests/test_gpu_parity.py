@@ -395,6 +395,14 @@ def test_predict_and_train_paper_family_net_stride3(G):
     run_train(G, desc, 2, 3, 7410, dict(clip_norm=40.0), frames=synth.rectangle_frames(7411, 6).reshape(2, 3, 4, 84, 84))
 
 
+def test_predict_and_train_forty_actions(G):
+    # more than 31 actions: the heads, the loss and the heads' backward pass run as separate kernels in training
+    # (the fused kernel gives a thread to every (frame, output) pair of 8 frames)
+    desc = G.SMALL_NET(40)
+    check_predict(G, desc, 9, 7500, frames=synth.rectangle_frames(7501, 9))
+    run_train(G, desc, 5, 5, 7510, dict(clip_norm=40.0), frames=synth.rectangle_frames(7511, 25).reshape(5, 5, 4, 84, 84))
+
+
 def test_train_large_net(G):
     run_train(G, G.LARGE_NET(18), 5, 5, synth.BASE_SEED + 3, dict(clip_norm=40.0))
 
