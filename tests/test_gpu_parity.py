@@ -403,6 +403,51 @@ def test_predict_and_train_forty_actions(G):
     run_train(G, desc, 5, 5, 7510, dict(clip_norm=40.0), frames=synth.rectangle_frames(7511, 25).reshape(5, 5, 4, 84, 84))
 
 
+@pytest.mark.parametrize("A,F", [(1, 5), (2, 8), (21, 12), (31, 16), (32, 16), (63, 64)])
+def test_action_count_edges(G, A, F):
+    # one action (softmax of a single logit), the counts around which the head kernels change their thread layout
+    # (20/21 in predictions, 31/32 in training) and the largest count the interface takes
+    shape = dict(TINY, fc_units=F, n_actions=A)
+    check_predict(G, G.NetDesc(**shape), 11, 7600 + A)
+    if A > 1:
+        run_train(G, G.NetDesc(**shape), 7, 3, 7700 + A, dict(beta=0.05, value_coef=0.5, gamma=0.9), g0_scale=1e-2)
+        return
+    # one action: pi = 1, so the policy and entropy terms and their gradients are exactly zero in exact arithmetic
+    # (relative errors against a zero reference mean nothing); the value path must still match
+    import torch
+    N, T = 7, 3
+    desc = G.NetDesc(**shape)
+    net, onet, theta = make(G, desc, N, N * T, 7700)
+    frames = synth.uniform_frames(7701, (N, T, desc.in_c, desc.in_h, desc.in_w))
+    tr = synth.trajectories(7702, N, T, A)
+    boot = synth.rng(7703).standard_normal(N).astype(np.float32)
+    kw = dict(beta=0.05, value_coef=0.5, gamma=0.9)
+    print("train with a single action", flush=True)
+    net.train_step(torch.from_numpy(frames).cuda(), torch.from_numpy(tr["actions"]).cuda(), torch.from_numpy(tr["rewards"]).cuda(),
+                   torch.from_numpy(tr["dones"]).cuda(), torch.from_numpy(boot).cuda(), G.HParams(**kw))
+    torch.cuda.synchronize()
+    ref = orc.train_step(onet, theta.astype(np.float64), np.zeros(net.n_params), frames, tr["actions"], tr["rewards"],
+                         tr["dones"], boot.astype(np.float64), orc.HParams(**kw))
+    grad = net.params_get(2).cpu().numpy()
+    scale = np.abs(ref["grad"]).max()
+    assert scale > 1e-3
+    assert np.abs(grad - ref["grad"]).max() <= TOL_BWD * scale
+    for name in ("policy.W", "policy.b"):
+        o, shp = net.offsets()[name]
+        assert np.abs(grad[o:o + int(np.prod(shp))]).max() <= 1e-6 * scale
+    assert rel_err(net.params_get(0).cpu().numpy(), ref["theta"]) <= TOL_BWD
+    net.close()
+
+
+def test_small_net_most_actions_that_fit(G):
+    # the heads keep both weight matrices in LDS: (n_actions + 5) * (fc_units + 16) <= 16384 floats
+    desc = G.SMALL_NET(55)
+    check_predict(G, desc, 6, 7800, frames=synth.rectangle_frames(7801, 6))
+    run_train(G, desc, 2, 5, 7810, dict(clip_norm=40.0), frames=synth.rectangle_frames(7811, 10).reshape(2, 5, 4, 84, 84))
+    with pytest.raises(G.Ga3cError):
+        G.Ga3c(G.SMALL_NET(56), 4, 0)
+
+
 def test_train_large_net(G):
     run_train(G, G.LARGE_NET(18), 5, 5, synth.BASE_SEED + 3, dict(clip_norm=40.0))
 
