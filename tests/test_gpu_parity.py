@@ -448,6 +448,13 @@ def test_small_net_most_actions_that_fit(G):
         G.Ga3c(G.SMALL_NET(56), 4, 0)
 
 
+@pytest.mark.parametrize("N,T", [(1, 1), (3, 1), (1, 7), (2, 150)])
+def test_segment_length_edges(G, N, T):
+    # one-step segments, a single agent, and segments so long that the rewards of a block's agents do not fit the
+    # training heads kernel's LDS copy (it then reads them from global memory)
+    run_train(G, G.NetDesc(**TINY), N, T, 7900 + 10 * N + T, dict(beta=0.02, value_coef=0.5, gamma=0.97), g0_scale=1e-2)
+
+
 def test_train_large_net(G):
     run_train(G, G.LARGE_NET(18), 5, 5, synth.BASE_SEED + 3, dict(clip_norm=40.0))
 
