@@ -488,6 +488,21 @@ def test_predict_full_size_sweep_end(G):
     check_predict(G, G.SMALL_NET(18), 1024, synth.BASE_SEED + 1, frames=frames)
 
 
+@pytest.mark.parametrize("B", [255, 257, 513])
+def test_predict_around_one_frame_per_compute_unit(G, B):
+    # the fused convolution kernel gives every compute unit (256) a queue of frames: one short of a full round,
+    # one over, and one over two rounds
+    frames = synth.rectangle_frames_tiled(synth.BASE_SEED + 5, B)
+    check_predict(G, G.SMALL_NET(18), B, synth.BASE_SEED + 5 + B, frames=frames)
+
+
+def test_train_just_over_the_benchmark_size(G):
+    # 513 agents x 5: the last blocks of every kernel carry a ragged tail
+    N, T = 513, 5
+    frames = synth.rectangle_frames_tiled(synth.BASE_SEED + 6, N * T).reshape(N, T, 4, 84, 84)
+    run_train(G, G.SMALL_NET(18), N, T, synth.BASE_SEED + 6, dict(clip_norm=40.0), frames=frames, g0_scale=1e-3)
+
+
 def test_train_full_size_512_agents(G):
     # largest training step of the sweep, in the configuration the benchmark times: 512 agents x 5, clip 40
     N, T = 512, 5
