@@ -538,6 +538,20 @@ def test_bf16_variant_train(G, which, N, T):
     run_train(G, bf16(desc), N, T, 7800 + N, dict(clip_norm=40.0), g0_scale=1e-3, steps=2)
 
 
+@pytest.mark.parametrize("A,F", [(21, 12), (40, 24), (63, 64)])
+def test_bf16_variant_many_actions(G, A, F):
+    shape = dict(TINY, fc_units=F, n_actions=A)
+    check_predict(G, bf16(G.NetDesc(**shape)), 11, 8100 + A)
+    run_train(G, bf16(G.NetDesc(**shape)), 7, 3, 8200 + A, dict(beta=0.05, value_coef=0.5, gamma=0.9), g0_scale=1e-2)
+
+
+def test_bf16_variant_full_size_step(G):
+    # the benchmark's training step with operands rounded to bfloat16
+    N, T = 512, 5
+    frames = synth.rectangle_frames_tiled(synth.BASE_SEED + 7, N * T).reshape(N, T, 4, 84, 84)
+    run_train(G, bf16(G.SMALL_NET(18)), N, T, synth.BASE_SEED + 7, dict(clip_norm=40.0), frames=frames, g0_scale=1e-3)
+
+
 def test_bf16_variant_differs_from_fp32(G):
     # the switch does something: the same parameters and frames give visibly different logits
     import torch
