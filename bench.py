@@ -261,10 +261,13 @@ def main() -> int:
     net.close()
     net = None
     if args.mixed_seconds > 0:
-        # 256 synthetic agents through the two-stream scheduler (bench_mixed.py): fixed caps, then adaptive caps
+        # synthetic agents through the two-stream scheduler (bench_mixed.py): 256 agents with fixed caps, then adaptive caps
         from bench_mixed import run_mixed
         out["mixed_load"] = [run_mixed(args.net, think_us=0.0, seconds=args.mixed_seconds, dynamic=False),
-                             run_mixed(args.net, think_us=0.0, seconds=2 * args.mixed_seconds, dynamic=True)]
+                             run_mixed(args.net, think_us=0.0, seconds=2 * args.mixed_seconds, dynamic=True),
+                             # enough agents to keep several batches in flight: what the whole queue system sustains
+                             run_mixed(args.net, n_agents=2048, think_us=0.0, seconds=args.mixed_seconds, dynamic=False,
+                                       predict_cap=1024, train_cap=2560)]
 
     if not args.no_cpu_baseline:
         import oracle as orc

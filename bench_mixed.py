@@ -26,7 +26,7 @@ if ROOT not in sys.path:
 
 
 def run_mixed(net_kind: str = "small", n_agents: int = 256, think_us: float = 0.0, seconds: float = 1.0,
-              dynamic: bool = True, seed: int = 1615):
+              dynamic: bool = True, seed: int = 1615, predict_cap: int = 256, train_cap: int = 1280):
     import numpy as np
     import torch
 
@@ -35,15 +35,15 @@ def run_mixed(net_kind: str = "small", n_agents: int = 256, think_us: float = 0.
 
     T, A = 5, 18
     desc = g.SMALL_NET(A) if net_kind == "small" else g.LARGE_NET(A)
-    net = g.Ga3c(desc, 256, 1280)
+    net = g.Ga3c(desc, predict_cap, train_cap)
     net.params_init(seed)
     pool = torch.from_numpy(synth.rectangle_frames_tiled(seed, n_agents * T).reshape(n_agents, T, 4, 84, 84)).cuda()
     torch.cuda.synchronize()
     fb = 4 * 84 * 84
     base = pool.data_ptr()
-    sched = g.Scheduler(net, g.HParams(clip_norm=40.0), t_max=T, predict_cap=256 if not dynamic else 32, train_min=40,
-                        train_cap=1280 if not dynamic else 320, adjust_period=1000 if dynamic else 0, predict_cap_lo=1,
-                        predict_cap_hi=256, train_cap_lo=40, train_cap_hi=1280, train_cap_step=40, seed=seed)
+    sched = g.Scheduler(net, g.HParams(clip_norm=40.0), t_max=T, predict_cap=predict_cap if not dynamic else 32, train_min=40,
+                        train_cap=train_cap if not dynamic else 320, adjust_period=1000 if dynamic else 0, predict_cap_lo=1,
+                        predict_cap_hi=predict_cap, train_cap_lo=40, train_cap_hi=train_cap, train_cap_step=40, seed=seed)
     rng = synth.rng(seed + 1)
     step = np.zeros(n_agents, np.int64)
     waiting = np.zeros(n_agents, bool)
@@ -82,7 +82,7 @@ def run_mixed(net_kind: str = "small", n_agents: int = 256, think_us: float = 0.
     sched.drain()
     wall = time.perf_counter() - t0
     st = sched.stats()
-    out = {"think_us": think_us, "dynamic": dynamic, "seconds": round(wall, 3),
+    out = {"agents": n_agents, "think_us": think_us, "dynamic": dynamic, "seconds": round(wall, 3),
            "pps": round(st["predictions"] / wall, 1), "tps_frames": round(st["trained_frames"] / wall, 1),
            "mean_predict_batch": round(st["predictions"] / max(1, st["predict_batches"]), 2),
            "mean_train_batch_frames": round(st["trained_frames"] / max(1, st["train_batches"]), 1),
