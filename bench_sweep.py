@@ -5,7 +5,10 @@
     predictions/s with calls issued back to back, and the latency of a single call
     (median of 200 calls bracketed by HIP events, after 20 warm-up calls);
   * training only, the same net, N = 32, 128, 512 agents x t_max = 5, clip 40: trained frames/s;
-  * the larger net (conv 32@8x8s4, 64@4x4s2, 64@3x3s1, fc 512): predict 256, train 256 x 5.
+  * the larger net (conv 32@8x8s4, 64@4x4s2, 64@3x3s1, fc 512): predict 256, train 256 x 5;
+  * the paper's own larger networks (Sec. 5, "GPU utilization and DNN size": conv 32@8x8 with stride 4, 3, 2 or 1,
+    conv 32@4x4s2, conv 64@4x4s2, fc 256, or 1024 for stride 1): predict 128, train 128 x 5 (128 agents is the
+    paper's fastest setting).
 
 Prints one JSON object.  `bench.py` remains the benchmark of record; this is the
 table behind it.
@@ -105,6 +108,12 @@ def main() -> int:
            "small_net_train": train_rows(g.SMALL_NET(A), [32, 128, 512]),
            "large_net_predict": predict_rows(g.LARGE_NET(A), [256]),
            "large_net_train": train_rows(g.LARGE_NET(A), [256])}
+    family = []
+    for stride in (4, 3, 2, 1):
+        desc = g.NetDesc(in_c=4, in_h=84, in_w=84, conv=((32, 8, stride), (32, 4, 2), (64, 4, 2)),
+                         fc_units=1024 if stride == 1 else 256, n_actions=A)
+        family.append({"conv1_stride": stride, "predict": predict_rows(desc, [128])[0], "train": train_rows(desc, [128])[0]})
+    out["paper_family"] = family
     print(json.dumps(out))
     return 0
 

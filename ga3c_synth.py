@@ -71,6 +71,25 @@ def trajectories(seed: int, n_agents: int, t_max: int, n_actions: int) -> Dict[s
     return {"actions": actions, "rewards": rewards, "dones": dones}
 
 
+def ragged_segments(seed: int, n_segments: int, t_max: int, n_actions: int, p_short: float = 0.3) -> Dict[str, np.ndarray]:
+    """Segments as the agents of Sec. 4.1 hand them in: t_max experiences, or fewer when the episode ended (then the
+    last step is terminal).  A fraction p_short of the segments is short, with a length uniform in [1, t_max).
+    Returns flat arrays over all frames plus seg_start [n_segments + 1] (int32) and the lengths."""
+    g = rng(seed)
+    short = g.random(n_segments) < p_short
+    lengths = np.where(short & (t_max > 1), g.integers(1, max(t_max, 2), size=n_segments), t_max).astype(np.int32)
+    seg_start = np.zeros(n_segments + 1, dtype=np.int32)
+    np.cumsum(lengths, out=seg_start[1:])
+    F = int(seg_start[-1])
+    actions = g.integers(0, n_actions, size=F, dtype=np.int32)
+    u = g.random(F)
+    rewards = np.where(u < 0.05, -1.0, np.where(u >= 0.95, 1.0, 0.0)).astype(np.float32)
+    dones = np.zeros(F, dtype=np.uint8)
+    ends = seg_start[1:][lengths < t_max] - 1
+    dones[ends] = 1
+    return {"actions": actions, "rewards": rewards, "dones": dones, "seg_start": seg_start, "lengths": lengths}
+
+
 def uniforms(seed: int, n: int) -> np.ndarray:
     """float32 uniforms in [0,1) handed to the sampler of both sides."""
     return rng(seed).random(n, dtype=np.float32)

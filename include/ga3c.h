@@ -58,7 +58,7 @@ typedef struct ga3c_ctx ga3c_ctx;   /* opaque: parameters, RMSProp state, gradie
  * stride 4, conv 32 filters 4x4 stride 2, fully connected 256, a rectifier
  * after each hidden layer, a softmax policy output and a linear value
  * output.  Convolutions are VALID cross-correlations.  Limits: n_conv in
- * [1,4]; n_actions in [1,63]; (n_actions + 5) * (fc_units + 16) <= 16384 (the
+ * [1,4]; n_actions in [1,63]; (n_actions + 5) * (fc_units + 16) <= 40960 (the
  * heads keep their weights in LDS); every spatial size must stay >= 1. */
 typedef struct {
     int in_c, in_h, in_w;                 /* input planes / height / width (4, 84, 84) */

@@ -186,6 +186,20 @@ def returns(rewards, dones, bootstrap, gamma: float) -> np.ndarray:
     return R
 
 
+def returns_ragged(rewards, dones, seg_start, bootstrap, gamma: float) -> np.ndarray:
+    """Returns of segments of unequal length laid end to end: segment n is entries seg_start[n] .. seg_start[n+1]-1."""
+    rewards = _f64(rewards).reshape(-1)
+    dones = np.ascontiguousarray(dones, dtype=np.uint8).reshape(-1)
+    seg = np.ascontiguousarray(seg_start, dtype=np.int32)
+    N = seg.size - 1
+    if N < 0 or (N >= 0 and (seg[0] != 0 or seg[-1] != rewards.size or np.any(np.diff(seg) < 0))):
+        raise ValueError("seg_start must rise from 0 to the number of frames")
+    boot = None if bootstrap is None else _f64(bootstrap)
+    R = np.zeros(rewards.size)
+    lib().orc_returns_ragged(_p(rewards), _p(dones), _p(seg), _p(boot), C.c_int(N), C.c_double(gamma), _p(R))
+    return R
+
+
 def loss_grad(logits, values, actions, R, beta: float, value_coef: float, log_eps: float):
     logits = _f64(logits); values = _f64(values); R = _f64(R).reshape(-1)
     actions = np.ascontiguousarray(actions, dtype=np.int32).reshape(-1)
@@ -254,3 +268,22 @@ def train_step(net: Net, theta, g, frames, actions, rewards, dones, bootstrap, h
     return {"theta": theta, "g": g, "grad": grad, "R": R, "dZ": dZ, "dV": dV,
             "logits": logits, "values": values,
             "stats": {n: getattr(st, n) for n, _ in _Stats._fields_}}
+
+
+def train_step_ragged(net: Net, theta, g, frames, actions, rewards, dones, seg_start, bootstrap, hp: HParams):
+    """One whole update on segments of unequal length (Sec. 4.1): frames u8 [F,C,H,W], actions / rewards / dones [F],
+    seg_start [N+1], bootstrap [N].  The steps of train_step in the same order, each through its own function:
+    forward, returns, loss and head gradients, backward, norm, clip, RMSProp."""
+    theta = _f64(theta); g = _f64(g)
+    frames = np.ascontiguousarray(frames, dtype=np.uint8)
+    actions = np.ascontiguousarray(actions, dtype=np.int32).reshape(-1)
+    fw = forward(net, theta, frames, want_acts=True)
+    logits, values, acts = fw["logits"], fw["values"], fw["acts"]
+    R = returns_ragged(rewards, dones, seg_start, bootstrap, hp.gamma)
+    dZ, dV, sums = loss_grad(logits, values, actions, R, hp.beta, hp.value_coef, hp.log_eps)
+    grad = backward(net, theta, acts, dZ, dV)
+    norm = grad_norm(grad)
+    s = clip_scale(norm, hp.clip_norm)
+    theta2, g2 = rmsprop(theta, g, grad, s, hp.lr, hp.rms_decay, hp.rms_eps)
+    return {"theta": theta2, "g": g2, "grad": grad, "R": R, "dZ": dZ, "dV": dV, "logits": logits, "values": values,
+            "stats": dict(sums, grad_norm=norm, clip_scale=s)}

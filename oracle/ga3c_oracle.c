@@ -260,6 +260,23 @@ void orc_returns(const double *rewards, const uint8_t *dones, const double *boot
     }
 }
 
+/* The same for segments of unequal length laid end to end (Sec. 4.1: an agent
+ * hands in its experiences after t_max actions or when its episode ends, so a
+ * training batch also holds shorter segments).  Segment n is the frames
+ * seg_start[n] .. seg_start[n+1]-1; the return after its last frame is
+ * bootstrap[n]. */
+void orc_returns_ragged(const double *rewards, const uint8_t *dones, const int32_t *seg_start,
+                        const double *bootstrap, int N, double gamma, double *R) {
+    for (int n = 0; n < N; ++n) {
+        double next = bootstrap ? bootstrap[n] : 0.0;
+        for (int i = seg_start[n + 1] - 1; i >= seg_start[n]; --i) {
+            double cont = dones[i] ? 0.0 : 1.0;
+            next = rewards[i] + gamma * cont * next;
+            R[i] = next;
+        }
+    }
+}
+
 /* ---- loss and its gradient w.r.t. the two heads (Eq. 1, 2, 5) ----------- */
 
 /* Minimised quantity per frame:

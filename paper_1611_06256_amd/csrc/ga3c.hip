@@ -981,6 +981,16 @@ inline int conv_like_tiles(int M, int N) {
 
 // LDS the fused training heads kernel may ask for; larger heads fall back to the separate kernels.
 constexpr size_t HEADS_TRAIN_MAX_LDS = 96 * 1024;
+constexpr size_t HEADS_FWD_MAX_LDS = 160 * 1024;      // all of a compute unit's LDS
+
+// A kernel may take more than 64 KB of dynamic LDS only after its limit has
+// been raised; `set` remembers the largest size asked for so far.
+static hipError_t allow_dynamic_lds(const void *kernel, size_t bytes, size_t &set) {
+    if (bytes <= 64 * 1024 || bytes <= set) return hipSuccess;
+    const hipError_t e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess) set = bytes;
+    return e;
+}
 
 // Fixed-geometry kernels exist for the layers of the paper's networks.
 typedef ConvSpec<uint8_t, 4, 84, 84, 16, 8, 4> SpecS1;    // small net, conv1
@@ -1089,8 +1099,11 @@ int forward(ga3c_ctx *c, int which, Work &w, const uint8_t *frames, int B, bool 
     }
     w.fc_ws = fc_ws; w.fc_nz = fc_nz;
     if (!with_heads) return GA3C_OK;          // the caller finishes the fc layer and the heads itself
+    const size_t hf_lds = sizeof(float) * heads_lds_floats(c->F, c->A);
+    static size_t hf_lds_set = 0;
+    HIP_TRY(allow_dynamic_lds((const void *)heads_fwd_kernel, hf_lds, hf_lds_set));
     STAGE("heads_fwd", 2.0 * B * c->F * (c->A + 1), 4.0 * (fc_nz + 1) * B * c->F);
-    hipLaunchKernelGGL(heads_fwd_kernel, dim3(cdiv(B, 4)), dim3(256), sizeof(float) * heads_lds_floats(c->F, c->A), s, fc_ws, fc_nz,
+    hipLaunchKernelGGL(heads_fwd_kernel, dim3(cdiv(B, 4)), dim3(256), hf_lds, s, fc_ws, fc_nz,
                        th + c->off[nb + 1], w.h, B, c->F, c->A, th + c->off[nb + 2],
                        th + c->off[nb + 3], th + c->off[nb + 4], th + c->off[nb + 5],
                        keep_zv ? w.zv : nullptr, logits, values, probs, uniforms, actions, c->rb);
@@ -1142,8 +1155,8 @@ extern "C" int ga3c_create(const ga3c_net_desc *d, int max_predict_batch, int ma
     if (d->in_c < 1 || d->in_h < 1 || d->in_w < 1 || d->fc_units < 1) return fail(GA3C_EINVAL, "ga3c_create: bad sizes");
     if (d->math != 0 && d->math != 1) return fail(GA3C_EINVAL, "ga3c_create: math must be 0 (fp32) or 1 (bfloat16 operands)");
     if (max_predict_batch < 0 || max_train_frames < 0) return fail(GA3C_EINVAL, "ga3c_create: negative capacity");
-    if ((size_t)heads_lds_floats(d->fc_units, d->n_actions) * sizeof(float) > 64 * 1024)
-        return fail(GA3C_EINVAL, "ga3c_create: (n_actions + 5) * (fc_units + 16) must not exceed 16384");
+    if ((size_t)heads_lds_floats(d->fc_units, d->n_actions) * sizeof(float) > HEADS_FWD_MAX_LDS)
+        return fail(GA3C_EINVAL, "ga3c_create: (n_actions + 5) * (fc_units + 16) must not exceed 40960");
 
     ga3c_ctx *c = new (std::nothrow) ga3c_ctx();
     if (!c) return fail(GA3C_ENOMEM, "ga3c_create: host allocation failed");
@@ -1431,15 +1444,14 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
         red_blocks += 8 * g.per_xcd;
         red_bytes += 4.0 * (nz_ + 1) * rows * Ncols;
     };
+    const size_t hd_lds = sizeof(float) * (A + 1) * (F + HD_FRAMES);      // heads_dgrad_kernel's LDS
+    static size_t hd_lds_set = 0;
     if (fused_heads) {
         const int nblk = cdiv(B, HD_FRAMES);
         float *part = region((size_t)nblk * (A + 1) * (F + 1));
         if (!part) return fail(GA3C_EINVAL, "internal: split-k workspace too small (heads)");
-        static size_t lds_set = 0;      // raise the kernel's LDS limit once per size
-        if (ht_lds > 64 * 1024 && ht_lds > lds_set) {
-            HIP_TRY(hipFuncSetAttribute((const void *)heads_train_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)ht_lds));
-            lds_set = ht_lds;
-        }
+        static size_t ht_lds_set = 0;
+        HIP_TRY(allow_dynamic_lds((const void *)heads_train_kernel, ht_lds, ht_lds_set));
         STAGE("heads_train", 6.0 * B * (A + 1) * F, 4.0 * (w.fc_nz + 1) * B * F);
         hipLaunchKernelGGL(heads_train_kernel, dim3(nblk), dim3(256), ht_lds, s, w.fc_ws, w.fc_nz, th + c->off[nb + 1], B, F, A, Wp,
                            th + c->off[nb + 3], Wv, th + c->off[nb + 5], actions, rewards, dones, bootstrap, T, hp->gamma, hp->beta,
@@ -1452,7 +1464,8 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
         float *part = region((size_t)nblk * (A + 1) * (F + 1));
         if (!part) return fail(GA3C_EINVAL, "internal: split-k workspace too small (heads)");
         STAGE("heads_bwd", 4.0 * B * (A + 1) * F, 0);
-        hipLaunchKernelGGL(heads_dgrad_kernel, dim3(nblk), dim3(256), sizeof(float) * (A + 1) * (F + HD_FRAMES), s, c->dzv, w.h, Wp, Wv, B,
+        HIP_TRY(allow_dynamic_lds((const void *)heads_dgrad_kernel, hd_lds, hd_lds_set));
+        hipLaunchKernelGGL(heads_dgrad_kernel, dim3(nblk), dim3(256), hd_lds, s, c->dzv, w.h, Wp, Wv, B,
                            F, A, c->dh, c->colpart, part, c->rb);
         HIP_TRY(hipGetLastError());
         add_seg(part, nblk, A + 1, F + 1, 0, A, c->grad + c->off[nb + 2], c->grad + c->off[nb + 3], 1);
@@ -1473,7 +1486,8 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
         add_seg(p.C, nz, A + 1, F + 1, 0, A, c->grad + c->off[nb + 2], c->grad + c->off[nb + 3], 1);
         add_seg(p.C, nz, A + 1, F + 1, A, 1, c->grad + c->off[nb + 4], c->grad + c->off[nb + 5], 1);
         STAGE("heads_dgrad", 2.0 * B * (A + 1) * F, 0);
-        hipLaunchKernelGGL(heads_dgrad_kernel, dim3(cdiv(B, HD_FRAMES)), dim3(256), sizeof(float) * (A + 1) * (F + HD_FRAMES), s, c->dzv, w.h, Wp, Wv, B,
+        HIP_TRY(allow_dynamic_lds((const void *)heads_dgrad_kernel, hd_lds, hd_lds_set));
+        hipLaunchKernelGGL(heads_dgrad_kernel, dim3(cdiv(B, HD_FRAMES)), dim3(256), hd_lds, s, c->dzv, w.h, Wp, Wv, B,
                            F, A, c->dh, c->colpart, (float *)nullptr, c->rb);
         HIP_TRY(hipGetLastError());
     }

@@ -386,13 +386,22 @@ def test_eps_variant_silences_a_near_zero_probability_sample(G):
     assert norms[0.0] > 1e-2 and norms[1e-2] < 1e-20 * norms[0.0] + 1e-20
 
 
-def test_predict_and_train_paper_family_net_stride3(G):
-    # one member of the paper's larger-network family (Sec. 5, footnote on network sizes): 32 filters of 8x8 in the
-    # first layer with stride 3, a third convolution of 64 filters of 4x4 with stride 2; VALID arithmetic gives
-    # 84 -> 26 -> 12 -> 5.  No shape-specific kernel exists for it: it runs on the any-shape kernels.
-    desc = G.NetDesc(in_c=4, in_h=84, in_w=84, conv=((32, 8, 3), (32, 4, 2), (64, 4, 2)), fc_units=256, n_actions=6)
-    check_predict(G, desc, 5, 7400, frames=synth.rectangle_frames(7401, 5))
-    run_train(G, desc, 2, 3, 7410, dict(clip_norm=40.0), frames=synth.rectangle_frames(7411, 6).reshape(2, 3, 4, 84, 84))
+def paper_family_net(G, stride, n_actions=18):
+    # Sec. 5 (GPU utilization and DNN size), footnote: 32 filters in the first layer, a third convolution of 64
+    # filters of 4x4 with stride 2, first-layer stride 4, 3, 2 or 1; the stride-1 member has a 4 times larger fully
+    # connected layer.  VALID arithmetic gives 84 -> 20/26/39/77 -> 9/12/18/37 -> 3/5/8/17.
+    return G.NetDesc(in_c=4, in_h=84, in_w=84, conv=((32, 8, stride), (32, 4, 2), (64, 4, 2)),
+                     fc_units=1024 if stride == 1 else 256, n_actions=n_actions)
+
+
+@pytest.mark.parametrize("stride,B,N,T", [(4, 5, 2, 3), (3, 5, 2, 3), (2, 4, 2, 2), (1, 3, 1, 2)])
+def test_predict_and_train_paper_family_net(G, stride, B, N, T):
+    # the four members of the paper's larger-network family; no shape-specific kernel exists for their second and
+    # third layers (nor for a first layer of stride 3, 2 or 1): those run on the any-shape kernels
+    desc = paper_family_net(G, stride)
+    check_predict(G, desc, B, 7400 + stride, frames=synth.rectangle_frames(7401 + stride, B))
+    run_train(G, desc, N, T, 7410 + stride, dict(clip_norm=40.0),
+              frames=synth.rectangle_frames(7420 + stride, N * T).reshape(N, T, 4, 84, 84))
 
 
 def test_predict_and_train_forty_actions(G):
@@ -439,13 +448,21 @@ def test_action_count_edges(G, A, F):
     net.close()
 
 
-def test_small_net_most_actions_that_fit(G):
-    # the heads keep both weight matrices in LDS: (n_actions + 5) * (fc_units + 16) <= 16384 floats
-    desc = G.SMALL_NET(55)
+def test_small_net_most_actions(G):
+    # the interface's largest action count on the small network
+    desc = G.SMALL_NET(63)
     check_predict(G, desc, 6, 7800, frames=synth.rectangle_frames(7801, 6))
     run_train(G, desc, 2, 5, 7810, dict(clip_norm=40.0), frames=synth.rectangle_frames(7811, 10).reshape(2, 5, 4, 84, 84))
+
+
+def test_wide_fc_most_actions_that_fit(G):
+    # the heads keep both weight matrices in LDS: (n_actions + 5) * (fc_units + 16) <= 40960 floats, i.e. at most
+    # 34 actions with 1024 hidden units; the three head kernels then take more than 64 KB of LDS each
+    shape = dict(TINY, fc_units=1024)
+    check_predict(G, G.NetDesc(**dict(shape, n_actions=34)), 9, 7820)
+    run_train(G, G.NetDesc(**dict(shape, n_actions=34)), 5, 3, 7830, dict(beta=0.05, value_coef=0.5, gamma=0.9), g0_scale=1e-2)
     with pytest.raises(G.Ga3cError):
-        G.Ga3c(G.SMALL_NET(56), 4, 0)
+        G.Ga3c(G.NetDesc(**dict(shape, n_actions=35)), 4, 0)
 
 
 @pytest.mark.parametrize("N,T", [(1, 1), (3, 1), (1, 7), (2, 150)])

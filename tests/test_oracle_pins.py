@@ -230,6 +230,78 @@ def test_returns_direct_sum_with_terminals():
             assert abs(R[n, t] - acc) < 1e-13
 
 
+def test_ragged_returns_against_padded_rectangles_and_direct_sums():
+    # Sec. 4.1: a segment is shorter than t_max when the episode ended.  (a) Equal lengths: the rectangular routine.
+    # (b) A segment of length L with bootstrap b is the first L steps of a rectangle of length T > L whose step L
+    # pays the reward b and is terminal.  (c) The defining sum, by brute force.  (d) No value crosses a boundary.
+    gam = 0.97
+    g = synth.rng(51)
+    N, T = 9, 5
+    r = g.standard_normal((N, T)); d = (g.random((N, T)) < 0.2).astype(np.uint8); boot = g.standard_normal(N)
+    np.testing.assert_allclose(orc.returns_ragged(r.reshape(-1), d.reshape(-1), np.arange(N + 1) * T, boot, gam),
+                               orc.returns(r, d, boot, gam).reshape(-1), rtol=0, atol=0)
+    seg = synth.ragged_segments(52, 40, 6, 4, p_short=0.6)
+    lens, start = seg["lengths"], seg["seg_start"]
+    assert lens.min() >= 1 and lens.max() == 6 and (lens < 6).sum() >= 10
+    F = int(start[-1])
+    rew = synth.rng(53).standard_normal(F); dn = (synth.rng(54).random(F) < 0.15).astype(np.uint8)
+    boot = synth.rng(55).standard_normal(40)
+    R = orc.returns_ragged(rew, dn, start, boot, gam)
+    Tpad = 7
+    rp = np.zeros((40, Tpad)); dp = np.zeros((40, Tpad), np.uint8)
+    for n in range(40):
+        L = lens[n]
+        rp[n, :L] = rew[start[n]:start[n + 1]]; dp[n, :L] = dn[start[n]:start[n + 1]]
+        rp[n, L] = boot[n]; dp[n, L] = 1
+    Rp = orc.returns(rp, dp, synth.rng(56).standard_normal(40), gam)      # the rectangle's own bootstrap must not matter
+    for n in range(40):
+        np.testing.assert_allclose(R[start[n]:start[n + 1]], Rp[n, :lens[n]], rtol=1e-14, atol=1e-14)
+        for i in range(start[n], start[n + 1]):
+            acc, disc, ended = 0.0, 1.0, False
+            for j in range(i, start[n + 1]):
+                acc += disc * rew[j]; disc *= gam
+                if dn[j]:
+                    ended = True
+                    break
+            if not ended:
+                acc += disc * boot[n]
+            assert abs(R[i] - acc) < 1e-13
+    # (d) changing one segment's rewards and bootstrap leaves every other segment's returns as they were
+    rew2 = rew.copy(); rew2[start[7]:start[8]] += 3.0
+    boot2 = boot.copy(); boot2[7] -= 5.0
+    R2 = orc.returns_ragged(rew2, dn, start, boot2, gam)
+    keep = np.ones(F, bool); keep[start[7]:start[8]] = False
+    np.testing.assert_array_equal(R2[keep], R[keep])
+    assert np.all(R2[~keep] != R[~keep]) or dn[start[7]:start[8]].any()
+    # empty segments are allowed and change nothing
+    start3 = np.concatenate([start[:5], start[4:5], start[5:]]).astype(np.int32)
+    boot3 = np.concatenate([boot[:4], [99.0], boot[4:]])
+    np.testing.assert_array_equal(orc.returns_ragged(rew, dn, start3, boot3, gam), R)
+    with pytest.raises(ValueError):
+        orc.returns_ragged(rew, dn, start[::-1].copy(), boot, gam)
+
+
+def test_ragged_train_step_equals_the_rectangular_one_on_equal_lengths():
+    # the ragged update is the rectangular update's steps with the ragged returns; on equal lengths the two must agree
+    net = orc.Net(in_c=2, in_h=12, in_w=12, conv=((3, 4, 2), (4, 2, 1)), fc_units=5, n_actions=3)
+    P = orc.param_count(net)
+    theta = synth.rng(61).standard_normal(P) * 0.3; g0 = synth.rng(62).random(P) * 0.01
+    N, T = 4, 3
+    frames = synth.uniform_frames(63, (N, T, 2, 12, 12))
+    tr = synth.trajectories(64, N, T, 3)
+    boot = synth.rng(65).standard_normal(N)
+    hp = orc.HParams(gamma=0.9, beta=0.05, value_coef=0.5, clip_norm=1.0)
+    a = orc.train_step(net, theta, g0, frames, tr["actions"], tr["rewards"], tr["dones"], boot, hp)
+    b = orc.train_step_ragged(net, theta, g0, frames.reshape(N * T, 2, 12, 12), tr["actions"].reshape(-1),
+                              tr["rewards"].reshape(-1), tr["dones"].reshape(-1), np.arange(N + 1) * T, boot, hp)
+    for k in ("theta", "g", "grad", "dZ", "dV", "logits", "values"):
+        np.testing.assert_allclose(b[k], a[k], rtol=1e-13, atol=1e-15)
+    np.testing.assert_allclose(b["R"], a["R"].reshape(-1), rtol=0, atol=0)
+    for k in ("policy_loss", "value_loss", "entropy", "grad_norm", "clip_scale"):
+        assert abs(b["stats"][k] - a["stats"][k]) <= 1e-12 * max(1.0, abs(a["stats"][k]))
+    assert a["stats"]["clip_scale"] < 1.0
+
+
 # ------------------------------------------------------- loss, output grads --
 
 def loss_total_np(z, V, a, R, adv, beta, cv, e):
