@@ -158,6 +158,28 @@ int ga3c_train_step(ga3c_ctx *ctx, const uint8_t *frames_dev, const int32_t *act
                     const float *bootstrap_dev, int N, int T,
                     const ga3c_hparams *hp, ga3c_train_stats *stats_dev, void *stream);
 
+/* The same update on N segments of unequal length laid end to end (Sec. 4.1:
+ * an agent hands in its experiences after t_max actions or when its episode
+ * ends, so a training batch also holds shorter segments):
+ *   frames_dev    u8  [n_frames][in_c][in_h][in_w]
+ *   actions_dev   i32 [n_frames];  rewards_dev f32 [n_frames];  dones_dev u8 [n_frames]
+ *   seg_start_dev i32 [N+1], device memory: segment n is the frames
+ *                 seg_start[n] .. seg_start[n+1]-1; seg_start[0] = 0,
+ *                 seg_start[N] = n_frames, never decreasing (an empty segment
+ *                 is allowed and contributes nothing).  The table is read on
+ *                 the device only, so it is not checked: with a table that
+ *                 breaks these rules the returns are meaningless, but no
+ *                 access leaves the arrays.
+ *   bootstrap_dev f32 [N] value of the state after each segment's last step
+ *                 (0 where the episode ended), or NULL = 0
+ * The return of frame i in segment n is r[i] + gamma (1 - done[i]) R[i+1],
+ * with R[seg_start[n+1]] = bootstrap[n]; everything else is as above.
+ * n_frames <= max_train_frames; n_frames = 0 is a no-op; N >= 1 otherwise. */
+int ga3c_train_step_ragged(ga3c_ctx *ctx, const uint8_t *frames_dev, const int32_t *actions_dev,
+                           const float *rewards_dev, const uint8_t *dones_dev, const int32_t *seg_start_dev,
+                           const float *bootstrap_dev, int N, int n_frames,
+                           const ga3c_hparams *hp, ga3c_train_stats *stats_dev, void *stream);
+
 /* Intermediates of the last ga3c_train_step, for checking it step by step.
  * which: 0 = returns R [N*T]; 1 = logits [N*T][A]; 2 = values [N*T];
  * 3 = dL/d(logits, value) [N*T][A+1].  Copies n floats (n must not exceed the

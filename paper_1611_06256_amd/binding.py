@@ -107,7 +107,8 @@ def lib_path() -> str:
 _lib = None
 
 EXPORTS = ("ga3c_create", "ga3c_destroy", "ga3c_params_count", "ga3c_params_offsets", "ga3c_params_init",
-           "ga3c_params_get", "ga3c_params_set", "ga3c_predict", "ga3c_train_step", "ga3c_train_debug_get",
+           "ga3c_params_get", "ga3c_params_set", "ga3c_predict", "ga3c_train_step", "ga3c_train_step_ragged",
+           "ga3c_train_debug_get",
            "ga3c_rmsprop_flat", "ga3c_last_error", "ga3c_profile_enable", "ga3c_profile_read",
            "ga3c_use_generic_kernels", "ga3c_get_desc",
            "ga3c_sched_create", "ga3c_sched_destroy", "ga3c_sched_submit_predict", "ga3c_sched_submit_trajectory",
@@ -137,6 +138,7 @@ def load_library() -> C.CDLL:
     lib.ga3c_params_set.argtypes = [vp, i32, vp, sz, vp]
     lib.ga3c_predict.argtypes = [vp, vp, i32, vp, vp, vp, vp, vp, vp]
     lib.ga3c_train_step.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, C.POINTER(_HParams), vp, vp]
+    lib.ga3c_train_step_ragged.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, C.POINTER(_HParams), vp, vp]
     lib.ga3c_train_debug_get.argtypes = [vp, i32, vp, sz, vp]
     lib.ga3c_rmsprop_flat.argtypes = [vp, vp, vp, sz, f32, f32, f32, f32, vp]
     lib.ga3c_last_error.restype = C.c_char_p
@@ -278,6 +280,27 @@ class Ga3c:
                                          _ptr(actions, torch.int32, "actions"), _ptr(rewards, torch.float32, "rewards"),
                                          _ptr(dones, torch.uint8, "dones"), _ptr(bootstrap, torch.float32, "bootstrap"),
                                          N, T, C.byref(hpc), sp, _stream(stream)), "ga3c_train_step")
+
+    def train_step_ragged(self, frames, actions, rewards, dones, seg_start, bootstrap, hp: HParams, stats=None,
+                          stream=None) -> None:
+        """Segments of unequal length laid end to end: frames u8 [F,C,H,W]; actions i32, rewards f32, dones u8 [F];
+        seg_start i32 [N+1] (GPU tensor); bootstrap f32 [N] or None."""
+        import torch
+        F, N = int(frames.shape[0]), int(seg_start.numel()) - 1
+        if actions.numel() != F or rewards.numel() != F or dones.numel() != F or N < 0 or \
+                (bootstrap is not None and bootstrap.numel() != N):
+            raise Ga3cError("train_step_ragged: array sizes do not match the frame or segment count")
+        hpc = hp.c()
+        sp = None
+        if stats is not None:
+            if not stats.is_cuda or stats.numel() * stats.element_size() < C.sizeof(TrainStats):
+                raise Ga3cError("stats: need a GPU tensor of at least 24 bytes")
+            sp = C.c_void_p(stats.data_ptr())
+        _check(self._lib.ga3c_train_step_ragged(
+            self._ctx, _ptr(frames, torch.uint8, "frames"), _ptr(actions, torch.int32, "actions"),
+            _ptr(rewards, torch.float32, "rewards"), _ptr(dones, torch.uint8, "dones"),
+            _ptr(seg_start, torch.int32, "seg_start"), _ptr(bootstrap, torch.float32, "bootstrap"),
+            N, F, C.byref(hpc), sp, _stream(stream)), "ga3c_train_step_ragged")
 
     def use_generic_kernels(self, on: bool) -> None:
         _check(self._lib.ga3c_use_generic_kernels(self._ctx, 1 if on else 0), "ga3c_use_generic_kernels")

@@ -321,6 +321,26 @@ __global__ __launch_bounds__(256) void heads_fwd_kernel(const float *__restrict_
     }
 }
 
+// n-step return (text after Eq. 1) of frame i when the segments have unequal
+// lengths (Sec. 4.1: an agent hands in fewer than t_max experiences when its
+// episode ends): segment n is the frames seg_start[n] .. seg_start[n+1]-1 and
+// the return after its last frame is bootstrap[n].  The segment of frame i is
+// the last n with seg_start[n] <= i, so empty segments are passed over.  The
+// walk is bounded by the frame count whatever the table holds.
+__device__ __forceinline__ float ragged_return(const float *__restrict__ rewards, const uint8_t *__restrict__ dones,
+                                               const int32_t *__restrict__ seg_start, const float *__restrict__ bootstrap,
+                                               int N, int B, int i, float gamma) {
+    int lo = 0, hi = N - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (seg_start[mid] <= i) lo = mid; else hi = mid - 1;
+    }
+    const int end = min(seg_start[lo + 1], B);
+    float next = bootstrap ? bootstrap[lo] : 0.f;
+    for (int j = end - 1; j >= i; --j) next = rewards[j] + gamma * (dones[j] ? 0.f : 1.f) * next;
+    return next;
+}
+
 // n-step returns (text after Eq. 1) and the loss with its gradient w.r.t. the
 // head outputs (Eq. 1, 2, 5), one thread per frame (n, t).  The thread walks
 // its agent's steps T-1 .. t to get R_t, in the order of the recursion.  The
@@ -329,24 +349,28 @@ __global__ __launch_bounds__(256) void heads_fwd_kernel(const float *__restrict_
 // Dynamic LDS: LOSS_THREADS * (A + 1) floats.
 __global__ __launch_bounds__(LOSS_THREADS) void returns_loss_kernel(
     const float *__restrict__ zv, const int32_t *__restrict__ actions, const float *__restrict__ rewards,
-    const uint8_t *__restrict__ dones, const float *__restrict__ bootstrap, int N, int T, int A, float gamma,
-    float beta, float cv, float eps, float *__restrict__ R, float *__restrict__ dzv, float *__restrict__ part) {
+    const uint8_t *__restrict__ dones, const float *__restrict__ bootstrap, const int32_t *__restrict__ seg_start, int N,
+    int T, int B, int A, float gamma, float beta, float cv, float eps, float *__restrict__ R, float *__restrict__ dzv,
+    float *__restrict__ part) {
     extern __shared__ float zsh[];     // [LOSS_THREADS][A+1]
     const int i0 = blockIdx.x * LOSS_THREADS;
     const int i = i0 + threadIdx.x;
-    const int B = N * T;
     const int nrows = min(LOSS_THREADS, B - i0);
     copy_to_lds<8>(zsh, zv + (size_t)i0 * (A + 1), nrows * (A + 1), threadIdx.x, LOSS_THREADS);
     float s_pl = 0.f, s_vl = 0.f, s_en = 0.f;
     float next = 0.f;
     int a = 0;
     if (i < B) {
-        const int n = i / T, t = i % T;
-        next = bootstrap ? bootstrap[n] : 0.f;
         a = actions[i];
-        for (int tt = T - 1; tt >= t; --tt) {
-            const size_t j = (size_t)n * T + tt;
-            next = rewards[j] + gamma * (dones[j] ? 0.f : 1.f) * next;
+        if (seg_start) {
+            next = ragged_return(rewards, dones, seg_start, bootstrap, N, B, i, gamma);
+        } else {
+            const int n = i / T, t = i % T;
+            next = bootstrap ? bootstrap[n] : 0.f;
+            for (int tt = T - 1; tt >= t; --tt) {
+                const size_t j = (size_t)n * T + tt;
+                next = rewards[j] + gamma * (dones[j] ? 0.f : 1.f) * next;
+            }
         }
         R[i] = next;
     }
@@ -485,8 +509,8 @@ __global__ __launch_bounds__(256) void heads_train_kernel(
     const float *__restrict__ ws, int nz, const float *__restrict__ fcb, int B, int F, int A,
     const float *__restrict__ Wp, const float *__restrict__ bp, const float *__restrict__ Wv, const float *__restrict__ bv,
     const int32_t *__restrict__ actions, const float *__restrict__ rewards, const uint8_t *__restrict__ dones,
-    const float *__restrict__ bootstrap, int T, float gamma, float beta, float cv, float eps,
-    float *__restrict__ zv, float *__restrict__ R, float *__restrict__ dzv, float *__restrict__ dh,
+    const float *__restrict__ bootstrap, const int32_t *__restrict__ seg_start, int N, int T, float gamma, float beta,
+    float cv, float eps, float *__restrict__ zv, float *__restrict__ R, float *__restrict__ dzv, float *__restrict__ dh,
     float *__restrict__ colpart, float *__restrict__ wpart, float *__restrict__ losspart, int rb) {
     extern __shared__ __attribute__((aligned(16))) float sm[];
     constexpr int NF = HD_FRAMES;
@@ -506,7 +530,7 @@ __global__ __launch_bounds__(256) void heads_train_kernel(
     // ---- everything from global memory is requested first
     const int n0 = b0 / T, n1 = (b0 + nf - 1) / T;          // agents of my frames
     const int nrw = (n1 - n0 + 1) * T;
-    const bool rw_lds = nrw <= 256;
+    const bool rw_lds = !seg_start && nrw <= 256;      // segments of unequal length read their rewards from global memory
     float my_rw = 0.f, my_dn = 0.f;
     if (rw_lds && tid < nrw) { my_rw = rewards[(size_t)n0 * T + tid]; my_dn = dones[(size_t)n0 * T + tid] ? 0.f : 1.f; }
     const int ofb = min(tid / A1, nf - 1), oa = tid % A1;   // thread tid < nf*A1 owns output oa of frame ofb
@@ -514,7 +538,7 @@ __global__ __launch_bounds__(256) void heads_train_kernel(
     const int ob = b0 + ofb;
     const float obias = oa < A ? bp[oa] : bv[0];
     const int oact = actions[ob];
-    const float oboot = bootstrap ? bootstrap[ob / T] : 0.f;
+    const float oboot = bootstrap && !seg_start ? bootstrap[ob / T] : 0.f;
     for (int e = tid; e < NF * (F4 - F); e += 256) hs[(e / (F4 - F)) * F4 + F + e % (F4 - F)] = 0.f;
     for (int e = tid; e < A1 * (WP - F); e += 256) wsh[(e / (WP - F)) * WP + F + e % (WP - F)] = 0.f;
     const int nw = A1 * F;
@@ -598,7 +622,9 @@ __global__ __launch_bounds__(256) void heads_train_kernel(
     if (mine && oa == A) {
         const int n = ob / T, t = ob % T;
         float next = oboot;
-        if (rw_lds) {
+        if (seg_start) {
+            next = ragged_return(rewards, dones, seg_start, bootstrap, N, B, ob, gamma);
+        } else if (rw_lds) {
             for (int tt = T - 1; tt >= t; --tt) { const int j = (n - n0) * T + tt; next = rw[j] + gamma * dn[j] * next; }
         } else {
             for (int tt = T - 1; tt >= t; --tt) {
@@ -1386,16 +1412,11 @@ extern "C" int ga3c_predict(ga3c_ctx *c, const uint8_t *frames, int B, const flo
     return GA3C_OK;
 }
 
-extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t *actions, const float *rewards,
-                               const uint8_t *dones, const float *bootstrap, int N, int T, const ga3c_hparams *hp,
-                               ga3c_train_stats *stats, void *stream) {
-    if (!c) return fail(GA3C_EINVAL, "ga3c_train_step: null context");
-    if (N < 0 || T < 0) return fail(GA3C_EINVAL, "ga3c_train_step: negative N or T");
-    const long long BL = (long long)N * T;
-    if (BL > c->max_train) return fail(GA3C_EINVAL, "ga3c_train_step: N*T = %lld above capacity %d", BL, c->max_train);
-    if (BL == 0) return GA3C_OK;
-    if (!frames || !actions || !rewards || !dones || !hp) return fail(GA3C_EINVAL, "ga3c_train_step: null argument");
-    const int B = (int)BL;
+// One update on B frames.  seg_start == nullptr: N segments of T frames each
+// (B = N*T); otherwise N segments of unequal length, T = 1.
+static int train_step_impl(ga3c_ctx *c, const uint8_t *frames, const int32_t *actions, const float *rewards,
+                           const uint8_t *dones, const float *bootstrap, const int32_t *seg_start, int N, int T, int B,
+                           const ga3c_hparams *hp, ga3c_train_stats *stats, void *stream) {
     hipStream_t s = (hipStream_t)stream;
     Work &w = c->train;
     const int nb = 2 * c->nconv, A = c->A, F = c->F;
@@ -1415,7 +1436,7 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
     if (!fused_heads) {
         STAGE("returns_loss", 0, 4.0 * B * (2 * (A + 1) + 4));
         hipLaunchKernelGGL(returns_loss_kernel, dim3(nloss), dim3(LOSS_THREADS), sizeof(float) * LOSS_THREADS * (A + 1), s, w.zv, actions, rewards, dones,
-                           bootstrap, N, T, A, hp->gamma, hp->beta, hp->value_coef, hp->log_eps, c->R, c->dzv, losspart);
+                           bootstrap, seg_start, N, T, B, A, hp->gamma, hp->beta, hp->value_coef, hp->log_eps, c->R, c->dzv, losspart);
         HIP_TRY(hipGetLastError());
     }
 
@@ -1454,7 +1475,7 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
         HIP_TRY(allow_dynamic_lds((const void *)heads_train_kernel, ht_lds, ht_lds_set));
         STAGE("heads_train", 6.0 * B * (A + 1) * F, 4.0 * (w.fc_nz + 1) * B * F);
         hipLaunchKernelGGL(heads_train_kernel, dim3(nblk), dim3(256), ht_lds, s, w.fc_ws, w.fc_nz, th + c->off[nb + 1], B, F, A, Wp,
-                           th + c->off[nb + 3], Wv, th + c->off[nb + 5], actions, rewards, dones, bootstrap, T, hp->gamma, hp->beta,
+                           th + c->off[nb + 3], Wv, th + c->off[nb + 5], actions, rewards, dones, bootstrap, seg_start, N, T, hp->gamma, hp->beta,
                            hp->value_coef, hp->log_eps, w.zv, c->R, c->dzv, c->dh, c->colpart, part, losspart, c->rb);
         HIP_TRY(hipGetLastError());
         add_seg(part, nblk, A + 1, F + 1, 0, A, c->grad + c->off[nb + 2], c->grad + c->off[nb + 3], 1);
@@ -1635,6 +1656,32 @@ extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t
     TRY(mark_ready(c, cur ^ 1, s));
     c->cur = cur ^ 1;        // calls enqueued from now on see the new parameters
     return GA3C_OK;
+}
+
+extern "C" int ga3c_train_step(ga3c_ctx *c, const uint8_t *frames, const int32_t *actions, const float *rewards,
+                               const uint8_t *dones, const float *bootstrap, int N, int T, const ga3c_hparams *hp,
+                               ga3c_train_stats *stats, void *stream) {
+    if (!c) return fail(GA3C_EINVAL, "ga3c_train_step: null context");
+    if (N < 0 || T < 0) return fail(GA3C_EINVAL, "ga3c_train_step: negative N or T");
+    const long long BL = (long long)N * T;
+    if (BL > c->max_train) return fail(GA3C_EINVAL, "ga3c_train_step: N*T = %lld above capacity %d", BL, c->max_train);
+    if (BL == 0) return GA3C_OK;
+    if (!frames || !actions || !rewards || !dones || !hp) return fail(GA3C_EINVAL, "ga3c_train_step: null argument");
+    return train_step_impl(c, frames, actions, rewards, dones, bootstrap, nullptr, N, T, (int)BL, hp, stats, stream);
+}
+
+extern "C" int ga3c_train_step_ragged(ga3c_ctx *c, const uint8_t *frames, const int32_t *actions, const float *rewards,
+                                      const uint8_t *dones, const int32_t *seg_start, const float *bootstrap, int N,
+                                      int n_frames, const ga3c_hparams *hp, ga3c_train_stats *stats, void *stream) {
+    if (!c) return fail(GA3C_EINVAL, "ga3c_train_step_ragged: null context");
+    if (N < 0 || n_frames < 0) return fail(GA3C_EINVAL, "ga3c_train_step_ragged: negative N or n_frames");
+    if (n_frames > c->max_train)
+        return fail(GA3C_EINVAL, "ga3c_train_step_ragged: %d frames above capacity %d", n_frames, c->max_train);
+    if (n_frames == 0) return GA3C_OK;
+    if (N == 0) return fail(GA3C_EINVAL, "ga3c_train_step_ragged: frames without a segment");
+    if (!frames || !actions || !rewards || !dones || !seg_start || !hp)
+        return fail(GA3C_EINVAL, "ga3c_train_step_ragged: null argument");
+    return train_step_impl(c, frames, actions, rewards, dones, bootstrap, seg_start, N, 1, n_frames, hp, stats, stream);
 }
 
 extern "C" int ga3c_train_debug_get(ga3c_ctx *c, int which, float *dst, size_t n, void *stream) {

@@ -174,13 +174,18 @@ def test_predict_subset_of_outputs_and_empty(G):
     net.close()
 
 
-def run_train(G, desc, N, T, seed, hp_kw, frames=None, g0_scale=0.0, steps=1):
+def run_train(G, desc, N, T, seed, hp_kw, frames=None, g0_scale=0.0, steps=1, seg=None):
+    """One or more updates on both sides, compared step by step.  seg = None: N segments of T frames; otherwise the
+    dict of synth.ragged_segments (N segments of unequal length, T unused), which goes through the ragged entry
+    point and the oracle's ragged update."""
     import torch
     from paper_1611_06256_amd.binding import stats_from_tensor
-    net, onet, theta = make(G, desc, N, N * T, seed)
+    nfr = N * T if seg is None else int(seg["seg_start"][-1])
+    net, onet, theta = make(G, desc, N, nfr, seed)
     if frames is None:
-        frames = synth.uniform_frames(seed + 1, (N, T, desc.in_c, desc.in_h, desc.in_w))
-    tr = synth.trajectories(seed + 2, N, T, desc.n_actions)
+        shape = (N, T) if seg is None else (nfr,)
+        frames = synth.uniform_frames(seed + 1, shape + (desc.in_c, desc.in_h, desc.in_w))
+    tr = synth.trajectories(seed + 2, N, T, desc.n_actions) if seg is None else seg
     # bootstrap value from the net itself, on N more frames, with the pre-update theta
     bf = synth.uniform_frames(seed + 3, (N, desc.in_c, desc.in_h, desc.in_w))
     boot_t = torch.zeros(N, device="cuda")
@@ -197,14 +202,22 @@ def run_train(G, desc, N, T, seed, hp_kw, frames=None, g0_scale=0.0, steps=1):
              rewards=torch.from_numpy(tr["rewards"]).cuda(), dones=torch.from_numpy(tr["dones"]).cuda())
     th_ref, g_ref = theta.astype(np.float64), g0.astype(np.float64)
     for step in range(steps):
-        print(f"train N={N} T={T} A={desc.n_actions} step={step}", flush=True)
-        net.train_step(d["frames"], d["actions"], d["rewards"], d["dones"], boot_t, hp, stats=stats_t)
+        print(f"train N={N} T={T if seg is None else 'ragged'} frames={nfr} A={desc.n_actions} step={step}", flush=True)
+        if seg is None:
+            net.train_step(d["frames"], d["actions"], d["rewards"], d["dones"], boot_t, hp, stats=stats_t)
+        else:
+            net.train_step_ragged(d["frames"], d["actions"], d["rewards"], d["dones"],
+                                  torch.from_numpy(seg["seg_start"]).cuda(), boot_t, hp, stats=stats_t)
         torch.cuda.synchronize()
         # the oracle starts each step from the library's own state, so that one
         # step's rounding does not compound into the next comparison
-        ref = orc.train_step(onet, th_ref, g_ref, frames, tr["actions"], tr["rewards"], tr["dones"],
-                             boot.astype(np.float64), ohp)
-        B, A = N * T, desc.n_actions
+        if seg is None:
+            ref = orc.train_step(onet, th_ref, g_ref, frames, tr["actions"], tr["rewards"], tr["dones"],
+                                 boot.astype(np.float64), ohp)
+        else:
+            ref = orc.train_step_ragged(onet, th_ref, g_ref, frames, tr["actions"], tr["rewards"], tr["dones"],
+                                        seg["seg_start"], boot.astype(np.float64), ohp)
+        B, A = nfr, desc.n_actions
         R = net.train_debug_get(0, torch.empty(B, device="cuda")).cpu().numpy()
         lg = net.train_debug_get(1, torch.empty(B * A, device="cuda")).cpu().numpy().reshape(B, A)
         vl = net.train_debug_get(2, torch.empty(B, device="cuda")).cpu().numpy()
@@ -470,6 +483,80 @@ def test_segment_length_edges(G, N, T):
     # one-step segments, a single agent, and segments so long that the rewards of a block's agents do not fit the
     # training heads kernel's LDS copy (it then reads them from global memory)
     run_train(G, G.NetDesc(**TINY), N, T, 7900 + 10 * N + T, dict(beta=0.02, value_coef=0.5, gamma=0.97), g0_scale=1e-2)
+
+
+@pytest.mark.parametrize("nseg,t_max,A", [(13, 5, 18), (40, 5, 6), (3, 1, 4), (1, 9, 3), (7, 40, 40)])
+def test_train_ragged_segments(G, nseg, t_max, A):
+    # Sec. 4.1: agents hand in fewer than t_max experiences when the episode ends.  Segments of mixed length through
+    # the fused heads kernel (A <= 31) and through the separate loss kernel (A = 40), on the small net for the first
+    # case and a tiny net otherwise; t_max = 1 makes every segment one frame, nseg = 1 a single segment.
+    seg = synth.ragged_segments(8100 + nseg, nseg, t_max, A, p_short=0.5)
+    if nseg == 13:
+        F = int(seg["seg_start"][-1])
+        run_train(G, G.SMALL_NET(A), nseg, t_max, 8110, dict(clip_norm=40.0), frames=synth.rectangle_frames(8111, F), seg=seg)
+    else:
+        run_train(G, G.NetDesc(**dict(TINY, fc_units=12, n_actions=A)), nseg, t_max, 8120 + nseg,
+                  dict(beta=0.02, value_coef=0.5, gamma=0.97, lr=1e-2), g0_scale=1e-2, seg=seg, steps=2 if nseg == 40 else 1)
+        # (lr = 1e-2: with a handful of frames the default step is a few fp32 units in the last place of theta, too
+        # coarse for the comparison of the step taken)
+
+
+def test_ragged_with_equal_lengths_is_the_rectangular_update_bit_for_bit(G):
+    # the two entry points differ only in how a frame finds its segment; an empty segment in the table changes nothing
+    import torch
+    N, T, A = 9, 5, 6
+    desc = G.NetDesc(**dict(TINY, n_actions=A))
+    frames = torch.from_numpy(synth.uniform_frames(8201, (N, T, desc.in_c, desc.in_h, desc.in_w))).cuda()
+    tr = synth.trajectories(8202, N, T, A)
+    ac, rw, dn = (torch.from_numpy(tr[k]).cuda() for k in ("actions", "rewards", "dones"))
+    boot = torch.from_numpy(synth.rng(8203).standard_normal(N).astype(np.float32)).cuda()
+    hp = G.HParams(clip_norm=1.0, gamma=0.9)
+    out = []
+    for mode in ("rect", "ragged", "ragged_with_empty"):
+        net = G.Ga3c(desc, 4, N * T)
+        net.use_generic_kernels(GENERIC)
+        net.params_init(77)
+        print("mode", mode, flush=True)
+        if mode == "rect":
+            net.train_step(frames, ac, rw, dn, boot, hp)
+        else:
+            start = np.arange(N + 1, dtype=np.int32) * T
+            b = boot
+            if mode == "ragged_with_empty":
+                start = np.concatenate([start[:4], start[3:4], start[4:]]).astype(np.int32)
+                b = torch.cat([boot[:3], torch.full((1,), 123.0, device="cuda"), boot[3:]])
+            net.train_step_ragged(frames.reshape(N * T, *frames.shape[2:]), ac.reshape(-1), rw.reshape(-1), dn.reshape(-1),
+                                  torch.from_numpy(start).cuda(), b, hp)
+        torch.cuda.synchronize()
+        out.append((net.params_get(0).cpu().numpy(), net.params_get(2).cpu().numpy(),
+                    net.train_debug_get(0, torch.empty(N * T, device="cuda")).cpu().numpy()))
+        net.close()
+    for o in out[1:]:
+        for x, y in zip(o, out[0]):
+            np.testing.assert_array_equal(x, y)
+
+
+def test_ragged_argument_errors(G):
+    import torch
+    desc = G.NetDesc(**TINY)
+    net = G.Ga3c(desc, 4, 10)
+    fr = torch.zeros(12, desc.in_c, desc.in_h, desc.in_w, dtype=torch.uint8, device="cuda")
+    z = lambda n, dt: torch.zeros(n, dtype=dt, device="cuda")
+    hp = G.HParams()
+    with pytest.raises(G.Ga3cError):      # above capacity
+        net.train_step_ragged(fr, z(12, torch.int32), z(12, torch.float32), z(12, torch.uint8),
+                              torch.tensor([0, 12], dtype=torch.int32, device="cuda"), None, hp)
+    with pytest.raises(G.Ga3cError):      # frames but no segment
+        net.train_step_ragged(fr[:4], z(4, torch.int32), z(4, torch.float32), z(4, torch.uint8),
+                              torch.tensor([0], dtype=torch.int32, device="cuda"), None, hp)
+    with pytest.raises(G.Ga3cError):      # array sizes do not match
+        net.train_step_ragged(fr[:4], z(3, torch.int32), z(4, torch.float32), z(4, torch.uint8),
+                              torch.tensor([0, 4], dtype=torch.int32, device="cuda"), None, hp)
+    # no frames: a no-op
+    net.train_step_ragged(fr[:0], z(0, torch.int32), z(0, torch.float32), z(0, torch.uint8),
+                          torch.tensor([0], dtype=torch.int32, device="cuda"), None, hp)
+    torch.cuda.synchronize()
+    net.close()
 
 
 def test_train_large_net(G):
