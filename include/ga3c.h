@@ -225,9 +225,15 @@ int ga3c_profile_read(ga3c_ctx *ctx, char *buf, size_t cap);
  * thread-safe against each other.  Frames are DEVICE memory owned by the
  * caller, 16-byte aligned, and must stay unchanged until the tick that
  * consumed them has finished on the GPU (ga3c_sched_drain, or the
- * prediction's result has been polled).  Trajectories have exactly t_max
- * steps; actions / rewards / dones are HOST arrays of t_max entries that are
- * copied at submit time. */
+ * prediction's result has been polled).  A segment has 1 .. t_max steps (fewer
+ * than t_max when the agent's episode ended, Sec. 4.1); actions / rewards /
+ * dones are HOST arrays of that many entries, copied at submit time.
+ *
+ * Policy lag (Sec. 4.2: the policy that acted may be several updates older
+ * than the parameters its experiences update): every prediction carries the
+ * number of updates that had been issued before the parameters it read; an
+ * agent hands that number back with the segment, and the scheduler adds up,
+ * per segment, how many updates were issued between the two. */
 typedef struct ga3c_sched ga3c_sched;
 typedef struct ga3c_tuner ga3c_tuner;
 
@@ -243,7 +249,10 @@ typedef struct {
     ga3c_hparams hp;                        /* used for every update */
 } ga3c_sched_config;
 
-typedef struct { int32_t agent; int32_t action; float value; } ga3c_prediction;
+typedef struct {
+    int32_t agent; int32_t action; float value;
+    int32_t policy_version;                 /* updates issued before the parameters this prediction read */
+} ga3c_prediction;
 
 typedef struct {
     int64_t ticks, predictions, predict_batches, trained_frames, train_batches;
@@ -252,6 +261,8 @@ typedef struct {
     int64_t trials_accepted, trials_rejected;
     int32_t predict_cap, train_cap;               /* now */
     double last_window_frames_per_s;
+    int64_t short_segments;                       /* trained segments with fewer than t_max steps */
+    int64_t lag_sum, lag_count, lag_max;          /* policy lag in updates over the trained segments that gave a version */
 } ga3c_sched_stats;
 
 int ga3c_sched_create(ga3c_ctx *ctx, const ga3c_sched_config *cfg, ga3c_sched **out);
@@ -260,9 +271,14 @@ int ga3c_sched_destroy(ga3c_sched *s);
 /* Agent `agent` asks for an action for the state in frame_dev (u8 [C][H][W]);
  * uniform in [0,1) drives the draw. */
 int ga3c_sched_submit_predict(ga3c_sched *s, int agent, const uint8_t *frame_dev, float uniform);
-/* Agent `agent` hands in t_max experiences: frames_dev u8 [t_max][C][H][W]
- * (device), actions / rewards / dones (host), and the value of the state
- * after the last step. */
+/* Agent `agent` hands in len experiences, 1 <= len <= t_max: frames_dev u8
+ * [len][C][H][W] (device), actions / rewards / dones (host, len entries), the
+ * value of the state after the last step (ignored when that step is terminal),
+ * and the policy_version of the prediction that chose the first action, or a
+ * negative number to leave the segment out of the lag statistics. */
+int ga3c_sched_submit_segment(ga3c_sched *s, int agent, const uint8_t *frames_dev, int len, const int32_t *actions,
+                              const float *rewards, const uint8_t *dones, float bootstrap, int64_t policy_version);
+/* The same with len = t_max and no version. */
 int ga3c_sched_submit_trajectory(ga3c_sched *s, int agent, const uint8_t *frames_dev, const int32_t *actions,
                                  const float *rewards, const uint8_t *dones, float bootstrap);
 /* The same for n agents at once (host arrays of n entries; actions, rewards
@@ -276,7 +292,9 @@ int ga3c_sched_submit_trajectory_many(ga3c_sched *s, int n, const int32_t *agent
                                       const float *bootstrap);
 /* One pass of predictor and trainer: at most one prediction batch (all queued
  * requests up to the cap) and at most one update (queued trajectories up to
- * the cap, if at least train_min frames wait) are enqueued on the GPU.
+ * the cap, if at least train_min frames wait; whole segments, oldest first;
+ * ga3c_train_step when all have t_max steps, ga3c_train_step_ragged
+ * otherwise) are enqueued on the GPU.
  * *predicted / *trained (may be NULL) receive the frames issued.  At the end of
  * an adjustment window the call waits for the window's GPU work to read the
  * clock. */

@@ -42,14 +42,15 @@ class _SchedConfig(C.Structure):
 
 
 class Prediction(C.Structure):
-    _fields_ = [("agent", C.c_int32), ("action", C.c_int32), ("value", C.c_float)]
+    _fields_ = [("agent", C.c_int32), ("action", C.c_int32), ("value", C.c_float), ("policy_version", C.c_int32)]
 
 
 class SchedStats(C.Structure):
     _fields_ = [(n, C.c_int64) for n in
                 ("ticks", "predictions", "predict_batches", "trained_frames", "train_batches", "sum_predict_queue",
                  "sum_train_queue", "predict_queue", "train_queue", "trials_accepted", "trials_rejected")] + \
-               [("predict_cap", C.c_int32), ("train_cap", C.c_int32), ("last_window_frames_per_s", C.c_double)]
+               [("predict_cap", C.c_int32), ("train_cap", C.c_int32), ("last_window_frames_per_s", C.c_double)] + \
+               [(n, C.c_int64) for n in ("short_segments", "lag_sum", "lag_count", "lag_max")]
 
 
 class TrainStats(C.Structure):
@@ -112,6 +113,7 @@ EXPORTS = ("ga3c_create", "ga3c_destroy", "ga3c_params_count", "ga3c_params_offs
            "ga3c_rmsprop_flat", "ga3c_last_error", "ga3c_profile_enable", "ga3c_profile_read",
            "ga3c_use_generic_kernels", "ga3c_get_desc",
            "ga3c_sched_create", "ga3c_sched_destroy", "ga3c_sched_submit_predict", "ga3c_sched_submit_trajectory",
+           "ga3c_sched_submit_segment",
            "ga3c_sched_submit_predict_many", "ga3c_sched_submit_trajectory_many",
            "ga3c_sched_tick", "ga3c_sched_poll", "ga3c_sched_drain", "ga3c_sched_get_stats", "ga3c_sched_last_error",
            "ga3c_tuner_create", "ga3c_tuner_report", "ga3c_tuner_state", "ga3c_tuner_destroy")
@@ -148,6 +150,7 @@ def load_library() -> C.CDLL:
     lib.ga3c_sched_destroy.argtypes = [vp]
     lib.ga3c_sched_submit_predict.argtypes = [vp, i32, vp, f32]
     lib.ga3c_sched_submit_trajectory.argtypes = [vp, i32, vp, vp, vp, vp, f32]
+    lib.ga3c_sched_submit_segment.argtypes = [vp, i32, vp, i32, vp, vp, vp, f32, C.c_int64]
     lib.ga3c_sched_submit_predict_many.argtypes = [vp, i32, vp, vp, vp]
     lib.ga3c_sched_submit_trajectory_many.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp]
     lib.ga3c_sched_tick.argtypes = [vp, C.POINTER(i32), C.POINTER(i32)]
@@ -400,6 +403,20 @@ class Scheduler:
                                                        d.ctypes.data_as(C.c_void_p), bootstrap),
                 "ga3c_sched_submit_trajectory")
 
+    def submit_segment(self, agent: int, frames, actions, rewards, dones, bootstrap: float, policy_version: int = -1) -> None:
+        """frames: GPU u8 [len,C,H,W] with 1 <= len <= t_max; actions / rewards / dones: numpy arrays of len entries;
+        policy_version: the one that came with the prediction of the first action (-1 = not given)."""
+        import numpy as np
+        import torch
+        a = np.ascontiguousarray(actions, dtype=np.int32); r = np.ascontiguousarray(rewards, dtype=np.float32)
+        d = np.ascontiguousarray(dones, dtype=np.uint8)
+        if r.size != a.size or d.size != a.size or int(frames.shape[0]) != a.size:
+            raise Ga3cError("segment arrays and frames must have the same number of entries")
+        _scheck(self._lib.ga3c_sched_submit_segment(self._s, agent, _ptr(frames, torch.uint8, "frames"), a.size,
+                                                    a.ctypes.data_as(C.c_void_p), r.ctypes.data_as(C.c_void_p),
+                                                    d.ctypes.data_as(C.c_void_p), bootstrap, policy_version),
+                "ga3c_sched_submit_segment")
+
     def submit_predict_many(self, agents, frame_ptrs, uniforms) -> None:
         """agents i32 [n], frame_ptrs u64 [n] (device addresses), uniforms f32 [n]: numpy arrays."""
         import numpy as np
@@ -421,13 +438,15 @@ class Scheduler:
             ac.ctypes.data_as(C.c_void_p), r.ctypes.data_as(C.c_void_p), d.ctypes.data_as(C.c_void_p),
             bo.ctypes.data_as(C.c_void_p)), "ga3c_sched_submit_trajectory_many")
 
-    def poll_arrays(self, cap: int = 4096):
-        """Finished predictions as numpy arrays (agents, actions, values)."""
+    def poll_arrays(self, cap: int = 4096, with_version: bool = False):
+        """Finished predictions as numpy arrays (agents, actions, values[, policy versions])."""
         import numpy as np
         buf = (Prediction * cap)()
         n = _scheck(self._lib.ga3c_sched_poll(self._s, buf, cap), "ga3c_sched_poll")
-        rec = np.frombuffer(buf, dtype=np.dtype([("agent", "<i4"), ("action", "<i4"), ("value", "<f4")]), count=n)
-        return rec["agent"].copy(), rec["action"].copy(), rec["value"].copy()
+        rec = np.frombuffer(buf, dtype=np.dtype([("agent", "<i4"), ("action", "<i4"), ("value", "<f4"),
+                                                 ("policy_version", "<i4")]), count=n)
+        out = (rec["agent"].copy(), rec["action"].copy(), rec["value"].copy())
+        return out + (rec["policy_version"].copy(),) if with_version else out
 
     def tick(self) -> Tuple[int, int]:
         p, t = C.c_int(), C.c_int()

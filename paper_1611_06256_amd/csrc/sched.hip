@@ -153,6 +153,8 @@ constexpr int RING = 4;    // batches in flight per stream
 struct PredReq { int agent; const uint8_t *frame; float uniform; };
 struct Traj {
     int agent;
+    int len;                 // experiences in the segment, 1 .. t_max
+    int64_t version;         // updates issued before the policy that chose its first action was read; -1 = not given
     const uint8_t *frames;
     std::vector<int32_t> actions;
     std::vector<float> rewards;
@@ -170,6 +172,7 @@ struct PredSlot {
     int32_t *act_d = nullptr, *act_h = nullptr;
     float *val_d = nullptr, *val_h = nullptr;
     std::vector<int> agents;
+    int64_t version = 0;     // updates issued before this batch
 };
 
 struct TrainSlot {
@@ -182,6 +185,7 @@ struct TrainSlot {
     float *rew_h = nullptr, *rew_d = nullptr;
     uint8_t *done_h = nullptr, *done_d = nullptr;
     float *boot_h = nullptr, *boot_d = nullptr;
+    int32_t *seg_h = nullptr, *seg_d = nullptr;          // first frame of every segment, and the frame count
 };
 
 }  // namespace
@@ -196,6 +200,7 @@ struct ga3c_sched {
     hipStream_t sp, st;
     std::deque<PredReq> pq;
     std::deque<Traj> tq;
+    int64_t tq_frames;       // experiences waiting in tq
     PredSlot ps[RING];
     TrainSlot ts[RING];
     int ps_next, ts_next;
@@ -221,8 +226,7 @@ int device(T **p, size_t n) {
 #define STRY(expr) do { int rc_ = (expr); if (rc_ != GA3C_OK) return rc_; } while (0)
 
 int alloc_slots(ga3c_sched *s) {
-    const int T = s->cfg.t_max;
-    const int maxN = s->max_train / T;
+    const int maxN = s->max_train;      // a segment has at least one frame
     for (int i = 0; i < RING; ++i) {
         PredSlot &p = s->ps[i];
         SHIP(hipEventCreateWithFlags(&p.done, hipEventDisableTiming));
@@ -239,6 +243,7 @@ int alloc_slots(ga3c_sched *s) {
         STRY(pinned(&t.rew_h, s->max_train)); STRY(device(&t.rew_d, s->max_train));
         STRY(pinned(&t.done_h, s->max_train)); STRY(device(&t.done_d, s->max_train));
         STRY(pinned(&t.boot_h, maxN)); STRY(device(&t.boot_d, maxN));
+        STRY(pinned(&t.seg_h, maxN + 1)); STRY(device(&t.seg_d, maxN + 1));
     }
     return GA3C_OK;
 }
@@ -254,7 +259,8 @@ int harvest(ga3c_sched *s, bool wait) {
             if (q == hipErrorNotReady) continue;
             if (q != hipSuccess) return sfail(GA3C_EHIP, "hipEventQuery: %s", hipGetErrorString(q));
         }
-        for (int i = 0; i < p.n; ++i) s->ready.push_back(ga3c_prediction{p.agents[i], p.act_h[i], p.val_h[i]});
+        for (int i = 0; i < p.n; ++i)
+            s->ready.push_back(ga3c_prediction{p.agents[i], p.act_h[i], p.val_h[i], (int32_t)p.version});
         p.busy = false;
     }
     for (int k = 0; k < RING; ++k) {
@@ -294,6 +300,7 @@ int issue_predict(ga3c_sched *s, int *count) {
     SHIP(hipMemcpyAsync(p.val_h, p.val_d, sizeof(float) * n, hipMemcpyDeviceToHost, s->sp));
     SHIP(hipEventRecord(p.done, s->sp));
     p.busy = true; p.n = n;
+    p.version = s->stats.train_batches;      // the call above reads the parameters that this many updates produced
     s->ps_next = (s->ps_next + 1) % RING;
     s->stats.predictions += n; s->stats.predict_batches += 1;
     *count = n;
@@ -303,40 +310,56 @@ int issue_predict(ga3c_sched *s, int *count) {
 int issue_train(ga3c_sched *s, int *count) {
     *count = 0;
     const int T = s->cfg.t_max;
-    if ((int64_t)s->tq.size() * T < s->cfg.train_min) return GA3C_OK;      // merge until the minimum batch is there
+    if (s->tq.empty() || s->tq_frames < s->cfg.train_min) return GA3C_OK;      // merge until the minimum batch is there
     TrainSlot &t = s->ts[s->ts_next];
     if (t.busy) {
         SHIP(hipEventSynchronize(t.done));
         t.busy = false;
     }
-    const int n = (int)std::min<size_t>(s->tq.size(), (size_t)std::max(1, s->train_cap / T));
-    for (int i = 0; i < n; ++i) {
+    // whole segments, oldest first, while they fit the cap (the first one always goes)
+    int n = 0, B = 0;
+    bool equal = true;
+    const int64_t now = s->stats.train_batches;       // updates issued so far = the version this update starts from
+    while (!s->tq.empty() && (n == 0 || B + s->tq.front().len <= s->train_cap)) {
         Traj &tr = s->tq.front();
-        t.ptrs_h[i] = (const uint4 *)tr.frames;
-        memcpy(t.act_h + (size_t)i * T, tr.actions.data(), sizeof(int32_t) * T);
-        memcpy(t.rew_h + (size_t)i * T, tr.rewards.data(), sizeof(float) * T);
-        memcpy(t.done_h + (size_t)i * T, tr.dones.data(), T);
-        t.boot_h[i] = tr.bootstrap;
+        const int L = tr.len;
+        for (int k = 0; k < L; ++k) t.ptrs_h[B + k] = (const uint4 *)(tr.frames + (size_t)k * s->frame_bytes);
+        memcpy(t.act_h + B, tr.actions.data(), sizeof(int32_t) * L);
+        memcpy(t.rew_h + B, tr.rewards.data(), sizeof(float) * L);
+        memcpy(t.done_h + B, tr.dones.data(), L);
+        t.boot_h[n] = tr.bootstrap;
+        t.seg_h[n] = B;
+        if (L != T) { equal = false; s->stats.short_segments += 1; }
+        if (tr.version >= 0) {
+            const int64_t lag = now - tr.version;
+            s->stats.lag_sum += lag; s->stats.lag_count += 1;
+            s->stats.lag_max = std::max(s->stats.lag_max, lag);
+        }
+        B += L; n += 1;
+        s->tq_frames -= L;
         s->tq.pop_front();
     }
-    const size_t B = (size_t)n * T;
-    SHIP(hipMemcpyAsync(t.ptrs_d, t.ptrs_h, sizeof(void *) * n, hipMemcpyHostToDevice, s->st));
+    t.seg_h[n] = B;
+    SHIP(hipMemcpyAsync(t.ptrs_d, t.ptrs_h, sizeof(void *) * B, hipMemcpyHostToDevice, s->st));
     SHIP(hipMemcpyAsync(t.act_d, t.act_h, sizeof(int32_t) * B, hipMemcpyHostToDevice, s->st));
     SHIP(hipMemcpyAsync(t.rew_d, t.rew_h, sizeof(float) * B, hipMemcpyHostToDevice, s->st));
     SHIP(hipMemcpyAsync(t.done_d, t.done_h, B, hipMemcpyHostToDevice, s->st));
     SHIP(hipMemcpyAsync(t.boot_d, t.boot_h, sizeof(float) * n, hipMemcpyHostToDevice, s->st));
-    const int vecs = (int)(s->frame_bytes * T / 16);       // a trajectory's frames are contiguous
-    hipLaunchKernelGGL(gather_frames_kernel, dim3(std::min(16, (vecs + 255) / 256), n), dim3(256), 0, s->st, t.ptrs_d,
+    if (!equal) SHIP(hipMemcpyAsync(t.seg_d, t.seg_h, sizeof(int32_t) * (n + 1), hipMemcpyHostToDevice, s->st));
+    const int vecs = (int)(s->frame_bytes / 16);
+    hipLaunchKernelGGL(gather_frames_kernel, dim3(std::min(8, (vecs + 255) / 256), B), dim3(256), 0, s->st, t.ptrs_d,
                        (uint4 *)t.frames_d, vecs);
     SHIP(hipGetLastError());
-    if (ga3c_train_step(s->ctx, t.frames_d, t.act_d, t.rew_d, t.done_d, t.boot_d, n, T, &s->cfg.hp, nullptr, s->st) !=
-        GA3C_OK)
-        return sfail(GA3C_EHIP, "ga3c_train_step: %s", ga3c_last_error());
+    const int rc = equal ? ga3c_train_step(s->ctx, t.frames_d, t.act_d, t.rew_d, t.done_d, t.boot_d, n, T, &s->cfg.hp,
+                                           nullptr, s->st)
+                         : ga3c_train_step_ragged(s->ctx, t.frames_d, t.act_d, t.rew_d, t.done_d, t.seg_d, t.boot_d, n, B,
+                                                  &s->cfg.hp, nullptr, s->st);
+    if (rc != GA3C_OK) return sfail(GA3C_EHIP, "ga3c_train_step: %s", ga3c_last_error());
     SHIP(hipEventRecord(t.done, s->st));
     t.busy = true; t.n_agents = n;
     s->ts_next = (s->ts_next + 1) % RING;
     s->stats.trained_frames += (int64_t)B; s->stats.train_batches += 1;
-    *count = (int)B;
+    *count = B;
     return GA3C_OK;
 }
 
@@ -362,7 +385,7 @@ extern "C" int ga3c_sched_create(ga3c_ctx *ctx, const ga3c_sched_config *cfg, ga
     if (!s) return sfail(GA3C_ENOMEM, "ga3c_sched_create: out of memory");
     s->ctx = ctx; s->cfg = *cfg; s->desc = d; s->max_pred = mp; s->max_train = mt; s->frame_bytes = fb;
     s->predict_cap = cfg->predict_cap; s->train_cap = cfg->train_cap;
-    s->sp = s->st = nullptr; s->ps_next = s->ts_next = 0; s->tuner = nullptr;
+    s->sp = s->st = nullptr; s->ps_next = s->ts_next = 0; s->tuner = nullptr; s->tq_frames = 0;
     memset(&s->stats, 0, sizeof(s->stats));
     s->stats.predict_cap = s->predict_cap; s->stats.train_cap = s->train_cap;
     s->window_ticks = s->window_frames = 0;
@@ -402,6 +425,7 @@ extern "C" int ga3c_sched_destroy(ga3c_sched *s) {
         (void)hipHostFree(t.ptrs_h); (void)hipFree(t.ptrs_d); (void)hipFree(t.frames_d);
         (void)hipHostFree(t.act_h); (void)hipFree(t.act_d); (void)hipHostFree(t.rew_h); (void)hipFree(t.rew_d);
         (void)hipHostFree(t.done_h); (void)hipFree(t.done_d); (void)hipHostFree(t.boot_h); (void)hipFree(t.boot_d);
+        (void)hipHostFree(t.seg_h); (void)hipFree(t.seg_d);
     }
     if (s->sp) (void)hipStreamDestroy(s->sp);
     if (s->st) (void)hipStreamDestroy(s->st);
@@ -417,23 +441,33 @@ extern "C" int ga3c_sched_submit_predict(ga3c_sched *s, int agent, const uint8_t
     return GA3C_OK;
 }
 
+extern "C" int ga3c_sched_submit_segment(ga3c_sched *s, int agent, const uint8_t *frames_dev, int len,
+                                         const int32_t *actions, const float *rewards, const uint8_t *dones,
+                                         float bootstrap, int64_t policy_version) {
+    if (!s || !frames_dev || !actions || !rewards || !dones)
+        return sfail(GA3C_EINVAL, "ga3c_sched_submit_segment: null argument");
+    if (((uintptr_t)frames_dev) & 15)
+        return sfail(GA3C_EINVAL, "ga3c_sched_submit_segment: frames must be 16-byte aligned");
+    if (len < 1 || len > s->cfg.t_max)
+        return sfail(GA3C_EINVAL, "ga3c_sched_submit_segment: length %d outside 1..t_max = %d", len, s->cfg.t_max);
+    for (int i = 0; i < len; ++i)
+        if (actions[i] < 0 || actions[i] >= s->desc.n_actions)
+            return sfail(GA3C_EINVAL, "ga3c_sched_submit_segment: action %d out of range", (int)actions[i]);
+    Traj tr;
+    tr.agent = agent; tr.len = len; tr.version = policy_version < 0 ? -1 : policy_version;
+    tr.frames = frames_dev; tr.bootstrap = bootstrap;
+    tr.actions.assign(actions, actions + len);
+    tr.rewards.assign(rewards, rewards + len);
+    tr.dones.assign(dones, dones + len);
+    s->tq.push_back(std::move(tr));
+    s->tq_frames += len;
+    return GA3C_OK;
+}
+
 extern "C" int ga3c_sched_submit_trajectory(ga3c_sched *s, int agent, const uint8_t *frames_dev, const int32_t *actions,
                                             const float *rewards, const uint8_t *dones, float bootstrap) {
-    if (!s || !frames_dev || !actions || !rewards || !dones)
-        return sfail(GA3C_EINVAL, "ga3c_sched_submit_trajectory: null argument");
-    if (((uintptr_t)frames_dev) & 15)
-        return sfail(GA3C_EINVAL, "ga3c_sched_submit_trajectory: frames must be 16-byte aligned");
-    const int T = s->cfg.t_max;
-    for (int i = 0; i < T; ++i)
-        if (actions[i] < 0 || actions[i] >= s->desc.n_actions)
-            return sfail(GA3C_EINVAL, "ga3c_sched_submit_trajectory: action %d out of range", (int)actions[i]);
-    Traj tr;
-    tr.agent = agent; tr.frames = frames_dev; tr.bootstrap = bootstrap;
-    tr.actions.assign(actions, actions + T);
-    tr.rewards.assign(rewards, rewards + T);
-    tr.dones.assign(dones, dones + T);
-    s->tq.push_back(std::move(tr));
-    return GA3C_OK;
+    if (!s) return sfail(GA3C_EINVAL, "ga3c_sched_submit_trajectory: null scheduler");
+    return ga3c_sched_submit_segment(s, agent, frames_dev, s->cfg.t_max, actions, rewards, dones, bootstrap, -1);
 }
 
 extern "C" int ga3c_sched_submit_predict_many(ga3c_sched *s, int n, const int32_t *agents,

@@ -150,3 +150,67 @@ def test_dynamic_adjustment_runs_within_bounds(G):
     assert best > 0
     assert np.isfinite(ns.params_get(0).cpu().numpy()).all()
     sched.close(); ns.close(); nd.close()
+
+
+def test_short_segments_and_policy_lag(G):
+    # Sec. 4.1: an agent hands in fewer than t_max experiences when its episode ends; Sec. 4.2: the policy that acted
+    # may be older than the parameters its experiences update.  Segments of mixed length go through the scheduler in
+    # whole-segment batches under a frame cap; the parameters must equal those of the same ragged updates made
+    # directly, and the lag statistics must count the updates issued between a prediction and its segment's update.
+    import torch
+    N, T = 12, 5
+    (ns, nd), frames, tr, u = setup(G, N, T, 4242)
+    seg = synth.ragged_segments(4243, N, T, 6, p_short=0.5)
+    lens, start = seg["lengths"], seg["seg_start"]
+    assert (lens < T).any() and (lens == T).any()
+    hp = G.HParams(lr=1e-3, clip_norm=40.0)
+    sched = G.Scheduler(ns, hp, t_max=T, predict_cap=64, train_min=1, train_cap=30)
+    for a in range(N):
+        sched.submit_predict(a, frames[a, 0], float(u[a, 0]))
+    assert sched.tick() == (N, 0)
+    sched.drain()
+    ag, _, _, ver = sched.poll_arrays(with_version=True)
+    assert sorted(ag) == list(range(N)) and (ver == 0).all()
+    boot = (0.1 * np.arange(N)).astype(np.float32)
+    for a in range(N):
+        sl = slice(start[a], start[a + 1])
+        sched.submit_segment(a, frames[a, :lens[a]], seg["actions"][sl], seg["rewards"][sl], seg["dones"][sl],
+                             float(boot[a]), policy_version=int(ver[list(ag).index(a)]))
+    with pytest.raises(G.Ga3cError):      # longer than t_max
+        sched.submit_segment(0, frames[0], np.zeros(6, np.int32), np.zeros(6, np.float32), np.zeros(6, np.uint8), 0.0)
+    # expected batches: whole segments, oldest first, while the frame count stays within the cap
+    batches, cur, cnt = [], [], 0
+    for a in range(N):
+        if cur and cnt + lens[a] > 30:
+            batches.append(cur); cur, cnt = [], 0
+        cur.append(a); cnt += int(lens[a])
+    batches.append(cur)
+    assert len(batches) >= 2
+    for k, b in enumerate(batches):
+        nfr = int(sum(lens[a] for a in b))
+        # a tick sends its prediction batch before its update: this prediction reads the parameters after k updates
+        sched.submit_predict(b[0], frames[b[0], 1], 0.5)
+        assert sched.tick() == (1, nfr)
+        sched.drain()
+        _, _, _, v = sched.poll_arrays(with_version=True)
+        assert list(v) == [k]
+        fr = torch.cat([frames[a, :lens[a]] for a in b]).contiguous()
+        cat = lambda key: torch.from_numpy(np.concatenate([seg[key][start[a]:start[a + 1]] for a in b])).cuda()
+        st_ = np.concatenate([[0], np.cumsum([lens[a] for a in b])]).astype(np.int32)
+        if all(lens[a] == T for a in b):
+            nd.train_step(fr.reshape(len(b), T, 4, 84, 84), cat("actions").reshape(len(b), T), cat("rewards").reshape(len(b), T),
+                          cat("dones").reshape(len(b), T), torch.from_numpy(boot[b]).cuda(), hp)
+        else:
+            nd.train_step_ragged(fr, cat("actions"), cat("rewards"), cat("dones"), torch.from_numpy(st_).cuda(),
+                                 torch.from_numpy(boot[b]).cuda(), hp)
+        torch.cuda.synchronize()
+    assert sched.tick() == (0, 0)
+    np.testing.assert_array_equal(ns.params_get(0).cpu().numpy(), nd.params_get(0).cpu().numpy())
+    np.testing.assert_array_equal(ns.params_get(1).cpu().numpy(), nd.params_get(1).cpu().numpy())
+    st = sched.stats()
+    assert st["train_batches"] == len(batches) and st["trained_frames"] == int(lens.sum())
+    assert st["short_segments"] == int((lens < T).sum())
+    # every segment was generated by version 0; batch k is update number k, so its segments lag by k updates
+    assert st["lag_count"] == N and st["lag_max"] == len(batches) - 1
+    assert st["lag_sum"] == sum(k * len(b) for k, b in enumerate(batches))
+    sched.close(); ns.close(); nd.close()
