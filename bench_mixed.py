@@ -11,6 +11,14 @@ Reports, per mean think time: predictions/s, trained frames/s, mean prediction
 batch, mean training-queue length (the quantities of the paper's Fig. 4) and
 the caps the adjustment ended with.  The driver loop is Python (numpy, one
 ctypes call per batch of requests); its cost per tick is reported too.
+
+With --episode-end-prob p > 0 every action ends the agent's episode with
+probability p: the agent then hands in the shorter segment at once, terminal
+at its last step (Sec. 4.1), so updates run on segments of unequal length.
+Every segment carries the version of the policy that chose its first action;
+the scheduler reports the policy lag in updates (Sec. 4.2).  --min-batch-sweep
+runs fixed caps with the minimum training batch set to 5, 10, 20, 40, 80, 160,
+320 frames (the knob of Sec. 5.3), for the first two think times given.
 """
 from __future__ import annotations
 
@@ -26,7 +34,8 @@ if ROOT not in sys.path:
 
 
 def run_mixed(net_kind: str = "small", n_agents: int = 256, think_us: float = 0.0, seconds: float = 1.0,
-              dynamic: bool = True, seed: int = 1615, predict_cap: int = 256, train_cap: int = 1280):
+              dynamic: bool = True, seed: int = 1615, predict_cap: int = 256, train_cap: int = 1280,
+              train_min: int = 40, episode_end_prob: float = 0.0):
     import numpy as np
     import torch
 
@@ -41,11 +50,14 @@ def run_mixed(net_kind: str = "small", n_agents: int = 256, think_us: float = 0.
     torch.cuda.synchronize()
     fb = 4 * 84 * 84
     base = pool.data_ptr()
-    sched = g.Scheduler(net, g.HParams(clip_norm=40.0), t_max=T, predict_cap=predict_cap if not dynamic else 32, train_min=40,
+    sched = g.Scheduler(net, g.HParams(clip_norm=40.0), t_max=T, predict_cap=predict_cap if not dynamic else 32,
+                        train_min=train_min,
                         train_cap=train_cap if not dynamic else 320, adjust_period=1000 if dynamic else 0, predict_cap_lo=1,
-                        predict_cap_hi=predict_cap, train_cap_lo=40, train_cap_hi=train_cap, train_cap_step=40, seed=seed)
+                        predict_cap_hi=predict_cap, train_cap_lo=max(40, train_min), train_cap_hi=train_cap, train_cap_step=40, seed=seed)
     rng = synth.rng(seed + 1)
-    step = np.zeros(n_agents, np.int64)
+    step = np.zeros(n_agents, np.int64)          # actions taken so far (picks the frame shown)
+    seg_len = np.zeros(n_agents, np.int32)       # experiences gathered since the last hand-in
+    seg_ver = np.zeros(n_agents, np.int64)       # version of the policy that chose the segment's first action
     waiting = np.zeros(n_agents, bool)
     ready_at = np.zeros(n_agents)
     acts = np.zeros((n_agents, T), np.int32)
@@ -64,21 +76,28 @@ def run_mixed(net_kind: str = "small", n_agents: int = 256, think_us: float = 0.
             waiting[a] = True
         sched.tick()
         ticks += 1
-        a, action, value = sched.poll_arrays()
+        a, action, value, version = sched.poll_arrays(with_version=True)
         if a.size:
-            acts[a, step[a] % T] = action
+            first = seg_len[a] == 0
+            seg_ver[a[first]] = version[first]
+            acts[a, seg_len[a]] = action
             step[a] += 1
+            seg_len[a] += 1
             waiting[a] = False
             ready_at[a] = now + (rng.exponential(think_us * 1e-6, a.size) if think_us > 0 else 0.0)
-            done = a[step[a] % T == 0]
+            ended = rng.random(a.size) < episode_end_prob if episode_end_prob > 0 else np.zeros(a.size, bool)
+            hand = (seg_len[a] == T) | ended
+            done = a[hand]
             if done.size:
+                lens = seg_len[done].copy()
                 u = rng.random((done.size, T))
                 rewards = np.where(u < 0.05, -1.0, np.where(u >= 0.95, 1.0, 0.0)).astype(np.float32)
                 dones = (rng.random((done.size, T)) < 0.02).astype(np.uint8)
+                dones[np.flatnonzero(ended[hand]), lens[ended[hand]] - 1] = 1
                 # the bootstrap is the value of the newest state the agent knows
-                vmap = dict(zip(a.tolist(), value.tolist()))
-                sched.submit_trajectory_many(done, base + done.astype(np.uint64) * T * fb, acts[done], rewards, dones,
-                                             np.array([vmap[int(i)] for i in done], np.float32))
+                sched.submit_segment_many(done, base + done.astype(np.uint64) * T * fb, lens, acts[done], rewards, dones,
+                                          value[hand], seg_ver[done])
+                seg_len[done] = 0
     sched.drain()
     wall = time.perf_counter() - t0
     st = sched.stats()
@@ -89,6 +108,9 @@ def run_mixed(net_kind: str = "small", n_agents: int = 256, think_us: float = 0.
            "mean_train_queue": round(st["sum_train_queue"] / max(1, st["ticks"]), 2),
            "predict_cap": st["predict_cap"], "train_cap": st["train_cap"],
            "trials_accepted": st["trials_accepted"], "trials_rejected": st["trials_rejected"],
+           "train_min": train_min, "episode_end_prob": episode_end_prob, "updates": st["train_batches"],
+           "short_segments": st["short_segments"],
+           "mean_policy_lag_updates": round(st["lag_sum"] / max(1, st["lag_count"]), 3), "max_policy_lag_updates": st["lag_max"],
            "host_us_per_tick": round(wall / max(1, ticks) * 1e6, 1)}
     sched.close()
     net.close()
@@ -100,12 +122,24 @@ def main() -> int:
     ap.add_argument("--net", choices=("small", "large"), default="small")
     ap.add_argument("--seconds", type=float, default=1.5)
     ap.add_argument("--think-us", type=float, nargs="*", default=[0.0, 200.0, 2000.0, 20000.0])
+    ap.add_argument("--agents", type=int, default=256)
+    ap.add_argument("--episode-end-prob", type=float, default=0.0)
+    ap.add_argument("--min-batch-sweep", action="store_true")
     args = ap.parse_args()
+    if args.min_batch_sweep:
+        rows = [run_mixed(args.net, n_agents=args.agents, think_us=th, seconds=args.seconds, dynamic=False,
+                          train_min=m, train_cap=max(1280, m), episode_end_prob=args.episode_end_prob)
+                for th in args.think_us[:2] for m in (5, 10, 20, 40, 80, 160, 320)]
+        print(json.dumps({"metric": "minimum training batch sweep (Sec. 5.3), synthetic agents, one GPU, two streams",
+                          "net": args.net, "data": "synthetic", "runs": rows}))
+        return 0
     rows = []
     for th in args.think_us:
-        rows.append(run_mixed(args.net, think_us=th, seconds=args.seconds, dynamic=True))
-    rows.append(run_mixed(args.net, think_us=0.0, seconds=args.seconds, dynamic=False))
-    print(json.dumps({"metric": "mixed load, 256 synthetic agents, one GPU, two streams", "net": args.net,
+        rows.append(run_mixed(args.net, n_agents=args.agents, think_us=th, seconds=args.seconds, dynamic=True,
+                              episode_end_prob=args.episode_end_prob))
+    rows.append(run_mixed(args.net, n_agents=args.agents, think_us=0.0, seconds=args.seconds, dynamic=False,
+                          episode_end_prob=args.episode_end_prob))
+    print(json.dumps({"metric": "mixed load, synthetic agents, one GPU, two streams", "net": args.net,
                       "data": "synthetic", "runs": rows}))
     return 0
 

@@ -290,6 +290,13 @@ int ga3c_sched_submit_predict_many(ga3c_sched *s, int n, const int32_t *agents, 
 int ga3c_sched_submit_trajectory_many(ga3c_sched *s, int n, const int32_t *agents, const uint8_t *const *frames_dev,
                                       const int32_t *actions, const float *rewards, const uint8_t *dones,
                                       const float *bootstrap);
+/* Segments of n agents at once: lens [n]; actions, rewards and dones are
+ * [n][t_max] with the first lens[i] entries of row i used; policy_versions [n]
+ * or NULL (no versions).  Queued in index order; on an error the entries
+ * before the offending one stay queued. */
+int ga3c_sched_submit_segment_many(ga3c_sched *s, int n, const int32_t *agents, const uint8_t *const *frames_dev,
+                                   const int32_t *lens, const int32_t *actions, const float *rewards,
+                                   const uint8_t *dones, const float *bootstrap, const int64_t *policy_versions);
 /* One pass of predictor and trainer: at most one prediction batch (all queued
  * requests up to the cap) and at most one update (queued trajectories up to
  * the cap, if at least train_min frames wait; whole segments, oldest first;

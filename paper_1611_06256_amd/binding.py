@@ -113,7 +113,7 @@ EXPORTS = ("ga3c_create", "ga3c_destroy", "ga3c_params_count", "ga3c_params_offs
            "ga3c_rmsprop_flat", "ga3c_last_error", "ga3c_profile_enable", "ga3c_profile_read",
            "ga3c_use_generic_kernels", "ga3c_get_desc",
            "ga3c_sched_create", "ga3c_sched_destroy", "ga3c_sched_submit_predict", "ga3c_sched_submit_trajectory",
-           "ga3c_sched_submit_segment",
+           "ga3c_sched_submit_segment", "ga3c_sched_submit_segment_many",
            "ga3c_sched_submit_predict_many", "ga3c_sched_submit_trajectory_many",
            "ga3c_sched_tick", "ga3c_sched_poll", "ga3c_sched_drain", "ga3c_sched_get_stats", "ga3c_sched_last_error",
            "ga3c_tuner_create", "ga3c_tuner_report", "ga3c_tuner_state", "ga3c_tuner_destroy")
@@ -151,6 +151,7 @@ def load_library() -> C.CDLL:
     lib.ga3c_sched_submit_predict.argtypes = [vp, i32, vp, f32]
     lib.ga3c_sched_submit_trajectory.argtypes = [vp, i32, vp, vp, vp, vp, f32]
     lib.ga3c_sched_submit_segment.argtypes = [vp, i32, vp, i32, vp, vp, vp, f32, C.c_int64]
+    lib.ga3c_sched_submit_segment_many.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.ga3c_sched_submit_predict_many.argtypes = [vp, i32, vp, vp, vp]
     lib.ga3c_sched_submit_trajectory_many.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp]
     lib.ga3c_sched_tick.argtypes = [vp, C.POINTER(i32), C.POINTER(i32)]
@@ -437,6 +438,24 @@ class Scheduler:
             self._s, a.size, a.ctypes.data_as(C.c_void_p), p.ctypes.data_as(C.c_void_p),
             ac.ctypes.data_as(C.c_void_p), r.ctypes.data_as(C.c_void_p), d.ctypes.data_as(C.c_void_p),
             bo.ctypes.data_as(C.c_void_p)), "ga3c_sched_submit_trajectory_many")
+
+    def submit_segment_many(self, agents, frame_ptrs, lens, actions, rewards, dones, bootstrap, policy_versions=None) -> None:
+        """n segments at once: lens i32 [n]; actions / rewards / dones [n, t_max] (row i: the first lens[i] entries
+        count); frame_ptrs u64 [n] (device addresses); policy_versions i64 [n] or None."""
+        import numpy as np
+        a = np.ascontiguousarray(agents, dtype=np.int32); p = np.ascontiguousarray(frame_ptrs, dtype=np.uint64)
+        ln = np.ascontiguousarray(lens, dtype=np.int32)
+        ac = np.ascontiguousarray(actions, dtype=np.int32); r = np.ascontiguousarray(rewards, dtype=np.float32)
+        d = np.ascontiguousarray(dones, dtype=np.uint8); bo = np.ascontiguousarray(bootstrap, dtype=np.float32)
+        pv = None if policy_versions is None else np.ascontiguousarray(policy_versions, dtype=np.int64)
+        if ac.size != a.size * self.t_max or r.size != ac.size or d.size != ac.size or bo.size != a.size or \
+                ln.size != a.size or p.size != a.size or (pv is not None and pv.size != a.size):
+            raise Ga3cError("segment arrays must be [n, t_max] and [n]")
+        _scheck(self._lib.ga3c_sched_submit_segment_many(
+            self._s, a.size, a.ctypes.data_as(C.c_void_p), p.ctypes.data_as(C.c_void_p), ln.ctypes.data_as(C.c_void_p),
+            ac.ctypes.data_as(C.c_void_p), r.ctypes.data_as(C.c_void_p), d.ctypes.data_as(C.c_void_p),
+            bo.ctypes.data_as(C.c_void_p), None if pv is None else pv.ctypes.data_as(C.c_void_p)),
+            "ga3c_sched_submit_segment_many")
 
     def poll_arrays(self, cap: int = 4096, with_version: bool = False):
         """Finished predictions as numpy arrays (agents, actions, values[, policy versions])."""

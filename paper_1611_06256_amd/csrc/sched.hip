@@ -495,6 +495,22 @@ extern "C" int ga3c_sched_submit_trajectory_many(ga3c_sched *s, int n, const int
     return GA3C_OK;
 }
 
+extern "C" int ga3c_sched_submit_segment_many(ga3c_sched *s, int n, const int32_t *agents,
+                                              const uint8_t *const *frames_dev, const int32_t *lens,
+                                              const int32_t *actions, const float *rewards, const uint8_t *dones,
+                                              const float *bootstrap, const int64_t *policy_versions) {
+    if (!s || n < 0 || (n > 0 && (!agents || !frames_dev || !lens || !actions || !rewards || !dones || !bootstrap)))
+        return sfail(GA3C_EINVAL, "ga3c_sched_submit_segment_many: bad argument");
+    const int T = s->cfg.t_max;
+    for (int i = 0; i < n; ++i) {
+        const int rc = ga3c_sched_submit_segment(s, agents[i], frames_dev[i], lens[i], actions + (size_t)i * T,
+                                                 rewards + (size_t)i * T, dones + (size_t)i * T, bootstrap[i],
+                                                 policy_versions ? policy_versions[i] : -1);
+        if (rc != GA3C_OK) return rc;
+    }
+    return GA3C_OK;
+}
+
 extern "C" int ga3c_sched_tick(ga3c_sched *s, int *predicted, int *trained) {
     if (!s) return sfail(GA3C_EINVAL, "ga3c_sched_tick: null scheduler");
     int np = 0, nt = 0;
