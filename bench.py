@@ -266,7 +266,9 @@ def main() -> int:
         out["mixed_load"] = [run_mixed(args.net, think_us=0.0, seconds=args.mixed_seconds, dynamic=False),
                              run_mixed(args.net, think_us=0.0, seconds=2 * args.mixed_seconds, dynamic=True),
                              # enough agents to keep several batches in flight: what the whole queue system sustains
-                             # (2 % of the actions end an episode, so the updates run on segments of unequal length)
+                             run_mixed(args.net, n_agents=2048, think_us=0.0, seconds=args.mixed_seconds, dynamic=False,
+                                       predict_cap=1024, train_cap=2560),
+                             # the same with 2 % of the actions ending an episode: updates on segments of unequal length
                              run_mixed(args.net, n_agents=2048, think_us=0.0, seconds=args.mixed_seconds, dynamic=False,
                                        predict_cap=1024, train_cap=2560, episode_end_prob=0.02)]
 
