@@ -217,6 +217,12 @@ def main() -> int:
         roofline = {"kernel": dom["stage"], "bound": "hbm", "achieved": round(ach, 2), "peak": PEAK_HBM / 1e9,
                     "unit": "GB/s", "frac": round(ach * 1e9 / PEAK_HBM, 4), "traffic": None,
                     "ms_per_launch": round(dp["ms"] / dp["calls"], 5)}
+    if dom["bound"] == "hbm" and dp["flop"] > 0:
+        # the same kernel seen as a contraction: algorithmic flops of the layers' definitions against the fp32 matrix
+        # peak (the split-bf16 arithmetic runs on the bf16 cores, so this can exceed 1)
+        fl = dp["flop"] / (dp["ms"] * 1e-3)
+        roofline["as_contraction"] = {"bound": "mfma", "achieved": round(fl / 1e12, 3), "peak": PEAK_FP32_MFMA / 1e12,
+                                      "unit": "TFLOP/s", "frac": round(fl / PEAK_FP32_MFMA, 4)}
     if args.net == "small" and N == 512:
         launches = {"conv12_fwd": [(N, T), (N * T, 1)], "fc_fwd": [(N, T), (N * T, 1)], "heads_fwd": [(N, T)]}
         roofline["traffic"] = counter_traffic(dom["stage"], launches.get(dom["stage"], [(N * T, 1)]))
