@@ -132,7 +132,8 @@ int ga3c_params_set(ga3c_ctx *ctx, int which, const float *src_dev, size_t n, vo
  *   actions_dev  i32 [B] (may be NULL): a = the first j whose running fp32 sum
  *                p_0 + ... + p_j (added left to right) exceeds u, else
  *                n_actions - 1.
- * 0 <= B <= max_predict_batch; B = 0 is a no-op. */
+ * 0 <= B <= max_predict_batch; B = 0 is a no-op.  Calls on one context share
+ * its workspace: issue them on one stream, or order them with events. */
 int ga3c_predict(ga3c_ctx *ctx, const uint8_t *frames_dev, int B,
                  const float *uniforms_dev,
                  float *logits_dev, float *values_dev, float *probs_dev, int32_t *actions_dev,

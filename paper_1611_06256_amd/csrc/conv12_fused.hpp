@@ -36,6 +36,10 @@ constexpr int C12_Y1 = 16 * 400;                     // elements of one plane of
 constexpr int C12_EX = 4 * 3 * 4 * 64;               // floats one exchange buffer holds: [wavefront][tile][r][lane]
 constexpr size_t C12_LDS_BYTES = sizeof(__bf16) * (C12_XS + 2 * 3 * C12_Y1) + sizeof(float) * 2 * C12_EX;
 
+// Where the single-frame variant leaves the layer-2 output: the second buffer of layer-1 planes, which one frame never
+// uses; everything below this offset is free once layer 2 has run.
+constexpr size_t C12_Y2S_OFF = sizeof(__bf16) * (C12_XS + 3 * C12_Y1);
+
 constexpr int C12_FRAG_SET = 3 * 8 * 64;             // 16-byte vectors of one fragment set: [term][slot][lane]
 
 // Filters of both layers as MFMA operand fragments, split into three bf16 terms
@@ -112,17 +116,20 @@ inline hipError_t launch_conv12_filter_fragments(const float *w1, const float *w
 // only the first plane of the layer-1 output is written and read.
 // KEEP: the layer-1 output is also written to y1 (a template parameter rather than a test of the pointer, so that
 // the stores do not cut the epilogue into a basic block each).
-template <bool ONE, bool KEEP>
-__global__ __launch_bounds__(512, 1) void conv12_fused_fwd_kernel(const uint8_t *__restrict__ x,
-                                                                  const u32x4 *__restrict__ frag,
-                                                                  const float *__restrict__ b1,
-                                                                  const float *__restrict__ b2, float *__restrict__ y1,
-                                                                  float *__restrict__ y2, int nframes, float scale,
-                                                                  int rb) {
+//
+// The body is a device function so that a second kernel can run it on one frame and go on with the rest of the
+// network: the block works on frames first, first + stride, ... below nframes.  TO_LDS: the layer-2 output of the
+// (single) frame goes to LDS instead of y2, as floats [32][81] at C12_Y2S_OFF; the caller synchronises before
+// reading it.  idle(it) is called by the layer-1 wavefronts in the
+// iterations in which they have no frame left to work on (while layer 2 runs).
+template <bool ONE, bool KEEP, bool TO_LDS, class Idle>
+__device__ __forceinline__ void conv12_fused_block(const uint8_t *__restrict__ x, const u32x4 *__restrict__ frag,
+                                                   const float *__restrict__ b1, const float *__restrict__ b2,
+                                                   float *__restrict__ y1, float *__restrict__ y2, int first, int stride,
+                                                   int nframes, float scale, unsigned char *c12_smem, Idle idle) {
     constexpr int CHW1 = 4 * 84 * 84, W1 = 84, NPIX1 = 400, OW1 = 20;
     constexpr int NV = CHW1 / 16, VPT = 7;                         // 16-byte vectors of a frame, per layer-1 thread
     constexpr int HW2 = 400, NPIX2 = 81, OW2 = 9, OC2 = 32;
-    extern __shared__ __attribute__((aligned(16))) unsigned char c12_smem[];
     __bf16 *xs = (__bf16 *)c12_smem;
     __bf16 *ys = xs + C12_XS;                                      // [2][3][C12_Y1]
     float *exb = (float *)(ys + 2 * 3 * C12_Y1);                   // [2][C12_EX]
@@ -141,7 +148,7 @@ __global__ __launch_bounds__(512, 1) void conv12_fused_fwd_kernel(const uint8_t 
 #pragma unroll
     for (int i = 0; i < VPT; ++i) vidx[i] = min(rt + 256 * i, NV - 1);
     if (layer1) {
-        const u32x4 *src = (const u32x4 *)(x + (size_t)blockIdx.x * CHW1);
+        const u32x4 *src = (const u32x4 *)(x + (size_t)first * CHW1);
 #pragma unroll
         for (int i = 0; i < VPT; ++i) pre[i] = src[vidx[i]];
     }
@@ -163,14 +170,16 @@ __global__ __launch_bounds__(512, 1) void conv12_fused_fwd_kernel(const uint8_t 
 #pragma unroll
     for (int r = 0; r < 4; ++r) bv[r] = layer1 ? b1[4 * g + r] : b2[kh * 16 + 4 * g + r];
 
-    const int grid = gridDim.x;
-    const int n = (nframes - (int)blockIdx.x + grid - 1) / grid;  // frames of this block (>= 1)
+    const int grid = stride;
+    const int n = TO_LDS ? 1 : (nframes - first + grid - 1) / grid;      // frames of this block (>= 1)
 
     floatx4 keep[3];                                               // layer 2: my filter tile's sums of the previous frame
 #pragma unroll
     for (int i = 0; i < 3; ++i) keep[i] = floatx4{0.f, 0.f, 0.f, 0.f};
 
     // iteration it: layer 1 of frame it, layer 2 of frame it - 1, last step of layer 2 of frame it - 2
+    // (one frame: the three iterations are written out, so that each keeps only what it needs in registers)
+#pragma unroll(TO_LDS ? 3 : 1)
     for (int it = 0; it <= n + 1; ++it) {
         __syncthreads();          // layer 1 of the previous frame has read xs; layer 2 has read its planes
         if (layer1 && it < n) {
@@ -185,7 +194,7 @@ __global__ __launch_bounds__(512, 1) void conv12_fused_fwd_kernel(const uint8_t 
         __syncthreads();
         if (layer1) {
             if (it < n) {
-                const int f = blockIdx.x + it * grid;
+                const int f = first + it * grid;
                 {
                     const u32x4 *src = (const u32x4 *)(x + (size_t)min(f + grid, nframes - 1) * CHW1);
 #pragma unroll
@@ -268,11 +277,13 @@ __global__ __launch_bounds__(512, 1) void conv12_fused_fwd_kernel(const uint8_t 
                     }
                     finish(24, acc);
                 }
+            } else {
+                idle(it);
             }
         } else {
             if (it >= 2) {       // frame it - 2: add what my partner summed over its taps, bias, ReLU, store
                 const float *ex = exb + ((it - 1) & 1) * C12_EX + (rw ^ 1) * (3 * 4 * 64);
-                float *yb = y2 + (size_t)(blockIdx.x + (it - 2) * grid) * OC2 * NPIX2;
+                float *yb = TO_LDS ? (float *)(c12_smem + C12_Y2S_OFF) : y2 + (size_t)(first + (it - 2) * grid) * OC2 * NPIX2;
 #pragma unroll
                 for (int i = 0; i < 3; ++i) {
                     const int p = (pg + 2 * i) * 16 + l16;
@@ -332,6 +343,18 @@ __global__ __launch_bounds__(512, 1) void conv12_fused_fwd_kernel(const uint8_t 
             }
         }
     }
+}
+
+template <bool ONE, bool KEEP>
+__global__ __launch_bounds__(512, 1) void conv12_fused_fwd_kernel(const uint8_t *__restrict__ x,
+                                                                  const u32x4 *__restrict__ frag,
+                                                                  const float *__restrict__ b1,
+                                                                  const float *__restrict__ b2, float *__restrict__ y1,
+                                                                  float *__restrict__ y2, int nframes, float scale,
+                                                                  int rb) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char c12_smem[];
+    conv12_fused_block<ONE, KEEP, false>(x, frag, b1, b2, y1, y2, (int)blockIdx.x, (int)gridDim.x, nframes, scale,
+                                         c12_smem, [](int) {});
 }
 
 inline int conv12_fused_blocks(int nframes) { return nframes < 256 ? nframes : 256; }

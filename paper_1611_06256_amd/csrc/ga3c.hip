@@ -80,6 +80,7 @@ struct Profiler {
 struct ga3c_ctx {
     Profiler *prof;
     bool fast;                    // use the fixed-geometry kernels where they apply
+    bool small_predict;           // predictions of a handful of frames go out as one launch
     int rb;                       // desc.math == 1: operands of every contraction are rounded to bfloat16
     ga3c_net_desc desc;
     int nconv, F, A, flat;
@@ -102,6 +103,7 @@ struct ga3c_ctx {
     // small net: conv1/conv2 filters of each parameter copy as split MFMA fragments (nullptr for other nets);
     // refreshed by whoever writes the copy
     u32x4 *cfrag[2];
+    int *ticket;                  // predict_small_kernel's per-frame counters, zero between launches
     Work pred, train;
     // training only
     float *dact[GA3C_MAX_CONV];   // dL/d(pre-activation) of each conv output
@@ -180,19 +182,42 @@ __device__ __forceinline__ void copy_to_lds(float *dst, const float *__restrict_
 __host__ __device__ inline int heads_f4(int F) { return (F + 3) / 4 * 4; }
 __host__ __device__ inline int heads_lds_floats(int F, int A) { return 4 * heads_f4(F) + (A + 1) * (heads_f4(F) + 4 + 12); }
 
-__global__ __launch_bounds__(256) void heads_fwd_kernel(const float *__restrict__ ws, int nz,
-                                                        const float *__restrict__ fcb, float *__restrict__ h, int B,
-                                                        int F, int A, const float *__restrict__ Wp,
-                                                        const float *__restrict__ bp, const float *__restrict__ Wv,
-                                                        const float *__restrict__ bv, float *zv, float *logits,
-                                                        float *values, float *probs, const float *uniforms,
-                                                        int32_t *actions, int rb) {
-    // rb: the products of the heads take h and the weights rounded to bfloat16 (h itself is stored as computed)
-    extern __shared__ __attribute__((aligned(16))) float hs[];      // [4][F4], weights [A+1][F4+4], partial dots
+// Both weight matrices into the block's LDS in the layout heads_fwd_body reads, by threads t = 0 .. NT-1.
+template <int NT>
+__device__ __forceinline__ void heads_stage_weights(float *hs, const int t, int F, int A, const float *__restrict__ Wp,
+                                                    const float *__restrict__ Wv, int rb) {
     const int F4 = heads_f4(F), WP = F4 + 4;
     float *wsh = hs + 4 * F4;
-    const int tid = threadIdx.x;
-    const int b0 = blockIdx.x * 4;
+    for (int e = t; e < (A + 1) * (WP - F); e += NT) wsh[(e / (WP - F)) * WP + F + e % (WP - F)] = 0.f;
+    const int nw = (A + 1) * F;
+    for (int e0 = 0; e0 < nw; e0 += 24 * NT) {
+        float wv[24];
+#pragma unroll
+        for (int j = 0; j < 24; ++j) {
+            const int e = min(e0 + j * NT + t, nw - 1);
+            wv[j] = e < A * F ? Wp[e] : Wv[e - A * F];
+        }
+#pragma unroll
+        for (int j = 0; j < 24; ++j) {
+            const int e = e0 + j * NT + t;
+            if (e < nw) wsh[(e / F) * WP + e % F] = rb ? bf16_rne(wv[j]) : wv[j];
+        }
+    }
+}
+
+// The body, for a block of NT threads (all of them must call it) that works on frames b0 .. min(b0 + 4, B) - 1;
+// hs is the block's LDS.  COHERENT: h was written by other blocks of the same launch, so it is read past the
+// caches that are not kept coherent within a launch.  WSTAGED: heads_stage_weights has already run on hs.
+template <int NT, bool COHERENT, bool WSTAGED>
+__device__ __forceinline__ void heads_fwd_body(float *hs, const int tid, const int b0, const float *__restrict__ ws, int nz,
+                                               const float *__restrict__ fcb, float *__restrict__ h, int B, int F, int A,
+                                               const float *__restrict__ Wp, const float *__restrict__ bp,
+                                               const float *__restrict__ Wv, const float *__restrict__ bv, float *zv,
+                                               float *logits, float *values, float *probs, const float *uniforms,
+                                               int32_t *actions, int rb) {
+    // rb: the products of the heads take h and the weights rounded to bfloat16 (h itself is stored as computed)
+    const int F4 = heads_f4(F), WP = F4 + 4;                        // hs: [4][F4], weights [A+1][F4+4], partial dots
+    float *wsh = hs + 4 * F4;
     const int nf = min(4, B - b0);
     const int nout = nf * (A + 1);
     // thread tid < nout finishes output a of frame fb
@@ -200,18 +225,21 @@ __global__ __launch_bounds__(256) void heads_fwd_kernel(const float *__restrict_
     const float obias = oa < A ? bp[oa] : bv[0];
     const float ou = (actions && tid < nout) ? uniforms[b0 + ofb] : 0.f;
     // padding columns of the LDS rows stay zero
-    for (int e = tid; e < 4 * (F4 - F); e += 256) hs[(e / (F4 - F)) * F4 + F + e % (F4 - F)] = 0.f;
-    for (int e = tid; e < (A + 1) * (WP - F); e += 256) wsh[(e / (WP - F)) * WP + F + e % (WP - F)] = 0.f;
+    for (int e = tid; e < 4 * (F4 - F); e += NT) hs[(e / (F4 - F)) * F4 + F + e % (F4 - F)] = 0.f;
+    if (!WSTAGED)
+        for (int e = tid; e < (A + 1) * (WP - F); e += NT) wsh[(e / (WP - F)) * WP + F + e % (WP - F)] = 0.f;
     const int nw = (A + 1) * F;                 // Wp [A][F] and Wv [F] are adjacent in LDS, not in global memory
-    for (int e0 = 0; e0 < nw || e0 == 0; e0 += 24 * 256) {
+    for (int e0 = 0; (!WSTAGED && e0 < nw) || e0 == 0; e0 += 24 * NT) {
         float wv[24];
+        if (!WSTAGED) {
 #pragma unroll
-        for (int j = 0; j < 24; ++j) {
-            const int e = min(e0 + j * 256 + tid, nw - 1);
-            wv[j] = e < A * F ? Wp[e] : Wv[e - A * F];
+            for (int j = 0; j < 24; ++j) {
+                const int e = min(e0 + j * NT + tid, nw - 1);
+                wv[j] = e < A * F ? Wp[e] : Wv[e - A * F];
+            }
         }
         if (e0 == 0) {
-            for (int o = tid; o < F; o += 256) {
+            for (int o = tid; o < F; o += NT) {
                 if (ws) {
                     const float bias = fcb[o];
                     const size_t stride = (size_t)B * F;
@@ -239,16 +267,21 @@ __global__ __launch_bounds__(256) void heads_fwd_kernel(const float *__restrict_
                 } else {
                     float v[4];
 #pragma unroll
-                    for (int fb = 0; fb < 4; ++fb) v[fb] = h[(size_t)(b0 + min(fb, nf - 1)) * F + o];
+                    for (int fb = 0; fb < 4; ++fb) {
+                        const float *src = h + (size_t)(b0 + min(fb, nf - 1)) * F + o;
+                        v[fb] = COHERENT ? __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : *src;
+                    }
 #pragma unroll
                     for (int fb = 0; fb < 4; ++fb) hs[fb * F4 + o] = rb ? bf16_rne(v[fb]) : v[fb];
                 }
             }
         }
+        if (!WSTAGED) {
 #pragma unroll
-        for (int j = 0; j < 24; ++j) {
-            const int e = e0 + j * 256 + tid;
-            if (e < nw) wsh[(e / F) * WP + e % F] = rb ? bf16_rne(wv[j]) : wv[j];
+            for (int j = 0; j < 24; ++j) {
+                const int e = e0 + j * NT + tid;
+                if (e < nw) wsh[(e / F) * WP + e % F] = rb ? bf16_rne(wv[j]) : wv[j];
+            }
         }
     }
     __syncthreads();
@@ -256,7 +289,7 @@ __global__ __launch_bounds__(256) void heads_fwd_kernel(const float *__restrict_
     // thread (frame, output, part of k) adds its share; KP shares make one output (three where the block has
     // threads for them, fewer when there are many actions).
     float *zs = wsh + (A + 1) * WP;                  // [4][A+1][3] partial dots, then [4][A+1] values
-    const int KP = max(1, min(3, 256 / (4 * (A + 1))));
+    const int KP = max(1, min(3, 256 / (4 * (A + 1))));      // the first 256 threads finish the outputs
     if (tid < KP * nout) {
         const int kp = tid / nout, r = tid % nout;
         const int fb = r / (A + 1), a = r % (A + 1);
@@ -319,6 +352,95 @@ __global__ __launch_bounds__(256) void heads_fwd_kernel(const float *__restrict_
         if (c > ou && !(oa > 0 && cprev > ou)) actions[b] = oa;
         else if (oa == A - 1 && !(c > ou)) actions[b] = A - 1;
     }
+}
+
+__global__ __launch_bounds__(256) void heads_fwd_kernel(const float *__restrict__ ws, int nz,
+                                                        const float *__restrict__ fcb, float *__restrict__ h, int B,
+                                                        int F, int A, const float *__restrict__ Wp,
+                                                        const float *__restrict__ bp, const float *__restrict__ Wv,
+                                                        const float *__restrict__ bv, float *zv, float *logits,
+                                                        float *values, float *probs, const float *uniforms,
+                                                        int32_t *actions, int rb) {
+    extern __shared__ __attribute__((aligned(16))) float heads_smem[];
+    heads_fwd_body<256, false, false>(heads_smem, threadIdx.x, blockIdx.x * 4, ws, nz, fcb, h, B, F, A, Wp, bp, Wv, bv, zv, logits,
+                               values, probs, uniforms, actions, rb);
+}
+
+// The whole forward pass of the small network (Sec. 3.2) for a handful of frames in ONE launch, for the latency of a
+// small prediction batch (the paper's Sec. 5.2 finds the per-call overhead, not the arithmetic, dominant there).
+// SP_SLICES blocks work on each frame: every one of them runs both convolution layers of the frame (the same work
+// SP_SLICES times: the chip is otherwise idle), keeps the result in LDS and computes its own 256 / SP_SLICES outputs
+// of the fully connected layer, whose weight rows its idle layer-1 wavefronts fetched while layer 2 ran.  The block
+// that finishes a frame's fc outputs last (a ticket counter per frame; nobody waits for anybody) runs the heads,
+// the softmax and the draw for that frame.  h [B][256]; ticket [B] zero before the launch and zero again after it.
+constexpr int SP_SLICES = 32, SP_FC = 256, SP_FLAT = 2592, SP_MAX_FRAMES = 8;
+constexpr int SP_ROWS = SP_FC / SP_SLICES / 4;             // fc outputs per layer-1 wavefront
+constexpr int SP_WJ = (SP_FLAT + 63) / 64;                 // weights of one fc row per lane
+
+template <bool ONE>
+__global__ __launch_bounds__(512, 1) void predict_small_kernel(
+    const uint8_t *__restrict__ x, const u32x4 *__restrict__ frag, const float *__restrict__ b1,
+    const float *__restrict__ b2, const float *__restrict__ Wfc, const float *__restrict__ fcb, float *__restrict__ h,
+    int *__restrict__ ticket, int A, const float *__restrict__ Wp, const float *__restrict__ bp,
+    const float *__restrict__ Wv, const float *__restrict__ bv, float *logits, float *values, float *probs,
+    const float *uniforms, int32_t *actions, float scale, int rb) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char sp_smem[];
+    __shared__ int last;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int frame = blockIdx.x / SP_SLICES, slice = blockIdx.x % SP_SLICES;
+    const int o0 = slice * (SP_FC / SP_SLICES) + wave * SP_ROWS;        // first fc output of a layer-1 wavefront
+
+    float wreg[SP_ROWS][SP_WJ];
+    auto fetch_rows = [&](int it) {
+        if (it != 1) return;
+#pragma unroll
+        for (int r = 0; r < SP_ROWS; ++r)
+#pragma unroll
+            for (int j = 0; j < SP_WJ; ++j)
+                wreg[r][j] = Wfc[(size_t)(o0 + r) * SP_FLAT + min(lane + 64 * j, SP_FLAT - 1)];
+    };
+    conv12_fused_block<ONE, false, true>(x, frag, b1, b2, nullptr, nullptr, frame, 1 << 24, frame + 1, scale, sp_smem,
+                                         fetch_rows);
+    __syncthreads();
+    if (wave >= 4) {
+        // meanwhile the layer-2 wavefronts put the heads' weights where the block that draws the last ticket wants them
+        heads_stage_weights<256>((float *)sp_smem, tid - 256, SP_FC, A, Wp, Wv, rb);
+    } else {
+        const float *y2s = (const float *)(sp_smem + C12_Y2S_OFF);
+#pragma unroll
+        for (int r = 0; r < SP_ROWS; ++r) {
+            float sum = 0.f;
+#pragma unroll
+            for (int j = 0; j < SP_WJ; ++j) {
+                const int k = lane + 64 * j;
+                float y = y2s[min(k, SP_FLAT - 1)], w = wreg[r][j];
+                if (rb) { y = bf16_rne(y); w = bf16_rne(w); }
+                sum += k < SP_FLAT ? y * w : 0.f;
+            }
+#pragma unroll
+            for (int m = 32; m >= 1; m >>= 1) sum += __shfl_xor(sum, m, 64);
+            if (lane == 0) {
+                const float v = sum + fcb[o0 + r];
+                // written through to where every compute unit sees it (a device-wide fence instead would write
+                // back and invalidate the whole L2 of this block's XCD, once per block)
+                __hip_atomic_store(h + (size_t)frame * SP_FC + o0 + r, v > 0.f ? v : 0.f, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    }
+    __syncthreads();                         // waits for the block's stores to be acknowledged
+    if (tid == 0) {
+        const int t = __hip_atomic_fetch_add(&ticket[frame], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        last = t == SP_SLICES - 1;
+        if (last) ticket[frame] = 0;         // for the next launch
+    }
+    __syncthreads();
+    if (!last) return;
+    // all SP_SLICES tickets are drawn, so every h of the frame has been acknowledged; the body reads h with
+    // device-scope loads, which do not stop at this compute unit's cache
+    heads_fwd_body<512, true, true>((float *)sp_smem, tid, frame, nullptr, 0, fcb, h, frame + 1, SP_FC, A, Wp, bp, Wv, bv, nullptr,
+                              logits, values, probs, uniforms, actions, rb);
 }
 
 // n-step return (text after Eq. 1) of frame i when the segments have unequal
@@ -1045,6 +1167,33 @@ int forward(ga3c_ctx *c, int which, Work &w, const uint8_t *frames, int B, bool 
     const float *th = c->theta2[which];
     const int nb = 2 * c->nconv;
     int first = 0;
+    if (c->fast && c->small_predict && c->ticket && c->cfrag[which] && is_aligned16(frames) && !keep_zv && with_heads &&
+        B <= SP_MAX_FRAMES && c->nconv == 2 && c->F == SP_FC && c->flat == SP_FLAT &&
+        sizeof(float) * heads_lds_floats(c->F, c->A) <= C12_Y2S_OFF) {
+        // a handful of frames: one launch for the whole network
+        static bool attr_set = false;
+        if (!attr_set) {
+            HIP_TRY(hipFuncSetAttribute((const void *)predict_small_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C12_LDS_BYTES));
+            HIP_TRY(hipFuncSetAttribute((const void *)predict_small_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C12_LDS_BYTES));
+            attr_set = true;
+        }
+        const ConvGeom &g0 = c->geom[0], &g1 = c->geom[1];
+        STAGE("predict_small", 2.0 * B * (g0.OHW * g0.OC * g0.K + g1.OHW * g1.OC * g1.K + (double)c->flat * c->F + c->F * (c->A + 1)),
+              (double)B * g0.CHW + 4.0 * c->flat * c->F);
+        const dim3 grid(B * SP_SLICES), block(512);
+        if (c->rb)
+            hipLaunchKernelGGL(predict_small_kernel<true>, grid, block, C12_LDS_BYTES, s, frames, c->cfrag[which], th + c->off[1],
+                               th + c->off[3], th + c->off[nb], th + c->off[nb + 1], w.h, c->ticket, c->A, th + c->off[nb + 2],
+                               th + c->off[nb + 3], th + c->off[nb + 4], th + c->off[nb + 5], logits, values, probs, uniforms,
+                               actions, 1.f / 255.f, c->rb);
+        else
+            hipLaunchKernelGGL(predict_small_kernel<false>, grid, block, C12_LDS_BYTES, s, frames, c->cfrag[which], th + c->off[1],
+                               th + c->off[3], th + c->off[nb], th + c->off[nb + 1], w.h, c->ticket, c->A, th + c->off[nb + 2],
+                               th + c->off[nb + 3], th + c->off[nb + 4], th + c->off[nb + 5], logits, values, probs, uniforms,
+                               actions, 1.f / 255.f, c->rb);
+        HIP_TRY(hipGetLastError());
+        return GA3C_OK;
+    }
     if (c->fast && c->cfrag[which] && is_aligned16(frames)) {
         // small net: both convolution layers in one kernel; layer-1 activations go to HBM only when training
         const ConvGeom &g0 = c->geom[0], &g1 = c->geom[1];
@@ -1189,6 +1338,7 @@ extern "C" int ga3c_create(const ga3c_net_desc *d, int max_predict_batch, int ma
     memset((void *)c, 0, sizeof(*c));
     c->prof = new (std::nothrow) Profiler();
     c->fast = true;
+    c->small_predict = true;
     c->rb = d->math;
     c->desc = *d;
     c->nconv = d->n_conv; c->F = d->fc_units; c->A = d->n_actions;
@@ -1270,6 +1420,11 @@ extern "C" int ga3c_create(const ga3c_net_desc *d, int max_predict_batch, int ma
             guard(dmalloc((void **)&c->cfrag[i], sizeof(u32x4) * 3 * C12_FRAG_SET));
             if (rc == GA3C_OK) guard(refresh_derived(c, i, nullptr));
         }
+        if (rc == GA3C_OK) guard(dmalloc((void **)&c->ticket, sizeof(int) * SP_MAX_FRAMES));
+        if (rc == GA3C_OK) {
+            const hipError_t e = hipMemset(c->ticket, 0, sizeof(int) * SP_MAX_FRAMES);
+            if (e != hipSuccess) guard(fail(GA3C_EHIP, "hipMemset: %s", hipGetErrorString(e)));
+        }
     }
     if (rc == GA3C_OK) guard(alloc_work(c->pred, c, max_predict_batch));
     if (rc == GA3C_OK) guard(alloc_work(c->train, c, max_train_frames));
@@ -1319,7 +1474,7 @@ extern "C" int ga3c_destroy(ga3c_ctx *c) {
         if (c->ev_readers[i]) (void)hipEventDestroy(c->ev_readers[i]);
     }
     (void)hipFree(c->g); (void)hipFree(c->grad);
-    (void)hipFree(c->cfrag[0]); (void)hipFree(c->cfrag[1]);
+    (void)hipFree(c->cfrag[0]); (void)hipFree(c->cfrag[1]); (void)hipFree(c->ticket);
     free_work(c->pred); free_work(c->train);
     (void)hipFree(c->dh); (void)hipFree(c->dzv); (void)hipFree(c->R);
     (void)hipFree(c->partials); (void)hipFree(c->colpart); (void)hipFree(c->scale); (void)hipFree(c->stats);

@@ -559,6 +559,44 @@ def test_ragged_argument_errors(G):
     net.close()
 
 
+@pytest.mark.parametrize("math", [0, 1])
+def test_handful_of_frames_in_one_launch(G, math):
+    # up to 8 frames of the small net go out as one kernel (convolutions, fc, heads, draw); more frames take the
+    # three-kernel path.  Both compute the same numbers up to summation order, call after call (the kernel's ticket
+    # counters must be back at zero after every launch), in any order of batch sizes.
+    import torch
+    import dataclasses
+    desc = dataclasses.replace(G.SMALL_NET(18), math=math)
+    net = G.Ga3c(desc, 16, 0)
+    net.use_generic_kernels(GENERIC)
+    net.params_init(31)
+    fr = torch.from_numpy(synth.rectangle_frames(8301, 16)).cuda()
+    u = torch.from_numpy(synth.uniforms(8302, 16)).cuda()
+    def run(B):
+        lg = torch.empty(B, 18, device="cuda"); vl = torch.empty(B, device="cuda"); pr = torch.empty(B, 18, device="cuda")
+        ac = torch.empty(B, dtype=torch.int32, device="cuda")
+        net.predict(fr[:B].contiguous(), uniforms=u[:B].contiguous(), logits=lg, values=vl, probs=pr, actions=ac)
+        torch.cuda.synchronize()
+        return lg.cpu().numpy(), vl.cpu().numpy(), pr.cpu().numpy(), ac.cpu().numpy()
+    ref = run(16)
+    tol = 1e-5 if math == 0 else TOL_FWD_BF16
+    first = {}
+    for B in (3, 8, 1, 5, 8, 2, 7, 4, 6, 1, 3):
+        print("frames", B, flush=True)
+        lg, vl, pr, ac = run(B)
+        assert rel_err(lg, ref[0][:B]) <= tol and rel_err(vl, ref[1][:B]) <= tol and rel_err(pr, ref[2][:B]) <= tol
+        cdf = np.cumsum(pr.astype(np.float64), 1)
+        clear = (np.abs(cdf - u[:B].cpu().numpy()[:, None]) > 1e-4).all(1)
+        if math == 0:
+            np.testing.assert_array_equal(ac[clear], ref[3][:B][clear])
+        assert ((ac >= 0) & (ac < 18)).all()
+        if B in first:            # the same call again: the same bits
+            for x, y in zip((lg, vl, pr, ac), first[B]):
+                np.testing.assert_array_equal(x, y)
+        first[B] = (lg, vl, pr, ac)
+    net.close()
+
+
 def test_train_large_net(G):
     run_train(G, G.LARGE_NET(18), 5, 5, synth.BASE_SEED + 3, dict(clip_norm=40.0))
 
