@@ -120,13 +120,14 @@ inline hipError_t launch_conv12_filter_fragments(const float *w1, const float *w
 // The body is a device function so that a second kernel can run it on one frame and go on with the rest of the
 // network: the block works on frames first, first + stride, ... below nframes.  TO_LDS: the layer-2 output of the
 // (single) frame goes to LDS instead of y2, as floats [32][81] at C12_Y2S_OFF; the caller synchronises before
-// reading it.  idle(it) is called by the layer-1 wavefronts in the
-// iterations in which they have no frame left to work on (while layer 2 runs).
-template <bool ONE, bool KEEP, bool TO_LDS, class Idle>
+// reading it.  idle(it) is called by the layer-1 wavefronts in the iterations in which they have no frame left to
+// work on (while layer 2 runs), idle2() by the layer-2 wavefronts in the first iteration, when there is no layer-1
+// output yet.
+template <bool ONE, bool KEEP, bool TO_LDS, class Idle, class Idle2>
 __device__ __forceinline__ void conv12_fused_block(const uint8_t *__restrict__ x, const u32x4 *__restrict__ frag,
                                                    const float *__restrict__ b1, const float *__restrict__ b2,
                                                    float *__restrict__ y1, float *__restrict__ y2, int first, int stride,
-                                                   int nframes, float scale, unsigned char *c12_smem, Idle idle) {
+                                                   int nframes, float scale, unsigned char *c12_smem, Idle idle, Idle2 idle2) {
     constexpr int CHW1 = 4 * 84 * 84, W1 = 84, NPIX1 = 400, OW1 = 20;
     constexpr int NV = CHW1 / 16, VPT = 7;                         // 16-byte vectors of a frame, per layer-1 thread
     constexpr int HW2 = 400, NPIX2 = 81, OW2 = 9, OC2 = 32;
@@ -281,6 +282,7 @@ __device__ __forceinline__ void conv12_fused_block(const uint8_t *__restrict__ x
                 idle(it);
             }
         } else {
+            if (TO_LDS && it == 0) idle2();
             if (it >= 2) {       // frame it - 2: add what my partner summed over its taps, bias, ReLU, store
                 const float *ex = exb + ((it - 1) & 1) * C12_EX + (rw ^ 1) * (3 * 4 * 64);
                 float *yb = TO_LDS ? (float *)(c12_smem + C12_Y2S_OFF) : y2 + (size_t)(first + (it - 2) * grid) * OC2 * NPIX2;
@@ -354,7 +356,7 @@ __global__ __launch_bounds__(512, 1) void conv12_fused_fwd_kernel(const uint8_t 
                                                                   int rb) {
     extern __shared__ __attribute__((aligned(16))) unsigned char c12_smem[];
     conv12_fused_block<ONE, KEEP, false>(x, frag, b1, b2, y1, y2, (int)blockIdx.x, (int)gridDim.x, nframes, scale,
-                                         c12_smem, [](int) {});
+                                         c12_smem, [](int) {}, []() {});
 }
 
 inline int conv12_fused_blocks(int nframes) { return nframes < 256 ? nframes : 256; }

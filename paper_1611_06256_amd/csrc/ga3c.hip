@@ -205,6 +205,30 @@ __device__ __forceinline__ void heads_stage_weights(float *hs, const int t, int 
     }
 }
 
+// The same in two steps for at most 24 * NT weights: the loads first, the stores whenever the caller has time.
+template <int NT>
+__device__ __forceinline__ void heads_load_weights(float (&wv)[24], const int t, int F, int A, const float *__restrict__ Wp,
+                                                   const float *__restrict__ Wv) {
+    const int nw = (A + 1) * F;
+#pragma unroll
+    for (int j = 0; j < 24; ++j) {
+        const int e = min(j * NT + t, nw - 1);
+        wv[j] = e < A * F ? Wp[e] : Wv[e - A * F];
+    }
+}
+template <int NT>
+__device__ __forceinline__ void heads_store_weights(float *hs, const float (&wv)[24], const int t, int F, int A, int rb) {
+    const int F4 = heads_f4(F), WP = F4 + 4;
+    float *wsh = hs + 4 * F4;
+    for (int e = t; e < (A + 1) * (WP - F); e += NT) wsh[(e / (WP - F)) * WP + F + e % (WP - F)] = 0.f;
+    const int nw = (A + 1) * F;
+#pragma unroll
+    for (int j = 0; j < 24; ++j) {
+        const int e = j * NT + t;
+        if (e < nw) wsh[(e / F) * WP + e % F] = rb ? bf16_rne(wv[j]) : wv[j];
+    }
+}
+
 // The body, for a block of NT threads (all of them must call it) that works on frames b0 .. min(b0 + 4, B) - 1;
 // hs is the block's LDS.  COHERENT: h was written by other blocks of the same launch, so it is read past the
 // caches that are not kept coherent within a launch.  WSTAGED: heads_stage_weights has already run on hs.
@@ -372,10 +396,16 @@ __global__ __launch_bounds__(256) void heads_fwd_kernel(const float *__restrict_
 // SP_SLICES times: the chip is otherwise idle), keeps the result in LDS and computes its own 256 / SP_SLICES outputs
 // of the fully connected layer, whose weight rows its idle layer-1 wavefronts fetched while layer 2 ran.  The block
 // that finishes a frame's fc outputs last (a ticket counter per frame; nobody waits for anybody) runs the heads,
-// the softmax and the draw for that frame.  h [B][256]; ticket [B] zero before the launch and zero again after it.
+// the softmax and the draw for that frame.  h [B][256]; ticket [B][SP_TICKET_PITCH], zero before the launch and zero
+// again after it.
 constexpr int SP_SLICES = 32, SP_FC = 256, SP_FLAT = 2592, SP_MAX_FRAMES = 8;
+constexpr int SP_TICKET_PITCH = 32;                        // ints between two frames' counters: a cache line each
+// LDS of the heads: the 4 KB of fc outputs end where the layer-2 output ends, the weights follow in the part of the
+// second layer-1 buffer that a single frame never touches, so that they can be staged while the convolutions run.
+constexpr size_t SP_HEADS_OFF = C12_Y2S_OFF + sizeof(float) * (SP_FLAT - 4 * SP_FC);
+constexpr size_t SP_HEADS_MAX = sizeof(__bf16) * (C12_XS + 2 * 3 * C12_Y1) - SP_HEADS_OFF;
 constexpr int SP_ROWS = SP_FC / SP_SLICES / 4;             // fc outputs per layer-1 wavefront
-constexpr int SP_WJ = (SP_FLAT + 63) / 64;                 // weights of one fc row per lane
+constexpr int SP_WJ = (SP_FLAT / 4 + 63) / 64;             // 16-byte vectors of one fc row per lane
 
 template <bool ONE>
 __global__ __launch_bounds__(512, 1) void predict_small_kernel(
@@ -391,37 +421,55 @@ __global__ __launch_bounds__(512, 1) void predict_small_kernel(
     const int frame = blockIdx.x / SP_SLICES, slice = blockIdx.x % SP_SLICES;
     const int o0 = slice * (SP_FC / SP_SLICES) + wave * SP_ROWS;        // first fc output of a layer-1 wavefront
 
-    float wreg[SP_ROWS][SP_WJ];
+    // the layer-2 wavefronts ask for the heads' weights now (with their filters, before the first barrier waits for
+    // both) and put them into LDS while layer 1 runs
+    float hw[24];
+    const bool hw_early = (A + 1) * SP_FC <= 24 * 256;
+    if (wave >= 4 && hw_early) heads_load_weights<256>(hw, tid - 256, SP_FC, A, Wp, Wv);
+    float4 wreg[SP_ROWS][SP_WJ];
+    float fbias[SP_ROWS];
     auto fetch_rows = [&](int it) {
         if (it != 1) return;
+#pragma unroll
+        for (int r = 0; r < SP_ROWS; ++r) fbias[r] = fcb[o0 + r];
+#pragma unroll
+        for (int r = 0; r < SP_ROWS; ++r)
+#pragma unroll
+            for (int j = 0; j < SP_WJ; ++j)          // rows are 16-byte aligned: the tensor starts on one and a row is 2592 floats
+                wreg[r][j] = ((const float4 *)(Wfc + (size_t)(o0 + r) * SP_FLAT))[min(lane + 64 * j, SP_FLAT / 4 - 1)];
+        // the loads happen here, while layer 2 runs, and not where the compiler finds their first use
 #pragma unroll
         for (int r = 0; r < SP_ROWS; ++r)
 #pragma unroll
             for (int j = 0; j < SP_WJ; ++j)
-                wreg[r][j] = Wfc[(size_t)(o0 + r) * SP_FLAT + min(lane + 64 * j, SP_FLAT - 1)];
+                asm volatile("" : "+v"(wreg[r][j].x), "+v"(wreg[r][j].y), "+v"(wreg[r][j].z), "+v"(wreg[r][j].w));
+#pragma unroll
+        for (int r = 0; r < SP_ROWS; ++r) asm volatile("" : "+v"(fbias[r]));
+    };
+    auto store_heads_weights = [&]() {
+        if (hw_early) heads_store_weights<256>((float *)(sp_smem + SP_HEADS_OFF), hw, tid - 256, SP_FC, A, rb);
+        else heads_stage_weights<256>((float *)(sp_smem + SP_HEADS_OFF), tid - 256, SP_FC, A, Wp, Wv, rb);
     };
     conv12_fused_block<ONE, false, true>(x, frag, b1, b2, nullptr, nullptr, frame, 1 << 24, frame + 1, scale, sp_smem,
-                                         fetch_rows);
+                                         fetch_rows, store_heads_weights);
     __syncthreads();
-    if (wave >= 4) {
-        // meanwhile the layer-2 wavefronts put the heads' weights where the block that draws the last ticket wants them
-        heads_stage_weights<256>((float *)sp_smem, tid - 256, SP_FC, A, Wp, Wv, rb);
-    } else {
+    if (wave < 4) {
         const float *y2s = (const float *)(sp_smem + C12_Y2S_OFF);
 #pragma unroll
         for (int r = 0; r < SP_ROWS; ++r) {
             float sum = 0.f;
 #pragma unroll
             for (int j = 0; j < SP_WJ; ++j) {
-                const int k = lane + 64 * j;
-                float y = y2s[min(k, SP_FLAT - 1)], w = wreg[r][j];
+                const int k4 = lane + 64 * j;
+                float4 y = ((const float4 *)y2s)[min(k4, SP_FLAT / 4 - 1)], w = wreg[r][j];
                 if (rb) { y = bf16_rne(y); w = bf16_rne(w); }
-                sum += k < SP_FLAT ? y * w : 0.f;
+                const float d = (y.x * w.x + y.y * w.y) + (y.z * w.z + y.w * w.w);
+                sum += k4 < SP_FLAT / 4 ? d : 0.f;
             }
 #pragma unroll
             for (int m = 32; m >= 1; m >>= 1) sum += __shfl_xor(sum, m, 64);
             if (lane == 0) {
-                const float v = sum + fcb[o0 + r];
+                const float v = sum + fbias[r];
                 // written through to where every compute unit sees it (a device-wide fence instead would write
                 // back and invalidate the whole L2 of this block's XCD, once per block)
                 __hip_atomic_store(h + (size_t)frame * SP_FC + o0 + r, v > 0.f ? v : 0.f, __ATOMIC_RELAXED,
@@ -431,15 +479,16 @@ __global__ __launch_bounds__(512, 1) void predict_small_kernel(
     }
     __syncthreads();                         // waits for the block's stores to be acknowledged
     if (tid == 0) {
-        const int t = __hip_atomic_fetch_add(&ticket[frame], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        int *mine = ticket + frame * SP_TICKET_PITCH;
+        const int t = __hip_atomic_fetch_add(mine, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         last = t == SP_SLICES - 1;
-        if (last) ticket[frame] = 0;         // for the next launch
+        if (last) *mine = 0;                 // for the next launch
     }
     __syncthreads();
     if (!last) return;
     // all SP_SLICES tickets are drawn, so every h of the frame has been acknowledged; the body reads h with
     // device-scope loads, which do not stop at this compute unit's cache
-    heads_fwd_body<512, true, true>((float *)sp_smem, tid, frame, nullptr, 0, fcb, h, frame + 1, SP_FC, A, Wp, bp, Wv, bv, nullptr,
+    heads_fwd_body<512, true, true>((float *)(sp_smem + SP_HEADS_OFF), tid, frame, nullptr, 0, fcb, h, frame + 1, SP_FC, A, Wp, bp, Wv, bv, nullptr,
                               logits, values, probs, uniforms, actions, rb);
 }
 
@@ -1168,8 +1217,8 @@ int forward(ga3c_ctx *c, int which, Work &w, const uint8_t *frames, int B, bool 
     const int nb = 2 * c->nconv;
     int first = 0;
     if (c->fast && c->small_predict && c->ticket && c->cfrag[which] && is_aligned16(frames) && !keep_zv && with_heads &&
-        B <= SP_MAX_FRAMES && c->nconv == 2 && c->F == SP_FC && c->flat == SP_FLAT &&
-        sizeof(float) * heads_lds_floats(c->F, c->A) <= C12_Y2S_OFF) {
+        B <= SP_MAX_FRAMES && c->nconv == 2 && c->F == SP_FC && c->flat == SP_FLAT && c->off[nb] % 4 == 0 &&
+        sizeof(float) * heads_lds_floats(c->F, c->A) <= SP_HEADS_MAX) {
         // a handful of frames: one launch for the whole network
         static bool attr_set = false;
         if (!attr_set) {
@@ -1420,9 +1469,9 @@ extern "C" int ga3c_create(const ga3c_net_desc *d, int max_predict_batch, int ma
             guard(dmalloc((void **)&c->cfrag[i], sizeof(u32x4) * 3 * C12_FRAG_SET));
             if (rc == GA3C_OK) guard(refresh_derived(c, i, nullptr));
         }
-        if (rc == GA3C_OK) guard(dmalloc((void **)&c->ticket, sizeof(int) * SP_MAX_FRAMES));
+        if (rc == GA3C_OK) guard(dmalloc((void **)&c->ticket, sizeof(int) * SP_MAX_FRAMES * SP_TICKET_PITCH));
         if (rc == GA3C_OK) {
-            const hipError_t e = hipMemset(c->ticket, 0, sizeof(int) * SP_MAX_FRAMES);
+            const hipError_t e = hipMemset(c->ticket, 0, sizeof(int) * SP_MAX_FRAMES * SP_TICKET_PITCH);
             if (e != hipSuccess) guard(fail(GA3C_EHIP, "hipMemset: %s", hipGetErrorString(e)));
         }
     }
