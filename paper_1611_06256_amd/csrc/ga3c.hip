@@ -392,22 +392,24 @@ __global__ __launch_bounds__(256) void heads_fwd_kernel(const float *__restrict_
 
 // The whole forward pass of the small network (Sec. 3.2) for a handful of frames in ONE launch, for the latency of a
 // small prediction batch (the paper's Sec. 5.2 finds the per-call overhead, not the arithmetic, dominant there).
-// SP_SLICES blocks work on each frame: every one of them runs both convolution layers of the frame (the same work
-// SP_SLICES times: the chip is otherwise idle), keeps the result in LDS and computes its own 256 / SP_SLICES outputs
-// of the fully connected layer, whose weight rows its idle layer-1 wavefronts fetched while layer 2 ran.  The block
-// that finishes a frame's fc outputs last (a ticket counter per frame; nobody waits for anybody) runs the heads,
-// the softmax and the draw for that frame.  h [B][256]; ticket [B][SP_TICKET_PITCH], zero before the launch and zero
+// SLICES blocks work on each frame (32 for up to 8 frames, 16 for up to 16: one block per compute unit either way):
+// every one of them runs both convolution layers of the frame (the same work SLICES times: the chip is otherwise
+// idle), keeps the result in LDS and computes its own 256 / SLICES outputs of the fully connected layer, two per
+// wavefront: the idle layer-1 wavefronts fetch their weight rows while layer 2 runs; with 16 slices the layer-2
+// wavefronts take two rows each as well and fetch them when they are done.  The block that finishes a frame's fc
+// outputs last (a ticket counter per frame; nobody waits for anybody) runs the heads, the softmax and the draw for
+// that frame.  h [B][256]; ticket [B][SP_TICKET_PITCH], zero before the launch and zero
 // again after it.
-constexpr int SP_SLICES = 32, SP_FC = 256, SP_FLAT = 2592, SP_MAX_FRAMES = 8;
+constexpr int SP_FC = 256, SP_FLAT = 2592, SP_MAX_FRAMES = 16;
 constexpr int SP_TICKET_PITCH = 32;                        // ints between two frames' counters: a cache line each
 // LDS of the heads: the 4 KB of fc outputs end where the layer-2 output ends, the weights follow in the part of the
 // second layer-1 buffer that a single frame never touches, so that they can be staged while the convolutions run.
 constexpr size_t SP_HEADS_OFF = C12_Y2S_OFF + sizeof(float) * (SP_FLAT - 4 * SP_FC);
 constexpr size_t SP_HEADS_MAX = sizeof(__bf16) * (C12_XS + 2 * 3 * C12_Y1) - SP_HEADS_OFF;
-constexpr int SP_ROWS = SP_FC / SP_SLICES / 4;             // fc outputs per layer-1 wavefront
+constexpr int SP_ROWS = 2;                                 // fc outputs per wavefront
 constexpr int SP_WJ = (SP_FLAT / 4 + 63) / 64;             // 16-byte vectors of one fc row per lane
 
-template <bool ONE>
+template <bool ONE, int SLICES>
 __global__ __launch_bounds__(512, 1) void predict_small_kernel(
     const uint8_t *__restrict__ x, const u32x4 *__restrict__ frag, const float *__restrict__ b1,
     const float *__restrict__ b2, const float *__restrict__ Wfc, const float *__restrict__ fcb, float *__restrict__ h,
@@ -418,8 +420,10 @@ __global__ __launch_bounds__(512, 1) void predict_small_kernel(
     __shared__ int last;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int frame = blockIdx.x / SP_SLICES, slice = blockIdx.x % SP_SLICES;
-    const int o0 = slice * (SP_FC / SP_SLICES) + wave * SP_ROWS;        // first fc output of a layer-1 wavefront
+    static_assert(SLICES * 4 * SP_ROWS == SP_FC || SLICES * 8 * SP_ROWS == SP_FC, "two fc outputs per wavefront");
+    constexpr bool ALL_WAVES_FC = SLICES * 8 * SP_ROWS == SP_FC;
+    const int frame = blockIdx.x / SLICES, slice = blockIdx.x % SLICES;
+    const int o0 = slice * (SP_FC / SLICES) + wave * SP_ROWS;           // first fc output of my wavefront
 
     // the layer-2 wavefronts ask for the heads' weights now (with their filters, before the first barrier waits for
     // both) and put them into LDS while layer 1 runs
@@ -431,12 +435,12 @@ __global__ __launch_bounds__(512, 1) void predict_small_kernel(
     auto fetch_rows = [&](int it) {
         if (it != 1) return;
 #pragma unroll
-        for (int r = 0; r < SP_ROWS; ++r) fbias[r] = fcb[o0 + r];
+        for (int r = 0; r < SP_ROWS; ++r) fbias[r] = fcb[min(o0 + r, SP_FC - 1)];
 #pragma unroll
         for (int r = 0; r < SP_ROWS; ++r)
 #pragma unroll
             for (int j = 0; j < SP_WJ; ++j)          // rows are 16-byte aligned: the tensor starts on one and a row is 2592 floats
-                wreg[r][j] = ((const float4 *)(Wfc + (size_t)(o0 + r) * SP_FLAT))[min(lane + 64 * j, SP_FLAT / 4 - 1)];
+                wreg[r][j] = ((const float4 *)(Wfc + (size_t)min(o0 + r, SP_FC - 1) * SP_FLAT))[min(lane + 64 * j, SP_FLAT / 4 - 1)];
         // the loads happen here, while layer 2 runs, and not where the compiler finds their first use
 #pragma unroll
         for (int r = 0; r < SP_ROWS; ++r)
@@ -452,8 +456,9 @@ __global__ __launch_bounds__(512, 1) void predict_small_kernel(
     };
     conv12_fused_block<ONE, false, true>(x, frag, b1, b2, nullptr, nullptr, frame, 1 << 24, frame + 1, scale, sp_smem,
                                          fetch_rows, store_heads_weights);
+    if (ALL_WAVES_FC && wave >= 4) fetch_rows(1);
     __syncthreads();
-    if (wave < 4) {
+    if (ALL_WAVES_FC || wave < 4) {
         const float *y2s = (const float *)(sp_smem + C12_Y2S_OFF);
 #pragma unroll
         for (int r = 0; r < SP_ROWS; ++r) {
@@ -481,12 +486,12 @@ __global__ __launch_bounds__(512, 1) void predict_small_kernel(
     if (tid == 0) {
         int *mine = ticket + frame * SP_TICKET_PITCH;
         const int t = __hip_atomic_fetch_add(mine, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        last = t == SP_SLICES - 1;
+        last = t == SLICES - 1;
         if (last) *mine = 0;                 // for the next launch
     }
     __syncthreads();
     if (!last) return;
-    // all SP_SLICES tickets are drawn, so every h of the frame has been acknowledged; the body reads h with
+    // all SLICES tickets are drawn, so every h of the frame has been acknowledged; the body reads h with
     // device-scope loads, which do not stop at this compute unit's cache
     heads_fwd_body<512, true, true>((float *)(sp_smem + SP_HEADS_OFF), tid, frame, nullptr, 0, fcb, h, frame + 1, SP_FC, A, Wp, bp, Wv, bv, nullptr,
                               logits, values, probs, uniforms, actions, rb);
@@ -1222,24 +1227,24 @@ int forward(ga3c_ctx *c, int which, Work &w, const uint8_t *frames, int B, bool 
         // a handful of frames: one launch for the whole network
         static bool attr_set = false;
         if (!attr_set) {
-            HIP_TRY(hipFuncSetAttribute((const void *)predict_small_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C12_LDS_BYTES));
-            HIP_TRY(hipFuncSetAttribute((const void *)predict_small_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C12_LDS_BYTES));
+            const void *ks[4] = {(const void *)predict_small_kernel<false, 32>, (const void *)predict_small_kernel<true, 32>,
+                                 (const void *)predict_small_kernel<false, 16>, (const void *)predict_small_kernel<true, 16>};
+            for (const void *k : ks) HIP_TRY(hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C12_LDS_BYTES));
             attr_set = true;
         }
         const ConvGeom &g0 = c->geom[0], &g1 = c->geom[1];
         STAGE("predict_small", 2.0 * B * (g0.OHW * g0.OC * g0.K + g1.OHW * g1.OC * g1.K + (double)c->flat * c->F + c->F * (c->A + 1)),
               (double)B * g0.CHW + 4.0 * c->flat * c->F);
-        const dim3 grid(B * SP_SLICES), block(512);
-        if (c->rb)
-            hipLaunchKernelGGL(predict_small_kernel<true>, grid, block, C12_LDS_BYTES, s, frames, c->cfrag[which], th + c->off[1],
-                               th + c->off[3], th + c->off[nb], th + c->off[nb + 1], w.h, c->ticket, c->A, th + c->off[nb + 2],
-                               th + c->off[nb + 3], th + c->off[nb + 4], th + c->off[nb + 5], logits, values, probs, uniforms,
-                               actions, 1.f / 255.f, c->rb);
-        else
-            hipLaunchKernelGGL(predict_small_kernel<false>, grid, block, C12_LDS_BYTES, s, frames, c->cfrag[which], th + c->off[1],
-                               th + c->off[3], th + c->off[nb], th + c->off[nb + 1], w.h, c->ticket, c->A, th + c->off[nb + 2],
-                               th + c->off[nb + 3], th + c->off[nb + 4], th + c->off[nb + 5], logits, values, probs, uniforms,
-                               actions, 1.f / 255.f, c->rb);
+        const int slices = B <= 8 ? 32 : 16;
+        const dim3 grid(B * slices), block(512);
+#define GA3C_SP_LAUNCH(ONE_, SL_)                                                                                              \
+    hipLaunchKernelGGL((predict_small_kernel<ONE_, SL_>), grid, block, C12_LDS_BYTES, s, frames, c->cfrag[which],             \
+                       th + c->off[1], th + c->off[3], th + c->off[nb], th + c->off[nb + 1], w.h, c->ticket, c->A,            \
+                       th + c->off[nb + 2], th + c->off[nb + 3], th + c->off[nb + 4], th + c->off[nb + 5], logits, values,    \
+                       probs, uniforms, actions, 1.f / 255.f, c->rb)
+        if (c->rb) { if (slices == 32) GA3C_SP_LAUNCH(true, 32); else GA3C_SP_LAUNCH(true, 16); }
+        else { if (slices == 32) GA3C_SP_LAUNCH(false, 32); else GA3C_SP_LAUNCH(false, 16); }
+#undef GA3C_SP_LAUNCH
         HIP_TRY(hipGetLastError());
         return GA3C_OK;
     }

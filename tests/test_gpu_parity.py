@@ -561,27 +561,27 @@ def test_ragged_argument_errors(G):
 
 @pytest.mark.parametrize("math", [0, 1])
 def test_handful_of_frames_in_one_launch(G, math):
-    # up to 8 frames of the small net go out as one kernel (convolutions, fc, heads, draw); more frames take the
-    # three-kernel path.  Both compute the same numbers up to summation order, call after call (the kernel's ticket
+    # up to 16 frames of the small net go out as one kernel (convolutions, fc, heads, draw; 32 blocks per frame up to
+    # 8 frames, 16 blocks per frame beyond); more frames take the three-kernel path.  Both compute the same numbers up to summation order, call after call (the kernel's ticket
     # counters must be back at zero after every launch), in any order of batch sizes.
     import torch
     import dataclasses
     desc = dataclasses.replace(G.SMALL_NET(18), math=math)
-    net = G.Ga3c(desc, 16, 0)
+    net = G.Ga3c(desc, 24, 0)
     net.use_generic_kernels(GENERIC)
     net.params_init(31)
-    fr = torch.from_numpy(synth.rectangle_frames(8301, 16)).cuda()
-    u = torch.from_numpy(synth.uniforms(8302, 16)).cuda()
+    fr = torch.from_numpy(synth.rectangle_frames(8301, 24)).cuda()
+    u = torch.from_numpy(synth.uniforms(8302, 24)).cuda()
     def run(B):
         lg = torch.empty(B, 18, device="cuda"); vl = torch.empty(B, device="cuda"); pr = torch.empty(B, 18, device="cuda")
         ac = torch.empty(B, dtype=torch.int32, device="cuda")
         net.predict(fr[:B].contiguous(), uniforms=u[:B].contiguous(), logits=lg, values=vl, probs=pr, actions=ac)
         torch.cuda.synchronize()
         return lg.cpu().numpy(), vl.cpu().numpy(), pr.cpu().numpy(), ac.cpu().numpy()
-    ref = run(16)
+    ref = run(24)
     tol = 1e-5 if math == 0 else TOL_FWD_BF16
     first = {}
-    for B in (3, 8, 1, 5, 8, 2, 7, 4, 6, 1, 3):
+    for B in (3, 8, 1, 16, 5, 8, 9, 2, 7, 12, 4, 6, 16, 1, 3, 9):
         print("frames", B, flush=True)
         lg, vl, pr, ac = run(B)
         assert rel_err(lg, ref[0][:B]) <= tol and rel_err(vl, ref[1][:B]) <= tol and rel_err(pr, ref[2][:B]) <= tol
