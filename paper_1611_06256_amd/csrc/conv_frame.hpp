@@ -1,13 +1,11 @@
-// Frame-resident convolution kernels for the shapes of the paper's small
-// network (Sec. 3.2: 16 filters 8x8 stride 4 on 4x84x84, then 32 filters 4x4
-// stride 2), compiled for a fixed geometry.
+// Frame-resident weight-gradient and stride-1 input-gradient kernels on the fp32
+// matrix cores, compiled for a fixed layer geometry (the layers of the networks
+// of Sec. 3.2 and of the larger network of the workload list).
 //
-// One block keeps a whole input frame and the layer's filters in LDS and walks
-// over the frames assigned to it, so that every byte of the frame is fetched
-// from HBM once and the im2col gather happens between LDS and registers.  The
-// products run on v_mfma_f32_16x16x4_f32 with the filters as the row operand
-// and 16 output pixels as the column operand, so that a lane ends up with 4
-// output channels of one pixel and stores are contiguous along pixels (NCHW).
+// One block keeps a whole input frame (and the layer's output gradient) in LDS
+// and walks over the frames assigned to it, so that every byte of the frame is
+// fetched from HBM once and the im2col gather happens between LDS and
+// registers.  The products run on v_mfma_f32_16x16x4_f32.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -24,14 +22,8 @@ struct ConvSpec {
     static constexpr int K = C * KS * KS, NPIX = OH * OW, CHW = C * H * W;
     static constexpr int NT = (NPIX + 15) / 16;      // pixel tiles per frame
     static constexpr int OT = OC / 16;               // filter tiles
-    static constexpr int WPITCH = K + 4;             // LDS row pitch of the filters (floats)
     static_assert(OC % 16 == 0 && (OT == 1 || OT == 2 || OT == 4), "filter count must be 16, 32 or 64");
     static_assert(K % 16 == 0, "filter length must be a multiple of 16");
-    // Order of the contraction index in the forward kernel.  Kernel widths 4 and 8: (c, u, v) as in memory,
-    // four consecutive taps of a filter row are fetched at once.  Other widths: (u, v, c), so that four
-    // consecutive indices are four channels of one tap; needs C to be a multiple of 16.
-    static constexpr bool TAPMAJOR = !(KS == 4 || KS == 8);
-    static_assert(!TAPMAJOR || C % 16 == 0, "tap-major order needs a multiple of 16 input channels");
     // element offset inside a frame of filter tap k = (c, u, v)
     __host__ __device__ static constexpr int koff(int k) {
         return (k / (KS * KS)) * H * W + ((k / KS) % KS) * W + (k % KS);
@@ -55,174 +47,6 @@ __device__ __forceinline__ u32x4 stage_round(u32x4 v, int rb) {
 __device__ __forceinline__ floatx4 mfma4(float a, float b, floatx4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
 }
-
-// Four consecutive taps of one filter row, as floats.
-__device__ __forceinline__ float4 lds_taps(const uint8_t *xs, int off) {
-    const uint32_t v = *(const uint32_t *)(xs + off);      // off is a multiple of 4
-    return make_float4((float)(v & 0xff), (float)((v >> 8) & 0xff), (float)((v >> 16) & 0xff), (float)(v >> 24));
-}
-__device__ __forceinline__ float4 lds_taps(const float *xs, int off) {
-    const float2 a = *(const float2 *)(xs + off);          // off is even
-    const float2 b = *(const float2 *)(xs + off + 2);
-    return make_float4(a.x, a.y, b.x, b.y);
-}
-
-// y[b][oc][pix] = max(0, scale * sum_k W[oc][k] x[b][tap k at pix] + bias[oc]).
-// Block = 4 wavefronts; frames blockIdx.x, blockIdx.x + gridDim.x, ...; filters
-// OCS * blockIdx.y .. + OCS - 1 (a layer whose filters do not fit LDS next to the
-// frame is cut into slices of OCS filters, gridDim.y = OC / OCS).
-template <class SP, int OCS = SP::OC>
-__global__ __launch_bounds__(256, 2) void conv_fwd_frame_kernel(const typename SP::TIn *__restrict__ x,
-                                                                const float *__restrict__ w,
-                                                                const float *__restrict__ bias,
-                                                                float *__restrict__ y, int nframes, float scale,
-                                                                int rb) {
-    // rb: filters and (float) frames are rounded to bfloat16 on their way to LDS
-    typedef typename SP::TIn TIn;
-    constexpr int FRAME_BYTES = SP::CHW * (int)sizeof(TIn);
-    static_assert(FRAME_BYTES % 16 == 0, "frame size must be a multiple of 16 bytes");
-    constexpr int NV = FRAME_BYTES / 16;                         // uint4 per frame
-    constexpr int VPT = (NV + 255) / 256;                        // uint4 per thread
-    constexpr int OT = OCS / 16;                                 // filter tiles of a slice
-    static_assert(OCS % 16 == 0 && SP::OC % OCS == 0, "a slice is a whole number of filter tiles");
-    constexpr int JOBS = SP::NT * OT;                            // (pixel tile, filter tile) pairs per frame
-    constexpr int TPW = (JOBS + 3) / 4;                          // pairs per wave, the last one maybe absent
-    constexpr int FULL = JOBS % 4 == 0 ? TPW : TPW - 1;          // pairs every wave has
-    constexpr int NLAST = JOBS - 4 * FULL;                       // waves that have one more
-    // the frame, padded so that every thread can store all of its VPT vectors
-    __shared__ __attribute__((aligned(16))) unsigned char xs_raw[VPT * 256 * 16];
-    __shared__ __attribute__((aligned(16))) float ws[OCS * SP::WPITCH];
-    const TIn *xs = (const TIn *)xs_raw;
-
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int l16 = lane & 15, g = lane >> 4;
-    const int ot = wave % OT;
-    const int oc0 = blockIdx.y * OCS;
-    w += (size_t)oc0 * SP::K;
-
-    // filters -> LDS, row pitch K+4 so that the 16 rows a wave reads hit different banks
-    if (!SP::TAPMAJOR) {
-        for (int e = tid; e < OCS * SP::K / 4; e += 256) {
-            const int oc = e / (SP::K / 4), kq = e % (SP::K / 4);
-            const float4 v = *(const float4 *)(w + (size_t)oc * SP::K + 4 * kq);
-            *(float4 *)(ws + oc * SP::WPITCH + 4 * kq) = rb ? bf16_rne(v) : v;
-        }
-    } else {   // position tap * C + c holds W[oc][c][tap]
-        for (int e = tid; e < OCS * SP::K; e += 256) {
-            const int oc = e / SP::K, kk = e % SP::K;
-            const int tap = kk / SP::C, c = kk % SP::C;
-            const float v = w[(size_t)oc * SP::K + c * (SP::KS * SP::KS) + tap];
-            ws[oc * SP::WPITCH + kk] = rb ? bf16_rne(v) : v;
-        }
-    }
-    float bv[4];
-#pragma unroll
-    for (int r = 0; r < 4; ++r) bv[r] = bias[oc0 + ot * 16 + 4 * g + r];
-
-    // per-lane constants: where each of my pixels starts in the frame, and the
-    // offset of my share (4g .. 4g+3) of every group of 16 taps
-    int pixbase[TPW], pixidx[TPW];
-#pragma unroll
-    for (int i = 0; i < TPW; ++i) {
-        const int job = wave + 4 * i;
-        const int pt = job / OT;
-        int p = pt * 16 + l16;
-        pixidx[i] = (job < JOBS && p < SP::NPIX) ? p : -1;
-        if (p >= SP::NPIX) p = 0;
-        pixbase[i] = (p / SP::OW) * SP::S * SP::W + (p % SP::OW) * SP::S;
-    }
-    // offset of my share (4g .. 4g+3) of a group of 16 contraction indices, and of group q
-    const int lane_koff = SP::TAPMAJOR ? 4 * g * (SP::H * SP::W) : SP::koff(4 * g);
-    auto group_koff = [](int q) {
-        if (!SP::TAPMAJOR) return SP::koff(16 * q);
-        const int tap = (16 * q) / SP::C, c = (16 * q) % SP::C;
-        return c * (SP::H * SP::W) + (tap / SP::KS) * SP::W + tap % SP::KS;
-    };
-    auto taps = [&](int off) {
-        if (!SP::TAPMAJOR) return lds_taps(xs, off);
-        return make_float4((float)xs[off], (float)xs[off + SP::H * SP::W], (float)xs[off + 2 * SP::H * SP::W],
-                           (float)xs[off + 3 * SP::H * SP::W]);
-    };
-    const float *wrow = ws + (ot * 16 + l16) * SP::WPITCH + 4 * g;
-
-    // a thread's vectors of the frame; indices past the end re-read the last one
-    int vidx[VPT];
-#pragma unroll
-    for (int i = 0; i < VPT; ++i) vidx[i] = min(tid + 256 * i, NV - 1);
-
-    u32x4 pre[VPT];
-    int f = blockIdx.x;
-    {
-        const u32x4 *src = (const u32x4 *)(x + (size_t)min(f, nframes - 1) * SP::CHW);
-#pragma unroll
-        for (int i = 0; i < VPT; ++i) pre[i] = src[vidx[i]];
-    }
-    for (; f < nframes; f += gridDim.x) {
-        __syncthreads();                       // everyone is done with the previous frame
-#pragma unroll
-        for (int i = 0; i < VPT; ++i) ((u32x4 *)xs_raw)[tid + 256 * i] = stage_round<TIn>(pre[i], rb);
-        __syncthreads();
-        {   // fetch the next frame while this one is computed
-            const u32x4 *src = (const u32x4 *)(x + (size_t)min(f + (int)gridDim.x, nframes - 1) * SP::CHW);
-#pragma unroll
-            for (int i = 0; i < VPT; ++i) pre[i] = src[vidx[i]];
-        }
-        floatx4 acc[TPW];
-#pragma unroll
-        for (int i = 0; i < TPW; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int q = 0; q < SP::K / 16; ++q) {
-            const float4 wv = *(const float4 *)(wrow + 16 * q);
-            const int ko = group_koff(q) + lane_koff;
-#pragma unroll
-            for (int i = 0; i < FULL; ++i) {
-                const float4 xv = taps(pixbase[i] + ko);
-                acc[i] = mfma4(wv.x, xv.x, acc[i]);
-                acc[i] = mfma4(wv.y, xv.y, acc[i]);
-                acc[i] = mfma4(wv.z, xv.z, acc[i]);
-                acc[i] = mfma4(wv.w, xv.w, acc[i]);
-            }
-        }
-        if (NLAST > 0 && wave < NLAST) {       // uniform per wave
-            constexpr int i = TPW - 1;
-#pragma unroll
-            for (int q = 0; q < SP::K / 16; ++q) {
-                const float4 wv = *(const float4 *)(wrow + 16 * q);
-                const float4 xv = taps(pixbase[i] + group_koff(q) + lane_koff);
-                acc[i] = mfma4(wv.x, xv.x, acc[i]);
-                acc[i] = mfma4(wv.y, xv.y, acc[i]);
-                acc[i] = mfma4(wv.z, xv.z, acc[i]);
-                acc[i] = mfma4(wv.w, xv.w, acc[i]);
-            }
-        }
-        float *yb = y + (size_t)f * SP::OC * SP::NPIX;
-#pragma unroll
-        for (int i = 0; i < TPW; ++i) {
-            if (pixidx[i] >= 0) {
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const float v = acc[i][r] * scale + bv[r];
-                    yb[(oc0 + ot * 16 + 4 * g + r) * SP::NPIX + pixidx[i]] = v > 0.f ? v : 0.f;
-                }
-            }
-        }
-    }
-}
-
-// `blocks`: how many blocks the chip holds at once (LDS decides), shared out over the slices.
-template <class SP, int OCS = SP::OC>
-inline hipError_t launch_conv_fwd_frame(const typename SP::TIn *x, const float *w, const float *bias, float *y,
-                                        int nframes, float scale, hipStream_t s, int blocks = 512, int rb = 0) {
-    if (nframes <= 0) return hipSuccess;
-    constexpr int SLICES = SP::OC / OCS;
-    const int per = blocks / SLICES;
-    const int grid = nframes < per ? nframes : per;
-    hipLaunchKernelGGL((conv_fwd_frame_kernel<SP, OCS>), dim3(grid, SLICES), dim3(256), 0, s, x, w, bias, y, nframes, scale,
-                       rb);
-    return hipGetLastError();
-}
-
 
 // Weight and bias gradient of the same layers.
 //   dW[oc][k] = sum over frames and output pixels of dY[oc][pix] * x[tap k at pix]

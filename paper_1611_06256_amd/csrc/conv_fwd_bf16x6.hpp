@@ -1,0 +1,211 @@
+// Forward pass of a convolution layer with 32 k input channels and 64 filters
+// (the second and third layers of the larger network) on the bf16 matrix cores
+// at fp32 accuracy:
+//
+//   y[oc][oy][ox] = max(0, b[oc] + sum_{c,u,v} W[oc][c][u][v] x[c][S oy + u][S ox + v])
+//
+// Activations and filters are split into three bf16 terms each (x = hi + mid + lo
+// exactly) and a product is evaluated as the six largest of the nine term
+// products (dense_gemm_bf16x6.hpp has the error argument), 6 x 16 cycles per 32 k
+// on v_mfma_f32_16x16x32_bf16 instead of 8 x 32 on the fp32 instruction.
+//
+// The contraction index is ordered (u, v, c): a k-block of 32 is 32 channels of
+// one tap.  The frame sits in LDS as [pixel][channel] per term (pitch 2 C + 16
+// bytes), so the 8 consecutive k a lane feeds to an MFMA are 8 consecutive
+// channels of one input pixel: one 16-byte LDS read per term.  With stride 2 the
+// even and the odd columns of a row are stored apart, so that the 16 output
+// pixels of a tile read 16 consecutive LDS pixels (and with them all banks)
+// instead of every other one.  A block works on
+// whole frames (blockIdx.x, + gridDim.x, ...): wavefront w computes filter tile
+// w % 4 for the pixel tiles w / 4, w / 4 + NW / 4, ... and keeps its tile's
+// filters for all k in registers as split fragments for the whole launch (that
+// is 12 registers per k-block: hence one or two wavefronts per SIMD).  The next
+// frame travels from memory while the current one is multiplied.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "conv1_bf16x3.hpp"
+
+namespace ga3c {
+
+template <class SP>
+struct ConvFwdBf16Geom {
+    static constexpr int CG = SP::C / 32;                          // channel groups of 32 per tap
+    static constexpr int KB = SP::KS * SP::KS * CG;                // k-blocks of 32
+    static constexpr int NT = (SP::NPIX + 15) / 16;                // pixel tiles
+    static constexpr int PIT = 2 * SP::C + 16;                     // bytes per input pixel and term
+    static constexpr int PLANE = SP::H * SP::W * PIT;
+    static_assert(SP::S == 1 || (SP::S == 2 && SP::W % 2 == 0), "stride 1, or stride 2 on an even width");
+    // where input pixel (row, column x) sits in a plane
+    __host__ __device__ static constexpr int pixel(int row, int xcol) {
+        return row * SP::W + (SP::S == 2 ? (xcol & 1) * (SP::W / 2) + (xcol >> 1) : xcol);
+    }
+    __host__ __device__ static constexpr int lds_bytes(bool one) { return (one ? 1 : 3) * PLANE; }
+};
+
+// NW wavefronts per block (4 or 8).  ONE: operands rounded to bfloat16 (the reduced-precision variant): one term,
+// one product.
+template <class SP, int NW, bool ONE>
+__global__ __launch_bounds__(64 * NW, 1) void conv_fwd_bf16x6_kernel(const float *__restrict__ x, const float *__restrict__ w,
+                                                                     const float *__restrict__ bias, float *__restrict__ y,
+                                                                     int nframes) {
+    typedef ConvFwdBf16Geom<SP> G;
+    static_assert(SP::C % 32 == 0 && SP::OC == 64, "32 k channels in, 64 filters out");
+    static_assert(NW == 4 || NW == 8, "one or two wavefronts per SIMD");
+    constexpr int C = SP::C, HW = SP::H * SP::W, KS = SP::KS, S = SP::S, OW = SP::OW, NPIX = SP::NPIX;
+    constexpr int CG = G::CG, KB = G::KB, NT = G::NT, PIT = G::PIT, PLANE = G::PLANE;
+    constexpr int NTERM = ONE ? 1 : 3, NTHR = 64 * NW;
+    constexpr int PG = NW / 4, TPW = (NT + PG - 1) / PG;           // pixel groups; pixel tiles per wavefront
+    constexpr int NITEM = (C / 4) * HW, DPT = (NITEM + NTHR - 1) / NTHR;      // items: 4 channels of one pixel
+    extern __shared__ __attribute__((aligned(16))) unsigned char cf_smem[];   // [term][pixel][channel] bf16
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l16 = lane & 15, g = lane >> 4;
+    const int ot = wave % 4, pg = wave / 4;
+
+    // the first frame is asked for before the filters are prepared
+    int src_off[DPT], dst_off[DPT];
+#pragma unroll
+    for (int i = 0; i < DPT; ++i) {
+        const int e = min(tid + NTHR * i, NITEM - 1);
+        const int cq = e / HW, pix = e % HW;
+        src_off[i] = 4 * cq * HW + pix;
+        dst_off[i] = G::pixel(pix / SP::W, pix % SP::W) * PIT + 8 * cq;
+    }
+    float pre[DPT][4];
+    auto fetch = [&](int f) {
+        const float *src = x + (size_t)f * SP::CHW;
+#pragma unroll
+        for (int i = 0; i < DPT; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) pre[i][j] = src[src_off[i] + j * HW];
+    };
+    int f = blockIdx.x;
+    fetch(min(f, nframes - 1));
+
+    // filter fragments of my tile: row = filter 16 ot + l16, k = (tap, channel 32 cg + 8 g .. + 7)
+    Bf16x8Bits wq[KB][NTERM];
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb) {
+        const int tap = kb / CG, cg = kb % CG, u = tap / KS, v = tap % KS;
+        Bf16x8Bits t[3];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float fw = w[((size_t)((ot * 16 + l16) * C + cg * 32 + 8 * g + j) * KS + u) * KS + v];
+            __bf16 h, m, l;
+            split3(fw, h, m, l);
+            t[0].v[j] = h; t[1].v[j] = m; t[2].v[j] = l;
+        }
+#pragma unroll
+        for (int q = 0; q < NTERM; ++q) wq[kb][q] = t[q];
+    }
+    float bv[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) bv[r] = bias[ot * 16 + 4 * g + r];
+
+    int pbyte[TPW], pidx[TPW];
+#pragma unroll
+    for (int i = 0; i < TPW; ++i) {
+        const int t = pg + PG * i;
+        int p = 16 * t + l16;
+        const bool ok = t < NT && p < NPIX;
+        if (!ok) p = 0;
+        pbyte[i] = ((p / OW) * S * SP::W + (p % OW)) * PIT + 16 * g;        // pixel (S oy, S ox) of the plane
+        pidx[i] = ok ? p : -1;
+    }
+
+    for (; f < nframes; f += gridDim.x) {
+        __syncthreads();                      // the last frame's planes have been read
+#pragma unroll
+        for (int i = 0; i < DPT; ++i)
+            if (tid + NTHR * i < NITEM) {
+                uint2 o3[3];
+                split3_pair(pre[i][0], pre[i][1], o3[0].x, o3[1].x, o3[2].x);
+                split3_pair(pre[i][2], pre[i][3], o3[0].y, o3[1].y, o3[2].y);
+#pragma unroll
+                for (int q = 0; q < NTERM; ++q) *(uint2 *)(cf_smem + q * PLANE + dst_off[i]) = o3[q];
+            }
+        __syncthreads();
+        fetch(min(f + (int)gridDim.x, nframes - 1));
+        floatx4 acc[TPW];
+#pragma unroll
+        for (int i = 0; i < TPW; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+        // pixel tiles in groups of at most four: the accumulators of a group take one term product each in turn
+        constexpr int IG = TPW <= 4 ? TPW : 3;
+#pragma unroll
+        for (int i0 = 0; i0 < TPW; i0 += IG) {
+            // the operands of k-block kb + 1 are read while the products of k-block kb run (one wavefront per SIMD:
+            // nobody else hides the LDS latency)
+            Bf16x8Bits b[2][IG][NTERM];
+            auto read_b = [&](int kb, int buf) {
+                const int tap = kb / CG, cg = kb % CG, u = tap / KS, v = tap % KS;
+                const int koff = G::pixel(u, v) * PIT + cg * 64;         // pixel (S oy + u, S ox + v) from there
+#pragma unroll
+                for (int ii = 0; ii < IG; ++ii)
+                    if (i0 + ii < TPW) {
+#pragma unroll
+                        for (int q = 0; q < NTERM; ++q)
+                            b[buf][ii][q].u = *(const u32x4 *)(cf_smem + q * PLANE + pbyte[i0 + ii] + koff);
+                    }
+            };
+            read_b(0, 0);
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) {
+                if (kb + 1 < KB) read_b(kb + 1, (kb + 1) & 1);
+                __builtin_amdgcn_sched_barrier(0);
+                constexpr int NPROD = ONE ? 1 : 6;
+                constexpr int PA[6] = {2, 1, 0, 1, 0, 0}, PB[6] = {0, 1, 2, 0, 1, 0};      // smallest products first
+#pragma unroll
+                for (int q = 0; q < NPROD; ++q) {
+                    const int ai = ONE ? 0 : PA[q], bi = ONE ? 0 : PB[q];
+#pragma unroll
+                    for (int ii = 0; ii < IG; ++ii)
+                        if (i0 + ii < TPW)
+                            acc[i0 + ii] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wq[kb][ai % NTERM].v, b[kb & 1][ii][bi % NTERM].v,
+                                                                                   acc[i0 + ii], 0, 0, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        float *yb = y + (size_t)f * SP::OC * NPIX;
+#pragma unroll
+        for (int i = 0; i < TPW; ++i)
+            if (pidx[i] >= 0) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float val = acc[i][r] + bv[r];
+                    yb[(ot * 16 + 4 * g + r) * NPIX + pidx[i]] = val > 0.f ? val : 0.f;
+                }
+            }
+    }
+}
+
+// `blocks`: how many blocks the chip holds at once.
+template <class SP, int NW>
+inline hipError_t launch_conv_fwd_bf16x6(const float *x, const float *w, const float *bias, float *y, int nframes,
+                                         hipStream_t s, int blocks, int rb = 0) {
+    if (nframes <= 0) return hipSuccess;
+    typedef ConvFwdBf16Geom<SP> G;
+    const int grid = nframes < blocks ? nframes : blocks;
+    static bool attr_set = false;          // once per layer shape: let the kernels use more than 64 KB of LDS
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)conv_fwd_bf16x6_kernel<SP, NW, false>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, G::lds_bytes(false));
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute((const void *)conv_fwd_bf16x6_kernel<SP, NW, true>,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, G::lds_bytes(true));
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    if (rb)
+        hipLaunchKernelGGL((conv_fwd_bf16x6_kernel<SP, NW, true>), dim3(grid), dim3(64 * NW), G::lds_bytes(true), s, x, w, bias, y,
+                           nframes);
+    else
+        hipLaunchKernelGGL((conv_fwd_bf16x6_kernel<SP, NW, false>), dim3(grid), dim3(64 * NW), G::lds_bytes(false), s, x, w, bias,
+                           y, nframes);
+    return hipGetLastError();
+}
+
+}  // namespace ga3c

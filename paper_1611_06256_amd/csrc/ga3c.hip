@@ -20,6 +20,7 @@
 #include "dense_gemm_bf16x6.hpp"
 #include "conv2_bf16x6.hpp"
 #include "conv12_fused.hpp"
+#include "conv_fwd_bf16x6.hpp"
 #include "conv_dgrad_bf16x6.hpp"
 
 using namespace ga3c;
@@ -1275,12 +1276,12 @@ int forward(ga3c_ctx *c, int which, Work &w, const uint8_t *frames, int B, bool 
                 HIP_TRY(launch_conv2_bf16x6_fwd((const float *)xin, wl, bl, w.act[l], B, s, c->rb));
                 continue;
             }
-            if (spec_matches<SpecL2>(g, l == 0)) {      // frame and 32 of the 64 filters in LDS: one block per CU
-                HIP_TRY((launch_conv_fwd_frame<SpecL2, 32>((const float *)xin, wl, bl, w.act[l], B, 1.f, s, 256, c->rb)));
+            if (spec_matches<SpecL2>(g, l == 0)) {      // the frame as split bf16 planes in LDS: one block per CU
+                HIP_TRY((launch_conv_fwd_bf16x6<SpecL2, 4>((const float *)xin, wl, bl, w.act[l], B, s, 256, c->rb)));
                 continue;
             }
-            if (spec_matches<SpecL3>(g, l == 0)) {      // 16 filters per block, two blocks per CU
-                HIP_TRY((launch_conv_fwd_frame<SpecL3, 16>((const float *)xin, wl, bl, w.act[l], B, 1.f, s, 512, c->rb)));
+            if (spec_matches<SpecL3>(g, l == 0)) {
+                HIP_TRY((launch_conv_fwd_bf16x6<SpecL3, 4>((const float *)xin, wl, bl, w.act[l], B, s, 256, c->rb)));
                 continue;
             }
         }
