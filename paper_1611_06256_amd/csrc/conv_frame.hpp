@@ -1,5 +1,5 @@
-// Frame-resident weight-gradient and stride-1 input-gradient kernels on the fp32
-// matrix cores, compiled for a fixed layer geometry (the layers of the networks
+// Frame-resident weight-gradient kernels on the fp32 matrix cores, compiled for
+// a fixed layer geometry (the layers of the networks
 // of Sec. 3.2 and of the larger network of the workload list).
 //
 // One block keeps a whole input frame (and the layer's output gradient) in LDS
@@ -202,132 +202,5 @@ inline hipError_t launch_conv_wgrad_frame(const typename SP::TIn *x, const float
     return hipGetLastError();
 }
 
-
-// Input gradient of a stride-1 layer:
-//   dX[c][y][x] = [xin[c][y][x] > 0] * sum_{oc,u,v} dY[oc][y-u][x-v] W[oc][c][u][v].
-// With dY padded by KS-1 zeros on every side this is a forward convolution of
-// the padded dY (OC planes) with the flipped, transposed filters
-// W'[c][oc][u'][v'] = W[oc][c][KS-1-u'][KS-1-v'], one output per input pixel.
-// The filters of CS input channels are the row operand, 16 pixels the column
-// operand, the contraction runs over (u', v', oc) with oc fastest, so that the
-// four values a lane feeds to four MFMAs are four planes at one offset.
-// Block = 4 wavefronts, (pixel tile, channel tile) pairs dealt round-robin;
-// input channels CS * blockIdx.y ..; frames blockIdx.x, + gridDim.x, ...
-template <class SP, int CS>
-__global__ __launch_bounds__(256) void conv_dgrad_s1_frame_kernel(const float *__restrict__ dy, const float *__restrict__ w,
-                                                                  const float *__restrict__ xin, float *__restrict__ dx,
-                                                                  int nframes, int rb) {
-    // rb: filters and dY are rounded to bfloat16 on their way to LDS
-    static_assert(SP::S == 1, "stride 1");
-    static_assert(SP::OC % 16 == 0 && CS % 16 == 0 && SP::C % CS == 0, "whole MFMA tiles");
-    constexpr int P = SP::KS - 1, PH = SP::OH + 2 * P, PW = SP::OW + 2 * P;
-    static_assert(PH == SP::H + P && PW == SP::W + P, "padded dY covers every window");
-    constexpr int OCP = ((PH * PW + 15) / 16) * 16 + 4;            // pitch per plane: a lane group's 4 planes are 16 banks on
-    constexpr int KP = SP::KS * SP::KS * SP::OC, WP = KP + 4;
-    constexpr int NPX = SP::H * SP::W, NT = (NPX + 15) / 16, CT = CS / 16;
-    constexpr int JOBS = NT * CT, TPW = (JOBS + 3) / 4;
-    constexpr int FULL = JOBS % 4 == 0 ? TPW : TPW - 1, NLAST = JOBS - 4 * FULL;
-    constexpr int NDY = SP::OC * SP::NPIX, DPT = (NDY + 255) / 256;
-    __shared__ __attribute__((aligned(16))) float wp[CS * WP];     // [c][(u', v', oc)]
-    __shared__ __attribute__((aligned(16))) float dp[SP::OC * OCP];
-
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int l16 = lane & 15, g = lane >> 4;
-    const int c0 = blockIdx.y * CS;
-
-    for (int e = tid; e < CS * KP; e += 256) {
-        const int c = e / KP, k = e % KP;
-        const int tap = k / SP::OC, oc = k % SP::OC;
-        const int u = P - tap / SP::KS, v = P - tap % SP::KS;
-        const float wv = w[((size_t)(oc * SP::C + c0 + c) * SP::KS + u) * SP::KS + v];
-        wp[c * WP + k] = rb ? bf16_rne(wv) : wv;
-    }
-    for (int e = tid; e < SP::OC * OCP; e += 256) dp[e] = 0.f;      // the border stays zero
-
-    int pbase[TPW], oidx[TPW], ct[TPW];
-#pragma unroll
-    for (int i = 0; i < TPW; ++i) {
-        const int job = wave + 4 * i;
-        ct[i] = job % CT;
-        int p = (job / CT) * 16 + l16;
-        const bool ok = job < JOBS && p < NPX;
-        if (p >= NPX) p = 0;
-        pbase[i] = (p / SP::W) * PW + p % SP::W + 4 * g * OCP;      // + my four planes of every group of 16
-        oidx[i] = ok ? p : -1;
-    }
-    int didx[DPT], dlds[DPT];
-#pragma unroll
-    for (int i = 0; i < DPT; ++i) {
-        const int e = min(tid + 256 * i, NDY - 1);
-        didx[i] = e;
-        const int oc = e / SP::NPIX, pix = e % SP::NPIX;
-        dlds[i] = oc * OCP + (pix / SP::OW + P) * PW + pix % SP::OW + P;
-    }
-    float dpre[DPT];
-    int f = blockIdx.x;
-    {
-        const float *dsrc = dy + (size_t)min(f, nframes - 1) * NDY;
-#pragma unroll
-        for (int i = 0; i < DPT; ++i) dpre[i] = dsrc[didx[i]];
-    }
-    for (; f < nframes; f += gridDim.x) {
-        __syncthreads();
-#pragma unroll
-        for (int i = 0; i < DPT; ++i) dp[dlds[i]] = rb ? bf16_rne(dpre[i]) : dpre[i];
-        __syncthreads();
-        {
-            const float *dsrc = dy + (size_t)min(f + (int)gridDim.x, nframes - 1) * NDY;
-#pragma unroll
-            for (int i = 0; i < DPT; ++i) dpre[i] = dsrc[didx[i]];
-        }
-        const size_t fbase = (size_t)f * SP::CHW + (size_t)c0 * NPX;
-        float mask[TPW][4];                                         // requested now, needed after the products
-#pragma unroll
-        for (int i = 0; i < TPW; ++i)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) mask[i][r] = xin[fbase + (size_t)(ct[i] * 16 + 4 * g + r) * NPX + max(oidx[i], 0)];
-        floatx4 acc[TPW];
-#pragma unroll
-        for (int i = 0; i < TPW; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
-        auto step = [&](int i, int q) {
-            const int tap = (16 * q) / SP::OC, ocb = (16 * q) % SP::OC;
-            const int qoff = ocb * OCP + (tap / SP::KS) * PW + tap % SP::KS;
-            const float4 wv = *(const float4 *)(wp + (ct[i] * 16 + l16) * WP + 16 * q + 4 * g);
-            const float *b = dp + pbase[i] + qoff;
-            acc[i] = mfma4(wv.x, b[0], acc[i]);
-            acc[i] = mfma4(wv.y, b[OCP], acc[i]);
-            acc[i] = mfma4(wv.z, b[2 * OCP], acc[i]);
-            acc[i] = mfma4(wv.w, b[3 * OCP], acc[i]);
-        };
-        // the pairs every wavefront has run in one branch-free sweep; the odd ones after it
-#pragma unroll
-        for (int q = 0; q < KP / 16; ++q)
-#pragma unroll
-            for (int i = 0; i < FULL; ++i) step(i, q);
-        if (NLAST > 0 && wave < NLAST) {                            // uniform per wave
-#pragma unroll
-            for (int q = 0; q < KP / 16; ++q) step(TPW - 1, q);
-        }
-#pragma unroll
-        for (int i = 0; i < TPW; ++i)
-            if (oidx[i] >= 0) {
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    dx[fbase + (size_t)(ct[i] * 16 + 4 * g + r) * NPX + oidx[i]] = mask[i][r] > 0.f ? acc[i][r] : 0.f;
-            }
-    }
-}
-
-template <class SP, int CS>
-inline hipError_t launch_conv_dgrad_s1_frame(const float *dy, const float *w, const float *xin, float *dx, int nframes,
-                                             hipStream_t s, int blocks, int rb) {
-    if (nframes <= 0) return hipSuccess;
-    constexpr int SLICES = SP::C / CS;
-    const int per = blocks / SLICES;
-    const int grid = nframes < per ? nframes : per;
-    hipLaunchKernelGGL((conv_dgrad_s1_frame_kernel<SP, CS>), dim3(grid, SLICES), dim3(256), 0, s, dy, w, xin, dx, nframes, rb);
-    return hipGetLastError();
-}
 
 }  // namespace ga3c

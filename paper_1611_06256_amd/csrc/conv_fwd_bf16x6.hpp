@@ -21,11 +21,21 @@
 // filters for all k in registers as split fragments for the whole launch (that
 // is 12 registers per k-block: hence one or two wavefronts per SIMD).  The next
 // frame travels from memory while the current one is multiplied.
+//
+// The input gradient of a stride-1 layer is the same computation with other
+// operands (DGRAD): dX = [xin > 0] * (dY zero-padded by KS - 1 on every side,
+// convolved with the filters flipped in both directions and transposed),
+//   dX[c][y][x] = sum_{oc,u,v} dY[oc][y - u][x - v] W[oc][c][u][v].
+// The kernel is then instantiated on that pseudo-layer: SP::C = the layer's
+// filter count, SP::H x SP::W = the padded dY, SP::OC = the layer's input
+// channels, SP::OH x SP::OW = the layer's input size; the border of the LDS
+// planes is zeroed once and only the interior is staged.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
 #include "conv1_bf16x3.hpp"
+#include "conv_frame.hpp"
 
 namespace ga3c {
 
@@ -45,10 +55,11 @@ struct ConvFwdBf16Geom {
 };
 
 // NW wavefronts per block (4 or 8).  ONE: operands rounded to bfloat16 (the reduced-precision variant): one term,
-// one product.
-template <class SP, int NW, bool ONE>
+// one product.  DGRAD: x = dY [SP::C][SP::H - 2 PAD][SP::W - 2 PAD], w = the layer's filters [SP::C][SP::OC][KS][KS],
+// aux = the layer's input (ReLU mask), y = dX; otherwise aux = bias.
+template <class SP, int NW, bool ONE, bool DGRAD>
 __global__ __launch_bounds__(64 * NW, 1) void conv_fwd_bf16x6_kernel(const float *__restrict__ x, const float *__restrict__ w,
-                                                                     const float *__restrict__ bias, float *__restrict__ y,
+                                                                     const float *__restrict__ aux, float *__restrict__ y,
                                                                      int nframes) {
     typedef ConvFwdBf16Geom<SP> G;
     static_assert(SP::C % 32 == 0 && SP::OC == 64, "32 k channels in, 64 filters out");
@@ -57,7 +68,10 @@ __global__ __launch_bounds__(64 * NW, 1) void conv_fwd_bf16x6_kernel(const float
     constexpr int CG = G::CG, KB = G::KB, NT = G::NT, PIT = G::PIT, PLANE = G::PLANE;
     constexpr int NTERM = ONE ? 1 : 3, NTHR = 64 * NW;
     constexpr int PG = NW / 4, TPW = (NT + PG - 1) / PG;           // pixel groups; pixel tiles per wavefront
-    constexpr int NITEM = (C / 4) * HW, DPT = (NITEM + NTHR - 1) / NTHR;      // items: 4 channels of one pixel
+    static_assert(!DGRAD || S == 1, "input gradient: stride 1 only");
+    constexpr int PAD = DGRAD ? KS - 1 : 0;
+    constexpr int SH = SP::H - 2 * PAD, SW = SP::W - 2 * PAD, SHW = SH * SW;  // the frame as it sits in memory
+    constexpr int NITEM = (C / 4) * SHW, DPT = (NITEM + NTHR - 1) / NTHR;     // items: 4 channels of one pixel
     extern __shared__ __attribute__((aligned(16))) unsigned char cf_smem[];   // [term][pixel][channel] bf16
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -70,17 +84,17 @@ __global__ __launch_bounds__(64 * NW, 1) void conv_fwd_bf16x6_kernel(const float
 #pragma unroll
     for (int i = 0; i < DPT; ++i) {
         const int e = min(tid + NTHR * i, NITEM - 1);
-        const int cq = e / HW, pix = e % HW;
-        src_off[i] = 4 * cq * HW + pix;
-        dst_off[i] = G::pixel(pix / SP::W, pix % SP::W) * PIT + 8 * cq;
+        const int cq = e / SHW, pix = e % SHW;
+        src_off[i] = 4 * cq * SHW + pix;
+        dst_off[i] = G::pixel(pix / SW + PAD, pix % SW + PAD) * PIT + 8 * cq;
     }
     float pre[DPT][4];
     auto fetch = [&](int f) {
-        const float *src = x + (size_t)f * SP::CHW;
+        const float *src = x + (size_t)f * (C * SHW);
 #pragma unroll
         for (int i = 0; i < DPT; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) pre[i][j] = src[src_off[i] + j * HW];
+            for (int j = 0; j < 4; ++j) pre[i][j] = src[src_off[i] + j * SHW];
     };
     int f = blockIdx.x;
     fetch(min(f, nframes - 1));
@@ -93,7 +107,9 @@ __global__ __launch_bounds__(64 * NW, 1) void conv_fwd_bf16x6_kernel(const float
         Bf16x8Bits t[3];
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            const float fw = w[((size_t)((ot * 16 + l16) * C + cg * 32 + 8 * g + j) * KS + u) * KS + v];
+            const int o = ot * 16 + l16, ic = cg * 32 + 8 * g + j;
+            const float fw = DGRAD ? w[((size_t)(ic * SP::OC + o) * KS + (KS - 1 - u)) * KS + (KS - 1 - v)]
+                                   : w[((size_t)(o * C + ic) * KS + u) * KS + v];
             __bf16 h, m, l;
             split3(fw, h, m, l);
             t[0].v[j] = h; t[1].v[j] = m; t[2].v[j] = l;
@@ -103,7 +119,9 @@ __global__ __launch_bounds__(64 * NW, 1) void conv_fwd_bf16x6_kernel(const float
     }
     float bv[4];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) bv[r] = bias[ot * 16 + 4 * g + r];
+    for (int r = 0; r < 4; ++r) bv[r] = DGRAD ? 0.f : aux[ot * 16 + 4 * g + r];
+    if (DGRAD)                                // the border stays zero: staging writes the interior only
+        for (int e = tid; e < NTERM * PLANE / 16; e += NTHR) ((u32x4 *)cf_smem)[e] = u32x4{0u, 0u, 0u, 0u};
 
     int pbyte[TPW], pidx[TPW];
 #pragma unroll
@@ -129,6 +147,14 @@ __global__ __launch_bounds__(64 * NW, 1) void conv_fwd_bf16x6_kernel(const float
             }
         __syncthreads();
         fetch(min(f + (int)gridDim.x, nframes - 1));
+        float mk[DGRAD ? TPW : 1][4];
+        if (DGRAD) {
+            const float *mb = aux + (size_t)f * SP::OC * NPIX;
+#pragma unroll
+            for (int i = 0; i < TPW; ++i)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) mk[i][r] = mb[(ot * 16 + 4 * g + r) * NPIX + max(pidx[i], 0)];
+        }
         floatx4 acc[TPW];
 #pragma unroll
         for (int i = 0; i < TPW; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
@@ -176,36 +202,53 @@ __global__ __launch_bounds__(64 * NW, 1) void conv_fwd_bf16x6_kernel(const float
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const float val = acc[i][r] + bv[r];
-                    yb[(ot * 16 + 4 * g + r) * NPIX + pidx[i]] = val > 0.f ? val : 0.f;
+                    yb[(ot * 16 + 4 * g + r) * NPIX + pidx[i]] = DGRAD ? (mk[i][r] > 0.f ? val : 0.f) : (val > 0.f ? val : 0.f);
                 }
             }
     }
 }
 
 // `blocks`: how many blocks the chip holds at once.
-template <class SP, int NW>
-inline hipError_t launch_conv_fwd_bf16x6(const float *x, const float *w, const float *bias, float *y, int nframes,
-                                         hipStream_t s, int blocks, int rb = 0) {
+template <class SP, int NW, bool DGRAD>
+inline hipError_t launch_conv_bf16x6_impl(const float *x, const float *w, const float *aux, float *y, int nframes,
+                                          hipStream_t s, int blocks, int rb) {
     if (nframes <= 0) return hipSuccess;
     typedef ConvFwdBf16Geom<SP> G;
     const int grid = nframes < blocks ? nframes : blocks;
     static bool attr_set = false;          // once per layer shape: let the kernels use more than 64 KB of LDS
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)conv_fwd_bf16x6_kernel<SP, NW, false>,
+        hipError_t e = hipFuncSetAttribute((const void *)conv_fwd_bf16x6_kernel<SP, NW, false, DGRAD>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, G::lds_bytes(false));
         if (e == hipSuccess)
-            e = hipFuncSetAttribute((const void *)conv_fwd_bf16x6_kernel<SP, NW, true>,
+            e = hipFuncSetAttribute((const void *)conv_fwd_bf16x6_kernel<SP, NW, true, DGRAD>,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, G::lds_bytes(true));
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     if (rb)
-        hipLaunchKernelGGL((conv_fwd_bf16x6_kernel<SP, NW, true>), dim3(grid), dim3(64 * NW), G::lds_bytes(true), s, x, w, bias, y,
-                           nframes);
+        hipLaunchKernelGGL((conv_fwd_bf16x6_kernel<SP, NW, true, DGRAD>), dim3(grid), dim3(64 * NW), G::lds_bytes(true), s, x, w,
+                           aux, y, nframes);
     else
-        hipLaunchKernelGGL((conv_fwd_bf16x6_kernel<SP, NW, false>), dim3(grid), dim3(64 * NW), G::lds_bytes(false), s, x, w, bias,
-                           y, nframes);
+        hipLaunchKernelGGL((conv_fwd_bf16x6_kernel<SP, NW, false, DGRAD>), dim3(grid), dim3(64 * NW), G::lds_bytes(false), s, x,
+                           w, aux, y, nframes);
     return hipGetLastError();
+}
+
+template <class SP, int NW>
+inline hipError_t launch_conv_fwd_bf16x6(const float *x, const float *w, const float *bias, float *y, int nframes,
+                                         hipStream_t s, int blocks, int rb = 0) {
+    return launch_conv_bf16x6_impl<SP, NW, false>(x, w, bias, y, nframes, s, blocks, rb);
+}
+
+// Input gradient of the stride-1 layer SP: dy [n][OC][OH][OW], w the layer's filters, xin the layer's input
+// [n][C][H][W] (its ReLU mask), dx [n][C][H][W].
+template <class SP, int NW>
+inline hipError_t launch_conv_dgrad_s1_bf16x6(const float *dy, const float *w, const float *xin, float *dx, int nframes,
+                                              hipStream_t s, int blocks, int rb = 0) {
+    static_assert(SP::S == 1, "stride 1");
+    typedef ConvSpec<float, SP::OC, SP::OH + 2 * (SP::KS - 1), SP::OW + 2 * (SP::KS - 1), SP::C, SP::KS, 1> Pseudo;
+    static_assert(Pseudo::OH == SP::H && Pseudo::OW == SP::W, "the padded correlation gives back the input size");
+    return launch_conv_bf16x6_impl<Pseudo, NW, true>(dy, w, xin, dx, nframes, s, blocks, rb);
 }
 
 }  // namespace ga3c

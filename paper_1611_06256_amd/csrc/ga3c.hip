@@ -1825,7 +1825,7 @@ static int train_step_impl(ga3c_ctx *c, const uint8_t *frames, const int32_t *ac
             continue;
         }
         if (c->fast && spec_matches<SpecL3>(g, false)) {
-            HIP_TRY((launch_conv_dgrad_s1_frame<SpecL3, 32>(c->dact[l], th + c->off[2 * l], w.act[l - 1], c->dact[l - 1], B, s, 256, c->rb)));
+            HIP_TRY((launch_conv_dgrad_s1_bf16x6<SpecL3, 4>(c->dact[l], th + c->off[2 * l], w.act[l - 1], c->dact[l - 1], B, s, 256, c->rb)));
             continue;
         }
         // general shapes: one launch per stride phase
