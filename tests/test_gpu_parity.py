@@ -302,10 +302,13 @@ def test_predict_follows_a_large_update(G):
     net.close()
 
 
-def test_predictions_on_one_stream_while_training_on_another(G):
+@pytest.mark.parametrize("PB", [64, 8])
+def test_predictions_on_one_stream_while_training_on_another(G, PB):
     # the way the benchmark and the scheduler submit work (Sec. 4.1: predictors and trainers share the GPU): every
     # prediction must see one whole parameter set, the one before or the one after the update, never a mixture,
-    # and the update itself must not be disturbed by the predictions reading next to it
+    # and the update itself must not be disturbed by the predictions reading next to it.  PB frames per prediction:
+    # 64 go through the three-kernel path, 8 through the one-launch kernel (which reads the filter fragments that
+    # the update's last kernel rewrites).
     import torch
     N, T, A = 64, 5, 18
     desc = G.SMALL_NET(A)
@@ -316,7 +319,7 @@ def test_predictions_on_one_stream_while_training_on_another(G):
     hp_kw = dict(lr=0.02)               # large, so that the two parameter sets give visibly different outputs
     ref = orc.train_step(onet, theta.astype(np.float64), np.zeros(net.n_params), frames, tr["actions"], tr["rewards"],
                          tr["dones"], boot.astype(np.float64), orc.HParams(**hp_kw))
-    pf = [frames[:, t] for t in range(T)]
+    pf = [frames[:PB, t] for t in range(T)]
     want = [(orc.forward(onet, theta.astype(np.float64), f)["logits"], orc.forward(onet, ref["theta"], f)["logits"])
             for f in pf]
     assert all(rel_err(a, b) > 1e-2 for a, b in want)
@@ -324,7 +327,7 @@ def test_predictions_on_one_stream_while_training_on_another(G):
              rewards=torch.from_numpy(tr["rewards"]).cuda(), dones=torch.from_numpy(tr["dones"]).cuda())
     boot_t = torch.from_numpy(boot).cuda()
     pft = [torch.from_numpy(np.ascontiguousarray(f)).cuda() for f in pf]
-    outs = [torch.full((N, A), float("nan"), device="cuda") for _ in range(3 * T)]
+    outs = [torch.full((PB, A), float("nan"), device="cuda") for _ in range(3 * T)]
     sp, st = torch.cuda.Stream(), torch.cuda.Stream()
     torch.cuda.synchronize()
     print("predictions and a training step on two streams", flush=True)
