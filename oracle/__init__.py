@@ -221,6 +221,50 @@ def backward(net: Net, theta, acts, dZ, dV) -> np.ndarray:
     return grad
 
 
+def conv_layer_forward(x, W, bias, stride: int, math: int = 0, xs: float = 1.0) -> np.ndarray:
+    """One convolution layer + ReLU on x [B,C,H,W] (the stored input; xs = 255 for the first layer of math = 1)."""
+    x = _f64(x); W = _f64(W); bias = _f64(bias)
+    B, Cc, H, Wd = x.shape
+    OC, _, K, _ = W.shape
+    y = np.zeros((B, OC, (H - K) // stride + 1, (Wd - K) // stride + 1))
+    lib().orc_conv_layer_forward(C.c_int(B), _p(x), C.c_int(Cc), C.c_int(H), C.c_int(Wd), _p(W), _p(bias), C.c_int(OC),
+                                 C.c_int(K), C.c_int(stride), C.c_int(math), C.c_double(xs), _p(y))
+    return y
+
+
+def conv_layer_backward(x, W, stride: int, y, dy, math: int = 0, xs: float = 1.0, want_dx: bool = True):
+    """Backward of one convolution layer: (gW, gb, dx).  dy is taken before the layer's ReLU mask (from y)."""
+    x = _f64(x); W = _f64(W); y = _f64(y); dy = _f64(dy)
+    B, Cc, H, Wd = x.shape
+    OC, _, K, _ = W.shape
+    gW = np.zeros(W.shape); gb = np.zeros(OC); dx = np.zeros(x.shape) if want_dx else None
+    lib().orc_conv_layer_backward(C.c_int(B), _p(x), C.c_int(Cc), C.c_int(H), C.c_int(Wd), _p(W), C.c_int(OC), C.c_int(K),
+                                  C.c_int(stride), _p(y), _p(dy), C.c_int(math), C.c_double(xs), _p(gW), _p(gb), _p(dx))
+    return gW, gb, dx
+
+
+def dense_forward(x, W, bias, relu: bool, math: int = 0) -> np.ndarray:
+    """x [B,I], W [O,I], bias [O] -> [B,O]."""
+    x = _f64(x); W = _f64(W); bias = _f64(bias)
+    B, I = x.shape
+    O = W.shape[0]
+    y = np.zeros((B, O))
+    lib().orc_dense_forward(C.c_int(B), _p(x), C.c_int64(I), _p(W), _p(bias), C.c_int(O), C.c_int(int(relu)),
+                            C.c_int(math), _p(y))
+    return y
+
+
+def dense_backward(x, W, dy, math: int = 0, want_dx: bool = True):
+    """Backward of a fully connected layer: (gW, gb, dx) for dy [B,O] = dL/d(pre-activation)."""
+    x = _f64(x); W = _f64(W); dy = _f64(dy)
+    B, I = x.shape
+    O = W.shape[0]
+    gW = np.zeros((O, I)); gb = np.zeros(O); dx = np.zeros((B, I)) if want_dx else None
+    lib().orc_dense_backward(C.c_int(B), _p(x), C.c_int64(I), _p(W), C.c_int(O), _p(dy), C.c_int(math),
+                             _p(gW), _p(gb), _p(dx))
+    return gW, gb, dx
+
+
 def bf16_round(values) -> np.ndarray:
     """Nearest bfloat16, ties to even, of every element (the rounding math = 1 applies to operands)."""
     L = lib()

@@ -164,6 +164,19 @@ static void conv_relu(const double *x, int C, int H, int W,
             }
 }
 
+/* Fully connected layer of one frame: y[o] = bias[o] + sum_i W[o][i] x[i],
+ * followed by the rectifier when relu != 0 (Sec. 3.2).  bf != 0: both operands
+ * of every product rounded to bfloat16. */
+static void dense(const double *x, int64_t I, const double *W, const double *bias, int O,
+                  int relu, int bf, double *y) {
+    for (int o = 0; o < O; ++o) {
+        double acc = bias[o];
+        if (!bf) for (int64_t i = 0; i < I; ++i) acc += W[o * I + i] * x[i];
+        else for (int64_t i = 0; i < I; ++i) acc += Q(W[o * I + i]) * Q(x[i]);
+        y[o] = (relu && !(acc > 0.0)) ? 0.0 : acc;
+    }
+}
+
 static void softmax(const double *z, int A, double *p) {
     double m = z[0];
     for (int j = 1; j < A; ++j) if (z[j] > m) m = z[j];
@@ -196,22 +209,9 @@ static void forward_one(const orc_net *net, const double *theta, const int64_t *
     int F = net->fc_units, A = net->n_actions;
     double *hfc = cur + cur_sz;
     const int q = net->math;
-    for (int o = 0; o < F; ++o) {
-        double acc = bf[o];
-        if (!q) for (int64_t i = 0; i < cur_sz; ++i) acc += Wf[o * cur_sz + i] * cur[i];
-        else for (int64_t i = 0; i < cur_sz; ++i) acc += Q(Wf[o * cur_sz + i]) * Q(cur[i]);
-        hfc[o] = acc > 0.0 ? acc : 0.0;
-    }
-    for (int a = 0; a < A; ++a) {
-        double acc = bp[a];
-        if (!q) for (int i = 0; i < F; ++i) acc += Wp[a * F + i] * hfc[i];
-        else for (int i = 0; i < F; ++i) acc += Q(Wp[a * F + i]) * Q(hfc[i]);
-        logits[a] = acc;
-    }
-    double v = bv[0];
-    if (!q) for (int i = 0; i < F; ++i) v += Wv[i] * hfc[i];
-    else for (int i = 0; i < F; ++i) v += Q(Wv[i]) * Q(hfc[i]);
-    *value = v;
+    dense(cur, cur_sz, Wf, bf, F, 1, q, hfc);
+    dense(hfc, F, Wp, bp, A, 0, q, logits);
+    dense(hfc, F, Wv, bv, 1, 0, q, value);
     if (probs) softmax(logits, A, probs);
 }
 
@@ -321,6 +321,72 @@ void orc_loss_grad(const double *logits, const double *values, const int32_t *ac
 
 /* ---- backward ----------------------------------------------------------- */
 
+/* Backward of a fully connected layer for one frame, by the chain rule:
+ * dy[O] = dL/d(pre-activation).  ADDS gW[o][i] += dy[o] x[i], gb[o] += dy[o]
+ * and, when dx is not NULL, dx[i] += sum_o dy[o] W[o][i] (rows in order).
+ * bf != 0: operands of every product rounded to bfloat16; the bias gradient is
+ * the product with ones, so its terms are the rounded dy. */
+static void dense_backward(const double *x, int64_t I, const double *W, int O, const double *dy,
+                           int bf, double *gW, double *gb, double *dx) {
+    for (int o = 0; o < O; ++o) {
+        if (!bf) {
+            gb[o] += dy[o];
+            for (int64_t i = 0; i < I; ++i) {
+                gW[o * I + i] += dy[o] * x[i];
+                if (dx) dx[i] += dy[o] * W[o * I + i];
+            }
+        } else {
+            const double d = Q(dy[o]);
+            gb[o] += d;
+            for (int64_t i = 0; i < I; ++i) {
+                gW[o * I + i] += d * Q(x[i]);
+                if (dx) dx[i] += d * Q(W[o * I + i]);
+            }
+        }
+    }
+}
+
+/* Backward of one convolution layer for one frame (the transposes of
+ * conv_relu): y is the layer's output (post-ReLU, gives the mask), dy the
+ * gradient w.r.t. that output before the mask is applied.  ADDS to gw and gb;
+ * dx (may be NULL: the first layer's input is data) must be zero on entry and
+ * receives the gradient w.r.t. the layer's input.  bf, xs as in conv_relu: the
+ * first layer multiplies the raw bytes and divides by xs afterwards. */
+static void conv_backward(const double *x, int C, int H, int W, const double *wt, int OC, int K, int S,
+                          const double *y, const double *dy, int bf, double xs,
+                          double *gw, double *gb, double *dx) {
+    int OH = (H - K) / S + 1, OW = (W - K) / S + 1;
+    for (int o = 0; o < OC; ++o)
+        for (int i = 0; i < OH; ++i)
+            for (int j = 0; j < OW; ++j) {
+                int64_t yi = (o * OH + i) * OW + j;
+                if (!(y[yi] > 0.0)) continue;          /* ReLU */
+                double d = dy[yi];
+                if (bf) {
+                    d = Q(d);
+                    gb[o] += d;
+                    for (int cc = 0; cc < C; ++cc)
+                        for (int u = 0; u < K; ++u)
+                            for (int v = 0; v < K; ++v) {
+                                int64_t wi = ((o * C + cc) * K + u) * K + v;
+                                int64_t xi = (cc * H + i * S + u) * W + j * S + v;
+                                gw[wi] += d * Q(xs * x[xi]) / xs;
+                                if (dx) dx[xi] += d * Q(wt[wi]);
+                            }
+                    continue;
+                }
+                gb[o] += d;
+                for (int cc = 0; cc < C; ++cc)
+                    for (int u = 0; u < K; ++u)
+                        for (int v = 0; v < K; ++v) {
+                            int64_t wi = ((o * C + cc) * K + u) * K + v;
+                            int64_t xi = (cc * H + i * S + u) * W + j * S + v;
+                            gw[wi] += d * x[xi];
+                            if (dx) dx[xi] += d * wt[wi];
+                        }
+            }
+}
+
 /* Gradient of one frame's loss w.r.t. all parameters, ADDED into grad.
  * dz[A], dv are dL/dlogits and dL/dvalue for this frame. */
 static void backward_one(const orc_net *net, const double *theta, const int64_t *off,
@@ -338,55 +404,19 @@ static void backward_one(const orc_net *net, const double *theta, const int64_t 
         layer_in[l] = acts + pos; pos += (int64_t)cc * hh * ww;
     }
     const double *hfc = acts + pos;
-    const double *Wf = theta + off[nb];
-    const double *Wp = theta + off[nb + 2], *Wv = theta + off[nb + 4];
-    double *gWf = grad + off[nb], *gbf = grad + off[nb + 1];
-    double *gWp = grad + off[nb + 2], *gbp = grad + off[nb + 3];
-    double *gWv = grad + off[nb + 4], *gbv = grad + off[nb + 5];
-
     const int q = net->math;
-    /* heads */
+
+    /* heads: policy rows first, then the value row */
     double *dh = scratch;                    /* F */
     for (int i = 0; i < F; ++i) dh[i] = 0.0;
-    if (!q) {
-        for (int a = 0; a < A; ++a) {
-            gbp[a] += dz[a];
-            for (int i = 0; i < F; ++i) { gWp[a * F + i] += dz[a] * hfc[i]; dh[i] += dz[a] * Wp[a * F + i]; }
-        }
-        gbv[0] += dv;
-        for (int i = 0; i < F; ++i) { gWv[i] += dv * hfc[i]; dh[i] += dv * Wv[i]; }
-    } else {
-        for (int a = 0; a < A; ++a) {
-            const double da = Q(dz[a]);
-            gbp[a] += da;
-            for (int i = 0; i < F; ++i) { gWp[a * F + i] += da * Q(hfc[i]); dh[i] += da * Q(Wp[a * F + i]); }
-        }
-        const double dq = Q(dv);
-        gbv[0] += dq;
-        for (int i = 0; i < F; ++i) { gWv[i] += dq * Q(hfc[i]); dh[i] += dq * Q(Wv[i]); }
-    }
+    dense_backward(hfc, F, theta + off[nb + 2], A, dz, q, grad + off[nb + 2], grad + off[nb + 3], dh);
+    dense_backward(hfc, F, theta + off[nb + 4], 1, &dv, q, grad + off[nb + 4], grad + off[nb + 5], dh);
     for (int i = 0; i < F; ++i) if (!(hfc[i] > 0.0)) dh[i] = 0.0;   /* ReLU of fc */
 
     /* fc */
-    const double *xin = layer_in[net->n_conv];
     double *dcur = scratch + F;              /* gradient w.r.t. current layer input */
     for (int64_t i = 0; i < flat; ++i) dcur[i] = 0.0;
-    for (int o = 0; o < F; ++o) {
-        if (!q) {
-            gbf[o] += dh[o];
-            for (int64_t i = 0; i < flat; ++i) {
-                gWf[o * flat + i] += dh[o] * xin[i];
-                dcur[i] += dh[o] * Wf[o * flat + i];
-            }
-        } else {
-            const double d = Q(dh[o]);
-            gbf[o] += d;
-            for (int64_t i = 0; i < flat; ++i) {
-                gWf[o * flat + i] += d * Q(xin[i]);
-                dcur[i] += d * Q(Wf[o * flat + i]);
-            }
-        }
-    }
+    dense_backward(layer_in[net->n_conv], flat, theta + off[nb], F, dh, q, grad + off[nb], grad + off[nb + 1], dcur);
 
     /* conv layers, last to first.  dcur holds dL/d(output of conv l) before
      * that layer's ReLU mask.  The two buffers swap roles per layer, so each
@@ -399,45 +429,12 @@ static void backward_one(const orc_net *net, const double *theta, const int64_t 
     double *dprev = dcur + maxsz;
     for (int l = net->n_conv - 1; l >= 0; --l) {
         int C, H, W; layer_in_shape(net, l, &C, &H, &W);
-        int OC = net->oc[l], K = net->k[l], S = net->stride[l];
-        int OH = (H - K) / S + 1, OW = (W - K) / S + 1;
-        const double *y = layer_in[l + 1];
-        const double *x = layer_in[l];
-        const double *wt = theta + off[2 * l];
-        double *gw = grad + off[2 * l], *gb = grad + off[2 * l + 1];
         int64_t in_sz = (int64_t)C * H * W;
         if (l > 0) for (int64_t i = 0; i < in_sz; ++i) dprev[i] = 0.0;
-        for (int o = 0; o < OC; ++o)
-            for (int i = 0; i < OH; ++i)
-                for (int j = 0; j < OW; ++j) {
-                    int64_t yi = (o * OH + i) * OW + j;
-                    if (!(y[yi] > 0.0)) continue;          /* ReLU */
-                    double d = dcur[yi];
-                    if (q) {        /* operands rounded; the first layer multiplies the raw bytes */
-                        const double xs = l == 0 ? 255.0 : 1.0;
-                        d = Q(d);
-                        gb[o] += d;
-                        for (int cc = 0; cc < C; ++cc)
-                            for (int u = 0; u < K; ++u)
-                                for (int v = 0; v < K; ++v) {
-                                    int64_t wi = ((o * C + cc) * K + u) * K + v;
-                                    int64_t xi = (cc * H + i * S + u) * W + j * S + v;
-                                    gw[wi] += d * Q(xs * x[xi]) / xs;
-                                    if (l > 0) dprev[xi] += d * Q(wt[wi]);
-                                }
-                        continue;
-                    }
-                    gb[o] += d;
-                    for (int cc = 0; cc < C; ++cc)
-                        for (int u = 0; u < K; ++u)
-                            for (int v = 0; v < K; ++v) {
-                                int64_t wi = ((o * C + cc) * K + u) * K + v;
-                                int64_t xi = (cc * H + i * S + u) * W + j * S + v;
-                                gw[wi] += d * x[xi];
-                                if (l > 0) dprev[xi] += d * wt[wi];
-                            }
-                }
         /* the input of layer 0 is data: no gradient needed */
+        conv_backward(layer_in[l], C, H, W, theta + off[2 * l], net->oc[l], net->k[l], net->stride[l],
+                      layer_in[l + 1], dcur, q, l == 0 ? 255.0 : 1.0,
+                      grad + off[2 * l], grad + off[2 * l + 1], l > 0 ? dprev : NULL);
         double *t = dcur; dcur = dprev; dprev = t;
     }
 }
@@ -547,4 +544,54 @@ int orc_train_step(const orc_net *net, double *theta, double *g, double *grad,
     }
     free(acts); free(logits); free(values); free(R); free(dZ); free(dV);
     return rc;
+}
+
+/* ---- single layers, batched ---------------------------------------------- */
+
+/* The layers above one at a time, so that a test can hand each layer the
+ * inputs another implementation actually used (for math = 1 this makes both
+ * sides round the same numbers).  They call the same routines as the whole
+ * network, frame by frame in index order.
+ *
+ * Convolution: x [B][C][H][W] is the layer's stored input (for the first layer
+ * byte / 255, with xs = 255; otherwise xs = 1), y [B][OC][OH][OW]. */
+void orc_conv_layer_forward(int B, const double *x, int C, int H, int W, const double *wt,
+                            const double *bias, int OC, int K, int S, int math, double xs, double *y) {
+    int OH = (H - K) / S + 1, OW = (W - K) / S + 1;
+#pragma omp parallel for schedule(static)
+    for (int b = 0; b < B; ++b)
+        conv_relu(x + (int64_t)b * C * H * W, C, H, W, wt, bias, OC, K, S, y + (int64_t)b * OC * OH * OW, math, xs);
+}
+
+/* gw [OC][C][K][K] and gb [OC] are overwritten with the sums over the frames;
+ * dx [B][C][H][W] (may be NULL) is overwritten.  dy is taken before the
+ * layer's ReLU mask, which comes from y. */
+void orc_conv_layer_backward(int B, const double *x, int C, int H, int W, const double *wt, int OC,
+                             int K, int S, const double *y, const double *dy, int math, double xs,
+                             double *gw, double *gb, double *dx) {
+    int OH = (H - K) / S + 1, OW = (W - K) / S + 1;
+    int64_t in_sz = (int64_t)C * H * W, out_sz = (int64_t)OC * OH * OW;
+    for (int64_t i = 0; i < (int64_t)OC * C * K * K; ++i) gw[i] = 0.0;
+    for (int o = 0; o < OC; ++o) gb[o] = 0.0;
+    if (dx) for (int64_t i = 0; i < B * in_sz; ++i) dx[i] = 0.0;
+    for (int b = 0; b < B; ++b)
+        conv_backward(x + b * in_sz, C, H, W, wt, OC, K, S, y + b * out_sz, dy + b * out_sz, math, xs,
+                      gw, gb, dx ? dx + b * in_sz : NULL);
+}
+
+/* x [B][I], W [O][I], bias [O] -> y [B][O]. */
+void orc_dense_forward(int B, const double *x, int64_t I, const double *W, const double *bias, int O,
+                       int relu, int math, double *y) {
+    for (int b = 0; b < B; ++b) dense(x + b * I, I, W, bias, O, relu, math, y + (int64_t)b * O);
+}
+
+/* dy [B][O] = dL/d(pre-activation).  gW [O][I], gb [O] are overwritten with the
+ * sums over the frames, dx [B][I] (may be NULL) is overwritten. */
+void orc_dense_backward(int B, const double *x, int64_t I, const double *W, int O, const double *dy,
+                        int math, double *gW, double *gb, double *dx) {
+    for (int64_t i = 0; i < O * I; ++i) gW[i] = 0.0;
+    for (int o = 0; o < O; ++o) gb[o] = 0.0;
+    if (dx) for (int64_t i = 0; i < B * I; ++i) dx[i] = 0.0;
+    for (int b = 0; b < B; ++b)
+        dense_backward(x + b * I, I, W, O, dy + (int64_t)b * O, math, gW, gb, dx ? dx + b * I : NULL);
 }

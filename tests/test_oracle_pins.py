@@ -579,3 +579,216 @@ def test_bf16_variant_backward_is_linear_in_rounded_operands():
     flat = fw["acts"][0, -F - g["fc.W"].shape[1]:-F]
     np.testing.assert_allclose(g["fc.W"], np.outer(q(dh), q(flat)), rtol=1e-12, atol=1e-15)
     np.testing.assert_allclose(g["fc.b"], q(dh), rtol=0, atol=0)
+
+
+# ---- math = 1, layer by layer: the same layers built by hand from library routines, with a switch per operand ----
+#
+# The whole-network comparison of the GPU library with math = 1 cannot be sharp: the two sides round numbers that
+# differ in their last fp32 bits, so now and then an operand goes to different bfloat16 neighbours.  The GPU tests
+# therefore also compare layer by layer, handing the oracle's single-layer functions the inputs the library itself
+# used; then both sides round the same numbers and only fp32 accumulation separates them.  The tests below pin those
+# single-layer functions (and through them the math = 1 branches of the whole backward pass, convolutions included)
+# to torch's fp64 convolution / matmul routines applied to operands rounded by torch's own bfloat16 conversion, and
+# show that the layer-by-layer bound used on the GPU (STAGE_TOL_BF16) would catch any operand class left unrounded.
+
+STAGE_TOL_BF16 = 5e-5          # the bound tests/test_gpu_parity.py uses for every single-layer output with math = 1
+
+
+def _tq(t):
+    return t.to(torch.float32).to(torch.bfloat16).to(torch.float64)
+
+
+def _r(skip, name, t):
+    return t if name == skip else _tq(t)
+
+
+def hand_conv_fwd(x, W, b, s, xs, skip=None):
+    T = torch.from_numpy
+    y = torch.nn.functional.conv2d(_r(skip, "x", T(x) * xs), _r(skip, "w", T(W)), None, stride=s) / xs
+    return torch.clamp(y + T(b)[None, :, None, None], min=0).numpy()
+
+
+def hand_dense_fwd(x, W, b, relu, skip=None):
+    T = torch.from_numpy
+    y = _r(skip, "x", T(x)) @ _r(skip, "w", T(W)).T + T(b)
+    return (torch.clamp(y, min=0) if relu else y).numpy()
+
+
+def hand_conv_bwd(x, W, s, y, dy, xs, skip=None, want_dx=True):
+    T = torch.from_numpy
+    d = _r(skip, "dy", T(dy) * (T(y) > 0))
+    gW = torch.nn.grad.conv2d_weight(_r(skip, "x", T(x) * xs), W.shape, d, stride=s) / xs
+    dx = torch.nn.grad.conv2d_input(x.shape, _r(skip, "w", T(W)), d, stride=s).numpy() if want_dx else None
+    return gW.numpy(), d.sum((0, 2, 3)).numpy(), dx
+
+
+def hand_dense_bwd(x, W, dy, skip=None):
+    T = torch.from_numpy
+    d = _r(skip, "dy", T(dy))
+    return (d.T @ _r(skip, "x", T(x))).numpy(), d.sum(0).numpy(), (d @ _r(skip, "w", T(W))).numpy()
+
+
+def _split_acts(net, acts):
+    """The saved activations of orc.forward as per-layer arrays: inputs of every conv layer, fc input, fc output."""
+    shapes = [(net.in_c, net.in_h, net.in_w)]
+    for (oc, k, s) in net.conv:
+        _, h, w = shapes[-1]
+        shapes.append((oc, (h - k) // s + 1, (w - k) // s + 1))
+    out, pos = [], 0
+    for sh in shapes:
+        n = int(np.prod(sh))
+        out.append(acts[:, pos:pos + n].reshape((-1,) + sh)); pos += n
+    return out, acts[:, pos:]
+
+
+def _relmax(a, b):
+    return np.abs(a - b).max() / max(np.abs(b).max(), 1e-300)
+
+
+def _layerwise_case(net0, N, T, seed):
+    net = _bf16_net(net0)
+    th = theta_for(net, seed)
+    frames, tr, boot = train_inputs(net, seed + 1, N, T)
+    ref = orc.train_step(net, th, np.zeros_like(th), frames, tr["actions"], tr["rewards"], tr["dones"], boot, orc.HParams())
+    fr = frames.reshape((-1,) + frames.shape[2:])
+    fw = orc.forward(net, th, fr, want_acts=True)
+    return net, th, fr, fw, ref
+
+
+@pytest.mark.parametrize("math", [0, 1])
+@pytest.mark.parametrize("net0,N,T", [(TINY, 3, 4), (TINY3, 4, 3)])
+def test_single_layer_functions_chain_to_the_whole_network(net0, N, T, math):
+    # forward and backward assembled from the single-layer functions reproduce orc.forward / orc.backward, and every
+    # single layer equals the hand-built one (torch fp64 routines on operands rounded by torch)
+    net = _bf16_net(net0) if math else net0
+    th = theta_for(net, 171)
+    frames, tr, boot = train_inputs(net, 172, N, T)
+    fr = frames.reshape((-1,) + frames.shape[2:])
+    fw = orc.forward(net, th, fr, want_acts=True)
+    acts, hfc = _split_acts(net, fw["acts"])
+    v = orc.views(net, th)
+    x = acts[0]
+    for l, (oc, k, s) in enumerate(net.conv):
+        xs = 255.0 if l == 0 else 1.0
+        y = orc.conv_layer_forward(x, v[f"conv{l + 1}.W"], v[f"conv{l + 1}.b"], s, math, xs)
+        np.testing.assert_array_equal(y, acts[l + 1])
+        if math:
+            np.testing.assert_allclose(hand_conv_fwd(x, v[f"conv{l + 1}.W"], v[f"conv{l + 1}.b"], s, xs), y, rtol=1e-12, atol=1e-13)
+        x = y
+    B = fr.shape[0]
+    flat = x.reshape(B, -1)
+    h = orc.dense_forward(flat, v["fc.W"], v["fc.b"], True, math)
+    np.testing.assert_array_equal(h, hfc)
+    Wh = np.concatenate([v["policy.W"], v["value.W"]], 0); bh = np.concatenate([v["policy.b"], v["value.b"]])
+    zv = orc.dense_forward(h, Wh, bh, False, math)
+    np.testing.assert_array_equal(zv[:, :-1], fw["logits"]); np.testing.assert_array_equal(zv[:, -1], fw["values"])
+    if math:
+        np.testing.assert_allclose(hand_dense_fwd(flat, v["fc.W"], v["fc.b"], True), h, rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(hand_dense_fwd(h, Wh, bh, False), zv, rtol=1e-12, atol=1e-13)
+    # backward from arbitrary head gradients
+    A = net.n_actions
+    dzv = synth.rng(173).standard_normal((B, A + 1))
+    whole = orc.views(net, orc.backward(net, th, fw["acts"], dzv[:, :A], dzv[:, A]))
+    got = {}
+    gWh, gbh, dh = orc.dense_backward(h, Wh, dzv, math)
+    got["policy.W"], got["value.W"], got["policy.b"], got["value.b"] = gWh[:A], gWh[A:], gbh[:A], gbh[A:]
+    hand = {}
+    if math:
+        hW, hb, hd = hand_dense_bwd(h, Wh, dzv)
+        hand["policy.W"], hand["value.W"], hand["policy.b"], hand["value.b"] = hW[:A], hW[A:], hb[:A], hb[A:]
+        np.testing.assert_allclose(hd, dh, rtol=1e-12, atol=1e-14)
+    dh = dh * (h > 0)
+    got["fc.W"], got["fc.b"], dflat = orc.dense_backward(flat, v["fc.W"], dh, math)
+    if math:
+        hand["fc.W"], hand["fc.b"], hd = hand_dense_bwd(flat, v["fc.W"], dh)
+        np.testing.assert_allclose(hd, dflat, rtol=1e-12, atol=1e-14)
+    dcur = dflat.reshape(acts[-1].shape)
+    for l in reversed(range(len(net.conv))):
+        oc, k, s = net.conv[l]
+        xs = 255.0 if l == 0 else 1.0
+        W = v[f"conv{l + 1}.W"]
+        got[f"conv{l + 1}.W"], got[f"conv{l + 1}.b"], dx = orc.conv_layer_backward(acts[l], W, s, acts[l + 1], dcur, math, xs, want_dx=l > 0)
+        if math:
+            hand[f"conv{l + 1}.W"], hand[f"conv{l + 1}.b"], hd = hand_conv_bwd(acts[l], W, s, acts[l + 1], dcur, xs, want_dx=l > 0)
+            if l > 0:
+                np.testing.assert_allclose(hd, dx, rtol=1e-12, atol=1e-14)
+        dcur = dx
+    for name in whole:
+        np.testing.assert_allclose(got[name].reshape(whole[name].shape), whole[name], rtol=1e-13, atol=1e-15, err_msg=name)
+        if math:      # the math = 1 branches of the whole backward pass, convolutions included, against torch
+            assert np.abs(whole[name]).max() > 0
+            np.testing.assert_allclose(hand[name].reshape(whole[name].shape), whole[name], rtol=1e-11, atol=1e-13, err_msg=name)
+
+
+def test_layer_by_layer_bound_catches_any_operand_left_unrounded():
+    # For every layer, forward and backward, and every operand class of its products (input x, weights w, output
+    # gradient dy): leave that one class unrounded and look at every output of the layer that depends on it.  The
+    # largest element error, relative to the tensor's largest value, must exceed the bound the GPU test applies to
+    # that output by a factor 4, so a kernel that forgot a rounding cannot pass.  Sizes are those of the GPU tests
+    # (small network, 8 agents x 5 steps; the 3-layer tiny network, 9 x 3).
+    worst = np.inf
+    for net0, N, T, seed in [(SMALL6, 8, 5, 181), (TINY3, 9, 3, 182)]:
+        net, th, fr, fw, ref = _layerwise_case(net0, N, T, seed)
+        acts, hfc = _split_acts(net, fw["acts"])
+        v = orc.views(net, th)
+        B = fr.shape[0]
+        seen = []
+
+        def check(tag, good, bad_of, classes, affected):
+            nonlocal worst
+            for sk in classes:
+                bad = bad_of(sk)
+                for i in affected[sk]:
+                    e = _relmax(bad[i], good[i])
+                    seen.append((tag, sk, i, e))
+                    worst = min(worst, e)
+                    assert e >= 4 * STAGE_TOL_BF16, (tag, sk, i, e)
+
+        for l, (oc, k, s) in enumerate(net.conv):
+            xs = 255.0 if l == 0 else 1.0
+            W, b = v[f"conv{l + 1}.W"], v[f"conv{l + 1}.b"]
+            good = [orc.conv_layer_forward(acts[l], W, b, s, 1, xs)]
+            # the bytes of the first layer are exact in bfloat16: rounding them is a no-op, nothing to catch
+            check(f"conv{l + 1} fwd", good, lambda sk: [hand_conv_fwd(acts[l], W, b, s, xs, sk)],
+                  ("w",) if l == 0 else ("x", "w"), {"x": [0], "w": [0]})
+        flat = acts[-1].reshape(B, -1)
+        check("fc fwd", [orc.dense_forward(flat, v["fc.W"], v["fc.b"], True, 1)],
+              lambda sk: [hand_dense_fwd(flat, v["fc.W"], v["fc.b"], True, sk)], ("x", "w"), {"x": [0], "w": [0]})
+        Wh = np.concatenate([v["policy.W"], v["value.W"]], 0); bh = np.concatenate([v["policy.b"], v["value.b"]])
+        check("heads fwd", [orc.dense_forward(hfc, Wh, bh, False, 1)],
+              lambda sk: [hand_dense_fwd(hfc, Wh, bh, False, sk)], ("x", "w"), {"x": [0], "w": [0]})
+        # backward: outputs (gW, gb, dx); dy enters all three, x only gW, w only dx
+        aff = {"dy": [0, 1, 2], "x": [0], "w": [2]}
+        dzv = np.concatenate([ref["dZ"], ref["dV"][:, None]], 1)
+        g = orc.dense_backward(hfc, Wh, dzv, 1)
+        check("heads bwd", g, lambda sk: hand_dense_bwd(hfc, Wh, dzv, sk), ("dy", "x", "w"), aff)
+        dh = g[2] * (hfc > 0)
+        g = orc.dense_backward(flat, v["fc.W"], dh, 1)
+        check("fc bwd", g, lambda sk: hand_dense_bwd(flat, v["fc.W"], dh, sk), ("dy", "x", "w"), aff)
+        dcur = g[2].reshape(acts[-1].shape)
+        for l in reversed(range(len(net.conv))):
+            oc, k, s = net.conv[l]
+            xs = 255.0 if l == 0 else 1.0
+            W = v[f"conv{l + 1}.W"]
+            g = orc.conv_layer_backward(acts[l], W, s, acts[l + 1], dcur, 1, xs, want_dx=l > 0)
+            a = aff if l > 0 else {"dy": [0, 1]}
+            check(f"conv{l + 1} bwd", g, lambda sk: hand_conv_bwd(acts[l], W, s, acts[l + 1], dcur, xs, sk, want_dx=l > 0),
+                  ("dy", "x", "w") if l > 0 else ("dy",), a)
+            dcur = g[2]
+    assert worst >= 4 * STAGE_TOL_BF16
+
+
+def test_whole_network_bounds_alone_would_not_catch_a_backward_operand():
+    # why the GPU tests compare layer by layer: on whole-network gradients an unrounded backward operand moves the
+    # median element by less than what differently rounded operands on two correct sides already do (observed up to
+    # 4e-4 of the largest element), so no bound on that statistic separates right from wrong
+    net, th, fr, fw, ref = _layerwise_case(SMALL6, 8, 5, 191)
+    acts, hfc = _split_acts(net, fw["acts"])
+    v = orc.views(net, th)
+    flat = acts[-1].reshape(fr.shape[0], -1)
+    dh = orc.dense_backward(hfc, np.concatenate([v["policy.W"], v["value.W"]], 0),
+                            np.concatenate([ref["dZ"], ref["dV"][:, None]], 1), 1)[2] * (hfc > 0)
+    good = orc.dense_backward(flat, v["fc.W"], dh, 1)[0]
+    bad = hand_dense_bwd(flat, v["fc.W"], dh, "x")[0]
+    med = np.median(np.abs(bad - good)) / np.abs(good).max()
+    assert med < 4e-4 and _relmax(bad, good) >= 4 * STAGE_TOL_BF16
