@@ -183,8 +183,14 @@ int ga3c_train_step_ragged(ga3c_ctx *ctx, const uint8_t *frames_dev, const int32
 
 /* Intermediates of the last ga3c_train_step, for checking it step by step.
  * which: 0 = returns R [N*T]; 1 = logits [N*T][A]; 2 = values [N*T];
- * 3 = dL/d(logits, value) [N*T][A+1].  Copies n floats (n must not exceed the
- * tensor's size for the last call's N*T). */
+ * 3 = dL/d(logits, value) [N*T][A+1];
+ * 4 + l = output of conv layer l after its rectifier [N*T][oc][oh][ow];
+ * 8 = output of the fully connected layer after its rectifier [N*T][fc_units];
+ * 9 = dL/d(pre-activation of the fully connected layer) [N*T][fc_units];
+ * 10 + l = dL/d(pre-activation of conv layer l), shaped like 4 + l.
+ * Copies n floats (n must not exceed the tensor's size for the last call's
+ * N*T).  With these a test can hand each layer of a reference the inputs the
+ * library itself used. */
 int ga3c_train_debug_get(ga3c_ctx *ctx, int which, float *dst_dev, size_t n, void *stream);
 
 /* RMSProp alone (Eq. 3) on caller-owned flat buffers of any length, with the

@@ -238,8 +238,11 @@ def conv_layer_backward(x, W, stride: int, y, dy, math: int = 0, xs: float = 1.0
     B, Cc, H, Wd = x.shape
     OC, _, K, _ = W.shape
     gW = np.zeros(W.shape); gb = np.zeros(OC); dx = np.zeros(x.shape) if want_dx else None
-    lib().orc_conv_layer_backward(C.c_int(B), _p(x), C.c_int(Cc), C.c_int(H), C.c_int(Wd), _p(W), C.c_int(OC), C.c_int(K),
-                                  C.c_int(stride), _p(y), _p(dy), C.c_int(math), C.c_double(xs), _p(gW), _p(gb), _p(dx))
+    rc = lib().orc_conv_layer_backward(C.c_int(B), _p(x), C.c_int(Cc), C.c_int(H), C.c_int(Wd), _p(W), C.c_int(OC),
+                                       C.c_int(K), C.c_int(stride), _p(y), _p(dy), C.c_int(math), C.c_double(xs),
+                                       _p(gW), _p(gb), _p(dx))
+    if rc != 0:
+        raise MemoryError("orc_conv_layer_backward")
     return gW, gb, dx
 
 
@@ -260,8 +263,10 @@ def dense_backward(x, W, dy, math: int = 0, want_dx: bool = True):
     B, I = x.shape
     O = W.shape[0]
     gW = np.zeros((O, I)); gb = np.zeros(O); dx = np.zeros((B, I)) if want_dx else None
-    lib().orc_dense_backward(C.c_int(B), _p(x), C.c_int64(I), _p(W), C.c_int(O), _p(dy), C.c_int(math),
-                             _p(gW), _p(gb), _p(dx))
+    rc = lib().orc_dense_backward(C.c_int(B), _p(x), C.c_int64(I), _p(W), C.c_int(O), _p(dy), C.c_int(math),
+                                  _p(gW), _p(gb), _p(dx))
+    if rc != 0:
+        raise MemoryError("orc_dense_backward")
     return gW, gb, dx
 
 

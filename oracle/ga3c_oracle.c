@@ -563,35 +563,76 @@ void orc_conv_layer_forward(int B, const double *x, int C, int H, int W, const d
         conv_relu(x + (int64_t)b * C * H * W, C, H, W, wt, bias, OC, K, S, y + (int64_t)b * OC * OH * OW, math, xs);
 }
 
+/* Frames are spread over threads as in orc_backward: each thread adds its
+ * frames, in index order, into private sums, which are then added in thread
+ * order.  Returns the number of threads to use for B frames. */
+static int frame_threads(int B) {
+    int nthreads = 1;
+#ifdef _OPENMP
+    extern int omp_get_max_threads(void);
+    nthreads = omp_get_max_threads();
+#endif
+    if (nthreads > B) nthreads = B > 0 ? B : 1;
+    return nthreads;
+}
+
 /* gw [OC][C][K][K] and gb [OC] are overwritten with the sums over the frames;
  * dx [B][C][H][W] (may be NULL) is overwritten.  dy is taken before the
  * layer's ReLU mask, which comes from y. */
-void orc_conv_layer_backward(int B, const double *x, int C, int H, int W, const double *wt, int OC,
-                             int K, int S, const double *y, const double *dy, int math, double xs,
-                             double *gw, double *gb, double *dx) {
+int orc_conv_layer_backward(int B, const double *x, int C, int H, int W, const double *wt, int OC,
+                            int K, int S, const double *y, const double *dy, int math, double xs,
+                            double *gw, double *gb, double *dx) {
     int OH = (H - K) / S + 1, OW = (W - K) / S + 1;
-    int64_t in_sz = (int64_t)C * H * W, out_sz = (int64_t)OC * OH * OW;
-    for (int64_t i = 0; i < (int64_t)OC * C * K * K; ++i) gw[i] = 0.0;
-    for (int o = 0; o < OC; ++o) gb[o] = 0.0;
+    int64_t in_sz = (int64_t)C * H * W, out_sz = (int64_t)OC * OH * OW, nw = (int64_t)OC * C * K * K;
+    int nthreads = frame_threads(B);
+    double *priv = (double *)calloc((size_t)nthreads * (nw + OC), sizeof(double));
+    if (!priv) return -1;
     if (dx) for (int64_t i = 0; i < B * in_sz; ++i) dx[i] = 0.0;
-    for (int b = 0; b < B; ++b)
-        conv_backward(x + b * in_sz, C, H, W, wt, OC, K, S, y + b * out_sz, dy + b * out_sz, math, xs,
-                      gw, gb, dx ? dx + b * in_sz : NULL);
+#pragma omp parallel for schedule(static) num_threads(nthreads)
+    for (int t = 0; t < nthreads; ++t) {
+        int b0 = (int)((int64_t)B * t / nthreads), b1 = (int)((int64_t)B * (t + 1) / nthreads);
+        double *pw = priv + (int64_t)t * (nw + OC);
+        for (int b = b0; b < b1; ++b)
+            conv_backward(x + b * in_sz, C, H, W, wt, OC, K, S, y + b * out_sz, dy + b * out_sz, math, xs,
+                          pw, pw + nw, dx ? dx + b * in_sz : NULL);
+    }
+    for (int64_t i = 0; i < nw + OC; ++i) {
+        double sum = 0.0;
+        for (int t = 0; t < nthreads; ++t) sum += priv[(int64_t)t * (nw + OC) + i];
+        if (i < nw) gw[i] = sum; else gb[i - nw] = sum;
+    }
+    free(priv);
+    return 0;
 }
 
 /* x [B][I], W [O][I], bias [O] -> y [B][O]. */
 void orc_dense_forward(int B, const double *x, int64_t I, const double *W, const double *bias, int O,
                        int relu, int math, double *y) {
+#pragma omp parallel for schedule(static)
     for (int b = 0; b < B; ++b) dense(x + b * I, I, W, bias, O, relu, math, y + (int64_t)b * O);
 }
 
 /* dy [B][O] = dL/d(pre-activation).  gW [O][I], gb [O] are overwritten with the
  * sums over the frames, dx [B][I] (may be NULL) is overwritten. */
-void orc_dense_backward(int B, const double *x, int64_t I, const double *W, int O, const double *dy,
-                        int math, double *gW, double *gb, double *dx) {
-    for (int64_t i = 0; i < O * I; ++i) gW[i] = 0.0;
-    for (int o = 0; o < O; ++o) gb[o] = 0.0;
+int orc_dense_backward(int B, const double *x, int64_t I, const double *W, int O, const double *dy,
+                       int math, double *gW, double *gb, double *dx) {
+    int64_t nw = (int64_t)O * I;
+    int nthreads = frame_threads(B);
+    double *priv = (double *)calloc((size_t)nthreads * (nw + O), sizeof(double));
+    if (!priv) return -1;
     if (dx) for (int64_t i = 0; i < B * I; ++i) dx[i] = 0.0;
-    for (int b = 0; b < B; ++b)
-        dense_backward(x + b * I, I, W, O, dy + (int64_t)b * O, math, gW, gb, dx ? dx + b * I : NULL);
+#pragma omp parallel for schedule(static) num_threads(nthreads)
+    for (int t = 0; t < nthreads; ++t) {
+        int b0 = (int)((int64_t)B * t / nthreads), b1 = (int)((int64_t)B * (t + 1) / nthreads);
+        double *pw = priv + (int64_t)t * (nw + O);
+        for (int b = b0; b < b1; ++b)
+            dense_backward(x + b * I, I, W, O, dy + (int64_t)b * O, math, pw, pw + nw, dx ? dx + b * I : NULL);
+    }
+    for (int64_t i = 0; i < nw + O; ++i) {
+        double sum = 0.0;
+        for (int t = 0; t < nthreads; ++t) sum += priv[(int64_t)t * (nw + O) + i];
+        if (i < nw) gW[i] = sum; else gb[i - nw] = sum;
+    }
+    free(priv);
+    return 0;
 }

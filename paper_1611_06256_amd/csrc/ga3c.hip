@@ -671,7 +671,7 @@ __global__ __launch_bounds__(256) void heads_dgrad_kernel(const float *__restric
 // do not depend on the thread layout; (4) heads backward: dh = [h > 0] dz W,
 // and the block's shares of the heads' weight and bias gradients (wpart
 // [block][A+1][F+1]) and of the fc bias gradient (colpart [block][F]).
-// Writes zv, R, dzv (kept for inspection), dh, colpart, wpart and three loss
+// Writes h, zv, R, dzv (kept for inspection), dh, colpart, wpart and three loss
 // sums per block.  rb: operands of every product rounded to bfloat16.
 // Dynamic LDS: heads_train_lds_floats(F, A) floats.
 __host__ __device__ inline int heads_train_kparts(int F, int A) {
@@ -687,8 +687,8 @@ __global__ __launch_bounds__(256) void heads_train_kernel(
     const float *__restrict__ Wp, const float *__restrict__ bp, const float *__restrict__ Wv, const float *__restrict__ bv,
     const int32_t *__restrict__ actions, const float *__restrict__ rewards, const uint8_t *__restrict__ dones,
     const float *__restrict__ bootstrap, const int32_t *__restrict__ seg_start, int N, int T, float gamma, float beta,
-    float cv, float eps, float *__restrict__ zv, float *__restrict__ R, float *__restrict__ dzv, float *__restrict__ dh,
-    float *__restrict__ colpart, float *__restrict__ wpart, float *__restrict__ losspart, int rb) {
+    float cv, float eps, float *__restrict__ h, float *__restrict__ zv, float *__restrict__ R, float *__restrict__ dzv,
+    float *__restrict__ dh, float *__restrict__ colpart, float *__restrict__ wpart, float *__restrict__ losspart, int rb) {
     extern __shared__ __attribute__((aligned(16))) float sm[];
     constexpr int NF = HD_FRAMES;
     const int F4 = heads_f4(F), WP = F4 + 4, A1 = A + 1, KP = heads_train_kparts(F, A);
@@ -750,6 +750,7 @@ __global__ __launch_bounds__(256) void heads_train_kernel(
                 for (int fb = 0; fb < NF; ++fb) {
                     float v = acc[fb] + bias;
                     v = v > 0.f ? v : 0.f;
+                    if (fb < nf) h[(size_t)(b0 + fb) * F + o] = v;
                     hs[fb * F4 + o] = rb ? bf16_rne(v) : v;
                 }
             }
@@ -1686,7 +1687,7 @@ static int train_step_impl(ga3c_ctx *c, const uint8_t *frames, const int32_t *ac
         STAGE("heads_train", 6.0 * B * (A + 1) * F, 4.0 * (w.fc_nz + 1) * B * F);
         hipLaunchKernelGGL(heads_train_kernel, dim3(nblk), dim3(256), ht_lds, s, w.fc_ws, w.fc_nz, th + c->off[nb + 1], B, F, A, Wp,
                            th + c->off[nb + 3], Wv, th + c->off[nb + 5], actions, rewards, dones, bootstrap, seg_start, N, T, hp->gamma, hp->beta,
-                           hp->value_coef, hp->log_eps, w.zv, c->R, c->dzv, c->dh, c->colpart, part, losspart, c->rb);
+                           hp->value_coef, hp->log_eps, w.h, w.zv, c->R, c->dzv, c->dh, c->colpart, part, losspart, c->rb);
         HIP_TRY(hipGetLastError());
         add_seg(part, nblk, A + 1, F + 1, 0, A, c->grad + c->off[nb + 2], c->grad + c->off[nb + 3], 1);
         add_seg(part, nblk, A + 1, F + 1, A, 1, c->grad + c->off[nb + 4], c->grad + c->off[nb + 5], 1);
@@ -1902,6 +1903,10 @@ extern "C" int ga3c_train_debug_get(ga3c_ctx *c, int which, float *dst, size_t n
     if (which == 0) { src = c->R; cap = B; }
     else if (which == 3) { src = c->dzv; cap = B * (c->A + 1); }
     else if (which == 1 || which == 2) { src = c->train.zv; cap = B * (c->A + 1); }
+    else if (which >= 4 && which < 4 + c->nconv) { src = c->train.act[which - 4]; cap = B * c->geom[which - 4].OC * c->geom[which - 4].OHW; }
+    else if (which == 8) { src = c->train.h; cap = B * c->F; }
+    else if (which == 9) { src = c->dh; cap = B * c->F; }
+    else if (which >= 10 && which < 10 + c->nconv) { src = c->dact[which - 10]; cap = B * c->geom[which - 10].OC * c->geom[which - 10].OHW; }
     if (!src || n > (which == 1 ? B * c->A : which == 2 ? B : cap))
         return fail(GA3C_EINVAL, "ga3c_train_debug_get: bad selector or size");
     hipStream_t s = (hipStream_t)stream;

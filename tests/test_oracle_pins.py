@@ -591,7 +591,7 @@ def test_bf16_variant_backward_is_linear_in_rounded_operands():
 # to torch's fp64 convolution / matmul routines applied to operands rounded by torch's own bfloat16 conversion, and
 # show that the layer-by-layer bound used on the GPU (STAGE_TOL_BF16) would catch any operand class left unrounded.
 
-STAGE_TOL_BF16 = 5e-5          # the bound tests/test_gpu_parity.py uses for every single-layer output with math = 1
+STAGE_TOL_BF16 = 1e-5          # the bound tests/test_gpu_parity.py uses for every single-layer output with math = 1
 
 
 def _tq(t):
@@ -724,7 +724,7 @@ def test_layer_by_layer_bound_catches_any_operand_left_unrounded():
     # For every layer, forward and backward, and every operand class of its products (input x, weights w, output
     # gradient dy): leave that one class unrounded and look at every output of the layer that depends on it.  The
     # largest element error, relative to the tensor's largest value, must exceed the bound the GPU test applies to
-    # that output by a factor 4, so a kernel that forgot a rounding cannot pass.  Sizes are those of the GPU tests
+    # that output by a factor 20, so a kernel that forgot a rounding cannot pass.  Sizes are those of the GPU tests
     # (small network, 8 agents x 5 steps; the 3-layer tiny network, 9 x 3).
     worst = np.inf
     for net0, N, T, seed in [(SMALL6, 8, 5, 181), (TINY3, 9, 3, 182)]:
@@ -742,7 +742,7 @@ def test_layer_by_layer_bound_catches_any_operand_left_unrounded():
                     e = _relmax(bad[i], good[i])
                     seen.append((tag, sk, i, e))
                     worst = min(worst, e)
-                    assert e >= 4 * STAGE_TOL_BF16, (tag, sk, i, e)
+                    assert e >= 20 * STAGE_TOL_BF16, (tag, sk, i, e)
 
         for l, (oc, k, s) in enumerate(net.conv):
             xs = 255.0 if l == 0 else 1.0
@@ -775,7 +775,7 @@ def test_layer_by_layer_bound_catches_any_operand_left_unrounded():
             check(f"conv{l + 1} bwd", g, lambda sk: hand_conv_bwd(acts[l], W, s, acts[l + 1], dcur, xs, sk, want_dx=l > 0),
                   ("dy", "x", "w") if l > 0 else ("dy",), a)
             dcur = g[2]
-    assert worst >= 4 * STAGE_TOL_BF16
+    assert worst >= 20 * STAGE_TOL_BF16
 
 
 def test_whole_network_bounds_alone_would_not_catch_a_backward_operand():
@@ -791,4 +791,4 @@ def test_whole_network_bounds_alone_would_not_catch_a_backward_operand():
     good = orc.dense_backward(flat, v["fc.W"], dh, 1)[0]
     bad = hand_dense_bwd(flat, v["fc.W"], dh, "x")[0]
     med = np.median(np.abs(bad - good)) / np.abs(good).max()
-    assert med < 4e-4 and _relmax(bad, good) >= 4 * STAGE_TOL_BF16
+    assert med < 4e-4 and _relmax(bad, good) >= 20 * STAGE_TOL_BF16
