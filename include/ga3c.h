@@ -334,6 +334,29 @@ int ga3c_tuner_state(const ga3c_tuner *t, int *kept_predict_cap, int *kept_train
                      int64_t *rejected);
 int ga3c_tuner_destroy(ga3c_tuner *t);
 
+/* Prediction without allocation, for callers that cannot call hipMalloc: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid device
+ * allocation.  The same kernels as ga3c_predict, for the network of Sec. 3.2
+ * only (4x84x84 input, 16 filters 8x8 stride 4, 32 filters 4x4 stride 2, 256
+ * fully connected units) with n_actions outputs, and no context: theta_dev is
+ * the caller's flat parameter vector in the order given at the top of this file
+ * (what ga3c_params_get writes), 16-byte aligned, as are the frames.  All
+ * intermediate results (filter fragments, activations, partial sums, tickets)
+ * live in one array of GA3C_STATIC_SCRATCH_BYTES that is part of the library's
+ * device image: every GPU the library runs on holds it until the process ends.
+ * The call allocates and frees nothing, on the device or through any library.
+ * 0 <= B <= GA3C_STATIC_MAX_FRAMES; a larger B is rejected with GA3C_EINVAL.
+ * The other arguments are those of ga3c_predict.
+ * All calls on one GPU share that GPU's array: calls that may overlap (two
+ * streams, two threads) race; order them on one stream or with events.  The
+ * array keeps the last call's contents; the only part that must start at zero
+ * (the tickets) is returned to zero by the kernel that uses it. */
+#define GA3C_STATIC_MAX_FRAMES 256
+#define GA3C_STATIC_SCRATCH_BYTES (14u << 20)
+int ga3c_predict_static(int n_actions, int math, const float *theta_dev, const uint8_t *frames_dev, int B,
+                        const float *uniforms_dev, float *logits_dev, float *values_dev, float *probs_dev,
+                        int32_t *actions_dev, void *stream);
+
 /* Shape and capacities the context was created with (any pointer may be NULL). */
 int ga3c_get_desc(const ga3c_ctx *ctx, ga3c_net_desc *desc, int *max_predict_batch, int *max_train_frames);
 

@@ -5,5 +5,5 @@ path runs in the HIP library, this package only marshals arguments.
 """
 from .binding import (  # noqa: F401
     Ga3c, Ga3cError, HParams, NetDesc, TrainStats, SMALL_NET, LARGE_NET, Scheduler, Tuner, lib_path, load_library,
-    rmsprop_flat,
+    rmsprop_flat, predict_static, STATIC_MAX_FRAMES,
 )

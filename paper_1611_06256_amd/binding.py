@@ -111,7 +111,7 @@ EXPORTS = ("ga3c_create", "ga3c_destroy", "ga3c_params_count", "ga3c_params_offs
            "ga3c_params_get", "ga3c_params_set", "ga3c_predict", "ga3c_train_step", "ga3c_train_step_ragged",
            "ga3c_train_debug_get",
            "ga3c_rmsprop_flat", "ga3c_last_error", "ga3c_profile_enable", "ga3c_profile_read",
-           "ga3c_use_generic_kernels", "ga3c_get_desc",
+           "ga3c_use_generic_kernels", "ga3c_get_desc", "ga3c_predict_static",
            "ga3c_sched_create", "ga3c_sched_destroy", "ga3c_sched_submit_predict", "ga3c_sched_submit_trajectory",
            "ga3c_sched_submit_segment", "ga3c_sched_submit_segment_many",
            "ga3c_sched_submit_predict_many", "ga3c_sched_submit_trajectory_many",
@@ -142,6 +142,7 @@ def load_library() -> C.CDLL:
     lib.ga3c_train_step.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, C.POINTER(_HParams), vp, vp]
     lib.ga3c_train_step_ragged.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, C.POINTER(_HParams), vp, vp]
     lib.ga3c_train_debug_get.argtypes = [vp, i32, vp, sz, vp]
+    lib.ga3c_predict_static.argtypes = [i32, i32, vp, vp, i32, vp, vp, vp, vp, vp, vp]
     lib.ga3c_rmsprop_flat.argtypes = [vp, vp, vp, sz, f32, f32, f32, f32, vp]
     lib.ga3c_last_error.restype = C.c_char_p
     lib.ga3c_profile_enable.argtypes = [vp, i32]
@@ -327,6 +328,22 @@ class Ga3c:
         _check(self._lib.ga3c_train_debug_get(self._ctx, which, _ptr(out, torch.float32, "out"), out.numel(),
                                               _stream(stream)), "ga3c_train_debug_get")
         return out
+
+
+STATIC_MAX_FRAMES = 256        # GA3C_STATIC_MAX_FRAMES of include/ga3c.h
+
+
+def predict_static(n_actions: int, math: int, theta, frames, uniforms=None, logits=None, values=None, probs=None,
+                   actions=None, stream=None) -> None:
+    """ga3c_predict_static: prediction of the Sec. 3.2 network from the caller's flat parameters, no context and no
+    device allocation (at most STATIC_MAX_FRAMES frames)."""
+    import torch
+    lib = load_library()
+    _check(lib.ga3c_predict_static(n_actions, math, _ptr(theta, torch.float32, "theta"), _ptr(frames, torch.uint8, "frames"),
+                                   int(frames.shape[0]), _ptr(uniforms, torch.float32, "uniforms"),
+                                   _ptr(logits, torch.float32, "logits"), _ptr(values, torch.float32, "values"),
+                                   _ptr(probs, torch.float32, "probs"), _ptr(actions, torch.int32, "actions"),
+                                   _stream(stream)), "ga3c_predict_static")
 
 
 def _scheck(rc: int, what: str) -> int:

@@ -9,6 +9,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -1375,6 +1376,39 @@ size_t workspace_floats(const ga3c_ctx *c, int cap, bool training) {
 
 }  // namespace
 
+// Host-only part of setting up a context: layer geometry, parameter offsets, counts.  Touches no device memory.
+// On a layer that does not fit its input, returns GA3C_EINVAL with c->nconv set to that layer's index.
+static int init_shape(ga3c_ctx *c, const ga3c_net_desc *d) {
+    c->rb = d->math;
+    c->desc = *d;
+    c->nconv = d->n_conv; c->F = d->fc_units; c->A = d->n_actions;
+    int C = d->in_c, H = d->in_h, W = d->in_w;
+    int64_t pos = 0; int no = 0;
+    for (int l = 0; l < c->nconv; ++l) {
+        const int oc = d->conv[l].oc, ks = d->conv[l].k, st = d->conv[l].stride;
+        if (oc < 1 || ks < 1 || st < 1 || ks > H || ks > W) { c->nconv = l; return GA3C_EINVAL; }
+        ConvGeom &g = c->geom[l];
+        g.C = C; g.H = H; g.W = W; g.OC = oc; g.KS = ks; g.S = st;
+        g.OH = (H - ks) / st + 1; g.OW = (W - ks) / st + 1;
+        g.K = C * ks * ks; g.OHW = g.OH * g.OW; g.CHW = C * H * W;
+        g.dOHW = FastDiv(g.OHW); g.dOW = FastDiv(g.OW);
+        g.koff = nullptr;
+        c->off[no++] = pos; pos += (int64_t)oc * g.K;
+        c->off[no++] = pos; pos += oc;
+        C = oc; H = g.OH; W = g.OW;
+    }
+    c->flat = C * H * W;
+    c->off[no++] = pos; pos += (int64_t)c->flat * c->F;
+    c->off[no++] = pos; pos += c->F;
+    c->off[no++] = pos; pos += (int64_t)c->A * c->F;
+    c->off[no++] = pos; pos += c->A;
+    c->off[no++] = pos; pos += c->F;
+    c->off[no++] = pos; pos += 1;
+    c->off[no++] = pos;
+    c->noff = no; c->P = (size_t)pos;
+    return GA3C_OK;
+}
+
 // ------------------------------------------------------------------ C ABI ---
 
 extern "C" int ga3c_create(const ga3c_net_desc *d, int max_predict_batch, int max_train_frames, ga3c_ctx **out) {
@@ -1395,42 +1429,19 @@ extern "C" int ga3c_create(const ga3c_net_desc *d, int max_predict_batch, int ma
     c->prof = new (std::nothrow) Profiler();
     c->fast = true;
     c->small_predict = true;
-    c->rb = d->math;
-    c->desc = *d;
-    c->nconv = d->n_conv; c->F = d->fc_units; c->A = d->n_actions;
     c->max_pred = max_predict_batch; c->max_train = max_train_frames;
 
-    int C = d->in_c, H = d->in_h, W = d->in_w;
-    int64_t pos = 0; int no = 0;
-    for (int l = 0; l < c->nconv; ++l) {
-        const int oc = d->conv[l].oc, ks = d->conv[l].k, st = d->conv[l].stride;
-        if (oc < 1 || ks < 1 || st < 1 || ks > H || ks > W) {
-            delete c;
-            return fail(GA3C_EINVAL, "ga3c_create: conv layer %d does not fit its input", l);
-        }
-        ConvGeom &g = c->geom[l];
-        g.C = C; g.H = H; g.W = W; g.OC = oc; g.KS = ks; g.S = st;
-        g.OH = (H - ks) / st + 1; g.OW = (W - ks) / st + 1;
-        g.K = C * ks * ks; g.OHW = g.OH * g.OW; g.CHW = C * H * W;
-        g.dOHW = FastDiv(g.OHW); g.dOW = FastDiv(g.OW);
-        g.koff = nullptr;
-        c->off[no++] = pos; pos += (int64_t)oc * g.K;
-        c->off[no++] = pos; pos += oc;
-        C = oc; H = g.OH; W = g.OW;
+    if (init_shape(c, d) != GA3C_OK) {
+        const int l = c->nconv;      // init_shape leaves the index of the offending layer here
+        delete c->prof;
+        delete c;
+        return fail(GA3C_EINVAL, "ga3c_create: conv layer %d does not fit its input", l);
     }
-    c->flat = C * H * W;
-    c->off[no++] = pos; pos += (int64_t)c->flat * c->F;
-    c->off[no++] = pos; pos += c->F;
-    c->off[no++] = pos; pos += (int64_t)c->A * c->F;
-    c->off[no++] = pos; pos += c->A;
-    c->off[no++] = pos; pos += c->F;
-    c->off[no++] = pos; pos += 1;
-    c->off[no++] = pos;
-    c->noff = no; c->P = (size_t)pos;
     // 32-bit index limits of the kernels
     const int maxB = std::max(max_predict_batch, max_train_frames);
     for (int l = 0; l < c->nconv; ++l)
         if ((double)maxB * std::max(c->geom[l].OHW, c->geom[l].H * c->geom[l].W) >= 2.0e9) {
+            delete c->prof;
             delete c;
             return fail(GA3C_EINVAL, "ga3c_create: capacity too large for 32-bit pixel indices");
         }
@@ -1975,4 +1986,91 @@ extern "C" int ga3c_get_desc(const ga3c_ctx *c, ga3c_net_desc *desc, int *max_pr
     if (max_predict_batch) *max_predict_batch = c->max_pred;
     if (max_train_frames) *max_train_frames = c->max_train;
     return GA3C_OK;
+}
+
+// ---------------------------------------------- prediction without allocation ---
+//
+// ga3c_predict_static: the prediction of the Sec. 3.2 network for callers that cannot allocate device memory.
+// Everything ga3c_predict keeps in buffers that ga3c_create allocates (filter fragments, layer-2 activations, split-k
+// partial sums of the fc layer, fc outputs, the one-launch path's tickets) lives in one file-scope device array here.
+// Each GPU holds its own copy of the array; its address on a device is looked up once, with that device current,
+// and kernels and copies only ever get that looked-up address.
+namespace {
+constexpr int STATIC_MAX_FRAMES = GA3C_STATIC_MAX_FRAMES;
+constexpr int STATIC_MAX_SPLITS = 40;                                    // k-chunks of the fc product: 2592 / 64
+constexpr size_t up256(size_t n) { return (n + 255) / 256 * 256; }
+constexpr size_t ST_FRAG_OFF = 0;
+constexpr size_t ST_TICKET_OFF = ST_FRAG_OFF + up256(sizeof(u32x4) * 3 * C12_FRAG_SET);
+constexpr size_t ST_H_OFF = ST_TICKET_OFF + up256(sizeof(int) * SP_MAX_FRAMES * SP_TICKET_PITCH);
+constexpr size_t ST_Y2_OFF = ST_H_OFF + up256(sizeof(float) * STATIC_MAX_FRAMES * SP_FC);
+constexpr size_t ST_WS_OFF = ST_Y2_OFF + up256(sizeof(float) * STATIC_MAX_FRAMES * SP_FLAT);
+constexpr size_t ST_WS_FLOATS = (size_t)STATIC_MAX_SPLITS * STATIC_MAX_FRAMES * SP_FC;
+constexpr size_t ST_BYTES = ST_WS_OFF + up256(sizeof(float) * ST_WS_FLOATS);
+static_assert(ST_BYTES <= (size_t)GA3C_STATIC_SCRATCH_BYTES, "the header promises a smaller array");
+
+constexpr int ST_MAX_DEVICES = 64;
+unsigned char *g_static_ptr[ST_MAX_DEVICES];      // device address of the array on each GPU, nullptr until looked up
+std::mutex g_static_mutex;
+}  // namespace
+
+static __device__ __align__(256) unsigned char ga3c_static_scratch[ST_BYTES];
+
+// Address of the array on the current device (looked up on the first call there).
+static int static_scratch(unsigned char **out) {
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= ST_MAX_DEVICES) return fail(GA3C_EINVAL, "ga3c_predict_static: device index %d not supported", dev);
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (!g_static_ptr[dev]) {
+        void *p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(ga3c_static_scratch)));
+        if (!p) return fail(GA3C_EHIP, "ga3c_predict_static: the scratch array has no address on device %d", dev);
+        g_static_ptr[dev] = (unsigned char *)p;
+    }
+    *out = g_static_ptr[dev];
+    return GA3C_OK;
+}
+
+extern "C" int ga3c_predict_static(int n_actions, int math, const float *theta, const uint8_t *frames, int B,
+                                   const float *uniforms, float *logits, float *values, float *probs, int32_t *actions,
+                                   void *stream) {
+    if (n_actions < 1 || n_actions > GA3C_MAX_ACTIONS)
+        return fail(GA3C_EINVAL, "ga3c_predict_static: n_actions must be 1..%d", GA3C_MAX_ACTIONS);
+    if (math != 0 && math != 1) return fail(GA3C_EINVAL, "ga3c_predict_static: math must be 0 or 1");
+    if (B < 0 || B > STATIC_MAX_FRAMES)
+        return fail(GA3C_EINVAL, "ga3c_predict_static: B = %d outside [0, %d] (the scratch array is sized for %d frames)", B,
+                    STATIC_MAX_FRAMES, STATIC_MAX_FRAMES);
+    if (B == 0) return GA3C_OK;
+    if (!theta || !frames) return fail(GA3C_EINVAL, "ga3c_predict_static: null theta or frames");
+    if (actions && !uniforms) return fail(GA3C_EINVAL, "ga3c_predict_static: actions requested without uniforms");
+    if (!is_aligned16(theta) || !is_aligned16(frames))
+        return fail(GA3C_EINVAL, "ga3c_predict_static: theta and frames must be 16-byte aligned");
+
+    // a context on the stack that owns nothing: shape and offsets on the host, every buffer inside the array
+    ga3c_ctx c;
+    memset((void *)&c, 0, sizeof(c));
+    ga3c_net_desc d;
+    memset(&d, 0, sizeof(d));
+    d.in_c = 4; d.in_h = 84; d.in_w = 84; d.n_conv = 2;
+    d.conv[0].oc = 16; d.conv[0].k = 8; d.conv[0].stride = 4;
+    d.conv[1].oc = 32; d.conv[1].k = 4; d.conv[1].stride = 2;
+    d.fc_units = SP_FC; d.n_actions = n_actions; d.math = math;
+    TRY(init_shape(&c, &d));
+    if (c.flat != SP_FLAT || c.off[2] % 4 != 0 || c.off[4] % 4 != 0)
+        return fail(GA3C_EINVAL, "ga3c_predict_static: internal: unexpected layout");
+    unsigned char *base = nullptr;
+    TRY(static_scratch(&base));
+    c.fast = true; c.small_predict = true; c.max_pred = STATIC_MAX_FRAMES;
+    c.theta2[0] = const_cast<float *>(theta);
+    c.cfrag[0] = (u32x4 *)(base + ST_FRAG_OFF);
+    c.ticket = (int *)(base + ST_TICKET_OFF);
+    c.pred.cap = STATIC_MAX_FRAMES;
+    c.pred.h = (float *)(base + ST_H_OFF);
+    c.pred.act[1] = (float *)(base + ST_Y2_OFF);
+    c.pred.ws = (float *)(base + ST_WS_OFF);
+    c.pred.ws_floats = ST_WS_FLOATS;
+    hipStream_t s = (hipStream_t)stream;
+    // the filters as split MFMA fragments, from the caller's parameters (a context does this when they change)
+    TRY(refresh_derived(&c, 0, s));
+    return forward(&c, 0, c.pred, frames, B, false, logits, values, probs, uniforms, actions, s);
 }
