@@ -154,18 +154,20 @@ __device__ __forceinline__ void conv12_fused_block(const uint8_t *__restrict__ x
         for (int i = 0; i < VPT; ++i) pre[i] = src[vidx[i]];
     }
 
-    // my filter fragments, split into three bf16 terms ahead of time (conv12_filter_fragments_kernel)
+    // My filter fragments, split into three bf16 terms ahead of time (conv12_filter_fragments_kernel).  Every block
+    // of the launch wants the same 72 KB at the same moment, and a wavefront's copy is 24 KB, so what the blocks ask
+    // of the L2 in their first microsecond is kept small: the four layer-1 wavefronts fetch their common set once
+    // between them and hand it round through LDS (the exchange buffers, which nobody uses before the second
+    // iteration); the layer-2 wavefronts fetch theirs during the first iteration, in which they have nothing else to
+    // do and the layer-1 set has already arrived.
+    constexpr int NTERM = ONE ? 1 : 3;
+    constexpr int FPT = NTERM * 8 * 64 / 256;                      // vectors of the layer-1 set per layer-1 thread
+    static_assert(sizeof(u32x4) * NTERM * 8 * 64 <= sizeof(float) * 2 * C12_EX, "the layer-1 set fits the exchange buffers");
     bf16x8 wq[3][8];
-    {
-        const u32x4 *src = frag + (size_t)(layer1 ? 0 : 1 + kh) * C12_FRAG_SET + lane;
+    u32x4 fpre[FPT];
+    if (layer1) {
 #pragma unroll
-        for (int t = 0; t < (ONE ? 1 : 3); ++t)
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                Bf16x8Bits v;
-                v.u = src[(t * 8 + j) * 64];
-                wq[t][j] = v.v;
-            }
+        for (int i = 0; i < FPT; ++i) fpre[i] = frag[rt + 256 * i];
     }
     float bv[4];                                                   // layer 2 finishes filter tile kh
 #pragma unroll
@@ -180,19 +182,52 @@ __device__ __forceinline__ void conv12_fused_block(const uint8_t *__restrict__ x
 
     // iteration it: layer 1 of frame it, layer 2 of frame it - 1, last step of layer 2 of frame it - 2
     // (one frame: the three iterations are written out, so that each keeps only what it needs in registers)
+    auto stage_frame = [&]() {
+#pragma unroll
+        for (int i = 0; i < VPT; ++i) {
+            u32x4 a, b;
+            bytes_to_bf16(pre[i], a, b);
+            u32x4 *dst = (u32x4 *)(xs + (size_t)(rt + 256 * i) * 16);
+            dst[0] = a; dst[1] = b;
+        }
+    };
+    // before the first iteration: the first frame and the layer-1 filter set go to LDS, then everybody takes its filters
+    if (layer1) {
+        stage_frame();
+#pragma unroll
+        for (int i = 0; i < FPT; ++i) ((u32x4 *)exb)[rt + 256 * i] = fpre[i];
+    }
+    __syncthreads();
+    {
+        if (layer1) {
+            const u32x4 *src = (const u32x4 *)exb + lane;
+#pragma unroll
+            for (int t = 0; t < NTERM; ++t)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    Bf16x8Bits v;
+                    v.u = src[(t * 8 + j) * 64];
+                    wq[t][j] = v.v;
+                }
+        } else {
+            const u32x4 *src = frag + (size_t)(1 + kh) * C12_FRAG_SET + lane;
+#pragma unroll
+            for (int t = 0; t < NTERM; ++t)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    Bf16x8Bits v;
+                    v.u = src[(t * 8 + j) * 64];
+                    wq[t][j] = v.v;
+                }
+        }
+    }
 #pragma unroll(TO_LDS ? 3 : 1)
     for (int it = 0; it <= n + 1; ++it) {
-        __syncthreads();          // layer 1 of the previous frame has read xs; layer 2 has read its planes
-        if (layer1 && it < n) {
-#pragma unroll
-            for (int i = 0; i < VPT; ++i) {
-                u32x4 a, b;
-                bytes_to_bf16(pre[i], a, b);
-                u32x4 *dst = (u32x4 *)(xs + (size_t)(rt + 256 * i) * 16);
-                dst[0] = a; dst[1] = b;
-            }
+        if (it > 0) {
+            __syncthreads();          // layer 1 of the previous frame has read xs; layer 2 has read its planes
+            if (layer1 && it < n) stage_frame();
+            __syncthreads();
         }
-        __syncthreads();
         if (layer1) {
             if (it < n) {
                 const int f = first + it * grid;

@@ -624,27 +624,28 @@ def test_ragged_argument_errors(G):
 
 @pytest.mark.parametrize("math", [0, 1])
 def test_handful_of_frames_in_one_launch(G, math):
-    # up to 16 frames of the small net go out as one kernel (convolutions, fc, heads, draw; 32 blocks per frame up to
-    # 8 frames, 16 blocks per frame beyond); more frames take the three-kernel path.  Both compute the same numbers up to summation order, call after call (the kernel's ticket
-    # counters must be back at zero after every launch), in any order of batch sizes.
+    # up to 64 frames of the small net go out as one kernel (convolutions, fc, heads, draw; 32 blocks per frame up to
+    # 8 frames, 16 up to 16, 8 up to 32, 4 up to 64); more frames take the three-kernel path.  Both compute the same
+    # numbers up to summation order, call after call (the kernel's ticket counters must be back at zero after every
+    # launch), in any order of batch sizes.
     import torch
     import dataclasses
     desc = dataclasses.replace(G.SMALL_NET(18), math=math)
-    net = G.Ga3c(desc, 24, 0)
+    net = G.Ga3c(desc, 96, 0)
     net.use_generic_kernels(GENERIC)
     net.params_init(31)
-    fr = torch.from_numpy(synth.rectangle_frames(8301, 24)).cuda()
-    u = torch.from_numpy(synth.uniforms(8302, 24)).cuda()
+    fr = torch.from_numpy(synth.rectangle_frames(8301, 96)).cuda()
+    u = torch.from_numpy(synth.uniforms(8302, 96)).cuda()
     def run(B):
         lg = torch.empty(B, 18, device="cuda"); vl = torch.empty(B, device="cuda"); pr = torch.empty(B, 18, device="cuda")
         ac = torch.empty(B, dtype=torch.int32, device="cuda")
         net.predict(fr[:B].contiguous(), uniforms=u[:B].contiguous(), logits=lg, values=vl, probs=pr, actions=ac)
         torch.cuda.synchronize()
         return lg.cpu().numpy(), vl.cpu().numpy(), pr.cpu().numpy(), ac.cpu().numpy()
-    ref = run(24)
+    ref = run(96)
     tol = 1e-5 if math == 0 else TOL_FWD_BF16
     first = {}
-    for B in (3, 8, 1, 16, 5, 8, 9, 2, 7, 12, 4, 6, 16, 1, 3, 9):
+    for B in (3, 8, 1, 16, 5, 8, 9, 2, 7, 12, 4, 6, 16, 1, 3, 9, 17, 64, 32, 33, 40, 5, 64, 17, 31, 33, 63):
         print("frames", B, flush=True)
         lg, vl, pr, ac = run(B)
         assert rel_err(lg, ref[0][:B]) <= tol and rel_err(vl, ref[1][:B]) <= tol and rel_err(pr, ref[2][:B]) <= tol
@@ -657,6 +658,58 @@ def test_handful_of_frames_in_one_launch(G, math):
             for x, y in zip((lg, vl, pr, ac), first[B]):
                 np.testing.assert_array_equal(x, y)
         first[B] = (lg, vl, pr, ac)
+    net.close()
+
+
+@pytest.mark.parametrize("math", [0, 1])
+@pytest.mark.parametrize("B", [17, 32, 33, 64])
+def test_one_launch_prediction_17_to_64_frames_against_the_oracle(G, B, math):
+    # the batch sizes that used to take three launches, element by element against the oracle
+    import dataclasses
+    check_predict(G, dataclasses.replace(G.SMALL_NET(18), math=math), B, 8400 + B, frames=synth.rectangle_frames(8400 + B, B))
+
+
+def test_one_launch_prediction_is_stable_next_to_a_training_step(G):
+    # The block that finishes a frame last reads what the other blocks of the launch wrote, with no device-wide fence
+    # (see predict_small_kernel).  20 000 calls of 1 .. 64 frames while training steps run on a second stream: every
+    # result must equal, bit for bit, the first result for that batch size.  Parameters are held fixed (lr = 0).
+    import torch
+    if GENERIC:
+        pytest.skip("the general kernels have no one-launch path")
+    net = G.Ga3c(G.SMALL_NET(18), 64, 640)
+    net.params_init(41)
+    fr = torch.from_numpy(synth.rectangle_frames(8501, 64)).cuda()
+    u = torch.from_numpy(synth.uniforms(8502, 64)).cuda()
+    tf = torch.from_numpy(synth.rectangle_frames_tiled(8503, 640).reshape(128, 5, 4, 84, 84)).cuda()
+    tr = synth.trajectories(8504, 128, 5, 18)
+    ta, trw, td = (torch.from_numpy(tr[k]).cuda() for k in ("actions", "rewards", "dones"))
+    hp = G.HParams(lr=0.0)
+    s_pred, s_train = torch.cuda.Stream(), torch.cuda.Stream()
+    sizes = [1, 2, 5, 8, 9, 16, 17, 31, 32, 33, 48, 64]
+    outs = {B: [torch.empty(B, 18, device="cuda"), torch.empty(B, device="cuda"), torch.empty(B, dtype=torch.int32, device="cuda")]
+            for B in sizes}
+    want = {}
+    for B in sizes:
+        net.predict(fr[:B], uniforms=u[:B], logits=outs[B][0], values=outs[B][1], actions=outs[B][2], stream=s_pred)
+        s_pred.synchronize()
+        want[B] = [t.clone() for t in outs[B]]
+    rng = synth.rng(8505)
+    order = rng.integers(0, len(sizes), 20000)
+    bad = torch.zeros(1, dtype=torch.int32, device="cuda")
+    for i, k in enumerate(order):
+        B = sizes[int(k)]
+        if i % 8 == 0:
+            net.train_step(tf, ta, trw, td, None, hp, stream=s_train)
+        net.predict(fr[:B], uniforms=u[:B], logits=outs[B][0], values=outs[B][1], actions=outs[B][2], stream=s_pred)
+        with torch.cuda.stream(s_pred):
+            for got, w in zip(outs[B], want[B]):
+                bad += (got != w).any().to(torch.int32)
+        if i % 2000 == 1999:
+            torch.cuda.synchronize()
+            print("calls", i + 1, "mismatches", int(bad.item()), flush=True)
+            assert int(bad.item()) == 0
+    torch.cuda.synchronize()
+    assert int(bad.item()) == 0
     net.close()
 
 
