@@ -35,7 +35,7 @@ if ROOT not in sys.path:
 
 def run_mixed(net_kind: str = "small", n_agents: int = 256, think_us: float = 0.0, seconds: float = 1.0,
               dynamic: bool = True, seed: int = 1615, predict_cap: int = 256, train_cap: int = 1280,
-              train_min: int = 40, episode_end_prob: float = 0.0):
+              train_min: int = 40, episode_end_prob: float = 0.0, adjust_period: int = 1000, trace: bool = False):
     import numpy as np
     import torch
 
@@ -52,7 +52,7 @@ def run_mixed(net_kind: str = "small", n_agents: int = 256, think_us: float = 0.
     base = pool.data_ptr()
     sched = g.Scheduler(net, g.HParams(clip_norm=40.0), t_max=T, predict_cap=predict_cap if not dynamic else 32,
                         train_min=train_min,
-                        train_cap=train_cap if not dynamic else 320, adjust_period=1000 if dynamic else 0, predict_cap_lo=1,
+                        train_cap=train_cap if not dynamic else 320, adjust_period=adjust_period if dynamic else 0, predict_cap_lo=1,
                         predict_cap_hi=predict_cap, train_cap_lo=max(40, train_min), train_cap_hi=train_cap, train_cap_step=40, seed=seed)
     rng = synth.rng(seed + 1)
     step = np.zeros(n_agents, np.int64)          # actions taken so far (picks the frame shown)
@@ -64,10 +64,15 @@ def run_mixed(net_kind: str = "small", n_agents: int = 256, think_us: float = 0.
     ids = np.arange(n_agents, dtype=np.int32)
     t0 = time.perf_counter()
     ticks = 0
+    windows_seen = []
+    half = None                                  # (time, trained frames, predictions) once half of the run is over
     while True:
         now = time.perf_counter() - t0
         if now > seconds:
             break
+        if half is None and now > 0.5 * seconds:
+            st = sched.stats()
+            half = (now, st["trained_frames"], st["predictions"])
         go = (~waiting) & (ready_at <= now)
         if go.any():
             a = ids[go]
@@ -76,6 +81,10 @@ def run_mixed(net_kind: str = "small", n_agents: int = 256, think_us: float = 0.
             waiting[a] = True
         sched.tick()
         ticks += 1
+        if trace and ticks % adjust_period == 0:      # the window that just closed: its reading and the caps proposed next
+            st = sched.stats()
+            windows_seen.append((st["windows"], round(st["last_window_frames_per_s"]), st["predict_cap"], st["train_cap"],
+                                 st["trials_accepted"], st["trials_rejected"]))
         a, action, value, version = sched.poll_arrays(with_version=True)
         if a.size:
             first = seg_len[a] == 0
@@ -101,17 +110,23 @@ def run_mixed(net_kind: str = "small", n_agents: int = 256, think_us: float = 0.
     sched.drain()
     wall = time.perf_counter() - t0
     st = sched.stats()
-    out = {"agents": n_agents, "think_us": think_us, "dynamic": dynamic, "seconds": round(wall, 3),
+    out = {"net": net_kind, "agents": n_agents, "think_us": think_us, "dynamic": dynamic, "seconds": round(wall, 3),
            "pps": round(st["predictions"] / wall, 1), "tps_frames": round(st["trained_frames"] / wall, 1),
+           # the second half of the run on its own: what the adjustment has arrived at, without the climb
+           "tps_frames_second_half": round((st["trained_frames"] - half[1]) / (wall - half[0]), 1) if half else None,
            "mean_predict_batch": round(st["predictions"] / max(1, st["predict_batches"]), 2),
            "mean_train_batch_frames": round(st["trained_frames"] / max(1, st["train_batches"]), 1),
            "mean_train_queue": round(st["sum_train_queue"] / max(1, st["ticks"]), 2),
            "predict_cap": st["predict_cap"], "train_cap": st["train_cap"],
            "trials_accepted": st["trials_accepted"], "trials_rejected": st["trials_rejected"],
+           "windows": st["windows"], "last_change_window": st["last_change_window"],
+           "seconds_to_last_change": round(wall * st["last_change_window"] / st["windows"], 3) if st["windows"] else None,
            "train_min": train_min, "episode_end_prob": episode_end_prob, "updates": st["train_batches"],
            "short_segments": st["short_segments"],
            "mean_policy_lag_updates": round(st["lag_sum"] / max(1, st["lag_count"]), 3), "max_policy_lag_updates": st["lag_max"],
            "host_us_per_tick": round(wall / max(1, ticks) * 1e6, 1)}
+    if trace:
+        out["window_trace"] = windows_seen
     sched.close()
     net.close()
     return out

@@ -23,6 +23,16 @@
  *     read and publishes it, and HIP events order that against the
  *     predictions (a prediction sees the parameters of the last update that
  *     was ENQUEUED before it, never a half-written set).
+ *   - One HOST thread at a time drives a context: the calls keep host-side
+ *     state without locks (which parameter copy is published, where each event
+ *     was last recorded, the profiler's lists).  The paper's predictor and
+ *     trainer THREADS exist because its GPU calls block their caller; here a
+ *     call only enqueues, so one thread can feed both streams (ga3c_sched_*
+ *     does exactly that).  Callers that do use several threads must serialise
+ *     their calls on one context themselves; the concurrency that matters, the
+ *     overlap of prediction and training on the GPU, comes from the two streams.
+ *     Different contexts are independent, except that ga3c_predict_static calls
+ *     on one GPU share one scratch array.
  *   - Return value: GA3C_OK or a negative GA3C_E* code.  Nothing is printed,
  *     no C++ exception crosses the boundary.  ga3c_last_error() returns a
  *     thread-local description of the last failure on the calling thread.
@@ -226,7 +236,9 @@ int ga3c_profile_read(ga3c_ctx *ctx, char *buf, size_t cap);
  * frames, Sec. 5.3), and every period one of the system's knobs is changed at
  * random by one step and the change kept if trainings per second did not drop
  * (Sec. 4.3).  Here the knobs are the two batch caps; the two kinds of call
- * run on two HIP streams of default priority that the scheduler owns.
+ * run on two HIP streams of default priority that the scheduler owns.  A
+ * request or segment leaves its queue only after the GPU work that serves it
+ * has been enqueued without error.
  *
  * One host thread drives a scheduler: submit, tick and poll are not
  * thread-safe against each other.  Frames are DEVICE memory owned by the
@@ -249,11 +261,14 @@ typedef struct {
     int predict_cap;                        /* frames per prediction batch, 1 .. max_predict_batch */
     int train_min;                          /* an update waits until this many frames are queued */
     int train_cap;                          /* frames per update, t_max .. max_train_frames */
-    int adjust_period;                      /* ticks per adjustment window; 0 = caps stay fixed */
+    int adjust_period;                      /* ticks per adjustment window; 0 = caps stay fixed.  With the adjustment
+                                               on, its training knob is the batch size itself: an update waits for
+                                               train_cap frames (never fewer than train_min) and takes at most as many */
     int predict_cap_lo, predict_cap_hi;     /* bounds for the adjustment (cap moves by factors of 2) */
     int train_cap_lo, train_cap_hi, train_cap_step;   /* bounds and step (frames) for the adjustment */
     uint64_t seed;                          /* of the adjustment's random choices */
     ga3c_hparams hp;                        /* used for every update */
+    float adjust_margin;                    /* a trial is kept iff throughput >= (1 - margin) * reference; 0 = 0.03 */
 } ga3c_sched_config;
 
 typedef struct {
@@ -270,6 +285,7 @@ typedef struct {
     double last_window_frames_per_s;
     int64_t short_segments;                       /* trained segments with fewer than t_max steps */
     int64_t lag_sum, lag_count, lag_max;          /* policy lag in updates over the trained segments that gave a version */
+    int64_t windows, last_change_window;          /* adjustment windows so far; the one in which the kept caps last changed */
 } ga3c_sched_stats;
 
 int ga3c_sched_create(ga3c_ctx *ctx, const ga3c_sched_config *cfg, ga3c_sched **out);
@@ -322,16 +338,31 @@ int ga3c_sched_get_stats(const ga3c_sched *s, ga3c_sched_stats *out);
 const char *ga3c_sched_last_error(void);
 
 /* The adjustment rule alone (host only, no GPU): caps within [lo, hi]; the
- * prediction cap moves by a factor 2 per step, the training cap by t_step.
+ * prediction cap moves by a factor 2 per step, the training cap by a fraction
+ * of its value: a quarter at first, halved after every rejected step of that
+ * knob (down to 1/64), doubled after every accepted one (at least t_step, a
+ * multiple of t_step; the last step to a bound may be shorter).
  * ga3c_tuner_report closes a window that ran the current caps at the given
- * throughput: a trial that lowered the throughput is undone, otherwise the
- * caps are kept; then one knob is stepped in a random direction and the new
- * caps are returned.  Deterministic for a given seed. */
+ * throughput.  The first two windows measure the starting caps (the
+ * reference; the first window also pays for the start of the run).  A trial
+ * is kept iff its throughput >= (1 - margin) * reference (margin 0.03 unless
+ * set): then the caps are kept and the reference becomes the larger of the two
+ * readings; if the gain exceeded half the margin the same knob is stepped in
+ * the same direction again.  A trial that is not kept is undone and the next
+ * window runs the kept caps again (a higher reading replaces the reference, a
+ * lower one is averaged into it).  Otherwise one knob is stepped in a random
+ * direction (not the same knob three times in a row; not a direction that
+ * was rejected from the knob's present value, unless the other one has been
+ * rejected since).  The new caps are returned.  Deterministic for a given seed
+ * and sequence of readings. */
 int ga3c_tuner_create(int p_lo, int p_hi, int p0, int t_lo, int t_hi, int t_step, int t0, uint64_t seed,
                       ga3c_tuner **out);
 int ga3c_tuner_report(ga3c_tuner *t, double throughput, int *predict_cap, int *train_cap);
 int ga3c_tuner_state(const ga3c_tuner *t, int *kept_predict_cap, int *kept_train_cap, int64_t *accepted,
                      int64_t *rejected);
+int ga3c_tuner_set_margin(ga3c_tuner *t, double margin);
+/* Windows reported so far, and the window in which the kept caps last changed (0 = never). */
+int ga3c_tuner_progress(const ga3c_tuner *t, int64_t *windows, int64_t *last_change_window);
 int ga3c_tuner_destroy(ga3c_tuner *t);
 
 /* Prediction without allocation, for callers that cannot call hipMalloc: code

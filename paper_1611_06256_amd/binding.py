@@ -38,7 +38,7 @@ class _SchedConfig(C.Structure):
     _fields_ = [("t_max", C.c_int), ("predict_cap", C.c_int), ("train_min", C.c_int), ("train_cap", C.c_int),
                 ("adjust_period", C.c_int), ("predict_cap_lo", C.c_int), ("predict_cap_hi", C.c_int),
                 ("train_cap_lo", C.c_int), ("train_cap_hi", C.c_int), ("train_cap_step", C.c_int),
-                ("seed", C.c_uint64), ("hp", _HParams)]
+                ("seed", C.c_uint64), ("hp", _HParams), ("adjust_margin", C.c_float)]
 
 
 class Prediction(C.Structure):
@@ -50,7 +50,8 @@ class SchedStats(C.Structure):
                 ("ticks", "predictions", "predict_batches", "trained_frames", "train_batches", "sum_predict_queue",
                  "sum_train_queue", "predict_queue", "train_queue", "trials_accepted", "trials_rejected")] + \
                [("predict_cap", C.c_int32), ("train_cap", C.c_int32), ("last_window_frames_per_s", C.c_double)] + \
-               [(n, C.c_int64) for n in ("short_segments", "lag_sum", "lag_count", "lag_max")]
+               [(n, C.c_int64) for n in ("short_segments", "lag_sum", "lag_count", "lag_max", "windows",
+                                         "last_change_window")]
 
 
 class TrainStats(C.Structure):
@@ -116,7 +117,8 @@ EXPORTS = ("ga3c_create", "ga3c_destroy", "ga3c_params_count", "ga3c_params_offs
            "ga3c_sched_submit_segment", "ga3c_sched_submit_segment_many",
            "ga3c_sched_submit_predict_many", "ga3c_sched_submit_trajectory_many",
            "ga3c_sched_tick", "ga3c_sched_poll", "ga3c_sched_drain", "ga3c_sched_get_stats", "ga3c_sched_last_error",
-           "ga3c_tuner_create", "ga3c_tuner_report", "ga3c_tuner_state", "ga3c_tuner_destroy")
+           "ga3c_tuner_create", "ga3c_tuner_report", "ga3c_tuner_state", "ga3c_tuner_destroy", "ga3c_tuner_set_margin",
+           "ga3c_tuner_progress")
 
 
 def load_library() -> C.CDLL:
@@ -164,6 +166,8 @@ def load_library() -> C.CDLL:
     lib.ga3c_tuner_report.argtypes = [vp, C.c_double, C.POINTER(i32), C.POINTER(i32)]
     lib.ga3c_tuner_state.argtypes = [vp, C.POINTER(i32), C.POINTER(i32), C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
     lib.ga3c_tuner_destroy.argtypes = [vp]
+    lib.ga3c_tuner_set_margin.argtypes = [vp, C.c_double]
+    lib.ga3c_tuner_progress.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
     lib.ga3c_use_generic_kernels.argtypes = [vp, i32]
     lib.ga3c_profile_read.argtypes = [vp, C.c_char_p, sz]
     _lib = lib
@@ -366,10 +370,15 @@ class Tuner:
         _scheck(self._lib.ga3c_tuner_report(self._t, throughput, C.byref(p), C.byref(t)), "ga3c_tuner_report")
         return p.value, t.value
 
+    def set_margin(self, margin: float) -> None:
+        _scheck(self._lib.ga3c_tuner_set_margin(self._t, margin), "ga3c_tuner_set_margin")
+
     def state(self):
-        p, t, a, r = C.c_int(), C.c_int(), C.c_int64(), C.c_int64()
+        p, t, a, r, w, lc = C.c_int(), C.c_int(), C.c_int64(), C.c_int64(), C.c_int64(), C.c_int64()
         _scheck(self._lib.ga3c_tuner_state(self._t, C.byref(p), C.byref(t), C.byref(a), C.byref(r)), "ga3c_tuner_state")
-        return {"predict_cap": p.value, "train_cap": t.value, "accepted": a.value, "rejected": r.value}
+        _scheck(self._lib.ga3c_tuner_progress(self._t, C.byref(w), C.byref(lc)), "ga3c_tuner_progress")
+        return {"predict_cap": p.value, "train_cap": t.value, "accepted": a.value, "rejected": r.value,
+                "windows": w.value, "last_change_window": lc.value}
 
     def __del__(self):
         try:
@@ -383,11 +392,11 @@ class Scheduler:
 
     def __init__(self, net: Ga3c, hp: HParams, t_max=5, predict_cap=256, train_min=40, train_cap=1280,
                  adjust_period=0, predict_cap_lo=1, predict_cap_hi=256, train_cap_lo=40, train_cap_hi=1280,
-                 train_cap_step=40, seed=0):
+                 train_cap_step=40, seed=0, adjust_margin=0.0):
         self._lib = load_library()
         self._net = net
         cfg = _SchedConfig(t_max, predict_cap, train_min, train_cap, adjust_period, predict_cap_lo, predict_cap_hi,
-                           train_cap_lo, train_cap_hi, train_cap_step, seed, hp.c())
+                           train_cap_lo, train_cap_hi, train_cap_step, seed, hp.c(), adjust_margin)
         self._s = C.c_void_p()
         self.t_max = t_max
         _scheck(self._lib.ga3c_sched_create(net._ctx, C.byref(cfg), C.byref(self._s)), "ga3c_sched_create")

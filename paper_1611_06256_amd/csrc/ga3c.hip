@@ -966,7 +966,7 @@ struct ReduceSeg {
     int nz, M, N, r0, rows, bias_col, zg, first_block;
     int per_xcd;         // the segment owns 8 * per_xcd block ids, first_block is a multiple of 8
 };
-constexpr int MAX_REDUCE_SEGS = 8;
+constexpr int MAX_REDUCE_SEGS = 12;
 struct ReduceArgs {
     ReduceSeg seg[MAX_REDUCE_SEGS];
     int nseg;
@@ -1771,7 +1771,9 @@ static int train_step_impl(ga3c_ctx *c, const uint8_t *frames, const int32_t *ac
         ws_used += (floats + 63) / 64 * 64;
         return r;
     };
+    bool seg_overflow = false;
     auto add_seg = [&](const float *ws, int nz_, int M, int Ncols, int r0, int rows, float *gW, float *gb, int bias_col) {
+        if (red.nseg >= MAX_REDUCE_SEGS) { seg_overflow = true; return; }
         ReduceSeg &g = red.seg[red.nseg++];
         g.ws = ws; g.nz = nz_; g.M = M; g.N = Ncols; g.r0 = r0; g.rows = rows; g.gW = gW; g.gb = gb; g.bias_col = bias_col;
         int zg = 1;
@@ -1952,6 +1954,7 @@ static int train_step_impl(ga3c_ctx *c, const uint8_t *frames, const int32_t *ac
             }
     }
     // all partial gradients -> gradient and its squared norm; then clip scale and stats; then RMSProp
+    if (seg_overflow) return fail(GA3C_EINVAL, "internal: more partial-gradient segments than the reduction kernel takes");
     if (red_blocks > c->max_norm_parts) return fail(GA3C_EINVAL, "internal: too many reduce blocks");
     {
         STAGE("wgrad_reduce", 0, red_bytes);

@@ -22,18 +22,11 @@
 #include <vector>
 
 #include "../../include/ga3c.h"
+#include "sched_error.hpp"
+
+using ga3c::sfail;
 
 namespace {
-
-thread_local char s_err[512] = "";
-
-int sfail(int code, const char *fmt, ...) {
-    va_list ap;
-    va_start(ap, fmt);
-    vsnprintf(s_err, sizeof(s_err), fmt, ap);
-    va_end(ap);
-    return code;
-}
 
 #define SHIP(expr)                                                                                   \
     do {                                                                                             \
@@ -42,14 +35,6 @@ int sfail(int code, const char *fmt, ...) {
             return sfail(e_ == hipErrorOutOfMemory ? GA3C_ENOMEM : GA3C_EHIP, "%s: %s", #expr,       \
                          hipGetErrorString(e_));                                                     \
     } while (0)
-
-uint64_t splitmix(uint64_t &x) {
-    x += 0x9E3779B97F4A7C15ull;
-    uint64_t z = x;
-    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
-    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
-    return z ^ (z >> 31);
-}
 
 // Copies whole frames by pointer: dst[i] = *src[i], frame_vecs 16-byte vectors each.
 __global__ __launch_bounds__(256) void gather_frames_kernel(const uint4 *const *__restrict__ src, uint4 *__restrict__ dst,
@@ -60,89 +45,6 @@ __global__ __launch_bounds__(256) void gather_frames_kernel(const uint4 *const *
 }
 
 }  // namespace
-
-// ---------------------------------------------------------------- tuner -----
-
-// Sec. 4.3: every period one knob is changed at random by one step; the change
-// is kept if the throughput did not drop, otherwise undone.  Knobs here are the
-// two batch caps: the prediction cap moves on the ladder lo, 2 lo, 4 lo, ...
-// (one step = a factor 2), the training cap in steps of t_step frames.
-struct ga3c_tuner {
-    int p_lo, p_hi, t_lo, t_hi, t_step;
-    int p, t;              // configuration now running
-    int kept_p, kept_t;    // last accepted configuration
-    double kept_thr;       // its throughput
-    bool have_ref, trial;
-    uint64_t rng;
-    int64_t accepted, rejected;
-};
-
-extern "C" int ga3c_tuner_create(int p_lo, int p_hi, int p0, int t_lo, int t_hi, int t_step, int t0, uint64_t seed,
-                                 ga3c_tuner **out) {
-    if (out) *out = nullptr;
-    if (!out || p_lo < 1 || p_hi < p_lo || p0 < p_lo || p0 > p_hi || t_lo < 1 || t_hi < t_lo || t0 < t_lo || t0 > t_hi ||
-        t_step < 1)
-        return sfail(GA3C_EINVAL, "ga3c_tuner_create: bad bounds");
-    ga3c_tuner *t = new (std::nothrow) ga3c_tuner();
-    if (!t) return sfail(GA3C_ENOMEM, "ga3c_tuner_create: out of memory");
-    t->p_lo = p_lo; t->p_hi = p_hi; t->t_lo = t_lo; t->t_hi = t_hi; t->t_step = t_step;
-    t->p = t->kept_p = p0; t->t = t->kept_t = t0;
-    t->kept_thr = 0.0; t->have_ref = false; t->trial = false;
-    t->rng = seed; t->accepted = t->rejected = 0;
-    *out = t;
-    return GA3C_OK;
-}
-
-extern "C" int ga3c_tuner_destroy(ga3c_tuner *t) {
-    delete t;
-    return GA3C_OK;
-}
-
-// End of a measurement window that ran the current configuration with the
-// given throughput.  Decides about the trial (if one was running), then
-// proposes the next configuration and returns it.
-extern "C" int ga3c_tuner_report(ga3c_tuner *t, double throughput, int *predict_cap, int *train_cap) {
-    if (!t) return sfail(GA3C_EINVAL, "ga3c_tuner_report: null tuner");
-    if (t->trial && t->have_ref && throughput < t->kept_thr) {
-        t->rejected += 1;                       // undo; the reference stays
-    } else {
-        if (t->trial) t->accepted += 1;
-        t->kept_p = t->p; t->kept_t = t->t;
-        t->kept_thr = throughput; t->have_ref = true;
-    }
-    // next trial: one knob, one step, random direction; a step that would leave
-    // the bounds goes the other way, a knob with a single value is skipped
-    int np = t->kept_p, nt = t->kept_t;
-    for (int tries = 0; tries < 8; ++tries) {
-        const uint64_t r = splitmix(t->rng);
-        const bool knob_p = (r & 1) == 0;
-        const bool up = (r & 2) != 0;
-        if (knob_p) {
-            int c = up ? t->kept_p * 2 : t->kept_p / 2;
-            if (c > t->p_hi || c < t->p_lo) c = up ? t->kept_p / 2 : t->kept_p * 2;
-            if (c >= t->p_lo && c <= t->p_hi && c != t->kept_p) { np = c; break; }
-        } else {
-            int c = up ? t->kept_t + t->t_step : t->kept_t - t->t_step;
-            if (c > t->t_hi || c < t->t_lo) c = up ? t->kept_t - t->t_step : t->kept_t + t->t_step;
-            if (c >= t->t_lo && c <= t->t_hi && c != t->kept_t) { nt = c; break; }
-        }
-    }
-    t->p = np; t->t = nt;
-    t->trial = (np != t->kept_p) || (nt != t->kept_t);
-    if (predict_cap) *predict_cap = t->p;
-    if (train_cap) *train_cap = t->t;
-    return GA3C_OK;
-}
-
-extern "C" int ga3c_tuner_state(const ga3c_tuner *t, int *kept_predict_cap, int *kept_train_cap, int64_t *accepted,
-                                int64_t *rejected) {
-    if (!t) return sfail(GA3C_EINVAL, "ga3c_tuner_state: null tuner");
-    if (kept_predict_cap) *kept_predict_cap = t->kept_p;
-    if (kept_train_cap) *kept_train_cap = t->kept_t;
-    if (accepted) *accepted = t->accepted;
-    if (rejected) *rejected = t->rejected;
-    return GA3C_OK;
-}
 
 // ------------------------------------------------------------- scheduler ----
 
@@ -281,11 +183,11 @@ int issue_predict(ga3c_sched *s, int *count) {
         SHIP(hipEventSynchronize(p.done));
         STRY(harvest(s, false));
     }
+    // the requests leave the queue only when the whole batch has been enqueued: a failing GPU call loses none
     const int n = (int)std::min<size_t>(s->pq.size(), (size_t)s->predict_cap);
     p.agents.resize(n);
     for (int i = 0; i < n; ++i) {
-        const PredReq r = s->pq.front();
-        s->pq.pop_front();
+        const PredReq &r = s->pq[i];
         p.agents[i] = r.agent; p.ptrs_h[i] = (const uint4 *)r.frame; p.unif_h[i] = r.uniform;
     }
     SHIP(hipMemcpyAsync(p.ptrs_d, p.ptrs_h, sizeof(void *) * n, hipMemcpyHostToDevice, s->sp));
@@ -299,6 +201,7 @@ int issue_predict(ga3c_sched *s, int *count) {
     SHIP(hipMemcpyAsync(p.act_h, p.act_d, sizeof(int32_t) * n, hipMemcpyDeviceToHost, s->sp));
     SHIP(hipMemcpyAsync(p.val_h, p.val_d, sizeof(float) * n, hipMemcpyDeviceToHost, s->sp));
     SHIP(hipEventRecord(p.done, s->sp));
+    s->pq.erase(s->pq.begin(), s->pq.begin() + n);
     p.busy = true; p.n = n;
     p.version = s->stats.train_batches;      // the call above reads the parameters that this many updates produced
     s->ps_next = (s->ps_next + 1) % RING;
@@ -310,18 +213,22 @@ int issue_predict(ga3c_sched *s, int *count) {
 int issue_train(ga3c_sched *s, int *count) {
     *count = 0;
     const int T = s->cfg.t_max;
-    if (s->tq.empty() || s->tq_frames < s->cfg.train_min) return GA3C_OK;      // merge until the minimum batch is there
+    // merge until the minimum batch is there (Sec. 5.3).  With the adjustment on, its training knob is the batch size
+    // itself: an update waits for train_cap frames and takes at most as many, so the knob decides how large the
+    // updates are whatever the pace at which segments arrive
+    const int need = s->tuner ? std::max(s->cfg.train_min, s->train_cap) : s->cfg.train_min;
+    if (s->tq.empty() || s->tq_frames < need) return GA3C_OK;
     TrainSlot &t = s->ts[s->ts_next];
     if (t.busy) {
         SHIP(hipEventSynchronize(t.done));
         t.busy = false;
     }
-    // whole segments, oldest first, while they fit the cap (the first one always goes)
+    // whole segments, oldest first, while they fit the cap (the first one always goes); they leave the queue, and
+    // enter the statistics, only when the update has been enqueued: a failing GPU call loses none
     int n = 0, B = 0;
     bool equal = true;
-    const int64_t now = s->stats.train_batches;       // updates issued so far = the version this update starts from
-    while (!s->tq.empty() && (n == 0 || B + s->tq.front().len <= s->train_cap)) {
-        Traj &tr = s->tq.front();
+    while ((size_t)n < s->tq.size() && (n == 0 || B + s->tq[n].len <= s->train_cap)) {
+        const Traj &tr = s->tq[n];
         const int L = tr.len;
         for (int k = 0; k < L; ++k) t.ptrs_h[B + k] = (const uint4 *)(tr.frames + (size_t)k * s->frame_bytes);
         memcpy(t.act_h + B, tr.actions.data(), sizeof(int32_t) * L);
@@ -329,15 +236,8 @@ int issue_train(ga3c_sched *s, int *count) {
         memcpy(t.done_h + B, tr.dones.data(), L);
         t.boot_h[n] = tr.bootstrap;
         t.seg_h[n] = B;
-        if (L != T) { equal = false; s->stats.short_segments += 1; }
-        if (tr.version >= 0) {
-            const int64_t lag = now - tr.version;
-            s->stats.lag_sum += lag; s->stats.lag_count += 1;
-            s->stats.lag_max = std::max(s->stats.lag_max, lag);
-        }
+        if (L != T) equal = false;
         B += L; n += 1;
-        s->tq_frames -= L;
-        s->tq.pop_front();
     }
     t.seg_h[n] = B;
     SHIP(hipMemcpyAsync(t.ptrs_d, t.ptrs_h, sizeof(void *) * B, hipMemcpyHostToDevice, s->st));
@@ -356,6 +256,18 @@ int issue_train(ga3c_sched *s, int *count) {
                                                   &s->cfg.hp, nullptr, s->st);
     if (rc != GA3C_OK) return sfail(GA3C_EHIP, "ga3c_train_step: %s", ga3c_last_error());
     SHIP(hipEventRecord(t.done, s->st));
+    const int64_t now = s->stats.train_batches;       // updates issued before this one = the version it starts from
+    for (int i = 0; i < n; ++i) {
+        const Traj &tr = s->tq[i];
+        if (tr.len != T) s->stats.short_segments += 1;
+        if (tr.version >= 0) {
+            const int64_t lag = now - tr.version;
+            s->stats.lag_sum += lag; s->stats.lag_count += 1;
+            s->stats.lag_max = std::max(s->stats.lag_max, lag);
+        }
+        s->tq_frames -= tr.len;
+    }
+    s->tq.erase(s->tq.begin(), s->tq.begin() + n);
     t.busy = true; t.n_agents = n;
     s->ts_next = (s->ts_next + 1) % RING;
     s->stats.trained_frames += (int64_t)B; s->stats.train_batches += 1;
@@ -398,11 +310,12 @@ extern "C" int ga3c_sched_create(ga3c_ctx *ctx, const ga3c_sched_config *cfg, ga
     if (rc == GA3C_OK && cfg->adjust_period > 0)
         rc = ga3c_tuner_create(cfg->predict_cap_lo, cfg->predict_cap_hi, cfg->predict_cap, cfg->train_cap_lo,
                                cfg->train_cap_hi, cfg->train_cap_step, cfg->train_cap, cfg->seed, &s->tuner);
+    if (rc == GA3C_OK && s->tuner && cfg->adjust_margin > 0.f) rc = ga3c_tuner_set_margin(s->tuner, cfg->adjust_margin);
     if (rc != GA3C_OK) {
-        char keep[sizeof(s_err)];
-        memcpy(keep, s_err, sizeof(keep));
+        char keep[512];
+        snprintf(keep, sizeof(keep), "%s", ga3c::sched_error_text());
         ga3c_sched_destroy(s);
-        memcpy(s_err, keep, sizeof(keep));
+        sfail(rc, "%s", keep);
         return rc;
     }
     s->window_start = std::chrono::steady_clock::now();
@@ -535,6 +448,7 @@ extern "C" int ga3c_sched_tick(ga3c_sched *s, int *predicted, int *trained) {
             s->stats.last_window_frames_per_s = thr;
             s->stats.predict_cap = s->predict_cap; s->stats.train_cap = s->train_cap;
             ga3c_tuner_state(s->tuner, nullptr, nullptr, &s->stats.trials_accepted, &s->stats.trials_rejected);
+            ga3c_tuner_progress(s->tuner, &s->stats.windows, &s->stats.last_change_window);
             s->window_ticks = s->window_frames = 0;
             s->window_start = std::chrono::steady_clock::now();
         }
@@ -568,4 +482,3 @@ extern "C" int ga3c_sched_get_stats(const ga3c_sched *s, ga3c_sched_stats *out) 
     return GA3C_OK;
 }
 
-extern "C" const char *ga3c_sched_last_error(void) { return s_err; }

@@ -146,7 +146,7 @@ def test_dynamic_adjustment_runs_within_bounds(G):
     polled += len(sched.poll())
     st = sched.stats()
     assert polled == st["predictions"] == 40 * N
-    assert st["trials_accepted"] + st["trials_rejected"] >= 20
+    assert st["windows"] >= 25 and st["trials_accepted"] + st["trials_rejected"] >= 10     # a rejected trial costs a second window
     assert best > 0
     assert np.isfinite(ns.params_get(0).cpu().numpy()).all()
     sched.close(); ns.close(); nd.close()
