@@ -23,8 +23,11 @@ median block, `spread` holds min / median / max.
 
 Prints ONE JSON line.  `value` = frames per second through predict AND
 train_step (each frame is predicted once and trained on once).  The line also
-carries: predict-only and train-only rates; per-stage times measured with HIP
-events inside the library; the roofline of the dominant kernel; the
+carries: predict-only and train-only rates; per-stage times (the execution
+time of each stage's kernel between two HIP events that the runtime stamps at
+the start and the end of that very dispatch, on the call's own stream: the
+same figure a kernel trace shows, a one-stream pass); the roofline of the
+dominant kernel; the
 prediction sweep (batch 1 .. 1024); the larger network (predict 256, train
 1280; fp32-grade and bfloat16-operand arithmetic); RMSProp on 2^28 parameters;
 the queue system under synthetic agents (fixed caps against the Sec. 4.3
@@ -68,17 +71,17 @@ TIMED_BLOCKS = 10
 # 0.5000 and 1.0000 of the known bytes, hence the scale factors.  The summary is kept under profiles/.
 FETCH_SCALE, WRITE_SCALE = 2.0, 1.0
 COUNTER_KIB = {   # stage: {frames per launch: (FETCH_SIZE, WRITE_SIZE)}
-    "conv12_fwd": {512: (7554.7, 5184.0), 1024: (14626.7, 10368.0), 2560: (36536.2, 94053.3)},   # 2560: training, keeps y1
-    "fc_fwd": {512: (4153.0, 7168.0), 1024: (6649.0, 8192.0), 2560: (14425.0, 20480.0)},
-    "heads_fwd": {512: (3789.0, 592.0), 1024: (4282.0, 1104.0)},
-    "heads_train": {2560: (10524.6, 9396.2)},
+    "conv12_fwd": {512: (7559.2, 5184.0), 1024: (14631.2, 10368.1), 2560: (36798.7, 95058.9)},   # 2560: training, keeps y1
+    "fc_fwd": {512: (4153.5, 7168.0), 1024: (6649.5, 8192.0), 2560: (14425.5, 20480.4)},
+    "heads_fwd": {512: (3791.5, 592.0), 1024: (4284.5, 1104.0)},
+    "heads_train": {2560: (10548.0, 11959.0)},
     "conv1_wgrad": {2560: (67617.1, 4112.0)},
-    "conv2_wgrad": {2560: (45123.3, 16558.4)},
-    "conv2_dgrad": {2560: (45193.5, 64000.0)},
-    "fc_wgrad": {2560: (19955.3, 20736.0)},
-    "fc_dgrad": {2560: (25372.6, 27011.7)},
-    "wgrad_reduce": {2560: (24878.8, 2809.9)},
-    "rmsprop": {2560: (4019.6, 5394.1)},
+    "conv2_wgrad": {2560: (45125.4, 16567.4)},
+    "conv2_dgrad": {2560: (45192.7, 64000.0)},
+    "fc_wgrad": {2560: (19886.1, 20736.0)},
+    "fc_dgrad": {2560: (25355.0, 27003.9)},
+    "wgrad_reduce": {2560: (24931.0, 2808.2)},
+    "rmsprop": {2560: (4111.6, 5394.2)},
 }
 
 # HIP kernel behind each stage of the small net's fast path, and the larger net's
@@ -246,7 +249,7 @@ def main() -> int:
     train_secs = timed_blocks(train_fn, max(args.steps, 20), 5)
     pred_sec, train_sec = statistics.median(pred_secs), statistics.median(train_secs)
 
-    # per-stage times with HIP events recorded by the library on the call's own stream
+    # per-stage times: an event pair per kernel launch, stamped at the dispatch's own start and end
     net.profile_enable(True)
     for _ in range(args.steps):
         step()

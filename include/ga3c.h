@@ -217,10 +217,12 @@ int ga3c_rmsprop_flat(float *theta_dev, float *g_dev, const float *grad_dev, siz
 int ga3c_use_generic_kernels(ga3c_ctx *ctx, int on);
 
 /* Per-stage timing for measurement, off by default.  While it is on, every
- * kernel launch (or group of launches that forms one stage) of ga3c_predict
- * and ga3c_train_step is bracketed by two HIP events recorded on the call's
- * stream.  ga3c_profile_read waits for the recorded events, adds up the
- * elapsed times and writes one text line per stage into the HOST buffer buf:
+ * kernel that ga3c_predict and ga3c_train_step launch carries a pair of HIP
+ * events which the runtime stamps with the start and the end of that very
+ * dispatch: a stage's time is the sum of the execution times of its kernels
+ * (what a kernel trace shows), without queueing or dispatch latency.
+ * ga3c_profile_read waits for the recorded events, adds up the elapsed times
+ * and writes one text line per stage into the HOST buffer buf:
  *   "<stage> <calls> <total_ms> <algorithmic_flop> <algorithmic_bytes>\n"
  * then forgets what it has reported.  Returns GA3C_EINVAL if cap is too small.
  * The flop and byte figures are those of the method (2 per multiply-add of

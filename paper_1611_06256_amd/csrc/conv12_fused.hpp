@@ -24,6 +24,8 @@
 //    tile each, one iteration later, so that no extra barrier is needed.
 #pragma once
 #include <hip/hip_runtime.h>
+
+#include "launch.hpp"
 #include <stdint.h>
 
 #include "conv1_bf16x3.hpp"
@@ -105,7 +107,7 @@ __device__ __forceinline__ void conv12_store_fragment4(u32x4 *__restrict__ frag,
 }
 
 inline hipError_t launch_conv12_filter_fragments(const float *w1, const float *w2, u32x4 *frag, hipStream_t s, int rb) {
-    hipLaunchKernelGGL(conv12_filter_fragments_kernel, dim3(1), dim3(192), 0, s, w1, w2, frag, rb);
+    ga3c::launch(conv12_filter_fragments_kernel, dim3(1), dim3(192), 0, s, w1, w2, frag, rb);
     return hipGetLastError();
 }
 
@@ -411,7 +413,7 @@ inline hipError_t launch_conv12_fused_fwd(const uint8_t *x, const u32x4 *frag, c
     }
     const dim3 grid(conv12_fused_blocks(nframes)), block(512);
 #define GA3C_C12_LAUNCH(ONE_, KEEP_)                                                                                          \
-    hipLaunchKernelGGL((conv12_fused_fwd_kernel<ONE_, KEEP_>), grid, block, C12_LDS_BYTES, s, x, frag, b1, b2, y1, y2, nframes, \
+    ga3c::launch((conv12_fused_fwd_kernel<ONE_, KEEP_>), grid, block, C12_LDS_BYTES, s, x, frag, b1, b2, y1, y2, nframes, \
                        scale, rb)
     if (rb) { if (y1) GA3C_C12_LAUNCH(true, true); else GA3C_C12_LAUNCH(true, false); }
     else { if (y1) GA3C_C12_LAUNCH(false, true); else GA3C_C12_LAUNCH(false, false); }

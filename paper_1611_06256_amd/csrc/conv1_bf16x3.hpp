@@ -11,6 +11,8 @@
 // layer then runs at the speed of fetching frames and storing activations.
 #pragma once
 #include <hip/hip_runtime.h>
+
+#include "launch.hpp"
 #include <stdint.h>
 
 #include <type_traits>
@@ -197,7 +199,7 @@ inline hipError_t launch_conv1_bf16x3_fwd(const uint8_t *x, const float *w, cons
                                           float scale, hipStream_t s, int rb = 0) {
     if (nframes <= 0) return hipSuccess;
     const int grid = nframes < 512 ? nframes : 512;
-    hipLaunchKernelGGL((conv1_bf16x3_fwd_kernel<OC>), dim3(grid), dim3(256), 0, s, x, w, bias, y, nframes, scale, rb);
+    ga3c::launch((conv1_bf16x3_fwd_kernel<OC>), dim3(grid), dim3(256), 0, s, x, w, bias, y, nframes, scale, rb);
     return hipGetLastError();
 }
 
@@ -405,7 +407,7 @@ template <int OCT = 16, int NPART = 4>
 inline hipError_t launch_conv1_bf16x3_wgrad(const uint8_t *x, const float *dy, float *part, int nframes, float scale,
                                             hipStream_t s, int rb = 0) {
     if (nframes <= 0) return hipSuccess;
-    hipLaunchKernelGGL((conv1_bf16x3_wgrad_kernel<OCT, NPART>), dim3(conv1_bf16x3_wgrad_blocks(nframes), OCT / 16),
+    ga3c::launch((conv1_bf16x3_wgrad_kernel<OCT, NPART>), dim3(conv1_bf16x3_wgrad_blocks(nframes), OCT / 16),
                        dim3(256 * NPART), 0, s, x, dy, part, nframes, scale, rb);
     return hipGetLastError();
 }

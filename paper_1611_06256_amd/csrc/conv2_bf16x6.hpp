@@ -6,6 +6,8 @@
 // three bf16 planes, the split filters in registers.
 #pragma once
 #include <hip/hip_runtime.h>
+
+#include "launch.hpp"
 #include <stdint.h>
 
 #include "conv1_bf16x3.hpp"
@@ -125,7 +127,7 @@ inline hipError_t launch_conv2_bf16x6_fwd(const float *x, const float *w, const 
                                           hipStream_t s, int rb = 0) {
     if (nframes <= 0) return hipSuccess;
     const int grid = nframes < 512 ? nframes : 512;
-    hipLaunchKernelGGL(conv2_bf16x6_fwd_kernel, dim3(grid), dim3(256), 0, s, x, w, bias, y, nframes, rb);
+    ga3c::launch(conv2_bf16x6_fwd_kernel, dim3(grid), dim3(256), 0, s, x, w, bias, y, nframes, rb);
     return hipGetLastError();
 }
 

@@ -25,6 +25,8 @@
 // fragments for the whole launch.
 #pragma once
 #include <hip/hip_runtime.h>
+
+#include "launch.hpp"
 #include <stdint.h>
 
 #include "conv1_bf16x3.hpp"
@@ -213,10 +215,10 @@ inline hipError_t launch_conv_dgrad_bf16x6(const float *dy, const float *w, cons
         attr_set = true;
     }
     if (rb)
-        hipLaunchKernelGGL((conv_dgrad_bf16x6_kernel<SP, true>), dim3(grid, SLICES), dim3(256), G::lds_bytes(true), s, dy, w, xin,
+        ga3c::launch((conv_dgrad_bf16x6_kernel<SP, true>), dim3(grid, SLICES), dim3(256), G::lds_bytes(true), s, dy, w, xin,
                            dx, nframes);
     else
-        hipLaunchKernelGGL((conv_dgrad_bf16x6_kernel<SP, false>), dim3(grid, SLICES), dim3(256), G::lds_bytes(false), s, dy, w,
+        ga3c::launch((conv_dgrad_bf16x6_kernel<SP, false>), dim3(grid, SLICES), dim3(256), G::lds_bytes(false), s, dy, w,
                            xin, dx, nframes);
     return hipGetLastError();
 }

@@ -8,6 +8,8 @@
 // registers.  The products run on v_mfma_f32_16x16x4_f32.
 #pragma once
 #include <hip/hip_runtime.h>
+
+#include "launch.hpp"
 #include <stdint.h>
 
 #include "gemm_mfma.hpp"
@@ -197,7 +199,7 @@ template <class SP, int KSL = 1, int NW = 4>
 inline hipError_t launch_conv_wgrad_frame(const typename SP::TIn *x, const float *dy, float *part, int nframes,
                                           float scale, hipStream_t s, int rb = 0) {
     if (nframes <= 0) return hipSuccess;
-    hipLaunchKernelGGL((conv_wgrad_frame_kernel<SP, KSL, NW>), dim3(conv_wgrad_frame_blocks<SP>(nframes), KSL), dim3(64 * NW), 0,
+    ga3c::launch((conv_wgrad_frame_kernel<SP, KSL, NW>), dim3(conv_wgrad_frame_blocks<SP>(nframes), KSL), dim3(64 * NW), 0,
                        s, x, dy, part, nframes, scale, rb);
     return hipGetLastError();
 }

@@ -32,6 +32,8 @@
 // planes is zeroed once and only the interior is staged.
 #pragma once
 #include <hip/hip_runtime.h>
+
+#include "launch.hpp"
 #include <stdint.h>
 
 #include "conv1_bf16x3.hpp"
@@ -226,10 +228,10 @@ inline hipError_t launch_conv_bf16x6_impl(const float *x, const float *w, const 
         attr_set = true;
     }
     if (rb)
-        hipLaunchKernelGGL((conv_fwd_bf16x6_kernel<SP, NW, true, DGRAD>), dim3(grid), dim3(64 * NW), G::lds_bytes(true), s, x, w,
+        ga3c::launch((conv_fwd_bf16x6_kernel<SP, NW, true, DGRAD>), dim3(grid), dim3(64 * NW), G::lds_bytes(true), s, x, w,
                            aux, y, nframes);
     else
-        hipLaunchKernelGGL((conv_fwd_bf16x6_kernel<SP, NW, false, DGRAD>), dim3(grid), dim3(64 * NW), G::lds_bytes(false), s, x,
+        ga3c::launch((conv_fwd_bf16x6_kernel<SP, NW, false, DGRAD>), dim3(grid), dim3(64 * NW), G::lds_bytes(false), s, x,
                            w, aux, y, nframes);
     return hipGetLastError();
 }

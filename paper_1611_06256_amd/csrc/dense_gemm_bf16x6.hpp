@@ -12,6 +12,8 @@
 // dense_gemm.hpp (see there).
 #pragma once
 #include <hip/hip_runtime.h>
+
+#include "launch.hpp"
 #include <stdint.h>
 
 #include "conv1_bf16x3.hpp"
@@ -207,10 +209,10 @@ inline hipError_t launch_dense_gemm_bf16x6(DenseGemmArgs p, int split, hipStream
     if (split == DG_SPLIT_Z) p.per_xcd = ((p.nz + DG_XCDS - 1) / DG_XCDS) * p.ntm * p.ntn;
     else p.per_xcd = ((p.ntn + DG_XCDS - 1) / DG_XCDS) * p.ntm * p.nz;
     if (p.rb)
-        hipLaunchKernelGGL((dense_gemm_bf16x6_kernel<TM, TN, WM, WN, A_ROWMAJOR, B_ROWMAJOR, EPI, true>),
+        ga3c::launch((dense_gemm_bf16x6_kernel<TM, TN, WM, WN, A_ROWMAJOR, B_ROWMAJOR, EPI, true>),
                            dim3(DG_XCDS * p.per_xcd), dim3(WM * WN * 64), 0, s, p);
     else
-        hipLaunchKernelGGL((dense_gemm_bf16x6_kernel<TM, TN, WM, WN, A_ROWMAJOR, B_ROWMAJOR, EPI, false>),
+        ga3c::launch((dense_gemm_bf16x6_kernel<TM, TN, WM, WN, A_ROWMAJOR, B_ROWMAJOR, EPI, false>),
                            dim3(DG_XCDS * p.per_xcd), dim3(WM * WN * 64), 0, s, p);
     return hipGetLastError();
 }

@@ -4,6 +4,8 @@
 // The matrix products are instances of gemm_mfma.hpp / problems.hpp.
 #include <hip/hip_runtime.h>
 
+#include "launch.hpp"
+
 #include <algorithm>
 #include <cmath>
 #include <cstdarg>
@@ -68,7 +70,7 @@ struct Work {            // activations of one call; predict and train own one e
 }  // namespace
 
 namespace {
-// Optional per-stage timing with HIP events on the stream of the call.
+// Optional per-stage timing: the execution times of the kernels of each stage (an event pair per launch).
 struct ProfStage { const char *name; long calls; double ms, flop, bytes; };
 struct ProfRec { int stage; hipEvent_t a, b; };
 struct Profiler {
@@ -1186,26 +1188,35 @@ int mark_readers(ga3c_ctx *c, int i, hipStream_t s) {
 }
 #define TRY(expr) do { int rc_ = (expr); if (rc_ != GA3C_OK) return rc_; } while (0)
 
-// Brackets the kernels launched during its lifetime with two events when
-// profiling is on; costs one branch when it is off.
-struct ProfScope {
-    Profiler *p; hipStream_t s; int idx;
-    ProfScope(ga3c_ctx *c, hipStream_t st, const char *name, double flop, double bytes) : p(c->prof), s(st), idx(-1) {
+// While one of these is alive and profiling is on, every kernel launched by this host thread carries an event pair
+// of its own (launch.hpp), booked to the stage: the stage's time is the sum of its kernels' execution times.  Costs
+// one branch when profiling is off.
+struct ProfScope final : ga3c::LaunchTimer {
+    Profiler *p; int sid;
+    ProfScope(ga3c_ctx *c, hipStream_t, const char *name, double flop, double bytes) : p(c->prof), sid(-1) {
         if (!p || !p->on) { p = nullptr; return; }
-        int sid = -1;
         for (size_t i = 0; i < p->stages.size(); ++i) if (!strcmp(p->stages[i].name, name)) { sid = (int)i; break; }
         if (sid < 0) { p->stages.push_back({name, 0, 0.0, 0.0, 0.0}); sid = (int)p->stages.size() - 1; }
         p->stages[sid].calls += 1; p->stages[sid].flop += flop; p->stages[sid].bytes += bytes;
+        ga3c::launch_timer = this;
+    }
+    bool next_events(hipEvent_t *start, hipEvent_t *stop) override {
         ProfRec r; r.stage = sid; r.a = r.b = nullptr;
         for (hipEvent_t *e : {&r.a, &r.b}) {
             if (!p->pool.empty()) { *e = p->pool.back(); p->pool.pop_back(); }
             else if (hipEventCreate(e) != hipSuccess) { *e = nullptr; }
         }
-        if (!r.a || !r.b) { p = nullptr; return; }
-        (void)hipEventRecord(r.a, s);
-        p->recs.push_back(r); idx = (int)p->recs.size() - 1;
+        if (!r.a || !r.b) {
+            for (hipEvent_t e : {r.a, r.b}) if (e) p->pool.push_back(e);
+            return false;
+        }
+        p->recs.push_back(r);
+        *start = r.a; *stop = r.b;
+        return true;
     }
-    ~ProfScope() { if (p && idx >= 0) (void)hipEventRecord(p->recs[idx].b, s); }
+    ~ProfScope() { if (p) ga3c::launch_timer = nullptr; }
+    ProfScope(const ProfScope &) = delete;
+    ProfScope &operator=(const ProfScope &) = delete;
 };
 #define STAGE(name, flop, bytes) ProfScope prof_scope_(c, s, name, (double)(flop), (double)(bytes))
 
@@ -1331,7 +1342,7 @@ int forward(ga3c_ctx *c, int which, Work &w, const uint8_t *frames, int B, bool 
         const int slices = B <= 8 ? 32 : B <= 16 ? 16 : B <= 32 ? 8 : 4;
         const dim3 grid(B * slices), block(512);
 #define GA3C_SP_LAUNCH(ONE_, SL_)                                                                                              \
-    hipLaunchKernelGGL((predict_small_kernel<ONE_, SL_>), grid, block, C12_LDS_BYTES, s, frames, c->cfrag[which],             \
+    ga3c::launch((predict_small_kernel<ONE_, SL_>), grid, block, C12_LDS_BYTES, s, frames, c->cfrag[which],             \
                        th + c->off[1], th + c->off[3], th + c->off[nb], th + c->off[nb + 1], w.h, c->ticket, c->A,            \
                        th + c->off[nb + 2], th + c->off[nb + 3], th + c->off[nb + 4], th + c->off[nb + 5], logits, values,    \
                        probs, uniforms, actions, 1.f / 255.f, c->rb)
@@ -1430,7 +1441,7 @@ int forward(ga3c_ctx *c, int which, Work &w, const uint8_t *frames, int B, bool 
     static size_t hf_lds_set = 0;
     HIP_TRY(allow_dynamic_lds((const void *)heads_fwd_kernel, hf_lds, hf_lds_set));
     STAGE("heads_fwd", 2.0 * B * c->F * (c->A + 1), 4.0 * (fc_nz + 1) * B * c->F);
-    hipLaunchKernelGGL(heads_fwd_kernel, dim3(cdiv(B, 4)), dim3(256), hf_lds, s, fc_ws, fc_nz,
+    ga3c::launch(heads_fwd_kernel, dim3(cdiv(B, 4)), dim3(256), hf_lds, s, fc_ws, fc_nz,
                        th + c->off[nb + 1], w.h, B, c->F, c->A, th + c->off[nb + 2],
                        th + c->off[nb + 3], th + c->off[nb + 4], th + c->off[nb + 5],
                        keep_zv ? w.zv : nullptr, logits, values, probs, uniforms, actions, c->rb);
@@ -1664,8 +1675,8 @@ extern "C" int ga3c_params_init(ga3c_ctx *c, uint64_t seed, void *stream) {
     // wait for whoever wrote or still reads this copy
     TRY(wait_ready(c, c->cur, s));
     TRY(wait_readers(c, c->cur, s));
-    hipLaunchKernelGGL(fill_kernel, dim3(blocks_for(c->P)), dim3(256), 0, s, theta, c->P, 0.f);
-    hipLaunchKernelGGL(fill_kernel, dim3(blocks_for(c->P)), dim3(256), 0, s, c->g, c->P, 0.f);
+    ga3c::launch(fill_kernel, dim3(blocks_for(c->P)), dim3(256), 0, s, theta, c->P, 0.f);
+    ga3c::launch(fill_kernel, dim3(blocks_for(c->P)), dim3(256), 0, s, c->g, c->P, 0.f);
     HIP_TRY(hipGetLastError());
     const int nb = 2 * c->nconv;
     // weight tensors and their fan-in; biases stay zero
@@ -1676,7 +1687,7 @@ extern "C" int ga3c_params_init(ga3c_ctx *c, uint64_t seed, void *stream) {
     t[nt++] = {c->off[nb + 2], (size_t)c->A * c->F, c->F};
     t[nt++] = {c->off[nb + 4], (size_t)c->F, c->F};
     for (int i = 0; i < nt; ++i) {
-        hipLaunchKernelGGL(init_normal_kernel, dim3(blocks_for(t[i].n)), dim3(256), 0, s, theta + t[i].off,
+        ga3c::launch(init_normal_kernel, dim3(blocks_for(t[i].n)), dim3(256), 0, s, theta + t[i].off,
                            (size_t)t[i].off, t[i].n, sqrtf(2.f / (float)t[i].fan_in), seed);
         HIP_TRY(hipGetLastError());
     }
@@ -1752,7 +1763,7 @@ static int train_step_impl(ga3c_ctx *c, const uint8_t *frames, const int32_t *ac
     float *losspart = c->partials + c->max_norm_parts;
     if (!fused_heads) {
         STAGE("returns_loss", 0, 4.0 * B * (2 * (A + 1) + 4));
-        hipLaunchKernelGGL(returns_loss_kernel, dim3(nloss), dim3(LOSS_THREADS), sizeof(float) * LOSS_THREADS * (A + 1), s, w.zv, actions, rewards, dones,
+        ga3c::launch(returns_loss_kernel, dim3(nloss), dim3(LOSS_THREADS), sizeof(float) * LOSS_THREADS * (A + 1), s, w.zv, actions, rewards, dones,
                            bootstrap, seg_start, N, T, B, A, hp->gamma, hp->beta, hp->value_coef, hp->log_eps, c->R, c->dzv, losspart);
         HIP_TRY(hipGetLastError());
     }
@@ -1793,7 +1804,7 @@ static int train_step_impl(ga3c_ctx *c, const uint8_t *frames, const int32_t *ac
         static size_t ht_lds_set = 0;
         HIP_TRY(allow_dynamic_lds((const void *)heads_train_kernel, ht_lds, ht_lds_set));
         STAGE("heads_train", 6.0 * B * (A + 1) * F, 4.0 * (w.fc_nz + 1) * B * F);
-        hipLaunchKernelGGL(heads_train_kernel, dim3(nblk), dim3(256), ht_lds, s, w.fc_ws, w.fc_nz, th + c->off[nb + 1], B, F, A, Wp,
+        ga3c::launch(heads_train_kernel, dim3(nblk), dim3(256), ht_lds, s, w.fc_ws, w.fc_nz, th + c->off[nb + 1], B, F, A, Wp,
                            th + c->off[nb + 3], Wv, th + c->off[nb + 5], actions, rewards, dones, bootstrap, seg_start, N, T, hp->gamma, hp->beta,
                            hp->value_coef, hp->log_eps, w.h, w.zv, c->R, c->dzv, c->dh, c->colpart, part, losspart, c->rb);
         HIP_TRY(hipGetLastError());
@@ -1805,7 +1816,7 @@ static int train_step_impl(ga3c_ctx *c, const uint8_t *frames, const int32_t *ac
         if (!part) return fail(GA3C_EINVAL, "internal: split-k workspace too small (heads)");
         STAGE("heads_bwd", 4.0 * B * (A + 1) * F, 0);
         HIP_TRY(allow_dynamic_lds((const void *)heads_dgrad_kernel, hd_lds, hd_lds_set));
-        hipLaunchKernelGGL(heads_dgrad_kernel, dim3(nblk), dim3(256), hd_lds, s, c->dzv, w.h, Wp, Wv, B,
+        ga3c::launch(heads_dgrad_kernel, dim3(nblk), dim3(256), hd_lds, s, c->dzv, w.h, Wp, Wv, B,
                            F, A, c->dh, c->colpart, part, c->rb);
         HIP_TRY(hipGetLastError());
         add_seg(part, nblk, A + 1, F + 1, 0, A, c->grad + c->off[nb + 2], c->grad + c->off[nb + 3], 1);
@@ -1827,7 +1838,7 @@ static int train_step_impl(ga3c_ctx *c, const uint8_t *frames, const int32_t *ac
         add_seg(p.C, nz, A + 1, F + 1, A, 1, c->grad + c->off[nb + 4], c->grad + c->off[nb + 5], 1);
         STAGE("heads_dgrad", 2.0 * B * (A + 1) * F, 0);
         HIP_TRY(allow_dynamic_lds((const void *)heads_dgrad_kernel, hd_lds, hd_lds_set));
-        hipLaunchKernelGGL(heads_dgrad_kernel, dim3(cdiv(B, HD_FRAMES)), dim3(256), hd_lds, s, c->dzv, w.h, Wp, Wv, B,
+        ga3c::launch(heads_dgrad_kernel, dim3(cdiv(B, HD_FRAMES)), dim3(256), hd_lds, s, c->dzv, w.h, Wp, Wv, B,
                            F, A, c->dh, c->colpart, (float *)nullptr, c->rb);
         HIP_TRY(hipGetLastError());
     }
@@ -1958,7 +1969,7 @@ static int train_step_impl(ga3c_ctx *c, const uint8_t *frames, const int32_t *ac
     if (red_blocks > c->max_norm_parts) return fail(GA3C_EINVAL, "internal: too many reduce blocks");
     {
         STAGE("wgrad_reduce", 0, red_bytes);
-        hipLaunchKernelGGL(reduce_all_kernel, dim3(red_blocks), dim3(256), 0, s, red);
+        ga3c::launch(reduce_all_kernel, dim3(red_blocks), dim3(256), 0, s, red);
         HIP_TRY(hipGetLastError());
     }
     STAGE("rmsprop", 8.0 * c->P, 20.0 * c->P);
@@ -1969,7 +1980,7 @@ static int train_step_impl(ga3c_ctx *c, const uint8_t *frames, const int32_t *ac
     RmsClip ca;
     ca.normpart = c->partials; ca.nnorm = red_blocks; ca.losspart = losspart; ca.nloss = nloss; ca.clip = hp->clip_norm;
     ca.scale_out = c->scale; ca.own = c->stats; ca.user = stats;
-    hipLaunchKernelGGL((rmsprop_kernel<0, 1>), dim3(rb), dim3(256), 0, s, th, c->theta2[cur ^ 1], c->g, c->grad, c->P, (const float *)nullptr,
+    ga3c::launch((rmsprop_kernel<0, 1>), dim3(rb), dim3(256), 0, s, th, c->theta2[cur ^ 1], c->g, c->grad, c->P, (const float *)nullptr,
                        1.f, hp->lr, hp->rms_decay, hp->rms_eps, c->cfrag[cur ^ 1], (unsigned)c->off[0], (unsigned)c->off[2], c->rb, ca);
     HIP_TRY(hipGetLastError());
     TRY(mark_ready(c, cur ^ 1, s));
@@ -2045,7 +2056,7 @@ extern "C" int ga3c_rmsprop_flat(float *theta, float *g, const float *grad, size
     RmsClip none;
     memset(&none, 0, sizeof(none));
 #define GA3C_RMS_LAUNCH(V)                                                                                               \
-    hipLaunchKernelGGL((rmsprop_kernel<V, 4>), dim3(rb), dim3(256), 0, (hipStream_t)stream, theta, theta, g, grad, n,         \
+    ga3c::launch((rmsprop_kernel<V, 4>), dim3(rb), dim3(256), 0, (hipStream_t)stream, theta, theta, g, grad, n,         \
                        (const float *)nullptr, scale, lr, rms_decay, rms_eps, (u32x4 *)nullptr, 0u, 0u, 0, none)
     if (stream_past_caches) GA3C_RMS_LAUNCH(3); else GA3C_RMS_LAUNCH(0);
 #undef GA3C_RMS_LAUNCH

@@ -22,6 +22,8 @@
 // which is all a dot product needs.
 #pragma once
 #include <hip/hip_runtime.h>
+
+#include "launch.hpp"
 #include <stdint.h>
 
 namespace ga3c {
@@ -161,7 +163,7 @@ inline hipError_t launch_gemm(const P &p, int nz, hipStream_t s) {
     constexpr int BM = 16 * TM * WM, BN = 16 * TN * WN;
     if (p.M <= 0 || p.N <= 0) return hipSuccess;
     dim3 grid((p.N + BN - 1) / BN, (p.M + BM - 1) / BM, nz);
-    hipLaunchKernelGGL((gemm_mfma_kernel<TM, TN, WM, WN, A_ROWS, B_ROWS, P>), grid, dim3(WM * WN * 64), 0, s, p);
+    ga3c::launch((gemm_mfma_kernel<TM, TN, WM, WN, A_ROWS, B_ROWS, P>), grid, dim3(WM * WN * 64), 0, s, p);
     return hipGetLastError();
 }
 
