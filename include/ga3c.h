@@ -340,23 +340,27 @@ int ga3c_sched_get_stats(const ga3c_sched *s, ga3c_sched_stats *out);
 const char *ga3c_sched_last_error(void);
 
 /* The adjustment rule alone (host only, no GPU): caps within [lo, hi]; the
- * prediction cap moves by a factor 2 per step, the training cap by a fraction
- * of its value: a quarter at first, halved after every rejected step of that
- * knob (down to 1/64), doubled after every accepted one (at least t_step, a
- * multiple of t_step; the last step to a bound may be shorter).
+ * prediction cap moves by a factor 2 per step, the training cap by a factor
+ * 1 + 2^-k up or down: k = 0 at first (a factor 2 as well), one finer after
+ * every rejected step of that knob (down to 1 + 1/64), one coarser after a
+ * step that brought a clear gain; training caps are multiples of t_step, a
+ * step is at least t_step, the last step to a bound may be shorter.
  * ga3c_tuner_report closes a window that ran the current caps at the given
  * throughput.  The first two windows measure the starting caps (the
  * reference; the first window also pays for the start of the run).  A trial
  * is kept iff its throughput >= (1 - margin) * reference (margin 0.03 unless
  * set): then the caps are kept and the reference becomes the larger of the two
- * readings; if the gain exceeded half the margin the same knob is stepped in
- * the same direction again.  A trial that is not kept is undone and the next
- * window runs the kept caps again (a higher reading replaces the reference, a
- * lower one is averaged into it).  Otherwise one knob is stepped in a random
- * direction (not the same knob three times in a row; not a direction that
- * was rejected from the knob's present value, unless the other one has been
- * rejected since).  The new caps are returned.  Deterministic for a given seed
- * and sequence of readings. */
+ * readings; if the gain exceeded half the margin ("clear gain") the same knob
+ * is stepped in the same direction again.  A trial that is not kept is undone
+ * and the kept caps run again before the next trial: for 1, 2, 4, then 8
+ * windows after the first, second, ... rejected trial since the last clear
+ * gain (the search cools down once it has settled and picks its pace up again
+ * with the next clear gain); each such window's reading replaces the reference
+ * if higher and is averaged into it if lower.  Otherwise one knob is stepped
+ * in a random direction (not the same knob three times in a row; not a
+ * direction that was rejected from the knob's present value, unless the other
+ * one has been rejected since).  The new caps are returned.  Deterministic for
+ * a given seed and sequence of readings. */
 int ga3c_tuner_create(int p_lo, int p_hi, int p0, int t_lo, int t_hi, int t_step, int t0, uint64_t seed,
                       ga3c_tuner **out);
 int ga3c_tuner_report(ga3c_tuner *t, double throughput, int *predict_cap, int *train_cap);

@@ -36,9 +36,11 @@ uint64_t splitmix(uint64_t &x) {
 
 // Sec. 4.3: every period one knob is changed by one step; the change is kept if the throughput did not drop,
 // otherwise undone.  Knobs here are the two batch caps: the prediction cap moves on the ladder lo, 2 lo, 4 lo, ...
-// (one step = a factor 2), the training cap by a fraction of its value (a quarter at first, halved after a rejected
-// step of that knob down to 1/64, doubled again after an accepted one; at least t_step, a multiple of t_step), so
-// that both knobs cross their range in a handful of steps and still settle finely.
+// (one step = a factor 2), the training cap by a factor 1 + 2^-k up or down (k = 0 at first, i.e. a factor 2 as
+// well; one finer after a rejected step of that knob, down to 1/64; one coarser again after a step that brought a
+// clear gain; values
+// are multiples of t_step and a step is at least t_step), so that both knobs cross their range in a handful of steps
+// and still settle finely.
 // What the paper leaves open, and what this does:
 //  * "did not drop" is judged against a relative margin (window-to-window noise of a few per cent would otherwise
 //    reject every neutral step): a trial is kept iff its throughput >= (1 - margin) * reference;
@@ -46,6 +48,9 @@ uint64_t splitmix(uint64_t &x) {
 //    neutral step, and measured again in the window after every rejected trial (a higher reading replaces it, a
 //    lower one is averaged in), so that one lucky reading cannot lock the tuner in; the starting configuration is
 //    measured twice, because the first window also pays for the start of the run;
+//  * the search cools down ("annealing"): after the k-th rejected trial in a row without a clear gain in between the
+//    kept configuration runs for 1, 2, 4, then 8 windows before the next trial, so that a settled system spends one
+//    window in nine on a trial that is likely to cost throughput; the first clear gain brings the pace back;
 //  * after a step that raised the throughput by more than half the margin the same knob is stepped in the same
 //    direction again; otherwise knob and direction are drawn at random (seeded), except that a knob is not drawn a
 //    third time in a row and the step that was rejected last is not repeated at once.
@@ -55,13 +60,15 @@ struct ga3c_tuner {
     int kept_p, kept_t;    // last accepted configuration
     double kept_thr;       // its throughput (the reference)
     double margin;
-    bool have_ref, trial, remeasure, persist;
+    bool have_ref, trial, persist;
+    int rest;              // windows the kept configuration still runs before the next trial
+    int rej_run;           // rejected trials since the last clear gain
     bool last_knob_p, last_up;
     bool have_rej[2], rej_up[2];           // per knob (0 training, 1 prediction): the direction rejected last from the
                                            // kept value (not tried again until that knob's kept value has moved)
     int knob_run;          // trials in a row on the knob of the last trial
-    int t_shift;           // the training cap moves by kept_t >> t_shift: 2 at first, finer after a rejected step of that
-                           // knob (up to 6), coarser again after an accepted one
+    int t_shift;           // the training cap moves by the factor 1 + 2^-t_shift: 0 at first, finer after a rejected step
+                           // of that knob (up to 6), coarser again after a clear gain
     uint64_t rng;
     int64_t accepted, rejected, windows, last_change;
 };
@@ -77,8 +84,8 @@ extern "C" int ga3c_tuner_create(int p_lo, int p_hi, int p0, int t_lo, int t_hi,
     t->p_lo = p_lo; t->p_hi = p_hi; t->t_lo = t_lo; t->t_hi = t_hi; t->t_step = t_step;
     t->p = t->kept_p = p0; t->t = t->kept_t = t0;
     t->kept_thr = 0.0; t->margin = 0.03;
-    t->have_ref = false; t->trial = false; t->remeasure = false; t->persist = false;
-    t->last_knob_p = false; t->last_up = false; t->t_shift = 2;
+    t->have_ref = false; t->trial = false; t->persist = false; t->rest = 0; t->rej_run = 0;
+    t->last_knob_p = false; t->last_up = false; t->t_shift = 0;
     t->have_rej[0] = t->have_rej[1] = false; t->rej_up[0] = t->rej_up[1] = false; t->knob_run = 0;
     t->rng = seed; t->accepted = t->rejected = 0; t->windows = 0; t->last_change = 0;
     *out = t;
@@ -105,8 +112,11 @@ bool tuner_move(const ga3c_tuner *t, bool knob_p, bool up, int &np, int &nt) {
         if (c < t->p_lo || c > t->p_hi || c == t->kept_p) return false;
         np = c;
     } else {
-        const int step = std::max(t->t_step, (t->kept_t >> t->t_shift) / t->t_step * t->t_step);
-        int c = up ? t->kept_t + step : t->kept_t - step;
+        // a factor 1 + 2^-t_shift up or down, rounded to the ladder of t_step, at least one rung
+        const double f = 1.0 + 1.0 / (double)(1 << t->t_shift);
+        const double want = up ? t->kept_t * f : t->kept_t / f;
+        int c = (int)(want / t->t_step + 0.5) * t->t_step;
+        if (up) c = std::max(c, t->kept_t + t->t_step); else c = std::min(c, t->kept_t - t->t_step);
         c = std::min(std::max(c, t->t_lo), t->t_hi);      // the last step to a bound may be shorter
         if (c == t->kept_t) return false;
         nt = c;
@@ -125,21 +135,23 @@ extern "C" int ga3c_tuner_report(ga3c_tuner *t, double throughput, int *predict_
         // the first window also pays for whatever starts up with the run: it gives a provisional reference, and the
         // starting configuration runs once more before the first trial
         t->kept_thr = throughput; t->have_ref = true;
-        t->remeasure = true;
+        t->rest = 1;
     } else if (t->trial) {
         if (throughput >= (1.0 - t->margin) * t->kept_thr) {
             t->accepted += 1;
             t->kept_p = t->p; t->kept_t = t->t;
             // a clear gain: step the same knob the same way again; a neutral step is kept but earns no repeat
-            t->persist = throughput >= (1.0 + 0.5 * t->margin) * t->kept_thr;
+            t->persist = throughput > (1.0 + 0.5 * t->margin) * t->kept_thr;
             t->kept_thr = std::max(t->kept_thr, throughput);
             t->last_change = t->windows;
             t->have_rej[t->last_knob_p ? 1 : 0] = false;
-            if (!t->last_knob_p) t->t_shift = std::max(2, t->t_shift - 1);
+            if (!t->last_knob_p && t->persist) t->t_shift = std::max(0, t->t_shift - 1);
+            if (t->persist) t->rej_run = 0;
         } else {
             t->rejected += 1;                    // undo, and look at the kept configuration again before the next trial
             t->persist = false;
-            t->remeasure = true;
+            t->rest = 1 << std::min(t->rej_run, 3);           // 1, 2, 4, 8, 8, ... windows
+            t->rej_run += 1;
             // both directions rejected: start over (conditions may have changed since the first of the two)
             const int kn = t->last_knob_p ? 1 : 0;
             if (t->have_rej[kn] && t->rej_up[kn] != t->last_up) t->have_rej[kn] = false;
@@ -153,8 +165,8 @@ extern "C" int ga3c_tuner_report(ga3c_tuner *t, double throughput, int *predict_
     }
     int np = t->kept_p, nt = t->kept_t;
     bool moved = false;
-    if (t->remeasure) {
-        t->remeasure = false;
+    if (t->rest > 0) {
+        t->rest -= 1;
     } else {
         if (t->persist) moved = tuner_move(t, t->last_knob_p, t->last_up, np, nt);
         t->persist = false;
