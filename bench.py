@@ -113,6 +113,31 @@ def spread(vals):
     return {"min": round(min(vals), 5), "median": round(statistics.median(vals), 5), "max": round(max(vals), 5)}
 
 
+def rmsprop_2p28(g, torch, stream):
+    """RMSProp (Eq. 3) on a buffer far larger than the caches: 2^28 parameters, 12 B read and 8 B written each."""
+    n = 1 << 28
+    th = torch.zeros(n, device="cuda"); gg = torch.zeros(n, device="cuda"); dd = torch.ones(n, device="cuda")
+    f = lambda: g.rmsprop_flat(th, gg, dd, 1.0, 3e-4, 0.99, 0.1, stream=stream)
+    f(); f()
+
+    def blocks():
+        out = []
+        for _ in range(5):
+            torch.cuda.synchronize(); t0 = time.perf_counter()
+            for _ in range(5):
+                f()
+            torch.cuda.synchronize(); out.append((time.perf_counter() - t0) / 5)
+        return out
+    rs = blocks()
+    s = statistics.median(rs)
+    rec = {"kernel": "rmsprop_kernel", "bound": "hbm", "achieved": round(20.0 * n / s / 1e9, 1), "peak": PEAK_HBM / 1e9,
+           "unit": "GB/s", "frac": round(20.0 * n / s / PEAK_HBM, 4), "ms": spread([x * 1e3 for x in rs]),
+           "bytes_per_parameter": 20, "parameters": n}
+    del th, gg, dd
+    torch.cuda.empty_cache()
+    return rec
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -128,6 +153,8 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--only-step", action="store_true",
                     help="the step and its stages only: no sweep, larger net, big RMSProp or queue system (for profilers)")
+    ap.add_argument("--only-rmsprop", action="store_true",
+                    help="RMSProp over 2^28 parameters only (a kernel of known traffic: the calibration of the HBM counters)")
     ap.add_argument("--mixed-seconds", type=float, default=1.5,
                     help="length of each mixed-load run through the scheduler (0 = skip)")
     args = ap.parse_args()
@@ -146,6 +173,9 @@ def main() -> int:
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         return 2
     torch.cuda.set_device(0)
+    if args.only_rmsprop:
+        print(json.dumps({"rmsprop_2p28": rmsprop_2p28(g, torch, torch.cuda.current_stream())}))
+        return 0
     N, T, A = args.agents, 5, 18
     NSETS = 4
     desc = dataclasses.replace(g.SMALL_NET(A) if args.net == "small" else g.LARGE_NET(A), math=args.math)
@@ -377,18 +407,7 @@ def main() -> int:
             ln.close()
         out["large_net"] = large
 
-        # ---- RMSProp (Eq. 3) on a buffer far larger than the caches: 2^28 parameters, 20 B each
-        n = 1 << 28
-        th = torch.zeros(n, device="cuda"); gg = torch.zeros(n, device="cuda"); dd = torch.ones(n, device="cuda")
-        f = lambda: g.rmsprop_flat(th, gg, dd, 1.0, 3e-4, 0.99, 0.1, stream=stream)
-        f(); f()
-        rs = timed_blocks(f, 5, 5)
-        s = statistics.median(rs)
-        out["rmsprop_2p28"] = {"kernel": "rmsprop_kernel", "bound": "hbm", "achieved": round(20.0 * n / s / 1e9, 1), "peak": PEAK_HBM / 1e9,
-                               "unit": "GB/s", "frac": round(20.0 * n / s / PEAK_HBM, 4), "ms": spread([x * 1e3 for x in rs]),
-                               "bytes_per_parameter": 20}
-        del th, gg, dd
-        torch.cuda.empty_cache()
+        out["rmsprop_2p28"] = rmsprop_2p28(g, torch, stream)
 
     if args.mixed_seconds > 0 and not args.only_step:
         # synthetic agents through the two-stream scheduler (bench_mixed.py): 256 closed-loop agents; fixed caps

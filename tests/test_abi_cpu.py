@@ -70,3 +70,11 @@ def test_ticket_hand_off_model_is_race_free_and_the_sanitizer_sees_the_ordering_
     assert "ThreadSanitizer" not in ok.stderr
     racy = subprocess.run([exe, "relaxed"], capture_output=True, text=True, timeout=300)
     assert racy.returncode != 0 and "data race" in racy.stderr
+
+
+def test_benchmark_refuses_more_than_one_gpu():
+    # this build is for one GPU: the benchmark says so instead of running a second rank
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "ONE GPU" in (r.stdout + r.stderr)
