@@ -31,5 +31,17 @@ def build(force: bool = True) -> str:
     return LIB
 
 
+MICROBENCH = os.path.join(HERE, "microbench")
+
+
+def build_microbench() -> str:
+    """The standalone micro-benchmark program (csrc/microbench.hip): chip rates the kernel designs rest on."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    flags = [f for f in FLAGS if f not in ("-shared", "-fPIC")]
+    subprocess.check_call([hipcc] + flags + ["-o", MICROBENCH, os.path.join(HERE, "csrc", "microbench.hip")])
+    return MICROBENCH
+
+
 if __name__ == "__main__":
-    print(build(True))
+    import sys
+    print(build_microbench() if sys.argv[1:] == ["microbench"] else build(True))
