@@ -81,10 +81,10 @@ def run_mixed(net_kind: str = "small", n_agents: int = 256, think_us: float = 0.
             waiting[a] = True
         sched.tick()
         ticks += 1
-        if trace and ticks % adjust_period == 0:      # the window that just closed: its reading and the caps proposed next
+        if dynamic and ticks % adjust_period == 0:    # the window that just closed: its reading and the caps proposed next
             st = sched.stats()
             windows_seen.append((st["windows"], round(st["last_window_frames_per_s"]), st["predict_cap"], st["train_cap"],
-                                 st["trials_accepted"], st["trials_rejected"]))
+                                 st["trials_accepted"], st["trials_rejected"], round(now, 4)))
         a, action, value, version = sched.poll_arrays(with_version=True)
         if a.size:
             first = seg_len[a] == 0
@@ -125,6 +125,10 @@ def run_mixed(net_kind: str = "small", n_agents: int = 256, think_us: float = 0.
            "short_segments": st["short_segments"],
            "mean_policy_lag_updates": round(st["lag_sum"] / max(1, st["lag_count"]), 3), "max_policy_lag_updates": st["lag_max"],
            "host_us_per_tick": round(wall / max(1, ticks) * 1e6, 1)}
+    if dynamic and half:
+        # time to converge: the end of the first window whose reading reached 90 % of what the second half averages
+        target = 0.9 * out["tps_frames_second_half"]
+        out["seconds_to_90pct_of_second_half"] = next((w[6] for w in windows_seen if w[1] >= target), None)
     if trace:
         out["window_trace"] = windows_seen
     sched.close()
