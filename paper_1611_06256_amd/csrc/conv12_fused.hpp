@@ -171,9 +171,9 @@ __device__ __forceinline__ void conv12_fused_block(const uint8_t *__restrict__ x
 #pragma unroll
         for (int i = 0; i < FPT; ++i) fpre[i] = frag[rt + 256 * i];
     }
-    float bv[4];                                                   // layer 2 finishes filter tile kh
+    float bv[4];                                                   // layer 1: bv[0] = bias of filter l16; layer 2 finishes filter tile kh
 #pragma unroll
-    for (int r = 0; r < 4; ++r) bv[r] = layer1 ? b1[4 * g + r] : b2[kh * 16 + 4 * g + r];
+    for (int r = 0; r < 4; ++r) bv[r] = layer1 ? b1[l16] : b2[kh * 16 + 4 * g + r];
 
     const int grid = stride;
     const int n = TO_LDS ? 1 : (nframes - first + grid - 1) / grid;      // frames of this block (>= 1)
@@ -253,31 +253,33 @@ __device__ __forceinline__ void conv12_fused_block(const uint8_t *__restrict__ x
                     xv.u = u32x4{lo.x, lo.y, hi.x, hi.y};
                     return xv.v;
                 };
+                // The MFMAs below take the pixels as rows and the filters as columns, so a lane ends up with four
+                // consecutive pixels (16 t + 4 g + r) of filter l16: one 16-byte store to y1, and pixel pairs that are
+                // neighbours in the planes' 2x2-block layout (one 4-byte LDS store per pair and term).
                 auto finish = [&](int t, const floatx4 acc) {
-                    const int p = t * 16 + l16;
+                    const int p = t * 16 + 4 * g;                           // a multiple of 4: the four pixels share a row
                     const int row = p / OW1, col = p % OW1;
-                    const int blk = (row >> 1) * 40 + (col >> 1) * 4 + (row & 1) * 2 + (col & 1);
+                    const int blk = (row >> 1) * 40 + (col >> 1) * 4 + (row & 1) * 2;      // pixels col, col+1; +4: col+2, col+3
                     float v[4];
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
-                        v[r] = acc[r] * scale + bv[r];
+                        v[r] = acc[r] * scale + bv[0];
                         v[r] = v[r] > 0.f ? v[r] : 0.f;
-                        if (KEEP) yb[(4 * g + r) * NPIX1 + p] = v[r];
                     }
+                    if (KEEP) *(float4 *)(yb + l16 * NPIX1 + p) = float4{v[0], v[1], v[2], v[3]};
                     // split two values per conversion instruction (v = hi + mid + lo exactly; ONE: v rounded)
 #pragma unroll
                     for (int q = 0; q < 2; ++q) {
                         const float a = v[2 * q], b = v[2 * q + 1];
-                        union { uint32_t u; __bf16 h[2]; } hi, mid, lo;
-                        hi.u = pack_bf16_rne(a, b);
-                        const int e0 = (4 * g + 2 * q) * HW2 + blk, e1 = e0 + HW2;
-                        yp[e0] = hi.h[0]; yp[e1] = hi.h[1];
+                        const int e0 = l16 * HW2 + blk + 4 * q;             // even: 4-byte aligned
+                        const uint32_t hi = pack_bf16_rne(a, b);
+                        *(uint32_t *)(yp + e0) = hi;
                         if (!ONE) {
-                            const float ra = a - __uint_as_float(hi.u << 16), rb2 = b - __uint_as_float(hi.u & 0xffff0000u);
-                            mid.u = pack_bf16_rne(ra, rb2);
-                            lo.u = pack_bf16_rne(ra - __uint_as_float(mid.u << 16), rb2 - __uint_as_float(mid.u & 0xffff0000u));
-                            yp[C12_Y1 + e0] = mid.h[0]; yp[C12_Y1 + e1] = mid.h[1];
-                            yp[2 * C12_Y1 + e0] = lo.h[0]; yp[2 * C12_Y1 + e1] = lo.h[1];
+                            const float ra = a - __uint_as_float(hi << 16), rb2 = b - __uint_as_float(hi & 0xffff0000u);
+                            const uint32_t mid = pack_bf16_rne(ra, rb2);
+                            const uint32_t lo = pack_bf16_rne(ra - __uint_as_float(mid << 16), rb2 - __uint_as_float(mid & 0xffff0000u));
+                            *(uint32_t *)(yp + C12_Y1 + e0) = mid;
+                            *(uint32_t *)(yp + 2 * C12_Y1 + e0) = lo;
                         }
                     }
                 };
@@ -298,7 +300,7 @@ __device__ __forceinline__ void conv12_fused_block(const uint8_t *__restrict__ x
                         for (int term = ONE ? 0 : 2; term >= 0; --term)
 #pragma unroll
                             for (int j = 0; j < 6; ++j)
-                                acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wq[term][kb], xv[j], acc[j], 0, 0, 0);
+                                acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xv[j], wq[term][kb], acc[j], 0, 0, 0);
                     }
 #pragma unroll
                     for (int j = 0; j < 6; ++j) finish(rw + 4 * j, acc[j]);
@@ -311,7 +313,7 @@ __device__ __forceinline__ void conv12_fused_block(const uint8_t *__restrict__ x
                         const bf16x8 xv = operand(base, kb);
 #pragma unroll
                         for (int term = ONE ? 0 : 2; term >= 0; --term)
-                            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wq[term][kb], xv, acc, 0, 0, 0);
+                            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xv, wq[term][kb], acc, 0, 0, 0);
                     }
                     finish(24, acc);
                 }
