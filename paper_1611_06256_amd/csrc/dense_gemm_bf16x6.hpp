@@ -98,6 +98,7 @@ __device__ __forceinline__ void stash_tile(u32x4 (&S)[3][4][ROWS + 1], int tid, 
 template <int TM, int TN, int WM, int WN, bool A_ROWMAJOR, bool B_ROWMAJOR, int EPI, bool ONE>
 __global__ __launch_bounds__(WM *WN * 64, 2) void dense_gemm_bf16x6_kernel(const DenseGemmArgs p) {
     constexpr int BM = 16 * TM * WM, BN = 16 * TN * WN, BK = 32, NT = WM * WN * 64;
+    constexpr bool SWAP = EPI == DG_MASK;            // the input gradient: output and mask are read and written in rows
     // LDS: [term][k-group of 8][row] in 16-byte units, one spare unit per line
     __shared__ u32x4 As[3][4][BM + 1];
     __shared__ u32x4 Bs[3][4][BN + 1];
@@ -160,20 +161,51 @@ __global__ __launch_bounds__(WM *WN * 64, 2) void dense_gemm_bf16x6_kernel(const
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int t = 0; t < (ONE ? 1 : 3); ++t) b[j][t].u = Bs[t][g][(wn * TN + j) * 16 + l16];
-        // smallest products first
+        // smallest products first.  SWAP: the instruction takes B's rows as its rows, so that a lane ends up with
+        // C[m = its l16][n = 4 g .. 4 g + 3] (four consecutive columns) instead of four rows of one column
+        auto mma = [&](const bf16x8 x, const bf16x8 y, floatx4 &c) {
+            c = SWAP ? __builtin_amdgcn_mfma_f32_16x16x32_bf16(y, x, c, 0, 0, 0) : __builtin_amdgcn_mfma_f32_16x16x32_bf16(x, y, c, 0, 0, 0);
+        };
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 if (!ONE) {
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][2].v, b[j][0].v, acc[i][j], 0, 0, 0);
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][1].v, b[j][1].v, acc[i][j], 0, 0, 0);
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][0].v, b[j][2].v, acc[i][j], 0, 0, 0);
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][1].v, b[j][0].v, acc[i][j], 0, 0, 0);
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][0].v, b[j][1].v, acc[i][j], 0, 0, 0);
+                    mma(a[i][2].v, b[j][0].v, acc[i][j]);
+                    mma(a[i][1].v, b[j][1].v, acc[i][j]);
+                    mma(a[i][0].v, b[j][2].v, acc[i][j]);
+                    mma(a[i][1].v, b[j][0].v, acc[i][j]);
+                    mma(a[i][0].v, b[j][1].v, acc[i][j]);
                 }
-                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][0].v, b[j][0].v, acc[i][j], 0, 0, 0);
+                mma(a[i][0].v, b[j][0].v, acc[i][j]);
             }
+    }
+
+    if (SWAP) {
+        // one 16-byte store (and one 16-byte load of the mask) per tile instead of four scattered 4-byte ones, where
+        // the row pitch and the pointers allow it
+        const bool vec = p.N % 4 == 0 && p.ldc % 4 == 0 && (uintptr_t)p.C % 16 == 0 && (uintptr_t)p.aux % 16 == 0;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int m = m0 + (wm * TM + i) * 16 + l16;
+                const int n = n0 + (wn * TN + j) * 16 + 4 * g;
+                if (m >= p.M || n >= p.N) continue;
+                float *dst = p.C + (size_t)m * p.ldc + n;
+                const float *msk = p.aux + (size_t)m * p.ldc + n;
+                if (vec) {
+                    const float4 k4 = *(const float4 *)msk;
+                    float4 v = float4{acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]};
+                    v.x = k4.x > 0.f ? v.x : 0.f; v.y = k4.y > 0.f ? v.y : 0.f; v.z = k4.z > 0.f ? v.z : 0.f; v.w = k4.w > 0.f ? v.w : 0.f;
+                    *(float4 *)dst = v;
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        if (n + r < p.N) dst[r] = msk[r] > 0.f ? acc[i][j][r] : 0.f;
+                }
+            }
+        return;
     }
 
 #pragma unroll
