@@ -121,16 +121,16 @@ __global__ __launch_bounds__(256, 2) void conv1_bf16x3_fwd_kernel(const uint8_t 
             wq[0][kb][e] = h; wq[1][kb][e] = m; wq[2][kb][e] = l;
         }
     }
-    float bv[4];
-#pragma unroll
-    for (int r = 0; r < 4; ++r) bv[r] = bias[ot * 16 + 4 * g + r];
+    // The MFMAs take the pixels as rows and the filters as columns: a lane ends up with four consecutive pixels
+    // (16 tile + 4 g + r) of filter ot * 16 + l16, which it stores as one 16-byte vector.
+    const float bv = bias[ot * 16 + l16];
 
     int pixbase[TPW], pixidx[TPW];
 #pragma unroll
     for (int i = 0; i < TPW; ++i) {
         const int job = wave + 4 * i;
         int p = (job / OT) * 16 + l16;
-        pixidx[i] = (job < JOBS && p < NPIX) ? p : -1;
+        pixidx[i] = (job < JOBS && p < NPIX) ? (job / OT) * 16 + 4 * g : -1;       // first of my four output pixels
         if (p >= NPIX) p = 0;
         pixbase[i] = (p / OW) * S * W + (p % OW) * S + g * W;     // + row g of the 4 rows of a tap block
     }
@@ -168,9 +168,9 @@ __global__ __launch_bounds__(256, 2) void conv1_bf16x3_fwd_kernel(const uint8_t 
             const uint2 lo = *(const uint2 *)src, hi = *(const uint2 *)(src + 4);
             Bf16x8Bits xv;
             xv.u = u32x4{lo.x, lo.y, hi.x, hi.y};
-            acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wq[2][kb], xv.v, acc[i], 0, 0, 0);
-            acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wq[1][kb], xv.v, acc[i], 0, 0, 0);
-            acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wq[0][kb], xv.v, acc[i], 0, 0, 0);
+            acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xv.v, wq[2][kb], acc[i], 0, 0, 0);
+            acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xv.v, wq[1][kb], acc[i], 0, 0, 0);
+            acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xv.v, wq[0][kb], acc[i], 0, 0, 0);
         };
 #pragma unroll
         for (int kb = 0; kb < 8; ++kb)
@@ -184,11 +184,13 @@ __global__ __launch_bounds__(256, 2) void conv1_bf16x3_fwd_kernel(const uint8_t 
 #pragma unroll
         for (int i = 0; i < TPW; ++i) {
             if (pixidx[i] >= 0) {
+                float v[4];
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const float v = acc[i][r] * scale + bv[r];
-                    yb[(ot * 16 + 4 * g + r) * NPIX + pixidx[i]] = v > 0.f ? v : 0.f;
+                    v[r] = acc[i][r] * scale + bv;
+                    v[r] = v[r] > 0.f ? v[r] : 0.f;
                 }
+                *(float4 *)(yb + (ot * 16 + l16) * NPIX + pixidx[i]) = float4{v[0], v[1], v[2], v[3]};      // NPIX % 4 == 0
             }
         }
     }
