@@ -233,6 +233,58 @@ __device__ __forceinline__ void heads_store_weights(float *hs, const float (&wv)
     }
 }
 
+// The loads of a heads block as 16-byte vectors (a quarter of the load instructions: a wavefront spends about a
+// hundred cycles issuing each one, whatever its width): the split-k partial sums of the fc layer for NF frames are
+// added up in chunk order, bias and ReLU follow, the result goes to h and (rounded if rb) to hs [NF][F4]; the heads'
+// weights go to wsh [A+1][WP] (the value head's row with 4-byte loads: it follows the policy biases in the parameter
+// vector and is not aligned).  Needs F % 4 == 0 and 16-byte aligned pointers (heads_vec4_ok).  Every load of a round
+// is issued before the first one is used.
+__device__ __forceinline__ bool heads_vec4_ok(int F, const void *ws, const void *fcb, const void *h, const void *Wp) {
+    return F % 4 == 0 && (((uintptr_t)ws | (uintptr_t)fcb | (uintptr_t)h | (uintptr_t)Wp) & 15) == 0;
+}
+template <int NT, int NF, int CH>
+__device__ __forceinline__ void heads_load_vec4(float *hs, float *wsh, const int tid, const int b0, const int nf,
+                                                const float *__restrict__ ws, int nz, const float *__restrict__ fcb,
+                                                float *__restrict__ h, int B, int F, int F4, int WP, int A,
+                                                const float *__restrict__ Wp, const float *__restrict__ Wv, int rb) {
+    const int FQ = F >> 2, nwq = A * FQ;
+    const size_t stride4 = (size_t)B * FQ;
+    for (int q0 = 0; q0 < nwq || q0 == 0; q0 += 8 * NT) {
+        float4 wv4[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) wv4[j] = ((const float4 *)Wp)[min(q0 + j * NT + tid, nwq - 1)];
+        if (q0 == 0) {
+            for (int k = tid; k < F; k += NT) wsh[A * WP + k] = rb ? bf16_rne(Wv[k]) : Wv[k];
+            for (int it = tid; it < NF * FQ; it += NT) {
+                const int fb = it / FQ, oq = it % FQ;
+                const float4 bias = ((const float4 *)fcb)[oq];
+                const float4 *src = (const float4 *)(ws + (size_t)(b0 + min(fb, nf - 1)) * F) + oq;
+                float4 acc = float4{0.f, 0.f, 0.f, 0.f};
+                for (int z = 0; z < nz; z += CH) {
+                    float4 v[CH];
+#pragma unroll
+                    for (int i = 0; i < CH; ++i) v[i] = src[(size_t)min(z + i, nz - 1) * stride4];
+#pragma unroll
+                    for (int i = 0; i < CH; ++i) {
+                        const bool in = z + i < nz;
+                        acc.x += in ? v[i].x : 0.f; acc.y += in ? v[i].y : 0.f;
+                        acc.z += in ? v[i].z : 0.f; acc.w += in ? v[i].w : 0.f;
+                    }
+                }
+                float4 r = float4{acc.x + bias.x, acc.y + bias.y, acc.z + bias.z, acc.w + bias.w};
+                r.x = r.x > 0.f ? r.x : 0.f; r.y = r.y > 0.f ? r.y : 0.f; r.z = r.z > 0.f ? r.z : 0.f; r.w = r.w > 0.f ? r.w : 0.f;
+                if (fb < nf) *(float4 *)(h + (size_t)(b0 + fb) * F + 4 * oq) = r;
+                *(float4 *)(hs + fb * F4 + 4 * oq) = rb ? bf16_rne(r) : r;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int q = q0 + j * NT + tid;
+            if (q < nwq) *(float4 *)(wsh + (q / FQ) * WP + 4 * (q % FQ)) = rb ? bf16_rne(wv4[j]) : wv4[j];
+        }
+    }
+}
+
 // The body, for a block of NT threads (all of them must call it) that works on frames b0 .. min(b0 + 4, B) - 1;
 // hs is the block's LDS.  COHERENT: h was written by other blocks of the same launch, so it is read past the
 // caches that are not kept coherent within a launch.  WSTAGED: heads_stage_weights has already run on hs.
@@ -257,7 +309,9 @@ __device__ __forceinline__ void heads_fwd_body(float *hs, const int tid, const i
     if (!WSTAGED)
         for (int e = tid; e < (A + 1) * (WP - F); e += NT) wsh[(e / (WP - F)) * WP + F + e % (WP - F)] = 0.f;
     const int nw = (A + 1) * F;                 // Wp [A][F] and Wv [F] are adjacent in LDS, not in global memory
-    for (int e0 = 0; (!WSTAGED && e0 < nw) || e0 == 0; e0 += 24 * NT) {
+    const bool vec4 = !WSTAGED && ws && heads_vec4_ok(F, ws, fcb, h, Wp);
+    if (vec4) heads_load_vec4<NT, 4, 16>(hs, wsh, tid, b0, nf, ws, nz, fcb, h, B, F, F4, WP, A, Wp, Wv, rb);
+    for (int e0 = 0; !vec4 && ((!WSTAGED && e0 < nw) || e0 == 0); e0 += 24 * NT) {
         float wv[24];
         if (!WSTAGED) {
 #pragma unroll
@@ -763,7 +817,9 @@ __global__ __launch_bounds__(256) void heads_train_kernel(
     for (int e = tid; e < NF * (F4 - F); e += 256) hs[(e / (F4 - F)) * F4 + F + e % (F4 - F)] = 0.f;
     for (int e = tid; e < A1 * (WP - F); e += 256) wsh[(e / (WP - F)) * WP + F + e % (WP - F)] = 0.f;
     const int nw = A1 * F;
-    for (int e0 = 0; e0 < nw || e0 == 0; e0 += 24 * 256) {
+    const bool vec4 = heads_vec4_ok(F, ws, fcb, h, Wp);
+    if (vec4) heads_load_vec4<256, NF, 8>(hs, wsh, tid, b0, nf, ws, nz, fcb, h, B, F, F4, WP, A, Wp, Wv, rb);
+    for (int e0 = 0; !vec4 && (e0 < nw || e0 == 0); e0 += 24 * 256) {
         float wv[24];
 #pragma unroll
         for (int j = 0; j < 24; ++j) {
