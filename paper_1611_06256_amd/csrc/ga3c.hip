@@ -1017,12 +1017,15 @@ __global__ __launch_bounds__(256) void heads_train_kernel(
 // on timing, so the gradient is reproducible bit for bit.
 // Block ids go round-robin over the 8 XCDs; the ids of one XCD take consecutive
 // groups of outputs, so that blocks which share 128-byte lines of the partial
-// sums also share an L2.
+// sums also share an L2.  Where the first row of the segment and the planes of the stack start on 16-byte
+// boundaries a thread takes four consecutive outputs and reads its partial sums as 16-byte vectors (a quarter of the
+// load instructions); the sums of an output are formed in the same order either way.
 struct ReduceSeg {
     const float *ws;
     float *gW, *gb;
     int nz, M, N, r0, rows, bias_col, zg, first_block;
     int per_xcd;         // the segment owns 8 * per_xcd block ids, first_block is a multiple of 8
+    int vec;             // a thread takes four consecutive outputs and reads 16-byte vectors (the stack allows it)
 };
 constexpr int MAX_REDUCE_SEGS = 12;
 struct ReduceArgs {
@@ -1032,7 +1035,7 @@ struct ReduceArgs {
 };
 
 __global__ __launch_bounds__(256) void reduce_all_kernel(const ReduceArgs a) {
-    __shared__ float sh[256];
+    __shared__ float4 sh[256];
     __shared__ float wsum[4];
     int si = 0;
     while (si + 1 < a.nseg && (int)blockIdx.x >= a.seg[si + 1].first_block) ++si;
@@ -1041,29 +1044,54 @@ __global__ __launch_bounds__(256) void reduce_all_kernel(const ReduceArgs a) {
     const int o = threadIdx.x % opb, zi = threadIdx.x / opb;
     const size_t cnt = (size_t)g.rows * g.N;
     const int lb = blockIdx.x - g.first_block;
-    const size_t i = ((size_t)(lb % 8) * g.per_xcd + lb / 8) * opb + o;
-    float s = 0.f;
-    if (i < cnt) {
-        const size_t src = (size_t)g.r0 * g.N + i, stride = (size_t)g.M * g.N;
+    const int per = g.vec ? 4 : 1;                      // outputs per thread
+    const size_t i = (((size_t)(lb % 8) * g.per_xcd + lb / 8) * opb + o) * per;
+    float4 s = float4{0.f, 0.f, 0.f, 0.f};
+    const size_t src = (size_t)g.r0 * g.N + i, stride = (size_t)g.M * g.N;
+    if (g.vec && i + 3 < cnt) {
         for (int z = zi; z < g.nz; z += 8 * g.zg) {
-            float v[8];
+            float4 v[8];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) v[j] = g.ws[(size_t)min(z + j * g.zg, g.nz - 1) * stride + src];
+            for (int j = 0; j < 8; ++j) v[j] = *(const float4 *)(g.ws + (size_t)min(z + j * g.zg, g.nz - 1) * stride + src);
 #pragma unroll
-            for (int j = 0; j < 8; ++j) s += (z + j * g.zg < g.nz) ? v[j] : 0.f;
+            for (int j = 0; j < 8; ++j) {
+                const bool in = z + j * g.zg < g.nz;
+                s.x += in ? v[j].x : 0.f; s.y += in ? v[j].y : 0.f; s.z += in ? v[j].z : 0.f; s.w += in ? v[j].w : 0.f;
+            }
+        }
+    } else if (i < cnt) {                               // one output, or the last, partial group of four
+        const int ne = (int)min((size_t)per, cnt - i);
+        for (int e = 0; e < ne; ++e) {
+            float t = 0.f;
+            for (int z = zi; z < g.nz; z += 8 * g.zg) {
+                float v[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) v[j] = g.ws[(size_t)min(z + j * g.zg, g.nz - 1) * stride + src + e];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) t += (z + j * g.zg < g.nz) ? v[j] : 0.f;
+            }
+            if (e == 0) s.x = t; else if (e == 1) s.y = t; else if (e == 2) s.z = t; else s.w = t;
         }
     }
     sh[threadIdx.x] = s;
     __syncthreads();
     float sq = 0.f;
     if (zi == 0 && i < cnt) {
-        float t = sh[o];
-        for (int j = 1; j < g.zg; ++j) t += sh[j * opb + o];
-        const int m = (int)(i / g.N), n = (int)(i % g.N);
-        if (!g.bias_col) g.gW[i] = t;
-        else if (n < g.N - 1) g.gW[(size_t)m * (g.N - 1) + n] = t;
-        else g.gb[m] = t;
-        sq = t * t;
+        float4 t = sh[o];
+        for (int j = 1; j < g.zg; ++j) {
+            const float4 u = sh[j * opb + o];
+            t.x += u.x; t.y += u.y; t.z += u.z; t.w += u.w;
+        }
+        const float te[4] = {t.x, t.y, t.z, t.w};
+        const int ne = (int)min((size_t)per, cnt - i);
+        for (int e = 0; e < ne; ++e) {
+            const size_t ie = i + e;
+            const int m = (int)(ie / g.N), n = (int)(ie % g.N);
+            if (!g.bias_col) g.gW[ie] = te[e];
+            else if (n < g.N - 1) g.gW[(size_t)m * (g.N - 1) + n] = te[e];
+            else g.gb[m] = te[e];
+            sq += te[e] * te[e];
+        }
     }
     sq = wave_sum(sq);
     if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = sq;
@@ -1846,7 +1874,9 @@ static int train_step_impl(ga3c_ctx *c, const uint8_t *frames, const int32_t *ac
         int zg = 1;
         while (zg < 64 && zg * 16 < nz_) zg *= 2;      // at most two rounds of eight loads per thread
         g.zg = zg; g.first_block = red_blocks;
-        const int nblk = (int)(((size_t)rows * Ncols + 256 / zg - 1) / (256 / zg));
+        g.vec = ((size_t)r0 * Ncols) % 4 == 0 && ((size_t)M * Ncols) % 4 == 0 && (uintptr_t)ws % 16 == 0;
+        const size_t per_block = (size_t)(256 / zg) * (g.vec ? 4 : 1);
+        const int nblk = (int)(((size_t)rows * Ncols + per_block - 1) / per_block);
         g.per_xcd = (nblk + 7) / 8;
         red_blocks += 8 * g.per_xcd;
         red_bytes += 4.0 * (nz_ + 1) * rows * Ncols;
