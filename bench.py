@@ -80,7 +80,7 @@ COUNTER_KIB = {   # stage: {frames per launch: (FETCH_SIZE, WRITE_SIZE)}
     "conv2_dgrad": {2560: (45192.7, 64000.0)},
     "fc_wgrad": {2560: (19886.1, 20736.0)},
     "fc_dgrad": {2560: (26030.8, 26006.7)},
-    "wgrad_reduce": {2560: (24931.0, 2808.2)},
+    "wgrad_reduce": {2560: (24263.7, 2728.6)},
     "rmsprop": {2560: (4111.6, 5394.2)},
 }
 
