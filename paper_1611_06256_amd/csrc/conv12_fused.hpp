@@ -14,7 +14,8 @@
 // written one iteration earlier.  The two groups hold only their own filters in
 // registers and share the matrix cores of each SIMD.
 //
-// LDS reads, not the matrix cores, bound this kernel, so the layout serves them:
+// Matrix and vector instructions of the two groups share each SIMD and their times add up (about 2 us of MFMAs and
+// 1.3 us of vector work per frame); the LDS layout is chosen so that operand reads stay out of the way:
 //  * the planes hold each channel as 2x2 pixel blocks, [row pair][column pair]
 //    [2][2]: the 2 rows x 4 columns a lane feeds to one MFMA are 16 contiguous
 //    bytes (the filter taps are permuted to that order when they are loaded);
