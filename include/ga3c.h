@@ -323,7 +323,11 @@ int ga3c_sched_submit_segment_many(ga3c_sched *s, int n, const int32_t *agents, 
                                    const int32_t *lens, const int32_t *actions, const float *rewards,
                                    const uint8_t *dones, const float *bootstrap, const int64_t *policy_versions);
 /* One pass of predictor and trainer: at most one prediction batch (all queued
- * requests up to the cap) and at most one update (queued trajectories up to
+ * requests up to the cap; fewer requests than the cap go out only when no
+ * earlier prediction batch is still in flight, otherwise they wait for it and
+ * are joined by what arrives meanwhile, as with a single predictor that is
+ * busy with its batch; full batches are issued back to back, up to four in
+ * flight) and at most one update (queued trajectories up to
  * the cap, if at least train_min frames wait; whole segments, oldest first;
  * ga3c_train_step when all have t_max steps, ga3c_train_step_ragged
  * otherwise) are enqueued on the GPU.

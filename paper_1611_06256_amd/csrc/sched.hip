@@ -178,6 +178,15 @@ int harvest(ga3c_sched *s, bool wait) {
 int issue_predict(ga3c_sched *s, int *count) {
     *count = 0;
     if (s->pq.empty()) return GA3C_OK;
+    if ((int)s->pq.size() < s->predict_cap) {
+        // Fewer requests than a full batch: they go out at once only if no earlier batch is still in flight;
+        // otherwise they wait for it, and what arrives meanwhile joins them.  (A single predictor of Sec. 4.1 behaves
+        // like this: it is busy with its batch.  Full batches are issued back to back, up to RING of them, like
+        // several predictors.)  Under light load this makes batches as large as the GPU's own pace allows.
+        STRY(harvest(s, false));
+        for (int k = 0; k < RING; ++k)
+            if (s->ps[k].busy) return GA3C_OK;
+    }
     PredSlot &p = s->ps[s->ps_next];
     if (p.busy) {                                   // ring full: wait for the oldest batch
         SHIP(hipEventSynchronize(p.done));

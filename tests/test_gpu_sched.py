@@ -55,12 +55,13 @@ def test_predictions_and_updates_match_direct_calls(G):
         if k >= 1 and (k - 1) * 8 < N:
             for a in range((k - 1) * 8, min(k * 8, N)):
                 sched.submit_trajectory(a, frames[a], tr["actions"][a], tr["rewards"][a], tr["dones"][a], 0.25 * a)
-        # the prediction queue holds 24 requests, the cap is 16: two ticks drain it
+        # the prediction queue holds 24 requests, the cap is 16: a full batch goes out at once, the other 8 (less
+        # than a full batch) when no earlier batch is in flight any more
         np_total, nt_total = 0, 0
         while True:
             p, t = sched.tick()
             np_total += p; nt_total += t
-            if p == 0 and t == 0:
+            if p == 0 and t == 0 and sched.stats()["predict_queue"] == 0:
                 break
         assert np_total == N
         assert nt_total == (40 if k >= 1 and (k - 1) * 8 < N else 0)
