@@ -42,6 +42,22 @@ def build_microbench() -> str:
     return MICROBENCH
 
 
+SCHED_SANITIZED = os.path.join(HERE, "sched_sanitized")
+
+
+def build_sched_sanitized() -> str:
+    """The whole library plus tests/sched_sanitizer_driver.cpp as one program whose HOST code is built with the
+    address and undefined-behaviour sanitizers (device code is not instrumented); a GPU test runs it."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    flags = [f for f in FLAGS if f not in ("-shared", "-fPIC", "-O3")] + [
+        "-O1", "-g", "-fno-omit-frame-pointer", "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+        "-Xarch_host", "-fno-sanitize-recover=all"]
+    driver = os.path.join(os.path.dirname(HERE), "tests", "sched_sanitizer_driver.cpp")
+    subprocess.check_call([hipcc] + flags + ["-o", SCHED_SANITIZED] + SOURCES + [driver])
+    return SCHED_SANITIZED
+
+
 if __name__ == "__main__":
     import sys
-    print(build_microbench() if sys.argv[1:] == ["microbench"] else build(True))
+    what = sys.argv[1:]
+    print(build_microbench() if what == ["microbench"] else build_sched_sanitized() if what == ["sched_sanitized"] else build(True))

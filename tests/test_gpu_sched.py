@@ -215,3 +215,20 @@ def test_short_segments_and_policy_lag(G):
     assert st["lag_count"] == N and st["lag_max"] == len(batches) - 1
     assert st["lag_sum"] == sum(k * len(b) for k, b in enumerate(batches))
     sched.close(); ns.close(); nd.close()
+
+
+def test_scheduler_host_code_is_clean_under_the_address_and_undefined_behaviour_sanitizers():
+    # paper_1611_06256_amd/sched_sanitized (built beforehand by build.py / the entry point's build()) is the whole
+    # library with its HOST code under ASan and UBSan plus tests/sched_sanitizer_driver.cpp: a closed loop of agents with
+    # short segments, policy versions, the adjustment, the many-at-once calls and the error paths.  Any finding in the
+    # queues, slot rings or staging buffers aborts it with a non-zero status.
+    import os
+    import subprocess
+    exe = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "paper_1611_06256_amd", "sched_sanitized")
+    if not os.path.exists(exe):
+        pytest.fail("paper_1611_06256_amd/sched_sanitized is not built: run python -m paper_1611_06256_amd.build sched_sanitized")
+    # (verify_asan_link_order=0: the environment may preload a library of its own; leaks are not looked for, the GPU
+    # runtime keeps its own allocations until exit)
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:abort_on_error=0:verify_asan_link_order=0", UBSAN_OPTIONS="print_stacktrace=1")
+    r = subprocess.run([exe], env=env, capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0 and "0 problems" in r.stdout, r.stdout[-2000:] + r.stderr[-4000:]
