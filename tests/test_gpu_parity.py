@@ -863,3 +863,37 @@ def test_rmsprop_flat(G):
     t_ref, g_ref = orc.rmsprop(th, g, d, 0.5, 3e-4, 0.99, 0.1)
     assert rel_err(gt.cpu().numpy(), g_ref) <= 1e-6
     assert rel_err(tt.cpu().numpy().astype(np.float64) - th, t_ref - th) <= 1e-3
+
+
+def test_stage_timer_changes_no_result_and_reports_every_stage(G):
+    # While the stage timer is on, every kernel goes out through another launch call of the runtime (one that stamps
+    # an event pair at the dispatch's own start and end): the numbers must be the same bit for bit, every stage of
+    # the two calls must be reported with its call count, and a stage's time must be a kernel's, not a launch gap's.
+    import torch
+    desc = G.SMALL_NET(18)
+    B, N, T = 64 + 5, 16, 5
+    frames = synth.rectangle_frames(9901, N * T).reshape(N, T, 4, 84, 84)
+    tr = synth.trajectories(9902, N, T, 18)
+    pf = torch.from_numpy(synth.rectangle_frames(9903, B)).cuda()
+    results = []
+    for timed in (False, True):
+        net, _, _ = make(G, desc, B, N * T, 9900)
+        net.profile_enable(timed)
+        lg = torch.empty(B, 18, device="cuda"); vl = torch.empty(B, device="cuda")
+        net.predict(pf, logits=lg, values=vl)
+        net.train_step(torch.from_numpy(frames).cuda(), torch.from_numpy(tr["actions"]).cuda(), torch.from_numpy(tr["rewards"]).cuda(),
+                       torch.from_numpy(tr["dones"]).cuda(), torch.zeros(N, device="cuda"), G.HParams(clip_norm=40.0))
+        torch.cuda.synchronize()
+        if timed:
+            st = net.profile_read()
+            net.profile_enable(False)
+            want = {"fc_fwd": 2, "wgrad_reduce": 1, "rmsprop": 1, "fc_dgrad": 1}
+            want.update({"conv1_fwd": 2, "conv2_fwd": 2, "conv1_wgrad": 1, "conv2_wgrad": 1, "conv2_dgrad": 1} if GENERIC
+                        else {"conv12_fwd": 2, "heads_fwd": 1, "heads_train": 1, "conv1_wgrad": 1, "conv2_wgrad": 1, "conv2_dgrad": 1})
+            for name, calls in want.items():
+                assert name in st and st[name]["calls"] == calls, (name, st.get(name))
+                assert 0.0005 < st[name]["ms"] / calls < 5.0, (name, st[name])      # between half a microsecond and 5 ms
+        results.append((lg.cpu().numpy(), vl.cpu().numpy(), net.params_get(0).cpu().numpy(), net.params_get(2).cpu().numpy()))
+        net.close()
+    for a, b in zip(*results):
+        np.testing.assert_array_equal(a, b)
