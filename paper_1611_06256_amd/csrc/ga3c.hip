@@ -28,6 +28,16 @@
 
 using namespace ga3c;
 
+// Fixed-geometry kernels exist for the layers of the paper's networks.
+typedef ConvSpec<uint8_t, 4, 84, 84, 16, 8, 4> SpecS1;    // small net, conv1
+typedef ConvSpec<float, 16, 20, 20, 32, 4, 2> SpecS2;     // small net, conv2
+typedef ConvSpec<uint8_t, 4, 84, 84, 32, 8, 4> SpecL1;    // large net, conv1
+typedef ConvSpec<float, 32, 20, 20, 64, 4, 2> SpecL2;     // large net, conv2
+typedef ConvSpec<float, 64, 9, 9, 64, 3, 1> SpecL3;       // large net, conv3
+// 16-byte vectors of a small-net fragment buffer: the filters of conv1 / conv2 for the fused forward kernel, then
+// those of conv2 for its input-gradient kernel
+constexpr int CFRAG_FWD_VECS = 3 * C12_FRAG_SET, CFRAG_VECS = CFRAG_FWD_VECS + ConvDgradBf16Geom<SpecS2>::FRAG_VECS;
+
 // ---------------------------------------------------------------- errors ----
 
 static thread_local char g_err[512] = "";
@@ -104,9 +114,10 @@ struct ga3c_ctx {
     hipStream_t ready_stream[2], readers_stream[2];   // where each event was last recorded
     bool ready_set[2], readers_set[2];
     float *g, *grad;
-    // small net: conv1/conv2 filters of each parameter copy as split MFMA fragments (nullptr for other nets);
-    // refreshed by whoever writes the copy
+    // small net: conv1/conv2 filters of each parameter copy as split MFMA fragments (nullptr for other nets), forward
+    // kernel's first, then (at CFRAG_FWD_VECS) the input-gradient kernel's; refreshed by whoever writes the copy
     u32x4 *cfrag[2];
+    bool cfrag_dgrad;             // the buffers hold the second part too (a context that can train)
     int *ticket;                  // predict_small_kernel's per-frame counters, zero between launches
     Work pred, train;
     // training only
@@ -1204,7 +1215,10 @@ __global__ __launch_bounds__(256) void rmsprop_kernel(const float *theta_in, flo
             if (frag) {
                 const unsigned r1 = (unsigned)(4 * (i + 256 * j)) - w1_off, r2 = (unsigned)(4 * (i + 256 * j)) - w2_off;
                 if (r1 < 16u * 256u) conv12_store_fragment4(frag, 0, (int)r1, t[j], frag_rb);
-                else if (r2 < 32u * 256u) conv12_store_fragment4(frag, 1, (int)r2, t[j], frag_rb);
+                else if (r2 < 32u * 256u) {
+                    conv12_store_fragment4(frag, 1, (int)r2, t[j], frag_rb);
+                    conv_dgrad_store_fragment4<SpecS2>(frag + CFRAG_FWD_VECS, (int)r2, t[j]);
+                }
             }
         }
     }
@@ -1215,7 +1229,10 @@ __global__ __launch_bounds__(256) void rmsprop_kernel(const float *theta_in, flo
         if (frag) {
             const unsigned r1 = (unsigned)(4 * i) - w1_off, r2 = (unsigned)(4 * i) - w2_off;
             if (r1 < 16u * 256u) conv12_store_fragment4(frag, 0, (int)r1, t, frag_rb);
-            else if (r2 < 32u * 256u) conv12_store_fragment4(frag, 1, (int)r2, t, frag_rb);
+            else if (r2 < 32u * 256u) {
+                conv12_store_fragment4(frag, 1, (int)r2, t, frag_rb);
+                conv_dgrad_store_fragment4<SpecS2>(frag + CFRAG_FWD_VECS, (int)r2, t);
+            }
         }
     }
     for (size_t k = n4 * 4 + (size_t)blockIdx.x * 256 + threadIdx.x; k < n; k += stride) {
@@ -1380,13 +1397,6 @@ static hipError_t allow_dynamic_lds(const void *kernel, size_t bytes, size_t &se
     return e;
 }
 
-// Fixed-geometry kernels exist for the layers of the paper's networks.
-typedef ConvSpec<uint8_t, 4, 84, 84, 16, 8, 4> SpecS1;    // small net, conv1
-typedef ConvSpec<float, 16, 20, 20, 32, 4, 2> SpecS2;     // small net, conv2
-typedef ConvSpec<uint8_t, 4, 84, 84, 32, 8, 4> SpecL1;    // large net, conv1
-typedef ConvSpec<float, 32, 20, 20, 64, 4, 2> SpecL2;     // large net, conv2
-typedef ConvSpec<float, 64, 9, 9, 64, 3, 1> SpecL3;       // large net, conv3
-
 template <class SP>
 inline bool spec_matches(const ConvGeom &g, bool byte_input) {
     return g.C == SP::C && g.H == SP::H && g.W == SP::W && g.OC == SP::OC && g.KS == SP::KS && g.S == SP::S &&
@@ -1396,8 +1406,11 @@ inline bool is_aligned16(const void *p) { return (((uintptr_t)p) & 15) == 0; }
 
 // Things derived from parameter copy i, rebuilt on s after that copy was written there.
 int refresh_derived(ga3c_ctx *c, int i, hipStream_t s) {
-    if (c->cfrag[i])
+    if (c->cfrag[i]) {
         HIP_TRY(launch_conv12_filter_fragments(c->theta2[i] + c->off[0], c->theta2[i] + c->off[2], c->cfrag[i], s, c->rb));
+        if (c->cfrag_dgrad)
+            HIP_TRY(launch_conv_dgrad_filter_fragments<SpecS2>(c->theta2[i] + c->off[2], c->cfrag[i] + CFRAG_FWD_VECS, s));
+    }
     return GA3C_OK;
 }
 
@@ -1673,8 +1686,9 @@ extern "C" int ga3c_create(const ga3c_net_desc *d, int max_predict_batch, int ma
     }
     if (rc == GA3C_OK && c->nconv >= 2 && spec_matches<SpecS1>(c->geom[0], true) && spec_matches<SpecS2>(c->geom[1], false) &&
         c->off[0] % 4 == 0 && c->off[2] % 4 == 0) {
+        c->cfrag_dgrad = true;
         for (int i = 0; i < 2 && rc == GA3C_OK; ++i) {
-            guard(dmalloc((void **)&c->cfrag[i], sizeof(u32x4) * 3 * C12_FRAG_SET));
+            guard(dmalloc((void **)&c->cfrag[i], sizeof(u32x4) * CFRAG_VECS));
             if (rc == GA3C_OK) guard(refresh_derived(c, i, nullptr));
         }
         if (rc == GA3C_OK) guard(dmalloc((void **)&c->ticket, sizeof(int) * SP_MAX_FRAMES * SP_TICKET_PITCH));
@@ -2023,7 +2037,9 @@ static int train_step_impl(ga3c_ctx *c, const uint8_t *frames, const int32_t *ac
         // bytes: dY in, the layer's input (for the ReLU mask) in, dX out
         STAGE(CONV_DGRAD[l], 2.0 * B * g.OHW * g.OC * g.K, 4.0 * B * (g.OC * g.OHW + 2.0 * g.C * g.H * g.W));
         if (c->fast && spec_matches<SpecS2>(g, false) && is_aligned16(th + c->off[2 * l])) {
-            HIP_TRY(launch_conv_dgrad_bf16x6<SpecS2>(c->dact[l], th + c->off[2 * l], w.act[l - 1], c->dact[l - 1], B, s, 512, c->rb));
+            // the fragments of the copy being trained on, when the context keeps them (it does when conv1 is the small net's too)
+            const u32x4 *wfrag = c->cfrag[cur] && c->cfrag_dgrad ? c->cfrag[cur] + CFRAG_FWD_VECS : nullptr;
+            HIP_TRY(launch_conv_dgrad_bf16x6<SpecS2>(c->dact[l], th + c->off[2 * l], w.act[l - 1], c->dact[l - 1], B, s, 512, c->rb, wfrag));
             continue;
         }
         if (c->fast && spec_matches<SpecL2>(g, false) && is_aligned16(th + c->off[2 * l])) {

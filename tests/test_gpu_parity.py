@@ -324,6 +324,15 @@ def test_train_config2_clip_two_steps(G):
     assert ref["stats"]["grad_norm"] > 0
 
 
+def test_a_large_update_keeps_the_derived_filter_fragments_current(G):
+    # the kernel that updates the parameters also rewrites the split filter fragments that the fused forward kernel and
+    # the conv2 input-gradient kernel read; with a learning rate this large a fragment left behind by one update shows
+    # in the next step's layer-by-layer comparison (conv outputs, d conv1), which uses the parameters of that step
+    # (a third update of this size drives probabilities to zero and the comparison into 0 * inf)
+    ref = run_train(G, G.SMALL_NET(6), 8, 5, 4300, dict(lr=0.02), steps=2)
+    assert ref["stats"]["grad_norm"] > 0
+
+
 def test_train_clip_active(G):
     ref = run_train(G, G.SMALL_NET(6), 6, 5, 900, dict(clip_norm=0.5, lr=1e-3))
     assert ref["stats"]["clip_scale"] < 1.0
