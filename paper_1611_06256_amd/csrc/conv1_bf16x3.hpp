@@ -246,14 +246,16 @@ __global__ __launch_bounds__(256 * NPART) void conv1_bf16x3_wgrad_kernel(const u
     for (int e = tid; e < 64 * XPLANE / 2; e += NTHR) ((uint32_t *)xp)[e] = 0u;     // padding stays zero
     for (int e = tid; e < 3 * OC * DOC / 2; e += NTHR) ((uint32_t *)dp)[e] = 0u;
 
-    // staging descriptors: where my dwords come from and where they go
+    // staging descriptors: where my dwords come from and where they go.  A row of 21 dwords is five groups of four
+    // and a last group of one; that one is fetched as the last of the row's dwords 17..20, so that every fetch is one
+    // 16-byte load (4-byte aligned) that stays inside the frame.
     int xsrc[IPT], xdst[IPT], xcnt[IPT];
 #pragma unroll
     for (int i = 0; i < IPT; ++i) {
         const int it = min(tid + NTHR * i, NITEM - 1);
         const int row = it / 6, gq = it % 6;               // row = c*84 + r
         const int c = row / H, r = row % H;
-        xsrc[i] = row * (W / 4) + 4 * gq;                  // dword index in the frame
+        xsrc[i] = row * (W / 4) + (gq == 5 ? 17 : 4 * gq); // dword index in the frame
         xcnt[i] = (tid + NTHR * i < NITEM) ? (gq == 5 ? 1 : 4) : 0;
         xdst[i] = ((c * 4 + r % 4) * 4) * XPLANE + (r / 4) * XROW + 4 * gq;   // plane (c, u'=r%4, v'=0)
     }
@@ -273,14 +275,13 @@ __global__ __launch_bounds__(256 * NPART) void conv1_bf16x3_wgrad_kernel(const u
         for (int b = 0; b < 2; ++b) acc[a][b] = floatx4{0.f, 0.f, 0.f, 0.f};
     float bsum = 0.f;
 
-    uint32_t xpre[IPT][4];
+    typedef uint32_t u32x4_dword_aligned __attribute__((ext_vector_type(4), aligned(4)));
+    u32x4 xpre[IPT];
     float4 dpre[DPT];
     auto fetch = [&](int ff) {
         const uint32_t *xs = (const uint32_t *)(x + (size_t)ff * CHW);
 #pragma unroll
-        for (int i = 0; i < IPT; ++i)
-#pragma unroll
-            for (int t = 0; t < 4; ++t) xpre[i][t] = xs[min(xsrc[i] + t, CHW / 4 - 1)];
+        for (int i = 0; i < IPT; ++i) xpre[i] = *(const u32x4_dword_aligned *)(xs + xsrc[i]);
         const float4 *ds = (const float4 *)(dy + ((size_t)ff * OCT + oc0) * NPIX);
 #pragma unroll
         for (int i = 0; i < DPT; ++i) dpre[i] = ds[dsrc[i]];
@@ -294,12 +295,13 @@ __global__ __launch_bounds__(256 * NPART) void conv1_bf16x3_wgrad_kernel(const u
 #pragma unroll
         for (int i = 0; i < IPT; ++i) {
             if (xcnt[i] > 0) {
+                // a last group holds its dword in the fourth place; the other three places become zero padding
+                const u32x4 xv = xcnt[i] == 4 ? xpre[i] : u32x4{xpre[i][3], 0u, 0u, 0u};
 #pragma unroll
                 for (int vq = 0; vq < 4; ++vq) {             // plane v' = vq gets byte vq of each dword
                     union { __bf16 h[4]; uint2 u; } o;
 #pragma unroll
-                    for (int t = 0; t < 4; ++t)
-                        o.h[t] = (__bf16)(float)((t < xcnt[i] ? xpre[i][t] >> (8 * vq) : 0u) & 0xff);
+                    for (int t = 0; t < 4; ++t) o.h[t] = (__bf16)(float)((xv[t] >> (8 * vq)) & 0xff);
                     *(uint2 *)(xp + xdst[i] + vq * XPLANE) = o.u;
                 }
             }

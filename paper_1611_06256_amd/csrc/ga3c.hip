@@ -779,7 +779,10 @@ __global__ __launch_bounds__(256) void heads_dgrad_kernel(const float *__restric
 // 5), one thread per (frame, action), sums taken in action order so that they
 // do not depend on the thread layout; (4) heads backward: dh = [h > 0] dz W,
 // and the block's shares of the heads' weight and bias gradients (wpart
-// [block][A+1][F+1]) and of the fc bias gradient (colpart [block][F]).
+// [block][A+1][F+1]) and of the fc bias gradient (colpart [block][F]): a
+// thread takes four consecutive k and every fourth output (its wavefront's),
+// so that weights, activations and gradients move as 16-byte vectors; the four
+// partial sums of dh meet in LDS.
 // Writes h, zv, R, dzv (kept for inspection), dh, colpart, wpart and three loss
 // sums per block.  rb: operands of every product rounded to bfloat16.
 // Dynamic LDS: heads_train_lds_floats(F, A) floats.
@@ -788,7 +791,8 @@ __host__ __device__ inline int heads_train_kparts(int F, int A) {
     return kp < nk ? kp : nk;
 }
 __host__ __device__ inline int heads_train_lds_floats(int F, int A) {
-    return HD_FRAMES * heads_f4(F) + (A + 1) * (heads_f4(F) + 4) + HD_FRAMES * (A + 1) * (heads_train_kparts(F, A) + 4) + 512;
+    return HD_FRAMES * heads_f4(F) + (A + 1) * (heads_f4(F) + 4) + 4 * HD_FRAMES * 256 + (A + 1) * HD_FRAMES +
+           3 * HD_FRAMES * heads_f4(A + 1) + HD_FRAMES * (A + 1) * heads_train_kparts(F, A) + 512;
 }
 
 __global__ __launch_bounds__(256) void heads_train_kernel(
@@ -801,13 +805,16 @@ __global__ __launch_bounds__(256) void heads_train_kernel(
     extern __shared__ __attribute__((aligned(16))) float sm[];
     constexpr int NF = HD_FRAMES;
     const int F4 = heads_f4(F), WP = F4 + 4, A1 = A + 1, KP = heads_train_kparts(F, A);
+    const int ZR = heads_f4(A1);             // row pitch of the per-(frame, output) arrays: rows start on 16 bytes
     float *hs = sm;                          // [NF][F4]   fc output of my frames (rounded if rb)
     float *wsh = hs + NF * F4;               // [A1][WP]   head weights (rounded if rb)
-    float *zp = wsh + A1 * WP;               // [NF][A1][KP] partial dots, later scratch of the loss
-    float *zs = zp + NF * A1 * KP;           // [NF][A1]   head outputs, later their gradients
-    float *ex = zs + NF * A1;                // [NF][A1]   exp / per-action terms
-    float *tm = ex + NF * A1;                // [NF][A1]   per-action terms
-    float *rw = tm + NF * A1;                // [256]      rewards of the agents my frames belong to
+    float *red = wsh + A1 * WP;              // [4][NF][256] partial sums of dh, one set per wavefront
+    float *zt = red + 4 * NF * 256;          // [A1][NF]   gradients of the head outputs, transposed
+    float *zs = zt + A1 * NF;                // [NF][ZR]   head outputs, later their gradients
+    float *ex = zs + NF * ZR;                // [NF][ZR]   exp / per-action terms
+    float *tm = ex + NF * ZR;                // [NF][ZR]   per-action terms
+    float *zp = tm + NF * ZR;                // [NF][A1][KP] partial dots
+    float *rw = zp + NF * A1 * KP;           // [256]      rewards of the agents my frames belong to
     float *dn = rw + 256;                    // [256]      1 - done
     const int tid = threadIdx.x;
     const int b0 = blockIdx.x * NF;
@@ -904,7 +911,7 @@ __global__ __launch_bounds__(256) void heads_train_kernel(
         for (int kp = 0; kp < KP; ++kp) z += q[kp];
         z += obias;
         zv[(size_t)ob * A1 + oa] = z;
-        zs[ofb * A1 + oa] = z;
+        zs[ofb * ZR + oa] = z;
     }
     // ---- n-step return of my frame (threads with oa == A: one per frame)
     float Rt = 0.f;
@@ -923,28 +930,41 @@ __global__ __launch_bounds__(256) void heads_train_kernel(
         }
         Rt = next;
         R[ob] = next;
-        tm[ofb * A1 + A] = next;             // the policy threads of the frame read it from here
+        tm[ofb * ZR + A] = next;             // the policy threads of the frame read it from here
     }
     __syncthreads();
     // ---- loss and dL/dz, thread (frame, action); sums over the actions run in index order
     const bool pol = mine && oa < A;
-    const float *zr = zs + ofb * A1;
+    // rows are read four values at a time; sums still add one value after the other, in index order
+    const float *zr = zs + ofb * ZR;
     float zmax = 0.f, e = 0.f;
     if (pol) {
         zmax = zr[0];
-        for (int j = 1; j < A; ++j) zmax = fmaxf(zmax, zr[j]);
+        for (int j = 0; j < A; j += 4) {
+            const float4 q = *(const float4 *)(zr + j);
+            zmax = fmaxf(zmax, q.x);
+            if (j + 1 < A) zmax = fmaxf(zmax, q.y);
+            if (j + 2 < A) zmax = fmaxf(zmax, q.z);
+            if (j + 3 < A) zmax = fmaxf(zmax, q.w);
+        }
         e = expf(z - zmax);
-        ex[ofb * A1 + oa] = e;
+        ex[ofb * ZR + oa] = e;
     }
     __syncthreads();
     float p = 0.f, lg = 0.f, r = 1.f, adv = 0.f;
     if (mine) {
         const float V = zr[A];
-        adv = tm[ofb * A1 + A] - V;
+        adv = tm[ofb * ZR + A] - V;
     }
     if (pol) {
         float S = 0.f;
-        for (int j = 0; j < A; ++j) S += ex[ofb * A1 + j];
+        for (int j = 0; j < A; j += 4) {
+            const float4 q = *(const float4 *)(ex + ofb * ZR + j);
+            S += q.x;
+            if (j + 1 < A) S += q.y;
+            if (j + 2 < A) S += q.z;
+            if (j + 3 < A) S += q.w;
+        }
         const float logS = logf(S), invS = 1.f / S;
         p = e * invS;
         if (eps == 0.f) { lg = z - zmax - logS; r = 1.f; }
@@ -952,8 +972,8 @@ __global__ __launch_bounds__(256) void heads_train_kernel(
     }
     __syncthreads();                                  // every exp has been read
     if (pol) {
-        ex[ofb * A1 + oa] = p * lg;                   // -H terms
-        tm[ofb * A1 + oa] = p * beta * (lg + r);      // dot terms
+        ex[ofb * ZR + oa] = p * lg;                   // -H terms
+        tm[ofb * ZR + oa] = p * beta * (lg + r);      // dot terms
     }
     __syncthreads();
     float dzo = 0.f, s_pl = 0.f, s_vl = 0.f, s_en = 0.f;
@@ -962,7 +982,13 @@ __global__ __launch_bounds__(256) void heads_train_kernel(
     __syncthreads();
     if (mine) {
         float H = 0.f, dot = 0.f;
-        for (int j = 0; j < A; ++j) { H -= ex[ofb * A1 + j]; dot += tm[ofb * A1 + j]; }
+        for (int j = 0; j < A; j += 4) {
+            const float4 q = *(const float4 *)(ex + ofb * ZR + j), u = *(const float4 *)(tm + ofb * ZR + j);
+            H -= q.x; dot += u.x;
+            if (j + 1 < A) { H -= q.y; dot += u.y; }
+            if (j + 2 < A) { H -= q.z; dot += u.z; }
+            if (j + 3 < A) { H -= q.w; dot += u.w; }
+        }
         const bool known = (unsigned)oact < (unsigned)A;
         const float lga = known ? dn[ofb * 2] : 0.f, ra = known ? dn[ofb * 2 + 1] : 1.f;
         dot -= adv * ra;
@@ -973,8 +999,8 @@ __global__ __launch_bounds__(256) void heads_train_kernel(
         }
         dzv[(size_t)ob * A1 + oa] = dzo;
     }
-    __syncthreads();                                  // zs (the head outputs) has been read by everyone
-    if (mine) zs[ofb * A1 + oa] = rb ? bf16_rne(dzo) : dzo;
+    // the gradients go to zt[output][frame] (zero for frames the block does not have) for the backward pass
+    if (tid < NF * A1) zt[oa * NF + tid / A1] = mine ? (rb ? bf16_rne(dzo) : dzo) : 0.f;
     // loss sums of the block, frames in order (threads oa == A hold them)
     if (mine && oa == A) { rw[ofb] = s_pl; rw[NF + ofb] = s_vl; rw[2 * NF + ofb] = s_en; }
     __syncthreads();
@@ -984,36 +1010,61 @@ __global__ __launch_bounds__(256) void heads_train_kernel(
         for (int fb = 0; fb < nf; ++fb) sum += src[fb];
         losspart[3 * blockIdx.x + tid] = sum;
     }
-    // ---- heads backward (zs now holds dz of my frames)
-    for (int k = tid; k < F; k += 256) {
-        float hv[NF], sdh[NF];
+    // ---- heads backward (zt holds dz of my frames).  Wavefront ag takes the outputs ag, ag + 4, ..; lane kl the four
+    // k starting at kbase + 4 kl, 256 k per pass.
+    typedef float f32x4_dword_aligned __attribute__((ext_vector_type(4), aligned(4)));
+    const int ag = tid >> 6, kl = tid & 63;
+    for (int kbase = 0; kbase < F; kbase += 256) {
+        const int k4 = kbase + 4 * kl;
+        const bool kin = k4 < F4;
+        float4 hv[NF], sd[NF];
 #pragma unroll
-        for (int fb = 0; fb < NF; ++fb) { hv[fb] = hs[fb * F4 + k]; sdh[fb] = 0.f; }
-        float *wp = wpart + (size_t)blockIdx.x * A1 * (F + 1) + k;
-        for (int a = 0; a <= A; ++a) {
-            const float wv = wsh[a * WP + k];
-            float gw = 0.f;
+        for (int fb = 0; fb < NF; ++fb) {
+            hv[fb] = kin ? *(const float4 *)(hs + fb * F4 + k4) : float4{0.f, 0.f, 0.f, 0.f};
+            sd[fb] = float4{0.f, 0.f, 0.f, 0.f};
+        }
+        float *wp = wpart + (size_t)blockIdx.x * A1 * (F + 1) + k4;
+        for (int a = ag; a < A1; a += 4) {
+            const float4 wv = kin ? *(const float4 *)(wsh + a * WP + k4) : float4{0.f, 0.f, 0.f, 0.f};
+            const float4 d0 = *(const float4 *)(zt + a * NF), d1 = *(const float4 *)(zt + a * NF + 4);
+            const float d[NF] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
+            float4 gw = float4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int fb = 0; fb < NF; ++fb) {
-                const float d = fb < nf ? zs[fb * A1 + a] : 0.f;
-                sdh[fb] += d * wv;
-                gw += d * hv[fb];
+                sd[fb].x += d[fb] * wv.x; sd[fb].y += d[fb] * wv.y; sd[fb].z += d[fb] * wv.z; sd[fb].w += d[fb] * wv.w;
+                gw.x += d[fb] * hv[fb].x; gw.y += d[fb] * hv[fb].y; gw.z += d[fb] * hv[fb].z; gw.w += d[fb] * hv[fb].w;
             }
-            wp[(size_t)a * (F + 1)] = gw;
+            float *dst = wp + (size_t)a * (F + 1);
+            if (k4 + 3 < F) {
+                *(f32x4_dword_aligned *)dst = f32x4_dword_aligned{gw.x, gw.y, gw.z, gw.w};
+            } else {
+                if (k4 < F) dst[0] = gw.x;
+                if (k4 + 1 < F) dst[1] = gw.y;
+                if (k4 + 2 < F) dst[2] = gw.z;
+            }
         }
-        float col = 0.f;
 #pragma unroll
-        for (int fb = 0; fb < NF; ++fb)
-            if (fb < nf) {
-                const float v = hv[fb] > 0.f ? sdh[fb] : 0.f;
-                dh[(size_t)(b0 + fb) * F + k] = v;
-                col += rb ? bf16_rne(v) : v;
-            }
-        colpart[(size_t)blockIdx.x * F + k] = col;
+        for (int fb = 0; fb < NF; ++fb) *(float4 *)(red + (ag * NF + fb) * 256 + 4 * kl) = sd[fb];
+        __syncthreads();
+        const int k = kbase + tid;
+        if (k < F) {
+            float col = 0.f;
+#pragma unroll
+            for (int fb = 0; fb < NF; ++fb)
+                if (fb < nf) {
+                    const float sum = (red[fb * 256 + tid] + red[(NF + fb) * 256 + tid]) +
+                                      (red[(2 * NF + fb) * 256 + tid] + red[(3 * NF + fb) * 256 + tid]);
+                    const float v = hs[fb * F4 + k] > 0.f ? sum : 0.f;
+                    dh[(size_t)(b0 + fb) * F + k] = v;
+                    col += rb ? bf16_rne(v) : v;
+                }
+            colpart[(size_t)blockIdx.x * F + k] = col;
+        }
+        __syncthreads();                              // red is written again in the next pass
     }
     if (tid <= A) {
         float gb = 0.f;
-        for (int fb = 0; fb < nf; ++fb) gb += zs[fb * A1 + tid];
+        for (int fb = 0; fb < nf; ++fb) gb += zt[tid * NF + fb];
         wpart[((size_t)blockIdx.x * A1 + tid) * (F + 1) + F] = gb;
     }
 }
@@ -1385,7 +1436,7 @@ inline int conv_like_tiles(int M, int N) {
 }
 
 // LDS the fused training heads kernel may ask for; larger heads fall back to the separate kernels.
-constexpr size_t HEADS_TRAIN_MAX_LDS = 96 * 1024;
+constexpr size_t HEADS_TRAIN_MAX_LDS = 128 * 1024;
 constexpr size_t HEADS_FWD_MAX_LDS = 160 * 1024;      // all of a compute unit's LDS
 
 // A kernel may take more than 64 KB of dynamic LDS only after its limit has
