@@ -16,6 +16,8 @@
 // 48-byte window of the plane: whole dwords for e = 0, a 16-bit funnel shift
 // for e = 1.  Wavefront w owns phase w: 4 shifts x OC / 16 filter tiles of
 // accumulators [16 filters] x [16 channels], kept over all frames of its block.
+// The bias gradient is one more product, dY times a column of ones, which the
+// wavefronts of channel slice 0 share by groups of 32 k.
 //
 // Both operands are split into three bf16 terms (x = hi + mid + lo exactly)
 // while they are staged, and a product is evaluated as the six largest of the
@@ -64,7 +66,7 @@ __global__ __launch_bounds__(256, ConvWgradBf16Geom<SP>::PER_CU) void conv_wgrad
                                                                                               int nframes, float scale) {
     typedef ConvWgradBf16Geom<SP> G;
     static_assert(SP::KS == 4 && SP::S == 2, "kernel must be 4x4 with stride 2");
-    static_assert(SP::C % 16 == 0 && SP::OC % 16 == 0 && 256 % SP::OC == 0, "channels and filters in groups of 16");
+    static_assert(SP::C % 16 == 0 && SP::OC % 16 == 0 && SP::OC <= 256, "channels and filters in groups of 16");
     static_assert(SP::H % 2 == 0 && SP::W % 4 == 0 && G::GW % 2 == 0, "rows are read four values at a time; shifts are whole dwords");
     static_assert(G::GW + 9 <= G::WIN, "the window must hold the largest shift plus eight elements");
     static_assert(SP::OW + 1 <= G::GW && SP::OH + 1 <= G::GH, "shifted pixels must stay on the phase grid");
@@ -74,7 +76,6 @@ __global__ __launch_bounds__(256, ConvWgradBf16Geom<SP>::PER_CU) void conv_wgrad
     constexpr int NTERM = ONE ? 1 : 3;
     constexpr int W4 = SP::W / 4, XV = CS * SP::H * W4, XPT = (XV + 255) / 256;       // float4 of the input slice
     constexpr int NDV = SP::OC * SP::NPIX / 4, DPT = (NDV + 255) / 256;                // float4 of dY
-    constexpr int TPO = 256 / SP::OC;                                                  // threads per filter in the bias sum
     constexpr int K1 = SP::K + 1;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     __bf16 *dsm = (__bf16 *)smem;                      // [term][oc][DROW]
@@ -112,7 +113,11 @@ __global__ __launch_bounds__(256, ConvWgradBf16Geom<SP>::PER_CU) void conv_wgrad
     for (int s = 0; s < 4; ++s)
 #pragma unroll
         for (int m = 0; m < MT; ++m) acc[s][m] = floatx4{0.f, 0.f, 0.f, 0.f};
-    float bsum = 0.f;
+    floatx4 bacc[MT];                                  // dY times ones: every column holds the row sums
+#pragma unroll
+    for (int m = 0; m < MT; ++m) bacc[m] = floatx4{0.f, 0.f, 0.f, 0.f};
+    Bf16x8Bits ones;
+    ones.u = u32x4{0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u};
 
     float4 xpre[XPT], dpre[DPT];
     auto fetch = [&](int f) {
@@ -158,19 +163,6 @@ __global__ __launch_bounds__(256, ConvWgradBf16Geom<SP>::PER_CU) void conv_wgrad
         fetch(min(f + (int)gridDim.x, nframes - 1));
         // the loads above go out before the products start (the compiler would otherwise sink them below the MFMAs)
         __builtin_amdgcn_sched_barrier(0);
-        if (blockIdx.y == 0) {   // bias: TPO threads share a filter row, combined in lane order; the terms add up to dY exactly
-            const int oc = tid / TPO, part_id = tid % TPO;
-            float sum = 0.f;
-            for (int pp = part_id; pp < SP::NPIX; pp += TPO) {
-                const int k = oc * DROW + (pp / SP::OW) * GW + pp % SP::OW;
-                float v = (float)dsm[k];
-                if (!ONE) v = (v + (float)dsm[DTERM + k]) + (float)dsm[2 * DTERM + k];
-                sum += v;
-            }
-#pragma unroll
-            for (int o = TPO / 2; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
-            bsum += sum;
-        }
         constexpr int NPROD = ONE ? 1 : 6;
         constexpr int PA[6] = {2, 1, 0, 1, 0, 0}, PB[6] = {0, 1, 2, 0, 1, 0};      // smallest products first
 #pragma unroll
@@ -181,6 +173,13 @@ __global__ __launch_bounds__(256, ConvWgradBf16Geom<SP>::PER_CU) void conv_wgrad
 #pragma unroll
                 for (int t = 0; t < NTERM; ++t)
                     a[m][t].u = *(const u32x4 *)(dsm + t * DTERM + (m * 16 + l16) * DROW + 32 * kb + 8 * g);
+            if (blockIdx.y == 0 && kb % 4 == wave) {      // bias: the terms add up to dY exactly, smallest first
+#pragma unroll
+                for (int t = NTERM - 1; t >= 0; --t)
+#pragma unroll
+                    for (int m = 0; m < MT; ++m)
+                        bacc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m][t].v, ones.v, bacc[m], 0, 0, 0);
+            }
 #pragma unroll
             for (int t = 0; t < NTERM; ++t) {
                 const u32x4 *src = (const u32x4 *)(psm + t * PTERM + (wave * CS + l16) * PROW + 32 * kb + 8 * g);
@@ -209,6 +208,13 @@ __global__ __launch_bounds__(256, ConvWgradBf16Geom<SP>::PER_CU) void conv_wgrad
     // The block's result is put together in LDS and leaves in rows.
     __syncthreads();
     float *ot = (float *)smem;                         // [oc][OTP]
+    __shared__ float bsh[4][SP::OC];                   // bias sums of the four wavefronts
+    if (l16 == 0) {
+#pragma unroll
+        for (int m = 0; m < MT; ++m)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) bsh[wave][m * 16 + 4 * g + r] = bacc[m][r];
+    }
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
         const int u = ry + 2 * (s / 2), v = rx + 2 * (s % 2);
@@ -225,7 +231,8 @@ __global__ __launch_bounds__(256, ConvWgradBf16Geom<SP>::PER_CU) void conv_wgrad
         const float4 v = *(const float4 *)(ot + oc * OTP + 4 * kq);
         *(f32x4_dword_aligned *)(pb + (size_t)oc * K1 + 4 * kq) = f32x4_dword_aligned{v.x * scale, v.y * scale, v.z * scale, v.w * scale};
     }
-    if (blockIdx.y == 0 && tid % TPO == 0) part[(size_t)blockIdx.x * SP::OC * K1 + (size_t)(tid / TPO) * K1 + SP::K] = bsum;
+    if (blockIdx.y == 0 && tid < SP::OC)
+        part[(size_t)blockIdx.x * SP::OC * K1 + (size_t)tid * K1 + SP::K] = (bsh[0][tid] + bsh[1][tid]) + (bsh[2][tid] + bsh[3][tid]);
 }
 
 // One partial dW per block: fewer blocks where a partial is large.
