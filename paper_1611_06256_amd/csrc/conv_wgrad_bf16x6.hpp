@@ -165,25 +165,31 @@ __global__ __launch_bounds__(256, ConvWgradBf16Geom<SP>::PER_CU) void conv_wgrad
         __builtin_amdgcn_sched_barrier(0);
         constexpr int NPROD = ONE ? 1 : 6;
         constexpr int PA[6] = {2, 1, 0, 1, 0, 0}, PB[6] = {0, 1, 2, 0, 1, 0};      // smallest products first
-#pragma unroll
-        for (int kb = 0; kb < NKB; ++kb) {
-            Bf16x8Bits a[MT][NTERM], b[4][NTERM];
+        // the operand reads of the next group of 32 k are issued before the products of this one
+        Bf16x8Bits a[2][MT][NTERM];
+        u32x4 win[2][NTERM][3];
+        auto read_operands = [&](int kb, Bf16x8Bits (&ad)[MT][NTERM], u32x4 (&wd)[NTERM][3]) {
 #pragma unroll
             for (int m = 0; m < MT; ++m)
 #pragma unroll
                 for (int t = 0; t < NTERM; ++t)
-                    a[m][t].u = *(const u32x4 *)(dsm + t * DTERM + (m * 16 + l16) * DROW + 32 * kb + 8 * g);
-            if (blockIdx.y == 0 && kb % 4 == wave) {      // bias: the terms add up to dY exactly, smallest first
-#pragma unroll
-                for (int t = NTERM - 1; t >= 0; --t)
-#pragma unroll
-                    for (int m = 0; m < MT; ++m)
-                        bacc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m][t].v, ones.v, bacc[m], 0, 0, 0);
-            }
+                    ad[m][t].u = *(const u32x4 *)(dsm + t * DTERM + (m * 16 + l16) * DROW + 32 * kb + 8 * g);
 #pragma unroll
             for (int t = 0; t < NTERM; ++t) {
                 const u32x4 *src = (const u32x4 *)(psm + t * PTERM + (wave * CS + l16) * PROW + 32 * kb + 8 * g);
-                const u32x4 w0 = src[0], w1 = src[1], w2 = src[2];
+                wd[t][0] = src[0]; wd[t][1] = src[1]; wd[t][2] = src[2];
+            }
+        };
+        read_operands(0, a[0], win[0]);
+        __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+        for (int kb = 0; kb < NKB; ++kb) {
+            if (kb + 1 < NKB) read_operands(kb + 1, a[(kb + 1) & 1], win[(kb + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+            Bf16x8Bits b[4][NTERM];
+#pragma unroll
+            for (int t = 0; t < NTERM; ++t) {
+                const u32x4 w0 = win[kb & 1][t][0], w1 = win[kb & 1][t][1], w2 = win[kb & 1][t][2];
                 const uint32_t dw[12] = {w0[0], w0[1], w0[2], w0[3], w1[0], w1[1], w1[2], w1[3], w2[0], w2[1], w2[2], w2[3]};
 #pragma unroll
                 for (int av = 0; av < 2; ++av) {
@@ -193,6 +199,13 @@ __global__ __launch_bounds__(256, ConvWgradBf16Geom<SP>::PER_CU) void conv_wgrad
                                                __builtin_amdgcn_alignbit(dw[o + 3], dw[o + 2], 16), __builtin_amdgcn_alignbit(dw[o + 4], dw[o + 3], 16)};
                 }
             }
+            if (blockIdx.y == 0 && kb % 4 == wave) {      // bias: the terms add up to dY exactly, smallest first
+#pragma unroll
+                for (int t = NTERM - 1; t >= 0; --t)
+#pragma unroll
+                    for (int m = 0; m < MT; ++m)
+                        bacc[m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[kb & 1][m][t].v, ones.v, bacc[m], 0, 0, 0);
+            }
 #pragma unroll
             for (int q = 0; q < NPROD; ++q) {
                 const int ai = ONE ? 0 : PA[q], bi = ONE ? 0 : PB[q];
@@ -200,9 +213,11 @@ __global__ __launch_bounds__(256, ConvWgradBf16Geom<SP>::PER_CU) void conv_wgrad
                 for (int s = 0; s < 4; ++s)
 #pragma unroll
                     for (int m = 0; m < MT; ++m)
-                        acc[s][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m][ai % NTERM].v, b[s][bi % NTERM].v, acc[s][m], 0, 0, 0);
+                        acc[s][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[kb & 1][m][ai % NTERM].v, b[s][bi % NTERM].v, acc[s][m], 0, 0, 0);
             }
+            __builtin_amdgcn_sched_barrier(0);
         }
+        __builtin_amdgcn_s_setprio(0);
     }
     // lane (l16, g), register r of acc[s = 2a + e][m]: filter 16 m + 4 g + r, channel c0 + l16, tap (ry + 2a, rx + 2e).
     // The block's result is put together in LDS and leaves in rows.
