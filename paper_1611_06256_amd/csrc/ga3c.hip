@@ -119,6 +119,7 @@ struct ga3c_ctx {
     // kernel's first, then (at CFRAG_FWD_VECS) the input-gradient kernel's; refreshed by whoever writes the copy
     u32x4 *cfrag[2];
     bool cfrag_dgrad;             // the buffers hold the second part too (a context that can train)
+    u32x4 *dfrag_large;           // larger net: conv2 filters as fragments for its input-gradient kernel, rebuilt by every update call
     int *ticket;                  // predict_small_kernel's per-frame counters, zero between launches
     Work pred, train;
     // training only
@@ -1749,6 +1750,8 @@ extern "C" int ga3c_create(const ga3c_net_desc *d, int max_predict_batch, int ma
             if (e != hipSuccess) guard(fail(GA3C_EHIP, "hipMemset: %s", hipGetErrorString(e)));
         }
     }
+    if (rc == GA3C_OK && c->nconv >= 2 && spec_matches<SpecL2>(c->geom[1], false) && c->off[2] % 4 == 0)
+        guard(dmalloc((void **)&c->dfrag_large, sizeof(u32x4) * ConvDgradBf16Geom<SpecL2>::FRAG_VECS));
     if (rc == GA3C_OK) guard(alloc_work(c->pred, c, max_predict_batch));
     if (rc == GA3C_OK) guard(alloc_work(c->train, c, max_train_frames));
     if (rc == GA3C_OK && max_train_frames > 0) {
@@ -1797,7 +1800,7 @@ extern "C" int ga3c_destroy(ga3c_ctx *c) {
         if (c->ev_readers[i]) (void)hipEventDestroy(c->ev_readers[i]);
     }
     (void)hipFree(c->g); (void)hipFree(c->grad);
-    (void)hipFree(c->cfrag[0]); (void)hipFree(c->cfrag[1]); (void)hipFree(c->ticket);
+    (void)hipFree(c->cfrag[0]); (void)hipFree(c->cfrag[1]); (void)hipFree(c->ticket); (void)hipFree(c->dfrag_large);
     free_work(c->pred); free_work(c->train);
     (void)hipFree(c->dh); (void)hipFree(c->dzv); (void)hipFree(c->R);
     (void)hipFree(c->partials); (void)hipFree(c->colpart); (void)hipFree(c->scale); (void)hipFree(c->stats);
@@ -2103,7 +2106,11 @@ static int train_step_impl(ga3c_ctx *c, const uint8_t *frames, const int32_t *ac
             continue;
         }
         if (c->fast && spec_matches<SpecL2>(g, false) && is_aligned16(th + c->off[2 * l])) {
-            HIP_TRY(launch_conv_dgrad_bf16x6<SpecL2>(c->dact[l], th + c->off[2 * l], w.act[l - 1], c->dact[l - 1], B, s, 512, c->rb));
+            // the filters as ready-made fragments first (one small launch: gathering them costs every block of the
+            // gradient kernel tens of scattered loads per lane)
+            if (c->dfrag_large && l == 1) HIP_TRY(launch_conv_dgrad_filter_fragments<SpecL2>(th + c->off[2 * l], c->dfrag_large, s));
+            HIP_TRY(launch_conv_dgrad_bf16x6<SpecL2>(c->dact[l], th + c->off[2 * l], w.act[l - 1], c->dact[l - 1], B, s, 512, c->rb,
+                                                     l == 1 ? c->dfrag_large : nullptr));
             continue;
         }
         if (c->fast && spec_matches<SpecL3>(g, false)) {
