@@ -20,7 +20,10 @@
 // w % 4 for the pixel tiles w / 4, w / 4 + NW / 4, ... and keeps its tile's
 // filters for all k in registers as split fragments for the whole launch (that
 // is 12 registers per k-block: hence one or two wavefronts per SIMD).  The next
-// frame travels from memory while the current one is multiplied.
+// frame travels from memory while the current one is multiplied.  The fragments
+// can be handed in ready-made (`wfrag`, the register image of the four filter
+// tiles, built once per parameter copy): gathering them costs 8 KB scattered
+// loads per lane, more than a frame's products when a block sees one frame.
 //
 // The input gradient of a stride-1 layer is the same computation with other
 // operands (DGRAD): dX = [xin > 0] * (dY zero-padded by KS - 1 on every side,
@@ -54,7 +57,40 @@ struct ConvFwdBf16Geom {
         return row * SP::W + (SP::S == 2 ? (xcol & 1) * (SP::W / 2) + (xcol >> 1) : xcol);
     }
     __host__ __device__ static constexpr int lds_bytes(bool one) { return (one ? 1 : 3) * PLANE; }
+    static constexpr int FRAG_VECS = 4 * KB * 3 * 64;             // ready-made fragments: [filter tile][k-block][term][lane]
 };
+
+// The value that sits at row (filter o of the tile layout), k = (tap, channel ic) of the kernel's filter operand.
+template <class SP, bool DGRAD>
+__device__ __forceinline__ float conv_fwd_filter_value(const float *__restrict__ w, int o, int ic, int u, int v) {
+    constexpr int KS = SP::KS;
+    return DGRAD ? w[((size_t)(ic * SP::OC + o) * KS + (KS - 1 - u)) * KS + (KS - 1 - v)]
+                 : w[((size_t)(o * SP::C + ic) * KS + u) * KS + v];
+}
+
+// All fragments of a layer (for DGRAD: of its pseudo-layer SP) from the filter tensor: thread i of 4 * KB * 64 writes
+// the three vectors of one (filter tile, k-block, lane).
+template <class SP, bool DGRAD>
+__device__ __forceinline__ void conv_fwd_filter_fragments_thread(const float *__restrict__ w, u32x4 *__restrict__ wfrag, int i) {
+    typedef ConvFwdBf16Geom<SP> G;
+    if (i >= 4 * G::KB * 64) return;
+    const int lane = i % 64, kb = (i / 64) % G::KB, ot = i / (64 * G::KB);
+    const int l16 = lane & 15, g = lane >> 4;
+    const int tap = kb / G::CG, cg = kb % G::CG, u = tap / SP::KS, v = tap % SP::KS;
+    Bf16x8Bits t[3];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        __bf16 h, m, l;
+        split3(conv_fwd_filter_value<SP, DGRAD>(w, ot * 16 + l16, cg * 32 + 8 * g + j, u, v), h, m, l);
+        t[0].v[j] = h; t[1].v[j] = m; t[2].v[j] = l;
+    }
+#pragma unroll
+    for (int q = 0; q < 3; ++q) wfrag[(size_t)((ot * G::KB + kb) * 3 + q) * 64 + lane] = t[q].u;
+}
+template <class SP, bool DGRAD>
+__global__ __launch_bounds__(256) void conv_fwd_filter_fragments_kernel(const float *__restrict__ w, u32x4 *__restrict__ wfrag) {
+    conv_fwd_filter_fragments_thread<SP, DGRAD>(w, wfrag, blockIdx.x * 256 + threadIdx.x);
+}
 
 // NW wavefronts per block (4 or 8).  ONE: operands rounded to bfloat16 (the reduced-precision variant): one term,
 // one product.  DGRAD: x = dY [SP::C][SP::H - 2 PAD][SP::W - 2 PAD], w = the layer's filters [SP::C][SP::OC][KS][KS],
@@ -62,7 +98,7 @@ struct ConvFwdBf16Geom {
 template <class SP, int NW, bool ONE, bool DGRAD>
 __global__ __launch_bounds__(64 * NW, 1) void conv_fwd_bf16x6_kernel(const float *__restrict__ x, const float *__restrict__ w,
                                                                      const float *__restrict__ aux, float *__restrict__ y,
-                                                                     int nframes) {
+                                                                     int nframes, const u32x4 *__restrict__ wfrag) {
     typedef ConvFwdBf16Geom<SP> G;
     static_assert(SP::C % 32 == 0 && SP::OC == 64, "32 k channels in, 64 filters out");
     static_assert(NW == 4 || NW == 8, "one or two wavefronts per SIMD");
@@ -103,21 +139,26 @@ __global__ __launch_bounds__(64 * NW, 1) void conv_fwd_bf16x6_kernel(const float
 
     // filter fragments of my tile: row = filter 16 ot + l16, k = (tap, channel 32 cg + 8 g .. + 7)
     Bf16x8Bits wq[KB][NTERM];
+    if (wfrag) {
+        const u32x4 *src = wfrag + (size_t)(ot * KB) * 3 * 64 + lane;
 #pragma unroll
-    for (int kb = 0; kb < KB; ++kb) {
-        const int tap = kb / CG, cg = kb % CG, u = tap / KS, v = tap % KS;
-        Bf16x8Bits t[3];
+        for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int o = ot * 16 + l16, ic = cg * 32 + 8 * g + j;
-            const float fw = DGRAD ? w[((size_t)(ic * SP::OC + o) * KS + (KS - 1 - u)) * KS + (KS - 1 - v)]
-                                   : w[((size_t)(o * C + ic) * KS + u) * KS + v];
-            __bf16 h, m, l;
-            split3(fw, h, m, l);
-            t[0].v[j] = h; t[1].v[j] = m; t[2].v[j] = l;
+            for (int q = 0; q < NTERM; ++q) wq[kb][q].u = src[(kb * 3 + q) * 64];
+    } else {
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) {
+            const int tap = kb / CG, cg = kb % CG, u = tap / KS, v = tap % KS;
+            Bf16x8Bits t[3];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                __bf16 h, m, l;
+                split3(conv_fwd_filter_value<SP, DGRAD>(w, ot * 16 + l16, cg * 32 + 8 * g + j, u, v), h, m, l);
+                t[0].v[j] = h; t[1].v[j] = m; t[2].v[j] = l;
+            }
+#pragma unroll
+            for (int q = 0; q < NTERM; ++q) wq[kb][q] = t[q];
         }
-#pragma unroll
-        for (int q = 0; q < NTERM; ++q) wq[kb][q] = t[q];
     }
     float bv[4];
 #pragma unroll
@@ -213,7 +254,7 @@ __global__ __launch_bounds__(64 * NW, 1) void conv_fwd_bf16x6_kernel(const float
 // `blocks`: how many blocks the chip holds at once.
 template <class SP, int NW, bool DGRAD>
 inline hipError_t launch_conv_bf16x6_impl(const float *x, const float *w, const float *aux, float *y, int nframes,
-                                          hipStream_t s, int blocks, int rb) {
+                                          hipStream_t s, int blocks, int rb, const u32x4 *wfrag) {
     if (nframes <= 0) return hipSuccess;
     typedef ConvFwdBf16Geom<SP> G;
     const int grid = nframes < blocks ? nframes : blocks;
@@ -229,28 +270,47 @@ inline hipError_t launch_conv_bf16x6_impl(const float *x, const float *w, const 
     }
     if (rb)
         ga3c::launch((conv_fwd_bf16x6_kernel<SP, NW, true, DGRAD>), dim3(grid), dim3(64 * NW), G::lds_bytes(true), s, x, w,
-                           aux, y, nframes);
+                           aux, y, nframes, wfrag);
     else
         ga3c::launch((conv_fwd_bf16x6_kernel<SP, NW, false, DGRAD>), dim3(grid), dim3(64 * NW), G::lds_bytes(false), s, x,
-                           w, aux, y, nframes);
+                           w, aux, y, nframes, wfrag);
     return hipGetLastError();
 }
 
 template <class SP, int NW>
 inline hipError_t launch_conv_fwd_bf16x6(const float *x, const float *w, const float *bias, float *y, int nframes,
-                                         hipStream_t s, int blocks, int rb = 0) {
-    return launch_conv_bf16x6_impl<SP, NW, false>(x, w, bias, y, nframes, s, blocks, rb);
+                                         hipStream_t s, int blocks, int rb = 0, const u32x4 *wfrag = nullptr) {
+    return launch_conv_bf16x6_impl<SP, NW, false>(x, w, bias, y, nframes, s, blocks, rb, wfrag);
+}
+
+// The ready-made fragments of layer SP's forward pass: wfrag [ConvFwdBf16Geom<SP>::FRAG_VECS].
+template <class SP>
+inline hipError_t launch_conv_fwd_filter_fragments(const float *w, u32x4 *wfrag, hipStream_t s) {
+    ga3c::launch((conv_fwd_filter_fragments_kernel<SP, false>), dim3(ConvFwdBf16Geom<SP>::KB), dim3(256), 0, s, w, wfrag);
+    return hipGetLastError();
 }
 
 // Input gradient of the stride-1 layer SP: dy [n][OC][OH][OW], w the layer's filters, xin the layer's input
 // [n][C][H][W] (its ReLU mask), dx [n][C][H][W].
 template <class SP, int NW>
 inline hipError_t launch_conv_dgrad_s1_bf16x6(const float *dy, const float *w, const float *xin, float *dx, int nframes,
-                                              hipStream_t s, int blocks, int rb = 0) {
+                                              hipStream_t s, int blocks, int rb = 0, const u32x4 *wfrag = nullptr) {
     static_assert(SP::S == 1, "stride 1");
     typedef ConvSpec<float, SP::OC, SP::OH + 2 * (SP::KS - 1), SP::OW + 2 * (SP::KS - 1), SP::C, SP::KS, 1> Pseudo;
     static_assert(Pseudo::OH == SP::H && Pseudo::OW == SP::W, "the padded correlation gives back the input size");
-    return launch_conv_bf16x6_impl<Pseudo, NW, true>(dy, w, xin, dx, nframes, s, blocks, rb);
+    return launch_conv_bf16x6_impl<Pseudo, NW, true>(dy, w, xin, dx, nframes, s, blocks, rb, wfrag);
+}
+
+// The ready-made fragments of that input gradient (of the pseudo-layer: as many vectors as conv_dgrad_s1_frag_vecs).
+template <class SP>
+constexpr int conv_dgrad_s1_frag_vecs() {
+    return ConvFwdBf16Geom<ConvSpec<float, SP::OC, SP::OH + 2 * (SP::KS - 1), SP::OW + 2 * (SP::KS - 1), SP::C, SP::KS, 1>>::FRAG_VECS;
+}
+template <class SP>
+inline hipError_t launch_conv_dgrad_s1_filter_fragments(const float *w, u32x4 *wfrag, hipStream_t s) {
+    typedef ConvSpec<float, SP::OC, SP::OH + 2 * (SP::KS - 1), SP::OW + 2 * (SP::KS - 1), SP::C, SP::KS, 1> Pseudo;
+    ga3c::launch((conv_fwd_filter_fragments_kernel<Pseudo, true>), dim3(ConvFwdBf16Geom<Pseudo>::KB), dim3(256), 0, s, w, wfrag);
+    return hipGetLastError();
 }
 
 }  // namespace ga3c

@@ -38,6 +38,25 @@ typedef ConvSpec<float, 64, 9, 9, 64, 3, 1> SpecL3;       // large net, conv3
 // 16-byte vectors of a small-net fragment buffer: the filters of conv1 / conv2 for the fused forward kernel, then
 // those of conv2 for its input-gradient kernel
 constexpr int CFRAG_FWD_VECS = 3 * C12_FRAG_SET, CFRAG_VECS = CFRAG_FWD_VECS + ConvDgradBf16Geom<SpecS2>::FRAG_VECS;
+// parts of a larger-net fragment buffer: conv2 forward, conv2 input gradient, conv3 forward, conv3 input gradient
+constexpr int LFRAG_FWD2 = 0, LFRAG_DGRAD2 = LFRAG_FWD2 + ConvFwdBf16Geom<SpecL2>::FRAG_VECS,
+              LFRAG_FWD3 = LFRAG_DGRAD2 + ConvDgradBf16Geom<SpecL2>::FRAG_VECS, LFRAG_DGRAD3 = LFRAG_FWD3 + ConvFwdBf16Geom<SpecL3>::FRAG_VECS,
+              LFRAG_VECS = LFRAG_DGRAD3 + conv_dgrad_s1_frag_vecs<SpecL3>();
+
+// All four parts in one launch (w2, w3: the filter tensors of conv2 and conv3).
+typedef ConvSpec<float, SpecL3::OC, SpecL3::OH + 2 * (SpecL3::KS - 1), SpecL3::OW + 2 * (SpecL3::KS - 1), SpecL3::C, SpecL3::KS, 1> SpecL3Dgrad;
+constexpr int LFRAG_B0 = ConvFwdBf16Geom<SpecL2>::KB, LFRAG_B1 = LFRAG_B0 + (SpecL2::OC * SpecL2::C * 4 + 255) / 256,
+              LFRAG_B2 = LFRAG_B1 + ConvFwdBf16Geom<SpecL3>::KB, LFRAG_B3 = LFRAG_B2 + ConvFwdBf16Geom<SpecL3Dgrad>::KB;
+__global__ __launch_bounds__(256) void large_filter_fragments_kernel(const float *__restrict__ w2, const float *__restrict__ w3,
+                                                                     u32x4 *__restrict__ lfrag) {
+    const int b = blockIdx.x, t = threadIdx.x;
+    if (b < LFRAG_B0) conv_fwd_filter_fragments_thread<SpecL2, false>(w2, lfrag + LFRAG_FWD2, b * 256 + t);
+    else if (b < LFRAG_B1) {
+        const int i = (b - LFRAG_B0) * 256 + t;
+        if (i < SpecL2::OC * SpecL2::C * 4) conv_dgrad_store_fragment4<SpecL2>(lfrag + LFRAG_DGRAD2, 4 * i, ((const float4 *)w2)[i]);
+    } else if (b < LFRAG_B2) conv_fwd_filter_fragments_thread<SpecL3, false>(w3, lfrag + LFRAG_FWD3, (b - LFRAG_B1) * 256 + t);
+    else conv_fwd_filter_fragments_thread<SpecL3Dgrad, true>(w3, lfrag + LFRAG_DGRAD3, (b - LFRAG_B2) * 256 + t);
+}
 
 // ---------------------------------------------------------------- errors ----
 
@@ -119,7 +138,9 @@ struct ga3c_ctx {
     // kernel's first, then (at CFRAG_FWD_VECS) the input-gradient kernel's; refreshed by whoever writes the copy
     u32x4 *cfrag[2];
     bool cfrag_dgrad;             // the buffers hold the second part too (a context that can train)
-    u32x4 *dfrag_large;           // larger net: conv2 filters as fragments for its input-gradient kernel, rebuilt by every update call
+    // larger net: the filters of conv2 and conv3 of each parameter copy as ready-made fragments for the forward and the
+    // input-gradient kernels (LFRAG_* give the parts); rebuilt by whoever writes the copy
+    u32x4 *lfrag[2];
     int *ticket;                  // predict_small_kernel's per-frame counters, zero between launches
     Work pred, train;
     // training only
@@ -1464,6 +1485,11 @@ int refresh_derived(ga3c_ctx *c, int i, hipStream_t s) {
         if (c->cfrag_dgrad)
             HIP_TRY(launch_conv_dgrad_filter_fragments<SpecS2>(c->theta2[i] + c->off[2], c->cfrag[i] + CFRAG_FWD_VECS, s));
     }
+    if (c->lfrag[i]) {
+        const float *w2 = c->theta2[i] + c->off[2], *w3 = c->theta2[i] + c->off[4];
+        ga3c::launch(large_filter_fragments_kernel, dim3(LFRAG_B3), dim3(256), 0, s, w2, w3, c->lfrag[i]);
+        HIP_TRY(hipGetLastError());
+    }
     return GA3C_OK;
 }
 
@@ -1535,11 +1561,13 @@ int forward(ga3c_ctx *c, int which, Work &w, const uint8_t *frames, int B, bool 
                 continue;
             }
             if (spec_matches<SpecL2>(g, l == 0)) {      // the frame as split bf16 planes in LDS: one block per CU
-                HIP_TRY((launch_conv_fwd_bf16x6<SpecL2, 4>((const float *)xin, wl, bl, w.act[l], B, s, 256, c->rb)));
+                HIP_TRY((launch_conv_fwd_bf16x6<SpecL2, 4>((const float *)xin, wl, bl, w.act[l], B, s, 256, c->rb,
+                                                           c->lfrag[which] && l == 1 ? c->lfrag[which] + LFRAG_FWD2 : nullptr)));
                 continue;
             }
             if (spec_matches<SpecL3>(g, l == 0)) {
-                HIP_TRY((launch_conv_fwd_bf16x6<SpecL3, 4>((const float *)xin, wl, bl, w.act[l], B, s, 256, c->rb)));
+                HIP_TRY((launch_conv_fwd_bf16x6<SpecL3, 4>((const float *)xin, wl, bl, w.act[l], B, s, 256, c->rb,
+                                                           c->lfrag[which] && l == 2 ? c->lfrag[which] + LFRAG_FWD3 : nullptr)));
                 continue;
             }
         }
@@ -1750,8 +1778,13 @@ extern "C" int ga3c_create(const ga3c_net_desc *d, int max_predict_batch, int ma
             if (e != hipSuccess) guard(fail(GA3C_EHIP, "hipMemset: %s", hipGetErrorString(e)));
         }
     }
-    if (rc == GA3C_OK && c->nconv >= 2 && spec_matches<SpecL2>(c->geom[1], false) && c->off[2] % 4 == 0)
-        guard(dmalloc((void **)&c->dfrag_large, sizeof(u32x4) * ConvDgradBf16Geom<SpecL2>::FRAG_VECS));
+    if (rc == GA3C_OK && c->nconv == 3 && spec_matches<SpecL2>(c->geom[1], false) && spec_matches<SpecL3>(c->geom[2], false) &&
+        c->off[2] % 4 == 0 && c->off[4] % 4 == 0) {
+        for (int i = 0; i < 2 && rc == GA3C_OK; ++i) {
+            guard(dmalloc((void **)&c->lfrag[i], sizeof(u32x4) * LFRAG_VECS));
+            if (rc == GA3C_OK) guard(refresh_derived(c, i, nullptr));
+        }
+    }
     if (rc == GA3C_OK) guard(alloc_work(c->pred, c, max_predict_batch));
     if (rc == GA3C_OK) guard(alloc_work(c->train, c, max_train_frames));
     if (rc == GA3C_OK && max_train_frames > 0) {
@@ -1800,7 +1833,7 @@ extern "C" int ga3c_destroy(ga3c_ctx *c) {
         if (c->ev_readers[i]) (void)hipEventDestroy(c->ev_readers[i]);
     }
     (void)hipFree(c->g); (void)hipFree(c->grad);
-    (void)hipFree(c->cfrag[0]); (void)hipFree(c->cfrag[1]); (void)hipFree(c->ticket); (void)hipFree(c->dfrag_large);
+    (void)hipFree(c->cfrag[0]); (void)hipFree(c->cfrag[1]); (void)hipFree(c->ticket); (void)hipFree(c->lfrag[0]); (void)hipFree(c->lfrag[1]);
     free_work(c->pred); free_work(c->train);
     (void)hipFree(c->dh); (void)hipFree(c->dzv); (void)hipFree(c->R);
     (void)hipFree(c->partials); (void)hipFree(c->colpart); (void)hipFree(c->scale); (void)hipFree(c->stats);
@@ -2106,15 +2139,13 @@ static int train_step_impl(ga3c_ctx *c, const uint8_t *frames, const int32_t *ac
             continue;
         }
         if (c->fast && spec_matches<SpecL2>(g, false) && is_aligned16(th + c->off[2 * l])) {
-            // the filters as ready-made fragments first (one small launch: gathering them costs every block of the
-            // gradient kernel tens of scattered loads per lane)
-            if (c->dfrag_large && l == 1) HIP_TRY(launch_conv_dgrad_filter_fragments<SpecL2>(th + c->off[2 * l], c->dfrag_large, s));
             HIP_TRY(launch_conv_dgrad_bf16x6<SpecL2>(c->dact[l], th + c->off[2 * l], w.act[l - 1], c->dact[l - 1], B, s, 512, c->rb,
-                                                     l == 1 ? c->dfrag_large : nullptr));
+                                                     c->lfrag[cur] && l == 1 ? c->lfrag[cur] + LFRAG_DGRAD2 : nullptr));
             continue;
         }
         if (c->fast && spec_matches<SpecL3>(g, false)) {
-            HIP_TRY((launch_conv_dgrad_s1_bf16x6<SpecL3, 4>(c->dact[l], th + c->off[2 * l], w.act[l - 1], c->dact[l - 1], B, s, 256, c->rb)));
+            HIP_TRY((launch_conv_dgrad_s1_bf16x6<SpecL3, 4>(c->dact[l], th + c->off[2 * l], w.act[l - 1], c->dact[l - 1], B, s, 256, c->rb,
+                                                            c->lfrag[cur] && l == 2 ? c->lfrag[cur] + LFRAG_DGRAD3 : nullptr)));
             continue;
         }
         // general shapes: one launch per stride phase
@@ -2152,6 +2183,7 @@ static int train_step_impl(ga3c_ctx *c, const uint8_t *frames, const int32_t *ac
     ga3c::launch((rmsprop_kernel<0, 1>), dim3(rb), dim3(256), 0, s, th, c->theta2[cur ^ 1], c->g, c->grad, c->P, (const float *)nullptr,
                        1.f, hp->lr, hp->rms_decay, hp->rms_eps, c->cfrag[cur ^ 1], (unsigned)c->off[0], (unsigned)c->off[2], c->rb, ca);
     HIP_TRY(hipGetLastError());
+    if (c->lfrag[cur ^ 1]) TRY(refresh_derived(c, cur ^ 1, s));      // the larger net's fragments follow the new parameters
     TRY(mark_ready(c, cur ^ 1, s));
     c->cur = cur ^ 1;        // calls enqueued from now on see the new parameters
     return GA3C_OK;

@@ -726,6 +726,14 @@ def test_train_large_net(G):
     run_train(G, G.LARGE_NET(18), 5, 5, synth.BASE_SEED + 3, dict(clip_norm=40.0))
 
 
+def test_a_large_update_keeps_the_larger_net_filter_fragments_current(G):
+    # the larger net's conv2 / conv3 kernels read their filters as fragments that are rebuilt after every update; two
+    # updates with a learning rate seven times the usual (larger ones saturate this net in one step): the second one's forward pass and input gradients (checked layer by layer
+    # against that step's parameters) would show fragments left behind by the first
+    ref = run_train(G, G.LARGE_NET(6), 4, 5, 4400, dict(lr=0.002), steps=2)
+    assert ref["stats"]["grad_norm"] > 0
+
+
 def test_train_degenerate_inputs(G):
     import torch
     net, onet, theta = make(G, G.SMALL_NET(6), 0, 10, 5)
