@@ -10,7 +10,7 @@ SOURCES = [os.path.join(HERE, "csrc", "ga3c.hip"), os.path.join(HERE, "csrc", "s
            os.path.join(HERE, "csrc", "tuner.cpp")]
 HEADERS = [os.path.join(HERE, "csrc", f) for f in ("gemm_mfma.hpp", "problems.hpp", "conv_frame.hpp", "dense_gemm.hpp",
                                                   "conv1_bf16x3.hpp", "dense_gemm_bf16x6.hpp", "conv2_bf16x6.hpp", "conv12_fused.hpp", "conv_fwd_bf16x6.hpp",
-                                                  "conv_dgrad_bf16x6.hpp", "conv_wgrad_bf16x6.hpp", "sched_error.hpp", "launch.hpp")] + [
+                                                  "conv_dgrad_bf16x6.hpp", "conv_wgrad_bf16x6.hpp", "conv_wgrad_s1_bf16x6.hpp", "sched_error.hpp", "launch.hpp")] + [
     os.path.join(os.path.dirname(HERE), "include", "ga3c.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
          # packed fp32 instructions stay off: the compiler must not form them

@@ -26,6 +26,7 @@
 #include "conv_fwd_bf16x6.hpp"
 #include "conv_dgrad_bf16x6.hpp"
 #include "conv_wgrad_bf16x6.hpp"
+#include "conv_wgrad_s1_bf16x6.hpp"
 
 using namespace ga3c;
 
@@ -2089,7 +2090,7 @@ static int train_step_impl(ga3c_ctx *c, const uint8_t *frames, const int32_t *ac
                                      : (spec_matches<SpecL1>(g, l == 0) && is_aligned16(c->dact[l])) ? 2
                                      : spec_matches<SpecS2>(g, l == 0) ? (is_aligned16(c->dact[l]) ? 6 : 3)
                                      : spec_matches<SpecL2>(g, l == 0) ? (is_aligned16(c->dact[l]) ? 7 : 4)
-                                     : spec_matches<SpecL3>(g, l == 0) ? 5 : 0;
+                                     : spec_matches<SpecL3>(g, l == 0) ? (is_aligned16(c->dact[l]) ? 8 : 5) : 0;
             if (kind == 1) nz = conv1_bf16x3_wgrad_blocks(B);
             else if (kind == 2) nz = conv1_bf16x3_wgrad_blocks(B);
             else if (kind == 3) nz = conv_wgrad_frame_blocks<SpecS2>(B);
@@ -2097,6 +2098,7 @@ static int train_step_impl(ga3c_ctx *c, const uint8_t *frames, const int32_t *ac
             else if (kind == 5) nz = conv_wgrad_frame_blocks<SpecL3>(B);
             else if (kind == 6) nz = conv_wgrad_bf16x6_blocks<SpecS2>(B);
             else if (kind == 7) nz = conv_wgrad_bf16x6_blocks<SpecL2>(B);
+            else if (kind == 8) nz = conv_wgrad_s1_bf16x6_blocks<SpecL3>(B);
             else pick_split(conv_like_tiles(g.OC, g.K + 1), B * g.OHW, nz, kchunk);
             float *part = region((size_t)nz * g.OC * (g.K + 1));
             if (!part) return fail(GA3C_EINVAL, "internal: split-k workspace too small (conv)");
@@ -2115,6 +2117,8 @@ static int train_step_impl(ga3c_ctx *c, const uint8_t *frames, const int32_t *ac
                 HIP_TRY(launch_conv_wgrad_bf16x6<SpecS2>((const float *)xin, c->dact[l], part, B, 1.f, s, c->rb));
             } else if (kind == 7) {
                 HIP_TRY(launch_conv_wgrad_bf16x6<SpecL2>((const float *)xin, c->dact[l], part, B, 1.f, s, c->rb));
+            } else if (kind == 8) {
+                HIP_TRY(launch_conv_wgrad_s1_bf16x6<SpecL3>((const float *)xin, c->dact[l], part, B, 1.f, s, c->rb));
             } else if (l == 0) {
                 ConvWgradP<uint8_t> p; p.rb = c->rb;
                 p.M = g.OC; p.N = g.K + 1; p.K = B * g.OHW; p.kchunk = kchunk; p.g = g;
