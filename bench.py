@@ -89,14 +89,14 @@ KERNELS = {"conv12_fwd": "conv12_fused_fwd_kernel", "fc_fwd": "dense_gemm_bf16x6
            "fc_wgrad": "dense_gemm_bf16x6_kernel<2,2,2,2,row-major,row-major>",
            "fc_dgrad": "dense_gemm_bf16x6_kernel<4,2,2,2,k-major,row-major,mask>", "heads_fwd": "heads_fwd_kernel",
            "heads_train": "heads_train_kernel", "conv1_wgrad": "conv1_bf16x3_wgrad_kernel",
-           "conv2_wgrad": "conv_wgrad_bf16x6_kernel", "conv3_wgrad": "conv_wgrad_frame_kernel",
+           "conv2_wgrad": "conv_wgrad_bf16x6_kernel", "conv3_wgrad": "conv_wgrad_s1_bf16x6_kernel",
            "conv2_dgrad": "conv_dgrad_bf16x6_kernel", "conv3_dgrad": "conv_fwd_bf16x6_kernel<dgrad>",
            "conv1_fwd": "conv1_bf16x3_fwd_kernel", "conv2_fwd": "conv_fwd_bf16x6_kernel", "conv3_fwd": "conv_fwd_bf16x6_kernel",
            "wgrad_reduce": "reduce_all_kernel", "rmsprop": "rmsprop_kernel", "predict_small": "predict_small_kernel"}
 # bf16 MFMAs executed per nominal one with fp32-grade accuracy (operand split into three bf16 terms); "f32" = the
 # stage runs on the fp32 matrix cores
 TERMS = {"conv1_fwd": 3, "conv2_fwd": 6, "conv3_fwd": 6, "fc_fwd": 6, "fc_wgrad": 6, "fc_dgrad": 6, "conv1_wgrad": 3,
-         "conv2_dgrad": 6, "conv3_dgrad": 6, "conv2_wgrad": 6, "conv3_wgrad": "f32"}
+         "conv2_dgrad": 6, "conv3_dgrad": 6, "conv2_wgrad": 6, "conv3_wgrad": 6}
 HBM_STAGES = {"rmsprop", "wgrad_reduce"}
 
 
