@@ -24,8 +24,10 @@
 // nine term products (dense_gemm_bf16x6.hpp): 6 x 16 cycles per 32 pixels
 // instead of 8 x 32 on the fp32 instruction.
 //
-// A block takes 16 input channels, 16 blockIdx.y .. (gridDim.y = C / 16), of
-// frames blockIdx.x, + gridDim.x, .. and writes one partial gradient,
+// A block takes 16 input channels, 16 blockIdx.y .. (gridDim.y = C / 16), and
+// OCB filters, OCB blockIdx.z .. (all of them, or 32 where two blocks then fit
+// a compute unit's LDS), of
+// frames blockIdx.x, + gridDim.x, .. and writes its part of one partial gradient,
 // part[blockIdx.x][OC][K + 1] (K = 16 C; the last column is the bias gradient,
 // written by the blocks of channel slice 0), which a second kernel adds up in
 // block order: no atomics, the result does not depend on timing.
@@ -39,7 +41,8 @@
 
 namespace ga3c {
 
-template <class SP>
+// OCB: filters per block (a multiple of 16; blockIdx.z takes the slices of OCB filters)
+template <class SP, int OCB = SP::OC>
 struct ConvWgradBf16Geom {
     static constexpr int CS = 16;
     static constexpr int GH = SP::H / 2, GW = SP::W / 2;
@@ -48,34 +51,35 @@ struct ConvWgradBf16Geom {
     static constexpr int DROW = NKB * 32 + 8;                      // bf16 per filter row of dY (52 dwords: 16 rows hit all banks)
     static constexpr int WIN = 24;                                 // elements of a plane row a lane reads per group and term
     static constexpr int PROW = NKB * 32 + WIN;                    // bf16 per channel row of a phase plane (60 dwords)
-    static constexpr int MT = SP::OC / 16;
-    static constexpr int DTERM = SP::OC * DROW, PTERM = 4 * CS * PROW;      // elements per term
+    static constexpr int MT = OCB / 16;
+    static constexpr int DTERM = OCB * DROW, PTERM = 4 * CS * PROW;         // elements per term
     static constexpr int OTP = CS * 16 + 4;                        // floats per filter row of the block's result in LDS
     __host__ __device__ static constexpr int lds_bytes(bool one) {
-        const int stage = (one ? 1 : 3) * (DTERM + PTERM) * 2, out = SP::OC * OTP * 4;
+        const int stage = (one ? 1 : 3) * (DTERM + PTERM) * 2, out = OCB * OTP * 4;
         return stage > out ? stage : out;
     }
     static constexpr int PER_CU = 2 * lds_bytes(false) <= 160 * 1024 ? 2 : 1;
 };
 
 // ONE: operands rounded to bfloat16 (the reduced-precision variant): one term, one product.
-template <class SP, bool ONE>
-__global__ __launch_bounds__(256, ConvWgradBf16Geom<SP>::PER_CU) void conv_wgrad_bf16x6_kernel(const float *__restrict__ x,
+template <class SP, bool ONE, int OCB = SP::OC>
+__global__ __launch_bounds__(256, (ConvWgradBf16Geom<SP, OCB>::PER_CU)) void conv_wgrad_bf16x6_kernel(const float *__restrict__ x,
                                                                                               const float *__restrict__ dy,
                                                                                               float *__restrict__ part,
                                                                                               int nframes, float scale) {
-    typedef ConvWgradBf16Geom<SP> G;
+    typedef ConvWgradBf16Geom<SP, OCB> G;
+    static_assert(SP::OC % OCB == 0 && OCB % 16 == 0, "whole slices of filters");
     static_assert(SP::KS == 4 && SP::S == 2, "kernel must be 4x4 with stride 2");
     static_assert(SP::C % 16 == 0 && SP::OC % 16 == 0 && SP::OC <= 256, "channels and filters in groups of 16");
     static_assert(SP::H % 2 == 0 && SP::W % 4 == 0 && G::GW % 2 == 0, "rows are read four values at a time; shifts are whole dwords");
     static_assert(G::GW + 9 <= G::WIN, "the window must hold the largest shift plus eight elements");
     static_assert(SP::OW + 1 <= G::GW && SP::OH + 1 <= G::GH, "shifted pixels must stay on the phase grid");
-    static_assert((SP::OC * SP::NPIX) % 4 == 0 && (G::DTERM % 8) == 0 && (G::PTERM % 8) == 0, "16-byte steps");
+    static_assert((OCB * SP::NPIX) % 4 == 0 && (G::DTERM % 8) == 0 && (G::PTERM % 8) == 0, "16-byte steps");
     constexpr int CS = G::CS, GW = G::GW, NKB = G::NKB, DROW = G::DROW, PROW = G::PROW, MT = G::MT;
     constexpr int DTERM = G::DTERM, PTERM = G::PTERM, OTP = G::OTP;
     constexpr int NTERM = ONE ? 1 : 3;
     constexpr int W4 = SP::W / 4, XV = CS * SP::H * W4, XPT = (XV + 255) / 256;       // float4 of the input slice
-    constexpr int NDV = SP::OC * SP::NPIX / 4, DPT = (NDV + 255) / 256;                // float4 of dY
+    constexpr int NDV = OCB * SP::NPIX / 4, DPT = (NDV + 255) / 256;                   // float4 of my filters' dY
     constexpr int K1 = SP::K + 1;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     __bf16 *dsm = (__bf16 *)smem;                      // [term][oc][DROW]
@@ -85,7 +89,7 @@ __global__ __launch_bounds__(256, ConvWgradBf16Geom<SP>::PER_CU) void conv_wgrad
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l16 = lane & 15, g = lane >> 4;
     const int ry = wave / 2, rx = wave % 2;
-    const int c0 = blockIdx.y * CS;
+    const int c0 = blockIdx.y * CS, oc0 = blockIdx.z * OCB;
 
     for (int e = tid; e < NTERM * (DTERM + PTERM) / 8; e += 256) ((u32x4 *)smem)[e] = u32x4{0u, 0u, 0u, 0u};   // padding stays zero
 
@@ -103,7 +107,7 @@ __global__ __launch_bounds__(256, ConvWgradBf16Geom<SP>::PER_CU) void conv_wgrad
     for (int i = 0; i < DPT; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const int el = min(4 * (tid + 256 * i) + j, SP::OC * SP::NPIX - 1);
+            const int el = min(4 * (tid + 256 * i) + j, OCB * SP::NPIX - 1);
             const int oc = el / SP::NPIX, pix = el % SP::NPIX;
             ddst[i][j] = oc * DROW + (pix / SP::OW) * GW + pix % SP::OW;
         }
@@ -124,7 +128,7 @@ __global__ __launch_bounds__(256, ConvWgradBf16Geom<SP>::PER_CU) void conv_wgrad
         const float4 *xs = (const float4 *)(x + (size_t)f * SP::CHW + (size_t)c0 * (SP::H * SP::W));
 #pragma unroll
         for (int i = 0; i < XPT; ++i) xpre[i] = xs[min(tid + 256 * i, XV - 1)];
-        const float4 *ds = (const float4 *)(dy + (size_t)f * (SP::OC * SP::NPIX));
+        const float4 *ds = (const float4 *)(dy + ((size_t)f * SP::OC + oc0) * SP::NPIX);
 #pragma unroll
         for (int i = 0; i < DPT; ++i) dpre[i] = ds[min(tid + 256 * i, NDV - 1)];
     };
@@ -223,7 +227,7 @@ __global__ __launch_bounds__(256, ConvWgradBf16Geom<SP>::PER_CU) void conv_wgrad
     // The block's result is put together in LDS and leaves in rows.
     __syncthreads();
     float *ot = (float *)smem;                         // [oc][OTP]
-    __shared__ float bsh[4][SP::OC];                   // bias sums of the four wavefronts
+    __shared__ float bsh[4][OCB];                      // bias sums of the four wavefronts
     if (l16 == 0) {
 #pragma unroll
         for (int m = 0; m < MT; ++m)
@@ -240,14 +244,14 @@ __global__ __launch_bounds__(256, ConvWgradBf16Geom<SP>::PER_CU) void conv_wgrad
     }
     __syncthreads();
     typedef float f32x4_dword_aligned __attribute__((ext_vector_type(4), aligned(4)));
-    float *pb = part + (size_t)blockIdx.x * SP::OC * K1 + c0 * 16;
-    for (int it = tid; it < SP::OC * CS * 4; it += 256) {
+    float *pb = part + ((size_t)blockIdx.x * SP::OC + oc0) * K1 + c0 * 16;
+    for (int it = tid; it < OCB * CS * 4; it += 256) {
         const int oc = it / (CS * 4), kq = it % (CS * 4);
         const float4 v = *(const float4 *)(ot + oc * OTP + 4 * kq);
         *(f32x4_dword_aligned *)(pb + (size_t)oc * K1 + 4 * kq) = f32x4_dword_aligned{v.x * scale, v.y * scale, v.z * scale, v.w * scale};
     }
-    if (blockIdx.y == 0 && tid < SP::OC)
-        part[(size_t)blockIdx.x * SP::OC * K1 + (size_t)tid * K1 + SP::K] = (bsh[0][tid] + bsh[1][tid]) + (bsh[2][tid] + bsh[3][tid]);
+    if (blockIdx.y == 0 && tid < OCB)
+        part[((size_t)blockIdx.x * SP::OC + oc0 + tid) * K1 + SP::K] = (bsh[0][tid] + bsh[1][tid]) + (bsh[2][tid] + bsh[3][tid]);
 }
 
 // One partial dW per block: fewer blocks where a partial is large.
@@ -258,26 +262,26 @@ inline int conv_wgrad_bf16x6_blocks(int nframes) {
 }
 
 // x: [n][C][H][W] and dy: [n][OC][OH][OW], both 16-byte aligned; part: [conv_wgrad_bf16x6_blocks(n)][OC][K + 1].
-template <class SP>
+template <class SP, int OCB = SP::OC>
 inline hipError_t launch_conv_wgrad_bf16x6(const float *x, const float *dy, float *part, int nframes, float scale,
                                            hipStream_t s, int rb = 0) {
     if (nframes <= 0) return hipSuccess;
-    typedef ConvWgradBf16Geom<SP> G;
+    typedef ConvWgradBf16Geom<SP, OCB> G;
     static bool attr_set = false;          // once per layer shape: let the kernels use more than 64 KB of LDS
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)conv_wgrad_bf16x6_kernel<SP, false>,
+        hipError_t e = hipFuncSetAttribute((const void *)conv_wgrad_bf16x6_kernel<SP, false, OCB>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, G::lds_bytes(false));
         if (e == hipSuccess)
-            e = hipFuncSetAttribute((const void *)conv_wgrad_bf16x6_kernel<SP, true>,
+            e = hipFuncSetAttribute((const void *)conv_wgrad_bf16x6_kernel<SP, true, OCB>,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, G::lds_bytes(true));
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const dim3 grid(conv_wgrad_bf16x6_blocks<SP>(nframes), SP::C / 16);
+    const dim3 grid(conv_wgrad_bf16x6_blocks<SP>(nframes), SP::C / 16, SP::OC / OCB);
     if (rb)
-        ga3c::launch((conv_wgrad_bf16x6_kernel<SP, true>), grid, dim3(256), G::lds_bytes(true), s, x, dy, part, nframes, scale);
+        ga3c::launch((conv_wgrad_bf16x6_kernel<SP, true, OCB>), grid, dim3(256), G::lds_bytes(true), s, x, dy, part, nframes, scale);
     else
-        ga3c::launch((conv_wgrad_bf16x6_kernel<SP, false>), grid, dim3(256), G::lds_bytes(false), s, x, dy, part, nframes, scale);
+        ga3c::launch((conv_wgrad_bf16x6_kernel<SP, false, OCB>), grid, dim3(256), G::lds_bytes(false), s, x, dy, part, nframes, scale);
     return hipGetLastError();
 }
 

@@ -2116,7 +2116,7 @@ static int train_step_impl(ga3c_ctx *c, const uint8_t *frames, const int32_t *ac
             } else if (kind == 6) {
                 HIP_TRY(launch_conv_wgrad_bf16x6<SpecS2>((const float *)xin, c->dact[l], part, B, 1.f, s, c->rb));
             } else if (kind == 7) {
-                HIP_TRY(launch_conv_wgrad_bf16x6<SpecL2>((const float *)xin, c->dact[l], part, B, 1.f, s, c->rb));
+                HIP_TRY((launch_conv_wgrad_bf16x6<SpecL2, 32>((const float *)xin, c->dact[l], part, B, 1.f, s, c->rb)));
             } else if (kind == 8) {
                 HIP_TRY(launch_conv_wgrad_s1_bf16x6<SpecL3>((const float *)xin, c->dact[l], part, B, 1.f, s, c->rb));
             } else if (l == 0) {
