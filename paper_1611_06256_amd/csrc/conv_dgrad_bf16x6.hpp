@@ -37,6 +37,22 @@
 
 namespace ga3c {
 
+// Optional instrumentation (the micro-benchmark program defines GA3C_BLOCK_STAMPS before it includes this file; the
+// library does not): thread 0 of every block of channel slice 0 records the wall clock (100 MHz) and the core clock at
+// its start (slot 0), after its prologue (1) and at its end (2).
+#ifdef GA3C_BLOCK_STAMPS
+__device__ long long conv_dgrad_block_stamps[1024 * 6];
+#define CONV_DGRAD_STAMP(slot)                                                                   \
+    do {                                                                                         \
+        if (threadIdx.x == 0 && blockIdx.x < 1024 && blockIdx.y == 0) {                          \
+            conv_dgrad_block_stamps[blockIdx.x * 6 + 2 * (slot)] = wall_clock64();               \
+            conv_dgrad_block_stamps[blockIdx.x * 6 + 2 * (slot) + 1] = clock64();                \
+        }                                                                                        \
+    } while (0)
+#else
+#define CONV_DGRAD_STAMP(slot)
+#endif
+
 template <class SP>
 struct ConvDgradBf16Geom {
     static constexpr int CS = 16, S = 2;
@@ -106,6 +122,7 @@ __global__ __launch_bounds__(256, 2) void conv_dgrad_bf16x6_kernel(const float *
     unsigned char *dp = smem;                                   // [term][padded pixel][oc] bf16
     float *outs = (float *)(smem + NTERM * PLANE);              // [c][H][W]
 
+    CONV_DGRAD_STAMP(0);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l16 = lane & 15, g = lane >> 4;
@@ -173,6 +190,7 @@ __global__ __launch_bounds__(256, 2) void conv_dgrad_bf16x6_kernel(const float *
             for (int x = 0; x < NTERM; ++x) af[kb][x] = t[x];
         }
     }
+    CONV_DGRAD_STAMP(1);
     for (; f < nframes; f += gridDim.x) {
         __syncthreads();                      // the border is zero; the last frame's dY and outs have been read
 #pragma unroll
@@ -256,6 +274,7 @@ __global__ __launch_bounds__(256, 2) void conv_dgrad_bf16x6_kernel(const float *
             }
         }
     }
+    CONV_DGRAD_STAMP(2);
 }
 
 // `blocks`: how many blocks the chip holds at once (two per CU), shared out over the channel slices.

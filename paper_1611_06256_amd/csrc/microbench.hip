@@ -2,13 +2,21 @@
 // bf16 MFMA, whether vector-ALU work, LDS traffic and MFMAs of different wavefronts of a SIMD overlap, LDS read and
 // write rates for the address patterns of the convolution and GEMM kernels, how fast operand tiles stream from L2 to
 // the compute units, and what a 16-byte global load costs its wavefront to issue for several lane-to-address maps.
+// One section runs a kernel of the library itself (the conv2 input gradient, with the clock stamps its header offers
+// to this program) and shows what counters average away: when the blocks of a launch start and end, what a block's
+// prologue costs with gathered and with ready-made filter fragments, and the core clock inside the kernel.
 // A standalone program (no part of the library): built by paper_1611_06256_amd/build.py (build_microbench) and run as
-//   paper_1611_06256_amd/microbench [mfma_rate|overlap|lds_read|lds_write|l2_stream|load_issue ...]   (default: all)
+//   paper_1611_06256_amd/microbench [mfma_rate|overlap|lds_read|lds_write|l2_stream|load_issue|block_lives ...]   (default: all)
 // Every kernel indexes inside its own buffers for the fixed launch shapes used below; nothing is read from files.
 #include <hip/hip_runtime.h>
 
+#define GA3C_BLOCK_STAMPS
+#include "conv_frame.hpp"
+#include "conv_dgrad_bf16x6.hpp"
+
 #include <cstdint>
 #include <cstdio>
+#include <algorithm>
 #include <cstring>
 #include <vector>
 
@@ -403,6 +411,67 @@ int run_all() {
 }
 }  // namespace load_issue
 
+namespace block_lives {
+typedef ga3c::ConvSpec<float, 16, 20, 20, 32, 4, 2> Conv2;      // conv2 of the small net (Sec. 3.2)
+__global__ void fill(float *p, size_t n, unsigned seed) {
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
+        unsigned h = (unsigned)i * 2654435761u + seed;
+        h ^= h >> 15; h *= 2246822519u; h ^= h >> 13;
+        p[i] = (float)((int)(h % 2001u) - 1000) * 1e-3f;          // [-1, 1]: about half of the mask entries positive
+    }
+}
+static double quantile(std::vector<double> v, double q) {
+    std::sort(v.begin(), v.end());
+    return v[(size_t)(q * (v.size() - 1))];
+}
+int run_all() {
+    const int B = 2560, NBLK = 512;
+    const size_t ndy = (size_t)B * Conv2::OC * Conv2::NPIX, nx = (size_t)B * Conv2::CHW, nw = (size_t)Conv2::OC * Conv2::K;
+    float *dy, *w, *xin, *dx;
+    ga3c::u32x4 *frag;
+    CK(hipMalloc(&dy, ndy * 4)); CK(hipMalloc(&w, nw * 4)); CK(hipMalloc(&xin, nx * 4)); CK(hipMalloc(&dx, nx * 4));
+    CK(hipMalloc(&frag, sizeof(ga3c::u32x4) * ga3c::ConvDgradBf16Geom<Conv2>::FRAG_VECS));
+    hipLaunchKernelGGL(fill, dim3(1024), dim3(256), 0, 0, dy, ndy, 1u);
+    hipLaunchKernelGGL(fill, dim3(64), dim3(256), 0, 0, w, nw, 2u);
+    hipLaunchKernelGGL(fill, dim3(1024), dim3(256), 0, 0, xin, nx, 3u);
+    CK(ga3c::launch_conv_dgrad_filter_fragments<Conv2>(w, frag, 0));
+    CK(hipDeviceSynchronize());
+    hipEvent_t e0, e1;
+    CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1));
+    for (int variant = 0; variant < 2; ++variant) {
+        const ga3c::u32x4 *wf = variant == 0 ? nullptr : frag;
+        float ms = 0.f;
+        for (int rep = 0; rep < 4; ++rep) {          // the last launch is the one reported
+            CK(hipEventRecord(e0, 0));
+            CK(ga3c::launch_conv_dgrad_bf16x6<Conv2>(dy, w, xin, dx, B, 0, NBLK, 0, wf));
+            CK(hipEventRecord(e1, 0));
+            CK(hipEventSynchronize(e1));
+            CK(hipEventElapsedTime(&ms, e0, e1));
+        }
+        std::vector<long long> st(1024 * 6);
+        CK(hipMemcpyFromSymbol(st.data(), HIP_SYMBOL(ga3c::conv_dgrad_block_stamps), sizeof(long long) * st.size()));
+        long long t0 = st[0], t1 = 0;
+        for (int i = 0; i < NBLK; ++i) { t0 = std::min(t0, st[6 * i]); t1 = std::max(t1, st[6 * i + 4]); }
+        std::vector<double> start, pro, life[2];
+        double ghz = 0.0;
+        for (int i = 0; i < NBLK; ++i) {
+            start.push_back((st[6 * i] - t0) * 0.01);                     // wall clock: 10 ns per tick
+            pro.push_back((st[6 * i + 2] - st[6 * i]) * 0.01);
+            life[i < NBLK / 2 ? 0 : 1].push_back((st[6 * i + 4] - st[6 * i]) * 0.01);
+            ghz += (double)(st[6 * i + 5] - st[6 * i + 1]) / ((st[6 * i + 4] - st[6 * i]) * 10.0) / NBLK;
+        }
+        printf("%-34s %d frames, %d blocks (two per CU), five frames each: first start to last end %.1f us (event pair %.1f us)\n",
+               variant == 0 ? "filters gathered by every block:" : "ready-made filter fragments:", B, NBLK, (t1 - t0) * 0.01, ms * 1e3);
+        printf("    block starts, us after the first: median %.2f, last %.2f; prologue (entry to first frame): median %.2f us, longest %.2f us\n",
+               quantile(start, 0.5), quantile(start, 1.0), quantile(pro, 0.5), quantile(pro, 1.0));
+        printf("    block lives, us (min / median / max): blocks 0..255 %.1f / %.1f / %.1f, blocks 256..511 %.1f / %.1f / %.1f\n",
+               quantile(life[0], 0.0), quantile(life[0], 0.5), quantile(life[0], 1.0), quantile(life[1], 0.0), quantile(life[1], 0.5), quantile(life[1], 1.0));
+        printf("    core clock over the blocks' lives (clock64 ticks per wall-clock ns): %.2f GHz\n", ghz);
+    }
+    return 0;
+}
+}  // namespace block_lives
+
 int main(int argc, char **argv) {
     struct Section { const char *name; int (*fn)(); const char *what; };
     const Section sections[] = {
@@ -412,6 +481,7 @@ int main(int argc, char **argv) {
         {"lds_write", lds_write::run_all, "LDS write rate per compute unit for contiguous accesses and for tile layouts of the GEMM staging"},
         {"l2_stream", l2_stream::run_all, "operand tiles from L2 / HBM to the compute units without LDS or MFMA work (share = blocks of an XCD reading the same rows)"},
         {"load_issue", load_issue::run_all, "cycles a wavefront needs to issue one 16-byte global load, by lane-to-address map (L2-resident data)"},
+        {"block_lives", block_lives::run_all, "the library's conv2 input-gradient kernel at 2560 frames: when its blocks start and end, their prologues, the core clock"},
     };
     for (const Section &s : sections) {
         bool want = argc < 2;
