@@ -36,6 +36,7 @@ typedef ConvSpec<float, 16, 20, 20, 32, 4, 2> SpecS2;     // small net, conv2
 typedef ConvSpec<uint8_t, 4, 84, 84, 32, 8, 4> SpecL1;    // large net, conv1
 typedef ConvSpec<float, 32, 20, 20, 64, 4, 2> SpecL2;     // large net, conv2
 typedef ConvSpec<float, 64, 9, 9, 64, 3, 1> SpecL3;       // large net, conv3
+typedef ConvSpec<float, 32, 20, 20, 32, 4, 2> SpecP2;     // the paper's larger-network family (Sec. 5), stride-4 member, conv2
 // 16-byte vectors of a small-net fragment buffer: the filters of conv1 / conv2 for the fused forward kernel, then
 // those of conv2 for its input-gradient kernel
 constexpr int CFRAG_FWD_VECS = 3 * C12_FRAG_SET, CFRAG_VECS = CFRAG_FWD_VECS + ConvDgradBf16Geom<SpecS2>::FRAG_VECS;
@@ -2090,7 +2091,8 @@ static int train_step_impl(ga3c_ctx *c, const uint8_t *frames, const int32_t *ac
                                      : (spec_matches<SpecL1>(g, l == 0) && is_aligned16(c->dact[l])) ? 2
                                      : spec_matches<SpecS2>(g, l == 0) ? (is_aligned16(c->dact[l]) ? 6 : 3)
                                      : spec_matches<SpecL2>(g, l == 0) ? (is_aligned16(c->dact[l]) ? 7 : 4)
-                                     : spec_matches<SpecL3>(g, l == 0) ? (is_aligned16(c->dact[l]) ? 8 : 5) : 0;
+                                     : spec_matches<SpecL3>(g, l == 0) ? (is_aligned16(c->dact[l]) ? 8 : 5)
+                                     : (spec_matches<SpecP2>(g, l == 0) && is_aligned16(c->dact[l])) ? 9 : 0;
             if (kind == 1) nz = conv1_bf16x3_wgrad_blocks(B);
             else if (kind == 2) nz = conv1_bf16x3_wgrad_blocks(B);
             else if (kind == 3) nz = conv_wgrad_frame_blocks<SpecS2>(B);
@@ -2099,6 +2101,7 @@ static int train_step_impl(ga3c_ctx *c, const uint8_t *frames, const int32_t *ac
             else if (kind == 6) nz = conv_wgrad_bf16x6_blocks<SpecS2>(B);
             else if (kind == 7) nz = conv_wgrad_bf16x6_blocks<SpecL2>(B);
             else if (kind == 8) nz = conv_wgrad_s1_bf16x6_blocks<SpecL3>(B);
+            else if (kind == 9) nz = conv_wgrad_bf16x6_blocks<SpecP2>(B);
             else pick_split(conv_like_tiles(g.OC, g.K + 1), B * g.OHW, nz, kchunk);
             float *part = region((size_t)nz * g.OC * (g.K + 1));
             if (!part) return fail(GA3C_EINVAL, "internal: split-k workspace too small (conv)");
@@ -2119,6 +2122,8 @@ static int train_step_impl(ga3c_ctx *c, const uint8_t *frames, const int32_t *ac
                 HIP_TRY((launch_conv_wgrad_bf16x6<SpecL2, 32>((const float *)xin, c->dact[l], part, B, 1.f, s, c->rb)));
             } else if (kind == 8) {
                 HIP_TRY(launch_conv_wgrad_s1_bf16x6<SpecL3>((const float *)xin, c->dact[l], part, B, 1.f, s, c->rb));
+            } else if (kind == 9) {
+                HIP_TRY(launch_conv_wgrad_bf16x6<SpecP2>((const float *)xin, c->dact[l], part, B, 1.f, s, c->rb));
             } else if (l == 0) {
                 ConvWgradP<uint8_t> p; p.rb = c->rb;
                 p.M = g.OC; p.N = g.K + 1; p.K = B * g.OHW; p.kchunk = kchunk; p.g = g;
@@ -2145,6 +2150,10 @@ static int train_step_impl(ga3c_ctx *c, const uint8_t *frames, const int32_t *ac
         if (c->fast && spec_matches<SpecL2>(g, false) && is_aligned16(th + c->off[2 * l])) {
             HIP_TRY(launch_conv_dgrad_bf16x6<SpecL2>(c->dact[l], th + c->off[2 * l], w.act[l - 1], c->dact[l - 1], B, s, 512, c->rb,
                                                      c->lfrag[cur] && l == 1 ? c->lfrag[cur] + LFRAG_DGRAD2 : nullptr));
+            continue;
+        }
+        if (c->fast && spec_matches<SpecP2>(g, false) && is_aligned16(th + c->off[2 * l])) {
+            HIP_TRY(launch_conv_dgrad_bf16x6<SpecP2>(c->dact[l], th + c->off[2 * l], w.act[l - 1], c->dact[l - 1], B, s, 512, c->rb));
             continue;
         }
         if (c->fast && spec_matches<SpecL3>(g, false)) {

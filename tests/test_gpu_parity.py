@@ -481,8 +481,9 @@ def paper_family_net(G, stride, n_actions=18):
 
 @pytest.mark.parametrize("stride,B,N,T", [(4, 5, 2, 3), (3, 5, 2, 3), (2, 4, 2, 2), (1, 3, 1, 2)])
 def test_predict_and_train_paper_family_net(G, stride, B, N, T):
-    # the four members of the paper's larger-network family; no shape-specific kernel exists for their second and
-    # third layers (nor for a first layer of stride 3, 2 or 1): those run on the any-shape kernels
+    # the four members of the paper's larger-network family; but for the stride-4 member's first layer and the
+    # backward pass of its second one (a 4x4 stride-2 layer on 20x20 maps, which the conv2 backward kernels take),
+    # every layer runs on the any-shape kernels
     desc = paper_family_net(G, stride)
     check_predict(G, desc, B, 7400 + stride, frames=synth.rectangle_frames(7401 + stride, B))
     run_train(G, desc, N, T, 7410 + stride, dict(clip_norm=40.0),
